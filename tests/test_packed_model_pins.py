@@ -1,0 +1,146 @@
+"""Pins of the big-integer packed model (oracle/packed_model.py): the values the paper prints
+for its worked example, the multi-channel identity it builds on, and equality with the direct
+definitions (library routines / brute force) on random, extreme and exhaustive inputs."""
+import itertools
+
+import numpy as np
+import pytest
+
+from conftest import read_golden
+from oracle import direct, packed_model as pm, plan_model as pl
+
+RNG = np.random.default_rng(99)
+
+
+def _range(bits, signed):
+    return (-(1 << (bits - 1)), (1 << (bits - 1)) - 1) if signed else (0, (1 << bits) - 1)
+
+
+def _rand(n, bits, signed):
+    lo, hi = _range(bits, signed)
+    return [int(v) for v in RNG.integers(lo, hi + 1, size=n)]
+
+
+def test_worked_example_integers():
+    gold = read_golden("worked_example_f32.txt")
+    f = [int(v) for v in gold["f"].split()]
+    g = [int(v) for v in gold["g"].split()]
+    s = int(gold["slice_bits"])
+    # the figure stores element 0 in the top slice: pack the reversed sequences
+    a, b = pm.pack(f[::-1], s), pm.pack(g[::-1], s)
+    assert a == int(gold["multiplicand_a"]) and b == int(gold["multiplicand_b"])
+    assert a * b == int(gold["product"]) == int(gold["product_binary"], 2)
+    segs = pm.split_unsigned(a * b, s, len(f) + len(g) - 1)
+    assert segs[::-1] == [int(v) for v in gold["y"].split()]
+    # Eq. (inpack) order (element 0 in the low slice) gives the same outputs, low segment first
+    y, _ = pm.fnk(f, g, s, False)
+    assert y == [int(v) for v in gold["y"].split()]
+
+
+def test_multichannel_int4_identity():
+    # Eq. (xilinx4bit): (V2*2^11 + V1)(W2*2^22 + W1), V unsigned 4-bit, W signed 4-bit,
+    # gives V1W1, V2W1, V1W2, V2W2 at bit offsets 0, 11, 22, 33.
+    for v1, v2 in itertools.product(range(16), repeat=2):
+        for w1, w2 in itertools.product(range(-8, 8), repeat=2):
+            prod = (v2 * 2 ** 11 + v1) * (w2 * 2 ** 22 + w1)
+            assert prod == pm.pack([v1, v2], 11) * pm.pack([w1, 0, w2], 11)
+            assert pm.split_signed(prod, 11, 4) == [v1 * w1, v2 * w1, v1 * w2, v2 * w2]
+            assert pm.split_signed_bias(prod, 11, 4) == [v1 * w1, v2 * w1, v1 * w2, v2 * w2]
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+@pytest.mark.parametrize("signs", [(False, False), (True, True), (False, True), (True, False)])
+def test_theorem1_polynomial_identity(bits, signs):
+    plan = pl.paper_search(bits, bits, 32, 32, pl.SINGLE)
+    n, k, s = plan["N"], plan["K"], plan["S"]
+    if bits == 1 and any(signs):
+        s += 1            # signed 1-bit values {-1,0}: the printed slice is one bit short (see plan tests)
+    cases = [(_rand(n, bits, signs[0]), _rand(k, bits, signs[1])) for _ in range(50)]
+    for fa, ga in itertools.product(_range(bits, signs[0]), _range(bits, signs[1])):
+        cases.append(([fa] * n, [ga] * k))
+    for f, g in cases:
+        y_ref = np.convolve(np.array(f, dtype=np.int64), np.array(g, dtype=np.int64)).tolist()
+        prod = pm.pack(f, s) * pm.pack(g, s)
+        assert prod == sum(v << (s * m) for m, v in enumerate(y_ref))          # Eq. (prod)
+        y, _ = pm.fnk(f, g, s, any(signs))
+        assert y == y_ref
+
+
+def test_signed_slice_packing_equals_shift_add():
+    for bits, s, n in ((4, 10, 3), (2, 6, 5), (8, 18, 2), (1, 4, 8), (3, 8, 4)):
+        for _ in range(200):
+            f = _rand(n, bits, True)
+            assert pm.pack_slices_signed(f, s) == pm.pack(f, s) % (1 << (s * n))
+
+
+def test_signed_split_exhaustive_small():
+    for bits in (1, 2):
+        lo, hi = _range(bits, True)
+        vals = range(lo, hi + 1)
+        for n, k in itertools.product((1, 2, 3), repeat=2):
+            s = pl.slice_bits(bits, bits, pl.guard_bits(pl.SINGLE, n, k)) + (1 if bits == 1 else 0)
+            for f in itertools.product(vals, repeat=n):
+                for g in itertools.product(vals, repeat=k):
+                    ref = np.convolve(np.array(f, dtype=np.int64), np.array(g, dtype=np.int64)).tolist()
+                    prod = pm.pack(f, s) * pm.pack(g, s)
+                    assert pm.split_signed(prod, s, n + k - 1) == ref
+                    assert pm.split_signed_bias(prod, s, n + k - 1) == ref
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+@pytest.mark.parametrize("signs", [(False, False), (True, True), (False, True)])
+@pytest.mark.parametrize("taps", [3, 5, 7])
+def test_theorem2_overlap_add_equals_direct(bits, signs, taps):
+    plan = pl.paper_search_taps(bits, bits, 32, 32, taps, pl.CONV1D)
+    n, k, s = plan["N"], plan["K"], plan["S"]
+    if bits == 1 and any(signs):
+        s += 1
+    lo_f, hi_f = _range(bits, signs[0])
+    for length in (1, n - 1 or 1, n, n + 1, 3 * n + 2, 50):
+        inputs = [_rand(length, bits, signs[0]), [lo_f] * length, [hi_f] * length]
+        for f in inputs:
+            for g in (_rand(taps, bits, signs[1]), [_range(bits, signs[1])[0]] * taps,
+                      [_range(bits, signs[1])[1]] * taps):
+                fa = np.array(f, dtype=np.int8 if signs[0] else np.uint8)
+                ga = np.array(g, dtype=np.int8 if signs[1] else np.uint8)
+                ref = direct.conv1d(fa, ga, direct.FULL).tolist()
+                assert pm.conv1d_packed(f, g, n, k, s, any(signs)) == ref
+
+
+def test_guard_bits_are_sufficient_and_tight():
+    # unsigned 4-bit, three products per segment: 3*15*15 = 675 needs 10 bits
+    f, g = [15] * 3, [15] * 3
+    ref = np.convolve(f, g).tolist()
+    assert max(ref) == 675
+    assert pm.fnk(f, g, 10, False)[0] == ref                      # G_b = 2: exact
+    assert pm.fnk(f, g, 9, False)[0] != ref                       # G_b = 1: fields collide
+    # 1-D mode with K=3 and a long row: still exact at S=10
+    assert pm.conv1d_packed([15] * 20, g, 3, 3, 10, False) == np.convolve([15] * 20, g).tolist()
+    assert pm.conv1d_packed([15] * 20, g, 3, 3, 9, False) != np.convolve([15] * 20, g).tolist()
+
+
+def test_signed_one_bit_needs_one_more_slice_bit():
+    # values {-1,0}: (-1)*(-1) = +1, eight of them sum to 8 = 2^(S-1) for the printed S=4
+    f, g = [-1] * 8, [-1] * 8
+    ref = np.convolve(f, g).tolist()
+    assert pm.fnk(f, g, 4, True)[0] != ref
+    assert pm.fnk(f, g, 5, True)[0] == ref
+
+
+@pytest.mark.parametrize("signs", [(False, False), (True, True), (False, True)])
+def test_theorem3_dnn_mapping_with_accumulation(signs):
+    bits = 4
+    rng = np.random.default_rng(5)
+    lo_a, hi_a = _range(bits, signs[0])
+    lo_w, hi_w = _range(bits, signs[1])
+    for (c, h, w, co, kh, kw, pad, m_acc) in [(3, 5, 7, 2, 3, 3, 1, 5), (4, 4, 9, 3, 3, 3, 0, 4),
+                                              (2, 6, 6, 2, 1, 1, 0, 2), (5, 3, 8, 2, 3, 5, 2, 3)]:
+        gb = pl.ceil_log2(m_acc * kw)
+        s = pl.slice_bits(bits, bits, gb)
+        n, k = 3, min(kw, 3)
+        x = rng.integers(lo_a, hi_a + 1, size=(1, c, h, w), dtype=np.int8 if signs[0] else np.uint8)
+        wt = rng.integers(lo_w, hi_w + 1, size=(co, c, kh, kw), dtype=np.int8 if signs[1] else np.uint8)
+        for xv, wv in ((x, wt), (np.full_like(x, lo_a if signs[0] else hi_a), np.full_like(wt, lo_w if signs[1] else hi_w))):
+            ref = direct.conv2d(xv, wv, 1, pad)[0]
+            got = pm.conv2d_packed(xv[0].tolist(), wv.tolist(), pad, n, k, s, m_acc, any(signs))
+            assert np.array_equal(np.array(got), ref)
