@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the HiKonv hot path on one MI355X.
+
+A step is one pass of the packed 1-D convolution path (load of bit-dense inputs, packing,
+one wide multiply per block, lane exchange, split, int32 store) over one batch of the
+bitwidth sweep: 4096 independent rows of 65536 values, K = 3 taps, 4-bit unsigned, valid
+outputs.  Inputs are resident in HBM before the timed region.  The JSON line also carries
+the 1-bit and 8-bit cases, the unpacked one-product-per-multiply GPU kernel on the same
+inputs, the two DNN-layer configurations (ALU-bound), the roofline of the dominant kernel
+and the CPU oracle timed on a bounded sample.
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+ROWS, LENGTH, TAPS = 4096, 65536, 3
+HBM_PEAK_GBS = 8000.0                      # MI355X published HBM3E bandwidth
+VALU_LANE_RATE = 256 * 64 * 2.4e9          # lane-instructions/s at full rate: 256 CUs x 64 lanes x 2.4 GHz
+
+
+def event_ms(fn, reps):
+    """Average milliseconds per call of fn over reps back-to-back calls (events on torch's stream)."""
+    import torch
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(reps):
+        fn()
+    end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) / reps
+
+
+def conv1d_case(hk, wl, bits, signed):
+    """Device buffers and launch closures for one case of the sweep."""
+    import torch
+    x, g = wl.conv1d_case(bits, signed, TAPS, ROWS, LENGTH)
+    x_d8 = torch.from_numpy(x.view("uint8")).cuda()
+    g_d = torch.from_numpy(g.view("uint8")).cuda()
+    row_bytes = hk.hikonv_bitdense_row_bytes(LENGTH, bits)
+    x_bd = torch.zeros(ROWS * row_bytes, dtype=torch.uint8, device="cuda")
+    hk.hikonv_compact(x_d8, ROWS, LENGTH, bits, False, x_bd)
+    del x_d8
+    out_len = LENGTH - TAPS + 1
+    y = torch.empty(ROWS * out_len, dtype=torch.int32, device="cuda")
+    plan = hk.hikonv_plan_ex(bits_a=bits, bits_w=bits, a_signed=int(signed), w_signed=int(signed), L_A=32, L_B=32,
+                             L_acc=64, mode=hk.MODE_CONV1D, taps=TAPS)
+
+    def packed():
+        hk.hikonv_conv1d(plan, x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d, TAPS, hk.OUT_VALID, y)
+
+    def unpacked():
+        hk.hikonv_conv1d_unpacked(bits, bits, hk.signedness(signed, signed), x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d,
+                                  TAPS, hk.OUT_VALID, y)
+
+    macs = ROWS * out_len * TAPS
+    algo_bytes = ROWS * out_len * 4 + ROWS * row_bytes + TAPS
+    return dict(x=x, g=g, y=y, plan=plan, packed=packed, unpacked=unpacked, macs=macs, bytes=algo_bytes,
+                out_len=out_len, keep=(x_bd, g_d))
+
+
+def cpu_baseline(x, g, sample_rows=256):
+    """The oracle as it stands, timed on the host cores on the first `sample_rows` rows."""
+    from oracle import direct
+    xs = x[:sample_rows]
+    direct.conv1d(xs[:8], g, direct.VALID)                     # warm-up (page in the library)
+    best = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        direct.conv1d(xs, g, direct.VALID)
+        best = min(best, time.perf_counter() - t0)
+    macs = sample_rows * (LENGTH - TAPS + 1) * TAPS
+    return dict(value=2 * macs / best / 1e9, unit="GOPS", cores=direct.num_threads(), kind="oracle",
+                sample="first %d of %d rows of the same 4-bit case, best of 3, int64 direct convolution" %
+                       (sample_rows, ROWS))
+
+
+def conv2d_extra(hk, wl, name, steps):
+    """Packed vs unpacked DNN layer (ALU-bound configurations); returns a small report."""
+    import torch
+    if name == "c3":
+        x, w = wl.config3()
+        plan_kw = dict(bits_a=4, bits_w=4, a_signed=1, w_signed=1)
+        sg, bits = hk.signedness(True, True), 4
+    else:
+        x, w = wl.config4()
+        plan_kw = dict(bits_a=1, bits_w=1, bipolar=1)
+        sg, bits = hk.BIPOLAR, 1
+    n, c, h, wd = x.shape
+    co, _, kh, kw = w.shape
+    x_d = torch.from_numpy(x.view("uint8")).cuda()
+    w_d = torch.from_numpy(w.view("uint8")).cuda()
+    y = torch.empty(n * co * h * wd, dtype=torch.int32, device="cuda")
+    macs = n * co * h * wd * c * kh * kw
+    report = {"macs": macs}
+    for label, width, acc in (("wide32", 32, 64), ("narrow24", 24, 32)):
+        try:
+            plan = hk.hikonv_plan_ex(L_A=width, L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=0, taps=kw, **plan_kw)
+            if plan.N > 8:
+                raise hk.HikonvError(hk.EUNSUPPORTED, "plan")
+        except hk.HikonvError:
+            continue
+        ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, n, c, h, wd, co, kh, kw, 1, 1, True), dtype=torch.uint8,
+                         device="cuda")
+        pw = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8, device="cuda")
+        hk.hikonv_pack_weights(plan, w_d, co, c, kh, kw, pw)
+
+        def run():
+            hk.hikonv_conv2d_prepacked(plan, x_d, hk.FMT_INT8, n, c, h, wd, pw, co, kh, kw, 1, 1, ws, y)
+
+        event_ms(run, 3)
+        ms = event_ms(run, steps)
+        report[label] = dict(ms=ms, gops=2 * macs / ms / 1e6, plan=dict(N=plan.N, K=plan.K, S=plan.S, M=plan.M),
+                             frac_of_unpacked_valu_peak=macs / (ms * 1e-3) / VALU_LANE_RATE)
+
+    def run_unpacked():
+        hk.hikonv_conv2d_unpacked(bits, bits, sg, x_d, n, c, h, wd, w_d, co, kh, kw, 1, 1, y)
+
+    event_ms(run_unpacked, 3)
+    ms = event_ms(run_unpacked, steps)
+    report["unpacked"] = dict(ms=ms, gops=2 * macs / ms / 1e6)
+    return report
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-extras", action="store_true", help="only the headline case and its roofline")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (every box has one); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2208_00763_amd as hk
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+
+    head = conv1d_case(hk, wl, 4, False)
+    for _ in range(args.warmup):
+        head["packed"]()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_kernel = event_ms(head["packed"], args.steps)          # exactly K steps between two events
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    gops = 2 * head["macs"] / (ms_kernel * 1e-3) / 1e9
+    achieved_gbs = head["bytes"] / (ms_kernel * 1e-3) / 1e9
+
+    traffic = None
+    traffic_file = os.path.join(ROOT, "profiles", "conv1d_packed_c2_b4u_k3_traffic.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as fh:
+            traffic = json.load(fh).get("hbm_bytes_per_launch")
+
+    line = {
+        "metric": "effective low-bit MACs/s (GOPS) at 4-bit, packed 1-D convolution",
+        "value": gops, "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_kernel, "wall_ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32xu32->u64 packed words of u4 (int32 outputs)", "data": "synthetic",
+        "config": {"workload": "1-D sweep case: 4096 rows x 65536, K=3, 4-bit unsigned, valid, bit-dense input",
+                   "plan": {k: getattr(head["plan"], k) for k in ("N", "K", "S", "G_b", "chunks")}},
+        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "k_conv1d_packed", "algorithmic_bytes_per_launch": head["bytes"]},
+    }
+
+    extras = {}
+    if not args.no_extras:
+        ms_unp = event_ms(head["unpacked"], max(3, args.steps // 5))
+        extras["unpacked_4bit"] = dict(ms=ms_unp, gops=2 * head["macs"] / ms_unp / 1e6)
+        by_bits = {"4u": dict(ms=ms_kernel, gops=gops, gbs=achieved_gbs)}
+        x_keep, g_keep = head["x"], head["g"]
+        for key in ("packed", "unpacked", "y", "keep"):
+            head.pop(key)
+        torch.cuda.empty_cache()
+        for bits, signed in ((1, False), (8, False), (4, True), (1, True), (8, True)):
+            case = conv1d_case(hk, wl, bits, signed)
+            event_ms(case["packed"], 3)
+            ms_p = event_ms(case["packed"], max(3, args.steps // 5))
+            ms_u = event_ms(case["unpacked"], max(3, args.steps // 5))
+            by_bits["%d%s" % (bits, "s" if signed else "u")] = dict(
+                ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=case["bytes"] / ms_p / 1e6, unpacked_ms=ms_u,
+                plan=dict(N=case["plan"].N, K=case["plan"].K, S=case["plan"].S, chunks=case["plan"].chunks))
+            del case
+            torch.cuda.empty_cache()
+        extras["conv1d_by_bits"] = by_bits
+        for name in ("c3", "c4"):
+            extras["conv2d_" + name] = conv2d_extra(hk, wl, name, max(5, args.steps // 2))
+        head["x"], head["g"] = x_keep, g_keep
+    line["extras"] = extras
+
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(head["x"], head["g"])
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

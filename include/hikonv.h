@@ -1,0 +1,217 @@
+/*
+ * hikonv.h -- C ABI of the MI355X (gfx950) HiKonv library.
+ *
+ * HiKonv computes low-bitwidth (1..8 bit, signed or unsigned) 1-D and 2-D
+ * convolutions by packing several quantised values into one wide integer word
+ * with guard bits, so that one full-width integer multiply yields a run of
+ * partial convolution sums, which are then split by shift and mask,
+ * sign-corrected and overlap-added across packed blocks.
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller; pointers
+ *     without that suffix are HOST pointers.  The library never allocates or
+ *     frees device memory; scratch space comes from a caller-supplied workspace.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All device work is enqueued asynchronously on it; no call synchronises.
+ *   - Return value: HIKONV_OK (0) or a negative HIKONV_E* code.  Nothing is
+ *     printed, thrown or aborted.  Values outside the declared bit range are
+ *     not detected on the hot path (undefined results, never a fault).
+ *   - Outputs are always int32.
+ */
+#ifndef HIKONV_H
+#define HIKONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HIKONV_OK 0
+#define HIKONV_EINVAL (-1)       /* bad argument: bits outside 1..8, NULL pointer, negative size ... */
+#define HIKONV_EOVERFLOW (-2)    /* a result could exceed int32 for values of the declared range   */
+#define HIKONV_ENOPLAN (-3)      /* no (N, K, S) satisfies the constraints                         */
+#define HIKONV_EHIP (-4)         /* a HIP call failed; see hikonv_last_hip_error()                 */
+#define HIKONV_EWORKSPACE (-5)   /* workspace missing or too small                                 */
+#define HIKONV_EUNSUPPORTED (-6) /* valid request that this build has no kernel for                */
+
+/* Use of the multiplier; selects the guard-bit rule (Section "Maximizing Processing Throughput"). */
+#define HIKONV_MODE_SINGLE 0 /* one multiply, F_{N,K}:           G_b = ceil(log2 min(K,N))  */
+#define HIKONV_MODE_CONV1D 1 /* blocks overlap-added (Theorem 2): G_b = ceil(log2 taps)      */
+#define HIKONV_MODE_DNN 2    /* M products accumulated before a split (Theorem 3)            */
+
+/* signedness argument / flags */
+#define HIKONV_A_SIGNED 1 /* activations / f are two's-complement signed */
+#define HIKONV_W_SIGNED 2 /* weights / g are two's-complement signed     */
+#define HIKONV_BIPOLAR 4  /* 1-bit values mean {-1,+1} (bit 1 = +1), both operands */
+
+/* storage format of activations */
+#define HIKONV_FMT_INT8 0     /* one value per byte (int8 if signed, uint8 if unsigned)              */
+#define HIKONV_FMT_BITDENSE 1 /* little-endian bit stream per innermost row, value i at bits          */
+                              /* [c*i, c*i+c), c = 1,2,4,4,8,8,8,8 for 1..8-bit values; rows padded   */
+                              /* to a multiple of 4 bytes (Section "Single convolver architecture":   */
+                              /* unused bits of quantised data are discarded in storage)              */
+
+#define HIKONV_OUT_FULL 0  /* len + taps - 1 outputs per row (Eq. pad_f) */
+#define HIKONV_OUT_VALID 1 /* y[taps-1 .. len-1]: len - taps + 1 outputs */
+
+/*
+ * A packing plan.  Request fields are read by hikonv_plan_ex; result fields are
+ * written by the planner and read by the convolution entry points.
+ *   Section "Multiplier for Convolution": p, q, L_A, L_B, slice S, guard bits G_b.
+ */
+typedef struct hikonv_plan_t {
+    /* request */
+    int32_t bits_a, bits_w;     /* p, q: bitwidths of f (activations) and g (weights), 1..8          */
+    int32_t a_signed, w_signed; /* per operand                                                       */
+    int32_t bipolar;            /* 1: both operands are 1-bit {-1,+1}; packed as unsigned bits        */
+    int32_t L_A, L_B;           /* multiplier input widths in bits                                   */
+    int32_t L_acc;              /* width of the product/accumulator register (0 = L_A + L_B)         */
+    int32_t mode;               /* HIKONV_MODE_*                                                     */
+    int32_t M;                  /* DNN mode: (channel, kernel-row) products accumulated per split;   */
+                                /* 0 = let the planner choose                                        */
+    int32_t taps;               /* kernel width that must be covered (0 = free: Algorithm 1 picks K) */
+    /* result */
+    int32_t N, K, S, G_b;       /* elements per A word, taps per B word, slice bits, guard bits      */
+    int32_t chunks;             /* ceil(taps / K): B words per kernel row (1 if taps == 0)           */
+    int32_t ops_per_mul;        /* N*K + (N-1)*(K-1), Eq. (tot_ops)                                  */
+    int32_t paper_exact;        /* 1: (N,K,S,G_b) are exactly what Eq. (slice1)-(slice3) and         */
+                                /* Algorithm 1 give; 0: adjusted so that every value of the declared */
+                                /* ranges is computed exactly (signed corner cases, accumulator fit) */
+} hikonv_plan_t;
+
+/*
+ * hikonv_plan -- Algorithm 1 ("Optimal Throughput Search") for a single
+ * multiplier with both inputs `mult_width` bits wide: finds (N, K) maximising
+ * N*K + (N-1)*(K-1) under Eq. (slice2)/(slice3) with S from Eq. (slice1).
+ * signedness: OR of HIKONV_A_SIGNED, HIKONV_W_SIGNED, HIKONV_BIPOLAR.
+ * out (host) receives the full plan.  Host only; touches no device.
+ */
+int hikonv_plan(int bits_a, int bits_w, int signedness, int mult_width, hikonv_plan_t *out);
+
+/*
+ * hikonv_plan_ex -- the same search for any mode, asymmetric widths, a fixed
+ * number of kernel taps (chunked over several B words when they do not fit one)
+ * and an accumulator width.  `request` (host): request fields set, result
+ * fields ignored.  `out` (host) may alias request.
+ */
+int hikonv_plan_ex(const hikonv_plan_t *request, hikonv_plan_t *out);
+
+/*
+ * hikonv_plan_check -- exact interval check of a fully specified plan: every
+ * segment sum, both packed operands and the accumulated product must fit their
+ * fields for all values of the declared ranges.  Returns HIKONV_OK,
+ * HIKONV_EOVERFLOW (would be inexact) or HIKONV_EINVAL.  Host only.
+ */
+int hikonv_plan_check(const hikonv_plan_t *plan);
+
+/* Bytes of one bit-dense row of `len` values of `bits` bits (multiple of 4); <0 on bad bits. */
+int64_t hikonv_bitdense_row_bytes(int64_t len, int bits);
+
+/*
+ * hikonv_compact -- convert [rows][len] one-value-per-byte data to the
+ * bit-dense format (the paper's runtime feature compression).  bipolar != 0
+ * stores bit 1 for values > 0.  out_dev must hold rows*row_bytes bytes.
+ */
+int hikonv_compact(const void *x_dev, int64_t rows, int64_t len, int bits, int bipolar,
+                   void *out_dev, void *stream);
+
+/*
+ * hikonv_conv1d -- packed 1-D convolution (Eq. pad_f, Theorem 2):
+ *   y[r][m] = sum_k h_r[m-k] g[k],  h_r = zero extension of row r of x.
+ * plan: mode CONV1D, L_A = L_B = 32, taps == `taps`, from hikonv_plan_ex.
+ * x_dev: [rows][len] in x_format.  g_dev: `taps` bytes on the device, shared by
+ * all rows.  y_dev: [rows][out_len] int32, out_len = len+taps-1 (FULL) or
+ * len-taps+1 (VALID, 0 if len < taps).
+ */
+int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows,
+                  int64_t len, const void *g_dev, int taps, int out_mode, int32_t *y_dev,
+                  void *stream);
+
+/* Baseline: the same convolution with one v_mad_i32_i24 per low-bit product (no packing). */
+int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int x_format,
+                           int64_t rows, int64_t len, const void *g_dev, int taps, int out_mode,
+                           int32_t *y_dev, void *stream);
+
+/*
+ * Weight pre-packing (Section "Basic HiKonv Operations": weights can be packed
+ * offline).  For a layer W[Co][C][Kh][Kw] (one value per byte) builds, per
+ * (co, ci, kh, chunk), the word B = sum_k g[k] 2^(S k) of the reversed kernel
+ * row g = W[co][ci][kh][Kw-1:0] (Eq. I_PRIME).  packed_dev must hold
+ * hikonv_packed_weights_bytes() bytes.
+ */
+size_t hikonv_packed_weights_bytes(const hikonv_plan_t *plan, int Co, int C, int Kh, int Kw);
+int hikonv_pack_weights(const hikonv_plan_t *plan, const void *w_dev, int Co, int C, int Kh, int Kw,
+                        void *packed_dev, void *stream);
+
+/*
+ * hikonv_conv2d -- packed DNN convolution layer (Eq. conv_org, Theorem 3),
+ * cross-correlation with zero padding `pad` (0 <= pad <= Kw-1, Kh-1) and
+ * `stride`:  O[n][co][h][w] = sum_{ci,kh,kw} Ipad[n][ci][h s+kh][w s+kw] W[co][ci][kh][kw].
+ * plan: mode DNN, taps == Kw, (L_A,L_B,L_acc) = (32,32,64) or (24,24,32).
+ * x_dev: NCHW in x_format (bit-dense rows are the W rows).  y_dev: NCHW int32.
+ * workspace_dev: at least hikonv_conv2d_workspace_bytes() bytes, 256-byte aligned.
+ * hikonv_conv2d packs the raw weights w_dev ([Co][C][Kh][Kw], one per byte) into
+ * the workspace on every call; hikonv_conv2d_prepacked takes weights already
+ * packed by hikonv_pack_weights with the same plan.
+ */
+size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co,
+                                     int Kh, int Kw, int stride, int pad, int prepacked);
+int hikonv_conv2d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H,
+                  int W, const void *w_dev, int Co, int Kh, int Kw, int stride, int pad,
+                  void *workspace_dev, size_t workspace_bytes, int32_t *y_dev, void *stream);
+int hikonv_conv2d_prepacked(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C,
+                            int H, int W, const void *w_packed_dev, int Co, int Kh, int Kw, int stride,
+                            int pad, void *workspace_dev, size_t workspace_bytes, int32_t *y_dev,
+                            void *stream);
+
+/* Baseline: direct layer, one v_mad_i32_i24 per product.  x_dev and w_dev one value per byte. */
+int hikonv_conv2d_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int N, int C,
+                           int H, int W, const void *w_dev, int Co, int Kh, int Kw, int stride, int pad,
+                           int32_t *y_dev, void *stream);
+
+/*
+ * hikonv_epilogue -- the un-accelerated rest of a layer in the complete-model
+ * experiment (Section "Complete model evaluation"): ReLU, requantise
+ * q = min(qmax, max(acc,0) >> shift), optional 2x2/stride-2 max-pool, written
+ * as the next layer's activations in out_format with out_bits-bit values.
+ * acc_dev: NCHW int32.  out_dev: [N][C][Ho][Wo] rows of Wo values.
+ */
+int hikonv_epilogue(const int32_t *acc_dev, int N, int C, int H, int W, int shift, int qmax, int pool,
+                    int out_bits, int out_format, void *out_dev, void *stream);
+
+/*
+ * Roofline micro-benchmarks.  kind: HIKONV_UB_*.  Launches one kernel on
+ * `stream`; the caller times it.  For VALU kinds every lane of `blocks` x 256
+ * threads issues iters x 64 dependent-chain-free instructions of the kind;
+ * buf_dev (>= 4*blocks*256 bytes) receives a checksum so nothing is optimised
+ * away.  For HBM kinds buf_dev holds `bytes` bytes (copy: first half -> second).
+ */
+#define HIKONV_UB_MAD_U32_U24 0
+#define HIKONV_UB_MAD_U64_U32 1
+#define HIKONV_UB_MUL_LO_U32 2
+#define HIKONV_UB_BFE_U32 3
+#define HIKONV_UB_LSHR_B64 4
+#define HIKONV_UB_DPP_MOV 5
+#define HIKONV_UB_ADD_U32 6
+#define HIKONV_UB_MAD_I32_I24 7
+#define HIKONV_UB_MAD_I64_I32 8
+#define HIKONV_UB_ADD_U64 9
+#define HIKONV_UB_ALIGNBIT 10
+#define HIKONV_UB_AND_B32 11
+#define HIKONV_UB_HBM_WRITE 16
+#define HIKONV_UB_HBM_COPY 17
+#define HIKONV_UB_HBM_READ 18
+int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream);
+
+/* Lane-exchange self check: out_dev[i] (64 ints) = value lane i receives from lane i-1 (lane 0: 0). */
+int hikonv_selftest_lane_shift(int32_t *out_dev, void *stream);
+
+const char *hikonv_strerror(int code);
+int hikonv_last_hip_error(void); /* hipError_t of the most recent failing HIP call in this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIKONV_H */

@@ -11,7 +11,9 @@ against the direct definitions.  It shares no code with the HIP library.
 Readings: Eq. inpack's slice order (element 0 in the least significant slice); the field of
 Eq. output_split is sign-extended before the bit below it is added; Algorithm 2 as printed
 is not executable (its packing register is never cleared, its index steps by one, `prev`
-is never updated), so the loop below is derived from Theorem 2 instead; a row whose length
+is never updated), so the loop below is derived from Theorem 2 and from the register-based
+1-D architecture of Section "1-D & DNN layer Convolution Architecture" instead (the stored
+word is shifted by N slices and the new product is added to it); a row whose length
 is not a multiple of N is zero-extended (Eq. pad_f0); kernels wider than one B word are cut
 into chunks and the chunk products are accumulated on correspondingly delayed inputs.
 
@@ -106,7 +108,7 @@ def conv1d_packed(f, g, n: int, k: int, s: int, signed: bool):
             prod += a * b
         comb = prod + _hi(prev, s * n, signed)
         y.extend(split(comb, s, n))
-        prev = prod
+        prev = comb          # the stored word keeps every pending segment (also when K-1 > N)
     return y[:out_len]
 
 
@@ -150,8 +152,9 @@ def conv2d_packed(x, w, pad: int, n: int, k: int, s: int, m_acc: int, signed: bo
                 y = []
                 prev = 0
                 for xb in range(n_blocks):
-                    y.extend(split(acc[xb] + _hi(prev, s * n, signed), s, n))
-                    prev = acc[xb]
+                    comb = acc[xb] + _hi(prev, s * n, signed)
+                    y.extend(split(comb, s, n))
+                    prev = comb
                 for wcol in range(wo):
                     out[co][h][wcol] += y[wcol + kw_n - 1]
     return out

@@ -1,0 +1,186 @@
+"""ctypes binding of libhikonv.so: same names as include/hikonv.h, argument marshalling only.
+
+Device buffers are torch tensors (PyTorch is used for device memory and streams, nothing
+else); every function enqueues on torch's current stream unless `stream` is given.  There is
+no CPU fallback: if the library is missing or was not built, importing this module fails.
+"""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhikonv.so")
+
+OK, EINVAL, EOVERFLOW, ENOPLAN, EHIP, EWORKSPACE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+MODE_SINGLE, MODE_CONV1D, MODE_DNN = 0, 1, 2
+A_SIGNED, W_SIGNED, BIPOLAR = 1, 2, 4
+FMT_INT8, FMT_BITDENSE = 0, 1
+OUT_FULL, OUT_VALID = 0, 1
+UB_MAD_U32_U24, UB_MAD_U64_U32, UB_MUL_LO_U32, UB_BFE_U32, UB_LSHR_B64, UB_DPP_MOV, UB_ADD_U32 = range(7)
+UB_MAD_I32_I24, UB_MAD_I64_I32, UB_ADD_U64, UB_ALIGNBIT, UB_AND_B32 = range(7, 12)
+UB_HBM_WRITE, UB_HBM_COPY, UB_HBM_READ = 16, 17, 18
+
+PLAN_FIELDS = ("bits_a bits_w a_signed w_signed bipolar L_A L_B L_acc mode M taps "
+               "N K S G_b chunks ops_per_mul paper_exact").split()
+
+
+class Plan(C.Structure):
+    """Mirror of hikonv_plan_t."""
+    _fields_ = [(name, C.c_int32) for name in PLAN_FIELDS]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name in PLAN_FIELDS}
+
+    def __repr__(self):
+        return "Plan(%s)" % ", ".join("%s=%d" % kv for kv in self.as_dict().items())
+
+
+class HikonvError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %s (code %d, hip error %d)" % (
+            where, lib.hikonv_strerror(code).decode(), code, lib.hikonv_last_hip_error()))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        from .build import build
+        build(force=True)
+    return C.CDLL(LIB_PATH)
+
+
+lib = _load()
+
+_vp, _i, _i64, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+_pp = C.POINTER(Plan)
+SIGNATURES = {
+    "hikonv_plan": (_i, [_i, _i, _i, _i, _pp]),
+    "hikonv_plan_ex": (_i, [_pp, _pp]),
+    "hikonv_plan_check": (_i, [_pp]),
+    "hikonv_bitdense_row_bytes": (_i64, [_i64, _i]),
+    "hikonv_compact": (_i, [_vp, _i64, _i64, _i, _i, _vp, _vp]),
+    "hikonv_conv1d": (_i, [_pp, _vp, _i, _i64, _i64, _vp, _i, _i, _vp, _vp]),
+    "hikonv_conv1d_unpacked": (_i, [_i, _i, _i, _vp, _i, _i64, _i64, _vp, _i, _i, _vp, _vp]),
+    "hikonv_packed_weights_bytes": (_sz, [_pp, _i, _i, _i, _i]),
+    "hikonv_pack_weights": (_i, [_pp, _vp, _i, _i, _i, _i, _vp, _vp]),
+    "hikonv_conv2d_workspace_bytes": (_sz, [_pp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i]),
+    "hikonv_conv2d": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
+    "hikonv_conv2d_prepacked": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
+    "hikonv_conv2d_unpacked": (_i, [_i, _i, _i, _vp, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hikonv_epilogue": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hikonv_ubench": (_i, [_i, _i, _i, _vp, _sz, _vp]),
+    "hikonv_selftest_lane_shift": (_i, [_vp, _vp]),
+    "hikonv_strerror": (C.c_char_p, [_i]),
+    "hikonv_last_hip_error": (_i, []),
+}
+for _name, (_res, _args) in SIGNATURES.items():
+    _fn = getattr(lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+def _check(code, where):
+    if code != OK:
+        raise HikonvError(code, where)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _stream(stream):
+    if stream is not None:
+        return C.c_void_p(stream)
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def signedness(a_signed=False, w_signed=False, bipolar=False):
+    return (A_SIGNED if a_signed else 0) | (W_SIGNED if w_signed else 0) | (BIPOLAR if bipolar else 0)
+
+
+# ---- host-only entry points ------------------------------------------------------------
+def hikonv_plan(bits_a, bits_w, signedness_flags, mult_width):
+    out = Plan()
+    _check(lib.hikonv_plan(bits_a, bits_w, signedness_flags, mult_width, C.byref(out)), "hikonv_plan")
+    return out
+
+
+def hikonv_plan_ex(**request):
+    req = Plan(**request)
+    out = Plan()
+    _check(lib.hikonv_plan_ex(C.byref(req), C.byref(out)), "hikonv_plan_ex")
+    return out
+
+
+def hikonv_plan_check(plan):
+    return lib.hikonv_plan_check(C.byref(plan))
+
+
+def hikonv_bitdense_row_bytes(length, bits):
+    return lib.hikonv_bitdense_row_bytes(length, bits)
+
+
+def hikonv_strerror(code):
+    return lib.hikonv_strerror(code).decode()
+
+
+# ---- device entry points ---------------------------------------------------------------
+def hikonv_compact(x, rows, length, bits, bipolar, out, stream=None):
+    _check(lib.hikonv_compact(_ptr(x), rows, length, bits, int(bipolar), _ptr(out), _stream(stream)), "hikonv_compact")
+
+
+def hikonv_conv1d(plan, x, x_format, rows, length, g, taps, out_mode, y, stream=None):
+    _check(lib.hikonv_conv1d(C.byref(plan), _ptr(x), x_format, rows, length, _ptr(g), taps, out_mode, _ptr(y),
+                             _stream(stream)), "hikonv_conv1d")
+
+
+def hikonv_conv1d_unpacked(bits_a, bits_w, signedness_flags, x, x_format, rows, length, g, taps, out_mode, y,
+                           stream=None):
+    _check(lib.hikonv_conv1d_unpacked(bits_a, bits_w, signedness_flags, _ptr(x), x_format, rows, length, _ptr(g),
+                                      taps, out_mode, _ptr(y), _stream(stream)), "hikonv_conv1d_unpacked")
+
+
+def hikonv_packed_weights_bytes(plan, co, c, kh, kw):
+    return lib.hikonv_packed_weights_bytes(C.byref(plan), co, c, kh, kw)
+
+
+def hikonv_pack_weights(plan, w, co, c, kh, kw, packed, stream=None):
+    _check(lib.hikonv_pack_weights(C.byref(plan), _ptr(w), co, c, kh, kw, _ptr(packed), _stream(stream)),
+           "hikonv_pack_weights")
+
+
+def hikonv_conv2d_workspace_bytes(plan, n, c, h, w, co, kh, kw, stride, pad, prepacked):
+    return lib.hikonv_conv2d_workspace_bytes(C.byref(plan), n, c, h, w, co, kh, kw, stride, pad, int(prepacked))
+
+
+def hikonv_conv2d(plan, x, x_format, n, c, h, w, weights, co, kh, kw, stride, pad, workspace, y, stream=None):
+    _check(lib.hikonv_conv2d(C.byref(plan), _ptr(x), x_format, n, c, h, w, _ptr(weights), co, kh, kw, stride, pad,
+                             _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(y),
+                             _stream(stream)), "hikonv_conv2d")
+
+
+def hikonv_conv2d_prepacked(plan, x, x_format, n, c, h, w, packed, co, kh, kw, stride, pad, workspace, y,
+                            stream=None):
+    _check(lib.hikonv_conv2d_prepacked(C.byref(plan), _ptr(x), x_format, n, c, h, w, _ptr(packed), co, kh, kw,
+                                       stride, pad, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                       _ptr(y), _stream(stream)), "hikonv_conv2d_prepacked")
+
+
+def hikonv_conv2d_unpacked(bits_a, bits_w, signedness_flags, x, n, c, h, w, weights, co, kh, kw, stride, pad, y,
+                           stream=None):
+    _check(lib.hikonv_conv2d_unpacked(bits_a, bits_w, signedness_flags, _ptr(x), n, c, h, w, _ptr(weights), co, kh,
+                                      kw, stride, pad, _ptr(y), _stream(stream)), "hikonv_conv2d_unpacked")
+
+
+def hikonv_epilogue(acc, n, c, h, w, shift, qmax, pool, out_bits, out_format, out, stream=None):
+    _check(lib.hikonv_epilogue(_ptr(acc), n, c, h, w, shift, qmax, int(pool), out_bits, out_format, _ptr(out),
+                               _stream(stream)), "hikonv_epilogue")
+
+
+def hikonv_ubench(kind, iters, blocks, buf, stream=None):
+    _check(lib.hikonv_ubench(kind, iters, blocks, _ptr(buf), buf.numel() * buf.element_size(), _stream(stream)),
+           "hikonv_ubench")
+
+
+def hikonv_selftest_lane_shift(out, stream=None):
+    _check(lib.hikonv_selftest_lane_shift(_ptr(out), _stream(stream)), "hikonv_selftest_lane_shift")

@@ -1,0 +1,62 @@
+"""Layer chaining for the complete-model experiment (Section "Complete model evaluation"):
+conv layers through the packed DNN path, each followed by the un-accelerated epilogue
+(ReLU, requantise, optional 2x2 max-pool) that writes the next layer's bit-dense input.
+
+Orchestration only: every step runs in libhikonv kernels on the caller's stream.
+"""
+import torch
+
+from . import binding as hk
+
+
+class PackedCnn:
+    """Pre-packs the weights of a list of conv layers once; forward() runs the chain."""
+
+    def __init__(self, weights, specs, act_bits=4, w_bits=4, w_signed=True, wide=True, m=0):
+        self.layers = []
+        width, acc = (32, 64) if wide else (24, 32)
+        for w_dev, spec in zip(weights, specs):
+            co, c, kh, kw = w_dev.shape
+            plan = hk.hikonv_plan_ex(bits_a=act_bits, bits_w=w_bits, a_signed=0, w_signed=int(w_signed), L_A=width,
+                                     L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=m, taps=kw)
+            packed = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8,
+                                 device=w_dev.device)
+            hk.hikonv_pack_weights(plan, w_dev, co, c, kh, kw, packed)
+            self.layers.append(dict(plan=plan, packed=packed, co=co, c=c, kh=kh, kw=kw, pad=spec["pad"],
+                                    pool=spec["pool"]))
+        self.act_bits = act_bits
+        self.buffers = None
+
+    def _allocate(self, n, h, w):
+        bufs = []
+        for layer in self.layers:
+            ho = h + 2 * layer["pad"] - layer["kh"] + 1
+            wo = w + 2 * layer["pad"] - layer["kw"] + 1
+            ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(layer["plan"], n, layer["c"], h, w, layer["co"],
+                                                              layer["kh"], layer["kw"], 1, layer["pad"], True),
+                             dtype=torch.uint8, device="cuda")
+            acc = torch.empty(n * layer["co"] * ho * wo, dtype=torch.int32, device="cuda")
+            h2, w2 = (ho // 2, wo // 2) if layer["pool"] else (ho, wo)
+            row_bytes = hk.hikonv_bitdense_row_bytes(w2, self.act_bits)
+            nxt = torch.empty(n * layer["co"] * h2 * row_bytes, dtype=torch.uint8, device="cuda")
+            bufs.append(dict(ws=ws, acc=acc, nxt=nxt, h=h, w=w, ho=ho, wo=wo))
+            h, w = h2, w2
+        self.buffers = (n, bufs)
+
+    def forward(self, x_bitdense, n, h, w, shifts, qmax=15):
+        """x_bitdense: [n][c0][h] bit-dense rows.  Returns (int32 accumulators of the last layer,
+        list of per-layer int32 accumulator tensors)."""
+        if self.buffers is None or self.buffers[0] != n or self.buffers[1][0]["h"] != h or self.buffers[1][0]["w"] != w:
+            self._allocate(n, h, w)
+        cur = x_bitdense
+        accs = []
+        for i, (layer, buf) in enumerate(zip(self.layers, self.buffers[1])):
+            hk.hikonv_conv2d_prepacked(layer["plan"], cur, hk.FMT_BITDENSE, n, layer["c"], buf["h"], buf["w"],
+                                       layer["packed"], layer["co"], layer["kh"], layer["kw"], 1, layer["pad"],
+                                       buf["ws"], buf["acc"])
+            accs.append(buf["acc"])
+            if i + 1 < len(self.layers):
+                hk.hikonv_epilogue(buf["acc"], n, layer["co"], buf["ho"], buf["wo"], shifts[i], qmax, layer["pool"],
+                                   self.act_bits, hk.FMT_BITDENSE, buf["nxt"])
+                cur = buf["nxt"]
+        return accs[-1], accs

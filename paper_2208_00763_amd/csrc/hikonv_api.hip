@@ -1,0 +1,390 @@
+// extern "C" entry points of libhikonv.so: argument checks, workspace layout, launches.
+// No entry point allocates device memory or synchronises.
+#include "hikonv_launch.h"
+
+using namespace hikonv;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_result(hipError_t e)
+{
+    if (e == hipSuccess) return HIKONV_OK;
+    g_last_hip_error = (int)e;
+    return e == hipErrorInvalidValue ? HIKONV_EUNSUPPORTED : HIKONV_EHIP;
+}
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+inline int64_t max_abs(int bits, int is_signed) { return is_signed ? (1LL << (bits - 1)) : (1LL << bits) - 1; }
+
+// fills Conv1dArgs from the public arguments; returns HIKONV_OK, or 1 if there is nothing to do
+int conv1d_common(int bits_a, int a_signed, int w_signed, const void *x_dev, int x_format, int64_t rows,
+                  int64_t len, const void *g_dev, int taps, int out_mode, int32_t *y_dev, Conv1dArgs *a)
+{
+    if (bits_a < 1 || bits_a > 8 || rows < 0 || len < 0 || taps < 1 || taps > 64) return HIKONV_EINVAL;
+    if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE) return HIKONV_EINVAL;
+    if (out_mode != HIKONV_OUT_FULL && out_mode != HIKONV_OUT_VALID) return HIKONV_EINVAL;
+    const int64_t out_len = out_mode == HIKONV_OUT_FULL ? len + taps - 1 : len - taps + 1;
+    if (rows == 0 || len == 0 || out_len <= 0) return 1;
+    if (!x_dev || !g_dev || !y_dev) return HIKONV_EINVAL;
+    if (!aligned(x_dev, 4) || !aligned(y_dev, 16)) return HIKONV_EINVAL;
+    if (rows > (1LL << 31) || len > (1LL << 40)) return HIKONV_EINVAL;
+    a->x = static_cast<const uint32_t *>(x_dev);
+    a->c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(bits_a);
+    a->b = bits_a;
+    const int64_t row_bytes = x_format == HIKONV_FMT_INT8 ? len : hikonv_bitdense_row_bytes(len, bits_a);
+    a->row_stride_bits = row_bytes * 8;
+    a->total_bytes = rows * row_bytes;
+    a->total_dwords = a->total_bytes / 4;
+    a->rows = rows;
+    a->len = len;
+    a->g = static_cast<const uint8_t *>(g_dev);
+    a->taps = taps;
+    a->w_signed = w_signed;
+    a->shift_m = out_mode == HIKONV_OUT_VALID ? taps - 1 : 0;
+    a->out_len = out_len;
+    a->y = y_dev;
+    (void)a_signed;
+    return HIKONV_OK;
+}
+
+struct Conv2dGeom {
+    int Ho, Wo, Wo1, X, Xs, Hp, terms, n_cog;
+    size_t apk_bytes, wp_bytes, ps_bytes, sa_bytes;
+};
+
+int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, int Kh, int Kw, int stride, int pad,
+                Conv2dGeom *g)
+{
+    if (!plan) return HIKONV_EINVAL;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || Co < 1 || Kh < 1 || Kw < 1 || stride < 1 || pad < 0) return HIKONV_EINVAL;
+    if (plan->mode != HIKONV_MODE_DNN || plan->taps != Kw || plan->M < 1) return HIKONV_EINVAL;
+    if (plan->N < 1 || plan->K < 1 || plan->S < 1 || plan->chunks != (Kw + plan->K - 1) / plan->K) return HIKONV_EINVAL;
+    const bool wide = plan->L_A == 32 && plan->L_B == 32 && (plan->L_acc == 64 || plan->L_acc == 0);
+    const bool narrow = plan->L_A == 24 && plan->L_B == 24 && plan->L_acc == 32;
+    if (!wide && !narrow) return HIKONV_EUNSUPPORTED;
+    if (plan->N > 8 || plan->chunks > 8 || Kh > 64 || Kw > 64) return HIKONV_EUNSUPPORTED;
+    if (pad > Kw - 1) return HIKONV_EUNSUPPORTED; // the leading padding must fit inside the kernel width
+    if (H + 2 * pad < Kh || W + 2 * pad < Kw) return HIKONV_EINVAL;
+    if (hikonv_plan_check(plan) != HIKONV_OK) return HIKONV_EOVERFLOW;
+    const int64_t worst = (int64_t)C * Kh * Kw * (plan->bipolar ? 1 : max_abs(plan->bits_a, plan->a_signed) *
+                                                                           max_abs(plan->bits_w, plan->w_signed));
+    if (worst >= (1LL << 31)) return HIKONV_EOVERFLOW;
+    g->Ho = (H + 2 * pad - Kh) / stride + 1;
+    g->Wo = (W + 2 * pad - Kw) / stride + 1;
+    g->Wo1 = W + 2 * pad - Kw + 1;
+    g->X = (W + pad + plan->N - 1) / plan->N;
+    g->Xs = g->X + 1;
+    g->Hp = H + 2 * pad;
+    g->terms = C * Kh * plan->chunks;
+    g->n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
+    g->apk_bytes = round256((size_t)plan->chunks * N * C * g->Hp * g->Xs * 4);
+    g->wp_bytes = round256((size_t)g->n_cog * g->terms * 8 * 4);
+    g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
+    g->sa_bytes = plan->bipolar ? round256((size_t)N * g->Ho * g->Wo * 4) : 0;
+    return HIKONV_OK;
+}
+
+int pack_weights_impl(const hikonv_plan_t *plan, const Conv2dGeom &g, const void *w_dev, int Co, int C, int Kh,
+                      int Kw, void *packed_dev, hipStream_t stream)
+{
+    PackWArgs a;
+    a.w = static_cast<const uint8_t *>(w_dev);
+    a.Co = Co;
+    a.C = C;
+    a.Kh = Kh;
+    a.Kw = Kw;
+    a.w_signed = plan->w_signed;
+    a.bipolar = plan->bipolar;
+    a.Kp = plan->K;
+    a.S = plan->S;
+    a.chunks = plan->chunks;
+    a.n_cog = g.n_cog;
+    a.wp = static_cast<uint32_t *>(packed_dev);
+    a.ps = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(packed_dev) + g.wp_bytes);
+    return hip_result(launch_pack_weights(a, stream));
+}
+
+int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,
+                const void *w_dev, int prepacked, int Co, int Kh, int Kw, int stride, int pad, void *workspace_dev,
+                size_t workspace_bytes, int32_t *y_dev, void *stream_v)
+{
+    Conv2dGeom g;
+    int rc = conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g);
+    if (rc != HIKONV_OK) return rc;
+    if (!x_dev || !w_dev || !y_dev) return HIKONV_EINVAL;
+    if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE) return HIKONV_EINVAL;
+    if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(w_dev, prepacked ? 256 : 1)) return HIKONV_EINVAL;
+    const size_t need = g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return HIKONV_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
+    uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
+    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+    const uint8_t *wpk = static_cast<const uint8_t *>(w_dev);
+    if (!prepacked) {
+        uint8_t *dst = ws + g.apk_bytes + g.sa_bytes;
+        rc = pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, dst, stream);
+        if (rc != HIKONV_OK) return rc;
+        wpk = dst;
+    }
+
+    PackActArgs pa;
+    pa.x = x_dev;
+    pa.x_format = x_format;
+    pa.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
+    pa.b = plan->bits_a;
+    pa.a_signed = plan->a_signed;
+    pa.bipolar = plan->bipolar;
+    pa.row_bytes = x_format == HIKONV_FMT_INT8 ? W : hikonv_bitdense_row_bytes(W, plan->bits_a);
+    pa.Nimg = N;
+    pa.C = C;
+    pa.H = H;
+    pa.W = W;
+    pa.pad = pad;
+    pa.N = plan->N;
+    pa.Kp = plan->K;
+    pa.S = plan->S;
+    pa.chunks = plan->chunks;
+    pa.Hp = g.Hp;
+    pa.Xs = g.Xs;
+    pa.apk = apk;
+    rc = hip_result(launch_pack_act(pa, stream));
+    if (rc != HIKONV_OK) return rc;
+
+    Conv2dArgs ca;
+    ca.apk = apk;
+    ca.wp = reinterpret_cast<const uint32_t *>(wpk);
+    ca.Nimg = N;
+    ca.C = C;
+    ca.Ho = g.Ho;
+    ca.Wo1 = g.Wo1;
+    ca.Kh = Kh;
+    ca.stride = stride;
+    ca.off = Kw - 1 - pad;
+    ca.Hp = g.Hp;
+    ca.Xs = g.Xs;
+    ca.X = g.X;
+    ca.N = plan->N;
+    ca.S = plan->S;
+    ca.chunks = plan->chunks;
+    ca.M = plan->M;
+    ca.terms = g.terms;
+    ca.chunk_stride = (int64_t)N * C * g.Hp * g.Xs;
+    if (g.Xs <= 64) {
+        ca.rows_per_wave = 64 / g.Xs;
+        ca.segs = 0;
+    } else {
+        ca.rows_per_wave = 1;
+        ca.segs = (g.X + 62) / 63;
+    }
+    ca.wave_rows = (int64_t)N * g.Ho;
+    ca.Wo = g.Wo;
+    const bool wide = plan->L_A == 32;
+    const bool any_signed = !plan->bipolar && (plan->a_signed || plan->w_signed);
+    const int64_t waves = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, ca.rows_per_wave);
+
+    if (plan->bipolar) {
+        // window sums of a: the same kernel with the all-ones weight group, one channel
+        Conv2dArgs sa_args = ca;
+        sa_args.Co = 1;
+        sa_args.cog0 = g.n_cog - 1;
+        sa_args.y = sa;
+        rc = hip_result(launch_conv2d_packed(sa_args, wide, any_signed, 2, stream));
+        if (rc != HIKONV_OK) return rc;
+    }
+    ca.Co = Co;
+    ca.cog0 = 0;
+    ca.y = y_dev;
+    const int co_tile = (Co >= 8 && waves * ((Co + 7) / 8) >= 1536) ? 8 : 2;
+    rc = hip_result(launch_conv2d_packed(ca, wide, any_signed, co_tile, stream));
+    if (rc != HIKONV_OK) return rc;
+
+    if (plan->bipolar) {
+        BipolarFixArgs fa;
+        fa.y = y_dev;
+        fa.sa = sa;
+        fa.ps = reinterpret_cast<const int32_t *>(wpk + g.wp_bytes);
+        fa.Nimg = N;
+        fa.Co = Co;
+        fa.Ho = g.Ho;
+        fa.Wo = g.Wo;
+        fa.C = C;
+        fa.H = H;
+        fa.W = W;
+        fa.Kh = Kh;
+        fa.Kw = Kw;
+        fa.stride = stride;
+        fa.pad = pad;
+        rc = hip_result(launch_bipolar_fix(fa, stream));
+    }
+    return rc;
+}
+
+} // namespace
+
+extern "C" int hikonv_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" int hikonv_compact(const void *x_dev, int64_t rows, int64_t len, int bits, int bipolar, void *out_dev,
+                              void *stream)
+{
+    if (container_bits(bits) == 0 || rows < 0 || len < 0 || (bipolar && bits != 1)) return HIKONV_EINVAL;
+    if (rows == 0 || len == 0) return HIKONV_OK;
+    if (!x_dev || !out_dev || !aligned(out_dev, 4)) return HIKONV_EINVAL;
+    const int64_t row_dwords = hikonv_bitdense_row_bytes(len, bits) / 4;
+    return hip_result(launch_compact(static_cast<const uint8_t *>(x_dev), rows, len, bits, bipolar,
+                                     static_cast<uint32_t *>(out_dev), row_dwords, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows, int64_t len,
+                             const void *g_dev, int taps, int out_mode, int32_t *y_dev, void *stream)
+{
+    if (!plan) return HIKONV_EINVAL;
+    if (plan->mode != HIKONV_MODE_CONV1D || plan->taps != taps) return HIKONV_EINVAL;
+    if (plan->bipolar) return HIKONV_EUNSUPPORTED;
+    if (plan->L_A != 32 || plan->L_B != 32 || (plan->L_acc != 64 && plan->L_acc != 0)) return HIKONV_EUNSUPPORTED;
+    if (plan->N < 1 || plan->N > 32 || plan->K < 1 || plan->S < 1 || plan->chunks < 1 || plan->chunks > 8)
+        return HIKONV_EUNSUPPORTED;
+    if (plan->chunks != (taps + plan->K - 1) / plan->K) return HIKONV_EINVAL;
+    if (hikonv_plan_check(plan) != HIKONV_OK) return HIKONV_EOVERFLOW;
+    Conv1dArgs a;
+    int rc = conv1d_common(plan->bits_a, plan->a_signed, plan->w_signed, x_dev, x_format, rows, len, g_dev, taps,
+                           out_mode, y_dev, &a);
+    if (rc != HIKONV_OK) return rc == 1 ? HIKONV_OK : rc;
+    a.N = plan->N;
+    a.Kp = plan->K;
+    a.S = plan->S;
+    a.chunks = plan->chunks;
+    const int64_t m_end = out_mode == HIKONV_OUT_VALID ? len : len + taps - 1;
+    a.n_blocks = ceil_div(m_end, a.N);
+    a.CH = conv1d_tile_chunks(a.N, a.n_blocks);
+    a.tiles_per_row = ceil_div(a.n_blocks, (int64_t)4 * a.CH * 63);
+    return hip_result(launch_conv1d_packed(a, plan->a_signed != 0, plan->a_signed || plan->w_signed,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int x_format,
+                                      int64_t rows, int64_t len, const void *g_dev, int taps, int out_mode,
+                                      int32_t *y_dev, void *stream)
+{
+    if (bits_w < 1 || bits_w > 8 || signedness < 0 || signedness > 3) return HIKONV_EINVAL;
+    Conv1dArgs a = {};
+    int rc = conv1d_common(bits_a, signedness & HIKONV_A_SIGNED, (signedness & HIKONV_W_SIGNED) ? 1 : 0, x_dev,
+                           x_format, rows, len, g_dev, taps, out_mode, y_dev, &a);
+    if (rc != HIKONV_OK) return rc == 1 ? HIKONV_OK : rc;
+    return hip_result(launch_conv1d_unpacked(a, (signedness & HIKONV_A_SIGNED) != 0, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" size_t hikonv_packed_weights_bytes(const hikonv_plan_t *plan, int Co, int C, int Kh, int Kw)
+{
+    if (!plan || Co < 1 || C < 1 || Kh < 1 || Kw < 1 || plan->chunks < 1) return 0;
+    const size_t n_cog = (size_t)(Co + 7) / 8 + (plan->bipolar ? 1 : 0);
+    size_t bytes = round256(n_cog * C * Kh * plan->chunks * 8 * 4);
+    if (plan->bipolar) bytes += round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4);
+    return bytes;
+}
+
+extern "C" int hikonv_pack_weights(const hikonv_plan_t *plan, const void *w_dev, int Co, int C, int Kh, int Kw,
+                                   void *packed_dev, void *stream)
+{
+    if (!plan || !w_dev || !packed_dev || Co < 1 || C < 1 || Kh < 1 || Kw < 1) return HIKONV_EINVAL;
+    if (plan->mode != HIKONV_MODE_DNN || plan->taps != Kw || plan->K < 1 || plan->S < 1) return HIKONV_EINVAL;
+    if (plan->chunks != (Kw + plan->K - 1) / plan->K || !aligned(packed_dev, 256)) return HIKONV_EINVAL;
+    Conv2dGeom g = {};
+    g.n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
+    g.wp_bytes = round256((size_t)g.n_cog * C * Kh * plan->chunks * 8 * 4);
+    return pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, packed_dev, static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, int Kh,
+                                                int Kw, int stride, int pad, int prepacked)
+{
+    Conv2dGeom g;
+    if (conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g) != HIKONV_OK) return 0;
+    return g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+}
+
+extern "C" int hikonv_conv2d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,
+                             const void *w_dev, int Co, int Kh, int Kw, int stride, int pad, void *workspace_dev,
+                             size_t workspace_bytes, int32_t *y_dev, void *stream)
+{
+    return conv2d_impl(plan, x_dev, x_format, N, C, H, W, w_dev, 0, Co, Kh, Kw, stride, pad, workspace_dev,
+                       workspace_bytes, y_dev, stream);
+}
+
+extern "C" int hikonv_conv2d_prepacked(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C,
+                                       int H, int W, const void *w_packed_dev, int Co, int Kh, int Kw, int stride,
+                                       int pad, void *workspace_dev, size_t workspace_bytes, int32_t *y_dev,
+                                       void *stream)
+{
+    return conv2d_impl(plan, x_dev, x_format, N, C, H, W, w_packed_dev, 1, Co, Kh, Kw, stride, pad, workspace_dev,
+                       workspace_bytes, y_dev, stream);
+}
+
+extern "C" int hikonv_conv2d_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int N, int C, int H,
+                                      int W, const void *w_dev, int Co, int Kh, int Kw, int stride, int pad,
+                                      int32_t *y_dev, void *stream)
+{
+    if (bits_a < 1 || bits_a > 8 || bits_w < 1 || bits_w > 8 || signedness < 0 || signedness > 7) return HIKONV_EINVAL;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || Co < 1 || Kh < 1 || Kw < 1 || stride < 1 || pad < 0) return HIKONV_EINVAL;
+    if (H + 2 * pad < Kh || W + 2 * pad < Kw || !x_dev || !w_dev || !y_dev) return HIKONV_EINVAL;
+    Conv2dDirectArgs a;
+    a.x = static_cast<const uint8_t *>(x_dev);
+    a.w = static_cast<const uint8_t *>(w_dev);
+    const bool bip = (signedness & HIKONV_BIPOLAR) != 0;
+    a.a_signed = bip || (signedness & HIKONV_A_SIGNED);
+    a.w_signed = bip || (signedness & HIKONV_W_SIGNED);
+    a.Nimg = N;
+    a.C = C;
+    a.H = H;
+    a.W = W;
+    a.Co = Co;
+    a.Kh = Kh;
+    a.Kw = Kw;
+    a.stride = stride;
+    a.pad = pad;
+    a.Ho = (H + 2 * pad - Kh) / stride + 1;
+    a.Wo = (W + 2 * pad - Kw) / stride + 1;
+    a.y = y_dev;
+    return hip_result(launch_conv2d_unpacked(a, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int hikonv_epilogue(const int32_t *acc_dev, int N, int C, int H, int W, int shift, int qmax, int pool,
+                               int out_bits, int out_format, void *out_dev, void *stream)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || shift < 0 || shift > 31 || container_bits(out_bits) == 0) return HIKONV_EINVAL;
+    if (qmax < 0 || qmax > (1 << out_bits) - 1 || !acc_dev || !out_dev || !aligned(out_dev, 4)) return HIKONV_EINVAL;
+    if (out_format != HIKONV_FMT_INT8 && out_format != HIKONV_FMT_BITDENSE) return HIKONV_EINVAL;
+    EpilogueArgs a;
+    a.acc = acc_dev;
+    a.Nimg = N;
+    a.C = C;
+    a.H = H;
+    a.W = W;
+    a.shift = shift;
+    a.qmax = qmax;
+    a.pool = pool ? 1 : 0;
+    a.Ho = pool ? H / 2 : H;
+    a.Wo = pool ? W / 2 : W;
+    if (a.Ho < 1 || a.Wo < 1) return HIKONV_EINVAL;
+    a.out_format = out_format;
+    a.c = out_format == HIKONV_FMT_BITDENSE ? container_bits(out_bits) : 8;
+    a.out_row_bytes = out_format == HIKONV_FMT_BITDENSE ? hikonv_bitdense_row_bytes(a.Wo, out_bits) : a.Wo;
+    a.out = static_cast<uint8_t *>(out_dev);
+    return hip_result(launch_epilogue(a, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream)
+{
+    if (!buf_dev || iters < 0 || blocks < 1 || blocks > (1 << 20) || !aligned(buf_dev, 16)) return HIKONV_EINVAL;
+    return hip_result(launch_ubench(kind, iters, blocks, buf_dev, bytes, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int hikonv_selftest_lane_shift(int32_t *out_dev, void *stream)
+{
+    if (!out_dev) return HIKONV_EINVAL;
+    return hip_result(launch_selftest_lane_shift(out_dev, static_cast<hipStream_t>(stream)));
+}

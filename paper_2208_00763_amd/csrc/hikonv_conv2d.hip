@@ -1,0 +1,259 @@
+// Kernels around the packed DNN-layer path: runtime packing of activation rows into A
+// words, offline packing of weights into B words, the {-1,+1} correction for binarised
+// layers, and the unpacked one-product-per-multiply baseline.
+#include <type_traits>
+#include "hikonv_conv2d_kernel.h"
+
+namespace hikonv {
+namespace {
+
+// A[chunk][n][ci][hp][xi] = sum_j f[(xi-1)N + j - chunk*K] 2^(S j), f = row hp-pad of the
+// image (zero outside it; Eq. I_PRIME / Eq. pad_f0).  Word xi = 0 of every row is zero.
+// The leading horizontal padding is not materialised: it only shifts the index at which
+// an output is read (Eq. off).
+__global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
+{
+    const int64_t total = (int64_t)p.chunks * p.Nimg * p.C * p.Hp * p.Xs;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int xi = (int)(idx % p.Xs);
+    int64_t t = idx / p.Xs;
+    const int hp = (int)(t % p.Hp);
+    t /= p.Hp;
+    const int64_t nc = t % ((int64_t)p.Nimg * p.C);
+    const int ch = (int)(t / ((int64_t)p.Nimg * p.C));
+    const int h = hp - p.pad;
+    uint32_t a = 0;
+    if (xi > 0 && h >= 0 && h < p.H) {
+        const uint8_t *rowp = static_cast<const uint8_t *>(p.x) + (nc * p.H + h) * p.row_bytes;
+        const int e0 = (xi - 1) * p.N - ch * p.Kp;
+        for (int j = 0; j < p.N; ++j) {
+            const int i = e0 + j;
+            if (i < 0 || i >= p.W) continue;
+            int32_t v;
+            if (p.x_format == HIKONV_FMT_INT8) {
+                const uint8_t byte = rowp[i];
+                if (p.bipolar)
+                    v = (int8_t)byte > 0 ? 1 : 0;
+                else
+                    v = p.a_signed ? __builtin_amdgcn_sbfe((int)byte, 0, p.b) : (int)__builtin_amdgcn_ubfe(byte, 0, p.b);
+            } else {
+                const int bit = i * p.c;
+                const uint32_t w = reinterpret_cast<const uint32_t *>(rowp)[bit >> 5];
+                v = (p.a_signed && !p.bipolar) ? __builtin_amdgcn_sbfe((int)w, bit & 31, p.b)
+                                               : (int)__builtin_amdgcn_ubfe(w, bit & 31, p.b);
+            }
+            a += (uint32_t)v << (p.S * j);
+        }
+    }
+    p.apk[idx] = a;
+}
+
+// B[group][term][8], term = (ci*Kh + kh)*chunks + chunk, word = sum_k g[chunk*K + k] 2^(S k)
+// with g = the reversed kernel row W[co][ci][kh][Kw-1:0] (Eq. I_PRIME).
+__global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
+{
+    const int terms = p.C * p.Kh * p.chunks;
+    const int64_t total = (int64_t)p.n_cog * terms * 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int c8 = (int)(idx & 7);
+    const int term = (int)((idx >> 3) % terms);
+    const int cog = (int)((idx >> 3) / terms);
+    const int ch = term % p.chunks;
+    const int kh = (term / p.chunks) % p.Kh;
+    const int ci = term / (p.chunks * p.Kh);
+    const int co = cog * 8 + c8;
+    const bool ones_group = p.bipolar && cog == p.n_cog - 1;
+    uint32_t bw = 0;
+    for (int k = 0; k < p.Kp; ++k) {
+        const int j = ch * p.Kp + k; // tap of the reversed row
+        if (j >= p.Kw) break;
+        int32_t v = 0;
+        if (ones_group) {
+            v = c8 == 0 ? 1 : 0;
+        } else if (co < p.Co) {
+            const uint8_t byte = p.w[(((int64_t)co * p.C + ci) * p.Kh + kh) * p.Kw + (p.Kw - 1 - j)];
+            if (p.bipolar)
+                v = (int8_t)byte > 0 ? 1 : 0;
+            else
+                v = p.w_signed ? (int32_t)(int8_t)byte : (int32_t)byte;
+        }
+        bw += (uint32_t)v << (p.S * k);
+    }
+    p.wp[idx] = bw;
+}
+
+// PS[co][i][j] = sum_{kh<i, kw<j} sum_ci beta[co][ci][kh][kw]   (beta = 1 for weight +1)
+__global__ __launch_bounds__(256) void k_weight_prefix(PackWArgs p)
+{
+    const int per_co = (p.Kh + 1) * (p.Kw + 1);
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= p.Co * per_co) return;
+    const int co = idx / per_co, i = (idx % per_co) / (p.Kw + 1), j = idx % (p.Kw + 1);
+    int32_t s = 0;
+    for (int ci = 0; ci < p.C; ++ci)
+        for (int kh = 0; kh < i; ++kh)
+            for (int kw = 0; kw < j; ++kw)
+                s += (int8_t)p.w[(((int64_t)co * p.C + ci) * p.Kh + kh) * p.Kw + kw] > 0 ? 1 : 0;
+    p.ps[idx] = s;
+}
+
+// {-1,+1} layers: with x = 2a - m and w = 2 beta - 1 (a, beta in {0,1}; m = 1 inside the
+// image, 0 in the zero padding):  sum x w = 4 sum a beta - 2 sum a - 2 sum m beta + sum m.
+__global__ __launch_bounds__(256) void k_bipolar_fix(BipolarFixArgs p)
+{
+    const int64_t total = (int64_t)p.Nimg * p.Co * p.Ho * p.Wo;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int wo = (int)(idx % p.Wo);
+    const int ho = (int)((idx / p.Wo) % p.Ho);
+    const int co = (int)((idx / ((int64_t)p.Wo * p.Ho)) % p.Co);
+    const int n = (int)(idx / ((int64_t)p.Wo * p.Ho * p.Co));
+    int kh_lo = p.pad - ho * p.stride, kh_hi = p.H + p.pad - ho * p.stride;
+    int kw_lo = p.pad - wo * p.stride, kw_hi = p.W + p.pad - wo * p.stride;
+    kh_lo = kh_lo < 0 ? 0 : kh_lo;
+    kw_lo = kw_lo < 0 ? 0 : kw_lo;
+    kh_hi = kh_hi > p.Kh ? p.Kh : kh_hi;
+    kw_hi = kw_hi > p.Kw ? p.Kw : kw_hi;
+    const int32_t *ps = p.ps + (int64_t)co * (p.Kh + 1) * (p.Kw + 1);
+    const int st = p.Kw + 1;
+    const int32_t rect = ps[kh_hi * st + kw_hi] - ps[kh_lo * st + kw_hi] - ps[kh_hi * st + kw_lo] + ps[kh_lo * st + kw_lo];
+    const int32_t cnt = (kh_hi - kh_lo) * (kw_hi - kw_lo);
+    const int32_t sa = p.sa[((int64_t)n * p.Ho + ho) * p.Wo + wo];
+    p.y[idx] = 4 * p.y[idx] - 2 * sa - 2 * rect + p.C * cnt;
+}
+
+// Baseline: direct layer, one v_mad_i32_i24 per low-bit product.  One lane owns one output
+// pixel and 8 output channels; the weights of 16 input channels are staged in LDS as int32.
+constexpr int kCiTile = 16;
+constexpr int kMaxTaps2d = 49;
+
+template <bool A_SIGNED>
+__global__ __launch_bounds__(256) void k_conv2d_unpacked(Conv2dDirectArgs p)
+{
+    __shared__ __attribute__((aligned(16))) int32_t s_w[kCiTile * kMaxTaps2d * 8];
+    const int64_t pix = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t npix = (int64_t)p.Nimg * p.Ho * p.Wo;
+    const bool active = pix < npix;
+    const int64_t pc = active ? pix : 0;
+    const int wo = (int)(pc % p.Wo), ho = (int)((pc / p.Wo) % p.Ho), n = (int)(pc / ((int64_t)p.Wo * p.Ho));
+    const int co0 = blockIdx.y * 8;
+    const int taps = p.Kh * p.Kw;
+    int32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int ci0 = 0; ci0 < p.C; ci0 += kCiTile) {
+        const int nci = p.C - ci0 < kCiTile ? p.C - ci0 : kCiTile;
+        __syncthreads();
+        for (int i = threadIdx.x; i < nci * taps * 8; i += 256) {
+            const int c8 = i & 7, t = (i >> 3) % taps, ci = (i >> 3) / taps;
+            int32_t v = 0;
+            if (co0 + c8 < p.Co) {
+                const uint8_t byte = p.w[((int64_t)(co0 + c8) * p.C + ci0 + ci) * taps + t];
+                v = p.w_signed ? (int32_t)(int8_t)byte : (int32_t)byte;
+            }
+            s_w[i] = v;
+        }
+        __syncthreads();
+        for (int ci = 0; ci < nci; ++ci) {
+            const uint8_t *xc = p.x + ((int64_t)n * p.C + ci0 + ci) * p.H * p.W;
+            for (int kh = 0; kh < p.Kh; ++kh) {
+                const int ih = ho * p.stride + kh - p.pad;
+                for (int kw = 0; kw < p.Kw; ++kw) {
+                    const int iw = wo * p.stride + kw - p.pad;
+                    int32_t v = 0;
+                    if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) {
+                        const uint8_t byte = xc[(int64_t)ih * p.W + iw];
+                        v = A_SIGNED ? (int32_t)(int8_t)byte : (int32_t)byte;
+                    }
+                    const int4 *wv = reinterpret_cast<const int4 *>(&s_w[(ci * taps + kh * p.Kw + kw) * 8]);
+                    const int4 w0 = wv[0], w1 = wv[1];
+                    acc[0] = __mul24(v, w0.x) + acc[0];
+                    acc[1] = __mul24(v, w0.y) + acc[1];
+                    acc[2] = __mul24(v, w0.z) + acc[2];
+                    acc[3] = __mul24(v, w0.w) + acc[3];
+                    acc[4] = __mul24(v, w1.x) + acc[4];
+                    acc[5] = __mul24(v, w1.y) + acc[5];
+                    acc[6] = __mul24(v, w1.z) + acc[6];
+                    acc[7] = __mul24(v, w1.w) + acc[7];
+                }
+            }
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        if (co0 + c < p.Co) p.y[(((int64_t)n * p.Co + co0 + c) * p.Ho + ho) * p.Wo + wo] = acc[c];
+}
+
+inline hipError_t grid_1d(int64_t total, dim3 *g)
+{
+    const int64_t blocks = ceil_div(total, 256);
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    *g = dim3((unsigned)blocks);
+    return hipSuccess;
+}
+
+} // namespace
+
+hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
+{
+    dim3 g;
+    hipError_t e = grid_1d((int64_t)a.chunks * a.Nimg * a.C * a.Hp * a.Xs, &g);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_pack_act, g, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream)
+{
+    dim3 g;
+    hipError_t e = grid_1d((int64_t)a.n_cog * a.C * a.Kh * a.chunks * 8, &g);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_pack_weights, g, dim3(256), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess || !a.bipolar) return e;
+    e = grid_1d((int64_t)a.Co * (a.Kh + 1) * (a.Kw + 1), &g);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_weight_prefix, g, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed, int co_tile, hipStream_t stream)
+{
+    int64_t waves;
+    if (a.segs == 0)
+        waves = ceil_div(a.wave_rows, a.rows_per_wave);
+    else
+        waves = a.wave_rows * a.segs;
+    const int64_t gx = ceil_div(waves, 4);
+    const int64_t gy = ceil_div(a.Co, co_tile);
+    if (gx <= 0 || gx > 0x7fffffffLL || gy <= 0 || gy > 65535) return hipErrorInvalidValue;
+    dim3 g((unsigned)gx, (unsigned)gy);
+    return wide ? launch_conv2d_wide(a, any_signed, co_tile, g, stream)
+                : launch_conv2d_narrow(a, any_signed, co_tile, g, stream);
+}
+
+hipError_t launch_bipolar_fix(const BipolarFixArgs &a, hipStream_t stream)
+{
+    dim3 g;
+    hipError_t e = grid_1d((int64_t)a.Nimg * a.Co * a.Ho * a.Wo, &g);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_bipolar_fix, g, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv2d_unpacked(const Conv2dDirectArgs &a, hipStream_t stream)
+{
+    if (a.Kh * a.Kw > kMaxTaps2d) return hipErrorInvalidValue;
+    const int64_t gx = ceil_div((int64_t)a.Nimg * a.Ho * a.Wo, 256);
+    const int64_t gy = ceil_div(a.Co, 8);
+    if (gx <= 0 || gx > 0x7fffffffLL || gy <= 0 || gy > 65535) return hipErrorInvalidValue;
+    dim3 g((unsigned)gx, (unsigned)gy);
+    if (a.a_signed)
+        hipLaunchKernelGGL((k_conv2d_unpacked<true>), g, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((k_conv2d_unpacked<false>), g, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+} // namespace hikonv

@@ -1,0 +1,11 @@
+// Instantiations of the packed layer kernel with the 24x24+32 multiply-accumulate.
+#include <type_traits>
+#include "hikonv_conv2d_kernel.h"
+
+namespace hikonv {
+hipError_t launch_conv2d_narrow(const Conv2dArgs &a, bool any_signed, int co_tile, dim3 g, hipStream_t stream)
+{
+    return any_signed ? launch_conv2d_sw<true, false>(a, co_tile, g, stream)
+                      : launch_conv2d_sw<false, false>(a, co_tile, g, stream);
+}
+} // namespace hikonv

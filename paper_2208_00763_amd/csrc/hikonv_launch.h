@@ -1,0 +1,107 @@
+// Host-visible kernel argument blocks and launcher prototypes (internal to libhikonv.so).
+#ifndef HIKONV_LAUNCH_H
+#define HIKONV_LAUNCH_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hikonv_internal.h"
+
+namespace hikonv {
+
+struct Conv1dArgs {
+    const uint32_t *x;       // input buffer (4-byte aligned), rows back to back
+    int64_t total_dwords;    // whole dwords in the buffer
+    int64_t total_bytes;     // bytes in the buffer
+    int64_t row_stride_bits; // bits from one row's element 0 to the next row's
+    int64_t rows, len;
+    int c, b;                // container bits, value bits
+    const uint8_t *g;        // taps bytes
+    int taps, w_signed;
+    int N, Kp, S, chunks;    // plan
+    int shift_m;             // taps-1 for VALID output, 0 for FULL
+    int64_t out_len;
+    int64_t n_blocks;        // packed blocks per row
+    int CH;                  // wave-chunks of 63 blocks per wave
+    int64_t tiles_per_row;
+    int32_t *y;
+};
+
+int conv1d_tile_chunks(int N, int64_t n_blocks);
+hipError_t launch_conv1d_packed(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
+hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream);
+
+// ---- 2-D ---------------------------------------------------------------------------
+
+struct PackActArgs {
+    const void *x;           // NCHW activations, INT8 or bit-dense rows
+    int x_format, c, b, a_signed, bipolar;
+    int64_t row_bytes;       // bytes per W-row of x (bit-dense: padded; INT8: W)
+    int Nimg, C, H, W, pad;
+    int N, Kp, S, chunks;    // plan
+    int Hp, Xs;              // padded rows (H + 2 pad), words per packed row (1 zero word + blocks)
+    uint32_t *apk;           // [chunks][Nimg][C][Hp][Xs]
+};
+hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream);
+
+struct PackWArgs {
+    const uint8_t *w;        // [Co][C][Kh][Kw], one value per byte
+    int Co, C, Kh, Kw, w_signed, bipolar;
+    int Kp, S, chunks;
+    int n_cog;               // ceil(Co / 8) (+1 all-ones group when bipolar)
+    uint32_t *wp;            // [n_cog][C*Kh*chunks][8]
+    int32_t *ps;             // bipolar only: [Co][Kh+1][Kw+1] prefix sums of sum_ci beta
+};
+hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream);
+
+struct Conv2dArgs {
+    const uint32_t *apk;     // packed activations
+    const uint32_t *wp;      // packed weights, group-of-8 layout
+    int Nimg, C, Ho, Wo1;    // Wo1 = stride-1 output width
+    int Kh, stride, off;     // off = Kw - 1 - pad: output w sits at row-convolution index w + off
+    int Hp, Xs, X;           // packed rows per image-channel, words per row, blocks per row
+    int N, S, chunks, M;     // plan; M = products accumulated per split
+    int terms;               // C*Kh*chunks
+    int Co, cog0;            // output channels to write, first weight group
+    int64_t chunk_stride;    // words between chunk planes of apk
+    int rows_per_wave, segs; // lane mapping
+    int64_t wave_rows;       // total rows = Nimg*Ho
+    int Wo;                  // strided output width
+    int32_t *y;              // [Nimg][Co][Ho][Wo]
+};
+hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed, int co_tile,
+                                hipStream_t stream);
+
+struct BipolarFixArgs {
+    int32_t *y;              // in: sum a*beta; out: sum x*w
+    const int32_t *sa;       // [Nimg][Ho][Wo] window sums of a
+    const int32_t *ps;       // [Co][Kh+1][Kw+1]
+    int Nimg, Co, Ho, Wo, C, H, W, Kh, Kw, stride, pad;
+};
+hipError_t launch_bipolar_fix(const BipolarFixArgs &a, hipStream_t stream);
+
+struct Conv2dDirectArgs {
+    const uint8_t *x, *w;
+    int a_signed, w_signed;
+    int Nimg, C, H, W, Co, Kh, Kw, stride, pad, Ho, Wo;
+    int32_t *y;
+};
+hipError_t launch_conv2d_unpacked(const Conv2dDirectArgs &a, hipStream_t stream);
+
+struct EpilogueArgs {
+    const int32_t *acc;
+    int Nimg, C, H, W, shift, qmax, pool, Ho, Wo;
+    int out_format, c;       // container bits when bit-dense
+    int64_t out_row_bytes;
+    uint8_t *out;
+};
+hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t stream);
+
+// ---- misc --------------------------------------------------------------------------
+hipError_t launch_compact(const uint8_t *x, int64_t rows, int64_t len, int bits, int bipolar,
+                          uint32_t *out, int64_t row_dwords, hipStream_t stream);
+hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t bytes, hipStream_t stream);
+hipError_t launch_selftest_lane_shift(int32_t *out, hipStream_t stream);
+
+} // namespace hikonv
+#endif

@@ -1,0 +1,209 @@
+// Small kernels around the hot path: runtime feature compression to the bit-dense format,
+// the un-accelerated layer epilogue of the complete-model experiment, roofline
+// micro-benchmarks, and a lane-exchange self check.
+#include "hikonv_device.h"
+#include "hikonv_launch.h"
+
+namespace hikonv {
+namespace {
+
+// one thread per output dword of the bit-dense stream
+__global__ __launch_bounds__(256) void k_compact(const uint8_t *x, int64_t rows, int64_t len, int b, int c,
+                                                 int bipolar, uint32_t *out, int64_t row_dwords)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * row_dwords) return;
+    const int64_t r = idx / row_dwords, j = idx % row_dwords;
+    const int per = 32 / c;
+    const uint32_t vmask = (1u << b) - 1u;
+    uint32_t word = 0;
+    for (int t = 0; t < per; ++t) {
+        int64_t i = j * per + t;
+        if (i < len) {
+            uint8_t v = x[r * len + i];
+            uint32_t f = bipolar ? ((int8_t)v > 0 ? 1u : 0u) : ((uint32_t)v & vmask);
+            word |= f << (t * c);
+        }
+    }
+    out[idx] = word;
+}
+
+// ReLU + requantise (+ 2x2 max-pool), one thread per output byte (INT8) or dword (bit-dense)
+__global__ __launch_bounds__(256) void k_epilogue(EpilogueArgs p)
+{
+    const int per = p.out_format == HIKONV_FMT_BITDENSE ? 32 / p.c : 1;
+    const int64_t units_per_row = p.out_format == HIKONV_FMT_BITDENSE ? p.out_row_bytes / 4 : p.Wo;
+    const int64_t rows = (int64_t)p.Nimg * p.C * p.Ho;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * units_per_row) return;
+    const int64_t row = idx / units_per_row, j = idx % units_per_row;
+    const int64_t nc = row / p.Ho;
+    const int h = (int)(row % p.Ho);
+    const int32_t *src = p.acc + nc * p.H * p.W;
+    uint32_t word = 0;
+    for (int t = 0; t < per; ++t) {
+        int64_t w = j * per + t;
+        if (w >= p.Wo) break;
+        int32_t v;
+        if (p.pool) {
+            const int32_t *s0 = src + (int64_t)(2 * h) * p.W + 2 * w;
+            int32_t a = s0[0], b = s0[1], cc = s0[p.W], d = s0[p.W + 1];
+            v = max(max(a, b), max(cc, d));
+        } else {
+            v = src[(int64_t)h * p.W + w];
+        }
+        v = v < 0 ? 0 : v;
+        v >>= p.shift;
+        v = v > p.qmax ? p.qmax : v;
+        word |= (uint32_t)v << (t * p.c);
+    }
+    if (p.out_format == HIKONV_FMT_BITDENSE)
+        reinterpret_cast<uint32_t *>(p.out + row * p.out_row_bytes)[j] = word;
+    else
+        p.out[row * p.Wo + j] = (uint8_t)word;
+}
+
+// ---- micro-benchmarks --------------------------------------------------------------
+template <int KIND>
+__global__ __launch_bounds__(256) void k_ubench_valu(int iters, uint32_t *buf, uint32_t s1, uint32_t s2)
+{
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    uint32_t a[8];
+    uint64_t w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = t * 2654435761u + i * 40503u + s1;
+        w[i] = ((uint64_t)a[i] << 32) | (a[i] ^ 0x9e3779b9u);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                // every chain feeds on its neighbour so that nothing folds into a closed form
+                const int nb = (i + 1) & 7;
+                if (KIND == HIKONV_UB_MAD_U32_U24) a[i] = __umul24(a[i], a[nb]) + s2;
+                if (KIND == HIKONV_UB_MAD_I32_I24) a[i] = (uint32_t)(__mul24((int)a[i], (int)a[nb]) + (int)s2);
+                if (KIND == HIKONV_UB_MAD_U64_U32) w[i] = (uint64_t)(uint32_t)w[nb] * (uint64_t)s1 + w[i];
+                if (KIND == HIKONV_UB_MAD_I64_I32)
+                    w[i] = (uint64_t)((int64_t)(int32_t)w[nb] * (int64_t)(int32_t)s1 + (int64_t)w[i]);
+                if (KIND == HIKONV_UB_MUL_LO_U32) a[i] = a[i] * a[nb];
+                if (KIND == HIKONV_UB_BFE_U32) a[i] = __builtin_amdgcn_ubfe(a[nb], s2, s1 + 20u) + 0u;
+                if (KIND == HIKONV_UB_LSHR_B64) w[i] = w[nb] >> s2;
+                if (KIND == HIKONV_UB_DPP_MOV) a[i] = lane_shr1(a[nb]);
+                if (KIND == HIKONV_UB_ADD_U32) a[i] = a[i] + a[nb];
+                if (KIND == HIKONV_UB_ADD_U64) w[i] = w[i] + w[nb];
+                if (KIND == HIKONV_UB_ALIGNBIT) a[i] = funnel_shr(a[i], a[nb], s2);
+                if (KIND == HIKONV_UB_AND_B32) a[i] = a[i] & a[nb];
+            }
+        }
+    }
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += a[i] + (uint32_t)w[i] + (uint32_t)(w[i] >> 32);
+    buf[t] = sum;
+}
+
+__global__ __launch_bounds__(256) void k_ubench_write(int4 *dst, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int4 v = make_int4(threadIdx.x, blockIdx.x, 3, 4);
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = v;
+}
+
+__global__ __launch_bounds__(256) void k_ubench_copy(const int4 *src, int4 *dst, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_ubench_read(const int4 *src, int64_t n16, int *sink)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int acc = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+        int4 v = src[i];
+        acc += v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x7fffffff) sink[0] = acc; // practically never: keeps the loads alive
+}
+
+__global__ void k_selftest_lane_shift(int32_t *out)
+{
+    out[threadIdx.x] = (int32_t)lane_shr1((uint32_t)(threadIdx.x + 100));
+}
+
+} // namespace
+
+hipError_t launch_compact(const uint8_t *x, int64_t rows, int64_t len, int bits, int bipolar, uint32_t *out,
+                          int64_t row_dwords, hipStream_t stream)
+{
+    const int64_t total = rows * row_dwords;
+    if (total <= 0) return hipSuccess;
+    const int64_t grid = ceil_div(total, 256);
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_compact, dim3((unsigned)grid), dim3(256), 0, stream, x, rows, len, bits,
+                       container_bits(bits), bipolar, out, row_dwords);
+    return hipGetLastError();
+}
+
+hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t stream)
+{
+    const int64_t units = a.out_format == HIKONV_FMT_BITDENSE ? a.out_row_bytes / 4 : a.Wo;
+    const int64_t total = (int64_t)a.Nimg * a.C * a.Ho * units;
+    if (total <= 0) return hipSuccess;
+    const int64_t grid = ceil_div(total, 256);
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_epilogue, dim3((unsigned)grid), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t bytes, hipStream_t stream)
+{
+    dim3 g((unsigned)blocks), b(256);
+    uint32_t *u = static_cast<uint32_t *>(buf);
+    switch (kind) {
+#define HIKONV_UB_CASE(K)                                                                      \
+    case K:                                                                                    \
+        if (bytes < (size_t)blocks * 256 * 4) return hipErrorInvalidValue;                     \
+        hipLaunchKernelGGL((k_ubench_valu<K>), g, b, 0, stream, iters, u, 3u, 1u);             \
+        break;
+        HIKONV_UB_CASE(HIKONV_UB_MAD_U32_U24)
+        HIKONV_UB_CASE(HIKONV_UB_MAD_U64_U32)
+        HIKONV_UB_CASE(HIKONV_UB_MUL_LO_U32)
+        HIKONV_UB_CASE(HIKONV_UB_BFE_U32)
+        HIKONV_UB_CASE(HIKONV_UB_LSHR_B64)
+        HIKONV_UB_CASE(HIKONV_UB_DPP_MOV)
+        HIKONV_UB_CASE(HIKONV_UB_ADD_U32)
+        HIKONV_UB_CASE(HIKONV_UB_MAD_I32_I24)
+        HIKONV_UB_CASE(HIKONV_UB_MAD_I64_I32)
+        HIKONV_UB_CASE(HIKONV_UB_ADD_U64)
+        HIKONV_UB_CASE(HIKONV_UB_ALIGNBIT)
+        HIKONV_UB_CASE(HIKONV_UB_AND_B32)
+#undef HIKONV_UB_CASE
+    case HIKONV_UB_HBM_WRITE:
+        hipLaunchKernelGGL(k_ubench_write, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));
+        break;
+    case HIKONV_UB_HBM_COPY: {
+        const int64_t half16 = (int64_t)(bytes / 32);
+        hipLaunchKernelGGL(k_ubench_copy, g, b, 0, stream, static_cast<const int4 *>(buf),
+                           static_cast<int4 *>(buf) + half16, half16);
+        break;
+    }
+    case HIKONV_UB_HBM_READ:
+        if (bytes < 32) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(k_ubench_read, g, b, 0, stream, static_cast<const int4 *>(buf) + 1,
+                           (int64_t)(bytes / 16) - 1, static_cast<int *>(buf));
+        break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_selftest_lane_shift(int32_t *out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_selftest_lane_shift, dim3(1), dim3(64), 0, stream, out);
+    return hipGetLastError();
+}
+
+} // namespace hikonv

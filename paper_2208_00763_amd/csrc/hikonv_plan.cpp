@@ -1,0 +1,326 @@
+// Host-side planner: the paper's performance model (Section "Multiplier for
+// Convolution", Eq. slice1-slice3, the guard-bit cases of "Maximizing Processing
+// Throughput", Eq. tot_ops and Algorithm 1), plus the exactness checks the model leaves
+// out for signed data and for accumulation in a register of finite width.
+//
+// Differences from the printed algorithm (all deliberate):
+//  * Eq. slice1's 1-bit cases are honoured (Algorithm 1 prints p+q+G_b only);
+//  * every n in [1,L_A], k in [1,L_B] is tried (the printed loop bounds cut off the optimum);
+//    order is the algorithm's: k outer, n inner, strict improvement;
+//  * a candidate is kept only if every segment sum, both packed operands and the
+//    accumulated product provably fit (exact interval arithmetic); when the slice of
+//    Eq. slice1 is one bit short for signed data, S+1 is tried;
+//  * with a fixed tap count the kernel may be cut into chunks of K taps;
+//  * outside single-multiplier mode K <= N+1 is required (one-neighbour overlap-add).
+#include "hikonv_internal.h"
+
+namespace {
+
+typedef __int128 i128;
+
+inline int ceil_log2(long long x)
+{
+    int e = 0;
+    while ((1LL << e) < x) ++e;
+    return e;
+}
+
+inline int slice_bits(int p, int q, int gb)
+{
+    if (p == 1) return q + gb;
+    if (q == 1) return p + gb;
+    return p + q + gb;
+}
+
+struct Range {
+    i128 lo, hi;
+};
+
+inline Range value_range(int bits, bool is_signed)
+{
+    if (is_signed) return Range{-((i128)1 << (bits - 1)), ((i128)1 << (bits - 1)) - 1};
+    return Range{0, ((i128)1 << bits) - 1};
+}
+
+inline Range mul_range(Range a, Range b)
+{
+    i128 c[4] = {a.lo * b.lo, a.lo * b.hi, a.hi * b.lo, a.hi * b.hi};
+    Range r{c[0], c[0]};
+    for (int i = 1; i < 4; ++i) {
+        if (c[i] < r.lo) r.lo = c[i];
+        if (c[i] > r.hi) r.hi = c[i];
+    }
+    return r;
+}
+
+inline bool fits_width(Range r, int width, bool is_signed)
+{
+    if (width >= 127) return true;
+    if (is_signed) return r.lo >= -((i128)1 << (width - 1)) && r.hi <= ((i128)1 << (width - 1)) - 1;
+    return r.lo >= 0 && r.hi <= ((i128)1 << width) - 1;
+}
+
+struct Req {
+    int p, q;
+    bool a_signed, w_signed, any_signed;
+    int L_A, L_B, L_acc, mode, M, taps;
+    Range fa, gw, prod;
+};
+
+Req make_req(const hikonv_plan_t &in)
+{
+    Req r;
+    r.p = in.bits_a;
+    r.q = in.bits_w;
+    r.a_signed = in.a_signed != 0 && !in.bipolar;
+    r.w_signed = in.w_signed != 0 && !in.bipolar;
+    r.any_signed = r.a_signed || r.w_signed;
+    r.L_A = in.L_A;
+    r.L_B = in.L_B;
+    r.L_acc = in.L_acc > 0 ? in.L_acc : in.L_A + in.L_B;
+    r.mode = in.mode;
+    r.M = in.mode == HIKONV_MODE_DNN ? (in.M > 0 ? in.M : 1) : 1;
+    r.taps = in.taps;
+    r.fa = value_range(r.p, r.a_signed);
+    r.gw = value_range(r.q, r.w_signed);
+    r.prod = mul_range(r.fa, r.gw);
+    return r;
+}
+
+// Largest number of low-bit products that can meet in one output segment.
+inline long long terms_per_segment(const Req &r, int n, int k)
+{
+    int kk = r.taps ? r.taps : k;
+    switch (r.mode) {
+    case HIKONV_MODE_SINGLE: return n < k ? n : k;
+    case HIKONV_MODE_CONV1D: return kk;
+    default: return (long long)r.M * kk;
+    }
+}
+
+inline int guard_bits(const Req &r, int n, int k) { return ceil_log2(terms_per_segment(r, n, k)); }
+
+// Eq. slice2 / slice3 as printed (bit counting only).
+inline bool paper_fits(const Req &r, int n, int k, int s)
+{
+    return r.p + (long long)(n - 1) * s <= r.L_A && r.q + (long long)(k - 1) * s <= r.L_B;
+}
+
+// Exact check of (n, k, s): segment fields, operand words, accumulator.
+bool exact_ok(const Req &r, int n, int k, int s)
+{
+    if (s < 1 || s > 62) return false;
+    // operands are at most 64 bits wide: longer packings cannot fit (and would overflow the checks below)
+    if ((long long)s * (n - 1) >= 64 || (long long)s * (k - 1) >= 64) return false;
+    // the kernels overlap-add a block with its immediate neighbour only: the K-1 high
+    // segments of a product must land inside the next block's N low segments
+    if (r.mode != HIKONV_MODE_SINGLE && k - 1 > n) return false;
+    const long long t = terms_per_segment(r, n, k);
+    const Range seg{r.prod.lo * t, r.prod.hi * t};
+    if (r.any_signed) {
+        // symmetric bound: the carried-sign split needs value-1 to fit as well
+        const i128 lim = ((i128)1 << (s - 1)) - 1;
+        if (seg.lo < -lim || seg.hi > lim) return false;
+    } else {
+        if (seg.hi > ((i128)1 << s) - 1) return false;
+    }
+    i128 rn = 0, rk = 0;
+    for (int i = 0; i < n; ++i) rn += (i128)1 << (s * i);
+    for (int i = 0; i < k; ++i) rk += (i128)1 << (s * i);
+    if (!fits_width(Range{r.fa.lo * rn, r.fa.hi * rn}, r.L_A, r.any_signed)) return false;
+    if (!fits_width(Range{r.gw.lo * rk, r.gw.hi * rk}, r.L_B, r.any_signed)) return false;
+    // a register of 127+ bits always holds one product of two <= 64-bit operands
+    if (r.L_acc >= 127) return r.M == 1 && r.mode == HIKONV_MODE_SINGLE;
+    if ((long long)s * (n + k - 1) > 120) return false;
+    // accumulated word: per multiply, segment m holds c_m = #{(i,j): i+j=m} products; every
+    // multiply that lands in the word before a split adds to it
+    const int chunks = r.taps ? (r.taps + k - 1) / k : 1;
+    const long long mults = (long long)r.M * chunks;
+    Range acc{0, 0};
+    for (int m = 0; m < n + k - 1; ++m) {
+        int lo_i = m - (k - 1) > 0 ? m - (k - 1) : 0;
+        int hi_i = m < n - 1 ? m : n - 1;
+        long long c = (long long)(hi_i - lo_i + 1) * mults;
+        // after the overlap-add the N low fields hold complete outputs
+        if (r.mode != HIKONV_MODE_SINGLE && m < n && c < t) c = t;
+        acc.lo += r.prod.lo * c * ((i128)1 << (s * m));
+        acc.hi += r.prod.hi * c * ((i128)1 << (s * m));
+    }
+    if (r.any_signed && r.mode != HIKONV_MODE_SINGLE) {
+        // the kernels add 2^(S-1) to each of the N low fields before reading them
+        for (int m = 0; m < n; ++m) acc.hi += (i128)1 << (s * m + s - 1);
+    }
+    return fits_width(acc, r.L_acc, r.any_signed);
+}
+
+struct Cand {
+    int n = 0, k = 0, s = 0, gb = 0, chunks = 1;
+    bool found = false;
+};
+
+// score comparison: free mode -> Eq. tot_ops; fixed taps -> MACs per multiply n*taps/chunks
+inline bool better(const Req &r, const Cand &c, const Cand &best)
+{
+    if (!best.found) return true;
+    if (r.taps == 0)
+        return (long long)c.n * c.k + (long long)(c.n - 1) * (c.k - 1) >
+               (long long)best.n * best.k + (long long)(best.n - 1) * (best.k - 1);
+    return (long long)c.n * best.chunks > (long long)best.n * c.chunks;
+}
+
+Cand search(const Req &r, bool paper_only)
+{
+    Cand best;
+    auto try_one = [&](int n, int k) {
+        Cand c;
+        c.n = n;
+        c.k = k;
+        c.gb = guard_bits(r, n, k);
+        c.chunks = r.taps ? (r.taps + k - 1) / k : 1;
+        const int s0 = slice_bits(r.p, r.q, c.gb);
+        if (paper_only) {
+            c.s = s0;
+            if (!paper_fits(r, n, k, s0)) return;
+        } else {
+            c.s = 0;
+            for (int s = s0; s <= s0 + 1; ++s)
+                if (exact_ok(r, n, k, s)) {
+                    c.s = s;
+                    break;
+                }
+            if (!c.s) return;
+        }
+        c.found = true;
+        if (better(r, c, best)) best = c;
+    };
+    if (r.taps == 0) {
+        for (int k = 1; k <= r.L_B; ++k)
+            for (int n = 1; n <= r.L_A; ++n) try_one(n, k);
+    } else {
+        for (int k = r.taps; k >= 1; --k)
+            for (int n = r.L_A; n >= 1; --n) try_one(n, k);
+    }
+    return best;
+}
+
+bool valid_request(const hikonv_plan_t &in)
+{
+    if (in.bits_a < 1 || in.bits_a > 8 || in.bits_w < 1 || in.bits_w > 8) return false;
+    if (in.L_A < 1 || in.L_A > 64 || in.L_B < 1 || in.L_B > 64) return false;
+    if (in.L_acc < 0 || in.L_acc > 128) return false;
+    if (in.mode < HIKONV_MODE_SINGLE || in.mode > HIKONV_MODE_DNN) return false;
+    if (in.M < 0 || in.M > (1 << 20) || in.taps < 0 || in.taps > 64) return false;
+    if (in.bipolar && (in.bits_a != 1 || in.bits_w != 1)) return false;
+    return true;
+}
+
+void fill_result(hikonv_plan_t *out, const Req &r, const Cand &c, bool paper_exact)
+{
+    out->L_acc = r.L_acc;
+    out->M = r.M;
+    out->N = c.n;
+    out->K = c.k;
+    out->S = c.s;
+    out->G_b = c.gb;
+    out->chunks = c.chunks;
+    out->ops_per_mul = c.n * c.k + (c.n - 1) * (c.k - 1);
+    out->paper_exact = paper_exact ? 1 : 0;
+}
+
+// Issue-slot model used only to choose M when the caller leaves it open: a wide
+// (32x32+64) multiply-accumulate costs 4 issue slots of a full-rate VALU
+// instruction, a 24-bit one costs 1; a split costs an exchange plus per-segment work.
+double modelled_macs_per_slot(const Req &r, const Cand &c)
+{
+    const bool wide = r.L_acc > 32;
+    const double c_mul = wide ? 4.0 : 1.0;
+    const double c_split = wide ? 10.0 + 3.0 * c.n : 4.0 + 2.0 * c.n;
+    const double macs = (double)r.M * c.n * r.taps;
+    return macs / (r.M * c.chunks * c_mul + c_split);
+}
+
+} // namespace
+
+extern "C" int hikonv_plan_ex(const hikonv_plan_t *request, hikonv_plan_t *out)
+{
+    if (!request || !out) return HIKONV_EINVAL;
+    hikonv_plan_t in = *request;
+    if (!valid_request(in)) return HIKONV_EINVAL;
+    if (in.mode == HIKONV_MODE_DNN && in.M == 0) {
+        // choose M by the issue-slot model; needs a fixed tap count
+        if (in.taps == 0) return HIKONV_EINVAL;
+        double best_score = -1.0;
+        hikonv_plan_t best_plan = in;
+        bool any = false;
+        for (int m = 1; m <= 512; ++m) {
+            hikonv_plan_t trial = in;
+            trial.M = m;
+            Req r = make_req(trial);
+            Cand c = search(r, false);
+            if (!c.found) continue;
+            double sc = modelled_macs_per_slot(r, c);
+            if (sc > best_score * 1.0000001) {
+                best_score = sc;
+                Cand pc = search(r, true);
+                fill_result(&trial, r, c, pc.found && pc.n == c.n && pc.k == c.k && pc.s == c.s);
+                best_plan = trial;
+                any = true;
+            }
+        }
+        if (!any) return HIKONV_ENOPLAN;
+        *out = best_plan;
+        return HIKONV_OK;
+    }
+    Req r = make_req(in);
+    Cand c = search(r, false);
+    if (!c.found) return HIKONV_ENOPLAN;
+    Cand pc = search(r, true);
+    *out = in;
+    fill_result(out, r, c, pc.found && pc.n == c.n && pc.k == c.k && pc.s == c.s);
+    return HIKONV_OK;
+}
+
+extern "C" int hikonv_plan(int bits_a, int bits_w, int signedness, int mult_width, hikonv_plan_t *out)
+{
+    if (!out || signedness < 0 || signedness > 7) return HIKONV_EINVAL;
+    hikonv_plan_t in = {};
+    in.bits_a = bits_a;
+    in.bits_w = bits_w;
+    in.a_signed = (signedness & HIKONV_A_SIGNED) ? 1 : 0;
+    in.w_signed = (signedness & HIKONV_W_SIGNED) ? 1 : 0;
+    in.bipolar = (signedness & HIKONV_BIPOLAR) ? 1 : 0;
+    in.L_A = in.L_B = mult_width;
+    in.L_acc = 2 * mult_width;
+    in.mode = HIKONV_MODE_SINGLE;
+    return hikonv_plan_ex(&in, out);
+}
+
+extern "C" int hikonv_plan_check(const hikonv_plan_t *plan)
+{
+    if (!plan || !valid_request(*plan)) return HIKONV_EINVAL;
+    if (plan->N < 1 || plan->K < 1 || plan->S < 1 || plan->N > 64 || plan->K > 64) return HIKONV_EINVAL;
+    if (plan->taps && plan->chunks != (plan->taps + plan->K - 1) / plan->K) return HIKONV_EINVAL;
+    Req r = make_req(*plan);
+    return exact_ok(r, plan->N, plan->K, plan->S) ? HIKONV_OK : HIKONV_EOVERFLOW;
+}
+
+extern "C" int64_t hikonv_bitdense_row_bytes(int64_t len, int bits)
+{
+    int c = hikonv::container_bits(bits);
+    if (c == 0 || len < 0) return -1;
+    return ((len * c + 31) / 32) * 4;
+}
+
+extern "C" const char *hikonv_strerror(int code)
+{
+    switch (code) {
+    case HIKONV_OK: return "ok";
+    case HIKONV_EINVAL: return "invalid argument";
+    case HIKONV_EOVERFLOW: return "result may not fit (int32 output or packed field)";
+    case HIKONV_ENOPLAN: return "no packing plan satisfies the constraints";
+    case HIKONV_EHIP: return "HIP runtime error";
+    case HIKONV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case HIKONV_EUNSUPPORTED: return "request not supported by this build";
+    default: return "unknown error";
+    }
+}

@@ -1,0 +1,83 @@
+"""Helpers for the GPU parity tests: device buffers through torch, calls through the C ABI."""
+import numpy as np
+import torch
+
+import paper_2208_00763_amd as hk
+from oracle import direct
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    """numpy (int8/uint8/int32) -> contiguous CUDA tensor of the same bytes."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.int8:
+        return torch.from_numpy(a.view(np.uint8)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def conv1d_plan(bits, a_signed, w_signed, taps):
+    return hk.hikonv_plan_ex(bits_a=bits, bits_w=bits, a_signed=int(a_signed), w_signed=int(w_signed),
+                             L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=taps)
+
+
+def compact(x_np: np.ndarray, bits: int, bipolar=False) -> torch.Tensor:
+    """[rows][len] bytes -> bit-dense rows on the device, through hikonv_compact."""
+    rows, length = x_np.shape
+    row_bytes = hk.hikonv_bitdense_row_bytes(length, bits)
+    out = torch.zeros(rows * row_bytes + 16, dtype=torch.uint8, device="cuda")
+    hk.hikonv_compact(dev(x_np), rows, length, bits, bipolar, out)
+    return out
+
+
+def run_conv1d(x_np, g_np, bits, a_signed, w_signed, mode, fmt, packed=True, plan=None):
+    rows, length = x_np.shape
+    taps = g_np.shape[0]
+    out_len = length + taps - 1 if mode == hk.OUT_FULL else max(length - taps + 1, 0)
+    y = torch.full((rows * out_len + 8,), -77777, dtype=torch.int32, device="cuda")
+    x_d = compact(x_np, bits) if fmt == hk.FMT_BITDENSE else dev(x_np)
+    g_d = dev(g_np)
+    if packed:
+        plan = plan or conv1d_plan(bits, a_signed, w_signed, taps)
+        hk.hikonv_conv1d(plan, x_d, fmt, rows, length, g_d, taps, mode, y)
+    else:
+        hk.hikonv_conv1d_unpacked(bits, bits, hk.signedness(a_signed, w_signed), x_d, fmt, rows, length, g_d, taps,
+                                  mode, y)
+    torch.cuda.synchronize()
+    res = y.cpu().numpy()
+    assert (res[rows * out_len:] == -77777).all(), "wrote past the end of the output"
+    return res[:rows * out_len].reshape(rows, out_len)
+
+
+def oracle_conv1d(x_np, g_np, mode):
+    return direct.conv1d(x_np, g_np, direct.FULL if mode == hk.OUT_FULL else direct.VALID)
+
+
+def dnn_plan(bits_a, bits_w, a_signed, w_signed, taps, m, wide=True, bipolar=False):
+    width = 32 if wide else 24
+    return hk.hikonv_plan_ex(bits_a=bits_a, bits_w=bits_w, a_signed=int(a_signed), w_signed=int(w_signed),
+                             bipolar=int(bipolar), L_A=width, L_B=width, L_acc=64 if wide else 32,
+                             mode=hk.MODE_DNN, M=m, taps=taps)
+
+
+def run_conv2d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
+    n, c, h, w = x_np.shape
+    co, _, kh, kw = w_np.shape
+    ho, wo = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad - kw) // stride + 1
+    y = torch.full((n * co * ho * wo + 8,), -77777, dtype=torch.int32, device="cuda")
+    if fmt == hk.FMT_BITDENSE:
+        x_d = compact(x_np.reshape(n * c * h, w), plan.bits_a, bool(plan.bipolar))
+    else:
+        x_d = dev(x_np)
+    w_d = dev(w_np)
+    ws_bytes = hk.hikonv_conv2d_workspace_bytes(plan, n, c, h, w, co, kh, kw, stride, pad, prepacked)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    if prepacked:
+        pw = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8, device="cuda")
+        hk.hikonv_pack_weights(plan, w_d, co, c, kh, kw, pw)
+        hk.hikonv_conv2d_prepacked(plan, x_d, fmt, n, c, h, w, pw, co, kh, kw, stride, pad, ws, y)
+    else:
+        hk.hikonv_conv2d(plan, x_d, fmt, n, c, h, w, w_d, co, kh, kw, stride, pad, ws, y)
+    torch.cuda.synchronize()
+    res = y.cpu().numpy()
+    assert (res[n * co * ho * wo:] == -77777).all(), "wrote past the end of the output"
+    return res[:n * co * ho * wo].reshape(n, co, ho, wo)

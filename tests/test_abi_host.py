@@ -1,0 +1,163 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and its host-side planner agrees with the paper's model (oracle/plan_model.py) and with the
+big-integer packed model on the corner inputs that decide exactness."""
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2208_00763_amd as hk
+from oracle import packed_model as pm, plan_model as pl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "hikonv.h")).read()
+    declared = set(re.findall(r"\b(hikonv_[a-z0-9_]+)\s*\(", header))
+    declared -= {"hikonv_plan_t"}
+    assert len(declared) >= 18
+    for name in declared:
+        assert hasattr(hk.lib, name), name
+    assert declared == set(hk.SIGNATURES), declared ^ set(hk.SIGNATURES)
+
+
+def test_strerror_and_codes():
+    assert hk.hikonv_strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert hk.hikonv_strerror(code) not in ("ok", "unknown error")
+    assert hk.hikonv_strerror(-99) == "unknown error"
+
+
+def test_bitdense_row_bytes():
+    assert hk.hikonv_bitdense_row_bytes(65536, 4) == 32768
+    assert hk.hikonv_bitdense_row_bytes(65536, 1) == 8192
+    assert hk.hikonv_bitdense_row_bytes(9, 1) == 4 and hk.hikonv_bitdense_row_bytes(0, 3) == 0
+    assert hk.hikonv_bitdense_row_bytes(10, 9) < 0
+
+
+@pytest.mark.parametrize("widths", [(27, 18), (32, 32), (24, 24), (64, 64)])
+def test_single_mode_unsigned_plans_equal_the_paper_model(widths):
+    l_a, l_b = widths
+    for p, q in itertools.product(range(1, 9), repeat=2):
+        got = hk.hikonv_plan_ex(bits_a=p, bits_w=q, L_A=l_a, L_B=l_b, mode=hk.MODE_SINGLE)
+        ref = pl.paper_search(p, q, l_a, l_b, pl.SINGLE)
+        assert (got.N, got.K, got.S, got.G_b, got.ops_per_mul) == (ref["N"], ref["K"], ref["S"], ref["G_b"], ref["ops"])
+        assert got.paper_exact == 1
+
+
+def test_headline_entry_point():
+    assert [hk.hikonv_plan(b, b, 0, 32).ops_per_mul for b in range(1, 9)] == [113, 41, 25, 13, 13, 8, 5, 5]
+    p = hk.hikonv_plan(4, 4, 0, 32)
+    assert (p.N, p.K, p.S, p.G_b, p.L_acc, p.mode) == (3, 3, 10, 2, 64, hk.MODE_SINGLE)
+
+
+@pytest.mark.parametrize("taps", [1, 2, 3, 5, 7])
+def test_conv1d_plans_unsigned_equal_the_paper_model(taps):
+    for b in range(1, 9):
+        got = hk.hikonv_plan_ex(bits_a=b, bits_w=b, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=taps)
+        ref = pl.paper_search_taps(b, b, 32, 32, taps, pl.CONV1D)
+        assert (got.N, got.K, got.S, got.G_b, got.chunks) == (ref["N"], ref["K"], ref["S"], ref["G_b"], ref["chunks"])
+        assert got.paper_exact == 1 and got.K <= got.N + 1
+
+
+def _corner_inputs(plan, length):
+    ra = (-(1 << (plan.bits_a - 1)), (1 << (plan.bits_a - 1)) - 1) if plan.a_signed else (0, (1 << plan.bits_a) - 1)
+    rw = (-(1 << (plan.bits_w - 1)), (1 << (plan.bits_w - 1)) - 1) if plan.w_signed else (0, (1 << plan.bits_w) - 1)
+    for fa in ra:
+        for gw in rw:
+            yield [fa] * length, [gw] * plan.taps
+
+
+@pytest.mark.parametrize("signs", [(1, 1), (0, 1), (1, 0)])
+@pytest.mark.parametrize("taps", [3, 5, 7])
+def test_signed_conv1d_plans_are_exact_on_corners(signs, taps):
+    for b in range(1, 9):
+        plan = hk.hikonv_plan_ex(bits_a=b, bits_w=b, a_signed=signs[0], w_signed=signs[1], L_A=32, L_B=32, L_acc=64,
+                                 mode=hk.MODE_CONV1D, taps=taps)
+        assert hk.hikonv_plan_check(plan) == hk.OK
+        for f, g in _corner_inputs(plan, 4 * plan.N + 1):
+            # operands must fit the signed 32-bit multiplier inputs
+            a_word = pm.pack(f[:plan.N], plan.S)
+            assert -2 ** 31 <= a_word < 2 ** 31
+            for c0 in range(0, taps, plan.K):
+                assert -2 ** 31 <= pm.pack(g[c0:c0 + plan.K], plan.S) < 2 ** 31
+            assert pm.conv1d_packed(f, g, plan.N, plan.K, plan.S, True) == np.convolve(f, g).tolist()
+        ref = pl.paper_search_taps(b, b, 32, 32, taps, pl.CONV1D)
+        same = (plan.N, plan.K, plan.S) == (ref["N"], ref["K"], ref["S"])
+        assert bool(plan.paper_exact) == same
+
+
+def test_paper_plans_that_are_one_bit_short_are_rejected():
+    # (i) signed 1-bit values {-1,0}: eight products of (-1)(-1) reach 2^(S-1) for the printed S=4
+    p = hk.hikonv_plan(1, 1, hk.A_SIGNED | hk.W_SIGNED, 32)
+    ref = pl.paper_search(1, 1, 32, 32, pl.SINGLE)
+    assert p.paper_exact == 0 and (ref["N"], ref["K"], ref["S"]) == (8, 8, 4)
+    bad = hk.Plan(**{**p.as_dict(), "N": 8, "K": 8, "S": 4, "G_b": 3})
+    assert hk.hikonv_plan_check(bad) == hk.EOVERFLOW
+    assert pm.fnk([-1] * 8, [-1] * 8, 4, True)[0] != np.convolve([-1] * 8, [-1] * 8).tolist()
+    assert pm.fnk([-1] * p.N, [-1] * p.K, p.S, True)[0] == np.convolve([-1] * p.N, [-1] * p.K).tolist()
+    # (ii) the signed packed word of all-minimum inputs needs one bit more than Eq. (slice2) counts:
+    # 2-bit signed, K=3 in 1-D mode: the printed N=6, S=6 fills 32 bits exactly
+    bad = hk.hikonv_plan_ex(bits_a=2, bits_w=2, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3)
+    assert (bad.N, bad.S) == (6, 6)
+    bad.a_signed = bad.w_signed = 1
+    assert hk.hikonv_plan_check(bad) == hk.EOVERFLOW
+    assert pm.pack([-2] * 6, 6) < -2 ** 31
+    good = hk.hikonv_plan_ex(bits_a=2, bits_w=2, a_signed=1, w_signed=1, L_A=32, L_B=32, L_acc=64,
+                             mode=hk.MODE_CONV1D, taps=3)
+    assert (good.N, good.S, good.paper_exact) == (5, 6, 0)
+    # 6-bit signed on a single 32x32 multiplier: N=3, S=13 fills 32 bits exactly
+    ref = pl.paper_search(6, 6, 32, 32, pl.SINGLE)
+    p6 = hk.hikonv_plan(6, 6, 3, 32)
+    assert (ref["N"], ref["S"]) == (3, 13) and pm.pack([-32] * 3, 13) < -2 ** 31
+    assert hk.hikonv_plan_check(p6) == hk.OK and -2 ** 31 <= pm.pack([-32] * p6.N, p6.S)
+
+
+@pytest.mark.parametrize("wide", [True, False])
+def test_dnn_plans_are_exact_on_corners(wide):
+    width, acc = (32, 64) if wide else (24, 32)
+    for b, sa, sw in ((1, 0, 0), (2, 1, 1), (4, 1, 1), (4, 0, 1), (4, 0, 0), (8, 1, 1), (3, 0, 1)):
+        for taps in (1, 3, 5):
+            for m in (1, 2, 5, 9, 0):
+                try:
+                    plan = hk.hikonv_plan_ex(bits_a=b, bits_w=b, a_signed=sa, w_signed=sw, L_A=width, L_B=width,
+                                             L_acc=acc, mode=hk.MODE_DNN, M=m, taps=taps)
+                except hk.HikonvError as e:
+                    assert e.code == hk.ENOPLAN
+                    continue
+                assert hk.hikonv_plan_check(plan) == hk.OK and plan.K <= plan.N + 1
+                signed = bool(sa or sw)
+                ra = (-(1 << (b - 1)), (1 << (b - 1)) - 1) if sa else (0, (1 << b) - 1)
+                rw = (-(1 << (b - 1)), (1 << (b - 1)) - 1) if sw else (0, (1 << b) - 1)
+                c_in = min(plan.M, 40)          # one split group of min(M, 40) channels, one kernel row
+                for fa, gw in itertools.product(ra, rw):
+                    x = [[[fa] * (2 * plan.N + 1)] for _ in range(c_in)]
+                    w = [[[[gw] * taps] for _ in range(c_in)]]
+                    got = pm.conv2d_packed(x, w, taps - 1, plan.N, plan.K, plan.S, plan.M, signed)
+                    row = np.convolve([fa] * (2 * plan.N + 1), [gw] * taps) * c_in
+                    assert got[0][taps - 1] == row.tolist()   # output row aligned with the only input row
+                    # accumulated word fits the accumulator register (top segment included)
+                    a_word = pm.pack([fa] * plan.N, plan.S)
+                    total = sum(a_word * pm.pack([gw] * min(plan.K, taps - c0), plan.S)
+                                for c0 in range(0, taps, plan.K)) * plan.M
+                    if signed:
+                        assert -2 ** (acc - 1) <= total < 2 ** (acc - 1)
+                    else:
+                        assert 0 <= total < 2 ** acc
+
+
+def test_bad_requests():
+    for kw in (dict(bits_a=0, bits_w=4), dict(bits_a=4, bits_w=9), dict(bits_a=4, bits_w=4, L_A=0),
+               dict(bits_a=4, bits_w=4, mode=7), dict(bits_a=2, bits_w=1, bipolar=1)):
+        base = dict(L_A=32, L_B=32, mode=hk.MODE_SINGLE)
+        base.update(kw)
+        with pytest.raises(hk.HikonvError) as e:
+            hk.hikonv_plan_ex(**base)
+        assert e.value.code == hk.EINVAL
+    with pytest.raises(hk.HikonvError) as e:
+        hk.hikonv_plan_ex(bits_a=8, bits_w=8, L_A=8, L_B=8, L_acc=8, mode=hk.MODE_SINGLE)
+    assert e.value.code == hk.ENOPLAN
+    assert hk.lib.hikonv_plan(4, 4, 0, 32, None) == hk.EINVAL

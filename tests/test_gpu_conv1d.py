@@ -1,0 +1,148 @@
+"""GPU parity: packed and unpacked 1-D convolution through the C ABI vs the int64 oracle,
+bit-exact, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2208_00763_amd as hk
+    from gpu_util import run_conv1d, oracle_conv1d, conv1d_plan, dev
+
+SIGNS = [(False, False), (True, True), (False, True), (True, False)]
+
+
+def test_lane_exchange_layout():
+    out = torch.zeros(64, dtype=torch.int32, device="cuda")
+    hk.hikonv_selftest_lane_shift(out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert got[0] == 0 and np.array_equal(got[1:], np.arange(100, 163))
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+@pytest.mark.parametrize("signs", SIGNS)
+def test_conv1d_small_shapes(bits, signs):
+    a_s, w_s = signs
+    for taps in (1, 2, 3, 5, 7):
+        for length in (1, 2, 6, 97, 1000):
+            x, g = wl.conv1d_case(bits, a_s, taps, 3, length, tag="t1") if a_s == w_s else (
+                wl.uniform_values(wl.rng_for("t1x", bits, taps, length), (3, length), bits, a_s),
+                wl.uniform_values(wl.rng_for("t1g", bits, taps, length), (taps,), bits, w_s))
+            for mode in (hk.OUT_FULL, hk.OUT_VALID):
+                ref = oracle_conv1d(x, g, mode)
+                for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
+                    got = run_conv1d(x, g, bits, a_s, w_s, mode, fmt)
+                    assert got.shape == ref.shape
+                    assert np.array_equal(got, ref), (bits, signs, taps, length, mode, fmt)
+
+
+@pytest.mark.parametrize("bits,signs,taps", [(1, (False, False), 3), (1, (True, True), 7), (2, (True, True), 3),
+                                             (4, (False, False), 3), (4, (True, True), 5), (3, (False, True), 3),
+                                             (6, (True, True), 3), (8, (False, False), 7), (8, (True, True), 3)])
+def test_conv1d_several_tiles_and_ragged_tail(bits, signs, taps):
+    a_s, w_s = signs
+    rng = wl.rng_for("t2", bits, signs, taps)
+    for rows, length in ((5, 20011), (2, 65536), (7, 4099)):
+        x = wl.uniform_values(rng, (rows, length), bits, a_s)
+        g = wl.uniform_values(rng, (taps,), bits, w_s)
+        for mode in (hk.OUT_FULL, hk.OUT_VALID):
+            ref = oracle_conv1d(x, g, mode)
+            for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
+                assert np.array_equal(run_conv1d(x, g, bits, a_s, w_s, mode, fmt), ref)
+            assert np.array_equal(run_conv1d(x, g, bits, a_s, w_s, mode, hk.FMT_BITDENSE, packed=False), ref)
+
+
+@pytest.mark.parametrize("bits,signed", [(1, False), (2, True), (4, False), (4, True), (8, True)])
+def test_conv1d_extreme_values(bits, signed):
+    lo, hi = wl.value_range(bits, signed)
+    dt = np.int8 if signed else np.uint8
+    for taps in (3, 7):
+        for fv in (lo, hi):
+            for gv in (lo, hi):
+                x = np.full((2, 3001), fv, dtype=dt)
+                g = np.full((taps,), gv, dtype=dt)
+                ref = oracle_conv1d(x, g, hk.OUT_FULL)
+                assert np.array_equal(run_conv1d(x, g, bits, signed, signed, hk.OUT_FULL, hk.FMT_BITDENSE), ref)
+
+
+def test_conv1d_config1():
+    x, g = wl.config1()
+    ref = oracle_conv1d(x, g, hk.OUT_VALID)
+    assert ref.shape == (1, 4094)
+    plan = conv1d_plan(4, False, False, 3)
+    assert (plan.N, plan.K, plan.S, plan.G_b) == (3, 3, 10, 2)
+    for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
+        assert np.array_equal(run_conv1d(x, g, 4, False, False, hk.OUT_VALID, fmt), ref)
+        assert np.array_equal(run_conv1d(x, g, 4, False, False, hk.OUT_VALID, fmt, packed=False), ref)
+
+
+def test_conv1d_unpacked_small():
+    for bits, signs in ((1, (False, False)), (4, (True, True)), (8, (False, True)), (5, (True, False))):
+        a_s, w_s = signs
+        rng = wl.rng_for("t3", bits, signs)
+        for taps, length in ((1, 9), (3, 130), (7, 1025), (5, 3)):
+            x = wl.uniform_values(rng, (4, length), bits, a_s)
+            g = wl.uniform_values(rng, (taps,), bits, w_s)
+            for mode in (hk.OUT_FULL, hk.OUT_VALID):
+                ref = oracle_conv1d(x, g, mode)
+                for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
+                    assert np.array_equal(run_conv1d(x, g, bits, a_s, w_s, mode, fmt, packed=False), ref)
+
+
+def test_conv1d_empty_and_error_paths():
+    plan = conv1d_plan(4, False, False, 3)
+    y = torch.zeros(16, dtype=torch.int32, device="cuda")
+    x = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    g = torch.zeros(3, dtype=torch.uint8, device="cuda")
+    hk.hikonv_conv1d(plan, x, hk.FMT_INT8, 0, 10, g, 3, hk.OUT_FULL, y)          # no rows: ok
+    hk.hikonv_conv1d(plan, x, hk.FMT_INT8, 2, 2, g, 3, hk.OUT_VALID, y)          # len < taps, valid: ok
+    with pytest.raises(hk.HikonvError) as e:
+        hk.hikonv_conv1d(plan, x, hk.FMT_INT8, 1, 10, g, 5, hk.OUT_FULL, y)      # taps differ from the plan
+    assert e.value.code == hk.EINVAL
+    with pytest.raises(hk.HikonvError) as e:
+        hk.hikonv_conv1d(plan, None, hk.FMT_INT8, 1, 10, g, 3, hk.OUT_FULL, y)
+    assert e.value.code == hk.EINVAL
+    with pytest.raises(hk.HikonvError) as e:
+        hk.hikonv_conv1d(plan, x, 7, 1, 10, g, 3, hk.OUT_FULL, y)
+    assert e.value.code == hk.EINVAL
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("bits", [1, 4, 8])
+def test_conv1d_full_size_all_rows(bits):
+    """4096 x 65536, K = 3, unsigned: every output compared (the bench launch configuration)."""
+    x, g = wl.conv1d_case(bits, False, 3, 4096, 65536)
+    plan = conv1d_plan(bits, False, False, 3)
+    x_d = torch.zeros(4096 * hk.hikonv_bitdense_row_bytes(65536, bits), dtype=torch.uint8, device="cuda")
+    hk.hikonv_compact(dev(x), 4096, 65536, bits, False, x_d)
+    y = torch.empty(4096 * 65534, dtype=torch.int32, device="cuda")
+    hk.hikonv_conv1d(plan, x_d, hk.FMT_BITDENSE, 4096, 65536, dev(g), 3, hk.OUT_VALID, y)
+    torch.cuda.synchronize()
+    ref = oracle_conv1d(x, g, hk.OUT_VALID)
+    assert np.array_equal(y.cpu().numpy().reshape(4096, 65534), ref)
+
+
+def test_conv1d_full_size_sweep_sampled_rows():
+    """All 48 cases of the sweep at 4096 x 65536; 24 sampled rows of each compared in full."""
+    rng = np.random.default_rng(7)
+    for bits in range(1, 9):
+        for signed in (False, True):
+            x = wl.uniform_values(wl.rng_for("c2x", bits, signed), (4096, 65536), bits, signed)
+            x_d = torch.zeros(4096 * hk.hikonv_bitdense_row_bytes(65536, bits), dtype=torch.uint8, device="cuda")
+            hk.hikonv_compact(dev(x), 4096, 65536, bits, False, x_d)
+            rows = np.unique(np.concatenate([[0, 1, 4095], rng.integers(0, 4096, size=21)]))
+            for taps in (3, 5, 7):
+                g = wl.uniform_values(wl.rng_for("c2g", bits, signed, taps), (taps,), bits, signed)
+                plan = conv1d_plan(bits, signed, signed, taps)
+                out_len = 65536 - taps + 1
+                y = torch.empty(4096 * out_len, dtype=torch.int32, device="cuda")
+                hk.hikonv_conv1d(plan, x_d, hk.FMT_BITDENSE, 4096, 65536, dev(g), taps, hk.OUT_VALID, y)
+                torch.cuda.synchronize()
+                got = y.view(4096, out_len)[torch.from_numpy(rows).cuda()].cpu().numpy()
+                ref = oracle_conv1d(x[rows], g, hk.OUT_VALID)
+                assert np.array_equal(got, ref), (bits, signed, taps)
+                del y

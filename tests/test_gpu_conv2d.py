@@ -1,0 +1,216 @@
+"""GPU parity: packed DNN layer (wide and 24-bit multipliers, {-1,+1} layers), unpacked
+baseline, epilogue and the chained CNN, through the C ABI vs the int64 oracle, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import direct
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2208_00763_amd as hk
+    from paper_2208_00763_amd.cnn import PackedCnn
+    from gpu_util import run_conv2d, dnn_plan, dev, compact
+
+SHAPES = [  # n, c, h, w, co, kh, kw, stride, pad
+    (1, 3, 5, 7, 2, 3, 3, 1, 1),
+    (2, 5, 9, 11, 9, 3, 3, 1, 0),
+    (1, 4, 8, 8, 16, 1, 1, 1, 0),
+    (1, 6, 10, 13, 4, 3, 3, 2, 1),
+    (1, 2, 7, 20, 3, 5, 5, 1, 2),
+    (1, 7, 6, 9, 10, 3, 2, 1, 1),
+    (1, 3, 4, 70, 2, 3, 3, 1, 1),
+]
+
+
+def _case(bits, a_s, w_s, shape, tag):
+    n, c, h, w, co, kh, kw, _, _ = shape
+    rng = wl.rng_for(tag, bits, a_s, w_s, shape)
+    return wl.uniform_values(rng, (n, c, h, w), bits, a_s), wl.uniform_values(rng, (co, c, kh, kw), bits, w_s)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 6, 8])
+@pytest.mark.parametrize("signs", [(False, False), (True, True), (False, True)])
+def test_conv2d_packed_small_shapes(bits, signs):
+    a_s, w_s = signs
+    ran = 0
+    for shape in SHAPES:
+        x, w = _case(bits, a_s, w_s, shape, "d1")
+        stride, pad, kw = shape[7], shape[8], shape[6]
+        ref = direct.conv2d(x, w, stride, pad)
+        for wide in (True, False):
+            for m in (1, 4, 0):
+                try:
+                    plan = dnn_plan(bits, bits, a_s, w_s, kw, m, wide)
+                except hk.HikonvError as e:
+                    assert e.code == hk.ENOPLAN
+                    continue
+                if plan.N > 8:
+                    continue
+                for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
+                    got = run_conv2d(plan, x, w, stride, pad, fmt, prepacked=(m == 4))
+                    assert np.array_equal(got, ref), (bits, signs, shape, wide, m, fmt, plan)
+                    ran += 1
+    assert ran > 0
+
+
+@pytest.mark.parametrize("wide", [True, False])
+def test_conv2d_long_rows_are_segmented(wide):
+    # rows of more than 63 packed blocks are cut into wave segments with a recomputed halo block
+    for bits, a_s, w_s, width in ((4, True, True, 400), (1, False, False, 1200), (2, False, True, 333)):
+        shape = (1, 3, 3, width, 4, 3, 3, 1, 1)
+        x, w = _case(bits, a_s, w_s, shape, "d2")
+        try:
+            plan = dnn_plan(bits, bits, a_s, w_s, 3, 3, wide)
+        except hk.HikonvError:
+            continue
+        if plan.N > 8:
+            continue
+        assert (width + 1 + plan.N - 1) // plan.N > 63
+        assert np.array_equal(run_conv2d(plan, x, w, 1, 1), direct.conv2d(x, w, 1, 1))
+
+
+def test_conv2d_extreme_values():
+    for bits, a_s, w_s in ((4, True, True), (4, False, True), (4, False, False), (2, True, True), (8, True, True)):
+        lo_a, hi_a = wl.value_range(bits, a_s)
+        lo_w, hi_w = wl.value_range(bits, w_s)
+        for av in (lo_a, hi_a):
+            for wv in (lo_w, hi_w):
+                x = np.full((1, 20, 6, 9), av, dtype=np.int8 if a_s else np.uint8)
+                w = np.full((3, 20, 3, 3), wv, dtype=np.int8 if w_s else np.uint8)
+                plan = dnn_plan(bits, bits, a_s, w_s, 3, 0, True)
+                assert np.array_equal(run_conv2d(plan, x, w, 1, 1), direct.conv2d(x, w, 1, 1)), (bits, av, wv, plan)
+
+
+def test_conv2d_config3_full():
+    x, w = wl.config3()
+    ref = direct.conv2d(x, w, 1, 1)
+    for m in (5, 0):
+        plan = dnn_plan(4, 4, True, True, 3, m, True)
+        assert np.array_equal(run_conv2d(plan, x, w, 1, 1, hk.FMT_BITDENSE, prepacked=True), ref)
+    plan = dnn_plan(4, 4, True, True, 3, 5, True)
+    assert (plan.N, plan.K, plan.S) == (3, 3, 12)
+
+
+@pytest.mark.parametrize("shape", [(1, 4, 6, 7, 5, 3, 3, 1, 1), (2, 16, 9, 9, 9, 3, 3, 1, 0), (1, 8, 8, 10, 4, 3, 3, 2, 1),
+                                   (1, 5, 5, 5, 3, 1, 1, 1, 0), (1, 33, 7, 30, 8, 3, 3, 1, 1)])
+def test_conv2d_bipolar_small(shape):
+    n, c, h, w, co, kh, kw, stride, pad = shape
+    x, wt = wl.bipolar_case(n, c, h, w, co, kh, kw, tag="d3")
+    ref = direct.conv2d(x, wt, stride, pad)
+    for wide in (True, False):
+        for m in (3, 0):
+            plan = dnn_plan(1, 1, False, False, kw, m, wide, bipolar=True)
+            if plan.N > 8:
+                continue
+            for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
+                got = run_conv2d(plan, x, wt, stride, pad, fmt, prepacked=(m == 3))
+                assert np.array_equal(got, ref), (shape, wide, m, fmt, plan)
+
+
+def test_conv2d_config4_full():
+    x, w = wl.config4()
+    assert x.shape == (8, 256, 28, 28) and w.shape == (256, 256, 3, 3)
+    ref = direct.conv2d(x, w, 1, 1)
+    for wide in (True, False):
+        plan = dnn_plan(1, 1, False, False, 3, 0, wide, bipolar=True)
+        if plan.N > 8:
+            plan = dnn_plan(1, 1, False, False, 3, 10, wide, bipolar=True)
+        assert np.array_equal(run_conv2d(plan, x, w, 1, 1, hk.FMT_BITDENSE, prepacked=True), ref)
+
+
+def test_conv2d_unpacked_baseline():
+    for bits, a_s, w_s in ((4, True, True), (8, False, True), (1, False, False)):
+        for shape in SHAPES:
+            x, w = _case(bits, a_s, w_s, shape, "d4")
+            n, c, h, wd, co, kh, kw, stride, pad = shape
+            ho, wo = (h + 2 * pad - kh) // stride + 1, (wd + 2 * pad - kw) // stride + 1
+            y = torch.zeros(n * co * ho * wo, dtype=torch.int32, device="cuda")
+            hk.hikonv_conv2d_unpacked(bits, bits, hk.signedness(a_s, w_s), dev(x), n, c, h, wd, dev(w), co, kh, kw,
+                                      stride, pad, y)
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy().reshape(n, co, ho, wo), direct.conv2d(x, w, stride, pad))
+    x, w = wl.config4(8)
+    n, c, h, wd = x.shape
+    co = w.shape[0]
+    y = torch.zeros(n * co * h * wd, dtype=torch.int32, device="cuda")
+    hk.hikonv_conv2d_unpacked(1, 1, hk.BIPOLAR, dev(x), n, c, h, wd, dev(w), co, 3, 3, 1, 1, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().reshape(n, co, h, wd), direct.conv2d(x, w, 1, 1))
+
+
+def test_compact_matches_oracle_layout():
+    for bits in range(1, 9):
+        for signed in (False, True):
+            x = wl.uniform_values(wl.rng_for("cp", bits, signed), (5, 1003), bits, signed)
+            got = compact(x, bits).cpu().numpy()
+            ref = direct.bitdense_pack(x, bits)
+            assert np.array_equal(got[:ref.size].reshape(ref.shape), ref)
+
+
+def test_epilogue_matches_oracle():
+    rng = np.random.default_rng(3)
+    for (n, c, h, w, shift, pool) in ((1, 3, 6, 10, 3, True), (2, 5, 7, 9, 0, False), (1, 4, 9, 17, 5, True),
+                                      (1, 2, 4, 64, 2, False)):
+        acc = rng.integers(-3000, 3000, size=(n, c, h, w), dtype=np.int32)
+        q = direct.relu_requant(acc, shift, 15)
+        if pool:
+            q = direct.maxpool2x2(q)
+        ho, wo = q.shape[2], q.shape[3]
+        ref_bd = direct.bitdense_pack(q.reshape(n * c * ho, wo), 4)
+        out_bd = torch.zeros(ref_bd.size, dtype=torch.uint8, device="cuda")
+        hk.hikonv_epilogue(dev(acc), n, c, h, w, shift, 15, pool, 4, hk.FMT_BITDENSE, out_bd)
+        out_i8 = torch.zeros(n * c * ho * wo + 4, dtype=torch.uint8, device="cuda")
+        hk.hikonv_epilogue(dev(acc), n, c, h, w, shift, 15, pool, 4, hk.FMT_INT8, out_i8)
+        torch.cuda.synchronize()
+        assert np.array_equal(out_bd.cpu().numpy().reshape(ref_bd.shape), ref_bd)
+        assert np.array_equal(out_i8.cpu().numpy()[:q.size].reshape(q.shape), q.view(np.uint8))
+
+
+def oracle_cnn(x, weights, specs):
+    """Layer-by-layer oracle forward; the per-layer requantisation shift is chosen here so that
+    the 99th percentile of the positive accumulators maps to at most 15."""
+    accs, shifts = [], []
+    cur = x
+    for i, (w, spec) in enumerate(zip(weights, specs)):
+        acc = direct.conv2d(cur, w, 1, spec["pad"])
+        accs.append(acc)
+        if i + 1 == len(weights):
+            break
+        pos = acc[acc > 0]
+        p99 = int(np.percentile(pos, 99)) if pos.size else 0
+        shift = 0
+        while (p99 >> shift) > 15:
+            shift += 1
+        shifts.append(shift)
+        q = direct.relu_requant(acc, shift, 15)
+        if spec["pool"]:
+            q = direct.maxpool2x2(q)
+        cur = q.view(np.uint8)
+    return accs, shifts
+
+
+@pytest.mark.parametrize("size", [(32, 64), (160, 320)])
+def test_cnn_forward_config5(size):
+    h, w = size
+    x, weights, specs = wl.config5(h, w)
+    ref_accs, shifts = oracle_cnn(x, weights, specs)
+    net = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs)
+    x_bd = compact(x.reshape(3 * h, w), 4)
+    _, accs = net.forward(x_bd, 1, h, w, shifts)
+    torch.cuda.synchronize()
+    for i, (got, ref) in enumerate(zip(accs, ref_accs)):
+        assert np.array_equal(got.cpu().numpy().reshape(ref.shape), ref), "layer %d" % i
+    # deep layers of a random-weight network go mostly to zero after ReLU, so every layer is
+    # also checked in isolation on fresh uniform inputs of its own shape
+    hh, ww = h, w
+    for i, (wt, spec) in enumerate(zip(weights, specs)):
+        co, c, kh, kw = wt.shape
+        xi = wl.uniform_values(wl.rng_for("c5iso", i, h, w), (1, c, hh, ww), 4, False)
+        plan = net.layers[i]["plan"]
+        got = run_conv2d(plan, xi, wt, 1, spec["pad"], hk.FMT_BITDENSE, prepacked=True)
+        assert np.array_equal(got, direct.conv2d(xi, wt, 1, spec["pad"])), "isolated layer %d" % i
+        if spec["pool"]:
+            hh, ww = hh // 2, ww // 2

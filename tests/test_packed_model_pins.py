@@ -144,3 +144,13 @@ def test_theorem3_dnn_mapping_with_accumulation(signs):
             ref = direct.conv2d(xv, wv, 1, pad)[0]
             got = pm.conv2d_packed(xv[0].tolist(), wv.tolist(), pad, n, k, s, m_acc, any(signs))
             assert np.array_equal(np.array(got), ref)
+
+
+def test_overlap_add_with_kernel_longer_than_block():
+    # K-1 > N: a block product reaches past its neighbour; the stored word carries it on
+    for n, k, s in ((1, 3, 10), (2, 5, 11), (1, 4, 10), (2, 4, 10)):
+        for _ in range(20):
+            f, g = _rand(17, 4, False), _rand(k, 4, False)
+            assert pm.conv1d_packed(f, g, n, k, s, False) == np.convolve(f, g).tolist()
+        f, g = _rand(17, 3, True), _rand(k, 3, True)
+        assert pm.conv1d_packed(f, g, n, k, s, True) == np.convolve(f, g).tolist()
