@@ -12,6 +12,7 @@ SOURCES = [
     "hikonv_plan.cpp",
     "hikonv_api.hip",
     "hikonv_conv1d.hip",
+    "hikonv_conv1d_fast.hip",
     "hikonv_conv2d.hip",
     "hikonv_conv2d_wide.hip",
     "hikonv_conv2d_narrow.hip",

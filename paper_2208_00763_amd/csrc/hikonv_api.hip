@@ -52,9 +52,11 @@ int conv1d_common(int bits_a, int a_signed, int w_signed, const void *x_dev, int
 }
 
 struct Conv2dGeom {
-    int Ho, Wo, Wo1, X, Xs, Hp, terms, n_cog;
-    size_t apk_bytes, wp_bytes, ps_bytes, sa_bytes;
+    int Ho, Wo, Wo1, X, Xs, Hp, terms, terms_pad, n_cog;
+    size_t apk_bytes, toff_bytes, wp_bytes, ps_bytes, sa_bytes;
 };
+
+inline int pad_terms(int terms) { return (terms + 3) & ~3; }
 
 int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, int Kh, int Kw, int stride, int pad,
                 Conv2dGeom *g)
@@ -80,9 +82,12 @@ int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, i
     g->Xs = g->X + 1;
     g->Hp = H + 2 * pad;
     g->terms = C * Kh * plan->chunks;
+    g->terms_pad = pad_terms(g->terms);
     g->n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
+    if ((int64_t)plan->chunks * N * C * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     g->apk_bytes = round256((size_t)plan->chunks * N * C * g->Hp * g->Xs * 4);
-    g->wp_bytes = round256((size_t)g->n_cog * g->terms * 8 * 4);
+    g->toff_bytes = round256((size_t)(g->terms_pad + 8) * 4);
+    g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
     g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
     g->sa_bytes = plan->bipolar ? round256((size_t)N * g->Ho * g->Wo * 4) : 0;
     return HIKONV_OK;
@@ -103,6 +108,7 @@ int pack_weights_impl(const hikonv_plan_t *plan, const Conv2dGeom &g, const void
     a.S = plan->S;
     a.chunks = plan->chunks;
     a.n_cog = g.n_cog;
+    a.terms_pad = g.terms_pad;
     a.wp = static_cast<uint32_t *>(packed_dev);
     a.ps = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(packed_dev) + g.wp_bytes);
     return hip_result(launch_pack_weights(a, stream));
@@ -118,15 +124,16 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     if (!x_dev || !w_dev || !y_dev) return HIKONV_EINVAL;
     if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE) return HIKONV_EINVAL;
     if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(w_dev, prepacked ? 256 : 1)) return HIKONV_EINVAL;
-    const size_t need = g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+    const size_t need = g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
     if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return HIKONV_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
     uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
-    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+    int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes + g.toff_bytes);
     const uint8_t *wpk = static_cast<const uint8_t *>(w_dev);
     if (!prepacked) {
-        uint8_t *dst = ws + g.apk_bytes + g.sa_bytes;
+        uint8_t *dst = ws + g.apk_bytes + g.toff_bytes + g.sa_bytes;
         rc = pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, dst, stream);
         if (rc != HIKONV_OK) return rc;
         wpk = dst;
@@ -173,7 +180,12 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.chunks = plan->chunks;
     ca.M = plan->M;
     ca.terms = g.terms;
+    ca.terms_pad = g.terms_pad;
+    ca.toff = toff;
     ca.chunk_stride = (int64_t)N * C * g.Hp * g.Xs;
+    rc = hip_result(launch_term_offsets(toff, g.terms_pad + 8, g.terms, Kh, plan->chunks, ca.chunk_stride,
+                                        (int64_t)g.Hp * g.Xs, g.Xs, stream));
+    if (rc != HIKONV_OK) return rc;
     if (g.Xs <= 64) {
         ca.rows_per_wave = 64 / g.Xs;
         ca.segs = 0;
@@ -185,7 +197,29 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.Wo = g.Wo;
     const bool wide = plan->L_A == 32;
     const bool any_signed = !plan->bipolar && (plan->a_signed || plan->w_signed);
-    const int64_t waves = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, ca.rows_per_wave);
+    const int64_t row_groups = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, ca.rows_per_wave);
+    // the pipelined kernel splits after a multiple of four terms
+    const int split_terms = (plan->M * plan->chunks) & ~3;
+    ca.pipelined = split_terms >= 4 ? 1 : 0;
+    ca.split_terms = split_terms;
+
+    // enough waves to cover the load latency: divide the term range over 2 or 4 waves of a
+    // workgroup when the layer has few (row group, channel tile) pairs
+    auto choose_split = [&](int64_t base_waves, Conv2dArgs *args) {
+        int ks = 1;
+        if (args->pipelined) {
+            if (base_waves < 2048 && g.terms_pad >= 64)
+                ks = 4;
+            else if (base_waves < 4096 && g.terms_pad >= 32)
+                ks = 2;
+        }
+        args->ksplit = ks;
+        args->slice_terms = (int)(((g.terms_pad + ks - 1) / ks + 3) & ~3);
+        if ((ks - 1) * args->slice_terms >= g.terms_pad) { // keep every slice non-empty
+            args->ksplit = 1;
+            args->slice_terms = g.terms_pad;
+        }
+    };
 
     if (plan->bipolar) {
         // window sums of a: the same kernel with the all-ones weight group, one channel
@@ -193,13 +227,15 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
         sa_args.Co = 1;
         sa_args.cog0 = g.n_cog - 1;
         sa_args.y = sa;
+        choose_split(row_groups, &sa_args);
         rc = hip_result(launch_conv2d_packed(sa_args, wide, any_signed, 2, stream));
         if (rc != HIKONV_OK) return rc;
     }
     ca.Co = Co;
     ca.cog0 = 0;
     ca.y = y_dev;
-    const int co_tile = (Co >= 8 && waves * ((Co + 7) / 8) >= 1536) ? 8 : 2;
+    const int co_tile = Co >= 8 ? 8 : 2;
+    choose_split(row_groups * ((Co + co_tile - 1) / co_tile), &ca);
     rc = hip_result(launch_conv2d_packed(ca, wide, any_signed, co_tile, stream));
     if (rc != HIKONV_OK) return rc;
 
@@ -260,10 +296,15 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
     a.chunks = plan->chunks;
     const int64_t m_end = out_mode == HIKONV_OUT_VALID ? len : len + taps - 1;
     a.n_blocks = ceil_div(m_end, a.N);
+    const bool any_signed = plan->a_signed || plan->w_signed;
+    if (conv1d_fast_applicable(a)) {
+        a.CH = 0;
+        a.tiles_per_row = conv1d_fast_runs_per_row(a.N, a.n_blocks);
+        return hip_result(launch_conv1d_fast(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
+    }
     a.CH = conv1d_tile_chunks(a.N, a.n_blocks);
     a.tiles_per_row = ceil_div(a.n_blocks, (int64_t)4 * a.CH * 63);
-    return hip_result(launch_conv1d_packed(a, plan->a_signed != 0, plan->a_signed || plan->w_signed,
-                                           static_cast<hipStream_t>(stream)));
+    return hip_result(launch_conv1d_packed(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int x_format,
@@ -282,7 +323,7 @@ extern "C" size_t hikonv_packed_weights_bytes(const hikonv_plan_t *plan, int Co,
 {
     if (!plan || Co < 1 || C < 1 || Kh < 1 || Kw < 1 || plan->chunks < 1) return 0;
     const size_t n_cog = (size_t)(Co + 7) / 8 + (plan->bipolar ? 1 : 0);
-    size_t bytes = round256(n_cog * C * Kh * plan->chunks * 8 * 4);
+    size_t bytes = round256(n_cog * pad_terms(C * Kh * plan->chunks) * 8 * 4);
     if (plan->bipolar) bytes += round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4);
     return bytes;
 }
@@ -295,7 +336,8 @@ extern "C" int hikonv_pack_weights(const hikonv_plan_t *plan, const void *w_dev,
     if (plan->chunks != (Kw + plan->K - 1) / plan->K || !aligned(packed_dev, 256)) return HIKONV_EINVAL;
     Conv2dGeom g = {};
     g.n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
-    g.wp_bytes = round256((size_t)g.n_cog * C * Kh * plan->chunks * 8 * 4);
+    g.terms_pad = pad_terms(C * Kh * plan->chunks);
+    g.wp_bytes = round256((size_t)g.n_cog * g.terms_pad * 8 * 4);
     return pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, packed_dev, static_cast<hipStream_t>(stream));
 }
 
@@ -304,7 +346,7 @@ extern "C" size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N
 {
     Conv2dGeom g;
     if (conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g) != HIKONV_OK) return 0;
-    return g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+    return g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
 }
 
 extern "C" int hikonv_conv2d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,

@@ -1,0 +1,223 @@
+// Streaming variant of the packed 1-D convolution (Theorem 2 with Theorem 1 blocks) for the
+// common plans (N <= 12, one 32-bit window holds a block's N containers).
+//
+// Every wavefront works alone, so the kernel has no workgroup barrier: a wave owns a run of
+// CH chunks of 63 consecutive blocks.  Per chunk, lane l > 0 owns block x0 + l - 1 and lane 0
+// recomputes block x0 - 1, whose high segments lane 1 needs.  A lane
+//   reads the two dwords around its block's first container straight from global memory
+//   (neighbouring lanes hit the same cache lines), funnel-shifts them into one window,
+//   packs A (Eq. inpack), multiplies by the wave-uniform B held in an SGPR
+//   (v_mad_u64_u32 / v_mad_i64_i32 with the bias as addend),
+//   adds the previous lane's high part (DPP wave_shr:1; Eq. 1dnx in the packed domain),
+//   reads the N fields (Eq. output_split in bias form) into the wave's LDS staging run.
+// After its CH chunks the wave copies the run to global memory with 16-byte aligned,
+// fully coalesced int32x4 stores.  Row edges (zero extension of Eq. pad_f0, and the end of
+// the buffer) take a masked path that only the first and last chunk of a row enter.
+#include "hikonv_device.h"
+#include "hikonv_launch.h"
+
+namespace hikonv {
+namespace {
+
+constexpr int kWavesPerGroup = 4;
+constexpr int kChunkBlocks = 63;
+
+// chunks per wave run: about 750 outputs per run
+__host__ __device__ constexpr int run_chunks(int n) { return n >= 7 ? 1 : (12 / n > 0 ? 12 / n : 1); }
+// LDS dwords per wave: outputs of a run + alignment slack, rounded to 16 bytes
+__host__ __device__ constexpr int run_stage_dwords(int n) { return ((run_chunks(n) * kChunkBlocks * n + 8 + 3) / 4) * 4; }
+
+__device__ __forceinline__ uint32_t load_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
+                                                       int64_t total_bytes)
+{
+    if (d < 0) return 0;
+    if (d < total_dwords) return x[d];
+    uint32_t v = 0;
+    const uint8_t *xb = reinterpret_cast<const uint8_t *>(x);
+    for (int t = 0; t < 4; ++t) {
+        int64_t byte = d * 4 + t;
+        if (byte < total_bytes) v |= (uint32_t)xb[byte] << (8 * t);
+    }
+    return v;
+}
+
+template <int N, bool A_SIGNED, bool ANY_SIGNED, bool MULTI>
+__global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
+{
+    constexpr int CH = run_chunks(N);
+    constexpr int STAGE = run_stage_dwords(N);
+    __shared__ __attribute__((aligned(16))) int32_t s_out[kWavesPerGroup * STAGE];
+    __shared__ uint32_t s_bw[kWavesPerGroup * 8];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t run = (int64_t)blockIdx.x * kWavesPerGroup + wave; // global run index
+    if (run >= p.rows * p.tiles_per_row) return;                      // wave-uniform
+    const int64_t r = run / p.tiles_per_row;
+    const int64_t xr0 = (run - r * p.tiles_per_row) * (CH * kChunkBlocks); // first owned block of the run
+    int32_t *stage = s_out + wave * STAGE;
+
+    const int S = p.S, c = p.c, b = p.b;
+    const uint32_t fmask = (1u << S) - 1u;
+    const uint32_t SN = (uint32_t)(S * N);
+    uint64_t bias_low = 0;
+    int32_t bias_f = 0;
+    if (ANY_SIGNED) {
+#pragma unroll
+        for (int m = 0; m < N; ++m) bias_low += 1ull << (S * m + S - 1);
+        bias_f = 1 << (S - 1);
+    }
+
+    // B words (Eq. inpack).  Lane t holds tap t shifted to its slice; the taps of a chunk are
+    // summed with lane reads, so B ends up wave-uniform (an SGPR in the single-chunk case).
+    uint32_t my_tap = 0;
+    if (lane < p.taps) {
+        int32_t gv = p.w_signed ? (int32_t)(int8_t)p.g[lane] : (int32_t)p.g[lane];
+        my_tap = (uint32_t)gv << (S * (lane % p.Kp));
+    }
+    uint32_t b0 = 0;
+    if (!MULTI) {
+        for (int k = 0; k < p.taps; ++k) b0 += __builtin_amdgcn_readlane(my_tap, k);
+    } else {
+        for (int ch = 0; ch < p.chunks; ++ch) {
+            uint32_t bw = 0;
+            for (int k = 0; k < p.Kp; ++k) {
+                int t = ch * p.Kp + k;
+                if (t < p.taps) bw += __builtin_amdgcn_readlane(my_tap, t);
+            }
+            if (lane == 0) s_bw[wave * 8 + ch] = bw;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    const int64_t row_bit0 = r * p.row_stride_bits;     // bit of element 0 of this row in the buffer
+    const int64_t len_bits = p.len * c;
+    const int64_t total_bits = p.total_bytes * 8;
+    const int64_t o_run0 = xr0 * N - p.shift_m;          // output index of the run's first value
+    const int a_off = (int)(((r * p.out_len + o_run0) % 4 + 4) % 4);
+    const int nc = N * c;
+
+#pragma unroll 1
+    for (int cc = 0; cc < CH; ++cc) {
+        const int64_t x0 = xr0 + (int64_t)cc * kChunkBlocks; // first owned block of the chunk
+        const int xl = cc * kChunkBlocks + lane - 1;          // this lane's block, relative to xr0
+        uint64_t acc = bias_low;
+        // wave-uniform test: every element of every lane's windows lies inside the row, and
+        // both dwords of every window lie inside the buffer
+        const int64_t e_min = (x0 - 1) * N - (MULTI ? (int64_t)(p.chunks - 1) * p.Kp : 0);
+        const int64_t e_end = (x0 + kChunkBlocks) * N;
+        const bool interior = e_min >= 0 && e_end <= p.len && row_bit0 + e_end * c + 64 <= total_bits;
+        const int nchunks = MULTI ? p.chunks : 1;
+        for (int ch = 0; ch < nchunks; ++ch) {
+            const int64_t e0 = (xr0 + xl) * N - (int64_t)ch * p.Kp; // first element of the window
+            const int64_t bit = row_bit0 + e0 * c;
+            uint32_t raw;
+            if (interior) {
+                const uint32_t *wp = p.x + (bit >> 5);
+                raw = funnel_shr(wp[1], wp[0], (uint32_t)bit & 31u);
+            } else {
+                // masked path: keep only the containers of elements in [0, len)
+                int64_t lo = e0 < 0 ? -e0 : 0, hi = p.len - e0;
+                if (hi > N) hi = N;
+                if (hi <= lo) {
+                    raw = 0;
+                } else {
+                    const int64_t d = bit >> 5; // arithmetic shift: floors for negative positions
+                    uint32_t w0 = load_dword_checked(p.x, d, p.total_dwords, p.total_bytes);
+                    uint32_t w1 = load_dword_checked(p.x, d + 1, p.total_dwords, p.total_bytes);
+                    raw = funnel_shr(w1, w0, (uint32_t)(bit & 31));
+                    const uint32_t hi_bits = (uint32_t)(hi * c), lo_bits = (uint32_t)(lo * c);
+                    const uint32_t m_hi = hi_bits >= 32 ? 0xffffffffu : ((1u << hi_bits) - 1u);
+                    raw &= m_hi & ~((1u << lo_bits) - 1u);
+                }
+            }
+            uint32_t a = 0;
+#pragma unroll
+            for (int n = 0; n < N; ++n) a += (uint32_t)field<A_SIGNED>(raw, (uint32_t)(n * c), (uint32_t)b) << (S * n);
+            const uint32_t bw = MULTI ? s_bw[wave * 8 + ch] : b0;
+            acc = mad_wide<ANY_SIGNED>(a, bw, acc);
+        }
+        (void)len_bits;
+        (void)nc;
+        const uint64_t hi = shr_wide<ANY_SIGNED>(acc, SN);
+        const uint64_t comb = acc + lane_shr1(hi);
+        if (lane > 0) {
+            int32_t *dst = stage + xl * N + a_off;
+#pragma unroll
+            for (int j = 0; j < N; ++j) dst[j] = (int32_t)((uint32_t)(comb >> (S * j)) & fmask) - bias_f;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    // copy the run to global memory: LDS quad q <-> outputs o_run0 - a_off + 4q .. +3
+    const int64_t o_lo = o_run0 > 0 ? o_run0 : 0;
+    int64_t o_hi = o_run0 + CH * kChunkBlocks * N;
+    if (o_hi > p.out_len) o_hi = p.out_len;
+    constexpr int NQ = (CH * kChunkBlocks * N + 3 + 3) / 4;
+    int32_t *yrow = p.y + r * p.out_len;
+#pragma unroll 1
+    for (int q = lane; q < NQ; q += 64) {
+        const int64_t o = o_run0 - a_off + 4 * (int64_t)q;
+        if (o >= o_lo && o + 4 <= o_hi) {
+            *reinterpret_cast<int4 *>(&yrow[o]) = *reinterpret_cast<const int4 *>(&stage[4 * q]);
+        } else {
+            for (int t = 0; t < 4; ++t)
+                if (o + t >= o_lo && o + t < o_hi) yrow[o + t] = stage[4 * q + t];
+        }
+    }
+}
+
+template <int N>
+hipError_t launch_n(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+{
+    const bool multi = a.chunks > 1;
+#define HIKONV_LAUNCH(AS, ANY, MU) hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU>), g, dim3(256), 0, stream, a)
+    if (a_signed) {
+        if (multi) HIKONV_LAUNCH(true, true, true); else HIKONV_LAUNCH(true, true, false);
+    } else if (any_signed) {
+        if (multi) HIKONV_LAUNCH(false, true, true); else HIKONV_LAUNCH(false, true, false);
+    } else {
+        if (multi) HIKONV_LAUNCH(false, false, true); else HIKONV_LAUNCH(false, false, false);
+    }
+#undef HIKONV_LAUNCH
+    return hipGetLastError();
+}
+
+} // namespace
+
+bool conv1d_fast_applicable(const Conv1dArgs &a)
+{
+    return a.N >= 1 && a.N <= 12 && a.N * a.c <= 32 && a.chunks <= 8 && a.taps <= 64;
+}
+
+int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks)
+{
+    int ch = 1;
+    switch (N) {
+#define HIKONV_CASE(n) case n: ch = run_chunks(n); break;
+        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
+        HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
+#undef HIKONV_CASE
+    default: break;
+    }
+    return ceil_div(n_blocks, (int64_t)ch * kChunkBlocks);
+}
+
+// a.tiles_per_row must hold conv1d_fast_runs_per_row(a.N, a.n_blocks)
+hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
+{
+    if (!conv1d_fast_applicable(a)) return hipErrorInvalidValue;
+    const int64_t runs = a.tiles_per_row * a.rows;
+    const int64_t grid = ceil_div(runs, kWavesPerGroup);
+    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 g((unsigned)grid);
+    switch (a.N) {
+#define HIKONV_CASE(n) case n: return launch_n<n>(a, a_signed, any_signed, g, stream);
+        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
+        HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
+#undef HIKONV_CASE
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace hikonv

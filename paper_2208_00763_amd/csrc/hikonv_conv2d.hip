@@ -54,12 +54,16 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
 __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
 {
     const int terms = p.C * p.Kh * p.chunks;
-    const int64_t total = (int64_t)p.n_cog * terms * 8;
+    const int64_t total = (int64_t)p.n_cog * p.terms_pad * 8;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     const int c8 = (int)(idx & 7);
-    const int term = (int)((idx >> 3) % terms);
-    const int cog = (int)((idx >> 3) / terms);
+    const int term = (int)((idx >> 3) % p.terms_pad);
+    const int cog = (int)((idx >> 3) / p.terms_pad);
+    if (term >= terms) { // padding of the pipeline group: contributes nothing
+        p.wp[idx] = 0;
+        return;
+    }
     const int ch = term % p.chunks;
     const int kh = (term / p.chunks) % p.Kh;
     const int ci = term / (p.chunks * p.Kh);
@@ -82,6 +86,19 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
         bw += (uint32_t)v << (p.S * k);
     }
     p.wp[idx] = bw;
+}
+
+__global__ __launch_bounds__(256) void k_term_offsets(int32_t *toff, int entries, int terms, int Kh, int chunks,
+                                                      int64_t chunk_stride, int64_t ci_words, int row_words)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= entries) return;
+    int32_t v = 0;
+    if (t < terms) {
+        const int ch = t % chunks, kh = (t / chunks) % Kh, ci = t / (chunks * Kh);
+        v = (int32_t)(ch * chunk_stride + ci * ci_words + (int64_t)kh * row_words);
+    }
+    toff[t] = v;
 }
 
 // PS[co][i][j] = sum_{kh<i, kw<j} sum_ci beta[co][ci][kh][kw]   (beta = 1 for weight +1)
@@ -204,10 +221,21 @@ hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+hipError_t launch_term_offsets(int32_t *toff, int entries, int terms, int Kh, int chunks, int64_t chunk_stride,
+                               int64_t ci_words, int row_words, hipStream_t stream)
+{
+    dim3 g;
+    hipError_t e = grid_1d(entries, &g);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_term_offsets, g, dim3(256), 0, stream, toff, entries, terms, Kh, chunks, chunk_stride,
+                       ci_words, row_words);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream)
 {
     dim3 g;
-    hipError_t e = grid_1d((int64_t)a.n_cog * a.C * a.Kh * a.chunks * 8, &g);
+    hipError_t e = grid_1d((int64_t)a.n_cog * a.terms_pad * 8, &g);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_pack_weights, g, dim3(256), 0, stream, a);
     e = hipGetLastError();
@@ -220,12 +248,12 @@ hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream)
 
 hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed, int co_tile, hipStream_t stream)
 {
-    int64_t waves;
+    int64_t row_groups;
     if (a.segs == 0)
-        waves = ceil_div(a.wave_rows, a.rows_per_wave);
+        row_groups = ceil_div(a.wave_rows, a.rows_per_wave);
     else
-        waves = a.wave_rows * a.segs;
-    const int64_t gx = ceil_div(waves, 4);
+        row_groups = a.wave_rows * a.segs;
+    const int64_t gx = ceil_div(row_groups, a.pipelined ? 4 / a.ksplit : 4);
     const int64_t gy = ceil_div(a.Co, co_tile);
     if (gx <= 0 || gx > 0x7fffffffLL || gy <= 0 || gy > 65535) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)gy);

@@ -30,6 +30,10 @@ struct Conv1dArgs {
 int conv1d_tile_chunks(int N, int64_t n_blocks);
 hipError_t launch_conv1d_packed(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
 hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream);
+// streaming variant (no workgroup barrier) for N <= 12 and N*c <= 32
+bool conv1d_fast_applicable(const Conv1dArgs &a);
+int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks);
+hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
 
 // ---- 2-D ---------------------------------------------------------------------------
 
@@ -43,13 +47,17 @@ struct PackActArgs {
     uint32_t *apk;           // [chunks][Nimg][C][Hp][Xs]
 };
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream);
+// toff[t] = chunk*chunk_stride + ci*Hp*Xs + kh*Xs for term t = (ci*Kh + kh)*chunks + chunk; 0 beyond `terms`
+hipError_t launch_term_offsets(int32_t *toff, int entries, int terms, int Kh, int chunks, int64_t chunk_stride,
+                               int64_t ci_words, int row_words, hipStream_t stream);
 
 struct PackWArgs {
     const uint8_t *w;        // [Co][C][Kh][Kw], one value per byte
     int Co, C, Kh, Kw, w_signed, bipolar;
     int Kp, S, chunks;
     int n_cog;               // ceil(Co / 8) (+1 all-ones group when bipolar)
-    uint32_t *wp;            // [n_cog][C*Kh*chunks][8]
+    int terms_pad;           // C*Kh*chunks rounded up to the pipeline group (zero words beyond)
+    uint32_t *wp;            // [n_cog][terms_pad][8]
     int32_t *ps;             // bipolar only: [Co][Kh+1][Kw+1] prefix sums of sum_ci beta
 };
 hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream);
@@ -62,6 +70,12 @@ struct Conv2dArgs {
     int Hp, Xs, X;           // packed rows per image-channel, words per row, blocks per row
     int N, S, chunks, M;     // plan; M = products accumulated per split
     int terms;               // C*Kh*chunks
+    int terms_pad;           // terms rounded up to a multiple of 4 (weights are zero beyond terms)
+    const int32_t *toff;     // [terms_pad + 8] word offset of each term's activation plane/row
+    int pipelined;           // 1: k_conv2d_pipe, 0: k_conv2d_packed
+    int ksplit;              // waves of a workgroup sharing one row group (1, 2 or 4)
+    int slice_terms;         // terms per slice (multiple of 4)
+    int split_terms;         // terms between splits in the pipelined kernel (multiple of 4)
     int Co, cog0;            // output channels to write, first weight group
     int64_t chunk_stride;    // words between chunk planes of apk
     int rows_per_wave, segs; // lane mapping
