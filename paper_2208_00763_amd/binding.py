@@ -8,7 +8,7 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libhikonv.so")
+LIB_PATH = os.environ.get("HIKONV_LIB", os.path.join(HERE, "libhikonv.so"))   # HIKONV_LIB: a tuning variant
 
 OK, EINVAL, EOVERFLOW, ENOPLAN, EHIP, EWORKSPACE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 MODE_SINGLE, MODE_CONV1D, MODE_DNN = 0, 1, 2

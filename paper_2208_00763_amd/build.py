@@ -42,16 +42,18 @@ def is_fresh() -> bool:
     return os.path.exists(LIB) and os.path.getmtime(LIB) >= _deps_mtime()
 
 
-def build(force: bool = True, jobs: int = 8) -> str:
-    """Compile every translation unit and link paper_2208_00763_amd/libhikonv.so."""
-    if not force and is_fresh():
+def build(force: bool = True, jobs: int = 8, extra_flags=(), out: str = LIB, obj_dir: str = OBJ_DIR) -> str:
+    """Compile every translation unit and link paper_2208_00763_amd/libhikonv.so.
+
+    extra_flags/out/obj_dir build a tuning variant next to the default library."""
+    if not force and out == LIB and is_fresh():
         return LIB
-    os.makedirs(OBJ_DIR, exist_ok=True)
+    os.makedirs(obj_dir, exist_ok=True)
     hipcc = _hipcc()
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc] + HIP_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        cmd = [hipcc] + HIP_FLAGS + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s" % (src, res.stderr[-4000:]))
@@ -59,11 +61,11 @@ def build(force: bool = True, jobs: int = 8) -> str:
 
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(compile_one, SOURCES))
-    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs
     res = subprocess.run(link, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n%s" % res.stderr[-4000:])
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

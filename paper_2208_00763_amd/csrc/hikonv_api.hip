@@ -53,7 +53,7 @@ int conv1d_common(int bits_a, int a_signed, int w_signed, const void *x_dev, int
 
 struct Conv2dGeom {
     int Ho, Wo, Wo1, X, Xs, Hp, terms, terms_pad, n_cog;
-    size_t apk_bytes, toff_bytes, wp_bytes, ps_bytes, sa_bytes;
+    size_t apk_bytes, wp_bytes, ps_bytes, sa_bytes;
 };
 
 inline int pad_terms(int terms) { return (terms + 3) & ~3; }
@@ -86,7 +86,6 @@ int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, i
     g->n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
     if ((int64_t)plan->chunks * N * C * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     g->apk_bytes = round256((size_t)plan->chunks * N * C * g->Hp * g->Xs * 4);
-    g->toff_bytes = round256((size_t)(g->terms_pad + 8) * 4);
     g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
     g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
     g->sa_bytes = plan->bipolar ? round256((size_t)N * g->Ho * g->Wo * 4) : 0;
@@ -124,16 +123,15 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     if (!x_dev || !w_dev || !y_dev) return HIKONV_EINVAL;
     if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE) return HIKONV_EINVAL;
     if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(w_dev, prepacked ? 256 : 1)) return HIKONV_EINVAL;
-    const size_t need = g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+    const size_t need = g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
     if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return HIKONV_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
     uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
-    int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
-    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes + g.toff_bytes);
+    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
     const uint8_t *wpk = static_cast<const uint8_t *>(w_dev);
     if (!prepacked) {
-        uint8_t *dst = ws + g.apk_bytes + g.toff_bytes + g.sa_bytes;
+        uint8_t *dst = ws + g.apk_bytes + g.sa_bytes;
         rc = pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, dst, stream);
         if (rc != HIKONV_OK) return rc;
         wpk = dst;
@@ -181,11 +179,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.M = plan->M;
     ca.terms = g.terms;
     ca.terms_pad = g.terms_pad;
-    ca.toff = toff;
     ca.chunk_stride = (int64_t)N * C * g.Hp * g.Xs;
-    rc = hip_result(launch_term_offsets(toff, g.terms_pad + 8, g.terms, Kh, plan->chunks, ca.chunk_stride,
-                                        (int64_t)g.Hp * g.Xs, g.Xs, stream));
-    if (rc != HIKONV_OK) return rc;
     if (g.Xs <= 64) {
         ca.rows_per_wave = 64 / g.Xs;
         ca.segs = 0;
@@ -214,15 +208,17 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
                 ks = 2;
         }
         args->ksplit = ks;
-        args->slice_terms = (int)(((g.terms_pad + ks - 1) / ks + 3) & ~3);
-        if ((ks - 1) * args->slice_terms >= g.terms_pad) { // keep every slice non-empty
-            args->ksplit = 1;
-            args->slice_terms = g.terms_pad;
-        }
     };
 
-    if (plan->bipolar) {
-        // window sums of a: the same kernel with the all-ones weight group, one channel
+    ca.fused_bipolar = plan->bipolar && ca.pipelined ? 1 : 0;
+    ca.ones_cog = g.n_cog - 1;
+    ca.ps = reinterpret_cast<const int32_t *>(wpk + g.wp_bytes);
+    ca.H = H;
+    ca.W = W;
+    ca.Kw = Kw;
+    ca.pad = pad;
+    if (plan->bipolar && !ca.fused_bipolar) {
+        // plain kernel: window sums of a from the all-ones weight group (one channel) ...
         Conv2dArgs sa_args = ca;
         sa_args.Co = 1;
         sa_args.cog0 = g.n_cog - 1;
@@ -239,11 +235,12 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     rc = hip_result(launch_conv2d_packed(ca, wide, any_signed, co_tile, stream));
     if (rc != HIKONV_OK) return rc;
 
-    if (plan->bipolar) {
+    if (plan->bipolar && !ca.fused_bipolar) {
+        // ... and the {-1,+1} correction as a separate pass
         BipolarFixArgs fa;
         fa.y = y_dev;
         fa.sa = sa;
-        fa.ps = reinterpret_cast<const int32_t *>(wpk + g.wp_bytes);
+        fa.ps = ca.ps;
         fa.Nimg = N;
         fa.Co = Co;
         fa.Ho = g.Ho;
@@ -286,7 +283,7 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
         return HIKONV_EUNSUPPORTED;
     if (plan->chunks != (taps + plan->K - 1) / plan->K) return HIKONV_EINVAL;
     if (hikonv_plan_check(plan) != HIKONV_OK) return HIKONV_EOVERFLOW;
-    Conv1dArgs a;
+    Conv1dArgs a = {};
     int rc = conv1d_common(plan->bits_a, plan->a_signed, plan->w_signed, x_dev, x_format, rows, len, g_dev, taps,
                            out_mode, y_dev, &a);
     if (rc != HIKONV_OK) return rc == 1 ? HIKONV_OK : rc;
@@ -299,7 +296,8 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
     const bool any_signed = plan->a_signed || plan->w_signed;
     if (conv1d_fast_applicable(a)) {
         a.CH = 0;
-        a.tiles_per_row = conv1d_fast_runs_per_row(a.N, a.n_blocks);
+        conv1d_fast_tuning(&a);
+        a.tiles_per_row = conv1d_fast_runs_per_row(a.N, a.n_blocks, a.big_runs && !a.direct_store);
         return hip_result(launch_conv1d_fast(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
     }
     a.CH = conv1d_tile_chunks(a.N, a.n_blocks);
@@ -346,7 +344,7 @@ extern "C" size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N
 {
     Conv2dGeom g;
     if (conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g) != HIKONV_OK) return 0;
-    return g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+    return g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
 }
 
 extern "C" int hikonv_conv2d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,

@@ -13,6 +13,8 @@
 // After its CH chunks the wave copies the run to global memory with 16-byte aligned,
 // fully coalesced int32x4 stores.  Row edges (zero extension of Eq. pad_f0, and the end of
 // the buffer) take a masked path that only the first and last chunk of a row enter.
+#include <cstdlib>
+
 #include "hikonv_device.h"
 #include "hikonv_launch.h"
 
@@ -23,9 +25,13 @@ constexpr int kWavesPerGroup = 4;
 constexpr int kChunkBlocks = 63;
 
 // chunks per wave run: about 750 outputs per run
-__host__ __device__ constexpr int run_chunks(int n) { return n >= 7 ? 1 : (12 / n > 0 ? 12 / n : 1); }
+// chunks per wave run: about 1500 outputs (BIG) or 750 outputs per run
+__host__ __device__ constexpr int run_chunks(int n, bool big) { return (big ? 24 : 12) / n > 0 ? (big ? 24 : 12) / n : 1; }
 // LDS dwords per wave: outputs of a run + alignment slack, rounded to 16 bytes
-__host__ __device__ constexpr int run_stage_dwords(int n) { return ((run_chunks(n) * kChunkBlocks * n + 8 + 3) / 4) * 4; }
+__host__ __device__ constexpr int run_stage_dwords(int n, bool big)
+{
+    return ((run_chunks(n, big) * kChunkBlocks * n + 8 + 3) / 4) * 4;
+}
 
 __device__ __forceinline__ uint32_t load_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
                                                        int64_t total_bytes)
@@ -41,11 +47,36 @@ __device__ __forceinline__ uint32_t load_dword_checked(const uint32_t *x, int64_
     return v;
 }
 
-template <int N, bool A_SIGNED, bool ANY_SIGNED, bool MULTI>
+// N consecutive int32 to a 4-byte aligned address with the widest stores available
+typedef int32_t v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef int32_t v3i_a4 __attribute__((ext_vector_type(3), aligned(4)));
+typedef int32_t v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
+
+template <int N>
+__device__ __forceinline__ void store_run(int32_t *dst, const int32_t (&v)[N])
+{
+    int j = 0;
+#pragma unroll
+    for (; j + 4 <= N; j += 4) {
+        v4i_a4 t = {v[j], v[j + 1], v[j + 2], v[j + 3]};
+        *reinterpret_cast<v4i_a4 *>(dst + j) = t;
+    }
+    if (N - j == 3) {
+        v3i_a4 t = {v[j], v[j + 1], v[j + 2]};
+        *reinterpret_cast<v3i_a4 *>(dst + j) = t;
+    } else if (N - j == 2) {
+        v2i_a4 t = {v[j], v[j + 1]};
+        *reinterpret_cast<v2i_a4 *>(dst + j) = t;
+    } else if (N - j == 1) {
+        dst[j] = v[j];
+    }
+}
+
+template <int N, bool A_SIGNED, bool ANY_SIGNED, bool MULTI, bool DIRECT, bool BIG>
 __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
 {
-    constexpr int CH = run_chunks(N);
-    constexpr int STAGE = run_stage_dwords(N);
+    constexpr int CH = run_chunks(N, BIG);
+    constexpr int STAGE = DIRECT ? 4 : run_stage_dwords(N, BIG);
     __shared__ __attribute__((aligned(16))) int32_t s_out[kWavesPerGroup * STAGE];
     __shared__ uint32_t s_bw[kWavesPerGroup * 8];
 
@@ -70,15 +101,20 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
 
     // B words (Eq. inpack).  Lane t holds tap t shifted to its slice; the taps of a chunk are
     // summed with lane reads, so B ends up wave-uniform (an SGPR in the single-chunk case).
-    uint32_t my_tap = 0;
-    if (lane < p.taps) {
-        int32_t gv = p.w_signed ? (int32_t)(int8_t)p.g[lane] : (int32_t)p.g[lane];
-        my_tap = (uint32_t)gv << (S * (lane % p.Kp));
-    }
-    uint32_t b0 = 0;
-    if (!MULTI) {
-        for (int k = 0; k < p.taps; ++k) b0 += __builtin_amdgcn_readlane(my_tap, k);
-    } else {
+    // The tap load is issued here and first used after the window loads have been issued.
+    const uint8_t g_byte = p.g[lane < p.taps ? lane : p.taps - 1]; // in bounds for every lane
+    auto tap_word = [&]() {
+        int32_t gv = p.w_signed ? (int32_t)(int8_t)g_byte : (int32_t)g_byte;
+        return lane < p.taps ? (uint32_t)gv << (S * (lane % p.Kp)) : 0u;
+    };
+    auto make_b0 = [&]() {
+        const uint32_t my_tap = tap_word();
+        uint32_t v = 0;
+        for (int k = 0; k < p.taps; ++k) v += __builtin_amdgcn_readlane(my_tap, k);
+        return v;
+    };
+    if (MULTI) {
+        const uint32_t my_tap = tap_word();
         for (int ch = 0; ch < p.chunks; ++ch) {
             uint32_t bw = 0;
             for (int k = 0; k < p.Kp; ++k) {
@@ -91,62 +127,122 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
     }
 
     const int64_t row_bit0 = r * p.row_stride_bits;     // bit of element 0 of this row in the buffer
-    const int64_t len_bits = p.len * c;
     const int64_t total_bits = p.total_bytes * 8;
     const int64_t o_run0 = xr0 * N - p.shift_m;          // output index of the run's first value
     const int a_off = (int)(((r * p.out_len + o_run0) % 4 + 4) % 4);
-    const int nc = N * c;
 
-#pragma unroll 1
-    for (int cc = 0; cc < CH; ++cc) {
-        const int64_t x0 = xr0 + (int64_t)cc * kChunkBlocks; // first owned block of the chunk
-        const int xl = cc * kChunkBlocks + lane - 1;          // this lane's block, relative to xr0
-        uint64_t acc = bias_low;
-        // wave-uniform test: every element of every lane's windows lies inside the row, and
-        // both dwords of every window lie inside the buffer
-        const int64_t e_min = (x0 - 1) * N - (MULTI ? (int64_t)(p.chunks - 1) * p.Kp : 0);
-        const int64_t e_end = (x0 + kChunkBlocks) * N;
-        const bool interior = e_min >= 0 && e_end <= p.len && row_bit0 + e_end * c + 64 <= total_bits;
-        const int nchunks = MULTI ? p.chunks : 1;
-        for (int ch = 0; ch < nchunks; ++ch) {
-            const int64_t e0 = (xr0 + xl) * N - (int64_t)ch * p.Kp; // first element of the window
-            const int64_t bit = row_bit0 + e0 * c;
-            uint32_t raw;
-            if (interior) {
-                const uint32_t *wp = p.x + (bit >> 5);
-                raw = funnel_shr(wp[1], wp[0], (uint32_t)bit & 31u);
-            } else {
-                // masked path: keep only the containers of elements in [0, len)
-                int64_t lo = e0 < 0 ? -e0 : 0, hi = p.len - e0;
-                if (hi > N) hi = N;
-                if (hi <= lo) {
-                    raw = 0;
-                } else {
-                    const int64_t d = bit >> 5; // arithmetic shift: floors for negative positions
-                    uint32_t w0 = load_dword_checked(p.x, d, p.total_dwords, p.total_bytes);
-                    uint32_t w1 = load_dword_checked(p.x, d + 1, p.total_dwords, p.total_bytes);
-                    raw = funnel_shr(w1, w0, (uint32_t)(bit & 31));
-                    const uint32_t hi_bits = (uint32_t)(hi * c), lo_bits = (uint32_t)(lo * c);
-                    const uint32_t m_hi = hi_bits >= 32 ? 0xffffffffu : ((1u << hi_bits) - 1u);
-                    raw &= m_hi & ~((1u << lo_bits) - 1u);
-                }
-            }
-            uint32_t a = 0;
+    // one block: pack A from a 32-bit window, multiply-accumulate over the chunks' B words
+    auto pack = [&](uint32_t raw) {
+        uint32_t a = 0;
 #pragma unroll
-            for (int n = 0; n < N; ++n) a += (uint32_t)field<A_SIGNED>(raw, (uint32_t)(n * c), (uint32_t)b) << (S * n);
-            const uint32_t bw = MULTI ? s_bw[wave * 8 + ch] : b0;
-            acc = mad_wide<ANY_SIGNED>(a, bw, acc);
-        }
-        (void)len_bits;
-        (void)nc;
+        for (int n = 0; n < N; ++n) a += (uint32_t)field<A_SIGNED>(raw, (uint32_t)(n * c), (uint32_t)b) << (S * n);
+        return a;
+    };
+    // overlap-add with the previous lane, split, then either stage in LDS or store directly
+    // (a lane's N outputs are contiguous and so are the lanes', so the wave writes one dense run)
+    int32_t *yrow = p.y + r * p.out_len;
+    auto finish = [&](uint64_t acc, int xl) {
         const uint64_t hi = shr_wide<ANY_SIGNED>(acc, SN);
         const uint64_t comb = acc + lane_shr1(hi);
         if (lane > 0) {
-            int32_t *dst = stage + xl * N + a_off;
+            int32_t v[N];
 #pragma unroll
-            for (int j = 0; j < N; ++j) dst[j] = (int32_t)((uint32_t)(comb >> (S * j)) & fmask) - bias_f;
+            for (int j = 0; j < N; ++j) v[j] = (int32_t)((uint32_t)(comb >> (S * j)) & fmask) - bias_f;
+            if (DIRECT) {
+                const int64_t o = o_run0 + (int64_t)xl * N;
+                if (o >= 0 && o + N <= p.out_len) {
+                    store_run<N>(yrow + o, v);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < N; ++j)
+                        if (o + j >= 0 && o + j < p.out_len) yrow[o + j] = v[j];
+                }
+            } else {
+                int32_t *dst = stage + xl * N + a_off;
+#pragma unroll
+                for (int j = 0; j < N; ++j) dst[j] = v[j];
+            }
+        }
+    };
+
+    // wave-uniform test: every element the run reads lies inside the row, and both dwords of
+    // every window lie inside the buffer
+    const int64_t e_min = (xr0 - 1) * N - (MULTI ? (int64_t)(p.chunks - 1) * p.Kp : 0);
+    const int64_t e_end = (xr0 + CH * kChunkBlocks) * N;
+    const bool interior = e_min >= 0 && e_end <= p.len && row_bit0 + e_end * c + 96 <= total_bits;
+
+    // MULTI: one aligned 64-bit window per block covers every chunk's (delayed) window
+    const int span_elems = MULTI ? (p.chunks - 1) * p.Kp + N : N;
+    if (interior && (!MULTI || span_elems * c <= 64)) {
+        // all loads of the run are issued before the first one is used
+        const int delay = MULTI ? (p.chunks - 1) * p.Kp : 0;          // elements the last chunk lags
+        const int64_t bit0 = row_bit0 + ((xr0 + lane - 1) * N - delay) * c; // window of chunk 0
+        const uint32_t *wp0 = p.x + (bit0 >> 5);
+        const uint32_t sh0 = (uint32_t)bit0 & 31u;
+        constexpr int kChunkStep = kChunkBlocks * N;                  // elements between chunks
+        uint32_t d0[CH], d1[CH], d2[CH], shv[CH];
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            const uint32_t bitc = sh0 + (uint32_t)(cc * kChunkStep * c); // relative to wp0's dword
+            const uint32_t *wp = wp0 + (bitc >> 5);
+            d0[cc] = wp[0];
+            d1[cc] = wp[1];
+            d2[cc] = MULTI ? wp[2] : 0u;
+            shv[cc] = bitc & 31u;
+        }
+        const uint32_t b0 = MULTI ? 0u : make_b0();
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            const uint32_t w_lo = funnel_shr(d1[cc], d0[cc], shv[cc]);
+            uint64_t acc = bias_low;
+            if (!MULTI) {
+                acc = mad_wide<ANY_SIGNED>(pack(w_lo), b0, acc);
+            } else {
+                const uint64_t win = ((uint64_t)funnel_shr(d2[cc], d1[cc], shv[cc]) << 32) | w_lo;
+                for (int ch = 0; ch < p.chunks; ++ch) {
+                    const uint32_t raw = (uint32_t)(win >> ((delay - ch * p.Kp) * c));
+                    acc = mad_wide<ANY_SIGNED>(pack(raw), s_bw[wave * 8 + ch], acc);
+                }
+            }
+            finish(acc, cc * kChunkBlocks + lane - 1);
+        }
+    } else {
+        const uint32_t b0 = MULTI ? 0u : make_b0();
+#pragma unroll 1
+        for (int cc = 0; cc < CH; ++cc) {
+            const int xl = cc * kChunkBlocks + lane - 1; // this lane's block, relative to xr0
+            uint64_t acc = bias_low;
+            const int nchunks = MULTI ? p.chunks : 1;
+            for (int ch = 0; ch < nchunks; ++ch) {
+                const int64_t e0 = (xr0 + xl) * N - (int64_t)ch * p.Kp; // first element of the window
+                const int64_t bit = row_bit0 + e0 * c;
+                uint32_t raw;
+                if (interior) {
+                    const uint32_t *wp = p.x + (bit >> 5);
+                    raw = funnel_shr(wp[1], wp[0], (uint32_t)bit & 31u);
+                } else {
+                    // masked path: keep only the containers of elements in [0, len)
+                    int64_t lo = e0 < 0 ? -e0 : 0, hi = p.len - e0;
+                    if (hi > N) hi = N;
+                    if (hi <= lo) {
+                        raw = 0;
+                    } else {
+                        const int64_t d = bit >> 5; // arithmetic shift: floors for negative positions
+                        uint32_t w0 = load_dword_checked(p.x, d, p.total_dwords, p.total_bytes);
+                        uint32_t w1 = load_dword_checked(p.x, d + 1, p.total_dwords, p.total_bytes);
+                        raw = funnel_shr(w1, w0, (uint32_t)(bit & 31));
+                        const uint32_t hi_bits = (uint32_t)(hi * c), lo_bits = (uint32_t)(lo * c);
+                        const uint32_t m_hi = hi_bits >= 32 ? 0xffffffffu : ((1u << hi_bits) - 1u);
+                        raw &= m_hi & ~((1u << lo_bits) - 1u);
+                    }
+                }
+                const uint32_t bw = MULTI ? s_bw[wave * 8 + ch] : b0;
+                acc = mad_wide<ANY_SIGNED>(pack(raw), bw, acc);
+            }
+            finish(acc, xl);
         }
     }
+    if (DIRECT) return;
     __builtin_amdgcn_wave_barrier();
 
     // copy the run to global memory: LDS quad q <-> outputs o_run0 - a_off + 4q .. +3
@@ -154,12 +250,17 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
     int64_t o_hi = o_run0 + CH * kChunkBlocks * N;
     if (o_hi > p.out_len) o_hi = p.out_len;
     constexpr int NQ = (CH * kChunkBlocks * N + 3 + 3) / 4;
-    int32_t *yrow = p.y + r * p.out_len;
 #pragma unroll 1
     for (int q = lane; q < NQ; q += 64) {
         const int64_t o = o_run0 - a_off + 4 * (int64_t)q;
         if (o >= o_lo && o + 4 <= o_hi) {
-            *reinterpret_cast<int4 *>(&yrow[o]) = *reinterpret_cast<const int4 *>(&stage[4 * q]);
+            typedef int32_t v4i __attribute__((ext_vector_type(4)));
+            const v4i v4 = *reinterpret_cast<const v4i *>(&stage[4 * q]);
+            // streaming hint for the outputs; measured faster for short blocks, slower for long ones
+            if (N <= 4)
+                __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o]));
+            else
+                *reinterpret_cast<v4i *>(&yrow[o]) = v4;
         } else {
             for (int t = 0; t < 4; ++t)
                 if (o + t >= o_lo && o + t < o_hi) yrow[o + t] = stage[4 * q + t];
@@ -171,7 +272,15 @@ template <int N>
 hipError_t launch_n(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
 {
     const bool multi = a.chunks > 1;
-#define HIKONV_LAUNCH(AS, ANY, MU) hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU>), g, dim3(256), 0, stream, a)
+#define HIKONV_LAUNCH(AS, ANY, MU)                                                                          \
+    do {                                                                                                    \
+        if (a.direct_store)                                                                                 \
+            hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU, true, false>), g, dim3(256), 0, stream, a);   \
+        else if (a.big_runs)                                                                                \
+            hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU, false, true>), g, dim3(256), 0, stream, a);   \
+        else                                                                                                \
+            hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU, false, false>), g, dim3(256), 0, stream, a);  \
+    } while (0)
     if (a_signed) {
         if (multi) HIKONV_LAUNCH(true, true, true); else HIKONV_LAUNCH(true, true, false);
     } else if (any_signed) {
@@ -185,16 +294,32 @@ hipError_t launch_n(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g,
 
 } // namespace
 
+// Launch shape of the streaming kernel.  Defaults come from measurements on MI355X; the
+// environment variables HIKONV_CONV1D_DIRECT / _BIG (0 or 1) override them for tuning.
+static int env_flag(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : dflt;
+}
+
+void conv1d_fast_tuning(Conv1dArgs *a)
+{
+    static const int direct = env_flag("HIKONV_CONV1D_DIRECT", -1);
+    static const int big = env_flag("HIKONV_CONV1D_BIG", -1);
+    a->direct_store = direct >= 0 ? direct : 0;
+    a->big_runs = big >= 0 ? big : 1;
+}
+
 bool conv1d_fast_applicable(const Conv1dArgs &a)
 {
     return a.N >= 1 && a.N <= 12 && a.N * a.c <= 32 && a.chunks <= 8 && a.taps <= 64;
 }
 
-int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks)
+int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks, bool big)
 {
     int ch = 1;
     switch (N) {
-#define HIKONV_CASE(n) case n: ch = run_chunks(n); break;
+#define HIKONV_CASE(n) case n: ch = run_chunks(n, big); break;
         HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
         HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
 #undef HIKONV_CASE
@@ -203,7 +328,7 @@ int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks)
     return ceil_div(n_blocks, (int64_t)ch * kChunkBlocks);
 }
 
-// a.tiles_per_row must hold conv1d_fast_runs_per_row(a.N, a.n_blocks)
+// a.tiles_per_row must hold conv1d_fast_runs_per_row(a.N, a.n_blocks, a.big_runs && !a.direct_store)
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
     if (!conv1d_fast_applicable(a)) return hipErrorInvalidValue;

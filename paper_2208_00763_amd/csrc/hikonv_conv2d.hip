@@ -88,19 +88,6 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
     p.wp[idx] = bw;
 }
 
-__global__ __launch_bounds__(256) void k_term_offsets(int32_t *toff, int entries, int terms, int Kh, int chunks,
-                                                      int64_t chunk_stride, int64_t ci_words, int row_words)
-{
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    if (t >= entries) return;
-    int32_t v = 0;
-    if (t < terms) {
-        const int ch = t % chunks, kh = (t / chunks) % Kh, ci = t / (chunks * Kh);
-        v = (int32_t)(ch * chunk_stride + ci * ci_words + (int64_t)kh * row_words);
-    }
-    toff[t] = v;
-}
-
 // PS[co][i][j] = sum_{kh<i, kw<j} sum_ci beta[co][ci][kh][kw]   (beta = 1 for weight +1)
 __global__ __launch_bounds__(256) void k_weight_prefix(PackWArgs p)
 {
@@ -218,17 +205,6 @@ hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
     hipError_t e = grid_1d((int64_t)a.chunks * a.Nimg * a.C * a.Hp * a.Xs, &g);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_pack_act, g, dim3(256), 0, stream, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_term_offsets(int32_t *toff, int entries, int terms, int Kh, int chunks, int64_t chunk_stride,
-                               int64_t ci_words, int row_words, hipStream_t stream)
-{
-    dim3 g;
-    hipError_t e = grid_1d(entries, &g);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_term_offsets, g, dim3(256), 0, stream, toff, entries, terms, Kh, chunks, chunk_stride,
-                       ci_words, row_words);
     return hipGetLastError();
 }
 

@@ -192,78 +192,125 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
 
 constexpr int kTermGroup = 4; // terms per pipelined group; packed weights are zero-padded to it
 
-template <int N, int CO_T, bool ANY_SIGNED, bool WIDE>
+// {-1,+1} layers (x = 2a - m, w = 2 beta - 1; a, beta in {0,1}; m = 1 inside the image):
+//   sum x w = 4 sum a beta - 2 sum a - 2 sum m beta + sum m
+// sum m beta is a rectangle sum over the per-channel prefix table of beta, sum m = C * (valid taps).
+__device__ __forceinline__ int32_t bipolar_value(const Conv2dArgs &p, int co, int ho, int wo, int32_t sum_ab, int32_t sum_a)
+{
+    int kh_lo = p.pad - ho * p.stride, kh_hi = p.H + p.pad - ho * p.stride;
+    int kw_lo = p.pad - wo * p.stride, kw_hi = p.W + p.pad - wo * p.stride;
+    kh_lo = kh_lo < 0 ? 0 : kh_lo;
+    kw_lo = kw_lo < 0 ? 0 : kw_lo;
+    kh_hi = kh_hi > p.Kh ? p.Kh : kh_hi;
+    kw_hi = kw_hi > p.Kw ? p.Kw : kw_hi;
+    const int st = p.Kw + 1;
+    const int32_t *ps = p.ps + (int64_t)co * (p.Kh + 1) * st;
+    const int32_t rect = ps[kh_hi * st + kw_hi] - ps[kh_lo * st + kw_hi] - ps[kh_hi * st + kw_lo] + ps[kh_lo * st + kw_lo];
+    return 4 * sum_ab - 2 * sum_a - 2 * rect + p.C * (kh_hi - kh_lo) * (kw_hi - kw_lo);
+}
+
+constexpr int kTermTile = 2048; // terms whose weights are staged in LDS at a time (72 KB at most)
+
+template <int N, int CO_T, bool ANY_SIGNED, bool WIDE, bool BIP>
 __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 {
     constexpr int U = kTermGroup;
-    extern __shared__ int32_t s_red[]; // (4 - 4/ksplit) * CO_T * N * 64 partial sums
+    constexpr int CE = CO_T + (BIP ? 1 : 0); // BIP: one more accumulator collects sum a (all-ones weights)
+    // LDS: weight words of the current term tile [tile][CO_T] (+ [tile] all-ones words), the
+    // activation offsets of its terms [tile + U]; reused at the end for the slice reduction
+    extern __shared__ __attribute__((aligned(16))) uint32_t s_mem[];
 
     const uint32_t *__restrict__ apk = p.apk;
     const uint32_t *__restrict__ wp = p.wp;
-    const int32_t *__restrict__ toff = p.toff;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int ks = wave % p.ksplit;                  // which slice of the term range
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ks = wave % p.ksplit;                  // which slice of every term tile
     const int64_t row_group = (int64_t)blockIdx.x * (4 / p.ksplit) + wave / p.ksplit;
     const LaneMap m = map_lane(p, row_group, lane);
     const int co0 = blockIdx.y * CO_T;
-    const uint32_t lane_off =
-        (uint32_t)(((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi); // words, < 2^31 (host check)
+    const uint32_t *a_lane = apk + ((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi;
+    const uint32_t *w_tile = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
+    const uint32_t *w_ones = wp + ((int64_t)p.ones_cog * p.terms_pad) * 8;
 
-    const int t_begin = ks * p.slice_terms;
-    int t_end = t_begin + p.slice_terms;
-    if (t_end > p.terms_pad) t_end = p.terms_pad;
-    const uint32_t *w_ptr = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad + t_begin) * 8 + (co0 & 7);
+    const int tile_cap = p.terms_pad < kTermTile ? p.terms_pad : kTermTile;
+    uint32_t *s_w = s_mem;                                   // [tile_cap][CO_T]
+    uint32_t *s_w1 = s_w + tile_cap * CO_T;                  // [tile_cap] (BIP)
+    int32_t *s_off = reinterpret_cast<int32_t *>(s_w1 + (BIP ? tile_cap : 0)); // [tile_cap + U]
 
-    SplitState<N, CO_T, ANY_SIGNED, WIDE> st;
+    SplitState<N, CE, ANY_SIGNED, WIDE> st;
     st.init(p.S);
     int since = 0, nsplit = 0;
 
-    // two-stage software pipeline: activation offsets are fetched two groups ahead (scalar),
-    // activation words and weight words one group ahead; the table has 2U spare zero entries
-    int32_t off_n[U];
-    uint32_t a_n[U], w_n[U][CO_T];
-#pragma unroll
-    for (int u = 0; u < U; ++u) off_n[u] = toff[t_begin + u];
-    if (t_begin < t_end) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            a_n[u] = (apk + off_n[u])[lane_off];
-#pragma unroll
-            for (int c = 0; c < CO_T; ++c) w_n[u][c] = w_ptr[u * 8 + c];
+    for (int tile0 = 0; tile0 < p.terms_pad; tile0 += tile_cap) {
+        const int tile_n = p.terms_pad - tile0 < tile_cap ? p.terms_pad - tile0 : tile_cap; // multiple of U
+        if (tile0 > 0) __syncthreads();
+        // stage the tile: weights (zero beyond the real terms), all-ones words, activation offsets
+        for (int i = tid; i < tile_n * CO_T; i += 256) {
+            const int t = i / CO_T, c = i - t * CO_T;
+            s_w[i] = w_tile[(int64_t)(tile0 + t) * 8 + c];
         }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) off_n[u] = toff[t_begin + U + u];
-    for (int t = t_begin; t < t_end; t += U) {
-        uint32_t a_c[U], w_c[U][CO_T];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            a_c[u] = a_n[u];
-#pragma unroll
-            for (int c = 0; c < CO_T; ++c) w_c[u][c] = w_n[u][c];
+        for (int t = tid; t < tile_n + U; t += 256) {
+            const int term = tile0 + t;
+            int32_t off = 0;
+            if (term < p.terms) {
+                const int ch = term % p.chunks, kh = (term / p.chunks) % p.Kh, ci = term / (p.chunks * p.Kh);
+                off = (int32_t)(ch * p.chunk_stride + ((int64_t)ci * p.Hp + kh) * p.Xs);
+            }
+            s_off[t] = off;
+            if (BIP && t < tile_n) s_w1[t] = w_ones[(int64_t)term * 8];
         }
-        w_ptr += U * 8;
-        if (t + U < t_end) {
+        __syncthreads();
+
+        // this wave's slice of the tile, in groups of U terms, two register buffers for the
+        // activation words: the next group's loads are in flight during the multiplies
+        const int slice = ((tile_n / U + p.ksplit - 1) / p.ksplit) * U;
+        const int t_begin = ks * slice;
+        int t_end = t_begin + slice;
+        if (t_end > tile_n) t_end = tile_n;
+        if (t_begin >= t_end) continue; // wave-uniform; barriers are outside this part
+
+        uint32_t a0[U], a1[U];
+        auto request = [&](uint32_t (&a)[U], int t) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) a[u] = a_lane[s_off[t + u]];
+        };
+        auto multiply = [&](const uint32_t (&a)[U], int t) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                a_n[u] = (apk + off_n[u])[lane_off];
+                uint32_t w[CE];
+                if (CO_T % 4 == 0) {
 #pragma unroll
-                for (int c = 0; c < CO_T; ++c) w_n[u][c] = w_ptr[u * 8 + c];
+                    for (int c4 = 0; c4 < CO_T / 4; ++c4) {
+                        const uint4 q = *reinterpret_cast<const uint4 *>(&s_w[(t + u) * CO_T + 4 * c4]);
+                        w[4 * c4] = q.x;
+                        w[4 * c4 + 1] = q.y;
+                        w[4 * c4 + 2] = q.z;
+                        w[4 * c4 + 3] = q.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < CO_T; ++c) w[c] = s_w[(t + u) * CO_T + c];
+                }
+                if (BIP) w[CO_T] = s_w1[t + u];
+#pragma unroll
+                for (int c = 0; c < CE; ++c) st.mad(c, a[u], w[c]);
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) off_n[u] = toff[t + 2 * U + u];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int c = 0; c < CO_T; ++c) st.mad(c, a_c[u], w_c[u][c]);
-        }
-        since += U;
-        if (since >= p.split_terms) { // split_terms is a multiple of U
-            st.split();
-            since = 0;
-            ++nsplit;
+            since += U;
+            if (since >= p.split_terms) { // split_terms is a multiple of U
+                st.split();
+                since = 0;
+                ++nsplit;
+            }
+        };
+
+        request(a0, t_begin);
+        for (int t = t_begin; t < t_end; t += 2 * U) {
+            request(a1, t + U < t_end ? t + U : t); // past the end: re-read this group
+            multiply(a0, t);
+            if (t + U >= t_end) break;
+            request(a0, t + 2 * U < t_end ? t + 2 * U : t);
+            multiply(a1, t + U);
         }
     }
     if (since) {
@@ -274,10 +321,12 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 
     if (p.ksplit > 1) {
         // reduce the partial sums of the slices through LDS; the wave with ks == 0 stores
+        int32_t *s_red = reinterpret_cast<int32_t *>(s_mem);
+        __syncthreads(); // the weight tile is no longer read
         if (ks > 0) {
-            int32_t *dst = s_red + ((wave - wave / p.ksplit - 1) * CO_T * N) * 64 + lane;
+            int32_t *dst = s_red + ((wave - wave / p.ksplit - 1) * CE * N) * 64 + lane;
 #pragma unroll
-            for (int c = 0; c < CO_T; ++c)
+            for (int c = 0; c < CE; ++c)
 #pragma unroll
                 for (int j = 0; j < N; ++j) dst[(c * N + j) * 64] = st.out[c][j] - unbias;
         }
@@ -285,26 +334,60 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
         if (ks > 0) return;
         for (int k2 = 1; k2 < p.ksplit; ++k2) {
             const int w2 = wave + k2;
-            const int32_t *src = s_red + ((w2 - w2 / p.ksplit - 1) * CO_T * N) * 64 + lane;
+            const int32_t *src = s_red + ((w2 - w2 / p.ksplit - 1) * CE * N) * 64 + lane;
 #pragma unroll
-            for (int c = 0; c < CO_T; ++c)
+            for (int c = 0; c < CE; ++c)
 #pragma unroll
                 for (int j = 0; j < N; ++j) st.out[c][j] += src[(c * N + j) * 64];
         }
     }
-    store_outputs<N, CO_T>(p, m, co0, st.out, unbias);
+
+    if (!BIP) {
+        store_outputs<N, CE>(p, m, co0, st.out, unbias);
+    } else {
+        if (!m.active || m.halo) return;
+        const int x = m.xi - 1;
+#pragma unroll
+        for (int c = 0; c < CO_T; ++c) {
+            if (co0 + c >= p.Co) break;
+            int32_t *yrow = p.y + (((int64_t)m.n * p.Co + co0 + c) * p.Ho + m.ho) * p.Wo;
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                const int w1 = x * N + j - p.off;
+                if (w1 >= 0 && w1 < p.Wo1 && w1 % p.stride == 0) {
+                    const int wo = w1 / p.stride;
+                    yrow[wo] = bipolar_value(p, co0 + c, m.ho, wo, st.out[c][j], st.out[CO_T][j]);
+                }
+            }
+        }
+    }
+}
+
+// dynamic LDS bytes of k_conv2d_pipe
+inline size_t conv2d_pipe_lds(const Conv2dArgs &a, int co_tile, int n)
+{
+    const int ce = co_tile + (a.fused_bipolar ? 1 : 0);
+    const size_t tile_cap = a.terms_pad < kTermTile ? a.terms_pad : kTermTile;
+    const size_t stage = (tile_cap * ce + tile_cap + kTermGroup) * 4;
+    const size_t reduce = (size_t)(4 - 4 / a.ksplit) * ce * n * 64 * 4;
+    return stage > reduce ? stage : reduce;
 }
 
 template <int N, bool ANY_SIGNED, bool WIDE>
 inline void launch_conv2d_n(const Conv2dArgs &a, int co_tile, dim3 g, hipStream_t stream)
 {
     if (a.pipelined) {
-        // one slot per wave that hands its partial sums over (4 waves, 4/ksplit of them keep theirs)
-        const size_t lds = (size_t)(4 - 4 / a.ksplit) * co_tile * N * 64 * sizeof(int32_t);
-        if (co_tile == 8)
-            hipLaunchKernelGGL((k_conv2d_pipe<N, 8, ANY_SIGNED, WIDE>), g, dim3(256), lds, stream, a);
+        const size_t lds = conv2d_pipe_lds(a, co_tile, N);
+        if (a.fused_bipolar) {
+            if (ANY_SIGNED) return; // bipolar layers are packed as unsigned bits
+            if (co_tile == 8)
+                hipLaunchKernelGGL((k_conv2d_pipe<N, 8, false, WIDE, true>), g, dim3(256), lds, stream, a);
+            else
+                hipLaunchKernelGGL((k_conv2d_pipe<N, 2, false, WIDE, true>), g, dim3(256), lds, stream, a);
+        } else if (co_tile == 8)
+            hipLaunchKernelGGL((k_conv2d_pipe<N, 8, ANY_SIGNED, WIDE, false>), g, dim3(256), lds, stream, a);
         else
-            hipLaunchKernelGGL((k_conv2d_pipe<N, 2, ANY_SIGNED, WIDE>), g, dim3(256), lds, stream, a);
+            hipLaunchKernelGGL((k_conv2d_pipe<N, 2, ANY_SIGNED, WIDE, false>), g, dim3(256), lds, stream, a);
     } else {
         if (co_tile == 8)
             hipLaunchKernelGGL((k_conv2d_packed<N, 8, ANY_SIGNED, WIDE>), g, dim3(256), 0, stream, a);

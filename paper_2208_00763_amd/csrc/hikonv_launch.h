@@ -24,6 +24,8 @@ struct Conv1dArgs {
     int64_t n_blocks;        // packed blocks per row
     int CH;                  // wave-chunks of 63 blocks per wave
     int64_t tiles_per_row;
+    int direct_store;        // streaming kernel: 1 = store from registers, 0 = through an LDS staging run
+    int big_runs;            // streaming kernel: 1 = about 1500 outputs per wave run, 0 = about 750
     int32_t *y;
 };
 
@@ -32,7 +34,8 @@ hipError_t launch_conv1d_packed(const Conv1dArgs &a, bool a_signed, bool any_sig
 hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream);
 // streaming variant (no workgroup barrier) for N <= 12 and N*c <= 32
 bool conv1d_fast_applicable(const Conv1dArgs &a);
-int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks);
+void conv1d_fast_tuning(Conv1dArgs *a);
+int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks, bool big);
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
 
 // ---- 2-D ---------------------------------------------------------------------------
@@ -47,9 +50,6 @@ struct PackActArgs {
     uint32_t *apk;           // [chunks][Nimg][C][Hp][Xs]
 };
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream);
-// toff[t] = chunk*chunk_stride + ci*Hp*Xs + kh*Xs for term t = (ci*Kh + kh)*chunks + chunk; 0 beyond `terms`
-hipError_t launch_term_offsets(int32_t *toff, int entries, int terms, int Kh, int chunks, int64_t chunk_stride,
-                               int64_t ci_words, int row_words, hipStream_t stream);
 
 struct PackWArgs {
     const uint8_t *w;        // [Co][C][Kh][Kw], one value per byte
@@ -71,11 +71,13 @@ struct Conv2dArgs {
     int N, S, chunks, M;     // plan; M = products accumulated per split
     int terms;               // C*Kh*chunks
     int terms_pad;           // terms rounded up to a multiple of 4 (weights are zero beyond terms)
-    const int32_t *toff;     // [terms_pad + 8] word offset of each term's activation plane/row
     int pipelined;           // 1: k_conv2d_pipe, 0: k_conv2d_packed
     int ksplit;              // waves of a workgroup sharing one row group (1, 2 or 4)
-    int slice_terms;         // terms per slice (multiple of 4)
     int split_terms;         // terms between splits in the pipelined kernel (multiple of 4)
+    int fused_bipolar;       // 1: the pipelined kernel also sums a and applies the {-1,+1} correction
+    int ones_cog;            // weight group holding the all-ones words (bipolar)
+    const int32_t *ps;       // bipolar: [Co][Kh+1][Kw+1] prefix sums of beta
+    int H, W, Kw, pad;       // bipolar correction needs the image and kernel extents
     int Co, cog0;            // output channels to write, first weight group
     int64_t chunk_stride;    // words between chunk planes of apk
     int rows_per_wave, segs; // lane mapping
