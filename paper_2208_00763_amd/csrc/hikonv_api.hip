@@ -1,5 +1,7 @@
 // extern "C" entry points of libhikonv.so: argument checks, workspace layout, launches.
 // No entry point allocates device memory or synchronises.
+#include <cstdlib>
+
 #include "hikonv_launch.h"
 
 using namespace hikonv;
@@ -53,10 +55,10 @@ int conv1d_common(int bits_a, int a_signed, int w_signed, const void *x_dev, int
 
 struct Conv2dGeom {
     int Ho, Wo, Wo1, X, Xs, Hp, terms, terms_pad, n_cog;
-    size_t apk_bytes, wp_bytes, ps_bytes, sa_bytes;
+    size_t apk_bytes, toff_bytes, wp_bytes, ps_bytes, ct_bytes, sa_bytes;
 };
 
-inline int pad_terms(int terms) { return (terms + 3) & ~3; }
+inline int pad_terms(int terms) { return (terms + kTermGroup - 1) / kTermGroup * kTermGroup; }
 
 int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, int Kh, int Kw, int stride, int pad,
                 Conv2dGeom *g)
@@ -87,7 +89,9 @@ int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, i
     if ((int64_t)plan->chunks * N * C * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     g->apk_bytes = round256((size_t)plan->chunks * N * C * g->Hp * g->Xs * 4);
     g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
+    g->toff_bytes = round256((size_t)(g->terms_pad + kTermGroup) * 4);
     g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
+    g->ct_bytes = plan->bipolar ? round256((size_t)Co * Kh * Kh * Kw * Kw * 4) : 0;
     g->sa_bytes = plan->bipolar ? round256((size_t)N * g->Ho * g->Wo * 4) : 0;
     return HIKONV_OK;
 }
@@ -110,6 +114,7 @@ int pack_weights_impl(const hikonv_plan_t *plan, const Conv2dGeom &g, const void
     a.terms_pad = g.terms_pad;
     a.wp = static_cast<uint32_t *>(packed_dev);
     a.ps = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(packed_dev) + g.wp_bytes);
+    a.ct = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(packed_dev) + g.wp_bytes + g.ps_bytes);
     return hip_result(launch_pack_weights(a, stream));
 }
 
@@ -123,15 +128,16 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     if (!x_dev || !w_dev || !y_dev) return HIKONV_EINVAL;
     if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE) return HIKONV_EINVAL;
     if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(w_dev, prepacked ? 256 : 1)) return HIKONV_EINVAL;
-    const size_t need = g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+    const size_t need = g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
     if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return HIKONV_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
     uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
-    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+    int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes + g.toff_bytes);
     const uint8_t *wpk = static_cast<const uint8_t *>(w_dev);
     if (!prepacked) {
-        uint8_t *dst = ws + g.apk_bytes + g.sa_bytes;
+        uint8_t *dst = ws + g.apk_bytes + g.toff_bytes + g.sa_bytes;
         rc = pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, dst, stream);
         if (rc != HIKONV_OK) return rc;
         wpk = dst;
@@ -157,6 +163,11 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     pa.Hp = g.Hp;
     pa.Xs = g.Xs;
     pa.apk = apk;
+    pa.toff = toff;
+    pa.toff_entries = g.terms_pad + kTermGroup;
+    pa.terms = g.terms;
+    pa.Kh = Kh;
+    pa.chunk_stride = (int64_t)N * C * g.Hp * g.Xs;
     rc = hip_result(launch_pack_act(pa, stream));
     if (rc != HIKONV_OK) return rc;
 
@@ -192,16 +203,22 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     const bool wide = plan->L_A == 32;
     const bool any_signed = !plan->bipolar && (plan->a_signed || plan->w_signed);
     const int64_t row_groups = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, ca.rows_per_wave);
-    // the pipelined kernel splits after a multiple of four terms
-    const int split_terms = (plan->M * plan->chunks) & ~3;
-    ca.pipelined = split_terms >= 4 ? 1 : 0;
+    // the pipelined kernel splits after a whole number of term groups
+    const int split_terms = (plan->M * plan->chunks) / kTermGroup * kTermGroup;
+    ca.pipelined = split_terms >= kTermGroup ? 1 : 0;
     ca.split_terms = split_terms;
 
     // enough waves to cover the load latency: divide the term range over 2 or 4 waves of a
     // workgroup when the layer has few (row group, channel tile) pairs
     auto choose_split = [&](int64_t base_waves, Conv2dArgs *args) {
         int ks = 1;
-        if (args->pipelined) {
+        static const int forced = [] {
+            const char *e = getenv("HIKONV_CONV2D_KSPLIT"); // tuning override: 1, 2 or 4
+            return e ? atoi(e) : 0;
+        }();
+        if (args->pipelined && (forced == 1 || forced == 2 || forced == 4)) {
+            ks = g.terms_pad >= kTermGroup * forced ? forced : 1;
+        } else if (args->pipelined) {
             if (base_waves < 2048 && g.terms_pad >= 64)
                 ks = 4;
             else if (base_waves < 4096 && g.terms_pad >= 32)
@@ -212,11 +229,15 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
 
     ca.fused_bipolar = plan->bipolar && ca.pipelined ? 1 : 0;
     ca.ones_cog = g.n_cog - 1;
-    ca.ps = reinterpret_cast<const int32_t *>(wpk + g.wp_bytes);
+    ca.ct = reinterpret_cast<const int32_t *>(wpk + g.wp_bytes + g.ps_bytes);
+    ca.toff = toff;
     ca.H = H;
     ca.W = W;
     ca.Kw = Kw;
     ca.pad = pad;
+    ca.Kp = plan->K;
+    ca.ones_word0 = 0;
+    for (int k = 0; k < plan->K && k < Kw; ++k) ca.ones_word0 += 1u << (plan->S * k);
     if (plan->bipolar && !ca.fused_bipolar) {
         // plain kernel: window sums of a from the all-ones weight group (one channel) ...
         Conv2dArgs sa_args = ca;
@@ -240,7 +261,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
         BipolarFixArgs fa;
         fa.y = y_dev;
         fa.sa = sa;
-        fa.ps = ca.ps;
+        fa.ct = ca.ct;
         fa.Nimg = N;
         fa.Co = Co;
         fa.Ho = g.Ho;
@@ -322,7 +343,8 @@ extern "C" size_t hikonv_packed_weights_bytes(const hikonv_plan_t *plan, int Co,
     if (!plan || Co < 1 || C < 1 || Kh < 1 || Kw < 1 || plan->chunks < 1) return 0;
     const size_t n_cog = (size_t)(Co + 7) / 8 + (plan->bipolar ? 1 : 0);
     size_t bytes = round256(n_cog * pad_terms(C * Kh * plan->chunks) * 8 * 4);
-    if (plan->bipolar) bytes += round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4);
+    if (plan->bipolar)
+        bytes += round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) + round256((size_t)Co * Kh * Kh * Kw * Kw * 4);
     return bytes;
 }
 
@@ -336,6 +358,7 @@ extern "C" int hikonv_pack_weights(const hikonv_plan_t *plan, const void *w_dev,
     g.n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
     g.terms_pad = pad_terms(C * Kh * plan->chunks);
     g.wp_bytes = round256((size_t)g.n_cog * g.terms_pad * 8 * 4);
+    g.ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
     return pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, packed_dev, static_cast<hipStream_t>(stream));
 }
 
@@ -344,7 +367,7 @@ extern "C" size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N
 {
     Conv2dGeom g;
     if (conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g) != HIKONV_OK) return 0;
-    return g.apk_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes);
+    return g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
 }
 
 extern "C" int hikonv_conv2d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,

@@ -15,6 +15,17 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
 {
     const int64_t total = (int64_t)p.chunks * p.Nimg * p.C * p.Hp * p.Xs;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    // the first threads also write the table of activation offsets of the terms
+    // t = (ci*Kh + kh)*chunks + chunk  ->  chunk*chunk_stride + (ci*Hp + kh)*Xs
+    if (idx < p.toff_entries) {
+        const int t = (int)idx;
+        int32_t off = 0;
+        if (t < p.terms) {
+            const int ch = t % p.chunks, kh = (t / p.chunks) % p.Kh, ci = t / (p.chunks * p.Kh);
+            off = (int32_t)(ch * p.chunk_stride + ((int64_t)ci * p.Hp + kh) * p.Xs);
+        }
+        p.toff[t] = off;
+    }
     if (idx >= total) return;
     const int xi = (int)(idx % p.Xs);
     int64_t t = idx / p.Xs;
@@ -103,6 +114,32 @@ __global__ __launch_bounds__(256) void k_weight_prefix(PackWArgs p)
     p.ps[idx] = s;
 }
 
+// CT[co][a][b][c][d] = C*(Kh-a-b)*(Kw-c-d) - 2 * sum_{kh in [a,Kh-b), kw in [c,Kw-d)} sum_ci beta:
+// the part of the {-1,+1} correction that depends only on the channel and on which kernel
+// taps fall inside the image (a, b rows cut at the top / bottom; c, d columns cut left / right).
+__global__ __launch_bounds__(256) void k_class_table(PackWArgs p)
+{
+    const int per_co = p.Kh * p.Kh * p.Kw * p.Kw;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= p.Co * per_co) return;
+    const int co = idx / per_co;
+    int r = idx % per_co;
+    const int d = r % p.Kw;
+    r /= p.Kw;
+    const int c = r % p.Kw;
+    r /= p.Kw;
+    const int b = r % p.Kh, a = r / p.Kh;
+    int32_t v = 0;
+    if (a + b < p.Kh && c + d < p.Kw) {
+        const int st = p.Kw + 1;
+        const int32_t *ps = p.ps + (int64_t)co * (p.Kh + 1) * st;
+        const int kh_hi = p.Kh - b, kw_hi = p.Kw - d;
+        const int32_t rect = ps[kh_hi * st + kw_hi] - ps[a * st + kw_hi] - ps[kh_hi * st + c] + ps[a * st + c];
+        v = p.C * (kh_hi - a) * (kw_hi - c) - 2 * rect;
+    }
+    p.ct[idx] = v;
+}
+
 // {-1,+1} layers: with x = 2a - m and w = 2 beta - 1 (a, beta in {0,1}; m = 1 inside the
 // image, 0 in the zero padding):  sum x w = 4 sum a beta - 2 sum a - 2 sum m beta + sum m.
 __global__ __launch_bounds__(256) void k_bipolar_fix(BipolarFixArgs p)
@@ -114,18 +151,9 @@ __global__ __launch_bounds__(256) void k_bipolar_fix(BipolarFixArgs p)
     const int ho = (int)((idx / p.Wo) % p.Ho);
     const int co = (int)((idx / ((int64_t)p.Wo * p.Ho)) % p.Co);
     const int n = (int)(idx / ((int64_t)p.Wo * p.Ho * p.Co));
-    int kh_lo = p.pad - ho * p.stride, kh_hi = p.H + p.pad - ho * p.stride;
-    int kw_lo = p.pad - wo * p.stride, kw_hi = p.W + p.pad - wo * p.stride;
-    kh_lo = kh_lo < 0 ? 0 : kh_lo;
-    kw_lo = kw_lo < 0 ? 0 : kw_lo;
-    kh_hi = kh_hi > p.Kh ? p.Kh : kh_hi;
-    kw_hi = kw_hi > p.Kw ? p.Kw : kw_hi;
-    const int32_t *ps = p.ps + (int64_t)co * (p.Kh + 1) * (p.Kw + 1);
-    const int st = p.Kw + 1;
-    const int32_t rect = ps[kh_hi * st + kw_hi] - ps[kh_lo * st + kw_hi] - ps[kh_hi * st + kw_lo] + ps[kh_lo * st + kw_lo];
-    const int32_t cnt = (kh_hi - kh_lo) * (kw_hi - kw_lo);
     const int32_t sa = p.sa[((int64_t)n * p.Ho + ho) * p.Wo + wo];
-    p.y[idx] = 4 * p.y[idx] - 2 * sa - 2 * rect + p.C * cnt;
+    p.y[idx] = bipolar_value(p.ct, co, ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, p.y[idx], sa);
+    return;
 }
 
 // Baseline: direct layer, one v_mad_i32_i24 per low-bit product.  One lane owns one output
@@ -202,7 +230,9 @@ inline hipError_t grid_1d(int64_t total, dim3 *g)
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
 {
     dim3 g;
-    hipError_t e = grid_1d((int64_t)a.chunks * a.Nimg * a.C * a.Hp * a.Xs, &g);
+    int64_t threads = (int64_t)a.chunks * a.Nimg * a.C * a.Hp * a.Xs;
+    if (threads < a.toff_entries) threads = a.toff_entries;
+    hipError_t e = grid_1d(threads, &g);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_pack_act, g, dim3(256), 0, stream, a);
     return hipGetLastError();
@@ -219,6 +249,11 @@ hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream)
     e = grid_1d((int64_t)a.Co * (a.Kh + 1) * (a.Kw + 1), &g);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_weight_prefix, g, dim3(256), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = grid_1d((int64_t)a.Co * a.Kh * a.Kh * a.Kw * a.Kw, &g);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_class_table, g, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -19,7 +19,7 @@
 // segments of 63 blocks whose lane 0 recomputes the preceding block.
 //
 // k_conv2d_packed is the plain loop (any M).  k_conv2d_pipe is the production kernel: terms
-// are walked in groups of four through a table of activation offsets, the loads of the next
+// are walked in small groups through a table of activation offsets, the loads of the next
 // group are issued before the multiplies of the current one, and the term range of a row
 // group can be divided among the 2 or 4 waves of a workgroup (partial int32 sums are
 // reduced through LDS), which supplies enough waves for layers with few output rows.
@@ -177,6 +177,7 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
                 w_ptr += 8;
             }
             if (++since == p.M) {
+                asm volatile("" ::: "memory"); // keep the split out of the multiply block (no speculation)
                 st.split();
                 since = 0;
                 ++nsplit;
@@ -190,23 +191,32 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
     store_outputs<N, CO_T>(p, m, co0, st.out, ANY_SIGNED ? nsplit * (1 << (p.S - 1)) : 0);
 }
 
-constexpr int kTermGroup = 4; // terms per pipelined group; packed weights are zero-padded to it
 
 // {-1,+1} layers (x = 2a - m, w = 2 beta - 1; a, beta in {0,1}; m = 1 inside the image):
 //   sum x w = 4 sum a beta - 2 sum a - 2 sum m beta + sum m
-// sum m beta is a rectangle sum over the per-channel prefix table of beta, sum m = C * (valid taps).
-__device__ __forceinline__ int32_t bipolar_value(const Conv2dArgs &p, int co, int ho, int wo, int32_t sum_ab, int32_t sum_a)
+// The last two terms depend only on the channel and on which kernel taps fall inside the
+// image; they come from the border-class table built when the weights are packed.
+__device__ __forceinline__ int32_t bipolar_value(const int32_t *ct, int co, int ho, int wo, int H, int W, int Kh, int Kw,
+                                                 int stride, int pad, int32_t sum_ab, int32_t sum_a)
 {
-    int kh_lo = p.pad - ho * p.stride, kh_hi = p.H + p.pad - ho * p.stride;
-    int kw_lo = p.pad - wo * p.stride, kw_hi = p.W + p.pad - wo * p.stride;
-    kh_lo = kh_lo < 0 ? 0 : kh_lo;
-    kw_lo = kw_lo < 0 ? 0 : kw_lo;
-    kh_hi = kh_hi > p.Kh ? p.Kh : kh_hi;
-    kw_hi = kw_hi > p.Kw ? p.Kw : kw_hi;
-    const int st = p.Kw + 1;
-    const int32_t *ps = p.ps + (int64_t)co * (p.Kh + 1) * st;
-    const int32_t rect = ps[kh_hi * st + kw_hi] - ps[kh_lo * st + kw_hi] - ps[kh_hi * st + kw_lo] + ps[kh_lo * st + kw_lo];
-    return 4 * sum_ab - 2 * sum_a - 2 * rect + p.C * (kh_hi - kh_lo) * (kw_hi - kw_lo);
+    int top = pad - ho * stride, bottom = ho * stride + Kh - pad - H;  // kernel rows cut off above / below
+    int left = pad - wo * stride, right = wo * stride + Kw - pad - W;  // kernel columns cut off left / right
+    top = top < 0 ? 0 : top;
+    bottom = bottom < 0 ? 0 : bottom;
+    left = left < 0 ? 0 : left;
+    right = right < 0 ? 0 : right;
+    if (top + bottom >= Kh || left + right >= Kw) return 4 * sum_ab - 2 * sum_a; // no tap inside the image
+    const int cls = ((top * Kh + bottom) * Kw + left) * Kw + right;
+    return 4 * sum_ab - 2 * sum_a + ct[(int64_t)co * Kh * Kh * Kw * Kw + cls];
+}
+
+// all-ones B word of chunk ch: one bit at the bottom of every slice that holds a real tap
+__device__ __forceinline__ uint32_t ones_word_of_chunk(const Conv2dArgs &p, int ch)
+{
+    uint32_t v = 0;
+    for (int k = 0; k < p.Kp; ++k)
+        if (ch * p.Kp + k < p.Kw) v += 1u << (p.S * k);
+    return v;
 }
 
 constexpr int kTermTile = 2048; // terms whose weights are staged in LDS at a time (72 KB at most)
@@ -216,8 +226,8 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 {
     constexpr int U = kTermGroup;
     constexpr int CE = CO_T + (BIP ? 1 : 0); // BIP: one more accumulator collects sum a (all-ones weights)
-    // LDS: weight words of the current term tile [tile][CO_T] (+ [tile] all-ones words), the
-    // activation offsets of its terms [tile + U]; reused at the end for the slice reduction
+    // LDS: weight words of the current term tile [tile][CO_T] and the activation offsets of its
+    // terms [tile + U]; reused at the end for the slice reduction
     extern __shared__ __attribute__((aligned(16))) uint32_t s_mem[];
 
     const uint32_t *__restrict__ apk = p.apk;
@@ -231,12 +241,13 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     const int co0 = blockIdx.y * CO_T;
     const uint32_t *a_lane = apk + ((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi;
     const uint32_t *w_tile = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
-    const uint32_t *w_ones = wp + ((int64_t)p.ones_cog * p.terms_pad) * 8;
 
     const int tile_cap = p.terms_pad < kTermTile ? p.terms_pad : kTermTile;
     uint32_t *s_w = s_mem;                                   // [tile_cap][CO_T]
-    uint32_t *s_w1 = s_w + tile_cap * CO_T;                  // [tile_cap] (BIP)
-    int32_t *s_off = reinterpret_cast<int32_t *>(s_w1 + (BIP ? tile_cap : 0)); // [tile_cap + U]
+    int32_t *s_off = reinterpret_cast<int32_t *>(s_w + tile_cap * CO_T); // [tile_cap + U]
+    __shared__ uint32_t s_ones[8];                                        // all-ones B word of each chunk (BIP)
+    const uint32_t ones0 = p.ones_word0;
+    if (BIP && tid < 8) s_ones[tid] = ones_word_of_chunk(p, tid);
 
     SplitState<N, CE, ANY_SIGNED, WIDE> st;
     st.init(p.S);
@@ -245,21 +256,32 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     for (int tile0 = 0; tile0 < p.terms_pad; tile0 += tile_cap) {
         const int tile_n = p.terms_pad - tile0 < tile_cap ? p.terms_pad - tile0 : tile_cap; // multiple of U
         if (tile0 > 0) __syncthreads();
-        // stage the tile: weights (zero beyond the real terms), all-ones words, activation offsets
-        for (int i = tid; i < tile_n * CO_T; i += 256) {
-            const int t = i / CO_T, c = i - t * CO_T;
-            s_w[i] = w_tile[(int64_t)(tile0 + t) * 8 + c];
-        }
-        for (int t = tid; t < tile_n + U; t += 256) {
-            const int term = tile0 + t;
-            int32_t off = 0;
-            if (term < p.terms) {
-                const int ch = term % p.chunks, kh = (term / p.chunks) % p.Kh, ci = term / (p.chunks * p.Kh);
-                off = (int32_t)(ch * p.chunk_stride + ((int64_t)ci * p.Hp + kh) * p.Xs);
+        // stage the tile: weight words (8 per term are contiguous in memory and zero beyond the
+        // real terms) and the activation offsets of the terms, with 128-bit copies issued in
+        // batches so that a thread waits for memory once per batch
+        if (CO_T == 8) {
+            const int total = tile_n * 2; // uint4 units
+            const uint4 *src = reinterpret_cast<const uint4 *>(w_tile + (int64_t)tile0 * 8);
+            uint4 *dst = reinterpret_cast<uint4 *>(s_w);
+            for (int i = tid; i < total; i += 1024) {
+                const int i1 = i + 256, i2 = i + 512, i3 = i + 768;
+                const uint4 v0 = src[i];
+                const uint4 v1 = src[i1 < total ? i1 : i];
+                const uint4 v2 = src[i2 < total ? i2 : i];
+                const uint4 v3 = src[i3 < total ? i3 : i];
+                dst[i] = v0;
+                if (i1 < total) dst[i1] = v1;
+                if (i2 < total) dst[i2] = v2;
+                if (i3 < total) dst[i3] = v3;
             }
-            s_off[t] = off;
-            if (BIP && t < tile_n) s_w1[t] = w_ones[(int64_t)term * 8];
+        } else {
+            const int total = tile_n * CO_T;
+            for (int i = tid; i < total; i += 256) {
+                const int t = i / CO_T, c = i - t * CO_T;
+                s_w[i] = w_tile[(int64_t)(tile0 + t) * 8 + c];
+            }
         }
+        for (int t = tid; t < tile_n + U; t += 256) s_off[t] = p.toff[tile0 + t];
         __syncthreads();
 
         // this wave's slice of the tile, in groups of U terms, two register buffers for the
@@ -292,12 +314,14 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 #pragma unroll
                     for (int c = 0; c < CO_T; ++c) w[c] = s_w[(t + u) * CO_T + c];
                 }
-                if (BIP) w[CO_T] = s_w1[t + u];
+                if (BIP) // padding terms beyond the real ones contribute nothing
+                    w[CO_T] = tile0 + t + u < p.terms ? (p.chunks == 1 ? ones0 : s_ones[(tile0 + t + u) % p.chunks]) : 0u;
 #pragma unroll
                 for (int c = 0; c < CE; ++c) st.mad(c, a[u], w[c]);
             }
             since += U;
             if (since >= p.split_terms) { // split_terms is a multiple of U
+                asm volatile("" ::: "memory"); // keep the split out of the multiply block (no speculation)
                 st.split();
                 since = 0;
                 ++nsplit;
@@ -319,45 +343,47 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     }
     const int32_t unbias = ANY_SIGNED ? nsplit * (1 << (p.S - 1)) : 0;
 
+    // Epilogue.  With ksplit > 1 the slices' partial sums meet in LDS and every wave of the
+    // row group finishes an equal share of the channels (sum, {-1,+1} correction, store).
+    int c_begin = 0, c_end = CO_T;
     if (p.ksplit > 1) {
-        // reduce the partial sums of the slices through LDS; the wave with ks == 0 stores
-        int32_t *s_red = reinterpret_cast<int32_t *>(s_mem);
-        __syncthreads(); // the weight tile is no longer read
-        if (ks > 0) {
-            int32_t *dst = s_red + ((wave - wave / p.ksplit - 1) * CE * N) * 64 + lane;
+        int32_t *s_red = reinterpret_cast<int32_t *>(s_mem); // [4 waves][CE*N][64]
+        __syncthreads();                                      // the weight tile is no longer read
+        int32_t *dst = s_red + (wave * CE * N) * 64 + lane;
 #pragma unroll
-            for (int c = 0; c < CE; ++c)
+        for (int c = 0; c < CE; ++c)
 #pragma unroll
-                for (int j = 0; j < N; ++j) dst[(c * N + j) * 64] = st.out[c][j] - unbias;
-        }
+            for (int j = 0; j < N; ++j) dst[(c * N + j) * 64] = st.out[c][j] - unbias;
         __syncthreads();
-        if (ks > 0) return;
-        for (int k2 = 1; k2 < p.ksplit; ++k2) {
-            const int w2 = wave + k2;
-            const int32_t *src = s_red + ((w2 - w2 / p.ksplit - 1) * CE * N) * 64 + lane;
+        c_begin = ks * CO_T / p.ksplit;
+        c_end = (ks + 1) * CO_T / p.ksplit;
+        const int w0 = wave - ks; // first wave of this row group
 #pragma unroll
-            for (int c = 0; c < CE; ++c)
-#pragma unroll
-                for (int j = 0; j < N; ++j) st.out[c][j] += src[(c * N + j) * 64];
-        }
-    }
-
-    if (!BIP) {
-        store_outputs<N, CE>(p, m, co0, st.out, unbias);
-    } else {
-        if (!m.active || m.halo) return;
-        const int x = m.xi - 1;
-#pragma unroll
-        for (int c = 0; c < CO_T; ++c) {
-            if (co0 + c >= p.Co) break;
-            int32_t *yrow = p.y + (((int64_t)m.n * p.Co + co0 + c) * p.Ho + m.ho) * p.Wo;
+        for (int c = 0; c < CE; ++c) {
+            if (!((c >= c_begin && c < c_end) || (BIP && c == CO_T))) continue;
 #pragma unroll
             for (int j = 0; j < N; ++j) {
-                const int w1 = x * N + j - p.off;
-                if (w1 >= 0 && w1 < p.Wo1 && w1 % p.stride == 0) {
-                    const int wo = w1 / p.stride;
-                    yrow[wo] = bipolar_value(p, co0 + c, m.ho, wo, st.out[c][j], st.out[CO_T][j]);
-                }
+                int32_t v = 0;
+                for (int k2 = 0; k2 < p.ksplit; ++k2) v += s_red[((w0 + k2) * CE * N + c * N + j) * 64 + lane];
+                st.out[c][j] = v + unbias; // store_outputs subtracts it again
+            }
+        }
+    }
+    if (!m.active || m.halo) return;
+    const int x = m.xi - 1;
+#pragma unroll
+    for (int c = 0; c < CO_T; ++c) {
+        if (c < c_begin || c >= c_end || co0 + c >= p.Co) continue;
+        int32_t *yrow = p.y + (((int64_t)m.n * p.Co + co0 + c) * p.Ho + m.ho) * p.Wo;
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const int w1 = x * N + j - p.off; // stride-1 output column
+            if (w1 >= 0 && w1 < p.Wo1 && (p.stride == 1 || w1 % p.stride == 0)) {
+                const int wo = p.stride == 1 ? w1 : w1 / p.stride;
+                const int32_t v = st.out[c][j] - unbias;
+                yrow[wo] = BIP ? bipolar_value(p.ct, co0 + c, m.ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, v,
+                                               st.out[CO_T][j] - unbias)
+                               : v;
             }
         }
     }
@@ -368,8 +394,8 @@ inline size_t conv2d_pipe_lds(const Conv2dArgs &a, int co_tile, int n)
 {
     const int ce = co_tile + (a.fused_bipolar ? 1 : 0);
     const size_t tile_cap = a.terms_pad < kTermTile ? a.terms_pad : kTermTile;
-    const size_t stage = (tile_cap * ce + tile_cap + kTermGroup) * 4;
-    const size_t reduce = (size_t)(4 - 4 / a.ksplit) * ce * n * 64 * 4;
+    const size_t stage = (tile_cap * co_tile + tile_cap + kTermGroup) * 4;
+    const size_t reduce = a.ksplit > 1 ? (size_t)4 * ce * n * 64 * 4 : 0;
     return stage > reduce ? stage : reduce;
 }
 

@@ -40,6 +40,13 @@ hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signe
 
 // ---- 2-D ---------------------------------------------------------------------------
 
+// Terms per group of the pipelined layer kernel: packed weights and the offset table are
+// zero-padded to a multiple of it, and splits happen after a multiple of it.
+#ifndef HIKONV_TERM_GROUP
+#define HIKONV_TERM_GROUP 4
+#endif
+constexpr int kTermGroup = HIKONV_TERM_GROUP;
+
 struct PackActArgs {
     const void *x;           // NCHW activations, INT8 or bit-dense rows
     int x_format, c, b, a_signed, bipolar;
@@ -48,6 +55,9 @@ struct PackActArgs {
     int N, Kp, S, chunks;    // plan
     int Hp, Xs;              // padded rows (H + 2 pad), words per packed row (1 zero word + blocks)
     uint32_t *apk;           // [chunks][Nimg][C][Hp][Xs]
+    int32_t *toff;           // [toff_entries] word offset of each term's activation row (0 beyond the terms)
+    int toff_entries, terms, Kh;
+    int64_t chunk_stride;    // words between chunk planes of apk
 };
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream);
 
@@ -59,6 +69,7 @@ struct PackWArgs {
     int terms_pad;           // C*Kh*chunks rounded up to the pipeline group (zero words beyond)
     uint32_t *wp;            // [n_cog][terms_pad][8]
     int32_t *ps;             // bipolar only: [Co][Kh+1][Kw+1] prefix sums of sum_ci beta
+    int32_t *ct;             // bipolar only: [Co][Kh][Kh][Kw][Kw] correction C*taps - 2*sum beta per border class
 };
 hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream);
 
@@ -76,7 +87,10 @@ struct Conv2dArgs {
     int split_terms;         // terms between splits in the pipelined kernel (multiple of 4)
     int fused_bipolar;       // 1: the pipelined kernel also sums a and applies the {-1,+1} correction
     int ones_cog;            // weight group holding the all-ones words (bipolar)
-    const int32_t *ps;       // bipolar: [Co][Kh+1][Kw+1] prefix sums of beta
+    const int32_t *ct;       // bipolar: [Co][Kh][Kh][Kw][Kw] border-class correction table
+    const int32_t *toff;     // [terms_pad + kTermGroup] activation word offset of every term
+    uint32_t ones_word0;     // bipolar: the all-ones B word of chunk 0
+    int Kp;                  // taps per B word
     int H, W, Kw, pad;       // bipolar correction needs the image and kernel extents
     int Co, cog0;            // output channels to write, first weight group
     int64_t chunk_stride;    // words between chunk planes of apk
@@ -91,7 +105,7 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed,
 struct BipolarFixArgs {
     int32_t *y;              // in: sum a*beta; out: sum x*w
     const int32_t *sa;       // [Nimg][Ho][Wo] window sums of a
-    const int32_t *ps;       // [Co][Kh+1][Kw+1]
+    const int32_t *ct;       // [Co][Kh][Kh][Kw][Kw]
     int Nimg, Co, Ho, Wo, C, H, W, Kh, Kw, stride, pad;
 };
 hipError_t launch_bipolar_fix(const BipolarFixArgs &a, hipStream_t stream);
