@@ -129,6 +129,27 @@ def conv2d_extra(hk, wl, name, steps):
     return report
 
 
+def microbench(hk):
+    """Issue rates (10^12 lane-instructions/s over the whole chip) and HBM bandwidths (TB/s)."""
+    import torch
+    kinds = {"v_mad_u32_u24": hk.UB_MAD_U32_U24, "v_mad_i32_i24": hk.UB_MAD_I32_I24,
+             "v_mad_u64_u32": hk.UB_MAD_U64_U32, "v_mad_i64_i32": hk.UB_MAD_I64_I32,
+             "v_mul_lo_u32": hk.UB_MUL_LO_U32, "v_bfe_u32": hk.UB_BFE_U32, "v_lshrrev_b64": hk.UB_LSHR_B64,
+             "v_lshl_add_u64": hk.UB_ADD_U64, "v_alignbit_b32": hk.UB_ALIGNBIT, "v_mov_b32_dpp wave_shr:1": hk.UB_DPP_MOV}
+    blocks, iters = 256 * 32, 2000                       # 32 waves per CU, 64 instructions per iteration
+    buf = torch.zeros(blocks * 256, dtype=torch.int32, device="cuda")
+    out = {"valu_T_lane_instr_per_s": {}, "hbm_TB_per_s": {}, "nominal_valu_T": VALU_LANE_RATE / 1e12}
+    for name, kind in kinds.items():
+        full = min(event_ms(lambda: hk.hikonv_ubench(kind, iters, blocks, buf), 3) for _ in range(3))
+        empty = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, blocks, buf), 3) for _ in range(3))
+        out["valu_T_lane_instr_per_s"][name] = blocks * 256 * iters * 64 / ((full - empty) * 1e-3) / 1e12
+    big = torch.zeros(2 * 1024 ** 3 // 4, dtype=torch.int32, device="cuda")
+    for name, kind in (("write", hk.UB_HBM_WRITE), ("copy_read_plus_write", hk.UB_HBM_COPY), ("read", hk.UB_HBM_READ)):
+        best = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, nb, big), 5) for nb in (4096, 16384, 32768, 65536))
+        out["hbm_TB_per_s"][name] = big.numel() * 4 / (best * 1e-3) / 1e12
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,6 +157,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true", help="only the headline case and its roofline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--ubench", action="store_true",
+                    help="print the measured issue rate of the integer VALU instructions the kernels use and the "
+                         "HBM write / copy / read bandwidth (the two rooflines), then exit")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain copy kernel of known size (512 MiB read + 512 MiB written, 3 launches) "
+                         "so that HBM byte counters collected by a profiler can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (every box has one); run with --gpus 1", file=sys.stderr)
@@ -148,6 +175,17 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
+
+    if args.ubench:
+        print(json.dumps(microbench(hk)))
+        return 0
+
+    if args.calibrate:
+        cal = torch.zeros(1024 ** 3 // 4, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            hk.hikonv_ubench(hk.UB_HBM_COPY, 0, 32768, cal)
+        torch.cuda.synchronize()
+        del cal
 
     head = conv1d_case(hk, wl, 4, False)
     for _ in range(args.warmup):
