@@ -129,6 +129,55 @@ def conv2d_extra(hk, wl, name, steps):
     return report
 
 
+def small_extras(hk, wl, steps):
+    """Latency-scale configurations: the 4096-value 1-D case and the nine-layer 4-bit CNN forward
+    (eager launches and the same launches replayed from a captured HIP graph)."""
+    import torch
+    from paper_2208_00763_amd.cnn import PackedCnn
+    out = {}
+    x, g = wl.config1()
+    plan = hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3)
+    x_d = torch.from_numpy(x).cuda()
+    g_d = torch.from_numpy(g).cuda()
+    x_bd = torch.zeros(hk.hikonv_bitdense_row_bytes(4096, 4), dtype=torch.uint8, device="cuda")
+    hk.hikonv_compact(x_d, 1, 4096, 4, False, x_bd)
+    y = torch.empty(4094, dtype=torch.int32, device="cuda")
+    run1 = lambda: hk.hikonv_conv1d(plan, x_bd, hk.FMT_BITDENSE, 1, 4096, g_d, 3, hk.OUT_VALID, y)
+    event_ms(run1, 10)
+    out["conv1d_c1_us_per_call"] = event_ms(run1, 200) * 1e3
+
+    xi, weights, specs = wl.config5()
+    net = PackedCnn([torch.from_numpy(w.view("uint8")).cuda() for w in weights], specs)
+    x5 = torch.zeros(3 * 160 * hk.hikonv_bitdense_row_bytes(320, 4), dtype=torch.uint8, device="cuda")
+    hk.hikonv_compact(torch.from_numpy(xi).cuda(), 3 * 160, 320, 4, False, x5)
+    shifts = [4, 6, 7, 7, 7, 7, 7, 7]
+    fwd = lambda: net.forward(x5, 1, 160, 320, shifts)
+    event_ms(fwd, 3)
+    out["cnn_c5_eager_us"] = event_ms(fwd, steps) * 1e3
+    macs = 0
+    h, w = 160, 320
+    for wt, spec in zip(weights, specs):
+        macs += wt.shape[0] * wt.shape[1] * wt.shape[2] * wt.shape[3] * h * w
+        if spec["pool"]:
+            h, w = h // 2, w // 2
+    out["cnn_c5_macs"] = macs
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fwd()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fwd()
+        graph.replay()
+        out["cnn_c5_graph_us"] = event_ms(graph.replay, steps) * 1e3
+    except Exception as exc:                                   # graph capture is optional
+        out["cnn_c5_graph_us"] = None
+        out["cnn_c5_graph_error"] = str(exc)[:200]
+    return out
+
+
 def microbench(hk):
     """Issue rates (10^12 lane-instructions/s over the whole chip) and HBM bandwidths (TB/s)."""
     import torch
@@ -237,6 +286,7 @@ def main():
         extras["conv1d_by_bits"] = by_bits
         for name in ("c3", "c4"):
             extras["conv2d_" + name] = conv2d_extra(hk, wl, name, max(5, args.steps // 2))
+        extras["latency"] = small_extras(hk, wl, max(5, args.steps // 2))
         head["x"], head["g"] = x_keep, g_keep
     line["extras"] = extras
 

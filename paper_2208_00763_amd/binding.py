@@ -42,6 +42,10 @@ class HikonvError(RuntimeError):
 
 
 def _load():
+    # PyTorch ships its own HIP runtime; it must be the one already loaded when libhikonv.so
+    # resolves libamdhip64, otherwise the process ends up with two runtimes and the library's
+    # launches see no device.  Importing torch first guarantees that.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         from .build import build
         build(force=True)

@@ -198,6 +198,75 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
     }
 }
 
+// Streaming form of the baseline: one lane produces one 16-byte aligned quad of outputs from
+// a 64-bit window of the row read straight from global memory (three dwords), and stores it
+// with one int32x4 store.  Still one v_mad_i32_i24 per low-bit product.  Needs
+// (taps + 3) containers to fit the 64-bit window; row edges take the general path above.
+template <bool A_SIGNED, int TAPS>
+__global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
+{
+    __shared__ int32_t s_g[64];
+    if (threadIdx.x < p.taps)
+        s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
+    __syncthreads();
+    const int64_t nquads = (p.out_len + 3 + 3) / 4;
+    const int64_t total_bits = p.total_bytes * 8;
+    const int c = p.c, b = p.b;
+    constexpr int taps = TAPS;
+    int32_t gk[TAPS];
+#pragma unroll
+    for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
+    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
+        const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+        if (q >= nquads) continue;
+        const int64_t row_bit0 = r * p.row_stride_bits;
+        const int a_off = (int)((r * p.out_len) & 3);
+        const int64_t o0 = 4 * q - a_off;                       // first output of this lane's aligned quad
+        const int64_t i0 = o0 + p.shift_m - (taps - 1);          // first element it reads
+        const int64_t bit = row_bit0 + i0 * c;
+        int32_t out[4] = {0, 0, 0, 0};
+        const bool interior = i0 >= 0 && i0 + taps + 3 <= p.len && o0 >= 0 && o0 + 4 <= p.out_len &&
+                              bit + 128 <= total_bits;
+        if (interior) {
+            const uint32_t *wp = p.x + (bit >> 5);
+            const uint32_t sh = (uint32_t)bit & 31u;
+            const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2];
+            const uint64_t win = ((uint64_t)funnel_shr(w2, w1, sh) << 32) | funnel_shr(w1, w0, sh);
+#pragma unroll
+            for (int t = 0; t < TAPS + 3; ++t) {
+                const int32_t v = field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int k = u + TAPS - 1 - t;
+                    if (k >= 0 && k < TAPS) out[u] = __mul24(v, gk[k]) + out[u];
+                }
+            }
+        } else {
+            for (int t = 0; t < taps + 3; ++t) {
+                const int64_t i = i0 + t;
+                int32_t v = 0;
+                if (i >= 0 && i < p.len) {
+                    const int64_t eb = row_bit0 + i * c;
+                    const uint32_t w = load_dword_safe(p.x, eb >> 5, p.total_dwords, p.total_bytes);
+                    v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int k = u + taps - 1 - t;
+                    if (k >= 0 && k < taps) out[u] = __mul24(v, s_g[k]) + out[u];
+                }
+            }
+        }
+        int32_t *yrow = p.y + r * p.out_len;
+        if (o0 >= 0 && o0 + 4 <= p.out_len) {
+            *reinterpret_cast<int4 *>(&yrow[o0]) = make_int4(out[0], out[1], out[2], out[3]);
+        } else {
+            for (int u = 0; u < 4; ++u)
+                if (o0 + u >= 0 && o0 + u < p.out_len) yrow[o0 + u] = out[u];
+        }
+    }
+}
+
 } // namespace
 
 int conv1d_tile_chunks(int N, int64_t n_blocks)
@@ -235,7 +304,19 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
     const int64_t gx = ceil_div(nquads, kThreads);
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
-    if (a_signed)
+    if ((a.taps + 3) * a.c <= 64 && a.taps <= 7) {
+#define HIKONV_UNP(T)                                                                        \
+    case T:                                                                                  \
+        if (a_signed)                                                                        \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T>), g, b, 0, stream, a);       \
+        else                                                                                 \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T>), g, b, 0, stream, a);      \
+        break;
+        switch (a.taps) {
+            HIKONV_UNP(1) HIKONV_UNP(2) HIKONV_UNP(3) HIKONV_UNP(4) HIKONV_UNP(5) HIKONV_UNP(6) HIKONV_UNP(7)
+        }
+#undef HIKONV_UNP
+    } else if (a_signed)
         hipLaunchKernelGGL((k_conv1d_unpacked<true>), g, b, 0, stream, a);
     else
         hipLaunchKernelGGL((k_conv1d_unpacked<false>), g, b, 0, stream, a);

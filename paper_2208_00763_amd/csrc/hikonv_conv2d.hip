@@ -217,6 +217,120 @@ __global__ __launch_bounds__(256) void k_conv2d_unpacked(Conv2dDirectArgs p)
         if (co0 + c < p.Co) p.y[(((int64_t)n * p.Co + co0 + c) * p.Ho + ho) * p.Wo + wo] = acc[c];
 }
 
+// Tuned form of the baseline for 3x3 kernels: the same work decomposition as the packed
+// kernel (one lane = one output pixel x 8 channels, weights of the channel tile staged in
+// LDS, the input-channel range divided among the waves of a workgroup when the layer is
+// small, next channel's activations loaded while the current one is multiplied), still one
+// v_mad_i32_i24 per low-bit product.
+constexpr int kCiStage = 64; // input channels whose weights are staged at a time (18 KB)
+
+template <bool A_SIGNED>
+__global__ __launch_bounds__(256) void k_conv2d_unpacked_3x3(Conv2dDirectArgs p, int ksplit)
+{
+    __shared__ __attribute__((aligned(16))) int32_t s_w[kCiStage * 9 * 8];
+    __shared__ int32_t s_red[3 * 8 * 64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ks = wave % ksplit;
+    const int64_t group = (int64_t)blockIdx.x * (4 / ksplit) + wave / ksplit;
+    const int64_t npix = (int64_t)p.Nimg * p.Ho * p.Wo;
+    const int64_t pix = group * 64 + lane;
+    const bool active = pix < npix;
+    const int64_t pc = active ? pix : 0;
+    const int wo = (int)(pc % p.Wo), ho = (int)((pc / p.Wo) % p.Ho), n = (int)(pc / ((int64_t)p.Wo * p.Ho));
+    const int co0 = blockIdx.y * 8;
+    // the nine tap offsets of this pixel (clamped inside the image) and their validity
+    int off[9];
+    bool ok[9];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const int ih = ho * p.stride + kh - p.pad, iw = wo * p.stride + kw - p.pad;
+            const bool v = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+            ok[kh * 3 + kw] = v;
+            off[kh * 3 + kw] = v ? ih * p.W + iw : 0;
+        }
+    const uint8_t *xn = p.x + (int64_t)n * p.C * p.H * p.W;
+    const int64_t plane = (int64_t)p.H * p.W;
+    int32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    auto fetch = [&](int32_t (&v)[9], int ci) {
+        const uint8_t *xc = xn + ci * plane;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const uint8_t byte = xc[off[t]];
+            const int32_t val = A_SIGNED ? (int32_t)(int8_t)byte : (int32_t)byte;
+            v[t] = ok[t] ? val : 0;
+        }
+    };
+    auto multiply = [&](const int32_t (&v)[9], int cl) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int4 *wv = reinterpret_cast<const int4 *>(&s_w[(cl * 9 + t) * 8]);
+            const int4 w0 = wv[0], w1 = wv[1];
+            acc[0] = __mul24(v[t], w0.x) + acc[0];
+            acc[1] = __mul24(v[t], w0.y) + acc[1];
+            acc[2] = __mul24(v[t], w0.z) + acc[2];
+            acc[3] = __mul24(v[t], w0.w) + acc[3];
+            acc[4] = __mul24(v[t], w1.x) + acc[4];
+            acc[5] = __mul24(v[t], w1.y) + acc[5];
+            acc[6] = __mul24(v[t], w1.z) + acc[6];
+            acc[7] = __mul24(v[t], w1.w) + acc[7];
+        }
+    };
+
+    for (int ci0 = 0; ci0 < p.C; ci0 += kCiStage) {
+        const int nci = p.C - ci0 < kCiStage ? p.C - ci0 : kCiStage;
+        if (ci0 > 0) __syncthreads();
+        for (int i = tid; i < nci * 72; i += 256) {
+            const int c8 = i & 7, t = (i >> 3) % 9, ci = (i >> 3) / 9;
+            int32_t v = 0;
+            if (co0 + c8 < p.Co) {
+                const uint8_t byte = p.w[((int64_t)(co0 + c8) * p.C + ci0 + ci) * 9 + t];
+                v = p.w_signed ? (int32_t)(int8_t)byte : (int32_t)byte;
+            }
+            s_w[i] = v;
+        }
+        __syncthreads();
+        // this wave's share of the staged channels
+        const int per = (nci + ksplit - 1) / ksplit;
+        const int c_begin = ks * per;
+        int c_end = c_begin + per;
+        if (c_end > nci) c_end = nci;
+        if (c_begin >= c_end) continue;
+        int32_t va[9], vb[9];
+        fetch(va, ci0 + c_begin);
+        for (int cl = c_begin; cl < c_end; cl += 2) {
+            fetch(vb, ci0 + (cl + 1 < c_end ? cl + 1 : cl));
+            multiply(va, cl);
+            if (cl + 1 >= c_end) break;
+            fetch(va, ci0 + (cl + 2 < c_end ? cl + 2 : cl + 1));
+            multiply(vb, cl + 1);
+        }
+    }
+    if (ksplit > 1) {
+        __syncthreads();
+        if (ks > 0) {
+            int32_t *dst = s_red + ((wave - wave / ksplit - 1) * 8) * 64 + lane;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) dst[c * 64] = acc[c];
+        }
+        __syncthreads();
+        if (ks > 0) return;
+        for (int k2 = 1; k2 < ksplit; ++k2) {
+            const int w2 = wave + k2;
+            const int32_t *src = s_red + ((w2 - w2 / ksplit - 1) * 8) * 64 + lane;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[c] += src[c * 64];
+        }
+    }
+    if (!active) return;
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        if (co0 + c < p.Co) p.y[(((int64_t)n * p.Co + co0 + c) * p.Ho + ho) * p.Wo + wo] = acc[c];
+}
+
 inline hipError_t grid_1d(int64_t total, dim3 *g)
 {
     const int64_t blocks = ceil_div(total, 256);
@@ -284,9 +398,22 @@ hipError_t launch_bipolar_fix(const BipolarFixArgs &a, hipStream_t stream)
 hipError_t launch_conv2d_unpacked(const Conv2dDirectArgs &a, hipStream_t stream)
 {
     if (a.Kh * a.Kw > kMaxTaps2d) return hipErrorInvalidValue;
-    const int64_t gx = ceil_div((int64_t)a.Nimg * a.Ho * a.Wo, 256);
     const int64_t gy = ceil_div(a.Co, 8);
-    if (gx <= 0 || gx > 0x7fffffffLL || gy <= 0 || gy > 65535) return hipErrorInvalidValue;
+    if (gy <= 0 || gy > 65535) return hipErrorInvalidValue;
+    if (a.Kh == 3 && a.Kw == 3) {
+        const int64_t groups = ceil_div((int64_t)a.Nimg * a.Ho * a.Wo, 64);
+        const int ksplit = groups * gy < 2048 && a.C >= 16 ? 4 : (groups * gy < 4096 && a.C >= 8 ? 2 : 1);
+        const int64_t gx3 = ceil_div(groups, 4 / ksplit);
+        if (gx3 <= 0 || gx3 > 0x7fffffffLL) return hipErrorInvalidValue;
+        dim3 g3((unsigned)gx3, (unsigned)gy);
+        if (a.a_signed)
+            hipLaunchKernelGGL((k_conv2d_unpacked_3x3<true>), g3, dim3(256), 0, stream, a, ksplit);
+        else
+            hipLaunchKernelGGL((k_conv2d_unpacked_3x3<false>), g3, dim3(256), 0, stream, a, ksplit);
+        return hipGetLastError();
+    }
+    const int64_t gx = ceil_div((int64_t)a.Nimg * a.Ho * a.Wo, 256);
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)gy);
     if (a.a_signed)
         hipLaunchKernelGGL((k_conv2d_unpacked<true>), g, dim3(256), 0, stream, a);

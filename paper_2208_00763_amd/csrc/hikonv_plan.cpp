@@ -227,14 +227,16 @@ void fill_result(hikonv_plan_t *out, const Req &r, const Cand &c, bool paper_exa
     out->paper_exact = paper_exact ? 1 : 0;
 }
 
-// Issue-slot model used only to choose M when the caller leaves it open: a wide
-// (32x32+64) multiply-accumulate costs 4 issue slots of a full-rate VALU
-// instruction, a 24-bit one costs 1; a split costs an exchange plus per-segment work.
+// Issue-slot model used only to choose M when the caller leaves it open.  Measured on
+// gfx950: v_mad_u64_u32 and v_mad_u32_u24 both issue at the full VALU rate, the layer
+// kernel spends about 1.4 issue slots per multiply-accumulate (address and LDS traffic
+// included), and a split costs an exchange (64-bit shift, two half-rate DPP moves, 64-bit
+// add) plus three instructions per field; the narrow path needs half the exchange.
 double modelled_macs_per_slot(const Req &r, const Cand &c)
 {
     const bool wide = r.L_acc > 32;
-    const double c_mul = wide ? 4.0 : 1.0;
-    const double c_split = wide ? 10.0 + 3.0 * c.n : 4.0 + 2.0 * c.n;
+    const double c_mul = 1.4;
+    const double c_split = (wide ? 8.0 : 5.0) + 3.0 * c.n;
     const double macs = (double)r.M * c.n * r.taps;
     return macs / (r.M * c.chunks * c_mul + c_split);
 }
