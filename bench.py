@@ -199,7 +199,8 @@ def microbench(hk):
         empty = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, blocks, buf), 3) for _ in range(3))
         out["valu_T_lane_instr_per_s"][name] = blocks * 256 * iters * 64 / ((full - empty) * 1e-3) / 1e12
     big = torch.zeros(2 * 1024 ** 3 // 4, dtype=torch.int32, device="cuda")
-    for name, kind in (("write", hk.UB_HBM_WRITE), ("copy_read_plus_write", hk.UB_HBM_COPY), ("read", hk.UB_HBM_READ)):
+    for name, kind in (("write", hk.UB_HBM_WRITE), ("write_nontemporal", hk.UB_HBM_WRITE_NT),
+                       ("copy_read_plus_write", hk.UB_HBM_COPY), ("read", hk.UB_HBM_READ)):
         best = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, nb, big), 5) for nb in (4096, 16384, 32768, 65536))
         out["hbm_TB_per_s"][name] = big.numel() * 4 / (best * 1e-3) / 1e12
     return out

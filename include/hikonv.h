@@ -203,6 +203,7 @@ int hikonv_epilogue(const int32_t *acc_dev, int N, int C, int H, int W, int shif
 #define HIKONV_UB_HBM_WRITE 16
 #define HIKONV_UB_HBM_COPY 17
 #define HIKONV_UB_HBM_READ 18
+#define HIKONV_UB_HBM_WRITE_NT 19 /* write with the non-temporal hint */
 int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream);
 
 /* Lane-exchange self check: out_dev[i] (64 ints) = value lane i receives from lane i-1 (lane 0: 0). */

@@ -142,8 +142,9 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
     // (a lane's N outputs are contiguous and so are the lanes', so the wave writes one dense run)
     int32_t *yrow = p.y + r * p.out_len;
     auto finish = [&](uint64_t acc, int xl) {
-        const uint64_t hi = shr_wide<ANY_SIGNED>(acc, SN);
-        const uint64_t comb = acc + lane_shr1(hi);
+        uint64_t comb = acc;
+        if (SN < 64u) // wave-uniform; a one-tap kernel whose slices fill the word has no high part
+            comb += lane_shr1(ANY_SIGNED ? (uint64_t)((int64_t)acc >> SN) : acc >> SN);
         if (lane > 0) {
             int32_t v[N];
 #pragma unroll
@@ -173,34 +174,68 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
 
     // MULTI: one aligned 64-bit window per block covers every chunk's (delayed) window
     const int span_elems = MULTI ? (p.chunks - 1) * p.Kp + N : N;
-    if (interior && (!MULTI || span_elems * c <= 64)) {
+    // Runs at a row edge stay on the streaming path as long as the buffer is a whole number
+    // of dwords: their loads use clamped dword indices (the clamped dwords only hold
+    // containers of elements outside [0, len), which the mask below removes).
+    const bool whole_dwords = (p.total_bytes & 3) == 0;
+    if ((interior || whole_dwords) && (!MULTI || span_elems * c <= 64)) {
         // all loads of the run are issued before the first one is used
         const int delay = MULTI ? (p.chunks - 1) * p.Kp : 0;          // elements the last chunk lags
-        const int64_t bit0 = row_bit0 + ((xr0 + lane - 1) * N - delay) * c; // window of chunk 0
-        const uint32_t *wp0 = p.x + (bit0 >> 5);
+        const int64_t e_lane0 = (xr0 + lane - 1) * N - delay;          // first element of chunk 0's window
+        const int64_t bit0 = row_bit0 + e_lane0 * c;
         const uint32_t sh0 = (uint32_t)bit0 & 31u;
         constexpr int kChunkStep = kChunkBlocks * N;                  // elements between chunks
         uint32_t d0[CH], d1[CH], d2[CH], shv[CH];
+        if (interior) {
+            const uint32_t *wp0 = p.x + (bit0 >> 5);
 #pragma unroll
-        for (int cc = 0; cc < CH; ++cc) {
-            const uint32_t bitc = sh0 + (uint32_t)(cc * kChunkStep * c); // relative to wp0's dword
-            const uint32_t *wp = wp0 + (bitc >> 5);
-            d0[cc] = wp[0];
-            d1[cc] = wp[1];
-            d2[cc] = MULTI ? wp[2] : 0u;
-            shv[cc] = bitc & 31u;
+            for (int cc = 0; cc < CH; ++cc) {
+                const uint32_t bitc = sh0 + (uint32_t)(cc * kChunkStep * c); // relative to wp0's dword
+                const uint32_t *wp = wp0 + (bitc >> 5);
+                d0[cc] = wp[0];
+                d1[cc] = wp[1];
+                d2[cc] = MULTI ? wp[2] : 0u;
+                shv[cc] = bitc & 31u;
+            }
+        } else {
+            const int64_t dbase = bit0 >> 5, dlast = p.total_dwords - 1;
+#pragma unroll
+            for (int cc = 0; cc < CH; ++cc) {
+                const uint32_t bitc = sh0 + (uint32_t)(cc * kChunkStep * c);
+                const int64_t d = dbase + (bitc >> 5);
+                const int64_t i0 = d < 0 ? 0 : (d > dlast ? dlast : d);
+                const int64_t i1 = d + 1 < 0 ? 0 : (d + 1 > dlast ? dlast : d + 1);
+                const int64_t i2 = d + 2 < 0 ? 0 : (d + 2 > dlast ? dlast : d + 2);
+                d0[cc] = p.x[i0];
+                d1[cc] = p.x[i1];
+                d2[cc] = MULTI ? p.x[i2] : 0u;
+                shv[cc] = bitc & 31u;
+            }
         }
+        // containers of elements outside [0, len) are cleared (zero extension of Eq. pad_f0)
+        auto keep_valid = [&](uint32_t raw, int64_t e0) {
+            int64_t lo = e0 < 0 ? -e0 : 0, hi = p.len - e0;
+            if (hi > N) hi = N;
+            if (hi <= lo) return 0u;
+            const uint32_t hi_bits = (uint32_t)(hi * c), lo_bits = (uint32_t)(lo * c);
+            const uint32_t m_hi = hi_bits >= 32 ? 0xffffffffu : ((1u << hi_bits) - 1u);
+            return raw & m_hi & ~((1u << lo_bits) - 1u);
+        };
         const uint32_t b0 = MULTI ? 0u : make_b0();
 #pragma unroll
         for (int cc = 0; cc < CH; ++cc) {
             const uint32_t w_lo = funnel_shr(d1[cc], d0[cc], shv[cc]);
+            const int64_t e_cc = e_lane0 + (int64_t)cc * kChunkStep; // first element of this 64-bit window
             uint64_t acc = bias_low;
             if (!MULTI) {
-                acc = mad_wide<ANY_SIGNED>(pack(w_lo), b0, acc);
+                const uint32_t raw = interior ? w_lo : keep_valid(w_lo, e_cc);
+                acc = mad_wide<ANY_SIGNED>(pack(raw), b0, acc);
             } else {
                 const uint64_t win = ((uint64_t)funnel_shr(d2[cc], d1[cc], shv[cc]) << 32) | w_lo;
                 for (int ch = 0; ch < p.chunks; ++ch) {
-                    const uint32_t raw = (uint32_t)(win >> ((delay - ch * p.Kp) * c));
+                    const int lag = delay - ch * p.Kp;        // elements between the window start and chunk ch
+                    uint32_t raw = (uint32_t)(win >> (lag * c));
+                    if (!interior) raw = keep_valid(raw, e_cc + lag);
                     acc = mad_wide<ANY_SIGNED>(pack(raw), s_bw[wave * 8 + ch], acc);
                 }
             }

@@ -111,6 +111,15 @@ __global__ __launch_bounds__(256) void k_ubench_write(int4 *dst, int64_t n16)
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = v;
 }
 
+__global__ __launch_bounds__(256) void k_ubench_write_nt(int4 *dst, int64_t n16)
+{
+    typedef int32_t v4i __attribute__((ext_vector_type(4)));
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const v4i v = {(int)threadIdx.x, (int)blockIdx.x, 3, 4};
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(dst) + i);
+}
+
 __global__ __launch_bounds__(256) void k_ubench_copy(const int4 *src, int4 *dst, int64_t n16)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -183,6 +192,9 @@ hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t byte
 #undef HIKONV_UB_CASE
     case HIKONV_UB_HBM_WRITE:
         hipLaunchKernelGGL(k_ubench_write, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));
+        break;
+    case HIKONV_UB_HBM_WRITE_NT:
+        hipLaunchKernelGGL(k_ubench_write_nt, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));
         break;
     case HIKONV_UB_HBM_COPY: {
         const int64_t half16 = (int64_t)(bytes / 32);
