@@ -161,3 +161,101 @@ def test_bad_requests():
         hk.hikonv_plan_ex(bits_a=8, bits_w=8, L_A=8, L_B=8, L_acc=8, mode=hk.MODE_SINGLE)
     assert e.value.code == hk.ENOPLAN
     assert hk.lib.hikonv_plan(4, 4, 0, 32, None) == hk.EINVAL
+
+
+# ---- argument checks of the device entry points (they fail before any launch) -------------
+class _Fake:
+    """Stands in for a device tensor: the checks below reject the call before it is touched."""
+    def __init__(self, addr, nbytes=1 << 20):
+        self._addr, self._n = addr, nbytes
+
+    def data_ptr(self):
+        return self._addr
+
+    def numel(self):
+        return self._n
+
+    def element_size(self):
+        return 1
+
+
+def _dnn_plan(**kw):
+    base = dict(bits_a=4, bits_w=4, a_signed=1, w_signed=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=5, taps=3)
+    base.update(kw)
+    return hk.hikonv_plan_ex(**base)
+
+
+def test_conv2d_argument_checks():
+    plan = _dnn_plan()
+    x, w, y, ws = _Fake(0x1000), _Fake(0x2000), _Fake(0x3000), _Fake(0x10000)
+    args = (hk.FMT_INT8, 1, 8, 10, 10)
+
+    def code(fn):
+        with pytest.raises(hk.HikonvError) as e:
+            fn()
+        return e.value.code
+
+    # kernel width differs from the plan's taps
+    assert code(lambda: hk.hikonv_conv2d(plan, x, *args, w, 8, 3, 5, 1, 1, ws, y, stream=0)) == hk.EINVAL
+    # padding wider than the kernel allows
+    assert code(lambda: hk.hikonv_conv2d(plan, x, *args, w, 8, 3, 3, 1, 3, ws, y, stream=0)) == hk.EUNSUPPORTED
+    # kernel larger than the padded image
+    assert code(lambda: hk.hikonv_conv2d(plan, x, hk.FMT_INT8, 1, 8, 1, 1, w, 8, 3, 3, 1, 0, ws, y, stream=0)) == hk.EINVAL
+    # workspace too small / misaligned / missing
+    assert code(lambda: hk.hikonv_conv2d(plan, x, *args, w, 8, 3, 3, 1, 1, _Fake(0x10000, 16), y, stream=0)) == hk.EWORKSPACE
+    assert code(lambda: hk.hikonv_conv2d(plan, x, *args, w, 8, 3, 3, 1, 1, _Fake(0x10004), y, stream=0)) == hk.EWORKSPACE
+    # null tensors, bad format
+    assert code(lambda: hk.hikonv_conv2d(plan, None, *args, w, 8, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
+    assert code(lambda: hk.hikonv_conv2d(plan, x, 9, 1, 8, 10, 10, w, 8, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
+    # a 1-D plan is not a layer plan
+    p1 = hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3)
+    assert code(lambda: hk.hikonv_conv2d(p1, x, *args, w, 8, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
+    # int32 overflow of the worst-case sum: 8-bit unsigned, 40000 channels of 3x3
+    p8 = _dnn_plan(bits_a=8, bits_w=8, a_signed=0, w_signed=0, M=1)
+    assert code(lambda: hk.hikonv_conv2d(p8, x, hk.FMT_INT8, 1, 40000, 10, 10, w, 8, 3, 3, 1, 1, ws, y, stream=0)) == hk.EOVERFLOW
+    # a plan edited so that its fields overflow is refused
+    bad = hk.Plan(**{**plan.as_dict(), "S": plan.S - 3})
+    assert code(lambda: hk.hikonv_conv2d(bad, x, *args, w, 8, 3, 3, 1, 1, ws, y, stream=0)) == hk.EOVERFLOW
+    # unsupported multiplier width
+    p64 = hk.Plan(**{**plan.as_dict(), "L_A": 64, "L_B": 64, "L_acc": 128})
+    assert code(lambda: hk.hikonv_conv2d(p64, x, *args, w, 8, 3, 3, 1, 1, ws, y, stream=0)) == hk.EUNSUPPORTED
+
+
+def test_workspace_and_packed_weight_sizes():
+    plan = _dnn_plan()
+    ws = hk.hikonv_conv2d_workspace_bytes(plan, 1, 64, 56, 56, 64, 3, 3, 1, 1, True)
+    ws_raw = hk.hikonv_conv2d_workspace_bytes(plan, 1, 64, 56, 56, 64, 3, 3, 1, 1, False)
+    pw = hk.hikonv_packed_weights_bytes(plan, 64, 64, 3, 3)
+    assert ws % 256 == 0 and pw % 256 == 0 and ws_raw == ws + pw
+    # packed activations: chunks * N * C * (H+2p) * (ceil((W+p)/N)+1) words
+    assert ws >= 64 * 58 * (19 + 1) * 4 and pw >= 8 * 64 * 3 * 8 * 4
+    assert hk.hikonv_conv2d_workspace_bytes(plan, 1, 64, 56, 56, 64, 3, 5, 1, 1, True) == 0   # taps differ from the plan
+    bip = hk.hikonv_plan_ex(bits_a=1, bits_w=1, bipolar=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3)
+    assert hk.hikonv_packed_weights_bytes(bip, 256, 256, 3, 3) > hk.hikonv_packed_weights_bytes(
+        hk.Plan(**{**bip.as_dict(), "bipolar": 0}), 256, 256, 3, 3)
+
+
+def test_conv1d_and_misc_argument_checks():
+    plan = hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3)
+    x, g, y = _Fake(0x1000), _Fake(0x2000), _Fake(0x3000)
+
+    def code(fn):
+        with pytest.raises(hk.HikonvError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: hk.hikonv_conv1d(plan, x, hk.FMT_INT8, 2, 100, g, 3, 5, y, stream=0)) == hk.EINVAL        # out mode
+    assert code(lambda: hk.hikonv_conv1d(plan, x, hk.FMT_INT8, -1, 100, g, 3, hk.OUT_FULL, y, stream=0)) == hk.EINVAL
+    assert code(lambda: hk.hikonv_conv1d(plan, _Fake(0x1002), hk.FMT_INT8, 2, 100, g, 3, hk.OUT_FULL, y, stream=0)) == hk.EINVAL  # x alignment
+    assert code(lambda: hk.hikonv_conv1d(plan, x, hk.FMT_INT8, 2, 100, g, 3, hk.OUT_FULL, _Fake(0x3004), stream=0)) == hk.EINVAL  # y alignment
+    bip = hk.Plan(**{**plan.as_dict(), "bipolar": 1, "bits_a": 1, "bits_w": 1})
+    assert code(lambda: hk.hikonv_conv1d(bip, x, hk.FMT_INT8, 2, 100, g, 3, hk.OUT_FULL, y, stream=0)) == hk.EUNSUPPORTED
+    narrow = hk.Plan(**{**plan.as_dict(), "L_A": 24, "L_B": 24, "L_acc": 32})
+    assert code(lambda: hk.hikonv_conv1d(narrow, x, hk.FMT_INT8, 2, 100, g, 3, hk.OUT_FULL, y, stream=0)) == hk.EUNSUPPORTED
+    assert code(lambda: hk.hikonv_compact(x, 2, 100, 9, False, y, stream=0)) == hk.EINVAL
+    assert code(lambda: hk.hikonv_compact(x, 2, 100, 4, True, y, stream=0)) == hk.EINVAL                          # bipolar needs 1 bit
+    assert code(lambda: hk.hikonv_epilogue(x, 1, 4, 8, 8, 40, 15, True, 4, hk.FMT_BITDENSE, y, stream=0)) == hk.EINVAL   # shift
+    assert code(lambda: hk.hikonv_epilogue(x, 1, 4, 8, 8, 3, 16, True, 4, hk.FMT_BITDENSE, y, stream=0)) == hk.EINVAL    # qmax > 2^bits-1
+    assert code(lambda: hk.hikonv_epilogue(x, 1, 4, 1, 8, 3, 15, True, 4, hk.FMT_BITDENSE, y, stream=0)) == hk.EINVAL    # nothing left after pooling
+    assert code(lambda: hk.hikonv_ubench(99, 1, 1, _Fake(0x1000), stream=0)) in (hk.EUNSUPPORTED, hk.EHIP)
+    assert code(lambda: hk.hikonv_conv1d_unpacked(4, 9, 0, x, hk.FMT_INT8, 2, 100, g, 3, hk.OUT_FULL, y, stream=0)) == hk.EINVAL

@@ -146,3 +146,27 @@ def test_conv1d_full_size_sweep_sampled_rows():
                 ref = oracle_conv1d(x[rows], g, hk.OUT_VALID)
                 assert np.array_equal(got, ref), (bits, signed, taps)
                 del y
+
+
+def test_conv1d_many_short_rows_and_one_long_row():
+    # more rows than a grid dimension holds; rows shorter than one packed run; one very long row
+    for bits, signed, taps in ((4, False, 3), (1, True, 7), (8, True, 3)):
+        for rows, length in ((70001, 37), (1, (1 << 22) + 5), (3, 1513 * 3)):
+            x = wl.uniform_values(wl.rng_for("t5", bits, signed, rows), (rows, length), bits, signed)
+            g = wl.uniform_values(wl.rng_for("t5g", bits, signed, taps), (taps,), bits, signed)
+            for mode in (hk.OUT_VALID, hk.OUT_FULL):
+                ref = oracle_conv1d(x, g, mode)
+                assert np.array_equal(run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_BITDENSE), ref)
+                assert np.array_equal(run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_INT8, packed=False), ref)
+
+
+def test_conv1d_int8_rows_that_do_not_fill_dwords():
+    # one value per byte, odd row length: rows start at any byte offset and the buffer ends mid-dword
+    for bits, signed in ((4, True), (7, False), (2, False)):
+        for rows, length in ((5, 1001), (3, 7), (2, 4099)):
+            x = wl.uniform_values(wl.rng_for("t6", bits, signed, rows, length), (rows, length), bits, signed)
+            g = wl.uniform_values(wl.rng_for("t6g", bits, signed), (3,), bits, signed)
+            for mode in (hk.OUT_VALID, hk.OUT_FULL):
+                ref = oracle_conv1d(x, g, mode)
+                assert np.array_equal(run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_INT8), ref)
+                assert np.array_equal(run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_INT8, packed=False), ref)

@@ -214,3 +214,29 @@ def test_cnn_forward_config5(size):
         assert np.array_equal(got, direct.conv2d(xi, wt, 1, spec["pad"])), "isolated layer %d" % i
         if spec["pool"]:
             hh, ww = hh // 2, ww // 2
+
+
+def test_conv2d_degenerate_and_strided_shapes():
+    cases = [  # n, c, h, w, co, kh, kw, stride, pad
+        (2, 3, 1, 9, 4, 1, 3, 1, 1),      # one image row
+        (1, 2, 9, 1, 3, 3, 1, 1, 0),      # one image column
+        (3, 8, 11, 12, 17, 3, 3, 2, 1),   # batch, stride 2, channels not a multiple of 8
+        (1, 1, 5, 5, 1, 3, 3, 1, 2),      # padding as wide as the kernel allows, single channels
+        (1, 40, 6, 6, 8, 3, 3, 3, 0),     # stride 3
+        (2, 9, 7, 130, 5, 3, 3, 1, 1),    # wide rows (several wave segments for short blocks)
+    ]
+    for shape in cases:
+        stride, pad, kw = shape[7], shape[8], shape[6]
+        for bits, a_s, w_s in ((4, False, True), (2, True, True), (1, False, False)):
+            x, w = _case(bits, a_s, w_s, shape, "d5")
+            ref = direct.conv2d(x, w, stride, pad)
+            for m in (2, 0):
+                plan = dnn_plan(bits, bits, a_s, w_s, kw, m, True)
+                if plan.N > 8:
+                    continue
+                assert np.array_equal(run_conv2d(plan, x, w, stride, pad, hk.FMT_BITDENSE), ref), (shape, bits, m, plan)
+        n, c, h, wd, co, kh, kw2 = shape[:7]
+        xb, wb = wl.bipolar_case(n, c, h, wd, co, kh, kw2, tag="d5")
+        plan = dnn_plan(1, 1, False, False, kw2, 0, True, bipolar=True)
+        if plan.N <= 8:
+            assert np.array_equal(run_conv2d(plan, xb, wb, stride, pad), direct.conv2d(xb, wb, stride, pad)), shape
