@@ -123,8 +123,15 @@ def conv2d_extra(hk, wl, name, steps):
 
         event_ms(run, 3)
         ms = event_ms(run, steps)
+        # algorithmic VALU work of the packed layer: one multiply-accumulate per (block, channel, term)
+        blocks = -(-(wd + 1) // plan.N)
+        lane_mads = n * co * h * blocks * c * kh * plan.chunks
         report[label] = dict(ms=ms, gops=2 * macs / ms / 1e6, plan=dict(N=plan.N, K=plan.K, S=plan.S, M=plan.M),
-                             frac_of_unpacked_valu_peak=macs / (ms * 1e-3) / VALU_LANE_RATE)
+                             frac_of_unpacked_valu_peak=macs / (ms * 1e-3) / VALU_LANE_RATE,
+                             roofline={"bound": "alu", "achieved": lane_mads / (ms * 1e-3) / 1e12,
+                                       "peak": VALU_LANE_RATE / 1e12, "unit": "T lane-instr/s",
+                                       "frac": lane_mads / (ms * 1e-3) / VALU_LANE_RATE,
+                                       "note": "packed multiply-accumulates only, whole call (input packing included)"})
 
     def run_unpacked():
         hk.hikonv_conv2d_unpacked(bits, bits, sg, x_d, n, c, h, wd, w_d, co, kh, kw, 1, 1, y)

@@ -112,13 +112,15 @@ struct SplitState {
     {
 #pragma unroll
         for (int c = 0; c < CO_T; ++c) {
-            acc_t comb;
-            if (WIDE) {
-                uint64_t hi = shr_wide<ANY_SIGNED>((uint64_t)acc[c], SN);
-                comb = (acc_t)((uint64_t)acc[c] + lane_shr1(hi));
-            } else {
-                uint32_t hi = shr_narrow<ANY_SIGNED>((uint32_t)acc[c], SN);
-                comb = (acc_t)((uint32_t)acc[c] + lane_shr1(hi));
+            acc_t comb = acc[c];
+            if (SN < (WIDE ? 64u : 32u)) { // wave-uniform; one-tap kernels that fill the word have no high part
+                if (WIDE) {
+                    const uint64_t a64 = (uint64_t)acc[c];
+                    comb = (acc_t)(a64 + lane_shr1(ANY_SIGNED ? (uint64_t)((int64_t)a64 >> SN) : a64 >> SN));
+                } else {
+                    const uint32_t a32 = (uint32_t)acc[c];
+                    comb = (acc_t)(a32 + lane_shr1(ANY_SIGNED ? (uint32_t)((int32_t)a32 >> SN) : a32 >> SN));
+                }
             }
 #pragma unroll
             for (int j = 0; j < N; ++j) out[c][j] += (int32_t)((uint32_t)(comb >> (S * j)) & fmask);
@@ -226,8 +228,8 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 {
     constexpr int U = kTermGroup;
     constexpr int CE = CO_T + (BIP ? 1 : 0); // BIP: one more accumulator collects sum a (all-ones weights)
-    // LDS: weight words of the current term tile [tile][CO_T] and the activation offsets of its
-    // terms [tile + U]; reused at the end for the slice reduction
+    // LDS: weight words of the current term tile [tile][CO_T], the activation offsets of its
+    // terms [tile + U] and (BIP) its all-ones words [tile]; reused at the end for the slice reduction
     extern __shared__ __attribute__((aligned(16))) uint32_t s_mem[];
 
     const uint32_t *__restrict__ apk = p.apk;
@@ -239,15 +241,14 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     const int64_t row_group = (int64_t)blockIdx.x * (4 / p.ksplit) + wave / p.ksplit;
     const LaneMap m = map_lane(p, row_group, lane);
     const int co0 = blockIdx.y * CO_T;
-    const uint32_t *a_lane = apk + ((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi;
+    // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
+    const uint32_t lane_byte = (uint32_t)((((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi) * 4);
     const uint32_t *w_tile = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
 
     const int tile_cap = p.terms_pad < kTermTile ? p.terms_pad : kTermTile;
     uint32_t *s_w = s_mem;                                   // [tile_cap][CO_T]
     int32_t *s_off = reinterpret_cast<int32_t *>(s_w + tile_cap * CO_T); // [tile_cap + U]
-    __shared__ uint32_t s_ones[8];                                        // all-ones B word of each chunk (BIP)
-    const uint32_t ones0 = p.ones_word0;
-    if (BIP && tid < 8) s_ones[tid] = ones_word_of_chunk(p, tid);
+    uint32_t *s_w1 = reinterpret_cast<uint32_t *>(s_off + tile_cap + U);  // [tile_cap] all-ones B words (BIP)
 
     SplitState<N, CE, ANY_SIGNED, WIDE> st;
     st.init(p.S);
@@ -282,6 +283,9 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
             }
         }
         for (int t = tid; t < tile_n + U; t += 256) s_off[t] = p.toff[tile0 + t];
+        if (BIP) // the sum-of-a accumulator multiplies by all-ones words; padding terms contribute nothing
+            for (int t = tid; t < tile_n; t += 256)
+                s_w1[t] = tile0 + t < p.terms ? ones_word_of_chunk(p, (tile0 + t) % p.chunks) : 0u;
         __syncthreads();
 
         // this wave's slice of the tile, in groups of U terms, two register buffers for the
@@ -295,7 +299,9 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
         uint32_t a0[U], a1[U];
         auto request = [&](uint32_t (&a)[U], int t) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) a[u] = a_lane[s_off[t + u]];
+            for (int u = 0; u < U; ++u) // uniform base + 32-bit lane offset: one VALU add per load
+                a[u] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(apk) +
+                                                            (uint32_t)(lane_byte + ((uint32_t)s_off[t + u] << 2)));
         };
         auto multiply = [&](const uint32_t (&a)[U], int t) {
 #pragma unroll
@@ -314,8 +320,7 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 #pragma unroll
                     for (int c = 0; c < CO_T; ++c) w[c] = s_w[(t + u) * CO_T + c];
                 }
-                if (BIP) // padding terms beyond the real ones contribute nothing
-                    w[CO_T] = tile0 + t + u < p.terms ? (p.chunks == 1 ? ones0 : s_ones[(tile0 + t + u) % p.chunks]) : 0u;
+                if (BIP) w[CO_T] = s_w1[t + u];
 #pragma unroll
                 for (int c = 0; c < CE; ++c) st.mad(c, a[u], w[c]);
             }
@@ -394,7 +399,7 @@ inline size_t conv2d_pipe_lds(const Conv2dArgs &a, int co_tile, int n)
 {
     const int ce = co_tile + (a.fused_bipolar ? 1 : 0);
     const size_t tile_cap = a.terms_pad < kTermTile ? a.terms_pad : kTermTile;
-    const size_t stage = (tile_cap * co_tile + tile_cap + kTermGroup) * 4;
+    const size_t stage = (tile_cap * co_tile + tile_cap + kTermGroup + (a.fused_bipolar ? tile_cap : 0)) * 4;
     const size_t reduce = a.ksplit > 1 ? (size_t)4 * ce * n * 64 * 4 : 0;
     return stage > reduce ? stage : reduce;
 }
