@@ -135,6 +135,29 @@ int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, const void *x
                            int32_t *y_dev, void *stream);
 
 /*
+ * hikonv_conv1d_requant -- the same convolution with the activation and the
+ * requantisation of the next operator fused into the packed kernel, and the
+ * result kept compressed (Section "Single convolver architecture": low-bit
+ * features stay packed at run time; requantisation rule as in hikonv_epilogue):
+ *   q[r][o] = min(qmax, max(y[r][o], 0) >> shift),  0 <= qmax < 2^out_bits.
+ * q_dev: [rows] bit-dense rows of out_len values of out_bits bits,
+ * hikonv_bitdense_row_bytes(out_len, out_bits) bytes each, 16-byte aligned;
+ * bits beyond out_len in a row are written as 0.  Nothing else is written.
+ * Plans with N <= 12 whose N containers fit 32 bits run the streaming kernel;
+ * other plans run a slow general kernel; N > 32 or more than 8 chunks give
+ * HIKONV_EUNSUPPORTED.
+ */
+int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows,
+                          int64_t len, const void *g_dev, int taps, int out_mode, int shift, int qmax,
+                          int out_bits, void *q_dev, void *stream);
+
+/* Baseline for hikonv_conv1d_requant: one v_mad_i32_i24 per low-bit product, same output. */
+int hikonv_conv1d_requant_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev,
+                                   int x_format, int64_t rows, int64_t len, const void *g_dev,
+                                   int taps, int out_mode, int shift, int qmax, int out_bits,
+                                   void *q_dev, void *stream);
+
+/*
  * Weight pre-packing (Section "Basic HiKonv Operations": weights can be packed
  * offline).  For a layer W[Co][C][Kh][Kw] (one value per byte) builds, per
  * (co, ci, kh, chunk), the word B = sum_k g[k] 2^(S k) of the reversed kernel

@@ -64,6 +64,8 @@ SIGNATURES = {
     "hikonv_compact": (_i, [_vp, _i64, _i64, _i, _i, _vp, _vp]),
     "hikonv_conv1d": (_i, [_pp, _vp, _i, _i64, _i64, _vp, _i, _i, _vp, _vp]),
     "hikonv_conv1d_unpacked": (_i, [_i, _i, _i, _vp, _i, _i64, _i64, _vp, _i, _i, _vp, _vp]),
+    "hikonv_conv1d_requant": (_i, [_pp, _vp, _i, _i64, _i64, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hikonv_conv1d_requant_unpacked": (_i, [_i, _i, _i, _vp, _i, _i64, _i64, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
     "hikonv_packed_weights_bytes": (_sz, [_pp, _i, _i, _i, _i]),
     "hikonv_pack_weights": (_i, [_pp, _vp, _i, _i, _i, _i, _vp, _vp]),
     "hikonv_conv2d_workspace_bytes": (_sz, [_pp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i]),
@@ -142,6 +144,18 @@ def hikonv_conv1d_unpacked(bits_a, bits_w, signedness_flags, x, x_format, rows, 
                            stream=None):
     _check(lib.hikonv_conv1d_unpacked(bits_a, bits_w, signedness_flags, _ptr(x), x_format, rows, length, _ptr(g),
                                       taps, out_mode, _ptr(y), _stream(stream)), "hikonv_conv1d_unpacked")
+
+
+def hikonv_conv1d_requant(plan, x, x_format, rows, length, g, taps, out_mode, shift, qmax, out_bits, q, stream=None):
+    _check(lib.hikonv_conv1d_requant(C.byref(plan), _ptr(x), x_format, rows, length, _ptr(g), taps, out_mode, shift,
+                                     qmax, out_bits, _ptr(q), _stream(stream)), "hikonv_conv1d_requant")
+
+
+def hikonv_conv1d_requant_unpacked(bits_a, bits_w, signedness_flags, x, x_format, rows, length, g, taps, out_mode,
+                                   shift, qmax, out_bits, q, stream=None):
+    _check(lib.hikonv_conv1d_requant_unpacked(bits_a, bits_w, signedness_flags, _ptr(x), x_format, rows, length,
+                                              _ptr(g), taps, out_mode, shift, qmax, out_bits, _ptr(q),
+                                              _stream(stream)), "hikonv_conv1d_requant_unpacked")
 
 
 def hikonv_packed_weights_bytes(plan, co, c, kh, kw):

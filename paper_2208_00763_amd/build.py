@@ -13,6 +13,7 @@ SOURCES = [
     "hikonv_api.hip",
     "hikonv_conv1d.hip",
     "hikonv_conv1d_fast.hip",
+    "hikonv_conv1d_requant.hip",
     "hikonv_conv2d.hip",
     "hikonv_conv2d_wide.hip",
     "hikonv_conv2d_narrow.hip",

@@ -338,6 +338,68 @@ extern "C" int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, co
     return hip_result(launch_conv1d_unpacked(a, (signedness & HIKONV_A_SIGNED) != 0, static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+
+// Output side of the requantising 1-D entry points.
+int requant_common(int shift, int qmax, int out_bits, void *q_dev, Conv1dArgs *a)
+{
+    const int c_out = container_bits(out_bits);
+    if (c_out == 0 || shift < 0 || shift > 31 || qmax < 0 || qmax > (1 << out_bits) - 1) return HIKONV_EINVAL;
+    a->rq_out = static_cast<uint32_t *>(q_dev);
+    a->rq_row_dwords = hikonv_bitdense_row_bytes(a->out_len, out_bits) / 4;
+    a->rq_shift = shift;
+    a->rq_qmax = qmax;
+    a->rq_c_out = c_out;
+    a->y = nullptr;
+    return HIKONV_OK;
+}
+
+} // namespace
+
+extern "C" int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows,
+                                     int64_t len, const void *g_dev, int taps, int out_mode, int shift, int qmax,
+                                     int out_bits, void *q_dev, void *stream)
+{
+    if (!plan) return HIKONV_EINVAL;
+    if (plan->mode != HIKONV_MODE_CONV1D || plan->taps != taps) return HIKONV_EINVAL;
+    if (plan->bipolar) return HIKONV_EUNSUPPORTED;
+    if (plan->L_A != 32 || plan->L_B != 32 || (plan->L_acc != 64 && plan->L_acc != 0)) return HIKONV_EUNSUPPORTED;
+    if (plan->N < 1 || plan->K < 1 || plan->S < 1 || plan->S > 31 || plan->chunks < 1) return HIKONV_EUNSUPPORTED;
+    if (plan->chunks != (taps + plan->K - 1) / plan->K) return HIKONV_EINVAL;
+    if (hikonv_plan_check(plan) != HIKONV_OK) return HIKONV_EOVERFLOW;
+    Conv1dArgs a = {};
+    int rc = conv1d_common(plan->bits_a, plan->a_signed, plan->w_signed, x_dev, x_format, rows, len, g_dev, taps,
+                           out_mode, static_cast<int32_t *>(q_dev), &a);
+    if (rc != HIKONV_OK) return rc == 1 ? HIKONV_OK : rc;
+    rc = requant_common(shift, qmax, out_bits, q_dev, &a);
+    if (rc != HIKONV_OK) return rc;
+    a.N = plan->N;
+    a.Kp = plan->K;
+    a.S = plan->S;
+    a.chunks = plan->chunks;
+    if (a.N > 32 || a.chunks > 8) return HIKONV_EUNSUPPORTED;
+    a.rq_run_outputs = conv1d_requant_run_outputs(a.N, a.c, a.rq_c_out);
+    if (a.rq_run_outputs <= 0) return HIKONV_EUNSUPPORTED;
+    a.tiles_per_row = ceil_div(a.out_len, a.rq_run_outputs);
+    const bool any_signed = plan->a_signed || plan->w_signed;
+    return hip_result(launch_conv1d_requant(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int hikonv_conv1d_requant_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int x_format,
+                                              int64_t rows, int64_t len, const void *g_dev, int taps, int out_mode,
+                                              int shift, int qmax, int out_bits, void *q_dev, void *stream)
+{
+    if (bits_w < 1 || bits_w > 8 || signedness < 0 || signedness > 3) return HIKONV_EINVAL;
+    Conv1dArgs a = {};
+    int rc = conv1d_common(bits_a, signedness & HIKONV_A_SIGNED, (signedness & HIKONV_W_SIGNED) ? 1 : 0, x_dev,
+                           x_format, rows, len, g_dev, taps, out_mode, static_cast<int32_t *>(q_dev), &a);
+    if (rc != HIKONV_OK) return rc == 1 ? HIKONV_OK : rc;
+    rc = requant_common(shift, qmax, out_bits, q_dev, &a);
+    if (rc != HIKONV_OK) return rc;
+    return hip_result(
+        launch_conv1d_requant_unpacked(a, (signedness & HIKONV_A_SIGNED) != 0, static_cast<hipStream_t>(stream)));
+}
+
 extern "C" size_t hikonv_packed_weights_bytes(const hikonv_plan_t *plan, int Co, int C, int Kh, int Kw)
 {
     if (!plan || Co < 1 || C < 1 || Kh < 1 || Kw < 1 || plan->chunks < 1) return 0;

@@ -1,0 +1,490 @@
+// 1-D convolution with the outputs requantised in the kernel and written bit-dense
+// (Section "Single convolver architecture": quantised feature data can be kept compressed at
+// run time): q = min(qmax, max(y, 0) >> shift) in out_bits-bit containers.  With 4 bytes per
+// output gone the path is bound by the integer VALUs instead of by HBM writes.
+//
+// k_conv1d_requant: the packed path (Theorem 2 with Theorem 1 blocks).  A wave owns a run of
+// whole output dwords; it computes the CH x 63 packed blocks that cover them (one block per
+// lane and chunk, lane 0 recomputing the block before the chunk), exactly as the streaming
+// int32 kernel does, clamps and shifts every field, stages the values in its LDS run and
+// packs `32/c_out` of them into each output dword.  Blocks that straddle a run boundary are
+// computed by both neighbouring waves, so no two waves ever write the same dword.
+// k_conv1d_requant_unpacked: the baseline, one v_mad_i32_i24 per low-bit product; one lane
+// produces one output dword from a 64-bit window of the row.
+#include "hikonv_device.h"
+#include "hikonv_launch.h"
+
+namespace hikonv {
+namespace {
+
+constexpr int kWavesPerGroup = 4;
+constexpr int kChunkBlocks = 63;
+
+__host__ __device__ constexpr int rq_chunks(int n) { return 24 / n > 0 ? 24 / n : 1; }
+__host__ __device__ constexpr int rq_stage_dwords(int n) { return ((rq_chunks(n) * kChunkBlocks * n + 4 + 3) / 4) * 4; }
+
+__device__ __forceinline__ uint32_t load_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
+                                                       int64_t total_bytes)
+{
+    if (d < 0) return 0;
+    if (d < total_dwords) return x[d];
+    uint32_t v = 0;
+    const uint8_t *xb = reinterpret_cast<const uint8_t *>(x);
+    for (int t = 0; t < 4; ++t) {
+        int64_t byte = d * 4 + t;
+        if (byte < total_bytes) v |= (uint32_t)xb[byte] << (8 * t);
+    }
+    return v;
+}
+
+template <int N, bool A_SIGNED, bool ANY_SIGNED, bool MULTI>
+__global__ __launch_bounds__(256) void k_conv1d_requant(Conv1dArgs p)
+{
+    constexpr int CH = rq_chunks(N);
+    constexpr int STAGE = rq_stage_dwords(N);
+    __shared__ int32_t s_out[kWavesPerGroup * STAGE];
+    __shared__ uint32_t s_bw[kWavesPerGroup * 8];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t run = (int64_t)blockIdx.x * kWavesPerGroup + wave;
+    if (run >= p.rows * p.tiles_per_row) return; // wave-uniform
+    const int64_t r = run / p.tiles_per_row;
+    const int64_t o_first = (run - r * p.tiles_per_row) * p.rq_run_outputs; // first output of the run (dword aligned)
+    const int64_t m_first = o_first + p.shift_m;                             // its index in the full convolution
+    const int64_t xr0 = m_first / N;                                         // first block that is needed
+    const int head = (int)(m_first - xr0 * N);                               // outputs of that block before o_first
+    int32_t *stage = s_out + wave * STAGE;
+
+    const int S = p.S, c = p.c, b = p.b;
+    const uint32_t fmask = (1u << S) - 1u;
+    const uint32_t SN = (uint32_t)(S * N);
+    uint64_t bias_low = 0;
+    int32_t bias_f = 0;
+    if (ANY_SIGNED) {
+#pragma unroll
+        for (int m = 0; m < N; ++m) bias_low += 1ull << (S * m + S - 1);
+        bias_f = 1 << (S - 1);
+    }
+
+    // B words (Eq. inpack): lane t holds tap t shifted to its slice, chunk sums by lane reads
+    const uint8_t g_byte = p.g[lane < p.taps ? lane : p.taps - 1];
+    auto tap_word = [&]() {
+        int32_t gv = p.w_signed ? (int32_t)(int8_t)g_byte : (int32_t)g_byte;
+        return lane < p.taps ? (uint32_t)gv << (S * (lane % p.Kp)) : 0u;
+    };
+
+    const int64_t row_bit0 = r * p.row_stride_bits;
+    const int64_t total_bits = p.total_bytes * 8;
+    const int delay = MULTI ? (p.chunks - 1) * p.Kp : 0;
+    const int64_t e_min = (xr0 - 1) * N - delay;
+    const int64_t e_end = (xr0 + CH * kChunkBlocks) * N;
+    const bool interior = e_min >= 0 && e_end <= p.len && row_bit0 + e_end * c + 96 <= total_bits;
+    const bool fits64 = !MULTI || (delay + N) * c <= 64; // one 64-bit window holds every chunk's window
+
+    // all window loads of the run first (three dwords cover every chunk's delayed window)
+    const int64_t e_lane0 = (xr0 + lane - 1) * N - delay;
+    const int64_t bit0 = row_bit0 + e_lane0 * c;
+    const uint32_t sh0 = (uint32_t)bit0 & 31u;
+    constexpr int kChunkStep = kChunkBlocks * N;
+    uint32_t d0[CH], d1[CH], d2[CH], shv[CH];
+    if (interior) {
+        const uint32_t *wp0 = p.x + (bit0 >> 5);
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            const uint32_t bitc = sh0 + (uint32_t)(cc * kChunkStep * c);
+            const uint32_t *wp = wp0 + (bitc >> 5);
+            d0[cc] = wp[0];
+            d1[cc] = wp[1];
+            d2[cc] = MULTI ? wp[2] : 0u;
+            shv[cc] = bitc & 31u;
+        }
+    } else {
+        const int64_t dbase = bit0 >> 5;
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            const uint32_t bitc = sh0 + (uint32_t)(cc * kChunkStep * c);
+            const int64_t d = dbase + (bitc >> 5);
+            d0[cc] = load_dword_checked(p.x, d, p.total_dwords, p.total_bytes);
+            d1[cc] = load_dword_checked(p.x, d + 1, p.total_dwords, p.total_bytes);
+            d2[cc] = MULTI ? load_dword_checked(p.x, d + 2, p.total_dwords, p.total_bytes) : 0u;
+            shv[cc] = bitc & 31u;
+        }
+    }
+    auto keep_valid = [&](uint32_t raw, int64_t e0) { // zero extension of Eq. pad_f0
+        int64_t lo = e0 < 0 ? -e0 : 0, hi = p.len - e0;
+        if (hi > N) hi = N;
+        if (hi <= lo) return 0u;
+        const uint32_t hi_bits = (uint32_t)(hi * c), lo_bits = (uint32_t)(lo * c);
+        const uint32_t m_hi = hi_bits >= 32 ? 0xffffffffu : ((1u << hi_bits) - 1u);
+        return raw & m_hi & ~((1u << lo_bits) - 1u);
+    };
+    auto pack = [&](uint32_t raw) {
+        uint32_t a = 0;
+#pragma unroll
+        for (int n = 0; n < N; ++n) a += (uint32_t)field<A_SIGNED>(raw, (uint32_t)(n * c), (uint32_t)b) << (S * n);
+        return a;
+    };
+
+    const uint32_t my_tap = tap_word();
+    uint32_t b0 = 0;
+    if (!MULTI) {
+        for (int k = 0; k < p.taps; ++k) b0 += __builtin_amdgcn_readlane(my_tap, k);
+    } else {
+        for (int ch = 0; ch < p.chunks; ++ch) {
+            uint32_t bw = 0;
+            for (int k = 0; k < p.Kp; ++k) {
+                int t = ch * p.Kp + k;
+                if (t < p.taps) bw += __builtin_amdgcn_readlane(my_tap, t);
+            }
+            if (lane == 0) s_bw[wave * 8 + ch] = bw;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+#pragma unroll
+    for (int cc = 0; cc < CH; ++cc) {
+        const uint32_t w_lo = funnel_shr(d1[cc], d0[cc], shv[cc]);
+        const int64_t e_cc = e_lane0 + (int64_t)cc * kChunkStep;
+        uint64_t acc = bias_low;
+        if (!MULTI) {
+            acc = mad_wide<ANY_SIGNED>(pack(interior ? w_lo : keep_valid(w_lo, e_cc)), b0, acc);
+        } else {
+            const uint64_t win = ((uint64_t)funnel_shr(d2[cc], d1[cc], shv[cc]) << 32) | w_lo;
+            for (int ch = 0; ch < p.chunks; ++ch) {
+                const int lag = delay - ch * p.Kp;
+                uint32_t raw;
+                if (fits64) {
+                    raw = (uint32_t)(win >> (lag * c));
+                    if (!interior) raw = keep_valid(raw, e_cc + lag);
+                } else { // rare: the delayed windows of a block span more than 64 bits
+                    const int64_t bit = row_bit0 + (e_cc + lag) * c;
+                    const int64_t d = bit >> 5;
+                    raw = funnel_shr(load_dword_checked(p.x, d + 1, p.total_dwords, p.total_bytes),
+                                     load_dword_checked(p.x, d, p.total_dwords, p.total_bytes), (uint32_t)bit & 31u);
+                    raw = keep_valid(raw, e_cc + lag);
+                }
+                acc = mad_wide<ANY_SIGNED>(pack(raw), s_bw[wave * 8 + ch], acc);
+            }
+        }
+        uint64_t comb = acc;
+        if (SN < 64u) comb += lane_shr1(ANY_SIGNED ? (uint64_t)((int64_t)acc >> SN) : acc >> SN);
+        if (lane > 0) {
+            int32_t *dst = stage + (cc * kChunkBlocks + lane - 1) * N;
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                int32_t y = (int32_t)((uint32_t)(comb >> (S * j)) & fmask) - bias_f;
+                y = y < 0 ? 0 : y;              // ReLU
+                y >>= p.rq_shift;
+                dst[j] = y > p.rq_qmax ? p.rq_qmax : y;
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    // pack the run's values into output dwords: dword k holds outputs o_first + k*per .. +per-1
+    const int per = 32 / p.rq_c_out;
+    int64_t n_out = p.out_len - o_first;
+    if (n_out > p.rq_run_outputs) n_out = p.rq_run_outputs;
+    const int n_dwords = (int)((n_out + per - 1) / per);
+    uint32_t *qrow = p.rq_out + r * p.rq_row_dwords + o_first / per;
+#pragma unroll 1
+    for (int k = lane; k < n_dwords; k += 64) {
+        uint32_t word = 0;
+        const int s0 = head + k * per;
+        for (int t = 0; t < per; ++t)
+            if ((int64_t)k * per + t < n_out) word |= (uint32_t)stage[s0 + t] << (t * p.rq_c_out);
+        qrow[k] = word;
+    }
+}
+
+// Plans outside the streaming kernel's domain (more than 12 slices per word, or a block's
+// containers wider than one dword): run-time N, one checked load per element, one chunk of 63
+// blocks per wave.  Same run partition and output packing as above.
+constexpr int kAnyMaxN = 32;
+constexpr int kAnyStage = kChunkBlocks * kAnyMaxN;
+
+template <bool ANY_SIGNED>
+__global__ __launch_bounds__(256) void k_conv1d_requant_any(Conv1dArgs p, int a_signed)
+{
+    __shared__ int32_t s_out[kWavesPerGroup * kAnyStage];
+    __shared__ uint32_t s_bw[kWavesPerGroup * 8];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t run = (int64_t)blockIdx.x * kWavesPerGroup + wave;
+    if (run >= p.rows * p.tiles_per_row) return; // wave-uniform
+    const int N = p.N, S = p.S, c = p.c, b = p.b;
+    const int64_t r = run / p.tiles_per_row;
+    const int64_t o_first = (run - r * p.tiles_per_row) * p.rq_run_outputs;
+    const int64_t m_first = o_first + p.shift_m;
+    const int64_t xr0 = m_first / N;
+    const int head = (int)(m_first - xr0 * N);
+    int32_t *stage = s_out + wave * kAnyStage;
+    const uint32_t fmask = (1u << S) - 1u;
+    const uint32_t SN = (uint32_t)(S * N);
+    uint64_t bias_low = 0;
+    int32_t bias_f = 0;
+    if (ANY_SIGNED) {
+        for (int m = 0; m < N; ++m) bias_low += 1ull << (S * m + S - 1);
+        bias_f = 1 << (S - 1);
+    }
+    const uint8_t g_byte = p.g[lane < p.taps ? lane : p.taps - 1];
+    const int32_t gv = p.w_signed ? (int32_t)(int8_t)g_byte : (int32_t)g_byte;
+    const uint32_t my_tap = lane < p.taps ? (uint32_t)gv << (S * (lane % p.Kp)) : 0u;
+    for (int ch = 0; ch < p.chunks; ++ch) {
+        uint32_t bw = 0;
+        for (int k = 0; k < p.Kp; ++k) {
+            int t = ch * p.Kp + k;
+            if (t < p.taps) bw += __builtin_amdgcn_readlane(my_tap, t);
+        }
+        if (lane == 0) s_bw[wave * 8 + ch] = bw;
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    const int64_t row_bit0 = r * p.row_stride_bits;
+    const int64_t X = xr0 + lane - 1; // this lane's block; lane 0 only supplies the overlap
+    uint64_t acc = bias_low;
+    for (int ch = 0; ch < p.chunks; ++ch) {
+        const int64_t e0 = X * N - (int64_t)ch * p.Kp;
+        uint32_t a = 0;
+        for (int n = 0; n < N; ++n) {
+            const int64_t e = e0 + n;
+            if (e < 0 || e >= p.len) continue;
+            const int64_t eb = row_bit0 + e * c;
+            const uint32_t w = load_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
+            const int32_t v = a_signed ? field<true>(w, (uint32_t)(eb & 31), (uint32_t)b)
+                                       : field<false>(w, (uint32_t)(eb & 31), (uint32_t)b);
+            a += (uint32_t)v << (S * n);
+        }
+        acc = mad_wide<ANY_SIGNED>(a, s_bw[wave * 8 + ch], acc);
+    }
+    uint64_t comb = acc;
+    if (SN < 64u) comb += lane_shr1(ANY_SIGNED ? (uint64_t)((int64_t)acc >> SN) : acc >> SN);
+    if (lane > 0) {
+        int32_t *dst = stage + (lane - 1) * N;
+        for (int j = 0; j < N; ++j) {
+            int32_t y = (int32_t)((uint32_t)(comb >> (S * j)) & fmask) - bias_f;
+            y = y < 0 ? 0 : y;
+            y >>= p.rq_shift;
+            dst[j] = y > p.rq_qmax ? p.rq_qmax : y;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const int per = 32 / p.rq_c_out;
+    int64_t n_out = p.out_len - o_first;
+    if (n_out > p.rq_run_outputs) n_out = p.rq_run_outputs;
+    const int n_dwords = (int)((n_out + per - 1) / per);
+    uint32_t *qrow = p.rq_out + r * p.rq_row_dwords + o_first / per;
+    for (int k = lane; k < n_dwords; k += 64) {
+        uint32_t word = 0;
+        const int s0 = head + k * per;
+        for (int t = 0; t < per; ++t)
+            if ((int64_t)k * per + t < n_out) word |= (uint32_t)stage[s0 + t] << (t * p.rq_c_out);
+        qrow[k] = word;
+    }
+}
+
+// Baseline with the same output format: one lane = one output dword (PER values).
+template <bool A_SIGNED, int TAPS, int PER>
+__global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
+{
+    __shared__ int32_t s_g[64];
+    if (threadIdx.x < p.taps)
+        s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
+    __syncthreads();
+    int32_t gk[TAPS];
+#pragma unroll
+    for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
+    const int64_t total_bits = p.total_bytes * 8;
+    const int c = p.c, b = p.b;
+    const int64_t row_out_dwords = (p.out_len + PER - 1) / PER;
+    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
+        const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (k >= row_out_dwords) continue;
+        const int64_t row_bit0 = r * p.row_stride_bits;
+        const int64_t o0 = k * PER;
+        const int64_t i0 = o0 + p.shift_m - (TAPS - 1); // first element read
+        const int64_t bit = row_bit0 + i0 * c;
+        int32_t out[PER];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) out[u] = 0;
+        const bool interior = i0 >= 0 && i0 + TAPS + PER - 1 <= p.len && bit + 128 <= total_bits;
+        if (interior) {
+            const uint32_t *wp = p.x + (bit >> 5);
+            const uint32_t sh = (uint32_t)bit & 31u;
+            const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2];
+            const uint64_t win = ((uint64_t)funnel_shr(w2, w1, sh) << 32) | funnel_shr(w1, w0, sh);
+#pragma unroll
+            for (int t = 0; t < TAPS + PER - 1; ++t) {
+                const int32_t v = field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b);
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    const int kk = u + TAPS - 1 - t;
+                    if (kk >= 0 && kk < TAPS) out[u] = __mul24(v, gk[kk]) + out[u];
+                }
+            }
+        } else {
+#pragma unroll 1
+            for (int t = 0; t < TAPS + PER - 1; ++t) {
+                const int64_t i = i0 + t;
+                int32_t v = 0;
+                if (i >= 0 && i < p.len) {
+                    const int64_t eb = row_bit0 + i * c;
+                    const uint32_t w = load_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
+                    v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
+                }
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    const int kk = u + TAPS - 1 - t;
+                    if (kk >= 0 && kk < TAPS) out[u] = __mul24(v, gk[kk]) + out[u];
+                }
+            }
+        }
+        uint32_t word = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            int32_t y = out[u] < 0 ? 0 : out[u];
+            y >>= p.rq_shift;
+            y = y > p.rq_qmax ? p.rq_qmax : y;
+            if (o0 + u < p.out_len) word |= (uint32_t)y << (u * (32 / PER));
+        }
+        p.rq_out[r * p.rq_row_dwords + k] = word;
+    }
+}
+
+// Any taps / widths: one lane = one output dword, one checked load per element.
+template <bool A_SIGNED>
+__global__ __launch_bounds__(256) void k_conv1d_requant_unpacked_any(Conv1dArgs p)
+{
+    __shared__ int32_t s_g[64];
+    if (threadIdx.x < p.taps)
+        s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
+    __syncthreads();
+    const int per = 32 / p.rq_c_out;
+    const int64_t row_out_dwords = (p.out_len + per - 1) / per;
+    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
+        const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (k >= row_out_dwords) continue;
+        const int64_t row_bit0 = r * p.row_stride_bits;
+        uint32_t word = 0;
+        for (int u = 0; u < per; ++u) {
+            const int64_t o = k * per + u;
+            if (o >= p.out_len) break;
+            int32_t acc = 0;
+            for (int kk = 0; kk < p.taps; ++kk) {
+                const int64_t i = o + p.shift_m - kk;
+                if (i < 0 || i >= p.len) continue;
+                const int64_t eb = row_bit0 + i * p.c;
+                const uint32_t w = load_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
+                acc += field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)p.b) * s_g[kk];
+            }
+            acc = acc < 0 ? 0 : acc;
+            acc >>= p.rq_shift;
+            acc = acc > p.rq_qmax ? p.rq_qmax : acc;
+            word |= (uint32_t)acc << (u * p.rq_c_out);
+        }
+        p.rq_out[r * p.rq_row_dwords + k] = word;
+    }
+}
+
+template <int N>
+hipError_t launch_rq_n(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+{
+    const bool multi = a.chunks > 1;
+#define HIKONV_LAUNCH(AS, ANY, MU) hipLaunchKernelGGL((k_conv1d_requant<N, AS, ANY, MU>), g, dim3(256), 0, stream, a)
+    if (a_signed) {
+        if (multi) HIKONV_LAUNCH(true, true, true); else HIKONV_LAUNCH(true, true, false);
+    } else if (any_signed) {
+        if (multi) HIKONV_LAUNCH(false, true, true); else HIKONV_LAUNCH(false, true, false);
+    } else {
+        if (multi) HIKONV_LAUNCH(false, false, true); else HIKONV_LAUNCH(false, false, false);
+    }
+#undef HIKONV_LAUNCH
+    return hipGetLastError();
+}
+
+template <int TAPS>
+hipError_t launch_rq_unpacked_t(const Conv1dArgs &a, bool a_signed, dim3 g, hipStream_t stream)
+{
+#define HIKONV_LAUNCH(PER)                                                                                       \
+    case PER:                                                                                                    \
+        if (a_signed)                                                                                            \
+            hipLaunchKernelGGL((k_conv1d_requant_unpacked<true, TAPS, PER>), g, dim3(256), 0, stream, a);        \
+        else                                                                                                     \
+            hipLaunchKernelGGL((k_conv1d_requant_unpacked<false, TAPS, PER>), g, dim3(256), 0, stream, a);       \
+        break;
+    switch (32 / a.rq_c_out) {
+        HIKONV_LAUNCH(4) HIKONV_LAUNCH(8) HIKONV_LAUNCH(16) HIKONV_LAUNCH(32)
+    default: return hipErrorInvalidValue;
+    }
+#undef HIKONV_LAUNCH
+    return hipGetLastError();
+}
+
+} // namespace
+
+// outputs per wave run of the packed requantising kernel: whole output dwords that CH*63 blocks cover
+bool conv1d_requant_streaming(int N, int c) { return N >= 1 && N <= 12 && N * c <= 32; }
+
+int64_t conv1d_requant_run_outputs(int N, int c, int c_out)
+{
+    const int per = 32 / c_out;
+    if (N < 1 || N > kAnyMaxN) return 0;
+    if (!conv1d_requant_streaming(N, c)) return (int64_t)((kChunkBlocks * N - (N - 1)) / per) * per;
+    int ch = 1;
+    switch (N) {
+#define HIKONV_CASE(n) case n: ch = rq_chunks(n); break;
+        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
+        HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
+#undef HIKONV_CASE
+    default: return 0;
+    }
+    return (int64_t)((ch * kChunkBlocks * N - (N - 1)) / per) * per;
+}
+
+hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
+{
+    if (a.N < 1 || a.N > kAnyMaxN || a.chunks < 1 || a.chunks > 8) return hipErrorInvalidValue;
+    if (a.rq_run_outputs <= 0 || a.rq_run_outputs != conv1d_requant_run_outputs(a.N, a.c, a.rq_c_out))
+        return hipErrorInvalidValue;
+    const int64_t grid = ceil_div(a.tiles_per_row * a.rows, kWavesPerGroup);
+    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 g((unsigned)grid);
+    if (!conv1d_requant_streaming(a.N, a.c)) {
+        if (any_signed)
+            hipLaunchKernelGGL(k_conv1d_requant_any<true>, g, dim3(256), 0, stream, a, (int)a_signed);
+        else
+            hipLaunchKernelGGL(k_conv1d_requant_any<false>, g, dim3(256), 0, stream, a, (int)a_signed);
+        return hipGetLastError();
+    }
+    switch (a.N) {
+#define HIKONV_CASE(n) case n: return launch_rq_n<n>(a, a_signed, any_signed, g, stream);
+        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
+        HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
+#undef HIKONV_CASE
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream)
+{
+    const int per = 32 / a.rq_c_out;
+    const int64_t gx = ceil_div(ceil_div(a.out_len, per), 256);
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
+    if (a.taps > 7 || (a.taps + per - 1) * a.c > 64) {
+        if (a_signed)
+            hipLaunchKernelGGL(k_conv1d_requant_unpacked_any<true>, g, dim3(256), 0, stream, a);
+        else
+            hipLaunchKernelGGL(k_conv1d_requant_unpacked_any<false>, g, dim3(256), 0, stream, a);
+        return hipGetLastError();
+    }
+    switch (a.taps) {
+#define HIKONV_CASE(t) case t: return launch_rq_unpacked_t<t>(a, a_signed, g, stream);
+        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6) HIKONV_CASE(7)
+#undef HIKONV_CASE
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace hikonv

@@ -27,6 +27,11 @@ struct Conv1dArgs {
     int direct_store;        // streaming kernel: 1 = store from registers, 0 = through an LDS staging run
     int big_runs;            // streaming kernel: 1 = about 1500 outputs per wave run, 0 = about 750
     int32_t *y;
+    // requantising kernels: q = min(qmax, max(y, 0) >> shift) in c_out-bit containers
+    uint32_t *rq_out;        // [rows][rq_row_dwords]
+    int64_t rq_row_dwords;
+    int64_t rq_run_outputs;  // outputs per wave run (whole output dwords)
+    int rq_shift, rq_qmax, rq_c_out;
 };
 
 int conv1d_tile_chunks(int N, int64_t n_blocks);
@@ -37,6 +42,11 @@ bool conv1d_fast_applicable(const Conv1dArgs &a);
 void conv1d_fast_tuning(Conv1dArgs *a);
 int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks, bool big);
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
+// requantised bit-dense output: packed (streaming kernel for N <= 12 and N*c <= 32, a slow
+// general kernel for the other plans up to N = 32) and baseline
+int64_t conv1d_requant_run_outputs(int N, int c, int c_out);
+hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
+hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream);
 
 // ---- 2-D ---------------------------------------------------------------------------
 
