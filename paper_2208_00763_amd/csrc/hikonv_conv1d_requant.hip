@@ -21,7 +21,10 @@ constexpr int kWavesPerGroup = 4;
 constexpr int kChunkBlocks = 63;
 
 __host__ __device__ constexpr int rq_chunks(int n) { return 24 / n > 0 ? 24 / n : 1; }
-__host__ __device__ constexpr int rq_stage_dwords(int n) { return ((rq_chunks(n) * kChunkBlocks * n + 4 + 3) / 4) * 4; }
+// LDS run of a wave: slot kStagePad + s - head holds the value at full-convolution index xr0*N + s,
+// so that the first output of the run sits on a 16-byte boundary
+constexpr int kStagePad = 16;
+__host__ __device__ constexpr int rq_stage_dwords(int n) { return ((rq_chunks(n) * kChunkBlocks * n + kStagePad + 3) / 4) * 4; }
 
 __device__ __forceinline__ uint32_t load_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
                                                        int64_t total_bytes)
@@ -42,7 +45,7 @@ __global__ __launch_bounds__(256) void k_conv1d_requant(Conv1dArgs p)
 {
     constexpr int CH = rq_chunks(N);
     constexpr int STAGE = rq_stage_dwords(N);
-    __shared__ int32_t s_out[kWavesPerGroup * STAGE];
+    __shared__ __align__(16) int32_t s_out[kWavesPerGroup * STAGE];
     __shared__ uint32_t s_bw[kWavesPerGroup * 8];
 
     const int lane = threadIdx.x & 63;
@@ -57,15 +60,19 @@ __global__ __launch_bounds__(256) void k_conv1d_requant(Conv1dArgs p)
     int32_t *stage = s_out + wave * STAGE;
 
     const int S = p.S, c = p.c, b = p.b;
-    const uint32_t fmask = (1u << S) - 1u;
     const uint32_t SN = (uint32_t)(S * N);
     uint64_t bias_low = 0;
-    int32_t bias_f = 0;
     if (ANY_SIGNED) {
 #pragma unroll
         for (int m = 0; m < N; ++m) bias_low += 1ull << (S * m + S - 1);
-        bias_f = 1 << (S - 1);
     }
+    // Requantisation on the biased field F = y + 2^(S-1) (signed) or F = y (unsigned): with
+    // s = min(shift, S-1), y >> shift clamps to the same value as (F >> s) - (2^(S-1) >> s).
+    const int rsh = p.rq_shift < S - 1 ? p.rq_shift : S - 1;
+    const uint32_t rmask = (1u << (S - rsh)) - 1u;
+    const int32_t rbias = ANY_SIGNED ? (1 << (S - 1)) >> rsh : 0;
+    // unsigned fields reach 2^S - 1: a shift of S or more leaves nothing
+    const int32_t qmax = (!ANY_SIGNED && p.rq_shift >= S) ? 0 : p.rq_qmax;
 
     // B words (Eq. inpack): lane t holds tap t shifted to its slice, chunk sums by lane reads
     const uint8_t g_byte = p.g[lane < p.taps ? lane : p.taps - 1];
@@ -170,30 +177,37 @@ __global__ __launch_bounds__(256) void k_conv1d_requant(Conv1dArgs p)
         uint64_t comb = acc;
         if (SN < 64u) comb += lane_shr1(ANY_SIGNED ? (uint64_t)((int64_t)acc >> SN) : acc >> SN);
         if (lane > 0) {
-            int32_t *dst = stage + (cc * kChunkBlocks + lane - 1) * N;
+            int32_t *dst = stage + kStagePad - head + (cc * kChunkBlocks + lane - 1) * N;
 #pragma unroll
             for (int j = 0; j < N; ++j) {
-                int32_t y = (int32_t)((uint32_t)(comb >> (S * j)) & fmask) - bias_f;
-                y = y < 0 ? 0 : y;              // ReLU
-                y >>= p.rq_shift;
-                dst[j] = y > p.rq_qmax ? p.rq_qmax : y;
+                const int32_t y = (int32_t)((uint32_t)(comb >> (S * j + rsh)) & rmask) - rbias;
+                dst[j] = ANY_SIGNED ? min(max(y, 0), qmax) : (int32_t)min((uint32_t)y, (uint32_t)qmax);
             }
         }
     }
     __builtin_amdgcn_wave_barrier();
 
     // pack the run's values into output dwords: dword k holds outputs o_first + k*per .. +per-1
-    const int per = 32 / p.rq_c_out;
+    const int per = 32 / p.rq_c_out, c_out = p.rq_c_out;
     int64_t n_out = p.out_len - o_first;
     if (n_out > p.rq_run_outputs) n_out = p.rq_run_outputs;
     const int n_dwords = (int)((n_out + per - 1) / per);
     uint32_t *qrow = p.rq_out + r * p.rq_row_dwords + o_first / per;
+    const int4 *src = reinterpret_cast<const int4 *>(stage + kStagePad);
 #pragma unroll 1
     for (int k = lane; k < n_dwords; k += 64) {
         uint32_t word = 0;
-        const int s0 = head + k * per;
-        for (int t = 0; t < per; ++t)
-            if ((int64_t)k * per + t < n_out) word |= (uint32_t)stage[s0 + t] << (t * p.rq_c_out);
+        const int4 *s4 = src + k * (per >> 2);
+        for (int t4 = 0; t4 < (per >> 2); ++t4) {
+            const int4 v = s4[t4];
+            const int sh = 4 * t4 * c_out;
+            word |= (uint32_t)v.x << sh;
+            word |= (uint32_t)v.y << (sh + c_out);
+            word |= (uint32_t)v.z << (sh + 2 * c_out);
+            word |= (uint32_t)v.w << (sh + 3 * c_out);
+        }
+        const int64_t valid = n_out - (int64_t)k * per; // values past the row's end are not output
+        if (valid < per) word &= (1u << (uint32_t)(valid * c_out)) - 1u;
         qrow[k] = word;
     }
 }
@@ -284,10 +298,14 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_any(Conv1dArgs p, int a_
     }
 }
 
-// Baseline with the same output format: one lane = one output dword (PER values).
+// Baseline with the same output format: a lane produces unpacked_unroll(PER) output dwords (PER
+// values each), 256 dwords apart, from 64-bit windows of the row whose loads are all issued first.
+__host__ __device__ constexpr int unpacked_unroll(int per) { return per <= 8 ? 4 : 1; }
+
 template <bool A_SIGNED, int TAPS, int PER>
 __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
 {
+    constexpr int U = unpacked_unroll(PER);
     __shared__ int32_t s_g[64];
     if (threadIdx.x < p.taps)
         s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
@@ -298,57 +316,78 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
     const int64_t total_bits = p.total_bytes * 8;
     const int c = p.c, b = p.b;
     const int64_t row_out_dwords = (p.out_len + PER - 1) / PER;
-    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
-        const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
-        if (k >= row_out_dwords) continue;
-        const int64_t row_bit0 = r * p.row_stride_bits;
-        const int64_t o0 = k * PER;
-        const int64_t i0 = o0 + p.shift_m - (TAPS - 1); // first element read
-        const int64_t bit = row_bit0 + i0 * c;
-        int32_t out[PER];
-#pragma unroll
-        for (int u = 0; u < PER; ++u) out[u] = 0;
-        const bool interior = i0 >= 0 && i0 + TAPS + PER - 1 <= p.len && bit + 128 <= total_bits;
-        if (interior) {
-            const uint32_t *wp = p.x + (bit >> 5);
-            const uint32_t sh = (uint32_t)bit & 31u;
-            const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2];
-            const uint64_t win = ((uint64_t)funnel_shr(w2, w1, sh) << 32) | funnel_shr(w1, w0, sh);
-#pragma unroll
-            for (int t = 0; t < TAPS + PER - 1; ++t) {
-                const int32_t v = field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b);
-#pragma unroll
-                for (int u = 0; u < PER; ++u) {
-                    const int kk = u + TAPS - 1 - t;
-                    if (kk >= 0 && kk < TAPS) out[u] = __mul24(v, gk[kk]) + out[u];
-                }
-            }
-        } else {
-#pragma unroll 1
-            for (int t = 0; t < TAPS + PER - 1; ++t) {
-                const int64_t i = i0 + t;
-                int32_t v = 0;
-                if (i >= 0 && i < p.len) {
-                    const int64_t eb = row_bit0 + i * c;
-                    const uint32_t w = load_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
-                    v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
-                }
-#pragma unroll
-                for (int u = 0; u < PER; ++u) {
-                    const int kk = u + TAPS - 1 - t;
-                    if (kk >= 0 && kk < TAPS) out[u] = __mul24(v, gk[kk]) + out[u];
-                }
-            }
-        }
+    const int rsh = p.rq_shift, qmax = p.rq_qmax;
+
+    auto emit = [&](int64_t r, int64_t k, const int32_t (&out)[PER]) {
         uint32_t word = 0;
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
-            int32_t y = out[u] < 0 ? 0 : out[u];
-            y >>= p.rq_shift;
-            y = y > p.rq_qmax ? p.rq_qmax : y;
-            if (o0 + u < p.out_len) word |= (uint32_t)y << (u * (32 / PER));
+            const int32_t y = min(max(out[u], 0) >> rsh, qmax);
+            if (k * PER + u < p.out_len) word |= (uint32_t)y << (u * (32 / PER));
         }
         p.rq_out[r * p.rq_row_dwords + k] = word;
+    };
+    auto accumulate = [&](int32_t (&out)[PER], int t, int32_t v) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int kk = u + TAPS - 1 - t;
+            if (kk >= 0 && kk < TAPS) out[u] = __mul24(v, gk[kk]) + out[u];
+        }
+    };
+
+    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
+        const int64_t row_bit0 = r * p.row_stride_bits;
+        const int64_t k0 = (int64_t)blockIdx.x * (256 * U) + threadIdx.x;
+        // first element read for dword k: k*PER + shift_m - (TAPS-1)
+        const int64_t i_first = k0 * PER + p.shift_m - (TAPS - 1);
+        const int64_t i_last = (k0 + (U - 1) * 256) * PER + p.shift_m - (TAPS - 1);
+        const bool fast = k0 + (U - 1) * 256 < row_out_dwords && i_first >= 0 && i_last + TAPS + PER - 1 <= p.len &&
+                          row_bit0 + i_last * c + 128 <= total_bits;
+        if (fast) {
+            uint32_t w0[U], w1[U], w2[U], sh[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int64_t bit = row_bit0 + (i_first + (int64_t)q * 256 * PER) * c;
+                const uint32_t *wp = p.x + (bit >> 5);
+                w0[q] = wp[0];
+                w1[q] = wp[1];
+                w2[q] = wp[2];
+                sh[q] = (uint32_t)bit & 31u;
+            }
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const uint64_t win = ((uint64_t)funnel_shr(w2[q], w1[q], sh[q]) << 32) | funnel_shr(w1[q], w0[q], sh[q]);
+                int32_t out[PER];
+#pragma unroll
+                for (int u = 0; u < PER; ++u) out[u] = 0;
+#pragma unroll
+                for (int t = 0; t < TAPS + PER - 1; ++t)
+                    accumulate(out, t, field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b));
+                emit(r, k0 + q * 256, out);
+            }
+        } else {
+#pragma unroll 1
+            for (int q = 0; q < U; ++q) {
+                const int64_t k = k0 + q * 256;
+                if (k >= row_out_dwords) break;
+                const int64_t i0 = k * PER + p.shift_m - (TAPS - 1);
+                int32_t out[PER];
+#pragma unroll
+                for (int u = 0; u < PER; ++u) out[u] = 0;
+#pragma unroll 1
+                for (int t = 0; t < TAPS + PER - 1; ++t) {
+                    const int64_t i = i0 + t;
+                    int32_t v = 0;
+                    if (i >= 0 && i < p.len) {
+                        const int64_t eb = row_bit0 + i * c;
+                        const uint32_t w = load_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
+                        v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
+                    }
+                    accumulate(out, t, v);
+                }
+                emit(r, k, out);
+            }
+        }
     }
 }
 
@@ -469,10 +508,11 @@ hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_si
 hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream)
 {
     const int per = 32 / a.rq_c_out;
-    const int64_t gx = ceil_div(ceil_div(a.out_len, per), 256);
+    const bool windowed = a.taps <= 7 && (a.taps + per - 1) * a.c <= 64;
+    const int64_t gx = ceil_div(ceil_div(a.out_len, per), windowed ? 256 * unpacked_unroll(per) : 256);
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
-    if (a.taps > 7 || (a.taps + per - 1) * a.c > 64) {
+    if (!windowed) {
         if (a_signed)
             hipLaunchKernelGGL(k_conv1d_requant_unpacked_any<true>, g, dim3(256), 0, stream, a);
         else

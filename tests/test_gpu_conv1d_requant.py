@@ -108,6 +108,17 @@ def test_requant_extreme_values_and_partial_clamp(bits, signed):
                 assert np.array_equal(got, ref), (bits, signed, xv, gv, qmax, out_bits, shift, packed)
 
 
+@pytest.mark.parametrize("signed", [False, True])
+def test_requant_shift_at_and_beyond_the_slice_width(signed):
+    """Shifts around S (10 for 4-bit, 3 taps) up to 31: everything ends at 0 or at the last value bit."""
+    x, g = values("rq5", 4, signed, signed, 3, 4, 5000)
+    for shift in (6, 7, 8, 9, 10, 11, 31):
+        ref = oracle_requant(x, g, hk.OUT_VALID, shift, 15, 4)
+        for packed in (True, False):
+            got = run_requant(x, g, 4, signed, signed, hk.OUT_VALID, hk.FMT_BITDENSE, shift, 15, 4, packed)
+            assert np.array_equal(got, ref), (signed, shift, packed)
+
+
 def test_requant_full_size_rows_sampled():
     """The benchmark's shape: 4096 x 65536, 3 taps, 4-bit unsigned in, 4-bit out; the oracle checks
     a sample of whole rows."""
