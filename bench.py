@@ -88,6 +88,41 @@ def cpu_baseline(x, g):
                        (ROWS, best * 1e3, 2 * 256 * (LENGTH - TAPS + 1) * TAPS / one / 1e9))
 
 
+def requant_extra(hk, wl, steps):
+    """The same 1-D cases with the outputs requantised in the kernel and written bit-dense at the
+    input's width: no int32 stream, so the integer VALUs bound it instead of HBM writes."""
+    import torch
+    report = {}
+    for bits, signed in ((4, False), (1, False), (2, False), (4, True)):
+        case = conv1d_case(hk, wl, bits, signed)
+        x_bd, g_d = case["keep"]
+        plan, out_len = case["plan"], case["out_len"]
+        row_bytes = hk.hikonv_bitdense_row_bytes(out_len, bits)
+        q = torch.empty(ROWS * row_bytes, dtype=torch.uint8, device="cuda")
+        shift, qmax = max(0, 2 * bits - 3), (1 << bits) - 1 if bits < 8 else 127
+
+        def packed():
+            hk.hikonv_conv1d_requant(plan, x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d, TAPS, hk.OUT_VALID, shift, qmax,
+                                     bits, q)
+
+        def unpacked():
+            hk.hikonv_conv1d_requant_unpacked(bits, bits, hk.signedness(signed, signed), x_bd, hk.FMT_BITDENSE, ROWS,
+                                              LENGTH, g_d, TAPS, hk.OUT_VALID, shift, qmax, bits, q)
+
+        event_ms(packed, 3)
+        ms_p = event_ms(packed, steps)
+        event_ms(unpacked, 3)
+        ms_u = event_ms(unpacked, steps)
+        algo = ROWS * (row_bytes + hk.hikonv_bitdense_row_bytes(LENGTH, bits)) + TAPS
+        report["%d%s" % (bits, "s" if signed else "u")] = dict(
+            ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=algo / ms_p / 1e6, unpacked_ms=ms_u,
+            frac_of_unpacked_valu_peak=case["macs"] / (ms_p * 1e-3) / VALU_LANE_RATE,
+            plan=dict(N=plan.N, K=plan.K, S=plan.S))
+        del case, q
+        torch.cuda.empty_cache()
+    return report
+
+
 def conv2d_extra(hk, wl, name, steps):
     """Packed vs unpacked DNN layer (ALU-bound configurations); returns a small report."""
     import torch
@@ -298,6 +333,7 @@ def main():
             del case
             torch.cuda.empty_cache()
         extras["conv1d_by_bits"] = by_bits
+        extras["conv1d_requant_bitdense_out"] = requant_extra(hk, wl, max(3, args.steps // 5))
         for name in ("c3", "c4"):
             extras["conv2d_" + name] = conv2d_extra(hk, wl, name, max(5, args.steps // 2))
         extras["latency"] = small_extras(hk, wl, max(5, args.steps // 2))

@@ -72,6 +72,10 @@ typedef struct hikonv_plan_t {
     int32_t M;                  /* DNN mode: (channel, kernel-row) products accumulated per split;   */
                                 /* 0 = let the planner choose                                        */
     int32_t taps;               /* kernel width that must be covered (0 = free: Algorithm 1 picks K) */
+    int32_t tight;              /* 0: S = p+q+G_b as in Eq. (slice1) (one more bit where signed data */
+                                /* needs it); 1: the smallest S for which every segment sum of the   */
+                                /* declared value ranges provably fits (G_b then reports S minus the */
+                                /* product width and may be smaller than the paper's)                */
     /* result */
     int32_t N, K, S, G_b;       /* elements per A word, taps per B word, slice bits, guard bits      */
     int32_t chunks;             /* ceil(taps / K): B words per kernel row (1 if taps == 0)           */

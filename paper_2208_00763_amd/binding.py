@@ -19,7 +19,7 @@ UB_MAD_U32_U24, UB_MAD_U64_U32, UB_MUL_LO_U32, UB_BFE_U32, UB_LSHR_B64, UB_DPP_M
 UB_MAD_I32_I24, UB_MAD_I64_I32, UB_ADD_U64, UB_ALIGNBIT, UB_AND_B32 = range(7, 12)
 UB_HBM_WRITE, UB_HBM_COPY, UB_HBM_READ, UB_HBM_WRITE_NT = 16, 17, 18, 19
 
-PLAN_FIELDS = ("bits_a bits_w a_signed w_signed bipolar L_A L_B L_acc mode M taps "
+PLAN_FIELDS = ("bits_a bits_w a_signed w_signed bipolar L_A L_B L_acc mode M taps tight "
                "N K S G_b chunks ops_per_mul paper_exact").split()
 
 

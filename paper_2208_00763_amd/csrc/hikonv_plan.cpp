@@ -11,7 +11,9 @@
 //    accumulated product provably fit (exact interval arithmetic); when the slice of
 //    Eq. slice1 is one bit short for signed data, S+1 is tried;
 //  * with a fixed tap count the kernel may be cut into chunks of K taps;
-//  * outside single-multiplier mode K <= N+1 is required (one-neighbour overlap-add).
+//  * outside single-multiplier mode K <= N+1 is required (one-neighbour overlap-add);
+//  * on request ("tight") the slice is the smallest one the exact check accepts, not
+//    p+q+G_b: e.g. 3 signed 4-bit products sum to at most 192 in magnitude, which fits 9 bits.
 #include "hikonv_internal.h"
 
 namespace {
@@ -64,6 +66,7 @@ struct Req {
     int p, q;
     bool a_signed, w_signed, any_signed;
     int L_A, L_B, L_acc, mode, M, taps;
+    bool tight;
     Range fa, gw, prod;
 };
 
@@ -81,6 +84,7 @@ Req make_req(const hikonv_plan_t &in)
     r.mode = in.mode;
     r.M = in.mode == HIKONV_MODE_DNN ? (in.M > 0 ? in.M : 1) : 1;
     r.taps = in.taps;
+    r.tight = in.tight != 0;
     r.fa = value_range(r.p, r.a_signed);
     r.gw = value_range(r.q, r.w_signed);
     r.prod = mul_range(r.fa, r.gw);
@@ -182,13 +186,16 @@ Cand search(const Req &r, bool paper_only)
             c.s = s0;
             if (!paper_fits(r, n, k, s0)) return;
         } else {
+            // tight: the smallest slice that is provably exact for the declared value ranges
+            // (the paper's p+q+G_b is an upper bound on what the segment sums need)
             c.s = 0;
-            for (int s = s0; s <= s0 + 1; ++s)
+            for (int s = r.tight ? 1 : s0; s <= s0 + 1; ++s)
                 if (exact_ok(r, n, k, s)) {
                     c.s = s;
                     break;
                 }
             if (!c.s) return;
+            if (c.s < s0) c.gb -= s0 - c.s;
         }
         c.found = true;
         if (better(r, c, best)) best = c;
@@ -211,6 +218,7 @@ bool valid_request(const hikonv_plan_t &in)
     if (in.mode < HIKONV_MODE_SINGLE || in.mode > HIKONV_MODE_DNN) return false;
     if (in.M < 0 || in.M > (1 << 20) || in.taps < 0 || in.taps > 64) return false;
     if (in.bipolar && (in.bits_a != 1 || in.bits_w != 1)) return false;
+    if (in.tight != 0 && in.tight != 1) return false;
     return true;
 }
 

@@ -14,9 +14,9 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(a).cuda()
 
 
-def conv1d_plan(bits, a_signed, w_signed, taps):
-    return hk.hikonv_plan_ex(bits_a=bits, bits_w=bits, a_signed=int(a_signed), w_signed=int(w_signed),
-                             L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=taps)
+def conv1d_plan(bits, a_signed, w_signed, taps, tight=0, bits_w=None):
+    return hk.hikonv_plan_ex(bits_a=bits, bits_w=bits_w or bits, a_signed=int(a_signed), w_signed=int(w_signed),
+                             L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=taps, tight=tight)
 
 
 def compact(x_np: np.ndarray, bits: int, bipolar=False) -> torch.Tensor:
@@ -51,11 +51,11 @@ def oracle_conv1d(x_np, g_np, mode):
     return direct.conv1d(x_np, g_np, direct.FULL if mode == hk.OUT_FULL else direct.VALID)
 
 
-def dnn_plan(bits_a, bits_w, a_signed, w_signed, taps, m, wide=True, bipolar=False):
+def dnn_plan(bits_a, bits_w, a_signed, w_signed, taps, m, wide=True, bipolar=False, tight=0):
     width = 32 if wide else 24
     return hk.hikonv_plan_ex(bits_a=bits_a, bits_w=bits_w, a_signed=int(a_signed), w_signed=int(w_signed),
                              bipolar=int(bipolar), L_A=width, L_B=width, L_acc=64 if wide else 32,
-                             mode=hk.MODE_DNN, M=m, taps=taps)
+                             mode=hk.MODE_DNN, M=m, taps=taps, tight=tight)
 
 
 def run_conv2d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):

@@ -71,12 +71,13 @@ def _corner_inputs(plan, length):
             yield [fa] * length, [gw] * plan.taps
 
 
+@pytest.mark.parametrize("tight", [0, 1])
 @pytest.mark.parametrize("signs", [(1, 1), (0, 1), (1, 0)])
 @pytest.mark.parametrize("taps", [3, 5, 7])
-def test_signed_conv1d_plans_are_exact_on_corners(signs, taps):
+def test_signed_conv1d_plans_are_exact_on_corners(signs, taps, tight):
     for b in range(1, 9):
         plan = hk.hikonv_plan_ex(bits_a=b, bits_w=b, a_signed=signs[0], w_signed=signs[1], L_A=32, L_B=32, L_acc=64,
-                                 mode=hk.MODE_CONV1D, taps=taps)
+                                 mode=hk.MODE_CONV1D, taps=taps, tight=tight)
         assert hk.hikonv_plan_check(plan) == hk.OK
         for f, g in _corner_inputs(plan, 4 * plan.N + 1):
             # operands must fit the signed 32-bit multiplier inputs
@@ -116,15 +117,48 @@ def test_paper_plans_that_are_one_bit_short_are_rejected():
     assert hk.hikonv_plan_check(p6) == hk.OK and -2 ** 31 <= pm.pack([-32] * p6.N, p6.S)
 
 
+def test_tight_plans_use_the_smallest_exact_slice():
+    """Beyond Eq. (slice1): the slice only has to hold the largest segment sum of the declared
+    ranges.  Three signed 4-bit products reach 192 in magnitude: 9 bits instead of 4+4+2."""
+    loose = hk.hikonv_plan_ex(bits_a=4, bits_w=4, a_signed=1, w_signed=1, L_A=32, L_B=32, L_acc=64,
+                              mode=hk.MODE_CONV1D, taps=3)
+    tight = hk.hikonv_plan_ex(bits_a=4, bits_w=4, a_signed=1, w_signed=1, L_A=32, L_B=32, L_acc=64,
+                              mode=hk.MODE_CONV1D, taps=3, tight=1)
+    assert (loose.N, loose.S, loose.ops_per_mul, loose.paper_exact) == (3, 10, 13, 1)
+    assert (tight.N, tight.S, tight.ops_per_mul, tight.paper_exact) == (4, 9, 18, 0)
+    # one bit less is inexact, and the planner's check says so
+    short = hk.Plan(**{**tight.as_dict(), "S": 8})
+    assert hk.hikonv_plan_check(short) == hk.EOVERFLOW
+    f, g = [-8] * 9, [-8] * 3
+    assert pm.conv1d_packed(f, g, 4, 3, 9, True) == np.convolve(f, g).tolist()
+    assert pm.conv1d_packed(f, g, 4, 3, 8, True) != np.convolve(f, g).tolist()
+    # 1-bit unsigned, 3 taps: sums reach 3, two bits suffice; 16 values per 32-bit word
+    t1 = hk.hikonv_plan_ex(bits_a=1, bits_w=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3, tight=1)
+    assert (t1.N, t1.S) == (16, 2)
+    # a tight plan is never worse than the default one, for every width and signedness
+    for b in range(1, 9):
+        for sa, sw in ((0, 0), (1, 1), (0, 1), (1, 0)):
+            for taps in (1, 3, 5, 7):
+                kw = dict(bits_a=b, bits_w=b, a_signed=sa, w_signed=sw, L_A=32, L_B=32, L_acc=64,
+                          mode=hk.MODE_CONV1D, taps=taps)
+                d, t = hk.hikonv_plan_ex(**kw), hk.hikonv_plan_ex(tight=1, **kw)
+                assert t.N * d.chunks >= d.N * t.chunks and hk.hikonv_plan_check(t) == hk.OK
+                if (t.N, t.K) == (d.N, d.K):
+                    assert t.S <= d.S
+                less = hk.Plan(**{**t.as_dict(), "S": t.S - 1})
+                assert t.S == 1 or hk.hikonv_plan_check(less) != hk.OK
+
+
+@pytest.mark.parametrize("tight", [0, 1])
 @pytest.mark.parametrize("wide", [True, False])
-def test_dnn_plans_are_exact_on_corners(wide):
+def test_dnn_plans_are_exact_on_corners(wide, tight):
     width, acc = (32, 64) if wide else (24, 32)
     for b, sa, sw in ((1, 0, 0), (2, 1, 1), (4, 1, 1), (4, 0, 1), (4, 0, 0), (8, 1, 1), (3, 0, 1)):
         for taps in (1, 3, 5):
             for m in (1, 2, 5, 9, 0):
                 try:
                     plan = hk.hikonv_plan_ex(bits_a=b, bits_w=b, a_signed=sa, w_signed=sw, L_A=width, L_B=width,
-                                             L_acc=acc, mode=hk.MODE_DNN, M=m, taps=taps)
+                                             L_acc=acc, mode=hk.MODE_DNN, M=m, taps=taps, tight=tight)
                 except hk.HikonvError as e:
                     assert e.code == hk.ENOPLAN
                     continue
@@ -132,7 +166,7 @@ def test_dnn_plans_are_exact_on_corners(wide):
                 signed = bool(sa or sw)
                 ra = (-(1 << (b - 1)), (1 << (b - 1)) - 1) if sa else (0, (1 << b) - 1)
                 rw = (-(1 << (b - 1)), (1 << (b - 1)) - 1) if sw else (0, (1 << b) - 1)
-                c_in = min(plan.M, 40)          # one split group of min(M, 40) channels, one kernel row
+                c_in = plan.M if tight else min(plan.M, 40)   # one split group of channels, one kernel row
                 for fa, gw in itertools.product(ra, rw):
                     x = [[[fa] * (2 * plan.N + 1)] for _ in range(c_in)]
                     w = [[[[gw] * taps] for _ in range(c_in)]]
