@@ -141,9 +141,10 @@ def conv2d_extra(hk, wl, name, steps):
     y = torch.empty(n * co * h * wd, dtype=torch.int32, device="cuda")
     macs = n * co * h * wd * c * kh * kw
     report = {"macs": macs}
-    for label, width, acc in (("wide32", 32, 64), ("narrow24", 24, 32)):
+    for label, width, acc, tight in (("wide32", 32, 64, 0), ("wide32_tight", 32, 64, 1), ("narrow24", 24, 32, 0)):
         try:
-            plan = hk.hikonv_plan_ex(L_A=width, L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=0, taps=kw, **plan_kw)
+            plan = hk.hikonv_plan_ex(L_A=width, L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=0, taps=kw, tight=tight,
+                                     **plan_kw)
             if plan.N > 8:
                 raise hk.HikonvError(hk.EUNSUPPORTED, "plan")
         except hk.HikonvError:

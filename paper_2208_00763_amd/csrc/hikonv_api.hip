@@ -251,7 +251,14 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.Co = Co;
     ca.cog0 = 0;
     ca.y = y_dev;
-    const int co_tile = Co >= 8 ? 8 : 2;
+    int co_tile = Co >= 8 ? 8 : 2;
+    {
+        static const int forced_tile = [] {
+            const char *e = getenv("HIKONV_CONV2D_COTILE"); // tuning override: 2 or 8
+            return e ? atoi(e) : 0;
+        }();
+        if (forced_tile == 2 || forced_tile == 8) co_tile = forced_tile;
+    }
     choose_split(row_groups * ((Co + co_tile - 1) / co_tile), &ca);
     rc = hip_result(launch_conv2d_packed(ca, wide, any_signed, co_tile, stream));
     if (rc != HIKONV_OK) return rc;
