@@ -88,6 +88,26 @@ def cpu_baseline(x, g):
                        (ROWS, best * 1e3, 2 * 256 * (LENGTH - TAPS + 1) * TAPS / one / 1e9))
 
 
+def graph_replay_ms(fn, calls, reps):
+    """Milliseconds per call of fn when `calls` calls are captured into one HIP graph and the
+    graph is replayed (no host launch cost between the kernels); None if capture fails."""
+    import torch
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(calls):
+                fn()
+        graph.replay()
+        return event_ms(graph.replay, reps) / calls
+    except Exception:                                          # graph capture is optional
+        return None
+
+
 def requant_extra(hk, wl, steps):
     """The same 1-D cases with the outputs requantised in the kernel and written bit-dense at the
     input's width: no int32 stream, so the integer VALUs bound it instead of HBM writes."""
@@ -159,10 +179,12 @@ def conv2d_extra(hk, wl, name, steps):
 
         event_ms(run, 3)
         ms = event_ms(run, steps)
+        graph_ms = graph_replay_ms(run, 20, max(3, steps // 4))
         # algorithmic VALU work of the packed layer: one multiply-accumulate per (block, channel, term)
         blocks = -(-(wd + 1) // plan.N)
         lane_mads = n * co * h * blocks * c * kh * plan.chunks
         report[label] = dict(ms=ms, gops=2 * macs / ms / 1e6, plan=dict(N=plan.N, K=plan.K, S=plan.S, M=plan.M),
+                             graph_ms=graph_ms, graph_gops=(2 * macs / graph_ms / 1e6) if graph_ms else None,
                              frac_of_unpacked_valu_peak=macs / (ms * 1e-3) / VALU_LANE_RATE,
                              roofline={"bound": "alu", "achieved": lane_mads / (ms * 1e-3) / 1e12,
                                        "peak": VALU_LANE_RATE / 1e12, "unit": "T lane-instr/s",
@@ -174,7 +196,7 @@ def conv2d_extra(hk, wl, name, steps):
 
     event_ms(run_unpacked, 3)
     ms = event_ms(run_unpacked, steps)
-    report["unpacked"] = dict(ms=ms, gops=2 * macs / ms / 1e6)
+    report["unpacked"] = dict(ms=ms, gops=2 * macs / ms / 1e6, graph_ms=graph_replay_ms(run_unpacked, 20, max(3, steps // 4)))
     return report
 
 
@@ -194,6 +216,8 @@ def small_extras(hk, wl, steps):
     run1 = lambda: hk.hikonv_conv1d(plan, x_bd, hk.FMT_BITDENSE, 1, 4096, g_d, 3, hk.OUT_VALID, y)
     event_ms(run1, 10)
     out["conv1d_c1_us_per_call"] = event_ms(run1, 200) * 1e3
+    g1 = graph_replay_ms(run1, 50, 10)
+    out["conv1d_c1_graph_us_per_call"] = g1 * 1e3 if g1 else None
 
     xi, weights, specs = wl.config5()
     net = PackedCnn([torch.from_numpy(w.view("uint8")).cuda() for w in weights], specs)
@@ -210,20 +234,13 @@ def small_extras(hk, wl, steps):
         if spec["pool"]:
             h, w = h // 2, w // 2
     out["cnn_c5_macs"] = macs
-    try:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            fwd()
-        torch.cuda.current_stream().wait_stream(side)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            fwd()
-        graph.replay()
-        out["cnn_c5_graph_us"] = event_ms(graph.replay, steps) * 1e3
-    except Exception as exc:                                   # graph capture is optional
-        out["cnn_c5_graph_us"] = None
-        out["cnn_c5_graph_error"] = str(exc)[:200]
+    g5 = graph_replay_ms(fwd, 1, steps)
+    out["cnn_c5_graph_us"] = g5 * 1e3 if g5 else None
+    # the same chain with separate epilogue and packing passes (bit-dense activations between layers)
+    plain = PackedCnn([torch.from_numpy(w.view("uint8")).cuda() for w in weights], specs, fused=False)
+    fwd_plain = lambda: plain.forward(x5, 1, 160, 320, shifts)
+    g5p = graph_replay_ms(fwd_plain, 1, steps)
+    out["cnn_c5_unfused_graph_us"] = g5p * 1e3 if g5p else None
     return out
 
 

@@ -53,6 +53,10 @@ extern "C" {
                               /* to a multiple of 4 bytes (Section "Single convolver architecture":   */
                               /* unused bits of quantised data are discarded in storage)              */
 
+#define HIKONV_FMT_PACKED 2   /* conv2d only: the call's workspace already holds this layer's packed  */
+                              /* activations, written by hikonv_epilogue_pack for the same plan and    */
+                              /* geometry; x_dev is ignored                                            */
+
 #define HIKONV_OUT_FULL 0  /* len + taps - 1 outputs per row (Eq. pad_f) */
 #define HIKONV_OUT_VALID 1 /* y[taps-1 .. len-1]: len - taps + 1 outputs */
 
@@ -207,6 +211,23 @@ int hikonv_conv2d_unpacked(int bits_a, int bits_w, int signedness, const void *x
  */
 int hikonv_epilogue(const int32_t *acc_dev, int N, int C, int H, int W, int shift, int qmax, int pool,
                     int out_bits, int out_format, void *out_dev, void *stream);
+
+/*
+ * hikonv_epilogue_pack -- the same epilogue (ReLU, q = min(qmax, max(acc,0) >> shift),
+ * optional 2x2/stride-2 max-pool) writing its result directly as the packed
+ * activation words of the NEXT layer (Section "Basic HiKonv Operations":
+ * features are packed at run time - here by their producer, so the next layer
+ * needs no packing pass).  acc_dev: NCHW int32 [N][C][H][W].  The next layer is
+ * described by its plan (unsigned activations of next_plan->bits_a bits,
+ * qmax < 2^bits_a) and its geometry: input [N][C][H'][W'] with H' = H/2, W' = W/2
+ * when pool, else H, W.  next_workspace_dev: the workspace later passed to
+ * hikonv_conv2d / hikonv_conv2d_prepacked for that layer, which must then be
+ * called with x_format = HIKONV_FMT_PACKED and the same plan and geometry.
+ */
+int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H, int W, int shift, int qmax, int pool,
+                         const hikonv_plan_t *next_plan, int next_Co, int next_Kh, int next_Kw,
+                         int next_stride, int next_pad, void *next_workspace_dev,
+                         size_t next_workspace_bytes, void *stream);
 
 /*
  * Roofline micro-benchmarks.  kind: HIKONV_UB_*.  Launches one kernel on

@@ -13,7 +13,7 @@ LIB_PATH = os.environ.get("HIKONV_LIB", os.path.join(HERE, "libhikonv.so"))   # 
 OK, EINVAL, EOVERFLOW, ENOPLAN, EHIP, EWORKSPACE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 MODE_SINGLE, MODE_CONV1D, MODE_DNN = 0, 1, 2
 A_SIGNED, W_SIGNED, BIPOLAR = 1, 2, 4
-FMT_INT8, FMT_BITDENSE = 0, 1
+FMT_INT8, FMT_BITDENSE, FMT_PACKED = 0, 1, 2
 OUT_FULL, OUT_VALID = 0, 1
 UB_MAD_U32_U24, UB_MAD_U64_U32, UB_MUL_LO_U32, UB_BFE_U32, UB_LSHR_B64, UB_DPP_MOV, UB_ADD_U32 = range(7)
 UB_MAD_I32_I24, UB_MAD_I64_I32, UB_ADD_U64, UB_ALIGNBIT, UB_AND_B32 = range(7, 12)
@@ -73,6 +73,7 @@ SIGNATURES = {
     "hikonv_conv2d_prepacked": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
     "hikonv_conv2d_unpacked": (_i, [_i, _i, _i, _vp, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
     "hikonv_epilogue": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hikonv_epilogue_pack": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _pp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "hikonv_ubench": (_i, [_i, _i, _i, _vp, _sz, _vp]),
     "hikonv_selftest_lane_shift": (_i, [_vp, _vp]),
     "hikonv_strerror": (C.c_char_p, [_i]),
@@ -93,11 +94,26 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
 
 
+def _raw_stream_getter():
+    """Fastest available way to read the raw handle of torch's current stream."""
+    import torch
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    if raw is not None:
+        return lambda: raw(torch.cuda.current_device())
+    return lambda: torch.cuda.current_stream().cuda_stream
+
+
+_current_raw_stream = None
+
+
 def _stream(stream):
+    """Handle of the stream to launch on: the caller's, else torch's current stream."""
+    global _current_raw_stream
     if stream is not None:
         return C.c_void_p(stream)
-    import torch
-    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if _current_raw_stream is None:
+        _current_raw_stream = _raw_stream_getter()
+    return C.c_void_p(_current_raw_stream())
 
 
 def signedness(a_signed=False, w_signed=False, bipolar=False):
@@ -193,6 +209,14 @@ def hikonv_conv2d_unpacked(bits_a, bits_w, signedness_flags, x, n, c, h, w, weig
 def hikonv_epilogue(acc, n, c, h, w, shift, qmax, pool, out_bits, out_format, out, stream=None):
     _check(lib.hikonv_epilogue(_ptr(acc), n, c, h, w, shift, qmax, int(pool), out_bits, out_format, _ptr(out),
                                _stream(stream)), "hikonv_epilogue")
+
+
+def hikonv_epilogue_pack(acc, n, c, h, w, shift, qmax, pool, next_plan, next_co, next_kh, next_kw, next_stride,
+                         next_pad, next_workspace, stream=None):
+    _check(lib.hikonv_epilogue_pack(_ptr(acc), n, c, h, w, shift, qmax, int(pool), C.byref(next_plan), next_co,
+                                    next_kh, next_kw, next_stride, next_pad, _ptr(next_workspace),
+                                    next_workspace.numel() * next_workspace.element_size(), _stream(stream)),
+           "hikonv_epilogue_pack")
 
 
 def hikonv_ubench(kind, iters, blocks, buf, stream=None):

@@ -12,19 +12,22 @@ from . import binding as hk
 class PackedCnn:
     """Pre-packs the weights of a list of conv layers once; forward() runs the chain."""
 
-    def __init__(self, weights, specs, act_bits=4, w_bits=4, w_signed=True, wide=True, m=0):
+    def __init__(self, weights, specs, act_bits=4, w_bits=4, w_signed=True, wide=True, m=0, tight=0, fused=True):
+        """fused: every epilogue writes the next layer's packed activation words directly
+        (hikonv_epilogue_pack); otherwise it writes bit-dense rows that the next layer packs."""
         self.layers = []
         width, acc = (32, 64) if wide else (24, 32)
         for w_dev, spec in zip(weights, specs):
             co, c, kh, kw = w_dev.shape
             plan = hk.hikonv_plan_ex(bits_a=act_bits, bits_w=w_bits, a_signed=0, w_signed=int(w_signed), L_A=width,
-                                     L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=m, taps=kw)
+                                     L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=m, taps=kw, tight=tight)
             packed = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8,
                                  device=w_dev.device)
             hk.hikonv_pack_weights(plan, w_dev, co, c, kh, kw, packed)
             self.layers.append(dict(plan=plan, packed=packed, co=co, c=c, kh=kh, kw=kw, pad=spec["pad"],
                                     pool=spec["pool"]))
         self.act_bits = act_bits
+        self.fused = fused
         self.buffers = None
 
     def _allocate(self, n, h, w):
@@ -48,14 +51,23 @@ class PackedCnn:
         list of per-layer int32 accumulator tensors)."""
         if self.buffers is None or self.buffers[0] != n or self.buffers[1][0]["h"] != h or self.buffers[1][0]["w"] != w:
             self._allocate(n, h, w)
-        cur = x_bitdense
+        cur, fmt = x_bitdense, hk.FMT_BITDENSE
         accs = []
-        for i, (layer, buf) in enumerate(zip(self.layers, self.buffers[1])):
-            hk.hikonv_conv2d_prepacked(layer["plan"], cur, hk.FMT_BITDENSE, n, layer["c"], buf["h"], buf["w"],
+        bufs = self.buffers[1]
+        for i, (layer, buf) in enumerate(zip(self.layers, bufs)):
+            hk.hikonv_conv2d_prepacked(layer["plan"], cur, fmt, n, layer["c"], buf["h"], buf["w"],
                                        layer["packed"], layer["co"], layer["kh"], layer["kw"], 1, layer["pad"],
                                        buf["ws"], buf["acc"])
             accs.append(buf["acc"])
-            if i + 1 < len(self.layers):
+            if i + 1 == len(self.layers):
+                break
+            if self.fused:
+                nxt = self.layers[i + 1]
+                hk.hikonv_epilogue_pack(buf["acc"], n, layer["co"], buf["ho"], buf["wo"], shifts[i], qmax,
+                                        layer["pool"], nxt["plan"], nxt["co"], nxt["kh"], nxt["kw"], 1, nxt["pad"],
+                                        bufs[i + 1]["ws"])
+                cur, fmt = None, hk.FMT_PACKED
+            else:
                 hk.hikonv_epilogue(buf["acc"], n, layer["co"], buf["ho"], buf["wo"], shifts[i], qmax, layer["pool"],
                                    self.act_bits, hk.FMT_BITDENSE, buf["nxt"])
                 cur = buf["nxt"]

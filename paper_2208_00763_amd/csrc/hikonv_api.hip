@@ -118,39 +118,14 @@ int pack_weights_impl(const hikonv_plan_t *plan, const Conv2dGeom &g, const void
     return hip_result(launch_pack_weights(a, stream));
 }
 
-int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,
-                const void *w_dev, int prepacked, int Co, int Kh, int Kw, int stride, int pad, void *workspace_dev,
-                size_t workspace_bytes, int32_t *y_dev, void *stream_v)
+// Geometry part of the activation-packing arguments (source fields are left to the caller).
+PackActArgs pack_act_args(const hikonv_plan_t *plan, const Conv2dGeom &g, int N, int C, int H, int W, int Kh, int pad,
+                          uint32_t *apk, int32_t *toff)
 {
-    Conv2dGeom g;
-    int rc = conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g);
-    if (rc != HIKONV_OK) return rc;
-    if (!x_dev || !w_dev || !y_dev) return HIKONV_EINVAL;
-    if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE) return HIKONV_EINVAL;
-    if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(w_dev, prepacked ? 256 : 1)) return HIKONV_EINVAL;
-    const size_t need = g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
-    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return HIKONV_EWORKSPACE;
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
-    uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
-    int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
-    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes + g.toff_bytes);
-    const uint8_t *wpk = static_cast<const uint8_t *>(w_dev);
-    if (!prepacked) {
-        uint8_t *dst = ws + g.apk_bytes + g.toff_bytes + g.sa_bytes;
-        rc = pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, dst, stream);
-        if (rc != HIKONV_OK) return rc;
-        wpk = dst;
-    }
-
-    PackActArgs pa;
-    pa.x = x_dev;
-    pa.x_format = x_format;
-    pa.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
+    PackActArgs pa = {};
     pa.b = plan->bits_a;
     pa.a_signed = plan->a_signed;
     pa.bipolar = plan->bipolar;
-    pa.row_bytes = x_format == HIKONV_FMT_INT8 ? W : hikonv_bitdense_row_bytes(W, plan->bits_a);
     pa.Nimg = N;
     pa.C = C;
     pa.H = H;
@@ -168,8 +143,45 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     pa.terms = g.terms;
     pa.Kh = Kh;
     pa.chunk_stride = (int64_t)N * C * g.Hp * g.Xs;
-    rc = hip_result(launch_pack_act(pa, stream));
+    return pa;
+}
+
+int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,
+                const void *w_dev, int prepacked, int Co, int Kh, int Kw, int stride, int pad, void *workspace_dev,
+                size_t workspace_bytes, int32_t *y_dev, void *stream_v)
+{
+    Conv2dGeom g;
+    int rc = conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g);
     if (rc != HIKONV_OK) return rc;
+    if (!w_dev || !y_dev) return HIKONV_EINVAL;
+    if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE && x_format != HIKONV_FMT_PACKED)
+        return HIKONV_EINVAL;
+    if (x_format != HIKONV_FMT_PACKED && (!x_dev || !aligned(x_dev, 4))) return HIKONV_EINVAL;
+    if (!aligned(y_dev, 4) || !aligned(w_dev, prepacked ? 256 : 1)) return HIKONV_EINVAL;
+    const size_t need = g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
+    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return HIKONV_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
+    uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
+    int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes + g.toff_bytes);
+    const uint8_t *wpk = static_cast<const uint8_t *>(w_dev);
+    if (!prepacked) {
+        uint8_t *dst = ws + g.apk_bytes + g.toff_bytes + g.sa_bytes;
+        rc = pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, dst, stream);
+        if (rc != HIKONV_OK) return rc;
+        wpk = dst;
+    }
+
+    if (x_format != HIKONV_FMT_PACKED) {
+        PackActArgs pa = pack_act_args(plan, g, N, C, H, W, Kh, pad, apk, toff);
+        pa.x = x_dev;
+        pa.x_format = x_format;
+        pa.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
+        pa.row_bytes = x_format == HIKONV_FMT_INT8 ? W : hikonv_bitdense_row_bytes(W, plan->bits_a);
+        rc = hip_result(launch_pack_act(pa, stream));
+        if (rc != HIKONV_OK) return rc;
+    }
 
     Conv2dArgs ca;
     ca.apk = apk;
@@ -251,7 +263,10 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.Co = Co;
     ca.cog0 = 0;
     ca.y = y_dev;
+    // Eight output channels per wave reuse every activation word eight times; layers with few
+    // (row group, channel tile) pairs run faster with two channels per wave and four times the waves.
     int co_tile = Co >= 8 ? 8 : 2;
+    if (ca.pipelined && row_groups * ((Co + 7) / 8) < 768) co_tile = 2;
     {
         static const int forced_tile = [] {
             const char *e = getenv("HIKONV_CONV2D_COTILE"); // tuning override: 2 or 8
@@ -507,6 +522,35 @@ extern "C" int hikonv_epilogue(const int32_t *acc_dev, int N, int C, int H, int 
     a.out_row_bytes = out_format == HIKONV_FMT_BITDENSE ? hikonv_bitdense_row_bytes(a.Wo, out_bits) : a.Wo;
     a.out = static_cast<uint8_t *>(out_dev);
     return hip_result(launch_epilogue(a, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H, int W, int shift, int qmax, int pool,
+                                    const hikonv_plan_t *next_plan, int next_Co, int next_Kh, int next_Kw,
+                                    int next_stride, int next_pad, void *next_workspace_dev,
+                                    size_t next_workspace_bytes, void *stream)
+{
+    if (!next_plan || N < 1 || C < 1 || H < 1 || W < 1 || shift < 0 || shift > 31 || !acc_dev) return HIKONV_EINVAL;
+    if (next_plan->bipolar || next_plan->a_signed) return HIKONV_EUNSUPPORTED; // the outputs are unsigned values
+    if (qmax < 0 || qmax > (1 << next_plan->bits_a) - 1) return HIKONV_EINVAL;
+    const int Hn = pool ? H / 2 : H, Wn = pool ? W / 2 : W;
+    if (Hn < 1 || Wn < 1) return HIKONV_EINVAL;
+    Conv2dGeom g;
+    int rc = conv2d_geom(next_plan, N, C, Hn, Wn, next_Co, next_Kh, next_Kw, next_stride, next_pad, &g);
+    if (rc != HIKONV_OK) return rc;
+    if (!next_workspace_dev || !aligned(next_workspace_dev, 256) ||
+        next_workspace_bytes < g.apk_bytes + g.toff_bytes + g.sa_bytes)
+        return HIKONV_EWORKSPACE;
+    uint8_t *ws = static_cast<uint8_t *>(next_workspace_dev);
+    PackActArgs pa = pack_act_args(next_plan, g, N, C, Hn, Wn, next_Kh, next_pad, reinterpret_cast<uint32_t *>(ws),
+                                   reinterpret_cast<int32_t *>(ws + g.apk_bytes));
+    pa.x_format = kPackFromAcc;
+    pa.acc = acc_dev;
+    pa.acc_H = H;
+    pa.acc_W = W;
+    pa.pool = pool ? 1 : 0;
+    pa.shift = shift;
+    pa.qmax = qmax;
+    return hip_result(launch_pack_act(pa, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream)

@@ -35,7 +35,24 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     const int ch = (int)(t / ((int64_t)p.Nimg * p.C));
     const int h = hp - p.pad;
     uint32_t a = 0;
-    if (xi > 0 && h >= 0 && h < p.H) {
+    if (xi > 0 && h >= 0 && h < p.H && p.x_format == kPackFromAcc) {
+        // fused epilogue of the producing layer (ReLU, shift, clamp, optional 2x2 max-pool)
+        const int32_t *src = p.acc + nc * p.acc_H * p.acc_W;
+        const int e0 = (xi - 1) * p.N - ch * p.Kp;
+        for (int j = 0; j < p.N; ++j) {
+            const int i = e0 + j;
+            if (i < 0 || i >= p.W) continue;
+            int32_t v;
+            if (p.pool) {
+                const int32_t *s0 = src + (int64_t)(2 * h) * p.acc_W + 2 * i;
+                v = max(max(s0[0], s0[1]), max(s0[p.acc_W], s0[p.acc_W + 1]));
+            } else {
+                v = src[(int64_t)h * p.acc_W + i];
+            }
+            v = min(max(v, 0) >> p.shift, p.qmax);
+            a += (uint32_t)v << (p.S * j);
+        }
+    } else if (xi > 0 && h >= 0 && h < p.H) {
         const uint8_t *rowp = static_cast<const uint8_t *>(p.x) + (nc * p.H + h) * p.row_bytes;
         const int e0 = (xi - 1) * p.N - ch * p.Kp;
         for (int j = 0; j < p.N; ++j) {

@@ -57,8 +57,14 @@ hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hi
 #endif
 constexpr int kTermGroup = HIKONV_TERM_GROUP;
 
+// source of the activations k_pack_act packs: INT8 / bit-dense rows, or the previous layer's
+// int32 accumulators, requantised (and max-pooled) on the way
+constexpr int kPackFromAcc = 100;
+
 struct PackActArgs {
     const void *x;           // NCHW activations, INT8 or bit-dense rows
+    const int32_t *acc;      // kPackFromAcc: [Nimg][C][acc_H][acc_W] accumulators of the producing layer
+    int acc_H, acc_W, pool, shift, qmax; // kPackFromAcc: q = min(qmax, max(acc, 0) >> shift) after 2x2 max-pool if pool
     int x_format, c, b, a_signed, bipolar;
     int64_t row_bytes;       // bytes per W-row of x (bit-dense: padded; INT8: W)
     int Nimg, C, H, W, pad;

@@ -192,12 +192,61 @@ def oracle_cnn(x, weights, specs):
     return accs, shifts
 
 
+@pytest.mark.parametrize("pool", [0, 1])
+@pytest.mark.parametrize("wide", [True, False])
+def test_epilogue_pack_feeds_the_next_layer(pool, wide):
+    """hikonv_epilogue_pack writes the next layer's packed words; that layer, called with
+    FMT_PACKED, must give what the oracle gives for requantise -> pool -> convolution."""
+    for (n, c, h, w, co, kh, kw, pad, shift, tight) in ((1, 5, 7, 9, 4, 3, 3, 1, 3, 0), (2, 16, 12, 30, 9, 3, 3, 1, 5, 1),
+                                                        (1, 8, 9, 70, 8, 1, 1, 0, 0, 0), (1, 3, 10, 150, 5, 3, 5, 2, 4, 0),
+                                                        (1, 4, 6, 8, 3, 5, 3, 0, 2, 0)):
+        rng = wl.rng_for("epack", n, c, h, w, co, pool, wide)
+        acc = rng.integers(-3000, 3000, size=(n, c, h, w)).astype(np.int32)
+        wt = wl.uniform_values(rng, (co, c, kh, kw), 4, True)
+        q = direct.relu_requant(acc, shift, 15)
+        if pool:
+            q = direct.maxpool2x2(q)
+        hn, wn = q.shape[2], q.shape[3]
+        if hn + 2 * pad < kh or wn + 2 * pad < kw:
+            continue
+        ref = direct.conv2d(q.view(np.uint8), wt, 1, pad)
+        try:
+            plan = dnn_plan(4, 4, False, True, kw, 0, wide, tight=tight)
+        except hk.HikonvError:
+            continue
+        ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, n, c, hn, wn, co, kh, kw, 1, pad, True),
+                         dtype=torch.uint8, device="cuda")
+        pw = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8, device="cuda")
+        hk.hikonv_pack_weights(plan, dev(wt), co, c, kh, kw, pw)
+        hk.hikonv_epilogue_pack(dev(acc), n, c, h, w, shift, 15, pool, plan, co, kh, kw, 1, pad, ws)
+        y = torch.full((ref.size + 8,), -77777, dtype=torch.int32, device="cuda")
+        hk.hikonv_conv2d_prepacked(plan, None, hk.FMT_PACKED, n, c, hn, wn, pw, co, kh, kw, 1, pad, ws, y)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert (got[ref.size:] == -77777).all()
+        assert np.array_equal(got[:ref.size].reshape(ref.shape), ref), (n, c, h, w, co, kh, kw, pad, pool, wide, plan)
+    # argument checks: signed next-layer activations, qmax beyond the width, workspace too small
+    plan = dnn_plan(4, 4, False, True, 3, 0, wide)
+    acc_d = torch.zeros(64, dtype=torch.int32, device="cuda")
+    ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, 1, 1, 8, 8, 2, 3, 3, 1, 1, True), dtype=torch.uint8,
+                     device="cuda")
+    for kwargs, code in ((dict(qmax=16), hk.EINVAL), (dict(shift=32), hk.EINVAL), (dict(ws=ws[:256]), hk.EWORKSPACE),
+                         (dict(plan=dnn_plan(4, 4, True, True, 3, 0, wide)), hk.EUNSUPPORTED)):
+        a = dict(qmax=15, shift=0, ws=ws, plan=plan)
+        a.update(kwargs)
+        with pytest.raises(hk.HikonvError) as e:
+            hk.hikonv_epilogue_pack(acc_d, 1, 1, 8, 8, a["shift"], a["qmax"], 0, a["plan"], 2, 3, 3, 1, 1, a["ws"])
+        assert e.value.code == code
+
+
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("size", [(32, 64), (160, 320)])
-def test_cnn_forward_config5(size):
+def test_cnn_forward_config5(size, fused):
     h, w = size
     x, weights, specs = wl.config5(h, w)
     ref_accs, shifts = oracle_cnn(x, weights, specs)
-    net = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs)
+    net = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs, fused=fused,
+                    tight=int(fused))
     x_bd = compact(x.reshape(3 * h, w), 4)
     _, accs = net.forward(x_bd, 1, h, w, shifts)
     torch.cuda.synchronize()
