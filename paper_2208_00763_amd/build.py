@@ -17,6 +17,9 @@ SOURCES = [
     "hikonv_conv2d.hip",
     "hikonv_conv2d_wide.hip",
     "hikonv_conv2d_narrow.hip",
+    "hikonv_conv2d_sreg_unsigned.hip",
+    "hikonv_conv2d_sreg_signed.hip",
+    "hikonv_conv2d_sreg_bipolar.hip",
     "hikonv_misc.hip",
 ]
 

@@ -214,11 +214,33 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.Wo = g.Wo;
     const bool wide = plan->L_A == 32;
     const bool any_signed = !plan->bipolar && (plan->a_signed || plan->w_signed);
-    const int64_t row_groups = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, ca.rows_per_wave);
-    // the pipelined kernel splits after a whole number of term groups
+    // the pipelined kernels split after a whole number of term groups
     const int split_terms = (plan->M * plan->chunks) / kTermGroup * kTermGroup;
     ca.pipelined = split_terms >= kTermGroup ? 1 : 0;
     ca.split_terms = split_terms;
+    // Kernel choice.  With the weights in scalar registers the term loop has no LDS traffic
+    // and rows need no lane for their zero word; measured faster once a layer has many terms
+    // and enough (row group, channel tile) pairs to fill the chip, slower on small layers.
+    // HIKONV_CONV2D_KERNEL (tuning / test override, read per call): 1 = LDS-staged kernels
+    // only, 2 = scalar-register kernel wherever the plan allows it.
+    const char *kernel_env = getenv("HIKONV_CONV2D_KERNEL");
+    const int forced_kernel = kernel_env ? atoi(kernel_env) : 0;
+    ca.sreg = 0;
+    if (forced_kernel != 1 && Co >= 8 &&
+        conv2d_sreg_applicable(plan->N, plan->K, plan->chunks, split_terms, wide, plan->bipolar != 0)) {
+        const int real = (W + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
+        const int lanes = ca.segs ? 64 : (real < g.X ? real : g.X);
+        const int64_t groups_s = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, 64 / lanes);
+        ca.sreg = forced_kernel == 2 || (g.terms_pad >= 512 && groups_s * ((Co + 7) / 8) >= 1024) ? 1 : 0;
+    }
+    ca.Lr = g.X;
+    if (ca.sreg && ca.segs == 0) {
+        // lanes only for the blocks that hold input values in some chunk
+        const int real = (W + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
+        ca.Lr = real < g.X ? real : g.X;
+        ca.rows_per_wave = 64 / ca.Lr;
+    }
+    const int64_t row_groups = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, ca.rows_per_wave);
 
     // enough waves to cover the load latency: divide the term range over 2 or 4 waves of a
     // workgroup when the layer has few (row group, channel tile) pairs
@@ -256,6 +278,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
         sa_args.Co = 1;
         sa_args.cog0 = g.n_cog - 1;
         sa_args.y = sa;
+        sa_args.sreg = 0;
         choose_split(row_groups, &sa_args);
         rc = hip_result(launch_conv2d_packed(sa_args, wide, any_signed, 2, stream));
         if (rc != HIKONV_OK) return rc;
@@ -266,13 +289,13 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     // Eight output channels per wave reuse every activation word eight times; layers with few
     // (row group, channel tile) pairs run faster with two channels per wave and four times the waves.
     int co_tile = Co >= 8 ? 8 : 2;
-    if (ca.pipelined && row_groups * ((Co + 7) / 8) < 768) co_tile = 2;
+    if (!ca.sreg && ca.pipelined && row_groups * ((Co + 7) / 8) < 768) co_tile = 2;
     {
         static const int forced_tile = [] {
             const char *e = getenv("HIKONV_CONV2D_COTILE"); // tuning override: 2 or 8
             return e ? atoi(e) : 0;
         }();
-        if (forced_tile == 2 || forced_tile == 8) co_tile = forced_tile;
+        if (!ca.sreg && (forced_tile == 2 || forced_tile == 8)) co_tile = forced_tile;
     }
     choose_split(row_groups * ((Co + co_tile - 1) / co_tile), &ca);
     rc = hip_result(launch_conv2d_packed(ca, wide, any_signed, co_tile, stream));

@@ -3,6 +3,7 @@
 // layers, and the unpacked one-product-per-multiply baseline.
 #include <type_traits>
 #include "hikonv_conv2d_kernel.h"
+#include "hikonv_conv2d_sreg.h"
 
 namespace hikonv {
 namespace {
@@ -399,6 +400,12 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed,
     const int64_t gy = ceil_div(a.Co, co_tile);
     if (gx <= 0 || gx > 0x7fffffffLL || gy <= 0 || gy > 65535) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)gy);
+    if (a.sreg) {
+        if (!wide || co_tile != 8) return hipErrorInvalidValue;
+        const int hi = a.Kp - 1;
+        if (a.fused_bipolar) return launch_conv2d_sreg_bipolar(a, hi, g, stream);
+        return any_signed ? launch_conv2d_sreg_signed(a, hi, g, stream) : launch_conv2d_sreg_unsigned(a, hi, g, stream);
+    }
     return wide ? launch_conv2d_wide(a, any_signed, co_tile, g, stream)
                 : launch_conv2d_narrow(a, any_signed, co_tile, g, stream);
 }

@@ -1,0 +1,407 @@
+// Packed DNN-layer kernel with the weight words in scalar registers (Theorem 3 of the paper;
+// products accumulated in the packed domain before a split, Section "DNN Convolution
+// Extension").
+//
+// One lane owns one packed block x of one output row and eight output channels.  The B
+// words of a term (ci, kh, chunk) are the same for every lane of a wave, so they are read
+// with scalar loads (32 bytes per term) and a packed multiply-accumulate is one
+// v_mad_u64_u32 / v_mad_i64_i32 with an SGPR operand; the A word of the term is one dword
+// load per lane from the packed activation rows.  No LDS traffic in the term loop.
+//
+// Software pipeline over groups of U terms:
+//   scalar loads of B for group g+1 and of the activation offsets for group g+2,
+//   vector loads of A for group g+1,
+//   multiply-accumulates of group g.
+// Scalar loads return out of order, so the only safe wait is "all of them"; it sits at the
+// top of a stage, before the next scalar loads are issued, and therefore never waits for
+// loads younger than one stage.
+//
+// Split (Eq. output_split in bias form): the accumulated word holds N + HI segments
+// (HI = taps per B word - 1).  Every segment but the top one starts from a bias of 2^(S-1)
+// when data are signed, so each is read as a non-negative field; the top segment is read
+// with a plain (arithmetic) shift and may be narrower than S bits.  All N + HI fields go to
+// int32 registers of the lane; the overlap-add of Theorem 2 (segments N.. of block x-1 land
+// on segments 0.. of block x) happens once, in int32, after the last split, through a DPP
+// move from the previous lane.  A segment therefore collects at most M*min(K,N) products,
+// as in the paper's guard-bit rule for this case.
+//
+// Lane mapping: rows of at most 64 blocks: several whole rows per wave, lanes only for the
+// blocks that hold input values; the last block of a row stores its high segments itself.
+// Longer rows: segments of 63 blocks whose lane 0 recomputes the preceding block.
+//
+// The term range of a row group can be divided over the 2 or 4 waves of the workgroup;
+// partial int32 sums meet in LDS (two passes over half of the channels each, to keep the
+// buffer small) and every wave finishes an equal share of the channels.
+#ifndef HIKONV_CONV2D_SREG_H
+#define HIKONV_CONV2D_SREG_H
+
+#include "hikonv_conv2d_kernel.h"
+
+namespace hikonv {
+
+struct LaneMapS {
+    int n, ho, xi;
+    bool active;   // lane stands for a block of an existing output row
+    bool recv;     // the previous lane holds the preceding block of the same row
+    bool store;    // lane writes its own N outputs
+    bool store_hi; // lane also writes its high segments (no lane owns the following block)
+};
+
+__device__ __forceinline__ LaneMapS map_lane_sreg(const Conv2dArgs &p, int64_t row_group, int lane)
+{
+    LaneMapS m;
+    int64_t row;
+    if (p.segs == 0) {
+        const int rw = lane / p.Lr;
+        const int l = lane - rw * p.Lr;
+        m.xi = l + 1;
+        row = row_group * p.rows_per_wave + rw;
+        m.active = rw < p.rows_per_wave && row < p.wave_rows;
+        m.recv = l != 0;
+        m.store = m.active;
+        m.store_hi = m.active && l == p.Lr - 1;
+    } else {
+        row = row_group / p.segs;
+        const int seg = (int)(row_group - row * p.segs);
+        m.xi = seg * 63 + lane;
+        m.active = row < p.wave_rows && m.xi < p.Xs;
+        m.recv = lane != 0;
+        m.store = m.active && lane != 0;
+        m.store_hi = false;
+    }
+    if (!m.active) {
+        row = 0;
+        m.xi = 0;
+    }
+    m.n = (int)(row / p.Ho);
+    m.ho = (int)(row - (int64_t)m.n * p.Ho);
+    return m;
+}
+
+// Overlap-add with the previous lane's high segments, {-1,+1} correction, bounds and stride
+// handling, store of one output channel.  v / sa: N own fields then HI high fields.
+template <int N, int HI, bool BIP>
+__device__ __forceinline__ void finish_channel(const Conv2dArgs &p, const LaneMapS &m, int co, const int32_t (&v)[N + HI],
+                                               const int32_t (&sa)[N + HI])
+{
+    int32_t o[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) o[j] = v[j];
+#pragma unroll
+    for (int j = 0; j < HI; ++j) {
+        const int32_t r = (int32_t)lane_shr1((uint32_t)v[N + j]); // every lane takes part in the move
+        if (j < N) o[j] += m.recv ? r : 0;
+    }
+    if (co >= p.Co) return;
+    int32_t *yrow = p.y + (((int64_t)m.n * p.Co + co) * p.Ho + m.ho) * p.Wo;
+    const int x = m.xi - 1;
+#pragma unroll
+    for (int j = 0; j < N + HI; ++j) {
+        const bool own = j < N;
+        if (!(own ? m.store : m.store_hi)) continue;
+        const int w1 = x * N + j - p.off; // stride-1 output column
+        if (w1 >= 0 && w1 < p.Wo1 && (p.stride == 1 || w1 % p.stride == 0)) {
+            const int wo = p.stride == 1 ? w1 : w1 / p.stride;
+            const int32_t val = own ? o[j] : v[j];
+            yrow[wo] = BIP ? bipolar_value(p.ct, co, m.ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, val, sa[j]) : val;
+        }
+    }
+}
+
+// sa (fields of the all-ones accumulator) -> window sums of a at the lane's own outputs
+// (overlap-added) followed by its high segments
+template <int N, int HI>
+__device__ __forceinline__ void finish_sum_a(const LaneMapS &m, int32_t (&sa)[N + HI])
+{
+#pragma unroll
+    for (int j = 0; j < HI; ++j) {
+        const int32_t r = (int32_t)lane_shr1((uint32_t)sa[N + j]);
+        if (j < N) sa[j] += m.recv ? r : 0;
+    }
+}
+
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+// Scalar loads and the packed multiply-accumulate are written as instructions: the B words
+// must stay in SGPRs, the four products of a group must chain on the accumulator (no
+// re-association into a separate sum), and the wait for the scalar loads must sit where the
+// pipeline wants it.  Every value loaded by sload_* is undefined until the next
+// wait_scalar_loads that names it; it is not read, copied or carried over a loop edge before.
+template <int BYTE_OFFSET>
+__device__ __forceinline__ void sload_x8(u32x8 &dst, const void *uniform_ptr)
+{
+    asm volatile("s_load_dwordx8 %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
+}
+__device__ __forceinline__ void sload_x4(i32x4 &dst, const void *uniform_ptr)
+{
+    asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=&s"(dst) : "s"(uniform_ptr));
+}
+__device__ __forceinline__ void wait_scalar_loads(u32x8 (&b)[4], i32x4 &o)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(b[0]), "+s"(b[1]), "+s"(b[2]), "+s"(b[3]), "+s"(o));
+}
+
+// acc += a * b with b in a scalar register: v_mad_u64_u32 / v_mad_i64_i32 (Theorem 1's
+// multiply fused with the accumulation of products before a split)
+template <bool SIGNED>
+__device__ __forceinline__ void mad_sreg(uint64_t &acc, uint32_t a, uint32_t b_uniform)
+{
+    acc = mad_wide<SIGNED>(a, b_uniform, acc);
+    asm("" : "+v"(acc)); // opaque: the products of a group chain on the accumulator, no separate sum
+}
+
+// 2^(S-1) in every segment but the top one
+template <int NF>
+__device__ __forceinline__ uint64_t field_bias(int S)
+{
+    uint64_t bias = 0;
+#pragma unroll
+    for (int j = 0; j < NF - 1; ++j) bias += (uint64_t)1 << (S * j + S - 1);
+    return bias;
+}
+
+template <int N, int HI, bool ANY_SIGNED, bool BIP>
+__global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
+{
+    constexpr int U = kTermGroup;
+    constexpr int CO_T = 8;
+    constexpr int CE = CO_T + (BIP ? 1 : 0); // BIP: one more accumulator collects sum a (all-ones weights)
+    constexpr int NF = N + HI;
+    static_assert(U == 4, "offset table is read four terms at a time");
+    extern __shared__ __attribute__((aligned(16))) int32_t s_red[]; // [4 waves][5*NF][64]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ks = wave % p.ksplit; // which slice of the term range
+    const int64_t row_group = (int64_t)blockIdx.x * (4 / p.ksplit) + wave / p.ksplit;
+    const LaneMapS m = map_lane_sreg(p, row_group, lane);
+    const int co0 = blockIdx.y * CO_T;
+    // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
+    const uint32_t lane_byte = (uint32_t)((((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi) * 4);
+    // weight rows of this channel tile: 32 bytes per term
+    const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)(p.cog0 + blockIdx.y) * p.terms_pad * 32;
+    const char *trow = reinterpret_cast<const char *>(p.toff); // 16 bytes per term group
+    const char *abytes = reinterpret_cast<const char *>(p.apk);
+    const uint32_t ones = p.ones_word0;
+
+    const int S = p.S;
+    const uint64_t bias = ANY_SIGNED ? field_bias<NF>(S) : 0;
+    uint64_t acc[CE];
+    int32_t out[CE][NF];
+#pragma unroll
+    for (int c = 0; c < CE; ++c) {
+        acc[c] = bias;
+#pragma unroll
+        for (int j = 0; j < NF; ++j) out[c][j] = 0;
+    }
+    int since = 0, nsplit = 0;
+
+    auto split = [&]() {
+        // shift amounts and masks are recomputed here from an opaque copy of S so that they do
+        // not occupy scalar registers across the term loop
+        int Sl = S;
+        asm volatile("" : "+s"(Sl));
+        const uint32_t fm = (1u << Sl) - 1u;
+#pragma unroll
+        for (int c = 0; c < CE; ++c) {
+            const uint64_t a = acc[c];
+#pragma unroll
+            for (int j = 0; j < NF - 1; ++j) out[c][j] += (int32_t)((uint32_t)(a >> (Sl * j)) & fm);
+            out[c][NF - 1] += ANY_SIGNED ? (int32_t)((int64_t)a >> (Sl * (NF - 1))) : (int32_t)(uint32_t)(a >> (Sl * (NF - 1)));
+            acc[c] = ANY_SIGNED ? field_bias<NF>(Sl) : 0;
+        }
+        since = 0;
+        ++nsplit;
+    };
+
+    // this wave's slice of the term groups
+    const int groups = p.terms_pad / U;
+    const int per = (groups + p.ksplit - 1) / p.ksplit;
+    const int g_begin = ks * per;
+    int g_end = g_begin + per;
+    if (g_end > groups) g_end = groups;
+
+    if (g_begin < g_end) { // wave-uniform; barriers are outside this part
+        const int g_last = groups - 1; // the weight rows end at terms_pad; the offset table has one more group
+        u32x8 b0[U], b1[U];
+        i32x4 o; // offsets of the next group; refilled right after the address adds that read it
+        uint32_t a0[U], a1[U];
+        auto issue_b = [&](u32x8 (&b)[U], int g) {
+            const char *src = wrow + (int64_t)(g < g_last ? g : g_last) * (U * 32);
+            sload_x8<0>(b[0], src);
+            sload_x8<32>(b[1], src);
+            sload_x8<64>(b[2], src);
+            sload_x8<96>(b[3], src);
+        };
+        auto issue_o = [&](i32x4 &o, int g) { sload_x4(o, trow + (int64_t)(g < groups ? g : groups) * 16); };
+        auto load_a = [&](uint32_t (&a)[U], const i32x4 &o) {
+            // uniform base + 32-bit lane offset: one VALU add per load.  The adds are pinned
+            // here, ahead of the scalar load that refills o.
+            uint32_t off[U] = {lane_byte + ((uint32_t)o.x << 2), lane_byte + ((uint32_t)o.y << 2),
+                               lane_byte + ((uint32_t)o.z << 2), lane_byte + ((uint32_t)o.w << 2)};
+            asm volatile("" : "+v"(off[0]), "+v"(off[1]), "+v"(off[2]), "+v"(off[3]));
+#pragma unroll
+            for (int u = 0; u < U; ++u) a[u] = *reinterpret_cast<const uint32_t *>(abytes + off[u]);
+        };
+        auto multiply = [&](const uint32_t (&a)[U], const u32x8 (&b)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                mad_sreg<ANY_SIGNED>(acc[0], a[u], b[u].s0);
+                mad_sreg<ANY_SIGNED>(acc[1], a[u], b[u].s1);
+                mad_sreg<ANY_SIGNED>(acc[2], a[u], b[u].s2);
+                mad_sreg<ANY_SIGNED>(acc[3], a[u], b[u].s3);
+                mad_sreg<ANY_SIGNED>(acc[4], a[u], b[u].s4);
+                mad_sreg<ANY_SIGNED>(acc[5], a[u], b[u].s5);
+                mad_sreg<ANY_SIGNED>(acc[6], a[u], b[u].s6);
+                mad_sreg<ANY_SIGNED>(acc[7], a[u], b[u].s7);
+                if (BIP) mad_sreg<false>(acc[CE - 1], a[u], ones);
+            }
+            since += U;
+            if (since >= p.split_terms) split(); // split_terms is a multiple of U
+        };
+
+        // prologue: B and A of the first group, offsets of the second
+        issue_b(b0, g_begin);
+        issue_o(o, g_begin);
+        wait_scalar_loads(b0, o);
+        load_a(a0, o);
+        issue_o(o, g_begin + 1);
+        wait_scalar_loads(b0, o);
+        for (int g = g_begin; g < g_end; g += 2) {
+            // group g from (a0, b0); o holds the offsets of g+1
+            issue_b(b1, g + 1);
+            load_a(a1, o);
+            issue_o(o, g + 2);
+            multiply(a0, b0);
+            wait_scalar_loads(b1, o);
+            if (g + 1 >= g_end) break;
+            // group g+1 from (a1, b1); o holds the offsets of g+2
+            issue_b(b0, g + 2);
+            load_a(a0, o);
+            issue_o(o, g + 3);
+            multiply(a1, b1);
+            wait_scalar_loads(b0, o);
+        }
+    }
+    if (since) split();
+
+    if (BIP && g_begin < g_end && g_end == p.terms_pad / U && p.terms_pad != p.terms) {
+        // the padding terms of the last group (offset 0, zero B words) still met the all-ones
+        // word: take their contribution out of the sum of a again
+        const uint32_t a = *reinterpret_cast<const uint32_t *>(abytes + lane_byte);
+        const uint64_t w = (uint64_t)a * ones * (uint32_t)(p.terms_pad - p.terms);
+        const uint32_t fm = (1u << S) - 1u;
+#pragma unroll
+        for (int j = 0; j < NF - 1; ++j) out[CE - 1][j] -= (int32_t)((uint32_t)(w >> (S * j)) & fm);
+        out[CE - 1][NF - 1] -= (int32_t)(uint32_t)(w >> (S * (NF - 1)));
+    }
+
+    // remove the biases: every split added 2^(S-1) to each segment but the top one
+    if (ANY_SIGNED) {
+        const int32_t unbias = nsplit * (1 << (S - 1));
+#pragma unroll
+        for (int c = 0; c < CE; ++c)
+#pragma unroll
+            for (int j = 0; j < NF - 1; ++j) out[c][j] -= unbias;
+    }
+
+    int32_t sa[NF];
+#pragma unroll
+    for (int j = 0; j < NF; ++j) sa[j] = 0;
+
+    if (p.ksplit == 1) {
+        if (BIP) {
+#pragma unroll
+            for (int j = 0; j < NF; ++j) sa[j] = out[CE - 1][j];
+            finish_sum_a<N, HI>(m, sa);
+        }
+#pragma unroll
+        for (int c = 0; c < CO_T; ++c) finish_channel<N, HI, BIP>(p, m, co0 + c, out[c], sa);
+        return;
+    }
+
+    // ksplit > 1: two passes through LDS, pass 0 = channels 0..3 (and sum a), pass 1 = channels 4..7.
+    // Slot s of a pass holds one channel: [wave][s*NF + j][lane].
+    constexpr int SLOTS = 5;
+    const int w0 = wave - ks; // first wave of this row group
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass) __syncthreads(); // pass 0 has been read
+        int32_t *dst = s_red + (wave * SLOTS * NF) * 64 + lane;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int j = 0; j < NF; ++j) dst[(s * NF + j) * 64] = out[pass * 4 + s][j];
+        if (BIP && pass == 0) {
+#pragma unroll
+            for (int j = 0; j < NF; ++j) dst[(4 * NF + j) * 64] = out[CE - 1][j];
+        }
+        __syncthreads();
+        if (BIP && pass == 0) {
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                int32_t v = 0;
+                for (int k2 = 0; k2 < p.ksplit; ++k2) v += s_red[((w0 + k2) * SLOTS * NF + 4 * NF + j) * 64 + lane];
+                sa[j] = v;
+            }
+            finish_sum_a<N, HI>(m, sa);
+        }
+        for (int s = ks; s < 4; s += p.ksplit) { // wave-uniform trip count
+            int32_t v[NF];
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                int32_t t = 0;
+                for (int k2 = 0; k2 < p.ksplit; ++k2) t += s_red[((w0 + k2) * SLOTS * NF + s * NF + j) * 64 + lane];
+                v[j] = t;
+            }
+            finish_channel<N, HI, BIP>(p, m, co0 + pass * 4 + s, v, sa);
+        }
+    }
+}
+
+inline size_t conv2d_sreg_lds(const Conv2dArgs &a, int n, int hi)
+{
+    return a.ksplit > 1 ? (size_t)4 * 5 * (n + hi) * 64 * 4 : 0;
+}
+
+template <int N, bool ANY_SIGNED, bool BIP>
+inline void launch_conv2d_sreg_n(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream)
+{
+    const size_t lds = conv2d_sreg_lds(a, N, hi);
+    switch (hi) {
+    case 0: hipLaunchKernelGGL((k_conv2d_sreg<N, 0, ANY_SIGNED, BIP>), g, dim3(256), lds, stream, a); break;
+    case 1:
+        if constexpr (N >= 1) hipLaunchKernelGGL((k_conv2d_sreg<N, 1, ANY_SIGNED, BIP>), g, dim3(256), lds, stream, a);
+        break;
+    case 2:
+        if constexpr (N >= 2) hipLaunchKernelGGL((k_conv2d_sreg<N, 2, ANY_SIGNED, BIP>), g, dim3(256), lds, stream, a);
+        break;
+    default: break;
+    }
+}
+
+template <bool ANY_SIGNED, bool BIP>
+inline hipError_t launch_conv2d_sreg_sw(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream)
+{
+    switch (a.N) {
+    case 1: launch_conv2d_sreg_n<1, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 2: launch_conv2d_sreg_n<2, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 3: launch_conv2d_sreg_n<3, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 4: launch_conv2d_sreg_n<4, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 5: launch_conv2d_sreg_n<5, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 6: launch_conv2d_sreg_n<6, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 7: launch_conv2d_sreg_n<7, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 8: launch_conv2d_sreg_n<8, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_conv2d_sreg_unsigned(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream);
+hipError_t launch_conv2d_sreg_signed(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream);
+hipError_t launch_conv2d_sreg_bipolar(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream);
+
+} // namespace hikonv
+#endif

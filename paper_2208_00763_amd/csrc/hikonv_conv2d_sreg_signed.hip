@@ -1,0 +1,9 @@
+// Instantiations of the scalar-register layer kernel: signed data.
+#include "hikonv_conv2d_sreg.h"
+
+namespace hikonv {
+hipError_t launch_conv2d_sreg_signed(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream)
+{
+    return launch_conv2d_sreg_sw<true, false>(a, hi, g, stream);
+}
+} // namespace hikonv

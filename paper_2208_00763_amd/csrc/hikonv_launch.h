@@ -111,12 +111,24 @@ struct Conv2dArgs {
     int Co, cog0;            // output channels to write, first weight group
     int64_t chunk_stride;    // words between chunk planes of apk
     int rows_per_wave, segs; // lane mapping
+    int sreg;                // 1: k_conv2d_sreg (weights in scalar registers), 0: the LDS-staged kernels
+    int Lr;                  // k_conv2d_sreg, segs == 0: lanes per row (blocks that hold input values)
     int64_t wave_rows;       // total rows = Nimg*Ho
     int Wo;                  // strided output width
     int32_t *y;              // [Nimg][Co][Ho][Wo]
 };
 hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed, int co_tile,
                                 hipStream_t stream);
+
+// plans this kernel covers: 32x32+64 multiply, at most three taps per B word and no more
+// high segments than own segments, a whole number of term groups between splits
+inline bool conv2d_sreg_applicable(int N, int Kp, int chunks, int split_terms, bool wide, bool bipolar)
+{
+    if (!wide || N < 1 || N > 8 || Kp < 1 || Kp > 3 || Kp - 1 > N) return false;
+    if (split_terms < kTermGroup) return false;
+    if (bipolar && chunks != 1) return false;
+    return true;
+}
 
 struct BipolarFixArgs {
     int32_t *y;              // in: sum a*beta; out: sum x*w
