@@ -22,6 +22,9 @@ _lib.oracle_conv1d.restype = C.c_int
 _lib.oracle_conv2d.argtypes = [_i8p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _i8p, C.c_int, C.c_int,
                                C.c_int, C.c_int, C.c_int, C.c_int, _i32p]
 _lib.oracle_conv2d.restype = C.c_int
+_lib.oracle_conv3d.argtypes = [_i8p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _i8p, C.c_int, C.c_int,
+                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _i32p]
+_lib.oracle_conv3d.restype = C.c_int
 _lib.oracle_relu_requant.argtypes = [_i32p, C.c_int64, C.c_int, C.c_int, _i8p]
 _lib.oracle_maxpool2x2.argtypes = [_i8p, C.c_int, C.c_int, C.c_int, C.c_int, _i8p]
 _lib.oracle_container_bits.argtypes = [C.c_int]
@@ -78,6 +81,23 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0) -> np.nd
     rc = _lib.oracle_conv2d(x, xu, n, c, h, wd, w, wu, co, kh, kw, stride, pad, y)
     if rc != 0:
         raise OverflowError("2-D convolution result does not fit int32")
+    return y
+
+
+def conv3d(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0) -> np.ndarray:
+    """Cross-correlation layer on NCDHW x and [Co][C][Kd][Kh][Kw] w (int8 or uint8), int32 NCDHW out."""
+    x, xu = _bytes(x)
+    w, wu = _bytes(w)
+    n, c, d, h, wd = x.shape
+    co, c2, kd, kh, kw = w.shape
+    assert c == c2
+    do = (d + 2 * pad - kd) // stride + 1
+    ho = (h + 2 * pad - kh) // stride + 1
+    wo = (wd + 2 * pad - kw) // stride + 1
+    y = np.zeros((n, co, max(do, 0), max(ho, 0), max(wo, 0)), dtype=np.int32)
+    rc = _lib.oracle_conv3d(x, xu, n, c, d, h, wd, w, wu, co, kd, kh, kw, stride, pad, y)
+    if rc != 0:
+        raise OverflowError("3-D convolution result does not fit int32")
     return y
 
 

@@ -131,6 +131,59 @@ int oracle_conv2d(const int8_t *x, int x_unsigned, int N, int C, int H, int W,
 }
 
 /*
+ * Three-dimensional convolution layer: the paper notes that the DNN extension carries
+ * over to higher-dimensional convolutions (end of Section "General purpose processors");
+ * the definition is Eq. (conv_org) with one more spatial axis, zero padding `pad` on all
+ * six sides and one output stride for the three axes:
+ *   O[n][co][d][h][w] = sum_{ci,kd,kh,kw} Ipad[n][ci][d*s+kd][h*s+kh][w*s+kw] * W[co][ci][kd][kh][kw]
+ * with Do = (D + 2*pad - Kd)/s + 1, Ho, Wo likewise (cross-correlation, kernel not
+ * flipped).  x is NCDHW, w is [Co][C][Kd][Kh][Kw], y is NCDHW.
+ * Returns 0, or -1 if a sum does not fit int32.
+ */
+int oracle_conv3d(const int8_t *x, int x_unsigned, int N, int C, int D, int H, int W,
+                  const int8_t *w, int w_unsigned, int Co, int Kd, int Kh, int Kw,
+                  int stride, int pad, int32_t *y)
+{
+    int Do = (D + 2 * pad - Kd) / stride + 1;
+    int Ho = (H + 2 * pad - Kh) / stride + 1;
+    int Wo = (W + 2 * pad - Kw) / stride + 1;
+    int bad = 0;
+    if (D + 2 * pad < Kd || H + 2 * pad < Kh || W + 2 * pad < Kw) return 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : bad)
+    for (int n = 0; n < N; ++n) {
+        for (int co = 0; co < Co; ++co) {
+            for (int d = 0; d < Do; ++d) {
+                for (int h = 0; h < Ho; ++h) {
+                    for (int wo = 0; wo < Wo; ++wo) {
+                        int64_t acc = 0;
+                        for (int ci = 0; ci < C; ++ci) {
+                            for (int kd = 0; kd < Kd; ++kd) {
+                                for (int kh = 0; kh < Kh; ++kh) {
+                                    for (int kw = 0; kw < Kw; ++kw) {
+                                        int id = d * stride + kd - pad;
+                                        int ih = h * stride + kh - pad;
+                                        int iw = wo * stride + kw - pad;
+                                        int64_t v = 0;
+                                        if (id >= 0 && id < D && ih >= 0 && ih < H && iw >= 0 && iw < W)
+                                            v = byte_value(x, ((((int64_t)n * C + ci) * D + id) * H + ih) * W + iw,
+                                                           x_unsigned);
+                                        acc += v * byte_value(w, ((((int64_t)co * C + ci) * Kd + kd) * Kh + kh) * Kw + kw,
+                                                              w_unsigned);
+                                    }
+                                }
+                            }
+                        }
+                        if (acc > INT32_MAX || acc < INT32_MIN) bad |= 1;
+                        y[((((int64_t)n * Co + co) * Do + d) * Ho + h) * Wo + wo] = (int32_t)acc;
+                    }
+                }
+            }
+        }
+    }
+    return bad ? -1 : 0;
+}
+
+/*
  * Activation + requantisation between layers of the complete-model experiment
  * (Section "Complete model evaluation": all calculations in integers).  The
  * paper gives no rule; the reading used here is

@@ -130,6 +130,57 @@ def test_conv2d_is_cross_correlation():
     assert np.array_equal(y[0, 0], x[0, 0, 0:3, 2:6])
 
 
+@pytest.mark.parametrize("stride,pad", [(1, 0), (1, 1), (2, 1), (2, 0), (3, 2)])
+@pytest.mark.parametrize("signed", [(True, True), (False, True), (False, False)])
+def test_conv3d_matches_torch(stride, pad, signed):
+    a_s, w_s = signed
+    x = _rand((2, 3, 6, 7, 9), 4, a_s)
+    w = _rand((4, 3, 3, 2, 3), 4, w_s)
+    got = direct.conv3d(x, w, stride, pad)
+    ref = torch.nn.functional.conv3d(torch.from_numpy(x.astype(np.float64)),
+                                     torch.from_numpy(w.astype(np.float64)), stride=stride, padding=pad)
+    assert np.array_equal(got, ref.numpy().astype(np.int64))
+
+
+def test_conv3d_brute_force_tiny():
+    x = _rand((1, 2, 3, 4, 5), 3, True)
+    w = _rand((2, 2, 2, 3, 2), 3, True)
+    pad, stride = 1, 2
+    n, c, d, h, wd = x.shape
+    co, _, kd, kh, kw = w.shape
+    xp = np.zeros((n, c, d + 2 * pad, h + 2 * pad, wd + 2 * pad), dtype=np.int64)
+    xp[:, :, pad:pad + d, pad:pad + h, pad:pad + wd] = x
+    do, ho, wo = ((d + 2 * pad - kd) // stride + 1, (h + 2 * pad - kh) // stride + 1,
+                  (wd + 2 * pad - kw) // stride + 1)
+    ref = np.zeros((n, co, do, ho, wo), dtype=np.int64)
+    for o in range(co):
+        for a in range(do):
+            for i in range(ho):
+                for j in range(wo):
+                    ref[0, o, a, i, j] = int((xp[0, :, a * stride:a * stride + kd, i * stride:i * stride + kh,
+                                                 j * stride:j * stride + kw] * w[o].astype(np.int64)).sum())
+    assert np.array_equal(direct.conv3d(x, w, stride, pad), ref)
+
+
+def test_conv3d_special_cases():
+    # depth 1 with a depth-1 kernel is the 2-D layer; a kernel that is 1 at one position
+    # (kd, kh, kw) = (1, 0, 2) reads that voxel (cross-correlation, no flip on any axis)
+    x = _rand((2, 3, 1, 6, 7), 4, True)
+    w = _rand((4, 3, 1, 3, 3), 4, True)
+    assert np.array_equal(direct.conv3d(x, w, 1, 1 * 0)[:, :, 0], direct.conv2d(x[:, :, 0], w[:, :, 0], 1, 0))
+    v = np.arange(1, 121, dtype=np.int8).reshape(1, 1, 4, 5, 6)
+    k = np.zeros((1, 1, 2, 3, 3), dtype=np.int8)
+    k[0, 0, 1, 0, 2] = 1
+    assert np.array_equal(direct.conv3d(v, k, 1, 0)[0, 0], v[0, 0, 1:4, 0:3, 2:6])
+    # linear in the kernel's depth slices: the 3-D layer is the sum over kd of 2-D layers on shifted depth slices
+    x = _rand((1, 2, 4, 5, 6), 4, False)
+    w = _rand((3, 2, 3, 3, 3), 4, True)
+    y = direct.conv3d(x, w, 1, 0)
+    for d in range(y.shape[2]):
+        acc = sum(direct.conv2d(x[:, :, d + kd], w[:, :, kd], 1, 0).astype(np.int64) for kd in range(3))
+        assert np.array_equal(y[:, :, d], acc)
+
+
 def test_relu_requant_hand_values():
     acc = np.array([-5, 0, 1, 7, 8, 15, 16, 127, 128, 1000, -2**31, 2**31 - 1], dtype=np.int32)
     got = direct.relu_requant(acc, 3, 15)
