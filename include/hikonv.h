@@ -178,14 +178,25 @@ int hikonv_pack_weights(const hikonv_plan_t *plan, const void *w_dev, int Co, in
 
 /*
  * hikonv_conv2d -- packed DNN convolution layer (Eq. conv_org, Theorem 3),
- * cross-correlation with zero padding `pad` (0 <= pad <= Kw-1, Kh-1) and
- * `stride`:  O[n][co][h][w] = sum_{ci,kh,kw} Ipad[n][ci][h s+kh][w s+kw] W[co][ci][kh][kw].
- * plan: mode DNN, taps == Kw, (L_A,L_B,L_acc) = (32,32,64) or (24,24,32).
+ * cross-correlation with zero padding `pad` and `stride`:
+ *   O[n][co][h][w] = sum_{ci,kh,kw} Ipad[n][ci][h s+kh][w s+kw] W[co][ci][kh][kw].
+ * plan: mode DNN, (L_A,L_B,L_acc) = (32,32,64) or (24,24,32), and
+ *   taps == Kw: rows are convolved at column stride 1 and every stride-th result
+ *     is stored (0 <= pad <= Kw-1); or
+ *   stride > 1 and taps == ceil(Kw/stride) (!= Kw): polyphase form.  The s column
+ *     phases of each padded input row are packed as separate channels and phase p
+ *     meets the kernel taps p, p+s, p+2s, ... (zero beyond Kw), so that
+ *       O[..][w] = sum_p sum_j Ipad_p[w+j] W[..][j s+p],  Ipad_p[i] = Ipad[s i+p]:
+ *     a sum of stride-1 row convolutions with ceil(Kw/s) taps, added in the packed
+ *     domain like channels are (Theorem 3); M counts (channel, kernel row, phase)
+ *     products.  No multiply is spent on discarded columns.  Any pad >= 0.  Not
+ *     for {-1,+1} layers.
  * x_dev: NCHW in x_format (bit-dense rows are the W rows).  y_dev: NCHW int32.
  * workspace_dev: at least hikonv_conv2d_workspace_bytes() bytes, 256-byte aligned.
  * hikonv_conv2d packs the raw weights w_dev ([Co][C][Kh][Kw], one per byte) into
  * the workspace on every call; hikonv_conv2d_prepacked takes weights already
- * packed by hikonv_pack_weights with the same plan.
+ * packed by hikonv_pack_weights (taps == Kw) or hikonv_pack_weights_ex (either
+ * form) with the same plan and stride.
  */
 size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co,
                                      int Kh, int Kw, int stride, int pad, int prepacked);
@@ -196,6 +207,37 @@ int hikonv_conv2d_prepacked(const hikonv_plan_t *plan, const void *x_dev, int x_
                             int H, int W, const void *w_packed_dev, int Co, int Kh, int Kw, int stride,
                             int pad, void *workspace_dev, size_t workspace_bytes, int32_t *y_dev,
                             void *stream);
+
+/*
+ * Weight pre-packing for any layer form: Kd kernel depth slices (1 for a 2-D
+ * layer) and the column stride the layer will be called with (it selects the
+ * polyphase form exactly as in hikonv_conv2d: plan->taps == ceil(Kw/stride)).
+ * w_dev: [Co][C][Kd][Kh][Kw], one value per byte.
+ */
+size_t hikonv_packed_weights_bytes_ex(const hikonv_plan_t *plan, int Co, int C, int Kd, int Kh, int Kw,
+                                      int stride);
+int hikonv_pack_weights_ex(const hikonv_plan_t *plan, const void *w_dev, int Co, int C, int Kd, int Kh,
+                           int Kw, int stride, void *packed_dev, void *stream);
+
+/*
+ * hikonv_conv3d -- packed three-dimensional convolution layer (the paper notes
+ * at the end of Section "General purpose processors" that the DNN extension
+ * carries to higher-dimensional convolutions): Eq. conv_org with one more axis,
+ *   O[n][co][d][h][w] = sum_{ci,kd,kh,kw} Ipad[n][ci][d s+kd][h s+kh][w s+kw] W[co][ci][kd][kh][kw],
+ * zero padding `pad` on all six sides, one stride for the three axes.  Every
+ * (ci, kd, kh) input row is one more 1-D row convolution accumulated in the
+ * packed domain (Theorem 3 with the kernel depth as a further outer sum); M
+ * counts (ci, kd, kh[, phase]) products.  plan as for hikonv_conv2d (both stride
+ * forms; not {-1,+1}).  x_dev: NCDHW in x_format (INT8 or BITDENSE).  w_dev:
+ * [Co][C][Kd][Kh][Kw] one value per byte when prepacked == 0, else the output of
+ * hikonv_pack_weights_ex.  y_dev: NCDHW int32.  workspace as for hikonv_conv2d,
+ * sized by hikonv_conv3d_workspace_bytes().
+ */
+size_t hikonv_conv3d_workspace_bytes(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int Co,
+                                     int Kd, int Kh, int Kw, int stride, int pad, int prepacked);
+int hikonv_conv3d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int D, int H,
+                  int W, const void *w_dev, int prepacked, int Co, int Kd, int Kh, int Kw, int stride,
+                  int pad, void *workspace_dev, size_t workspace_bytes, int32_t *y_dev, void *stream);
 
 /* Baseline: direct layer, one v_mad_i32_i24 per product.  x_dev and w_dev one value per byte. */
 int hikonv_conv2d_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int N, int C,

@@ -68,6 +68,10 @@ SIGNATURES = {
     "hikonv_conv1d_requant_unpacked": (_i, [_i, _i, _i, _vp, _i, _i64, _i64, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
     "hikonv_packed_weights_bytes": (_sz, [_pp, _i, _i, _i, _i]),
     "hikonv_pack_weights": (_i, [_pp, _vp, _i, _i, _i, _i, _vp, _vp]),
+    "hikonv_packed_weights_bytes_ex": (_sz, [_pp, _i, _i, _i, _i, _i, _i]),
+    "hikonv_pack_weights_ex": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp]),
+    "hikonv_conv3d_workspace_bytes": (_sz, [_pp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i]),
+    "hikonv_conv3d": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
     "hikonv_conv2d_workspace_bytes": (_sz, [_pp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i]),
     "hikonv_conv2d": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
     "hikonv_conv2d_prepacked": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
@@ -181,6 +185,27 @@ def hikonv_packed_weights_bytes(plan, co, c, kh, kw):
 def hikonv_pack_weights(plan, w, co, c, kh, kw, packed, stream=None):
     _check(lib.hikonv_pack_weights(C.byref(plan), _ptr(w), co, c, kh, kw, _ptr(packed), _stream(stream)),
            "hikonv_pack_weights")
+
+
+def hikonv_packed_weights_bytes_ex(plan, co, c, kd, kh, kw, stride):
+    return lib.hikonv_packed_weights_bytes_ex(C.byref(plan), co, c, kd, kh, kw, stride)
+
+
+def hikonv_pack_weights_ex(plan, w, co, c, kd, kh, kw, stride, packed, stream=None):
+    _check(lib.hikonv_pack_weights_ex(C.byref(plan), _ptr(w), co, c, kd, kh, kw, stride, _ptr(packed),
+                                      _stream(stream)), "hikonv_pack_weights_ex")
+
+
+def hikonv_conv3d_workspace_bytes(plan, n, c, d, h, w, co, kd, kh, kw, stride, pad, prepacked):
+    return lib.hikonv_conv3d_workspace_bytes(C.byref(plan), n, c, d, h, w, co, kd, kh, kw, stride, pad,
+                                             int(prepacked))
+
+
+def hikonv_conv3d(plan, x, x_format, n, c, d, h, w, weights, prepacked, co, kd, kh, kw, stride, pad, workspace, y,
+                  stream=None):
+    _check(lib.hikonv_conv3d(C.byref(plan), _ptr(x), x_format, n, c, d, h, w, _ptr(weights), int(prepacked), co, kd,
+                             kh, kw, stride, pad, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                             _ptr(y), _stream(stream)), "hikonv_conv3d")
 
 
 def hikonv_conv2d_workspace_bytes(plan, n, c, h, w, co, kh, kw, stride, pad, prepacked):

@@ -53,41 +53,81 @@ int conv1d_common(int bits_a, int a_signed, int w_signed, const void *x_dev, int
     return HIKONV_OK;
 }
 
+// Geometry of a layer call.  "Packed" quantities describe the rows the kernels see: a
+// polyphase layer packs the column phases of each source channel as separate channels and
+// materialises the horizontal padding; a 3-D layer adds a padded depth axis and counts the
+// kernel's depth x height rows as the rows of a packed channel.
 struct Conv2dGeom {
+    int phases;          // column phases packed separately (= stride) or 1
+    int Ce, We, Kwe;     // packed channels, values per packed row, taps per packed kernel row
+    int padwe;           // horizontal padding that only shifts the read index (0 when materialised)
+    int stride_w;        // column decimation on store (1 when the phases are packed separately)
+    int pad_d, Dp, Do;   // depth padding, padded depth, output depth (0, 1, 1 for a 2-D layer)
+    int Khe;             // kernel rows per packed channel (Kd*Kh)
     int Ho, Wo, Wo1, X, Xs, Hp, terms, terms_pad, n_cog;
     size_t apk_bytes, toff_bytes, wp_bytes, ps_bytes, ct_bytes, sa_bytes;
 };
 
 inline int pad_terms(int terms) { return (terms + kTermGroup - 1) / kTermGroup * kTermGroup; }
 
-int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, int Kh, int Kw, int stride, int pad,
-                Conv2dGeom *g)
+// taps a plan must cover for a kernel row of Kw taps at column stride `stride`, polyphase form
+inline int polyphase_taps(int Kw, int stride) { return (Kw + stride - 1) / stride; }
+
+int conv_geom(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int Co, int Kd, int Kh, int Kw, int stride,
+              int pad, int is3d, Conv2dGeom *g)
 {
     if (!plan) return HIKONV_EINVAL;
-    if (N < 1 || C < 1 || H < 1 || W < 1 || Co < 1 || Kh < 1 || Kw < 1 || stride < 1 || pad < 0) return HIKONV_EINVAL;
-    if (plan->mode != HIKONV_MODE_DNN || plan->taps != Kw || plan->M < 1) return HIKONV_EINVAL;
-    if (plan->N < 1 || plan->K < 1 || plan->S < 1 || plan->chunks != (Kw + plan->K - 1) / plan->K) return HIKONV_EINVAL;
+    if (N < 1 || C < 1 || D < 1 || H < 1 || W < 1 || Co < 1 || Kd < 1 || Kh < 1 || Kw < 1 || stride < 1 || pad < 0)
+        return HIKONV_EINVAL;
+    if (plan->mode != HIKONV_MODE_DNN || plan->M < 1) return HIKONV_EINVAL;
+    const bool polyphase = stride > 1 && plan->taps != Kw && plan->taps == polyphase_taps(Kw, stride);
+    if (!polyphase && plan->taps != Kw) return HIKONV_EINVAL;
+    g->phases = polyphase ? stride : 1;
+    g->Kwe = polyphase ? polyphase_taps(Kw, stride) : Kw;
+    if (plan->N < 1 || plan->K < 1 || plan->S < 1 || plan->chunks != (g->Kwe + plan->K - 1) / plan->K) return HIKONV_EINVAL;
     const bool wide = plan->L_A == 32 && plan->L_B == 32 && (plan->L_acc == 64 || plan->L_acc == 0);
     const bool narrow = plan->L_A == 24 && plan->L_B == 24 && plan->L_acc == 32;
     if (!wide && !narrow) return HIKONV_EUNSUPPORTED;
-    if (plan->N > 8 || plan->chunks > 8 || Kh > 64 || Kw > 64) return HIKONV_EUNSUPPORTED;
-    if (pad > Kw - 1) return HIKONV_EUNSUPPORTED; // the leading padding must fit inside the kernel width
-    if (H + 2 * pad < Kh || W + 2 * pad < Kw) return HIKONV_EINVAL;
+    if (plan->N > 8 || plan->chunks > 8 || Kd > 64 || Kh > 64 || Kw > 64) return HIKONV_EUNSUPPORTED;
+    if (plan->bipolar && (polyphase || is3d)) return HIKONV_EUNSUPPORTED; // the border correction is 2-D, one phase
+    if (!polyphase && pad > Kw - 1) return HIKONV_EUNSUPPORTED; // the leading padding must fit inside the kernel width
+    if (H + 2 * pad < Kh || W + 2 * pad < Kw || (is3d && D + 2 * pad < Kd)) return HIKONV_EINVAL;
+    if (!is3d && (D != 1 || Kd != 1)) return HIKONV_EINVAL;
     if (hikonv_plan_check(plan) != HIKONV_OK) return HIKONV_EOVERFLOW;
-    const int64_t worst = (int64_t)C * Kh * Kw * (plan->bipolar ? 1 : max_abs(plan->bits_a, plan->a_signed) *
-                                                                           max_abs(plan->bits_w, plan->w_signed));
+    const int64_t worst = (int64_t)C * Kd * Kh * Kw * (plan->bipolar ? 1 : max_abs(plan->bits_a, plan->a_signed) *
+                                                                                max_abs(plan->bits_w, plan->w_signed));
     if (worst >= (1LL << 31)) return HIKONV_EOVERFLOW;
+    g->pad_d = is3d ? pad : 0;
+    g->Dp = D + 2 * g->pad_d;
+    g->Do = is3d ? (D + 2 * pad - Kd) / stride + 1 : 1;
+    g->Khe = Kd * Kh;
     g->Ho = (H + 2 * pad - Kh) / stride + 1;
     g->Wo = (W + 2 * pad - Kw) / stride + 1;
-    g->Wo1 = W + 2 * pad - Kw + 1;
-    g->X = (W + pad + plan->N - 1) / plan->N;
+    if (polyphase) {
+        // output w reads the padded source row at s*w + k = s*(w + j) + phase: phase rows of
+        // Wo + Kwe - 1 values, convolved at stride 1 with the phase kernels, no padding left
+        g->Ce = C * stride;
+        g->We = g->Wo + g->Kwe - 1;
+        g->padwe = 0;
+        g->stride_w = 1;
+        g->Wo1 = g->Wo;
+    } else {
+        g->Ce = C;
+        g->We = W;
+        g->padwe = pad;
+        g->stride_w = stride;
+        g->Wo1 = W + 2 * pad - Kw + 1;
+    }
+    g->X = (g->We + g->padwe + plan->N - 1) / plan->N;
     g->Xs = g->X + 1;
     g->Hp = H + 2 * pad;
-    g->terms = C * Kh * plan->chunks;
+    if ((int64_t)g->Ce * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
+    g->terms = g->Ce * g->Khe * plan->chunks;
     g->terms_pad = pad_terms(g->terms);
     g->n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
-    if ((int64_t)plan->chunks * N * C * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
-    g->apk_bytes = round256((size_t)plan->chunks * N * C * g->Hp * g->Xs * 4);
+    if ((int64_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
+    if ((int64_t)N * g->Do * g->Ho >= (1LL << 31) || (int64_t)g->Do * g->Ho >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
+    g->apk_bytes = round256((size_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs * 4);
     g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
     g->toff_bytes = round256((size_t)(g->terms_pad + kTermGroup) * 4);
     g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
@@ -96,15 +136,26 @@ int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, i
     return HIKONV_OK;
 }
 
+int conv2d_geom(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, int Kh, int Kw, int stride, int pad,
+                Conv2dGeom *g)
+{
+    return conv_geom(plan, N, C, 1, H, W, Co, 1, Kh, Kw, stride, pad, 0, g);
+}
+
+// C, Kw: the source tensor's channels and kernel width; Khe = Kd*Kh kernel rows per channel
 int pack_weights_impl(const hikonv_plan_t *plan, const Conv2dGeom &g, const void *w_dev, int Co, int C, int Kh,
                       int Kw, void *packed_dev, hipStream_t stream)
 {
     PackWArgs a;
     a.w = static_cast<const uint8_t *>(w_dev);
     a.Co = Co;
-    a.C = C;
-    a.Kh = Kh;
-    a.Kw = Kw;
+    a.C = g.Ce;
+    a.Csrc = C;
+    a.phases = g.phases;
+    a.Kh = g.Khe;
+    a.Kw = g.Kwe;
+    a.Kwsrc = Kw;
+    (void)Kh;
     a.w_signed = plan->w_signed;
     a.bipolar = plan->bipolar;
     a.Kp = plan->K;
@@ -119,17 +170,24 @@ int pack_weights_impl(const hikonv_plan_t *plan, const Conv2dGeom &g, const void
 }
 
 // Geometry part of the activation-packing arguments (source fields are left to the caller).
-PackActArgs pack_act_args(const hikonv_plan_t *plan, const Conv2dGeom &g, int N, int C, int H, int W, int Kh, int pad,
-                          uint32_t *apk, int32_t *toff)
+PackActArgs pack_act_args(const hikonv_plan_t *plan, const Conv2dGeom &g, int N, int C, int D, int H, int W, int Kd,
+                          int Kh, int pad, uint32_t *apk, int32_t *toff)
 {
     PackActArgs pa = {};
     pa.b = plan->bits_a;
     pa.a_signed = plan->a_signed;
     pa.bipolar = plan->bipolar;
     pa.Nimg = N;
-    pa.C = C;
+    pa.C = g.Ce;
+    pa.Csrc = C;
+    pa.phases = g.phases;
+    pa.pad_w_mat = g.phases > 1 ? pad : 0;
+    pa.D = D;
+    pa.Dp = g.Dp;
+    pa.pad_d = g.pad_d;
     pa.H = H;
-    pa.W = W;
+    pa.W = g.We;
+    pa.Wsrc = W;
     pa.pad = pad;
     pa.N = plan->N;
     pa.Kp = plan->K;
@@ -142,16 +200,17 @@ PackActArgs pack_act_args(const hikonv_plan_t *plan, const Conv2dGeom &g, int N,
     pa.toff_entries = g.terms_pad + kTermGroup;
     pa.terms = g.terms;
     pa.Kh = Kh;
-    pa.chunk_stride = (int64_t)N * C * g.Hp * g.Xs;
+    pa.Kd = Kd;
+    pa.chunk_stride = (int64_t)N * g.Ce * g.Dp * g.Hp * g.Xs;
     return pa;
 }
 
-int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,
-                const void *w_dev, int prepacked, int Co, int Kh, int Kw, int stride, int pad, void *workspace_dev,
-                size_t workspace_bytes, int32_t *y_dev, void *stream_v)
+int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int D, int H, int W,
+               const void *w_dev, int prepacked, int Co, int Kd, int Kh, int Kw, int stride, int pad, int is3d,
+               void *workspace_dev, size_t workspace_bytes, int32_t *y_dev, void *stream_v)
 {
     Conv2dGeom g;
-    int rc = conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g);
+    int rc = conv_geom(plan, N, C, D, H, W, Co, Kd, Kh, Kw, stride, pad, is3d, &g);
     if (rc != HIKONV_OK) return rc;
     if (!w_dev || !y_dev) return HIKONV_EINVAL;
     if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE && x_format != HIKONV_FMT_PACKED)
@@ -174,7 +233,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     }
 
     if (x_format != HIKONV_FMT_PACKED) {
-        PackActArgs pa = pack_act_args(plan, g, N, C, H, W, Kh, pad, apk, toff);
+        PackActArgs pa = pack_act_args(plan, g, N, C, D, H, W, Kd, Kh, pad, apk, toff);
         pa.x = x_dev;
         pa.x_format = x_format;
         pa.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
@@ -187,12 +246,16 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.apk = apk;
     ca.wp = reinterpret_cast<const uint32_t *>(wpk);
     ca.Nimg = N;
-    ca.C = C;
-    ca.Ho = g.Ho;
+    ca.C = g.Ce;
+    ca.Ho = g.Do * g.Ho;
+    ca.Ho2d = g.Ho;
+    ca.img_rows = (int64_t)g.Ce * g.Dp * g.Hp;
+    ca.d_rows = (int64_t)stride * g.Hp;
+    ca.stride_w = g.stride_w;
     ca.Wo1 = g.Wo1;
     ca.Kh = Kh;
     ca.stride = stride;
-    ca.off = Kw - 1 - pad;
+    ca.off = g.Kwe - 1 - g.padwe;
     ca.Hp = g.Hp;
     ca.Xs = g.Xs;
     ca.X = g.X;
@@ -202,7 +265,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.M = plan->M;
     ca.terms = g.terms;
     ca.terms_pad = g.terms_pad;
-    ca.chunk_stride = (int64_t)N * C * g.Hp * g.Xs;
+    ca.chunk_stride = (int64_t)N * g.Ce * g.Dp * g.Hp * g.Xs;
     if (g.Xs <= 64) {
         ca.rows_per_wave = 64 / g.Xs;
         ca.segs = 0;
@@ -210,7 +273,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
         ca.rows_per_wave = 1;
         ca.segs = (g.X + 62) / 63;
     }
-    ca.wave_rows = (int64_t)N * g.Ho;
+    ca.wave_rows = (int64_t)N * g.Do * g.Ho;
     ca.Wo = g.Wo;
     const bool wide = plan->L_A == 32;
     const bool any_signed = !plan->bipolar && (plan->a_signed || plan->w_signed);
@@ -228,7 +291,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.sreg = 0;
     if (forced_kernel != 1 && Co >= 8 &&
         conv2d_sreg_applicable(plan->N, plan->K, plan->chunks, split_terms, wide, plan->bipolar != 0)) {
-        const int real = (W + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
+        const int real = (g.We + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
         const int lanes = ca.segs ? 64 : (real < g.X ? real : g.X);
         const int64_t groups_s = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, 64 / lanes);
         ca.sreg = forced_kernel == 2 || (g.terms_pad >= 512 && groups_s * ((Co + 7) / 8) >= 1024) ? 1 : 0;
@@ -236,7 +299,7 @@ int conv2d_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int 
     ca.Lr = g.X;
     if (ca.sreg && ca.segs == 0) {
         // lanes only for the blocks that hold input values in some chunk
-        const int real = (W + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
+        const int real = (g.We + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
         ca.Lr = real < g.X ? real : g.X;
         ca.rows_per_wave = 64 / ca.Lr;
     }
@@ -445,28 +508,62 @@ extern "C" int hikonv_conv1d_requant_unpacked(int bits_a, int bits_w, int signed
         launch_conv1d_requant_unpacked(a, (signedness & HIKONV_A_SIGNED) != 0, static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+
+// weight-side geometry only (no activations): the fields pack_weights_impl reads
+int weights_geom(const hikonv_plan_t *plan, int Co, int C, int Kd, int Kh, int Kw, int stride, Conv2dGeom *g)
+{
+    if (!plan || Co < 1 || C < 1 || Kd < 1 || Kh < 1 || Kw < 1 || stride < 1) return HIKONV_EINVAL;
+    if (plan->mode != HIKONV_MODE_DNN || plan->K < 1 || plan->S < 1 || plan->chunks < 1) return HIKONV_EINVAL;
+    const bool polyphase = stride > 1 && plan->taps != Kw && plan->taps == polyphase_taps(Kw, stride);
+    if (!polyphase && plan->taps != Kw) return HIKONV_EINVAL;
+    if (plan->bipolar && (polyphase || Kd != 1)) return HIKONV_EUNSUPPORTED;
+    *g = Conv2dGeom{};
+    g->phases = polyphase ? stride : 1;
+    g->Kwe = polyphase ? polyphase_taps(Kw, stride) : Kw;
+    if (plan->chunks != (g->Kwe + plan->K - 1) / plan->K) return HIKONV_EINVAL;
+    g->Ce = C * g->phases;
+    g->Khe = Kd * Kh;
+    if ((int64_t)g->Ce * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
+    g->terms = g->Ce * g->Khe * plan->chunks;
+    g->terms_pad = pad_terms(g->terms);
+    g->n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
+    g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
+    g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
+    g->ct_bytes = plan->bipolar ? round256((size_t)Co * Kh * Kh * Kw * Kw * 4) : 0;
+    return HIKONV_OK;
+}
+
+} // namespace
+
+extern "C" size_t hikonv_packed_weights_bytes_ex(const hikonv_plan_t *plan, int Co, int C, int Kd, int Kh, int Kw,
+                                                 int stride)
+{
+    Conv2dGeom g;
+    if (weights_geom(plan, Co, C, Kd, Kh, Kw, stride, &g) != HIKONV_OK) return 0;
+    return g.wp_bytes + g.ps_bytes + g.ct_bytes;
+}
+
 extern "C" size_t hikonv_packed_weights_bytes(const hikonv_plan_t *plan, int Co, int C, int Kh, int Kw)
 {
-    if (!plan || Co < 1 || C < 1 || Kh < 1 || Kw < 1 || plan->chunks < 1) return 0;
-    const size_t n_cog = (size_t)(Co + 7) / 8 + (plan->bipolar ? 1 : 0);
-    size_t bytes = round256(n_cog * pad_terms(C * Kh * plan->chunks) * 8 * 4);
-    if (plan->bipolar)
-        bytes += round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) + round256((size_t)Co * Kh * Kh * Kw * Kw * 4);
-    return bytes;
+    return hikonv_packed_weights_bytes_ex(plan, Co, C, 1, Kh, Kw, 1);
+}
+
+extern "C" int hikonv_pack_weights_ex(const hikonv_plan_t *plan, const void *w_dev, int Co, int C, int Kd, int Kh,
+                                      int Kw, int stride, void *packed_dev, void *stream)
+{
+    if (!w_dev || !packed_dev) return HIKONV_EINVAL;
+    Conv2dGeom g;
+    int rc = weights_geom(plan, Co, C, Kd, Kh, Kw, stride, &g);
+    if (rc != HIKONV_OK) return rc;
+    if (!aligned(packed_dev, 256)) return HIKONV_EINVAL;
+    return pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, packed_dev, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int hikonv_pack_weights(const hikonv_plan_t *plan, const void *w_dev, int Co, int C, int Kh, int Kw,
                                    void *packed_dev, void *stream)
 {
-    if (!plan || !w_dev || !packed_dev || Co < 1 || C < 1 || Kh < 1 || Kw < 1) return HIKONV_EINVAL;
-    if (plan->mode != HIKONV_MODE_DNN || plan->taps != Kw || plan->K < 1 || plan->S < 1) return HIKONV_EINVAL;
-    if (plan->chunks != (Kw + plan->K - 1) / plan->K || !aligned(packed_dev, 256)) return HIKONV_EINVAL;
-    Conv2dGeom g = {};
-    g.n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
-    g.terms_pad = pad_terms(C * Kh * plan->chunks);
-    g.wp_bytes = round256((size_t)g.n_cog * g.terms_pad * 8 * 4);
-    g.ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
-    return pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, packed_dev, static_cast<hipStream_t>(stream));
+    return hikonv_pack_weights_ex(plan, w_dev, Co, C, 1, Kh, Kw, 1, packed_dev, stream);
 }
 
 extern "C" size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N, int C, int H, int W, int Co, int Kh,
@@ -481,8 +578,8 @@ extern "C" int hikonv_conv2d(const hikonv_plan_t *plan, const void *x_dev, int x
                              const void *w_dev, int Co, int Kh, int Kw, int stride, int pad, void *workspace_dev,
                              size_t workspace_bytes, int32_t *y_dev, void *stream)
 {
-    return conv2d_impl(plan, x_dev, x_format, N, C, H, W, w_dev, 0, Co, Kh, Kw, stride, pad, workspace_dev,
-                       workspace_bytes, y_dev, stream);
+    return layer_impl(plan, x_dev, x_format, N, C, 1, H, W, w_dev, 0, Co, 1, Kh, Kw, stride, pad, 0, workspace_dev,
+                      workspace_bytes, y_dev, stream);
 }
 
 extern "C" int hikonv_conv2d_prepacked(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C,
@@ -490,8 +587,25 @@ extern "C" int hikonv_conv2d_prepacked(const hikonv_plan_t *plan, const void *x_
                                        int pad, void *workspace_dev, size_t workspace_bytes, int32_t *y_dev,
                                        void *stream)
 {
-    return conv2d_impl(plan, x_dev, x_format, N, C, H, W, w_packed_dev, 1, Co, Kh, Kw, stride, pad, workspace_dev,
-                       workspace_bytes, y_dev, stream);
+    return layer_impl(plan, x_dev, x_format, N, C, 1, H, W, w_packed_dev, 1, Co, 1, Kh, Kw, stride, pad, 0,
+                      workspace_dev, workspace_bytes, y_dev, stream);
+}
+
+extern "C" size_t hikonv_conv3d_workspace_bytes(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int Co,
+                                                int Kd, int Kh, int Kw, int stride, int pad, int prepacked)
+{
+    Conv2dGeom g;
+    if (conv_geom(plan, N, C, D, H, W, Co, Kd, Kh, Kw, stride, pad, 1, &g) != HIKONV_OK) return 0;
+    return g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
+}
+
+extern "C" int hikonv_conv3d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int D, int H,
+                             int W, const void *w_dev, int prepacked, int Co, int Kd, int Kh, int Kw, int stride,
+                             int pad, void *workspace_dev, size_t workspace_bytes, int32_t *y_dev, void *stream)
+{
+    if (x_format == HIKONV_FMT_PACKED) return HIKONV_EINVAL;
+    return layer_impl(plan, x_dev, x_format, N, C, D, H, W, w_dev, prepacked ? 1 : 0, Co, Kd, Kh, Kw, stride, pad, 1,
+                      workspace_dev, workspace_bytes, y_dev, stream);
 }
 
 extern "C" int hikonv_conv2d_unpacked(int bits_a, int bits_w, int signedness, const void *x_dev, int N, int C, int H,
@@ -560,11 +674,12 @@ extern "C" int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H,
     Conv2dGeom g;
     int rc = conv2d_geom(next_plan, N, C, Hn, Wn, next_Co, next_Kh, next_Kw, next_stride, next_pad, &g);
     if (rc != HIKONV_OK) return rc;
+    if (g.phases != 1) return HIKONV_EUNSUPPORTED; // the fused packing writes one column phase
     if (!next_workspace_dev || !aligned(next_workspace_dev, 256) ||
         next_workspace_bytes < g.apk_bytes + g.toff_bytes + g.sa_bytes)
         return HIKONV_EWORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(next_workspace_dev);
-    PackActArgs pa = pack_act_args(next_plan, g, N, C, Hn, Wn, next_Kh, next_pad, reinterpret_cast<uint32_t *>(ws),
+    PackActArgs pa = pack_act_args(next_plan, g, N, C, 1, Hn, Wn, 1, next_Kh, next_pad, reinterpret_cast<uint32_t *>(ws),
                                    reinterpret_cast<int32_t *>(ws + g.apk_bytes));
     pa.x_format = kPackFromAcc;
     pa.acc = acc_dev;

@@ -8,22 +8,29 @@
 namespace hikonv {
 namespace {
 
-// A[chunk][n][ci][hp][xi] = sum_j f[(xi-1)N + j - chunk*K] 2^(S j), f = row hp-pad of the
-// image (zero outside it; Eq. I_PRIME / Eq. pad_f0).  Word xi = 0 of every row is zero.
-// The leading horizontal padding is not materialised: it only shifts the index at which
-// an output is read (Eq. off).
+// A[chunk][n][c][dp][hp][xi] = sum_j f[(xi-1)N + j - chunk*K] 2^(S j), f = row hp-pad of depth
+// slice dp-pad_d of the image (zero outside it; Eq. I_PRIME / Eq. pad_f0).  Word xi = 0 of
+// every row is zero.  A 2-D layer has one depth slice (Dp = 1).
+// Ordinary layers: the packed channel c is the source channel and f[i] is its value i; the
+// leading horizontal padding is not materialised, it only shifts the index at which an
+// output is read (Eq. off).
+// Polyphase layers (column stride s packed as s phases): packed channel c = (source channel
+// c / s, phase c % s) and f[i] = padded source row at s*i + phase, i.e. source value
+// s*i + phase - pad, so that a stride-s row convolution becomes the sum over the phases of
+// stride-1 row convolutions with the phase kernels.
 __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
 {
-    const int64_t total = (int64_t)p.chunks * p.Nimg * p.C * p.Hp * p.Xs;
+    const int64_t total = (int64_t)p.chunks * p.Nimg * p.C * p.Dp * p.Hp * p.Xs;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     // the first threads also write the table of activation offsets of the terms
-    // t = (ci*Kh + kh)*chunks + chunk  ->  chunk*chunk_stride + (ci*Hp + kh)*Xs
+    // t = ((c*Kd + kd)*Kh + kh)*chunks + chunk  ->  chunk*chunk_stride + ((c*Dp + kd)*Hp + kh)*Xs
     if (idx < p.toff_entries) {
         const int t = (int)idx;
         int32_t off = 0;
         if (t < p.terms) {
-            const int ch = t % p.chunks, kh = (t / p.chunks) % p.Kh, ci = t / (p.chunks * p.Kh);
-            off = (int32_t)(ch * p.chunk_stride + ((int64_t)ci * p.Hp + kh) * p.Xs);
+            const int ch = t % p.chunks, kh = (t / p.chunks) % p.Kh, kd = (t / (p.chunks * p.Kh)) % p.Kd;
+            const int c = t / (p.chunks * p.Kh * p.Kd);
+            off = (int32_t)(ch * p.chunk_stride + (((int64_t)c * p.Dp + kd) * p.Hp + kh) * p.Xs);
         }
         p.toff[t] = off;
     }
@@ -32,12 +39,15 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     int64_t t = idx / p.Xs;
     const int hp = (int)(t % p.Hp);
     t /= p.Hp;
+    const int dp = (int)(t % p.Dp);
+    t /= p.Dp;
     const int64_t nc = t % ((int64_t)p.Nimg * p.C);
     const int ch = (int)(t / ((int64_t)p.Nimg * p.C));
-    const int h = hp - p.pad;
+    const int h = hp - p.pad, d = dp - p.pad_d;
+    const bool inside = xi > 0 && h >= 0 && h < p.H && d >= 0 && d < p.D;
     uint32_t a = 0;
-    if (xi > 0 && h >= 0 && h < p.H && p.x_format == kPackFromAcc) {
-        // fused epilogue of the producing layer (ReLU, shift, clamp, optional 2x2 max-pool)
+    if (inside && p.x_format == kPackFromAcc) {
+        // fused epilogue of the producing layer (ReLU, shift, clamp, optional 2x2 max-pool); 2-D, one phase
         const int32_t *src = p.acc + nc * p.acc_H * p.acc_W;
         const int e0 = (xi - 1) * p.N - ch * p.Kp;
         for (int j = 0; j < p.N; ++j) {
@@ -53,21 +63,27 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
             v = min(max(v, 0) >> p.shift, p.qmax);
             a += (uint32_t)v << (p.S * j);
         }
-    } else if (xi > 0 && h >= 0 && h < p.H) {
-        const uint8_t *rowp = static_cast<const uint8_t *>(p.x) + (nc * p.H + h) * p.row_bytes;
+    } else if (inside) {
+        const int64_t n = nc / p.C;
+        const int c = (int)(nc - n * p.C);
+        const int csrc = c / p.phases, phase = c - csrc * p.phases;
+        const uint8_t *rowp =
+            static_cast<const uint8_t *>(p.x) + (((n * p.Csrc + csrc) * p.D + d) * p.H + h) * p.row_bytes;
         const int e0 = (xi - 1) * p.N - ch * p.Kp;
         for (int j = 0; j < p.N; ++j) {
-            const int i = e0 + j;
+            const int i = e0 + j; // element of the packed row
             if (i < 0 || i >= p.W) continue;
+            const int is = i * p.phases + phase - p.pad_w_mat; // source value
+            if (is < 0 || is >= p.Wsrc) continue;
             int32_t v;
             if (p.x_format == HIKONV_FMT_INT8) {
-                const uint8_t byte = rowp[i];
+                const uint8_t byte = rowp[is];
                 if (p.bipolar)
                     v = (int8_t)byte > 0 ? 1 : 0;
                 else
                     v = p.a_signed ? __builtin_amdgcn_sbfe((int)byte, 0, p.b) : (int)__builtin_amdgcn_ubfe(byte, 0, p.b);
             } else {
-                const int bit = i * p.c;
+                const int bit = is * p.c;
                 const uint32_t w = reinterpret_cast<const uint32_t *>(rowp)[bit >> 5];
                 v = (p.a_signed && !p.bipolar) ? __builtin_amdgcn_sbfe((int)w, bit & 31, p.b)
                                                : (int)__builtin_amdgcn_ubfe(w, bit & 31, p.b);
@@ -78,8 +94,10 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     p.apk[idx] = a;
 }
 
-// B[group][term][8], term = (ci*Kh + kh)*chunks + chunk, word = sum_k g[chunk*K + k] 2^(S k)
-// with g = the reversed kernel row W[co][ci][kh][Kw-1:0] (Eq. I_PRIME).
+// B[group][term][8], term = (c*Kh + kh)*chunks + chunk (Kh counts depth x height kernel rows),
+// word = sum_k g[chunk*K + k] 2^(S k) with g = the reversed kernel row (Eq. I_PRIME) of the
+// packed channel c: the source row W[co][c][kh][Kw-1:0], or, for a polyphase layer, the
+// reversed phase kernel g_phase[j] = W[co][c / s][kh][j*s + phase] (zero beyond the row).
 __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
 {
     const int terms = p.C * p.Kh * p.chunks;
@@ -95,7 +113,8 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
     }
     const int ch = term % p.chunks;
     const int kh = (term / p.chunks) % p.Kh;
-    const int ci = term / (p.chunks * p.Kh);
+    const int c = term / (p.chunks * p.Kh);
+    const int csrc = c / p.phases, phase = c - csrc * p.phases;
     const int co = cog * 8 + c8;
     const bool ones_group = p.bipolar && cog == p.n_cog - 1;
     uint32_t bw = 0;
@@ -103,10 +122,11 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
         const int j = ch * p.Kp + k; // tap of the reversed row
         if (j >= p.Kw) break;
         int32_t v = 0;
+        const int ksrc = (p.Kw - 1 - j) * p.phases + phase; // source tap
         if (ones_group) {
             v = c8 == 0 ? 1 : 0;
-        } else if (co < p.Co) {
-            const uint8_t byte = p.w[(((int64_t)co * p.C + ci) * p.Kh + kh) * p.Kw + (p.Kw - 1 - j)];
+        } else if (co < p.Co && ksrc < p.Kwsrc) {
+            const uint8_t byte = p.w[(((int64_t)co * p.Csrc + csrc) * p.Kh + kh) * p.Kwsrc + ksrc];
             if (p.bipolar)
                 v = (int8_t)byte > 0 ? 1 : 0;
             else
@@ -362,7 +382,7 @@ inline hipError_t grid_1d(int64_t total, dim3 *g)
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
 {
     dim3 g;
-    int64_t threads = (int64_t)a.chunks * a.Nimg * a.C * a.Hp * a.Xs;
+    int64_t threads = (int64_t)a.chunks * a.Nimg * a.C * a.Dp * a.Hp * a.Xs;
     if (threads < a.toff_entries) threads = a.toff_entries;
     hipError_t e = grid_1d(threads, &g);
     if (e != hipSuccess) return e;

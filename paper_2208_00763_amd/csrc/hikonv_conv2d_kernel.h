@@ -42,7 +42,8 @@ struct acc_type<false> {
 
 // lane -> (output row, packed word index xi); block x = xi - 1
 struct LaneMap {
-    int n, ho, xi;
+    int n, ho, xi;   // image, output row inside the image (depth slice * Ho2d + row), packed word index
+    int64_t in_row;  // packed input row that kernel row 0 of this output row reads
     bool active, halo;
 };
 
@@ -69,6 +70,9 @@ __device__ __forceinline__ LaneMap map_lane(const Conv2dArgs &p, int64_t row_gro
     }
     m.n = (int)(row / p.Ho);
     m.ho = (int)(row - (int64_t)m.n * p.Ho);
+    // first packed input row of this output row: image, output depth, output row inside the depth slice
+    const int d = m.ho / p.Ho2d;
+    m.in_row = (int64_t)m.n * p.img_rows + (int64_t)d * p.d_rows + (int64_t)(m.ho - d * p.Ho2d) * p.stride;
     return m;
 }
 
@@ -143,10 +147,10 @@ __device__ __forceinline__ void store_outputs(const Conv2dArgs &p, const LaneMap
         for (int j = 0; j < N; ++j) {
             const int w1 = x * N + j - p.off; // stride-1 output column
             if (w1 >= 0 && w1 < p.Wo1) {
-                if (p.stride == 1)
+                if (p.stride_w == 1)
                     yrow[w1] = out[c][j] - unbias;
-                else if (w1 % p.stride == 0)
-                    yrow[w1 / p.stride] = out[c][j] - unbias;
+                else if (w1 % p.stride_w == 0)
+                    yrow[w1 / p.stride_w] = out[c][j] - unbias;
             }
         }
     }
@@ -161,29 +165,25 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
     const int64_t wave = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const LaneMap m = map_lane(p, wave, lane);
     const int co0 = blockIdx.y * CO_T;
-    const int64_t row_words = p.Xs;
-    const int64_t ci_words = (int64_t)p.Hp * row_words;
-    const uint32_t *a_base = apk + ((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * row_words + m.xi;
+    const uint32_t *a_base = apk + m.in_row * p.Xs + m.xi;
     const uint32_t *w_ptr = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
 
     SplitState<N, CO_T, ANY_SIGNED, WIDE> st;
     st.init(p.S);
     int since = 0, nsplit = 0;
-    for (int ci = 0; ci < p.C; ++ci) {
-        const uint32_t *a_ci = a_base + ci * ci_words;
-        for (int kh = 0; kh < p.Kh; ++kh) {
-            for (int ch = 0; ch < p.chunks; ++ch) {
-                const uint32_t a = a_ci[ch * p.chunk_stride + kh * row_words];
+    // terms in the order of the offset table: channel, kernel row (depth x height), chunk
+    for (int t = 0; t < p.terms; t += p.chunks) {
+        for (int ch = 0; ch < p.chunks; ++ch) {
+            const uint32_t a = a_base[p.toff[t + ch]];
 #pragma unroll
-                for (int c = 0; c < CO_T; ++c) st.mad(c, a, w_ptr[c]);
-                w_ptr += 8;
-            }
-            if (++since == p.M) {
-                asm volatile("" ::: "memory"); // keep the split out of the multiply block (no speculation)
-                st.split();
-                since = 0;
-                ++nsplit;
-            }
+            for (int c = 0; c < CO_T; ++c) st.mad(c, a, w_ptr[c]);
+            w_ptr += 8;
+        }
+        if (++since == p.M) {
+            asm volatile("" ::: "memory"); // keep the split out of the multiply block (no speculation)
+            st.split();
+            since = 0;
+            ++nsplit;
         }
     }
     if (since) {
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     const LaneMap m = map_lane(p, row_group, lane);
     const int co0 = blockIdx.y * CO_T;
     // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
-    const uint32_t lane_byte = (uint32_t)((((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi) * 4);
+    const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 4);
     const uint32_t *w_tile = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
 
     const int tile_cap = p.terms_pad < kTermTile ? p.terms_pad : kTermTile;
@@ -383,8 +383,8 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const int w1 = x * N + j - p.off; // stride-1 output column
-            if (w1 >= 0 && w1 < p.Wo1 && (p.stride == 1 || w1 % p.stride == 0)) {
-                const int wo = p.stride == 1 ? w1 : w1 / p.stride;
+            if (w1 >= 0 && w1 < p.Wo1 && (p.stride_w == 1 || w1 % p.stride_w == 0)) {
+                const int wo = p.stride_w == 1 ? w1 : w1 / p.stride_w;
                 const int32_t v = st.out[c][j] - unbias;
                 yrow[wo] = BIP ? bipolar_value(p.ct, co0 + c, m.ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, v,
                                                st.out[CO_T][j] - unbias)

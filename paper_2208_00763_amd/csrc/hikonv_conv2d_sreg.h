@@ -40,7 +40,8 @@
 namespace hikonv {
 
 struct LaneMapS {
-    int n, ho, xi;
+    int n, ho, xi; // image, output row inside the image (depth slice * Ho2d + row), packed word index
+    int64_t in_row; // packed input row that kernel row 0 of this output row reads
     bool active;   // lane stands for a block of an existing output row
     bool recv;     // the previous lane holds the preceding block of the same row
     bool store;    // lane writes its own N outputs
@@ -75,6 +76,9 @@ __device__ __forceinline__ LaneMapS map_lane_sreg(const Conv2dArgs &p, int64_t r
     }
     m.n = (int)(row / p.Ho);
     m.ho = (int)(row - (int64_t)m.n * p.Ho);
+    // first packed input row of this output row: image, output depth, output row inside the depth slice
+    const int d = m.ho / p.Ho2d;
+    m.in_row = (int64_t)m.n * p.img_rows + (int64_t)d * p.d_rows + (int64_t)(m.ho - d * p.Ho2d) * p.stride;
     return m;
 }
 
@@ -100,8 +104,8 @@ __device__ __forceinline__ void finish_channel(const Conv2dArgs &p, const LaneMa
         const bool own = j < N;
         if (!(own ? m.store : m.store_hi)) continue;
         const int w1 = x * N + j - p.off; // stride-1 output column
-        if (w1 >= 0 && w1 < p.Wo1 && (p.stride == 1 || w1 % p.stride == 0)) {
-            const int wo = p.stride == 1 ? w1 : w1 / p.stride;
+        if (w1 >= 0 && w1 < p.Wo1 && (p.stride_w == 1 || w1 % p.stride_w == 0)) {
+            const int wo = p.stride_w == 1 ? w1 : w1 / p.stride_w;
             const int32_t val = own ? o[j] : v[j];
             yrow[wo] = BIP ? bipolar_value(p.ct, co, m.ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, val, sa[j]) : val;
         }
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     const LaneMapS m = map_lane_sreg(p, row_group, lane);
     const int co0 = blockIdx.y * CO_T;
     // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
-    const uint32_t lane_byte = (uint32_t)((((int64_t)m.n * p.C * p.Hp + (int64_t)m.ho * p.stride) * p.Xs + m.xi) * 4);
+    const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 4);
     // weight rows of this channel tile: 32 bytes per term
     const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)(p.cog0 + blockIdx.y) * p.terms_pad * 32;
     const char *trow = reinterpret_cast<const char *>(p.toff); // 16 bytes per term group

@@ -62,7 +62,12 @@ constexpr int kTermGroup = HIKONV_TERM_GROUP;
 constexpr int kPackFromAcc = 100;
 
 struct PackActArgs {
-    const void *x;           // NCHW activations, INT8 or bit-dense rows
+    const void *x;           // NC(D)HW activations, INT8 or bit-dense rows
+    int D, Dp, pad_d;        // source depth, padded depth of the packed rows, depth padding (1, 1, 0 for 2-D)
+    int phases;              // column phases packed as separate channels (polyphase stride), else 1
+    int pad_w_mat;           // horizontal padding materialised in the packed rows (polyphase), else 0
+    int Csrc, Wsrc;          // source channels and row length (C = Csrc*phases packed channels of W elements)
+    int Kd;                  // kernel depth (offset table)
     const int32_t *acc;      // kPackFromAcc: [Nimg][C][acc_H][acc_W] accumulators of the producing layer
     int acc_H, acc_W, pool, shift, qmax; // kPackFromAcc: q = min(qmax, max(acc, 0) >> shift) after 2x2 max-pool if pool
     int x_format, c, b, a_signed, bipolar;
@@ -78,7 +83,9 @@ struct PackActArgs {
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream);
 
 struct PackWArgs {
-    const uint8_t *w;        // [Co][C][Kh][Kw], one value per byte
+    const uint8_t *w;        // [Co][Csrc][Kh][Kwsrc], one value per byte (Kh counts depth x height kernel rows)
+    int phases, Csrc, Kwsrc; // polyphase: packed channel c = source channel c / phases, column phase c % phases;
+                             // tap j of a phase is source tap j*phases + phase (zero beyond Kwsrc)
     int Co, C, Kh, Kw, w_signed, bipolar;
     int Kp, S, chunks;
     int n_cog;               // ceil(Co / 8) (+1 all-ones group when bipolar)
@@ -92,8 +99,13 @@ hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream);
 struct Conv2dArgs {
     const uint32_t *apk;     // packed activations
     const uint32_t *wp;      // packed weights, group-of-8 layout
-    int Nimg, C, Ho, Wo1;    // Wo1 = stride-1 output width
-    int Kh, stride, off;     // off = Kw - 1 - pad: output w sits at row-convolution index w + off
+    int Nimg, C, Ho, Wo1;    // Ho = output rows per (image, channel), all depth slices; Wo1 = stride-1 output width
+    int Ho2d;                // output rows per depth slice (= Ho for a 2-D layer)
+    int64_t img_rows;        // packed input rows per image (channels x padded depth x padded height)
+    int64_t d_rows;          // packed input rows between the inputs of consecutive output depth slices
+    int stride_w;            // column decimation applied when storing (1 when the phases are packed separately)
+    int Kh, stride, off;     // stride between input rows of consecutive output rows; off = Kw - 1 - pad:
+                             // output w sits at row-convolution index w + off
     int Hp, Xs, X;           // packed rows per image-channel, words per row, blocks per row
     int N, S, chunks, M;     // plan; M = products accumulated per split
     int terms;               // C*Kh*chunks

@@ -72,8 +72,9 @@ def run_conv2d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
     assert ws_bytes > 0
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     if prepacked:
-        pw = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8, device="cuda")
-        hk.hikonv_pack_weights(plan, w_d, co, c, kh, kw, pw)
+        pw = torch.empty(hk.hikonv_packed_weights_bytes_ex(plan, co, c, 1, kh, kw, stride), dtype=torch.uint8,
+                         device="cuda")
+        hk.hikonv_pack_weights_ex(plan, w_d, co, c, 1, kh, kw, stride, pw)
         hk.hikonv_conv2d_prepacked(plan, x_d, fmt, n, c, h, w, pw, co, kh, kw, stride, pad, ws, y)
     else:
         hk.hikonv_conv2d(plan, x_d, fmt, n, c, h, w, w_d, co, kh, kw, stride, pad, ws, y)
@@ -81,3 +82,28 @@ def run_conv2d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
     res = y.cpu().numpy()
     assert (res[n * co * ho * wo:] == -77777).all(), "wrote past the end of the output"
     return res[:n * co * ho * wo].reshape(n, co, ho, wo)
+
+
+def run_conv3d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
+    n, c, d, h, w = x_np.shape
+    co, _, kd, kh, kw = w_np.shape
+    do, ho, wo = ((d + 2 * pad - kd) // stride + 1, (h + 2 * pad - kh) // stride + 1,
+                  (w + 2 * pad - kw) // stride + 1)
+    count = n * co * do * ho * wo
+    y = torch.full((count + 8,), -77777, dtype=torch.int32, device="cuda")
+    x_d = compact(x_np.reshape(n * c * d * h, w), plan.bits_a) if fmt == hk.FMT_BITDENSE else dev(x_np)
+    w_d = dev(w_np)
+    ws_bytes = hk.hikonv_conv3d_workspace_bytes(plan, n, c, d, h, w, co, kd, kh, kw, stride, pad, prepacked)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    if prepacked:
+        pw = torch.empty(hk.hikonv_packed_weights_bytes_ex(plan, co, c, kd, kh, kw, stride), dtype=torch.uint8,
+                         device="cuda")
+        hk.hikonv_pack_weights_ex(plan, w_d, co, c, kd, kh, kw, stride, pw)
+        hk.hikonv_conv3d(plan, x_d, fmt, n, c, d, h, w, pw, True, co, kd, kh, kw, stride, pad, ws, y)
+    else:
+        hk.hikonv_conv3d(plan, x_d, fmt, n, c, d, h, w, w_d, False, co, kd, kh, kw, stride, pad, ws, y)
+    torch.cuda.synchronize()
+    res = y.cpu().numpy()
+    assert (res[count:] == -77777).all(), "wrote past the end of the output"
+    return res[:count].reshape(n, co, do, ho, wo)
