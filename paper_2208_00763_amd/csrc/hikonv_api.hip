@@ -427,6 +427,14 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
         a.CH = 0;
         conv1d_fast_tuning(&a);
         a.tiles_per_row = conv1d_fast_runs_per_row(a.N, a.n_blocks, a.big_runs && !a.direct_store);
+        if (a.aligned_runs && !a.direct_store) {
+            a.run_outputs = conv1d_fast_run_outputs(a.N, a.big_runs != 0);
+            a.y_phase = (int)((reinterpret_cast<uintptr_t>(y_dev) >> 2) & 31);
+            if (a.run_outputs >= 32)
+                a.tiles_per_row = ceil_div(a.out_len + 31, a.run_outputs);
+            else
+                a.aligned_runs = 0;
+        }
         return hip_result(launch_conv1d_fast(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
     }
     a.CH = conv1d_tile_chunks(a.N, a.n_blocks);

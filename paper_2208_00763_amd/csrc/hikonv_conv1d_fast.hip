@@ -85,7 +85,22 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
     const int64_t run = (int64_t)blockIdx.x * kWavesPerGroup + wave; // global run index
     if (run >= p.rows * p.tiles_per_row) return;                      // wave-uniform
     const int64_t r = run / p.tiles_per_row;
-    const int64_t xr0 = (run - r * p.tiles_per_row) * (CH * kChunkBlocks); // first owned block of the run
+    const int64_t t_run = run - r * p.tiles_per_row;
+    // Block-aligned runs: the run owns CH*63 consecutive blocks.  Line-aligned runs (staged
+    // stores only): the run owns the outputs [o_own0, o_own1) whose ends fall on 128-byte lines
+    // of y, starts at the block that holds o_own0 and computes CH*63 blocks from there; the few
+    // outputs beyond o_own1 belong to the next run, which recomputes them.
+    int64_t xr0 = t_run * (CH * kChunkBlocks); // first owned block of the run
+    int64_t o_own0 = 0, o_own1 = 0;
+    const bool line_runs = !DIRECT && p.aligned_runs;
+    if (line_runs) {
+        const int phase = (int)((p.y_phase + r * p.out_len) & 31); // position of this row's output 0 inside its line
+        o_own0 = t_run == 0 ? 0 : t_run * p.run_outputs - phase;
+        o_own1 = (t_run + 1) * p.run_outputs - phase;
+        if (o_own1 > p.out_len) o_own1 = p.out_len;
+        if (o_own0 >= o_own1) return; // wave-uniform: the last interval of this row is empty
+        xr0 = (o_own0 + p.shift_m) / N;
+    }
     int32_t *stage = s_out + wave * STAGE;
 
     const int S = p.S, c = p.c, b = p.b;
@@ -281,9 +296,13 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
     __builtin_amdgcn_wave_barrier();
 
     // copy the run to global memory: LDS quad q <-> outputs o_run0 - a_off + 4q .. +3
-    const int64_t o_lo = o_run0 > 0 ? o_run0 : 0;
+    int64_t o_lo = o_run0 > 0 ? o_run0 : 0;
     int64_t o_hi = o_run0 + CH * kChunkBlocks * N;
     if (o_hi > p.out_len) o_hi = p.out_len;
+    if (line_runs) {
+        o_lo = o_own0;
+        o_hi = o_own1;
+    }
     constexpr int NQ = (CH * kChunkBlocks * N + 3 + 3) / 4;
 #pragma unroll 1
     for (int q = lane; q < NQ; q += 64) {
@@ -341,8 +360,10 @@ void conv1d_fast_tuning(Conv1dArgs *a)
 {
     static const int direct = env_flag("HIKONV_CONV1D_DIRECT", -1);
     static const int big = env_flag("HIKONV_CONV1D_BIG", -1);
+    static const int aligned = env_flag("HIKONV_CONV1D_ALIGNED", -1);
     a->direct_store = direct >= 0 ? direct : 0;
     a->big_runs = big >= 0 ? big : 1;
+    a->aligned_runs = aligned >= 0 ? aligned : 1;
 }
 
 bool conv1d_fast_applicable(const Conv1dArgs &a)
@@ -361,6 +382,21 @@ int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks, bool big)
     default: break;
     }
     return ceil_div(n_blocks, (int64_t)ch * kChunkBlocks);
+}
+
+// Outputs per line-aligned interval: CH*63 blocks hold CH*63*N outputs, the run may start up
+// to N-1 outputs before its interval, and the interval is a whole number of 128-byte lines.
+int64_t conv1d_fast_run_outputs(int N, bool big)
+{
+    int ch = 1;
+    switch (N) {
+#define HIKONV_CASE(n) case n: ch = run_chunks(n, big); break;
+        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
+        HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
+#undef HIKONV_CASE
+    default: break;
+    }
+    return ((int64_t)ch * kChunkBlocks * N - N + 1) / 32 * 32;
 }
 
 // a.tiles_per_row must hold conv1d_fast_runs_per_row(a.N, a.n_blocks, a.big_runs && !a.direct_store)
