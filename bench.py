@@ -38,9 +38,10 @@ def event_ms(fn, reps):
     return start.elapsed_time(end) / reps
 
 
-def conv1d_case(hk, wl, bits, signed):
+def conv1d_case(hk, wl, bits, signed, taps=TAPS):
     """Device buffers and launch closures for one case of the sweep."""
     import torch
+    TAPS = taps
     x, g = wl.conv1d_case(bits, signed, TAPS, ROWS, LENGTH)
     x_d8 = torch.from_numpy(x.view("uint8")).cuda()
     g_d = torch.from_numpy(g.view("uint8")).cuda()
@@ -200,6 +201,55 @@ def conv2d_extra(hk, wl, name, steps):
     return report
 
 
+def widened_extras(hk, steps):
+    """The two widened layer forms on 4-bit signed data: a stride-2 3x3 layer (every column
+    computed and every second stored, against the polyphase form) and a 3x3x3 volume layer."""
+    import numpy as np
+    import torch
+    rng = np.random.default_rng(2208)
+    out = {}
+    kw_plan = dict(bits_a=4, bits_w=4, a_signed=1, w_signed=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0)
+
+    n, c, h, w, co = 8, 64, 56, 56, 128
+    x_d = torch.from_numpy(rng.integers(-8, 8, (n, c, h, w), dtype=np.int8).view("uint8")).cuda()
+    w_d = torch.from_numpy(rng.integers(-8, 8, (co, c, 3, 3), dtype=np.int8).view("uint8")).cuda()
+    ho = wo = (h + 2 - 3) // 2 + 1
+    y = torch.empty(n * co * ho * wo, dtype=torch.int32, device="cuda")
+    macs = n * co * ho * wo * c * 9
+    rep = {"shape": "8x64x56x56 -> 128, 3x3, stride 2, pad 1, int4", "macs": macs}
+    for label, taps in (("decimate", 3), ("polyphase", 2)):
+        plan = hk.hikonv_plan_ex(taps=taps, **kw_plan)
+        ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, n, c, h, w, co, 3, 3, 2, 1, True), dtype=torch.uint8,
+                         device="cuda")
+        pw = torch.empty(hk.hikonv_packed_weights_bytes_ex(plan, co, c, 1, 3, 3, 2), dtype=torch.uint8, device="cuda")
+        hk.hikonv_pack_weights_ex(plan, w_d, co, c, 1, 3, 3, 2, pw)
+        run = lambda: hk.hikonv_conv2d_prepacked(plan, x_d, hk.FMT_INT8, n, c, h, w, pw, co, 3, 3, 2, 1, ws, y)
+        event_ms(run, 3)
+        ms = event_ms(run, steps)
+        rep[label] = dict(ms=ms, gops=2 * macs / ms / 1e6, plan=dict(N=plan.N, K=plan.K, S=plan.S, M=plan.M))
+    run_u = lambda: hk.hikonv_conv2d_unpacked(4, 4, hk.signedness(True, True), x_d, n, c, h, w, w_d, co, 3, 3, 2, 1, y)
+    event_ms(run_u, 3)
+    rep["unpacked_ms"] = event_ms(run_u, steps)
+    out["conv2d_stride2"] = rep
+
+    n, c, d, h, w, co = 1, 16, 16, 56, 56, 32
+    x_d = torch.from_numpy(rng.integers(-8, 8, (n, c, d, h, w), dtype=np.int8).view("uint8")).cuda()
+    w_d = torch.from_numpy(rng.integers(-8, 8, (co, c, 3, 3, 3), dtype=np.int8).view("uint8")).cuda()
+    y = torch.empty(n * co * d * h * w, dtype=torch.int32, device="cuda")
+    macs = n * co * d * h * w * c * 27
+    plan = hk.hikonv_plan_ex(taps=3, **kw_plan)
+    ws = torch.empty(hk.hikonv_conv3d_workspace_bytes(plan, n, c, d, h, w, co, 3, 3, 3, 1, 1, True), dtype=torch.uint8,
+                     device="cuda")
+    pw = torch.empty(hk.hikonv_packed_weights_bytes_ex(plan, co, c, 3, 3, 3, 1), dtype=torch.uint8, device="cuda")
+    hk.hikonv_pack_weights_ex(plan, w_d, co, c, 3, 3, 3, 1, pw)
+    run3 = lambda: hk.hikonv_conv3d(plan, x_d, hk.FMT_INT8, n, c, d, h, w, pw, True, co, 3, 3, 3, 1, 1, ws, y)
+    event_ms(run3, 3)
+    ms = event_ms(run3, steps)
+    out["conv3d"] = dict(shape="1x16x16x56x56 -> 32, 3x3x3, stride 1, pad 1, int4", macs=macs, ms=ms,
+                         gops=2 * macs / ms / 1e6, plan=dict(N=plan.N, K=plan.K, S=plan.S, M=plan.M))
+    return out
+
+
 def small_extras(hk, wl, steps):
     """Latency-scale configurations: the 4096-value 1-D case and the nine-layer 4-bit CNN forward
     (eager launches and the same launches replayed from a captured HIP graph)."""
@@ -244,6 +294,30 @@ def small_extras(hk, wl, steps):
     return out
 
 
+def sweep(hk, wl, steps):
+    """All 48 cases of the 1-D bitwidth sweep (1..8 bit, signed and unsigned, 3/5/7 taps, 4096 rows
+    of 65536 values, valid outputs): packed and unpacked kernel time, effective GOPS, achieved
+    algorithmic HBM bandwidth."""
+    import torch
+    rows = []
+    for bits in range(1, 9):
+        for signed in (False, True):
+            for taps in (3, 5, 7):
+                case = conv1d_case(hk, wl, bits, signed, taps)
+                event_ms(case["packed"], 2)
+                ms_p = min(event_ms(case["packed"], steps) for _ in range(2))
+                event_ms(case["unpacked"], 2)
+                ms_u = min(event_ms(case["unpacked"], steps) for _ in range(2))
+                plan = case["plan"]
+                rows.append(dict(bits=bits, signed=signed, taps=taps, N=plan.N, K=plan.K, S=plan.S, chunks=plan.chunks,
+                                 packed_ms=ms_p, unpacked_ms=ms_u, gops=2 * case["macs"] / ms_p / 1e6,
+                                 gbs=case["bytes"] / ms_p / 1e6, hbm_frac=case["bytes"] / ms_p / 1e6 / HBM_PEAK_GBS,
+                                 speedup_vs_unpacked=ms_u / ms_p))
+                del case
+                torch.cuda.empty_cache()
+    return rows
+
+
 def microbench(hk):
     """Issue rates (10^12 lane-instructions/s over the whole chip) and HBM bandwidths (TB/s)."""
     import torch
@@ -276,6 +350,9 @@ def main():
     ap.add_argument("--ubench", action="store_true",
                     help="print the measured issue rate of the integer VALU instructions the kernels use and the "
                          "HBM write / copy / read bandwidth (the two rooflines), then exit")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time all 48 cases of the 1-D bitwidth sweep (packed and unpacked), print them as JSON "
+                         "and as a table, then exit")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain copy kernel of known size (512 MiB read + 512 MiB written, 3 launches) "
                          "so that HBM byte counters collected by a profiler can be scaled")
@@ -294,6 +371,16 @@ def main():
 
     if args.ubench:
         print(json.dumps(microbench(hk)))
+        return 0
+
+    if args.sweep:
+        rows = sweep(hk, wl, max(3, args.steps // 5))
+        print(json.dumps({"metric": "1-D bitwidth sweep, 4096 rows x 65536, valid, bit-dense input", "cases": rows}))
+        print("bits signed taps  N  K  S chunks  packed_ms unpacked_ms  speedup   GOPS  GB/s  frac_of_8TB/s", file=sys.stderr)
+        for r in rows:
+            print("%4d %6s %4d %2d %2d %2d %6d %10.4f %11.4f %8.2f %6.0f %5.0f %8.3f" % (
+                r["bits"], "s" if r["signed"] else "u", r["taps"], r["N"], r["K"], r["S"], r["chunks"], r["packed_ms"],
+                r["unpacked_ms"], r["speedup_vs_unpacked"], r["gops"], r["gbs"], r["hbm_frac"]), file=sys.stderr)
         return 0
 
     if args.calibrate:
@@ -354,6 +441,7 @@ def main():
         extras["conv1d_requant_bitdense_out"] = requant_extra(hk, wl, max(3, args.steps // 5))
         for name in ("c3", "c4"):
             extras["conv2d_" + name] = conv2d_extra(hk, wl, name, max(5, args.steps // 2))
+        extras["widened_layers"] = widened_extras(hk, max(5, args.steps // 2))
         extras["latency"] = small_extras(hk, wl, max(5, args.steps // 2))
         head["x"], head["g"] = x_keep, g_keep
     line["extras"] = extras

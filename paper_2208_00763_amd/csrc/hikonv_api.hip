@@ -426,12 +426,12 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
     if (conv1d_fast_applicable(a)) {
         a.CH = 0;
         conv1d_fast_tuning(&a);
-        a.tiles_per_row = conv1d_fast_runs_per_row(a.N, a.n_blocks, a.big_runs && !a.direct_store);
+        a.tiles_per_row = conv1d_fast_runs_per_row(a);
         if (a.aligned_runs && !a.direct_store) {
-            a.run_outputs = conv1d_fast_run_outputs(a.N, a.big_runs != 0);
-            a.y_phase = (int)((reinterpret_cast<uintptr_t>(y_dev) >> 2) & 31);
-            if (a.run_outputs >= 32)
-                a.tiles_per_row = ceil_div(a.out_len + 31, a.run_outputs);
+            a.run_outputs = conv1d_fast_run_outputs(a);
+            a.y_phase = (int)((reinterpret_cast<uintptr_t>(y_dev) >> 2) & (a.align_outputs - 1));
+            if (a.run_outputs >= a.align_outputs)
+                a.tiles_per_row = ceil_div(a.out_len + a.align_outputs - 1, a.run_outputs);
             else
                 a.aligned_runs = 0;
         }

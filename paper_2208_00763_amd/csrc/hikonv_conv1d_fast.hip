@@ -22,15 +22,24 @@ namespace hikonv {
 namespace {
 
 constexpr int kWavesPerGroup = 4;
-constexpr int kChunkBlocks = 63;
 
-// chunks per wave run: about 750 outputs per run
-// chunks per wave run: about 1500 outputs (BIG) or 750 outputs per run
-__host__ __device__ constexpr int run_chunks(int n, bool big) { return (big ? 24 : 12) / n > 0 ? (big ? 24 : 12) / n : 1; }
+// Lanes of a wave chunk that own no block.  Ordinary kernels: lane 0 recomputes the block
+// before the chunk (its high segments feed lane 1).  Kernels whose taps are cut into SHARE
+// B words of N taps each (K = N): chunk j of a block multiplies the input delayed by j*N
+// values, which is the packed word of the block j places back, so a lane packs only its own
+// block and takes the delayed words from the lanes before it (DPP); SHARE - 1 more leading
+// lanes supply those words and own nothing.
+__host__ __device__ constexpr int halo_lanes(int share) { return share > 1 ? share : 1; }
+__host__ __device__ constexpr int chunk_blocks(int share) { return 64 - halo_lanes(share); }
+// Wave chunks per run: about 1500 outputs.  A run owns an output interval whose ends fall on
+// 128-byte lines of y (kAlignOutputs values).  Measured on MI355X: shorter runs are slower, and
+// so are coarser alignments once the outputs they leave outside the interval exceed a few percent.
+constexpr int kAlignOutputs = 32;
+__host__ __device__ constexpr int run_chunks(int n, int /*share*/) { return 24 / n > 0 ? 24 / n : 1; }
 // LDS dwords per wave: outputs of a run + alignment slack, rounded to 16 bytes
-__host__ __device__ constexpr int run_stage_dwords(int n, bool big)
+__host__ __device__ constexpr int run_stage_dwords(int n, int share)
 {
-    return ((run_chunks(n, big) * kChunkBlocks * n + 8 + 3) / 4) * 4;
+    return ((run_chunks(n, share) * chunk_blocks(share) * n + 8 + 3) / 4) * 4;
 }
 
 __device__ __forceinline__ uint32_t load_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
@@ -47,36 +56,17 @@ __device__ __forceinline__ uint32_t load_dword_checked(const uint32_t *x, int64_
     return v;
 }
 
-// N consecutive int32 to a 4-byte aligned address with the widest stores available
-typedef int32_t v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
-typedef int32_t v3i_a4 __attribute__((ext_vector_type(3), aligned(4)));
-typedef int32_t v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
-
-template <int N>
-__device__ __forceinline__ void store_run(int32_t *dst, const int32_t (&v)[N])
-{
-    int j = 0;
-#pragma unroll
-    for (; j + 4 <= N; j += 4) {
-        v4i_a4 t = {v[j], v[j + 1], v[j + 2], v[j + 3]};
-        *reinterpret_cast<v4i_a4 *>(dst + j) = t;
-    }
-    if (N - j == 3) {
-        v3i_a4 t = {v[j], v[j + 1], v[j + 2]};
-        *reinterpret_cast<v3i_a4 *>(dst + j) = t;
-    } else if (N - j == 2) {
-        v2i_a4 t = {v[j], v[j + 1]};
-        *reinterpret_cast<v2i_a4 *>(dst + j) = t;
-    } else if (N - j == 1) {
-        dst[j] = v[j];
-    }
-}
-
-template <int N, bool A_SIGNED, bool ANY_SIGNED, bool MULTI, bool DIRECT, bool BIG>
+// MULTI: the taps need several B words.  SHARE = 0: every chunk's delayed window is cut out of
+// one 64-bit window and packed again; SHARE = 2..4 (plans with K = N and SHARE chunks): the
+// delayed words come from the preceding lanes.
+template <int N, bool A_SIGNED, bool ANY_SIGNED, bool MULTI, int SHARE>
 __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
 {
-    constexpr int CH = run_chunks(N, BIG);
-    constexpr int STAGE = DIRECT ? 4 : run_stage_dwords(N, BIG);
+    constexpr int HALO = halo_lanes(SHARE);
+    constexpr int kChunkBlocks = chunk_blocks(SHARE);
+    constexpr int CH = run_chunks(N, SHARE);
+    constexpr int STAGE = run_stage_dwords(N, SHARE);
+    static_assert(SHARE == 0 || (MULTI && SHARE >= 2 && SHARE <= 4), "shared packing is for 2..4 B words");
     __shared__ __attribute__((aligned(16))) int32_t s_out[kWavesPerGroup * STAGE];
     __shared__ uint32_t s_bw[kWavesPerGroup * 8];
 
@@ -92,9 +82,9 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
     // outputs beyond o_own1 belong to the next run, which recomputes them.
     int64_t xr0 = t_run * (CH * kChunkBlocks); // first owned block of the run
     int64_t o_own0 = 0, o_own1 = 0;
-    const bool line_runs = !DIRECT && p.aligned_runs;
+    const bool line_runs = p.aligned_runs != 0;
     if (line_runs) {
-        const int phase = (int)((p.y_phase + r * p.out_len) & 31); // position of this row's output 0 inside its line
+        const int phase = (int)((p.y_phase + r * p.out_len) & (p.align_outputs - 1)); // position of this row's output 0 inside its aligned unit
         o_own0 = t_run == 0 ? 0 : t_run * p.run_outputs - phase;
         o_own1 = (t_run + 1) * p.run_outputs - phase;
         if (o_own1 > p.out_len) o_own1 = p.out_len;
@@ -153,50 +143,38 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
         for (int n = 0; n < N; ++n) a += (uint32_t)field<A_SIGNED>(raw, (uint32_t)(n * c), (uint32_t)b) << (S * n);
         return a;
     };
-    // overlap-add with the previous lane, split, then either stage in LDS or store directly
-    // (a lane's N outputs are contiguous and so are the lanes', so the wave writes one dense run)
+    // overlap-add with the previous lane, split, stage in the wave's LDS run
     int32_t *yrow = p.y + r * p.out_len;
     auto finish = [&](uint64_t acc, int xl) {
         uint64_t comb = acc;
         if (SN < 64u) // wave-uniform; a one-tap kernel whose slices fill the word has no high part
             comb += lane_shr1(ANY_SIGNED ? (uint64_t)((int64_t)acc >> SN) : acc >> SN);
-        if (lane > 0) {
+        if (lane >= HALO) {
             int32_t v[N];
 #pragma unroll
             for (int j = 0; j < N; ++j) v[j] = (int32_t)((uint32_t)(comb >> (S * j)) & fmask) - bias_f;
-            if (DIRECT) {
-                const int64_t o = o_run0 + (int64_t)xl * N;
-                if (o >= 0 && o + N <= p.out_len) {
-                    store_run<N>(yrow + o, v);
-                } else {
+            int32_t *dst = stage + xl * N + a_off;
 #pragma unroll
-                    for (int j = 0; j < N; ++j)
-                        if (o + j >= 0 && o + j < p.out_len) yrow[o + j] = v[j];
-                }
-            } else {
-                int32_t *dst = stage + xl * N + a_off;
-#pragma unroll
-                for (int j = 0; j < N; ++j) dst[j] = v[j];
-            }
+            for (int j = 0; j < N; ++j) dst[j] = v[j];
         }
     };
 
     // wave-uniform test: every element the run reads lies inside the row, and both dwords of
     // every window lie inside the buffer
-    const int64_t e_min = (xr0 - 1) * N - (MULTI ? (int64_t)(p.chunks - 1) * p.Kp : 0);
+    const int64_t e_min = (xr0 - HALO) * N - (MULTI && !SHARE ? (int64_t)(p.chunks - 1) * p.Kp : 0);
     const int64_t e_end = (xr0 + CH * kChunkBlocks) * N;
     const bool interior = e_min >= 0 && e_end <= p.len && row_bit0 + e_end * c + 96 <= total_bits;
 
     // MULTI: one aligned 64-bit window per block covers every chunk's (delayed) window
-    const int span_elems = MULTI ? (p.chunks - 1) * p.Kp + N : N;
+    const int span_elems = MULTI && !SHARE ? (p.chunks - 1) * p.Kp + N : N;
     // Runs at a row edge stay on the streaming path as long as the buffer is a whole number
     // of dwords: their loads use clamped dword indices (the clamped dwords only hold
     // containers of elements outside [0, len), which the mask below removes).
     const bool whole_dwords = (p.total_bytes & 3) == 0;
-    if ((interior || whole_dwords) && (!MULTI || span_elems * c <= 64)) {
+    if ((interior || whole_dwords) && (!MULTI || SHARE || span_elems * c <= 64)) {
         // all loads of the run are issued before the first one is used
-        const int delay = MULTI ? (p.chunks - 1) * p.Kp : 0;          // elements the last chunk lags
-        const int64_t e_lane0 = (xr0 + lane - 1) * N - delay;          // first element of chunk 0's window
+        const int delay = MULTI && !SHARE ? (p.chunks - 1) * p.Kp : 0; // elements the last chunk lags
+        const int64_t e_lane0 = (xr0 + lane - HALO) * N - delay;       // first element of chunk 0's window
         const int64_t bit0 = row_bit0 + e_lane0 * c;
         const uint32_t sh0 = (uint32_t)bit0 & 31u;
         constexpr int kChunkStep = kChunkBlocks * N;                  // elements between chunks
@@ -209,7 +187,7 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
                 const uint32_t *wp = wp0 + (bitc >> 5);
                 d0[cc] = wp[0];
                 d1[cc] = wp[1];
-                d2[cc] = MULTI ? wp[2] : 0u;
+                d2[cc] = MULTI && !SHARE ? wp[2] : 0u;
                 shv[cc] = bitc & 31u;
             }
         } else {
@@ -223,7 +201,7 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
                 const int64_t i2 = d + 2 < 0 ? 0 : (d + 2 > dlast ? dlast : d + 2);
                 d0[cc] = p.x[i0];
                 d1[cc] = p.x[i1];
-                d2[cc] = MULTI ? p.x[i2] : 0u;
+                d2[cc] = MULTI && !SHARE ? p.x[i2] : 0u;
                 shv[cc] = bitc & 31u;
             }
         }
@@ -237,6 +215,11 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
             return raw & m_hi & ~((1u << lo_bits) - 1u);
         };
         const uint32_t b0 = MULTI ? 0u : make_b0();
+        uint32_t bsh[SHARE > 0 ? SHARE : 1];
+        if (SHARE) {
+#pragma unroll
+            for (int j = 0; j < SHARE; ++j) bsh[j] = s_bw[wave * 8 + j];
+        }
 #pragma unroll
         for (int cc = 0; cc < CH; ++cc) {
             const uint32_t w_lo = funnel_shr(d1[cc], d0[cc], shv[cc]);
@@ -245,6 +228,15 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
             if (!MULTI) {
                 const uint32_t raw = interior ? w_lo : keep_valid(w_lo, e_cc);
                 acc = mad_wide<ANY_SIGNED>(pack(raw), b0, acc);
+            } else if (SHARE) {
+                // one packed word per block; chunk j multiplies the word of the block j places back
+                uint32_t a = pack(interior ? w_lo : keep_valid(w_lo, e_cc));
+                acc = mad_wide<ANY_SIGNED>(a, bsh[0], acc);
+#pragma unroll
+                for (int j = 1; j < SHARE; ++j) {
+                    a = lane_shr1(a);
+                    acc = mad_wide<ANY_SIGNED>(a, bsh[j], acc);
+                }
             } else {
                 const uint64_t win = ((uint64_t)funnel_shr(d2[cc], d1[cc], shv[cc]) << 32) | w_lo;
                 for (int ch = 0; ch < p.chunks; ++ch) {
@@ -254,13 +246,13 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
                     acc = mad_wide<ANY_SIGNED>(pack(raw), s_bw[wave * 8 + ch], acc);
                 }
             }
-            finish(acc, cc * kChunkBlocks + lane - 1);
+            finish(acc, cc * kChunkBlocks + lane - HALO);
         }
     } else {
         const uint32_t b0 = MULTI ? 0u : make_b0();
 #pragma unroll 1
         for (int cc = 0; cc < CH; ++cc) {
-            const int xl = cc * kChunkBlocks + lane - 1; // this lane's block, relative to xr0
+            const int xl = cc * kChunkBlocks + lane - HALO; // this lane's block, relative to xr0
             uint64_t acc = bias_low;
             const int nchunks = MULTI ? p.chunks : 1;
             for (int ch = 0; ch < nchunks; ++ch) {
@@ -292,7 +284,6 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
             finish(acc, xl);
         }
     }
-    if (DIRECT) return;
     __builtin_amdgcn_wave_barrier();
 
     // copy the run to global memory: LDS quad q <-> outputs o_run0 - a_off + 4q .. +3
@@ -322,34 +313,42 @@ __global__ __launch_bounds__(256) void k_conv1d_fast(Conv1dArgs p)
     }
 }
 
+// number of B words whose delayed inputs come from the preceding lanes (0: not this form)
+inline int share_of(const Conv1dArgs &a)
+{
+    return a.chunks >= 2 && a.chunks <= 4 && a.Kp == a.N && a.N >= 2 && a.N <= 5 ? a.chunks : 0;
+}
+
+template <int N, bool AS, bool ANY>
+hipError_t launch_signs(const Conv1dArgs &a, dim3 g, hipStream_t stream)
+{
+    const int share = share_of(a);
+    if (a.chunks == 1) {
+        hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, false, 0>), g, dim3(256), 0, stream, a);
+    } else if constexpr (N >= 2 && N <= 5) {
+        switch (share) {
+        case 2: hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, true, 2>), g, dim3(256), 0, stream, a); break;
+        case 3: hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, true, 3>), g, dim3(256), 0, stream, a); break;
+        case 4: hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, true, 4>), g, dim3(256), 0, stream, a); break;
+        default: hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, true, 0>), g, dim3(256), 0, stream, a); break;
+        }
+    } else {
+        hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, true, 0>), g, dim3(256), 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
 template <int N>
 hipError_t launch_n(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
 {
-    const bool multi = a.chunks > 1;
-#define HIKONV_LAUNCH(AS, ANY, MU)                                                                          \
-    do {                                                                                                    \
-        if (a.direct_store)                                                                                 \
-            hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU, true, false>), g, dim3(256), 0, stream, a);   \
-        else if (a.big_runs)                                                                                \
-            hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU, false, true>), g, dim3(256), 0, stream, a);   \
-        else                                                                                                \
-            hipLaunchKernelGGL((k_conv1d_fast<N, AS, ANY, MU, false, false>), g, dim3(256), 0, stream, a);  \
-    } while (0)
-    if (a_signed) {
-        if (multi) HIKONV_LAUNCH(true, true, true); else HIKONV_LAUNCH(true, true, false);
-    } else if (any_signed) {
-        if (multi) HIKONV_LAUNCH(false, true, true); else HIKONV_LAUNCH(false, true, false);
-    } else {
-        if (multi) HIKONV_LAUNCH(false, false, true); else HIKONV_LAUNCH(false, false, false);
-    }
-#undef HIKONV_LAUNCH
-    return hipGetLastError();
+    if (a_signed) return launch_signs<N, true, true>(a, g, stream);
+    if (any_signed) return launch_signs<N, false, true>(a, g, stream);
+    return launch_signs<N, false, false>(a, g, stream);
 }
 
 } // namespace
 
-// Launch shape of the streaming kernel.  Defaults come from measurements on MI355X; the
-// environment variables HIKONV_CONV1D_DIRECT / _BIG (0 or 1) override them for tuning.
+// HIKONV_CONV1D_ALIGNED=0 (tuning override) switches the line-aligned output intervals off.
 static int env_flag(const char *name, int dflt)
 {
     const char *e = getenv(name);
@@ -358,12 +357,11 @@ static int env_flag(const char *name, int dflt)
 
 void conv1d_fast_tuning(Conv1dArgs *a)
 {
-    static const int direct = env_flag("HIKONV_CONV1D_DIRECT", -1);
-    static const int big = env_flag("HIKONV_CONV1D_BIG", -1);
     static const int aligned = env_flag("HIKONV_CONV1D_ALIGNED", -1);
-    a->direct_store = direct >= 0 ? direct : 0;
-    a->big_runs = big >= 0 ? big : 1;
+    a->direct_store = 0;
+    a->big_runs = 1;
     a->aligned_runs = aligned >= 0 ? aligned : 1;
+    a->align_outputs = kAlignOutputs;
 }
 
 bool conv1d_fast_applicable(const Conv1dArgs &a)
@@ -371,35 +369,34 @@ bool conv1d_fast_applicable(const Conv1dArgs &a)
     return a.N >= 1 && a.N <= 12 && a.N * a.c <= 32 && a.chunks <= 8 && a.taps <= 64;
 }
 
-int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks, bool big)
+static int chunks_per_run(int N, int share)
 {
-    int ch = 1;
-    switch (N) {
-#define HIKONV_CASE(n) case n: ch = run_chunks(n, big); break;
+    switch (N * 8 + share) {
+#define HIKONV_CASE(n) case n * 8: return run_chunks(n, 0); case n * 8 + 2: return run_chunks(n, 2); \
+                       case n * 8 + 3: return run_chunks(n, 3); case n * 8 + 4: return run_chunks(n, 4);
         HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
         HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
 #undef HIKONV_CASE
-    default: break;
+    default: return 1;
     }
-    return ceil_div(n_blocks, (int64_t)ch * kChunkBlocks);
 }
 
-// Outputs per line-aligned interval: CH*63 blocks hold CH*63*N outputs, the run may start up
-// to N-1 outputs before its interval, and the interval is a whole number of 128-byte lines.
-int64_t conv1d_fast_run_outputs(int N, bool big)
+// blocks a wave run owns
+static int64_t run_blocks(const Conv1dArgs &a)
 {
-    int ch = 1;
-    switch (N) {
-#define HIKONV_CASE(n) case n: ch = run_chunks(n, big); break;
-        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
-        HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
-#undef HIKONV_CASE
-    default: break;
-    }
-    return ((int64_t)ch * kChunkBlocks * N - N + 1) / 32 * 32;
+    return (int64_t)chunks_per_run(a.N, share_of(a)) * chunk_blocks(share_of(a));
 }
 
-// a.tiles_per_row must hold conv1d_fast_runs_per_row(a.N, a.n_blocks, a.big_runs && !a.direct_store)
+int64_t conv1d_fast_runs_per_row(const Conv1dArgs &a) { return ceil_div(a.n_blocks, run_blocks(a)); }
+
+// Outputs per line-aligned interval: the run's blocks hold run_blocks*N outputs, the run may
+// start up to N-1 outputs before its interval, and the interval is a whole number of 128-byte lines.
+int64_t conv1d_fast_run_outputs(const Conv1dArgs &a)
+{
+    return (run_blocks(a) * a.N - a.N + 1) / a.align_outputs * a.align_outputs;
+}
+
+// a.tiles_per_row must hold conv1d_fast_runs_per_row(a), or the number of line-aligned intervals
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
     if (!conv1d_fast_applicable(a)) return hipErrorInvalidValue;

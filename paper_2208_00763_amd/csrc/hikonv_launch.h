@@ -24,12 +24,12 @@ struct Conv1dArgs {
     int64_t n_blocks;        // packed blocks per row
     int CH;                  // wave-chunks of 63 blocks per wave
     int64_t tiles_per_row;
-    int direct_store;        // streaming kernel: 1 = store from registers, 0 = through an LDS staging run
-    int big_runs;            // streaming kernel: 1 = about 1500 outputs per wave run, 0 = about 750
+    int direct_store, big_runs; // unused (kept at 0, 1)
     int aligned_runs;        // streaming kernel, staged stores: 1 = a wave owns an output interval whose
                              // ends fall on 128-byte lines of y (it recomputes a few blocks at its start)
     int64_t run_outputs;     // aligned runs: outputs per interval (a multiple of 32)
-    int y_phase;             // aligned runs: (y / 4) mod 32, position of y inside its 128-byte line
+    int y_phase;             // aligned runs: (y / 4) mod align_outputs, position of y inside its aligned unit
+    int align_outputs;       // aligned runs: outputs per aligned unit (32 = 128 bytes), a power of two
     int32_t *y;
     // requantising kernels: q = min(qmax, max(y, 0) >> shift) in c_out-bit containers
     uint32_t *rq_out;        // [rows][rq_row_dwords]
@@ -44,8 +44,8 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
 // streaming variant (no workgroup barrier) for N <= 12 and N*c <= 32
 bool conv1d_fast_applicable(const Conv1dArgs &a);
 void conv1d_fast_tuning(Conv1dArgs *a);
-int64_t conv1d_fast_runs_per_row(int N, int64_t n_blocks, bool big);
-int64_t conv1d_fast_run_outputs(int N, bool big); // outputs per line-aligned interval
+int64_t conv1d_fast_runs_per_row(const Conv1dArgs &a);
+int64_t conv1d_fast_run_outputs(const Conv1dArgs &a); // outputs per line-aligned interval
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
 // requantised bit-dense output: packed (streaming kernel for N <= 12 and N*c <= 32, a slow
 // general kernel for the other plans up to N = 32) and baseline
