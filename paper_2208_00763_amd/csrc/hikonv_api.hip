@@ -451,6 +451,7 @@ extern "C" int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, co
     int rc = conv1d_common(bits_a, signedness & HIKONV_A_SIGNED, (signedness & HIKONV_W_SIGNED) ? 1 : 0, x_dev,
                            x_format, rows, len, g_dev, taps, out_mode, y_dev, &a);
     if (rc != HIKONV_OK) return rc == 1 ? HIKONV_OK : rc;
+    a.y_phase = (int)((reinterpret_cast<uintptr_t>(y_dev) >> 2) & 31);
     return hip_result(launch_conv1d_unpacked(a, (signedness & HIKONV_A_SIGNED) != 0, static_cast<hipStream_t>(stream)));
 }
 

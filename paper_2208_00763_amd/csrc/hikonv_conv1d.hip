@@ -165,10 +165,13 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
     __syncthreads();
     const int64_t nquads = (p.out_len + 3 + 3) / 4;
     for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
-        const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-        if (q >= nquads) continue;
-        const int64_t row_bit0 = r * p.row_stride_bits;
         const int a_off = (int)((r * p.out_len) & 3);
+        // the quads of a wave start on a 128-byte line of y, as in the packed kernel: the row's
+        // quad 0 sits `lead` quads into its line, so the lanes are shifted back by that much
+        const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> 2) & 7);
+        const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x - lead;
+        if (q < 0 || q >= nquads) continue;
+        const int64_t row_bit0 = r * p.row_stride_bits;
         const int64_t o0 = 4 * q - a_off; // first output of this thread's aligned quad
         // elements f[m - taps + 1 .. m + 3], m = o0 + shift_m; element t feeds output u through tap
         // k = u + taps - 1 - t
@@ -190,7 +193,9 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
         }
         int32_t *yrow = p.y + r * p.out_len;
         if (o0 >= 0 && o0 + 4 <= p.out_len) {
-            *reinterpret_cast<int4 *>(&yrow[o0]) = make_int4(out[0], out[1], out[2], out[3]);
+            typedef int32_t v4i __attribute__((ext_vector_type(4)));
+            const v4i v4 = {out[0], out[1], out[2], out[3]};
+            __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o0])); // streaming hint, whole lines per wave
         } else {
             for (int u = 0; u < 4; ++u)
                 if (o0 + u >= 0 && o0 + u < p.out_len) yrow[o0 + u] = out[u];
@@ -217,10 +222,13 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
 #pragma unroll
     for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
     for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
-        const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-        if (q >= nquads) continue;
-        const int64_t row_bit0 = r * p.row_stride_bits;
         const int a_off = (int)((r * p.out_len) & 3);
+        // the quads of a wave start on a 128-byte line of y, as in the packed kernel: the row's
+        // quad 0 sits `lead` quads into its line, so the lanes are shifted back by that much
+        const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> 2) & 7);
+        const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x - lead;
+        if (q < 0 || q >= nquads) continue;
+        const int64_t row_bit0 = r * p.row_stride_bits;
         const int64_t o0 = 4 * q - a_off;                       // first output of this lane's aligned quad
         const int64_t i0 = o0 + p.shift_m - (taps - 1);          // first element it reads
         const int64_t bit = row_bit0 + i0 * c;
@@ -259,7 +267,9 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
         }
         int32_t *yrow = p.y + r * p.out_len;
         if (o0 >= 0 && o0 + 4 <= p.out_len) {
-            *reinterpret_cast<int4 *>(&yrow[o0]) = make_int4(out[0], out[1], out[2], out[3]);
+            typedef int32_t v4i __attribute__((ext_vector_type(4)));
+            const v4i v4 = {out[0], out[1], out[2], out[3]};
+            __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o0])); // streaming hint, whole lines per wave
         } else {
             for (int u = 0; u < 4; ++u)
                 if (o0 + u >= 0 && o0 + u < p.out_len) yrow[o0 + u] = out[u];
@@ -301,7 +311,7 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
 {
     if (a.taps > 64) return hipErrorInvalidValue;
     const int64_t nquads = (a.out_len + 6) / 4;
-    const int64_t gx = ceil_div(nquads, kThreads);
+    const int64_t gx = ceil_div(nquads + 7, kThreads); // the streaming baseline shifts its lanes by up to 7 quads
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
     if ((a.taps + 3) * a.c <= 64 && a.taps <= 7) {
