@@ -19,7 +19,6 @@ SOURCES = [
     "hikonv_conv2d_narrow.hip",
     "hikonv_conv2d_sreg_unsigned.hip",
     "hikonv_conv2d_sreg_signed.hip",
-    "hikonv_conv2d_sreg_bipolar.hip",
     "hikonv_misc.hip",
 ]
 

@@ -65,7 +65,7 @@ struct Conv2dGeom {
     int pad_d, Dp, Do;   // depth padding, padded depth, output depth (0, 1, 1 for a 2-D layer)
     int Khe;             // kernel rows per packed channel (Kd*Kh)
     int Ho, Wo, Wo1, X, Xs, Hp, terms, terms_pad, n_cog;
-    size_t apk_bytes, toff_bytes, wp_bytes, ps_bytes, ct_bytes, sa_bytes;
+    size_t apk_bytes, toff_bytes, wp_bytes;
 };
 
 inline int pad_terms(int terms) { return (terms + kTermGroup - 1) / kTermGroup * kTermGroup; }
@@ -89,7 +89,6 @@ int conv_geom(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int 
     const bool narrow = plan->L_A == 24 && plan->L_B == 24 && plan->L_acc == 32;
     if (!wide && !narrow) return HIKONV_EUNSUPPORTED;
     if (plan->N > 8 || plan->chunks > 8 || Kd > 64 || Kh > 64 || Kw > 64) return HIKONV_EUNSUPPORTED;
-    if (plan->bipolar && (polyphase || is3d)) return HIKONV_EUNSUPPORTED; // the border correction is 2-D, one phase
     if (!polyphase && pad > Kw - 1) return HIKONV_EUNSUPPORTED; // the leading padding must fit inside the kernel width
     if (H + 2 * pad < Kh || W + 2 * pad < Kw || (is3d && D + 2 * pad < Kd)) return HIKONV_EINVAL;
     if (!is3d && (D != 1 || Kd != 1)) return HIKONV_EINVAL;
@@ -124,15 +123,12 @@ int conv_geom(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int 
     if ((int64_t)g->Ce * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
     g->terms = g->Ce * g->Khe * plan->chunks;
     g->terms_pad = pad_terms(g->terms);
-    g->n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
+    g->n_cog = (Co + 7) / 8;
     if ((int64_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     if ((int64_t)N * g->Do * g->Ho >= (1LL << 31) || (int64_t)g->Do * g->Ho >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     g->apk_bytes = round256((size_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs * 4);
     g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
     g->toff_bytes = round256((size_t)(g->terms_pad + kTermGroup) * 4);
-    g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
-    g->ct_bytes = plan->bipolar ? round256((size_t)Co * Kh * Kh * Kw * Kw * 4) : 0;
-    g->sa_bytes = plan->bipolar ? round256((size_t)N * g->Ho * g->Wo * 4) : 0;
     return HIKONV_OK;
 }
 
@@ -164,8 +160,6 @@ int pack_weights_impl(const hikonv_plan_t *plan, const Conv2dGeom &g, const void
     a.n_cog = g.n_cog;
     a.terms_pad = g.terms_pad;
     a.wp = static_cast<uint32_t *>(packed_dev);
-    a.ps = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(packed_dev) + g.wp_bytes);
-    a.ct = reinterpret_cast<int32_t *>(static_cast<uint8_t *>(packed_dev) + g.wp_bytes + g.ps_bytes);
     return hip_result(launch_pack_weights(a, stream));
 }
 
@@ -217,16 +211,15 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
         return HIKONV_EINVAL;
     if (x_format != HIKONV_FMT_PACKED && (!x_dev || !aligned(x_dev, 4))) return HIKONV_EINVAL;
     if (!aligned(y_dev, 4) || !aligned(w_dev, prepacked ? 256 : 1)) return HIKONV_EINVAL;
-    const size_t need = g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
+    const size_t need = g.apk_bytes + g.toff_bytes + (prepacked ? 0 : g.wp_bytes);
     if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < need) return HIKONV_EWORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
     uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
     int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
-    int32_t *sa = reinterpret_cast<int32_t *>(ws + g.apk_bytes + g.toff_bytes);
     const uint8_t *wpk = static_cast<const uint8_t *>(w_dev);
     if (!prepacked) {
-        uint8_t *dst = ws + g.apk_bytes + g.toff_bytes + g.sa_bytes;
+        uint8_t *dst = ws + g.apk_bytes + g.toff_bytes;
         rc = pack_weights_impl(plan, g, w_dev, Co, C, Kh, Kw, dst, stream);
         if (rc != HIKONV_OK) return rc;
         wpk = dst;
@@ -276,25 +269,29 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     ca.wave_rows = (int64_t)N * g.Do * g.Ho;
     ca.Wo = g.Wo;
     const bool wide = plan->L_A == 32;
-    const bool any_signed = !plan->bipolar && (plan->a_signed || plan->w_signed);
+    const bool any_signed = plan->bipolar || plan->a_signed || plan->w_signed; // {-1,+1}: signed slices
     // the pipelined kernels split after a whole number of term groups
     const int split_terms = (plan->M * plan->chunks) / kTermGroup * kTermGroup;
     ca.pipelined = split_terms >= kTermGroup ? 1 : 0;
     ca.split_terms = split_terms;
     // Kernel choice.  With the weights in scalar registers the term loop has no LDS traffic
-    // and rows need no lane for their zero word; measured faster once a layer has many terms
-    // and enough (row group, channel tile) pairs to fill the chip, slower on small layers.
+    // and rows need no lane for their zero word; it needs enough (row group, channel tile)
+    // pairs to fill the chip and is slower on small layers.
     // HIKONV_CONV2D_KERNEL (tuning / test override, read per call): 1 = LDS-staged kernels
     // only, 2 = scalar-register kernel wherever the plan allows it.
     const char *kernel_env = getenv("HIKONV_CONV2D_KERNEL");
     const int forced_kernel = kernel_env ? atoi(kernel_env) : 0;
     ca.sreg = 0;
     if (forced_kernel != 1 && Co >= 8 &&
-        conv2d_sreg_applicable(plan->N, plan->K, plan->chunks, split_terms, wide, plan->bipolar != 0)) {
+        conv2d_sreg_applicable(plan->N, plan->K, split_terms, wide)) {
         const int real = (g.We + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
         const int lanes = ca.segs ? 64 : (real < g.X ? real : g.X);
         const int64_t groups_s = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, 64 / lanes);
-        ca.sreg = forced_kernel == 2 || (g.terms_pad >= 512 && groups_s * ((Co + 7) / 8) >= 1024) ? 1 : 0;
+        // measured: it wins where the LDS-staged weight tile would be large (>= 1024 terms) and
+        // where splits are frequent (its split needs no lane exchange); otherwise the two are close
+        const bool many_terms = g.terms_pad >= 1024;
+        const bool frequent_splits = g.terms_pad >= 512 && split_terms <= 32;
+        ca.sreg = forced_kernel == 2 || ((many_terms || frequent_splits) && groups_s * ((Co + 7) / 8) >= 1024) ? 1 : 0;
     }
     ca.Lr = g.X;
     if (ca.sreg && ca.segs == 0) {
@@ -324,28 +321,8 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
         args->ksplit = ks;
     };
 
-    ca.fused_bipolar = plan->bipolar && ca.pipelined ? 1 : 0;
-    ca.ones_cog = g.n_cog - 1;
-    ca.ct = reinterpret_cast<const int32_t *>(wpk + g.wp_bytes + g.ps_bytes);
     ca.toff = toff;
-    ca.H = H;
-    ca.W = W;
-    ca.Kw = Kw;
-    ca.pad = pad;
     ca.Kp = plan->K;
-    ca.ones_word0 = 0;
-    for (int k = 0; k < plan->K && k < Kw; ++k) ca.ones_word0 += 1u << (plan->S * k);
-    if (plan->bipolar && !ca.fused_bipolar) {
-        // plain kernel: window sums of a from the all-ones weight group (one channel) ...
-        Conv2dArgs sa_args = ca;
-        sa_args.Co = 1;
-        sa_args.cog0 = g.n_cog - 1;
-        sa_args.y = sa;
-        sa_args.sreg = 0;
-        choose_split(row_groups, &sa_args);
-        rc = hip_result(launch_conv2d_packed(sa_args, wide, any_signed, 2, stream));
-        if (rc != HIKONV_OK) return rc;
-    }
     ca.Co = Co;
     ca.cog0 = 0;
     ca.y = y_dev;
@@ -364,25 +341,6 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     rc = hip_result(launch_conv2d_packed(ca, wide, any_signed, co_tile, stream));
     if (rc != HIKONV_OK) return rc;
 
-    if (plan->bipolar && !ca.fused_bipolar) {
-        // ... and the {-1,+1} correction as a separate pass
-        BipolarFixArgs fa;
-        fa.y = y_dev;
-        fa.sa = sa;
-        fa.ct = ca.ct;
-        fa.Nimg = N;
-        fa.Co = Co;
-        fa.Ho = g.Ho;
-        fa.Wo = g.Wo;
-        fa.C = C;
-        fa.H = H;
-        fa.W = W;
-        fa.Kh = Kh;
-        fa.Kw = Kw;
-        fa.stride = stride;
-        fa.pad = pad;
-        rc = hip_result(launch_bipolar_fix(fa, stream));
-    }
     return rc;
 }
 
@@ -526,7 +484,6 @@ int weights_geom(const hikonv_plan_t *plan, int Co, int C, int Kd, int Kh, int K
     if (plan->mode != HIKONV_MODE_DNN || plan->K < 1 || plan->S < 1 || plan->chunks < 1) return HIKONV_EINVAL;
     const bool polyphase = stride > 1 && plan->taps != Kw && plan->taps == polyphase_taps(Kw, stride);
     if (!polyphase && plan->taps != Kw) return HIKONV_EINVAL;
-    if (plan->bipolar && (polyphase || Kd != 1)) return HIKONV_EUNSUPPORTED;
     *g = Conv2dGeom{};
     g->phases = polyphase ? stride : 1;
     g->Kwe = polyphase ? polyphase_taps(Kw, stride) : Kw;
@@ -536,10 +493,8 @@ int weights_geom(const hikonv_plan_t *plan, int Co, int C, int Kd, int Kh, int K
     if ((int64_t)g->Ce * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
     g->terms = g->Ce * g->Khe * plan->chunks;
     g->terms_pad = pad_terms(g->terms);
-    g->n_cog = (Co + 7) / 8 + (plan->bipolar ? 1 : 0);
+    g->n_cog = (Co + 7) / 8;
     g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
-    g->ps_bytes = plan->bipolar ? round256((size_t)Co * (Kh + 1) * (Kw + 1) * 4) : 0;
-    g->ct_bytes = plan->bipolar ? round256((size_t)Co * Kh * Kh * Kw * Kw * 4) : 0;
     return HIKONV_OK;
 }
 
@@ -550,7 +505,7 @@ extern "C" size_t hikonv_packed_weights_bytes_ex(const hikonv_plan_t *plan, int 
 {
     Conv2dGeom g;
     if (weights_geom(plan, Co, C, Kd, Kh, Kw, stride, &g) != HIKONV_OK) return 0;
-    return g.wp_bytes + g.ps_bytes + g.ct_bytes;
+    return g.wp_bytes;
 }
 
 extern "C" size_t hikonv_packed_weights_bytes(const hikonv_plan_t *plan, int Co, int C, int Kh, int Kw)
@@ -580,7 +535,7 @@ extern "C" size_t hikonv_conv2d_workspace_bytes(const hikonv_plan_t *plan, int N
 {
     Conv2dGeom g;
     if (conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g) != HIKONV_OK) return 0;
-    return g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
+    return g.apk_bytes + g.toff_bytes + (prepacked ? 0 : g.wp_bytes);
 }
 
 extern "C" int hikonv_conv2d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H, int W,
@@ -605,7 +560,7 @@ extern "C" size_t hikonv_conv3d_workspace_bytes(const hikonv_plan_t *plan, int N
 {
     Conv2dGeom g;
     if (conv_geom(plan, N, C, D, H, W, Co, Kd, Kh, Kw, stride, pad, 1, &g) != HIKONV_OK) return 0;
-    return g.apk_bytes + g.toff_bytes + g.sa_bytes + (prepacked ? 0 : g.wp_bytes + g.ps_bytes + g.ct_bytes);
+    return g.apk_bytes + g.toff_bytes + (prepacked ? 0 : g.wp_bytes);
 }
 
 extern "C" int hikonv_conv3d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int D, int H,
@@ -685,7 +640,7 @@ extern "C" int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H,
     if (rc != HIKONV_OK) return rc;
     if (g.phases != 1) return HIKONV_EUNSUPPORTED; // the fused packing writes one column phase
     if (!next_workspace_dev || !aligned(next_workspace_dev, 256) ||
-        next_workspace_bytes < g.apk_bytes + g.toff_bytes + g.sa_bytes)
+        next_workspace_bytes < g.apk_bytes + g.toff_bytes)
         return HIKONV_EWORKSPACE;
     uint8_t *ws = static_cast<uint8_t *>(next_workspace_dev);
     PackActArgs pa = pack_act_args(next_plan, g, N, C, 1, Hn, Wn, 1, next_Kh, next_pad, reinterpret_cast<uint32_t *>(ws),

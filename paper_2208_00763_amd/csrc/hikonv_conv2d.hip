@@ -1,6 +1,6 @@
 // Kernels around the packed DNN-layer path: runtime packing of activation rows into A
-// words, offline packing of weights into B words, the {-1,+1} correction for binarised
-// layers, and the unpacked one-product-per-multiply baseline.
+// words, offline packing of weights into B words, and the unpacked
+// one-product-per-multiply baseline.
 #include <type_traits>
 #include "hikonv_conv2d_kernel.h"
 #include "hikonv_conv2d_sreg.h"
@@ -79,14 +79,16 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
             if (p.x_format == HIKONV_FMT_INT8) {
                 const uint8_t byte = rowp[is];
                 if (p.bipolar)
-                    v = (int8_t)byte > 0 ? 1 : 0;
+                    v = (int8_t)byte > 0 ? 1 : -1;
                 else
                     v = p.a_signed ? __builtin_amdgcn_sbfe((int)byte, 0, p.b) : (int)__builtin_amdgcn_ubfe(byte, 0, p.b);
             } else {
                 const int bit = is * p.c;
                 const uint32_t w = reinterpret_cast<const uint32_t *>(rowp)[bit >> 5];
-                v = (p.a_signed && !p.bipolar) ? __builtin_amdgcn_sbfe((int)w, bit & 31, p.b)
-                                               : (int)__builtin_amdgcn_ubfe(w, bit & 31, p.b);
+                if (p.bipolar)
+                    v = ((w >> (bit & 31)) & 1u) ? 1 : -1;
+                else
+                    v = p.a_signed ? __builtin_amdgcn_sbfe((int)w, bit & 31, p.b) : (int)__builtin_amdgcn_ubfe(w, bit & 31, p.b);
             }
             a += (uint32_t)v << (p.S * j);
         }
@@ -116,82 +118,22 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
     const int c = term / (p.chunks * p.Kh);
     const int csrc = c / p.phases, phase = c - csrc * p.phases;
     const int co = cog * 8 + c8;
-    const bool ones_group = p.bipolar && cog == p.n_cog - 1;
     uint32_t bw = 0;
     for (int k = 0; k < p.Kp; ++k) {
         const int j = ch * p.Kp + k; // tap of the reversed row
         if (j >= p.Kw) break;
         int32_t v = 0;
         const int ksrc = (p.Kw - 1 - j) * p.phases + phase; // source tap
-        if (ones_group) {
-            v = c8 == 0 ? 1 : 0;
-        } else if (co < p.Co && ksrc < p.Kwsrc) {
+        if (co < p.Co && ksrc < p.Kwsrc) {
             const uint8_t byte = p.w[(((int64_t)co * p.Csrc + csrc) * p.Kh + kh) * p.Kwsrc + ksrc];
             if (p.bipolar)
-                v = (int8_t)byte > 0 ? 1 : 0;
+                v = (int8_t)byte > 0 ? 1 : -1;
             else
                 v = p.w_signed ? (int32_t)(int8_t)byte : (int32_t)byte;
         }
         bw += (uint32_t)v << (p.S * k);
     }
     p.wp[idx] = bw;
-}
-
-// PS[co][i][j] = sum_{kh<i, kw<j} sum_ci beta[co][ci][kh][kw]   (beta = 1 for weight +1)
-__global__ __launch_bounds__(256) void k_weight_prefix(PackWArgs p)
-{
-    const int per_co = (p.Kh + 1) * (p.Kw + 1);
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= p.Co * per_co) return;
-    const int co = idx / per_co, i = (idx % per_co) / (p.Kw + 1), j = idx % (p.Kw + 1);
-    int32_t s = 0;
-    for (int ci = 0; ci < p.C; ++ci)
-        for (int kh = 0; kh < i; ++kh)
-            for (int kw = 0; kw < j; ++kw)
-                s += (int8_t)p.w[(((int64_t)co * p.C + ci) * p.Kh + kh) * p.Kw + kw] > 0 ? 1 : 0;
-    p.ps[idx] = s;
-}
-
-// CT[co][a][b][c][d] = C*(Kh-a-b)*(Kw-c-d) - 2 * sum_{kh in [a,Kh-b), kw in [c,Kw-d)} sum_ci beta:
-// the part of the {-1,+1} correction that depends only on the channel and on which kernel
-// taps fall inside the image (a, b rows cut at the top / bottom; c, d columns cut left / right).
-__global__ __launch_bounds__(256) void k_class_table(PackWArgs p)
-{
-    const int per_co = p.Kh * p.Kh * p.Kw * p.Kw;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= p.Co * per_co) return;
-    const int co = idx / per_co;
-    int r = idx % per_co;
-    const int d = r % p.Kw;
-    r /= p.Kw;
-    const int c = r % p.Kw;
-    r /= p.Kw;
-    const int b = r % p.Kh, a = r / p.Kh;
-    int32_t v = 0;
-    if (a + b < p.Kh && c + d < p.Kw) {
-        const int st = p.Kw + 1;
-        const int32_t *ps = p.ps + (int64_t)co * (p.Kh + 1) * st;
-        const int kh_hi = p.Kh - b, kw_hi = p.Kw - d;
-        const int32_t rect = ps[kh_hi * st + kw_hi] - ps[a * st + kw_hi] - ps[kh_hi * st + c] + ps[a * st + c];
-        v = p.C * (kh_hi - a) * (kw_hi - c) - 2 * rect;
-    }
-    p.ct[idx] = v;
-}
-
-// {-1,+1} layers: with x = 2a - m and w = 2 beta - 1 (a, beta in {0,1}; m = 1 inside the
-// image, 0 in the zero padding):  sum x w = 4 sum a beta - 2 sum a - 2 sum m beta + sum m.
-__global__ __launch_bounds__(256) void k_bipolar_fix(BipolarFixArgs p)
-{
-    const int64_t total = (int64_t)p.Nimg * p.Co * p.Ho * p.Wo;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
-    const int wo = (int)(idx % p.Wo);
-    const int ho = (int)((idx / p.Wo) % p.Ho);
-    const int co = (int)((idx / ((int64_t)p.Wo * p.Ho)) % p.Co);
-    const int n = (int)(idx / ((int64_t)p.Wo * p.Ho * p.Co));
-    const int32_t sa = p.sa[((int64_t)n * p.Ho + ho) * p.Wo + wo];
-    p.y[idx] = bipolar_value(p.ct, co, ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, p.y[idx], sa);
-    return;
 }
 
 // Baseline: direct layer, one v_mad_i32_i24 per low-bit product.  One lane owns one output
@@ -396,16 +338,6 @@ hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream)
     hipError_t e = grid_1d((int64_t)a.n_cog * a.terms_pad * 8, &g);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_pack_weights, g, dim3(256), 0, stream, a);
-    e = hipGetLastError();
-    if (e != hipSuccess || !a.bipolar) return e;
-    e = grid_1d((int64_t)a.Co * (a.Kh + 1) * (a.Kw + 1), &g);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_weight_prefix, g, dim3(256), 0, stream, a);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    e = grid_1d((int64_t)a.Co * a.Kh * a.Kh * a.Kw * a.Kw, &g);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_class_table, g, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -423,20 +355,10 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed,
     if (a.sreg) {
         if (!wide || co_tile != 8) return hipErrorInvalidValue;
         const int hi = a.Kp - 1;
-        if (a.fused_bipolar) return launch_conv2d_sreg_bipolar(a, hi, g, stream);
         return any_signed ? launch_conv2d_sreg_signed(a, hi, g, stream) : launch_conv2d_sreg_unsigned(a, hi, g, stream);
     }
     return wide ? launch_conv2d_wide(a, any_signed, co_tile, g, stream)
                 : launch_conv2d_narrow(a, any_signed, co_tile, g, stream);
-}
-
-hipError_t launch_bipolar_fix(const BipolarFixArgs &a, hipStream_t stream)
-{
-    dim3 g;
-    hipError_t e = grid_1d((int64_t)a.Nimg * a.Co * a.Ho * a.Wo, &g);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_bipolar_fix, g, dim3(256), 0, stream, a);
-    return hipGetLastError();
 }
 
 hipError_t launch_conv2d_unpacked(const Conv2dDirectArgs &a, hipStream_t stream)

@@ -23,6 +23,8 @@
 // group are issued before the multiplies of the current one, and the term range of a row
 // group can be divided among the 2 or 4 waves of a workgroup (partial int32 sums are
 // reduced through LDS), which supplies enough waves for layers with few output rows.
+// {-1,+1} layers are ordinary signed layers here: their values (0 in the zero padding)
+// travel as signed slices.
 #ifndef HIKONV_CONV2D_KERNEL_H
 #define HIKONV_CONV2D_KERNEL_H
 
@@ -194,42 +196,15 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
 }
 
 
-// {-1,+1} layers (x = 2a - m, w = 2 beta - 1; a, beta in {0,1}; m = 1 inside the image):
-//   sum x w = 4 sum a beta - 2 sum a - 2 sum m beta + sum m
-// The last two terms depend only on the channel and on which kernel taps fall inside the
-// image; they come from the border-class table built when the weights are packed.
-__device__ __forceinline__ int32_t bipolar_value(const int32_t *ct, int co, int ho, int wo, int H, int W, int Kh, int Kw,
-                                                 int stride, int pad, int32_t sum_ab, int32_t sum_a)
-{
-    int top = pad - ho * stride, bottom = ho * stride + Kh - pad - H;  // kernel rows cut off above / below
-    int left = pad - wo * stride, right = wo * stride + Kw - pad - W;  // kernel columns cut off left / right
-    top = top < 0 ? 0 : top;
-    bottom = bottom < 0 ? 0 : bottom;
-    left = left < 0 ? 0 : left;
-    right = right < 0 ? 0 : right;
-    if (top + bottom >= Kh || left + right >= Kw) return 4 * sum_ab - 2 * sum_a; // no tap inside the image
-    const int cls = ((top * Kh + bottom) * Kw + left) * Kw + right;
-    return 4 * sum_ab - 2 * sum_a + ct[(int64_t)co * Kh * Kh * Kw * Kw + cls];
-}
+constexpr int kTermTile = 1536; // terms whose weights are staged in LDS at a time (54 KB + offsets at most)
 
-// all-ones B word of chunk ch: one bit at the bottom of every slice that holds a real tap
-__device__ __forceinline__ uint32_t ones_word_of_chunk(const Conv2dArgs &p, int ch)
-{
-    uint32_t v = 0;
-    for (int k = 0; k < p.Kp; ++k)
-        if (ch * p.Kp + k < p.Kw) v += 1u << (p.S * k);
-    return v;
-}
-
-constexpr int kTermTile = 2048; // terms whose weights are staged in LDS at a time (72 KB at most)
-
-template <int N, int CO_T, bool ANY_SIGNED, bool WIDE, bool BIP>
+template <int N, int CO_T, bool ANY_SIGNED, bool WIDE>
 __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 {
     constexpr int U = kTermGroup;
-    constexpr int CE = CO_T + (BIP ? 1 : 0); // BIP: one more accumulator collects sum a (all-ones weights)
+    constexpr int CE = CO_T;
     // LDS: weight words of the current term tile [tile][CO_T], the activation offsets of its
-    // terms [tile + U] and (BIP) its all-ones words [tile]; reused at the end for the slice reduction
+    // terms [tile + U]; reused at the end for the slice reduction
     extern __shared__ __attribute__((aligned(16))) uint32_t s_mem[];
 
     const uint32_t *__restrict__ apk = p.apk;
@@ -248,7 +223,6 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     const int tile_cap = p.terms_pad < kTermTile ? p.terms_pad : kTermTile;
     uint32_t *s_w = s_mem;                                   // [tile_cap][CO_T]
     int32_t *s_off = reinterpret_cast<int32_t *>(s_w + tile_cap * CO_T); // [tile_cap + U]
-    uint32_t *s_w1 = reinterpret_cast<uint32_t *>(s_off + tile_cap + U);  // [tile_cap] all-ones B words (BIP)
 
     SplitState<N, CE, ANY_SIGNED, WIDE> st;
     st.init(p.S);
@@ -283,9 +257,6 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
             }
         }
         for (int t = tid; t < tile_n + U; t += 256) s_off[t] = p.toff[tile0 + t];
-        if (BIP) // the sum-of-a accumulator multiplies by all-ones words; padding terms contribute nothing
-            for (int t = tid; t < tile_n; t += 256)
-                s_w1[t] = tile0 + t < p.terms ? ones_word_of_chunk(p, (tile0 + t) % p.chunks) : 0u;
         __syncthreads();
 
         // this wave's slice of the tile, in groups of U terms, two register buffers for the
@@ -320,7 +291,6 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 #pragma unroll
                     for (int c = 0; c < CO_T; ++c) w[c] = s_w[(t + u) * CO_T + c];
                 }
-                if (BIP) w[CO_T] = s_w1[t + u];
 #pragma unroll
                 for (int c = 0; c < CE; ++c) st.mad(c, a[u], w[c]);
             }
@@ -365,7 +335,7 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
         const int w0 = wave - ks; // first wave of this row group
 #pragma unroll
         for (int c = 0; c < CE; ++c) {
-            if (!((c >= c_begin && c < c_end) || (BIP && c == CO_T))) continue;
+            if (!(c >= c_begin && c < c_end)) continue;
 #pragma unroll
             for (int j = 0; j < N; ++j) {
                 int32_t v = 0;
@@ -385,10 +355,7 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
             const int w1 = x * N + j - p.off; // stride-1 output column
             if (w1 >= 0 && w1 < p.Wo1 && (p.stride_w == 1 || w1 % p.stride_w == 0)) {
                 const int wo = p.stride_w == 1 ? w1 : w1 / p.stride_w;
-                const int32_t v = st.out[c][j] - unbias;
-                yrow[wo] = BIP ? bipolar_value(p.ct, co0 + c, m.ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, v,
-                                               st.out[CO_T][j] - unbias)
-                               : v;
+                yrow[wo] = st.out[c][j] - unbias;
             }
         }
     }
@@ -397,9 +364,9 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 // dynamic LDS bytes of k_conv2d_pipe
 inline size_t conv2d_pipe_lds(const Conv2dArgs &a, int co_tile, int n)
 {
-    const int ce = co_tile + (a.fused_bipolar ? 1 : 0);
+    const int ce = co_tile;
     const size_t tile_cap = a.terms_pad < kTermTile ? a.terms_pad : kTermTile;
-    const size_t stage = (tile_cap * co_tile + tile_cap + kTermGroup + (a.fused_bipolar ? tile_cap : 0)) * 4;
+    const size_t stage = (tile_cap * co_tile + tile_cap + kTermGroup) * 4;
     const size_t reduce = a.ksplit > 1 ? (size_t)4 * ce * n * 64 * 4 : 0;
     return stage > reduce ? stage : reduce;
 }
@@ -409,16 +376,10 @@ inline void launch_conv2d_n(const Conv2dArgs &a, int co_tile, dim3 g, hipStream_
 {
     if (a.pipelined) {
         const size_t lds = conv2d_pipe_lds(a, co_tile, N);
-        if (a.fused_bipolar) {
-            if (ANY_SIGNED) return; // bipolar layers are packed as unsigned bits
-            if (co_tile == 8)
-                hipLaunchKernelGGL((k_conv2d_pipe<N, 8, false, WIDE, true>), g, dim3(256), lds, stream, a);
-            else
-                hipLaunchKernelGGL((k_conv2d_pipe<N, 2, false, WIDE, true>), g, dim3(256), lds, stream, a);
-        } else if (co_tile == 8)
-            hipLaunchKernelGGL((k_conv2d_pipe<N, 8, ANY_SIGNED, WIDE, false>), g, dim3(256), lds, stream, a);
+        if (co_tile == 8)
+            hipLaunchKernelGGL((k_conv2d_pipe<N, 8, ANY_SIGNED, WIDE>), g, dim3(256), lds, stream, a);
         else
-            hipLaunchKernelGGL((k_conv2d_pipe<N, 2, ANY_SIGNED, WIDE, false>), g, dim3(256), lds, stream, a);
+            hipLaunchKernelGGL((k_conv2d_pipe<N, 2, ANY_SIGNED, WIDE>), g, dim3(256), lds, stream, a);
     } else {
         if (co_tile == 8)
             hipLaunchKernelGGL((k_conv2d_packed<N, 8, ANY_SIGNED, WIDE>), g, dim3(256), 0, stream, a);

@@ -82,11 +82,10 @@ __device__ __forceinline__ LaneMapS map_lane_sreg(const Conv2dArgs &p, int64_t r
     return m;
 }
 
-// Overlap-add with the previous lane's high segments, {-1,+1} correction, bounds and stride
-// handling, store of one output channel.  v / sa: N own fields then HI high fields.
-template <int N, int HI, bool BIP>
-__device__ __forceinline__ void finish_channel(const Conv2dArgs &p, const LaneMapS &m, int co, const int32_t (&v)[N + HI],
-                                               const int32_t (&sa)[N + HI])
+// Overlap-add with the previous lane's high segments, bounds and stride handling, store of
+// one output channel.  v: N own fields then HI high fields.
+template <int N, int HI>
+__device__ __forceinline__ void finish_channel(const Conv2dArgs &p, const LaneMapS &m, int co, const int32_t (&v)[N + HI])
 {
     int32_t o[N];
 #pragma unroll
@@ -106,21 +105,8 @@ __device__ __forceinline__ void finish_channel(const Conv2dArgs &p, const LaneMa
         const int w1 = x * N + j - p.off; // stride-1 output column
         if (w1 >= 0 && w1 < p.Wo1 && (p.stride_w == 1 || w1 % p.stride_w == 0)) {
             const int wo = p.stride_w == 1 ? w1 : w1 / p.stride_w;
-            const int32_t val = own ? o[j] : v[j];
-            yrow[wo] = BIP ? bipolar_value(p.ct, co, m.ho, wo, p.H, p.W, p.Kh, p.Kw, p.stride, p.pad, val, sa[j]) : val;
+            yrow[wo] = own ? o[j] : v[j];
         }
-    }
-}
-
-// sa (fields of the all-ones accumulator) -> window sums of a at the lane's own outputs
-// (overlap-added) followed by its high segments
-template <int N, int HI>
-__device__ __forceinline__ void finish_sum_a(const LaneMapS &m, int32_t (&sa)[N + HI])
-{
-#pragma unroll
-    for (int j = 0; j < HI; ++j) {
-        const int32_t r = (int32_t)lane_shr1((uint32_t)sa[N + j]);
-        if (j < N) sa[j] += m.recv ? r : 0;
     }
 }
 
@@ -165,15 +151,15 @@ __device__ __forceinline__ uint64_t field_bias(int S)
     return bias;
 }
 
-template <int N, int HI, bool ANY_SIGNED, bool BIP>
+template <int N, int HI, bool ANY_SIGNED>
 __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
 {
     constexpr int U = kTermGroup;
     constexpr int CO_T = 8;
-    constexpr int CE = CO_T + (BIP ? 1 : 0); // BIP: one more accumulator collects sum a (all-ones weights)
+    constexpr int CE = CO_T;
     constexpr int NF = N + HI;
     static_assert(U == 4, "offset table is read four terms at a time");
-    extern __shared__ __attribute__((aligned(16))) int32_t s_red[]; // [4 waves][5*NF][64]
+    extern __shared__ __attribute__((aligned(16))) int32_t s_red[]; // [4 waves][4*NF][64]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -188,7 +174,6 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)(p.cog0 + blockIdx.y) * p.terms_pad * 32;
     const char *trow = reinterpret_cast<const char *>(p.toff); // 16 bytes per term group
     const char *abytes = reinterpret_cast<const char *>(p.apk);
-    const uint32_t ones = p.ones_word0;
 
     const int S = p.S;
     const uint64_t bias = ANY_SIGNED ? field_bias<NF>(S) : 0;
@@ -260,7 +245,6 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
                 mad_sreg<ANY_SIGNED>(acc[5], a[u], b[u].s5);
                 mad_sreg<ANY_SIGNED>(acc[6], a[u], b[u].s6);
                 mad_sreg<ANY_SIGNED>(acc[7], a[u], b[u].s7);
-                if (BIP) mad_sreg<false>(acc[CE - 1], a[u], ones);
             }
             since += U;
             if (since >= p.split_terms) split(); // split_terms is a multiple of U
@@ -291,17 +275,6 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     }
     if (since) split();
 
-    if (BIP && g_begin < g_end && g_end == p.terms_pad / U && p.terms_pad != p.terms) {
-        // the padding terms of the last group (offset 0, zero B words) still met the all-ones
-        // word: take their contribution out of the sum of a again
-        const uint32_t a = *reinterpret_cast<const uint32_t *>(abytes + lane_byte);
-        const uint64_t w = (uint64_t)a * ones * (uint32_t)(p.terms_pad - p.terms);
-        const uint32_t fm = (1u << S) - 1u;
-#pragma unroll
-        for (int j = 0; j < NF - 1; ++j) out[CE - 1][j] -= (int32_t)((uint32_t)(w >> (S * j)) & fm);
-        out[CE - 1][NF - 1] -= (int32_t)(uint32_t)(w >> (S * (NF - 1)));
-    }
-
     // remove the biases: every split added 2^(S-1) to each segment but the top one
     if (ANY_SIGNED) {
         const int32_t unbias = nsplit * (1 << (S - 1));
@@ -311,24 +284,15 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
             for (int j = 0; j < NF - 1; ++j) out[c][j] -= unbias;
     }
 
-    int32_t sa[NF];
-#pragma unroll
-    for (int j = 0; j < NF; ++j) sa[j] = 0;
-
     if (p.ksplit == 1) {
-        if (BIP) {
 #pragma unroll
-            for (int j = 0; j < NF; ++j) sa[j] = out[CE - 1][j];
-            finish_sum_a<N, HI>(m, sa);
-        }
-#pragma unroll
-        for (int c = 0; c < CO_T; ++c) finish_channel<N, HI, BIP>(p, m, co0 + c, out[c], sa);
+        for (int c = 0; c < CO_T; ++c) finish_channel<N, HI>(p, m, co0 + c, out[c]);
         return;
     }
 
-    // ksplit > 1: two passes through LDS, pass 0 = channels 0..3 (and sum a), pass 1 = channels 4..7.
+    // ksplit > 1: two passes through LDS, pass 0 = channels 0..3, pass 1 = channels 4..7.
     // Slot s of a pass holds one channel: [wave][s*NF + j][lane].
-    constexpr int SLOTS = 5;
+    constexpr int SLOTS = 4;
     const int w0 = wave - ks; // first wave of this row group
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
@@ -338,20 +302,7 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
         for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int j = 0; j < NF; ++j) dst[(s * NF + j) * 64] = out[pass * 4 + s][j];
-        if (BIP && pass == 0) {
-#pragma unroll
-            for (int j = 0; j < NF; ++j) dst[(4 * NF + j) * 64] = out[CE - 1][j];
-        }
         __syncthreads();
-        if (BIP && pass == 0) {
-#pragma unroll
-            for (int j = 0; j < NF; ++j) {
-                int32_t v = 0;
-                for (int k2 = 0; k2 < p.ksplit; ++k2) v += s_red[((w0 + k2) * SLOTS * NF + 4 * NF + j) * 64 + lane];
-                sa[j] = v;
-            }
-            finish_sum_a<N, HI>(m, sa);
-        }
         for (int s = ks; s < 4; s += p.ksplit) { // wave-uniform trip count
             int32_t v[NF];
 #pragma unroll
@@ -360,44 +311,44 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
                 for (int k2 = 0; k2 < p.ksplit; ++k2) t += s_red[((w0 + k2) * SLOTS * NF + s * NF + j) * 64 + lane];
                 v[j] = t;
             }
-            finish_channel<N, HI, BIP>(p, m, co0 + pass * 4 + s, v, sa);
+            finish_channel<N, HI>(p, m, co0 + pass * 4 + s, v);
         }
     }
 }
 
 inline size_t conv2d_sreg_lds(const Conv2dArgs &a, int n, int hi)
 {
-    return a.ksplit > 1 ? (size_t)4 * 5 * (n + hi) * 64 * 4 : 0;
+    return a.ksplit > 1 ? (size_t)4 * 4 * (n + hi) * 64 * 4 : 0;
 }
 
-template <int N, bool ANY_SIGNED, bool BIP>
+template <int N, bool ANY_SIGNED>
 inline void launch_conv2d_sreg_n(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream)
 {
     const size_t lds = conv2d_sreg_lds(a, N, hi);
     switch (hi) {
-    case 0: hipLaunchKernelGGL((k_conv2d_sreg<N, 0, ANY_SIGNED, BIP>), g, dim3(256), lds, stream, a); break;
+    case 0: hipLaunchKernelGGL((k_conv2d_sreg<N, 0, ANY_SIGNED>), g, dim3(256), lds, stream, a); break;
     case 1:
-        if constexpr (N >= 1) hipLaunchKernelGGL((k_conv2d_sreg<N, 1, ANY_SIGNED, BIP>), g, dim3(256), lds, stream, a);
+        if constexpr (N >= 1) hipLaunchKernelGGL((k_conv2d_sreg<N, 1, ANY_SIGNED>), g, dim3(256), lds, stream, a);
         break;
     case 2:
-        if constexpr (N >= 2) hipLaunchKernelGGL((k_conv2d_sreg<N, 2, ANY_SIGNED, BIP>), g, dim3(256), lds, stream, a);
+        if constexpr (N >= 2) hipLaunchKernelGGL((k_conv2d_sreg<N, 2, ANY_SIGNED>), g, dim3(256), lds, stream, a);
         break;
     default: break;
     }
 }
 
-template <bool ANY_SIGNED, bool BIP>
+template <bool ANY_SIGNED>
 inline hipError_t launch_conv2d_sreg_sw(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream)
 {
     switch (a.N) {
-    case 1: launch_conv2d_sreg_n<1, ANY_SIGNED, BIP>(a, hi, g, stream); break;
-    case 2: launch_conv2d_sreg_n<2, ANY_SIGNED, BIP>(a, hi, g, stream); break;
-    case 3: launch_conv2d_sreg_n<3, ANY_SIGNED, BIP>(a, hi, g, stream); break;
-    case 4: launch_conv2d_sreg_n<4, ANY_SIGNED, BIP>(a, hi, g, stream); break;
-    case 5: launch_conv2d_sreg_n<5, ANY_SIGNED, BIP>(a, hi, g, stream); break;
-    case 6: launch_conv2d_sreg_n<6, ANY_SIGNED, BIP>(a, hi, g, stream); break;
-    case 7: launch_conv2d_sreg_n<7, ANY_SIGNED, BIP>(a, hi, g, stream); break;
-    case 8: launch_conv2d_sreg_n<8, ANY_SIGNED, BIP>(a, hi, g, stream); break;
+    case 1: launch_conv2d_sreg_n<1, ANY_SIGNED>(a, hi, g, stream); break;
+    case 2: launch_conv2d_sreg_n<2, ANY_SIGNED>(a, hi, g, stream); break;
+    case 3: launch_conv2d_sreg_n<3, ANY_SIGNED>(a, hi, g, stream); break;
+    case 4: launch_conv2d_sreg_n<4, ANY_SIGNED>(a, hi, g, stream); break;
+    case 5: launch_conv2d_sreg_n<5, ANY_SIGNED>(a, hi, g, stream); break;
+    case 6: launch_conv2d_sreg_n<6, ANY_SIGNED>(a, hi, g, stream); break;
+    case 7: launch_conv2d_sreg_n<7, ANY_SIGNED>(a, hi, g, stream); break;
+    case 8: launch_conv2d_sreg_n<8, ANY_SIGNED>(a, hi, g, stream); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -405,7 +356,6 @@ inline hipError_t launch_conv2d_sreg_sw(const Conv2dArgs &a, int hi, dim3 g, hip
 
 hipError_t launch_conv2d_sreg_unsigned(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream);
 hipError_t launch_conv2d_sreg_signed(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream);
-hipError_t launch_conv2d_sreg_bipolar(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream);
 
 } // namespace hikonv
 #endif

@@ -4,6 +4,6 @@
 namespace hikonv {
 hipError_t launch_conv2d_sreg_signed(const Conv2dArgs &a, int hi, dim3 g, hipStream_t stream)
 {
-    return launch_conv2d_sreg_sw<true, false>(a, hi, g, stream);
+    return launch_conv2d_sreg_sw<true>(a, hi, g, stream);
 }
 } // namespace hikonv

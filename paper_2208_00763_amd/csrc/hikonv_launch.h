@@ -93,11 +93,9 @@ struct PackWArgs {
                              // tap j of a phase is source tap j*phases + phase (zero beyond Kwsrc)
     int Co, C, Kh, Kw, w_signed, bipolar;
     int Kp, S, chunks;
-    int n_cog;               // ceil(Co / 8) (+1 all-ones group when bipolar)
+    int n_cog;               // ceil(Co / 8)
     int terms_pad;           // C*Kh*chunks rounded up to the pipeline group (zero words beyond)
     uint32_t *wp;            // [n_cog][terms_pad][8]
-    int32_t *ps;             // bipolar only: [Co][Kh+1][Kw+1] prefix sums of sum_ci beta
-    int32_t *ct;             // bipolar only: [Co][Kh][Kh][Kw][Kw] correction C*taps - 2*sum beta per border class
 };
 hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream);
 
@@ -118,13 +116,8 @@ struct Conv2dArgs {
     int pipelined;           // 1: k_conv2d_pipe, 0: k_conv2d_packed
     int ksplit;              // waves of a workgroup sharing one row group (1, 2 or 4)
     int split_terms;         // terms between splits in the pipelined kernel (multiple of 4)
-    int fused_bipolar;       // 1: the pipelined kernel also sums a and applies the {-1,+1} correction
-    int ones_cog;            // weight group holding the all-ones words (bipolar)
-    const int32_t *ct;       // bipolar: [Co][Kh][Kh][Kw][Kw] border-class correction table
     const int32_t *toff;     // [terms_pad + kTermGroup] activation word offset of every term
-    uint32_t ones_word0;     // bipolar: the all-ones B word of chunk 0
     int Kp;                  // taps per B word
-    int H, W, Kw, pad;       // bipolar correction needs the image and kernel extents
     int Co, cog0;            // output channels to write, first weight group
     int64_t chunk_stride;    // words between chunk planes of apk
     int rows_per_wave, segs; // lane mapping
@@ -139,21 +132,12 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed,
 
 // plans this kernel covers: 32x32+64 multiply, at most three taps per B word and no more
 // high segments than own segments, a whole number of term groups between splits
-inline bool conv2d_sreg_applicable(int N, int Kp, int chunks, int split_terms, bool wide, bool bipolar)
+inline bool conv2d_sreg_applicable(int N, int Kp, int split_terms, bool wide)
 {
     if (!wide || N < 1 || N > 8 || Kp < 1 || Kp > 3 || Kp - 1 > N) return false;
     if (split_terms < kTermGroup) return false;
-    if (bipolar && chunks != 1) return false;
     return true;
 }
-
-struct BipolarFixArgs {
-    int32_t *y;              // in: sum a*beta; out: sum x*w
-    const int32_t *sa;       // [Nimg][Ho][Wo] window sums of a
-    const int32_t *ct;       // [Co][Kh][Kh][Kw][Kw]
-    int Nimg, Co, Ho, Wo, C, H, W, Kh, Kw, stride, pad;
-};
-hipError_t launch_bipolar_fix(const BipolarFixArgs &a, hipStream_t stream);
 
 struct Conv2dDirectArgs {
     const uint8_t *x, *w;

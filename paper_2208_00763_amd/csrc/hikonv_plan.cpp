@@ -64,7 +64,7 @@ inline bool fits_width(Range r, int width, bool is_signed)
 
 struct Req {
     int p, q;
-    bool a_signed, w_signed, any_signed;
+    bool a_signed, w_signed, any_signed, bipolar;
     int L_A, L_B, L_acc, mode, M, taps;
     bool tight;
     Range fa, gw, prod;
@@ -75,8 +75,14 @@ Req make_req(const hikonv_plan_t &in)
     Req r;
     r.p = in.bits_a;
     r.q = in.bits_w;
-    r.a_signed = in.a_signed != 0 && !in.bipolar;
-    r.w_signed = in.w_signed != 0 && !in.bipolar;
+    r.a_signed = in.a_signed != 0;
+    r.w_signed = in.w_signed != 0;
+    r.bipolar = in.bipolar != 0;
+    if (r.bipolar) {
+        // {-1,+1} values (0 in the zero padding) travel as signed two-bit slices
+        r.p = r.q = 2;
+        r.a_signed = r.w_signed = true;
+    }
     r.any_signed = r.a_signed || r.w_signed;
     r.L_A = in.L_A;
     r.L_B = in.L_B;
@@ -85,8 +91,8 @@ Req make_req(const hikonv_plan_t &in)
     r.M = in.mode == HIKONV_MODE_DNN ? (in.M > 0 ? in.M : 1) : 1;
     r.taps = in.taps;
     r.tight = in.tight != 0;
-    r.fa = value_range(r.p, r.a_signed);
-    r.gw = value_range(r.q, r.w_signed);
+    r.fa = r.bipolar ? Range{-1, 1} : value_range(r.p, r.a_signed);
+    r.gw = r.bipolar ? Range{-1, 1} : value_range(r.q, r.w_signed);
     r.prod = mul_range(r.fa, r.gw);
     return r;
 }
@@ -189,7 +195,8 @@ Cand search(const Req &r, bool paper_only)
             // tight: the smallest slice that is provably exact for the declared value ranges
             // (the paper's p+q+G_b is an upper bound on what the segment sums need)
             c.s = 0;
-            for (int s = r.tight ? 1 : s0; s <= s0 + 1; ++s)
+            // ({-1,+1} data always: products are -1, 0 or 1, far below what two-bit operands could give)
+            for (int s = r.tight || r.bipolar ? 1 : s0; s <= s0 + 1; ++s)
                 if (exact_ok(r, n, k, s)) {
                     c.s = s;
                     break;

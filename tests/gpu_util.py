@@ -91,7 +91,7 @@ def run_conv3d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
                   (w + 2 * pad - kw) // stride + 1)
     count = n * co * do * ho * wo
     y = torch.full((count + 8,), -77777, dtype=torch.int32, device="cuda")
-    x_d = compact(x_np.reshape(n * c * d * h, w), plan.bits_a) if fmt == hk.FMT_BITDENSE else dev(x_np)
+    x_d = compact(x_np.reshape(n * c * d * h, w), plan.bits_a, bool(plan.bipolar)) if fmt == hk.FMT_BITDENSE else dev(x_np)
     w_d = dev(w_np)
     ws_bytes = hk.hikonv_conv3d_workspace_bytes(plan, n, c, d, h, w, co, kd, kh, kw, stride, pad, prepacked)
     assert ws_bytes > 0

@@ -265,8 +265,9 @@ def test_workspace_and_packed_weight_sizes():
     assert ws >= 64 * 58 * (19 + 1) * 4 and pw >= 8 * 64 * 3 * 8 * 4
     assert hk.hikonv_conv2d_workspace_bytes(plan, 1, 64, 56, 56, 64, 3, 5, 1, 1, True) == 0   # taps differ from the plan
     bip = hk.hikonv_plan_ex(bits_a=1, bits_w=1, bipolar=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3)
-    assert hk.hikonv_packed_weights_bytes(bip, 256, 256, 3, 3) > hk.hikonv_packed_weights_bytes(
-        hk.Plan(**{**bip.as_dict(), "bipolar": 0}), 256, 256, 3, 3)
+    # {-1,+1} layers are ordinary signed layers (values travel as signed slices): one B word per term, no extra tables
+    assert hk.hikonv_packed_weights_bytes(bip, 256, 256, 3, 3) == 32 * 768 * 8 * 4
+    assert (bip.N, bip.K, bip.S, bip.M) == (4, 3, 10, 170) and hk.hikonv_plan_check(bip) == hk.OK
 
 
 def test_conv1d_and_misc_argument_checks():

@@ -96,12 +96,29 @@ def test_polyphase_stride_narrow_multiplier():
 
 
 def test_polyphase_rejections():
-    x, wt = _values("p3", 1, False, False, (1, 4, 8, 8), (8, 4, 3, 3))
-    plan = dnn_plan(1, 1, False, False, 2, 0, True, bipolar=True)      # {-1,+1}: one phase only
-    assert hk.hikonv_conv2d_workspace_bytes(plan, 1, 4, 8, 8, 8, 3, 3, 2, 1, False) == 0
     plan = dnn_plan(4, 4, True, True, 2, 0, True)
     assert hk.hikonv_conv2d_workspace_bytes(plan, 1, 4, 8, 8, 8, 3, 3, 1, 1, False) == 0   # taps fit no form at stride 1
     assert hk.hikonv_conv2d_workspace_bytes(plan, 1, 4, 8, 8, 8, 3, 3, 2, 1, False) > 0
+
+
+def test_bipolar_layers_in_both_widened_forms(kernel_choice):
+    # {-1,+1} values travel as signed slices (0 in the zero padding), so every layer form takes them
+    for shape in ((1, 6, 9, 17, 8, 3, 3, 2, 1), (2, 5, 8, 16, 9, 3, 5, 2, 2), (1, 40, 7, 15, 8, 3, 3, 3, 1)):
+        n, c, h, w, co, kh, kw, stride, pad = shape
+        x, wt = wl.bipolar_case(n, c, h, w, co, kh, kw, tag="p4")
+        ref = direct.conv2d(x, wt, stride, pad)
+        for taps in (kw, -(-kw // stride)):
+            plan = dnn_plan(1, 1, False, False, taps, 0, True, bipolar=True)
+            for fmt, pre in ((hk.FMT_INT8, False), (hk.FMT_BITDENSE, True)):
+                assert np.array_equal(run_conv2d(plan, x, wt, stride, pad, fmt, prepacked=pre), ref), (shape, taps, fmt, plan)
+    rng = wl.rng_for("p5")
+    x = (rng.integers(0, 2, (1, 5, 4, 6, 9)) * 2 - 1).astype(np.int8)
+    wt = (rng.integers(0, 2, (8, 5, 3, 3, 3)) * 2 - 1).astype(np.int8)
+    plan = dnn_plan(1, 1, False, False, 3, 0, True, bipolar=True)
+    for fmt, pre in ((hk.FMT_INT8, False), (hk.FMT_BITDENSE, True)):
+        # bit-dense {-1,+1} volumes: bit 1 stands for +1
+        got = run_conv3d(plan, x, wt, 1, 1, fmt, prepacked=pre)
+        assert np.array_equal(got, direct.conv3d(x, wt, 1, 1)), (fmt, plan)
 
 
 VOLUMES = [  # n, c, d, h, w, co, kd, kh, kw, stride, pad
