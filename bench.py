@@ -334,8 +334,9 @@ def microbench(hk):
         out["valu_T_lane_instr_per_s"][name] = blocks * 256 * iters * 64 / ((full - empty) * 1e-3) / 1e12
     big = torch.zeros(2 * 1024 ** 3 // 4, dtype=torch.int32, device="cuda")
     for name, kind in (("write", hk.UB_HBM_WRITE), ("write_nontemporal", hk.UB_HBM_WRITE_NT),
+                       ("write_nontemporal_runs_per_wave", hk.UB_HBM_WRITE_RUNS),
                        ("copy_read_plus_write", hk.UB_HBM_COPY), ("read", hk.UB_HBM_READ)):
-        best = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, nb, big), 5) for nb in (4096, 16384, 32768, 65536))
+        best = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, nb, big), 5) for nb in (4096, 16384, 32768, 65536, 89240))
         out["hbm_TB_per_s"][name] = big.numel() * 4 / (best * 1e-3) / 1e12
     return out
 

@@ -294,6 +294,7 @@ int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H, int W, int
 #define HIKONV_UB_HBM_COPY 17
 #define HIKONV_UB_HBM_READ 18
 #define HIKONV_UB_HBM_WRITE_NT 19 /* write with the non-temporal hint */
+#define HIKONV_UB_HBM_WRITE_RUNS 20 /* non-temporal, one contiguous 6016-byte run per wave (the 1-D kernel's store pattern) */
 int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream);
 
 /* Lane-exchange self check: out_dev[i] (64 ints) = value lane i receives from lane i-1 (lane 0: 0). */

@@ -120,6 +120,22 @@ __global__ __launch_bounds__(256) void k_ubench_write_nt(int4 *dst, int64_t n16)
         __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(dst) + i);
 }
 
+// The store pattern of the streaming 1-D kernel without its arithmetic: every wave owns one
+// contiguous run of 47 lines of 128 bytes and writes it with six line-aligned 1 KB stores.
+__global__ __launch_bounds__(256) void k_ubench_write_runs(int4 *dst, int64_t n16)
+{
+    typedef int32_t v4i __attribute__((ext_vector_type(4)));
+    constexpr int kRunQuads = 47 * 8;
+    const int lane = threadIdx.x & 63;
+    const int64_t run = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const v4i v = {(int)threadIdx.x, (int)blockIdx.x, 3, 4};
+    for (int64_t r = run; r * kRunQuads < n16; r += (int64_t)gridDim.x * 4) {
+        const int64_t q0 = r * kRunQuads;
+        for (int q = lane; q < kRunQuads && q0 + q < n16; q += 64)
+            __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(dst) + q0 + q);
+    }
+}
+
 __global__ __launch_bounds__(256) void k_ubench_copy(const int4 *src, int4 *dst, int64_t n16)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -195,6 +211,9 @@ hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t byte
         break;
     case HIKONV_UB_HBM_WRITE_NT:
         hipLaunchKernelGGL(k_ubench_write_nt, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));
+        break;
+    case HIKONV_UB_HBM_WRITE_RUNS:
+        hipLaunchKernelGGL(k_ubench_write_runs, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));
         break;
     case HIKONV_UB_HBM_COPY: {
         const int64_t half16 = (int64_t)(bytes / 32);
