@@ -69,7 +69,8 @@ typedef struct hikonv_plan_t {
     /* request */
     int32_t bits_a, bits_w;     /* p, q: bitwidths of f (activations) and g (weights), 1..8          */
     int32_t a_signed, w_signed; /* per operand                                                       */
-    int32_t bipolar;            /* 1: both operands are 1-bit {-1,+1}; packed as unsigned bits        */
+    int32_t bipolar;            /* 1: both operands are {-1,+1}, one bit each in storage (bit 1 = +1); */
+                                /* packed as signed slices, 0 in the zero padding                      */
     int32_t L_A, L_B;           /* multiplier input widths in bits                                   */
     int32_t L_acc;              /* width of the product/accumulator register (0 = L_A + L_B)         */
     int32_t mode;               /* HIKONV_MODE_*                                                     */
