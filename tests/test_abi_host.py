@@ -255,6 +255,44 @@ def test_conv2d_argument_checks():
     assert code(lambda: hk.hikonv_conv2d(p64, x, *args, w, 8, 3, 3, 1, 1, ws, y, stream=0)) == hk.EUNSUPPORTED
 
 
+def test_strided_and_3d_argument_checks():
+    plan3 = _dnn_plan()                                   # taps = 3
+    plan2 = _dnn_plan(taps=2)                             # ceil(3/2): the polyphase form of a 3-tap row at stride 2
+    x, w, y, ws = _Fake(0x1000), _Fake(0x2000), _Fake(0x3000), _Fake(0x100000)
+
+    def code(fn):
+        with pytest.raises(hk.HikonvError) as e:
+            fn()
+        return e.value.code
+
+    # which tap counts a strided layer accepts: Kw (every column computed) or ceil(Kw/stride) (polyphase)
+    assert hk.hikonv_conv2d_workspace_bytes(plan3, 1, 8, 10, 10, 8, 3, 3, 2, 1, True) > 0
+    assert hk.hikonv_conv2d_workspace_bytes(plan2, 1, 8, 10, 10, 8, 3, 3, 2, 1, True) > 0
+    assert hk.hikonv_conv2d_workspace_bytes(plan2, 1, 8, 10, 10, 8, 3, 3, 1, 1, True) == 0
+    assert hk.hikonv_conv2d_workspace_bytes(plan2, 1, 8, 10, 10, 8, 3, 5, 2, 1, True) == 0
+    assert code(lambda: hk.hikonv_conv2d(plan2, x, hk.FMT_INT8, 1, 8, 10, 10, w, 8, 3, 3, 3, 1, ws, y, stream=0)) == hk.EINVAL
+    # polyphase packs `stride` phases per channel: more packed channels, narrower rows, any padding
+    assert hk.hikonv_packed_weights_bytes_ex(plan2, 8, 8, 1, 3, 3, 2) == 2 * hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 1, 3, 3, 2)
+    assert hk.hikonv_packed_weights_bytes_ex(plan2, 8, 8, 1, 3, 3, 1) == 0
+    assert hk.hikonv_conv2d_workspace_bytes(plan2, 1, 8, 10, 10, 8, 3, 3, 2, 4, True) > 0       # pad > Kw-1 is fine here
+    assert hk.hikonv_conv2d_workspace_bytes(plan3, 1, 8, 10, 10, 8, 3, 3, 2, 4, True) == 0
+    # 3-D: workspace grows with the padded depth, kernel depth must fit, no pre-packed activations
+    ws1 = hk.hikonv_conv3d_workspace_bytes(plan3, 1, 8, 4, 10, 10, 8, 3, 3, 3, 1, 1, True)
+    ws2 = hk.hikonv_conv3d_workspace_bytes(plan3, 1, 8, 10, 10, 10, 8, 3, 3, 3, 1, 1, True)
+    assert 0 < ws1 < ws2
+    assert hk.hikonv_conv3d_workspace_bytes(plan3, 1, 8, 1, 10, 10, 8, 5, 3, 3, 1, 1, True) == 0   # depth 1 + 2 < 5
+    assert hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 3, 3, 3, 1) == 3 * hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 1, 3, 3, 1)
+    args3 = (1, 8, 4, 10, 10)
+    assert code(lambda: hk.hikonv_conv3d(plan3, x, hk.FMT_PACKED, *args3, w, False, 8, 3, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
+    assert code(lambda: hk.hikonv_conv3d(plan3, None, hk.FMT_INT8, *args3, w, False, 8, 3, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
+    assert code(lambda: hk.hikonv_conv3d(plan3, x, hk.FMT_INT8, *args3, w, False, 8, 3, 3, 3, 1, 1, _Fake(0x100000, 64), y, stream=0)) == hk.EWORKSPACE
+    assert code(lambda: hk.hikonv_conv3d(plan3, x, hk.FMT_INT8, 1, 8, 0, 10, 10, w, False, 8, 3, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
+    assert code(lambda: hk.hikonv_pack_weights_ex(plan3, w, 8, 8, 3, 3, 3, 1, _Fake(0x100010), stream=0)) == hk.EINVAL   # alignment
+    # the fused epilogue writes one column phase only
+    nxt = _dnn_plan(bits_a=4, bits_w=4, a_signed=0, w_signed=1, taps=2)
+    assert code(lambda: hk.hikonv_epilogue_pack(x, 1, 8, 10, 10, 3, 15, False, nxt, 8, 3, 3, 2, 1, ws, stream=0)) == hk.EUNSUPPORTED
+
+
 def test_workspace_and_packed_weight_sizes():
     plan = _dnn_plan()
     ws = hk.hikonv_conv2d_workspace_bytes(plan, 1, 64, 56, 56, 64, 3, 3, 1, 1, True)
