@@ -1,6 +1,7 @@
 // Kernels around the packed DNN-layer path: runtime packing of activation rows into A
 // words, offline packing of weights into B words, and the unpacked
 // one-product-per-multiply baseline.
+#include <cstdlib>
 #include <type_traits>
 #include "hikonv_conv2d_kernel.h"
 #include "hikonv_conv2d_sreg.h"
@@ -341,8 +342,9 @@ hipError_t launch_pack_weights(const PackWArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed, int co_tile, hipStream_t stream)
+hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_signed, int co_tile, hipStream_t stream)
 {
+    Conv2dArgs a = a_in;
     int64_t row_groups;
     if (a.segs == 0)
         row_groups = ceil_div(a.wave_rows, a.rows_per_wave);
@@ -350,8 +352,16 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed,
         row_groups = a.wave_rows * a.segs;
     const int64_t gx = ceil_div(row_groups, a.pipelined ? 4 / a.ksplit : 4);
     const int64_t gy = ceil_div(a.Co, co_tile);
-    if (gx <= 0 || gx > 0x7fffffffLL || gy <= 0 || gy > 65535) return hipErrorInvalidValue;
-    dim3 g((unsigned)gx, (unsigned)gy);
+    if (gx <= 0 || gy <= 0 || gx * gy > 0x3fffffffLL) return hipErrorInvalidValue;
+    // 1-D grid, tiles dealt to the XCDs in contiguous ranges (HIKONV_CONV2D_XCD=0: plain order)
+    static const int xcd_order = [] {
+        const char *e = getenv("HIKONV_CONV2D_XCD");
+        return e ? atoi(e) : 1;
+    }();
+    a.tiles_x = (int)gx;
+    a.tiles_y = (int)gy;
+    a.per_xcd = xcd_order && gx * gy >= 64 ? (int)ceil_div(gx * gy, 8) : 0;
+    dim3 g((unsigned)(a.per_xcd ? (int64_t)a.per_xcd * 8 : gx * gy));
     if (a.sreg) {
         if (!wide || co_tile != 8) return hipErrorInvalidValue;
         const int hi = a.Kp - 1;

@@ -42,6 +42,22 @@ struct acc_type<false> {
     typedef uint32_t type;
 };
 
+// Workgroup -> (row-group block bx, channel tile by).  Workgroups are handed to the eight
+// XCDs of the chip in turn (workgroup i runs on XCD i mod 8) and every XCD has its own L2, so
+// the tiles are numbered such that one XCD gets a contiguous range of them, channel tile
+// fastest: the workgroups that read the same activation rows run on the same XCD, close in
+// time, and an XCD's L2 sees only its share of the activations.  Returns false for the
+// workgroups that pad the grid to a multiple of 8.
+__device__ __forceinline__ bool tile_of_workgroup(const Conv2dArgs &p, int *bx, int *by)
+{
+    int64_t v = blockIdx.x;
+    if (p.per_xcd) v = (int64_t)(blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
+    if (v >= (int64_t)p.tiles_x * p.tiles_y) return false;
+    *bx = (int)(v / p.tiles_y);
+    *by = (int)(v - (int64_t)*bx * p.tiles_y);
+    return true;
+}
+
 // lane -> (output row, packed word index xi); block x = xi - 1
 struct LaneMap {
     int n, ho, xi;   // image, output row inside the image (depth slice * Ho2d + row), packed word index
@@ -164,9 +180,11 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
     const uint32_t *__restrict__ apk = p.apk;
     const uint32_t *__restrict__ wp = p.wp;
     const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int bx, by;
+    if (!tile_of_workgroup(p, &bx, &by)) return; // workgroup-uniform, no barrier in this kernel
+    const int64_t wave = (int64_t)bx * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const LaneMap m = map_lane(p, wave, lane);
-    const int co0 = blockIdx.y * CO_T;
+    const int co0 = by * CO_T;
     const uint32_t *a_base = apk + m.in_row * p.Xs + m.xi;
     const uint32_t *w_ptr = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
 
@@ -213,9 +231,11 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ks = wave % p.ksplit;                  // which slice of every term tile
-    const int64_t row_group = (int64_t)blockIdx.x * (4 / p.ksplit) + wave / p.ksplit;
+    int bx, by;
+    if (!tile_of_workgroup(p, &bx, &by)) return; // workgroup-uniform, before any barrier
+    const int64_t row_group = (int64_t)bx * (4 / p.ksplit) + wave / p.ksplit;
     const LaneMap m = map_lane(p, row_group, lane);
-    const int co0 = blockIdx.y * CO_T;
+    const int co0 = by * CO_T;
     // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
     const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 4);
     const uint32_t *w_tile = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);

@@ -165,13 +165,15 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ks = wave % p.ksplit; // which slice of the term range
-    const int64_t row_group = (int64_t)blockIdx.x * (4 / p.ksplit) + wave / p.ksplit;
+    int bx, by;
+    if (!tile_of_workgroup(p, &bx, &by)) return; // workgroup-uniform, before any barrier
+    const int64_t row_group = (int64_t)bx * (4 / p.ksplit) + wave / p.ksplit;
     const LaneMapS m = map_lane_sreg(p, row_group, lane);
-    const int co0 = blockIdx.y * CO_T;
+    const int co0 = by * CO_T;
     // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
     const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 4);
     // weight rows of this channel tile: 32 bytes per term
-    const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)(p.cog0 + blockIdx.y) * p.terms_pad * 32;
+    const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)(p.cog0 + by) * p.terms_pad * 32;
     const char *trow = reinterpret_cast<const char *>(p.toff); // 16 bytes per term group
     const char *abytes = reinterpret_cast<const char *>(p.apk);
 

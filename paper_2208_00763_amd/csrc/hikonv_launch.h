@@ -121,6 +121,8 @@ struct Conv2dArgs {
     int Co, cog0;            // output channels to write, first weight group
     int64_t chunk_stride;    // words between chunk planes of apk
     int rows_per_wave, segs; // lane mapping
+    int tiles_x, tiles_y;    // row-group blocks x channel tiles; the grid is 1-D (see tile_of_workgroup)
+    int per_xcd;             // ceil(tiles_x*tiles_y / 8), 0 = plain order
     int sreg;                // 1: k_conv2d_sreg (weights in scalar registers), 0: the LDS-staged kernels
     int Lr;                  // k_conv2d_sreg, segs == 0: lanes per row (blocks that hold input values)
     int64_t wave_rows;       // total rows = Nimg*Ho
