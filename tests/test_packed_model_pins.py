@@ -154,3 +154,73 @@ def test_overlap_add_with_kernel_longer_than_block():
             assert pm.conv1d_packed(f, g, n, k, s, False) == np.convolve(f, g).tolist()
         f, g = _rand(17, 3, True), _rand(k, 3, True)
         assert pm.conv1d_packed(f, g, n, k, s, True) == np.convolve(f, g).tolist()
+
+
+def test_bipolar_values_as_signed_slices():
+    # {-1,+1} data with zero padding are three-valued; as signed slices the products are -1, 0, 1,
+    # so a 10-bit slice holds 170 accumulated (channel, kernel-row) products of 3 taps (|sum| <= 510)
+    # and four such slices fill a signed 32-bit word.  One more product per segment does not fit.
+    s, n, k = 10, 4, 3
+    assert abs(pm.pack([-1] * n, s)) < 2 ** 31 and pm.pack([1] * n, s) < 2 ** 31
+    assert abs(pm.pack([-1] * (n + 1), s)) >= 2 ** 31           # a fifth slice overflows the signed word
+    rng = np.random.default_rng(11)
+    x = (rng.integers(0, 2, size=(1, 6, 5, 9)) * 2 - 1).astype(np.int8)
+    wt = (rng.integers(0, 2, size=(3, 6, 3, 3)) * 2 - 1).astype(np.int8)
+    ref = direct.conv2d(x, wt, 1, 1)[0]
+    assert np.array_equal(np.array(pm.conv2d_packed(x[0].tolist(), wt.tolist(), 1, n, k, s, 170, True)), ref)
+    # every segment at its bound: 170 x 3 products of (+1)(-1) or (-1)(-1)
+    for av, wv in itertools.product((-1, 1), (-1, 1)):
+        xe = np.full((1, 170, 1, 12), av, dtype=np.int8)
+        we = np.full((1, 170, 1, 3), wv, dtype=np.int8)
+        ref = direct.conv2d(xe, we, 1, 1)[0]
+        assert np.array_equal(np.array(pm.conv2d_packed(xe[0].tolist(), we.tolist(), 1, n, k, s, 170, True)), ref)
+    xe = np.full((1, 171, 1, 12), 1, dtype=np.int8)
+    we = np.full((1, 171, 1, 3), -1, dtype=np.int8)
+    bad = pm.conv2d_packed(xe[0].tolist(), we.tolist(), 1, n, k, s, 171, True)
+    assert not np.array_equal(np.array(bad), direct.conv2d(xe, we, 1, 1)[0])     # -513 leaves the 10-bit field
+
+
+@pytest.mark.parametrize("stride,kw,pad", [(2, 3, 1), (2, 5, 2), (3, 5, 1), (2, 7, 3), (4, 4, 0), (2, 3, 4)])
+def test_polyphase_identity_of_a_strided_layer(stride, kw, pad):
+    # O[w] = sum_p sum_j Ipad_p[w+j] W[j*s+p] with Ipad_p[i] = Ipad[s*i+p]: a stride-s row convolution is the
+    # sum over the s column phases of stride-1 convolutions with the phase kernels (zero beyond Kw); checked
+    # with the direct definitions only (columns of the layer), then through the packed model
+    rng = np.random.default_rng(stride * 100 + kw)
+    c, h, w, co, kh = 3, 6, 19, 2, 3
+    x = rng.integers(-8, 8, size=(1, c, h, w), dtype=np.int8)
+    wt = rng.integers(-8, 8, size=(co, c, kh, kw), dtype=np.int8)
+    ref = direct.conv2d(x, wt, stride, pad)
+    wo = ref.shape[3]
+    kp = -(-kw // stride)
+    # phase tensors: channel (ci, p) holds the padded row at s*i + p; kernel (ci, p) holds taps j*s + p
+    xp = np.zeros((1, c, h, w + 2 * pad + stride * kp), dtype=np.int8)
+    xp[:, :, :, pad:pad + w] = x
+    xph = np.zeros((1, c * stride, h, wo + kp - 1), dtype=np.int8)
+    wph = np.zeros((co, c * stride, kh, kp), dtype=np.int8)
+    for ci in range(c):
+        for p in range(stride):
+            xph[0, ci * stride + p] = xp[0, ci, :, p::stride][:, :wo + kp - 1]
+            taps = wt[:, ci, :, p::stride]
+            wph[:, ci * stride + p, :, :taps.shape[2]] = taps
+    # rows still step by `stride` and keep their vertical padding: take every stride-th row of a stride-1 layer
+    xv = np.zeros((1, c * stride, h + 2 * pad, wo + kp - 1), dtype=np.int8)
+    xv[:, :, pad:pad + h] = xph
+    got = direct.conv2d(xv, wph, 1, 0)[:, :, ::stride][:, :, :ref.shape[2]]
+    assert np.array_equal(got, ref)
+    packed = pm.conv2d_packed(xv[0].tolist(), wph.tolist(), 0, 3, min(kp, 3), 16, 4, True)
+    assert np.array_equal(np.array(packed)[:, ::stride][:, :ref.shape[2]], ref[0])
+
+
+def test_volume_layer_is_an_outer_sum_over_kernel_depth():
+    # every (channel, kernel depth slice) pair of a 3-D layer is a channel of a 2-D layer on the input's depth
+    # slice d + kd: the packed model run on those stacked channels equals the direct 3-D definition
+    rng = np.random.default_rng(21)
+    c, d, h, w, co, kd, kh, kw = 2, 4, 5, 8, 2, 3, 3, 3
+    x = rng.integers(-8, 8, size=(1, c, d, h, w), dtype=np.int8)
+    wt = rng.integers(-8, 8, size=(co, c, kd, kh, kw), dtype=np.int8)
+    ref = direct.conv3d(x, wt, 1, 0)
+    for dd in range(ref.shape[2]):
+        xs = np.concatenate([x[0, :, dd + k] for k in range(kd)], axis=0)             # [(kd, ci)][h][w]
+        ws = np.concatenate([wt[:, :, k] for k in range(kd)], axis=1)                 # [co][(kd, ci)][kh][kw]
+        got = pm.conv2d_packed(xs.tolist(), ws.tolist(), 0, 3, 3, 14, 6, True)
+        assert np.array_equal(np.array(got), ref[0, :, dd])
