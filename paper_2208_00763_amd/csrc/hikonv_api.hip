@@ -127,8 +127,8 @@ int conv_geom(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int 
     if ((int64_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     if ((int64_t)N * g->Do * g->Ho >= (1LL << 31) || (int64_t)g->Do * g->Ho >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     g->apk_bytes = round256((size_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs * 4);
-    g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
-    g->toff_bytes = round256((size_t)(g->terms_pad + kTermGroup) * 4);
+    g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4 + kTermGroup * 32); // one group of slack: read ahead, never used
+    g->toff_bytes = round256((size_t)(g->terms_pad + 5 * kTermGroup) * 4);
     return HIKONV_OK;
 }
 
@@ -191,7 +191,7 @@ PackActArgs pack_act_args(const hikonv_plan_t *plan, const Conv2dGeom &g, int N,
     pa.Xs = g.Xs;
     pa.apk = apk;
     pa.toff = toff;
-    pa.toff_entries = g.terms_pad + kTermGroup;
+    pa.toff_entries = g.terms_pad + 5 * kTermGroup; // zero beyond the terms: the kernels read up to four groups ahead
     pa.terms = g.terms;
     pa.Kh = Kh;
     pa.Kd = Kd;
@@ -287,11 +287,13 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
         const int real = (g.We + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
         const int lanes = ca.segs ? 64 : (real < g.X ? real : g.X);
         const int64_t groups_s = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, 64 / lanes);
-        // measured: it wins where the LDS-staged weight tile would be large (>= 1024 terms) and
-        // where splits are frequent (its split needs no lane exchange); otherwise the two are close
-        const bool many_terms = g.terms_pad >= 1024;
-        const bool frequent_splits = g.terms_pad >= 512 && split_terms <= 32;
-        ca.sreg = forced_kernel == 2 || ((many_terms || frequent_splits) && groups_s * ((Co + 7) / 8) >= 1024) ? 1 : 0;
+        // measured: with at least 1024 (row group, channel tile) pairs it wins where splits are
+        // frequent (its split needs no lane exchange), where the LDS-staged weight tile would
+        // be large (>= 1024 terms), and on very large layers (the LDS-staged kernel is bound by
+        // its broadcast reads of B); on small layers it is slower
+        const int64_t pairs = groups_s * ((Co + 7) / 8);
+        const bool pick = pairs >= 1024 && (split_terms <= 32 || g.terms_pad >= 1024 || pairs >= 4096);
+        ca.sreg = forced_kernel == 2 || pick ? 1 : 0;
     }
     ca.Lr = g.X;
     if (ca.sreg && ca.segs == 0) {
@@ -322,6 +324,7 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     };
 
     ca.toff = toff;
+    ca.apk_bytes = (uint32_t)((size_t)plan->chunks * N * g.Ce * g.Dp * g.Hp * g.Xs * 4);
     ca.Kp = plan->K;
     ca.Co = Co;
     ca.cog0 = 0;
@@ -494,7 +497,7 @@ int weights_geom(const hikonv_plan_t *plan, int Co, int C, int Kd, int Kh, int K
     g->terms = g->Ce * g->Khe * plan->chunks;
     g->terms_pad = pad_terms(g->terms);
     g->n_cog = (Co + 7) / 8;
-    g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4);
+    g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4 + kTermGroup * 32); // one group of slack: read ahead, never used
     return HIKONV_OK;
 }
 

@@ -24,14 +24,14 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     const int64_t total = (int64_t)p.chunks * p.Nimg * p.C * p.Dp * p.Hp * p.Xs;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     // the first threads also write the table of activation offsets of the terms
-    // t = ((c*Kd + kd)*Kh + kh)*chunks + chunk  ->  chunk*chunk_stride + ((c*Dp + kd)*Hp + kh)*Xs
+    // t = ((c*Kd + kd)*Kh + kh)*chunks + chunk  ->  byte offset 4*(chunk*chunk_stride + ((c*Dp + kd)*Hp + kh)*Xs)
     if (idx < p.toff_entries) {
         const int t = (int)idx;
         int32_t off = 0;
         if (t < p.terms) {
             const int ch = t % p.chunks, kh = (t / p.chunks) % p.Kh, kd = (t / (p.chunks * p.Kh)) % p.Kd;
             const int c = t / (p.chunks * p.Kh * p.Kd);
-            off = (int32_t)(ch * p.chunk_stride + (((int64_t)c * p.Dp + kd) * p.Hp + kh) * p.Xs);
+            off = (int32_t)(uint32_t)(4 * (ch * p.chunk_stride + (((int64_t)c * p.Dp + kd) * p.Hp + kh) * p.Xs)); // < 2^32
         }
         p.toff[t] = off;
     }
@@ -361,6 +361,7 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_sign
     a.tiles_x = (int)gx;
     a.tiles_y = (int)gy;
     a.per_xcd = xcd_order && gx * gy >= 64 ? (int)ceil_div(gx * gy, 8) : 0;
+    a.tile_order = xcd_order == 2 || (xcd_order == 3 && a.sreg) ? 1 : 0;
     dim3 g((unsigned)(a.per_xcd ? (int64_t)a.per_xcd * 8 : gx * gy));
     if (a.sreg) {
         if (!wide || co_tile != 8) return hipErrorInvalidValue;

@@ -53,8 +53,16 @@ __device__ __forceinline__ bool tile_of_workgroup(const Conv2dArgs &p, int *bx, 
     int64_t v = blockIdx.x;
     if (p.per_xcd) v = (int64_t)(blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
     if (v >= (int64_t)p.tiles_x * p.tiles_y) return false;
-    *bx = (int)(v / p.tiles_y);
-    *by = (int)(v - (int64_t)*bx * p.tiles_y);
+    if (p.tile_order == 1) { // row-group block fastest: neighbours in time share the weight rows
+        *by = (int)(v / p.tiles_x);
+        *bx = (int)(v - (int64_t)*by * p.tiles_x);
+    } else { // channel tile fastest: neighbours in time share the activation rows
+        *bx = (int)(v / p.tiles_y);
+        *by = (int)(v - (int64_t)*bx * p.tiles_y);
+    }
+    // the divisions run on the vector ALU; the results are workgroup uniform and are used as scalars
+    *bx = __builtin_amdgcn_readfirstlane(*bx);
+    *by = __builtin_amdgcn_readfirstlane(*by);
     return true;
 }
 
@@ -194,7 +202,8 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
     // terms in the order of the offset table: channel, kernel row (depth x height), chunk
     for (int t = 0; t < p.terms; t += p.chunks) {
         for (int ch = 0; ch < p.chunks; ++ch) {
-            const uint32_t a = a_base[p.toff[t + ch]];
+            const uint32_t a =
+                *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a_base) + (uint32_t)p.toff[t + ch]);
 #pragma unroll
             for (int c = 0; c < CO_T; ++c) st.mad(c, a, w_ptr[c]);
             w_ptr += 8;
@@ -292,7 +301,7 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 #pragma unroll
             for (int u = 0; u < U; ++u) // uniform base + 32-bit lane offset: one VALU add per load
                 a[u] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(apk) +
-                                                            (uint32_t)(lane_byte + ((uint32_t)s_off[t + u] << 2)));
+                                                            (uint32_t)(lane_byte + (uint32_t)s_off[t + u]));
         };
         auto multiply = [&](const uint32_t (&a)[U], int t) {
 #pragma unroll

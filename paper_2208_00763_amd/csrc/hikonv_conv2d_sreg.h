@@ -9,8 +9,9 @@
 // load per lane from the packed activation rows.  No LDS traffic in the term loop.
 //
 // Software pipeline over groups of U terms:
-//   scalar loads of B for group g+1 and of the activation offsets for group g+2,
-//   vector loads of A for group g+1,
+//   scalar loads of B for group g+1 and of the activation offsets for group g+4,
+//   buffer loads of A for group g+3 (they return in order, so three groups can be in flight;
+//   the address is resource + lane offset + a scalar term offset: no address arithmetic),
 //   multiply-accumulates of group g.
 // Scalar loads return out of order, so the only safe wait is "all of them"; it sits at the
 // top of a stage, before the next scalar loads are issued, and therefore never waits for
@@ -123,14 +124,19 @@ __device__ __forceinline__ void sload_x8(u32x8 &dst, const void *uniform_ptr)
 {
     asm volatile("s_load_dwordx8 %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
 }
+template <int BYTE_OFFSET>
 __device__ __forceinline__ void sload_x4(i32x4 &dst, const void *uniform_ptr)
 {
-    asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=&s"(dst) : "s"(uniform_ptr));
+    asm volatile("s_load_dwordx4 %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
 }
 __device__ __forceinline__ void wait_scalar_loads(u32x8 (&b)[4], i32x4 &o)
 {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(b[0]), "+s"(b[1]), "+s"(b[2]), "+s"(b[3]), "+s"(o));
 }
+
+// Keeps the multiply-accumulates of a stage behind the loads issued at its top: the (empty)
+// statement is ordered after those loads and the first accumulator passes through it.
+__device__ __forceinline__ void pin_before_multiply(uint64_t &acc0) { asm volatile("" : "+v"(acc0)); }
 
 // acc += a * b with b in a scalar register: v_mad_u64_u32 / v_mad_i64_i32 (Theorem 1's
 // multiply fused with the accumulation of products before a split)
@@ -175,7 +181,6 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     // weight rows of this channel tile: 32 bytes per term
     const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)(p.cog0 + by) * p.terms_pad * 32;
     const char *trow = reinterpret_cast<const char *>(p.toff); // 16 bytes per term group
-    const char *abytes = reinterpret_cast<const char *>(p.apk);
 
     const int S = p.S;
     const uint64_t bias = ANY_SIGNED ? field_bias<NF>(S) : 0;
@@ -215,26 +220,36 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     if (g_end > groups) g_end = groups;
 
     if (g_begin < g_end) { // wave-uniform; barriers are outside this part
-        const int g_last = groups - 1; // the weight rows end at terms_pad; the offset table has one more group
+        // Two pointers walk the weight rows (128 bytes per group) and the offset table (16 bytes
+        // per group); the groups of a stage are reached through immediate offsets, so a pair of
+        // stages costs two scalar pointer updates.  The loads run up to two groups past the
+        // wave's range: the weight buffer and the offset table are padded for that.
         u32x8 b0[U], b1[U];
         i32x4 o; // offsets of the next group; refilled right after the address adds that read it
-        uint32_t a0[U], a1[U];
-        auto issue_b = [&](u32x8 (&b)[U], int g) {
-            const char *src = wrow + (int64_t)(g < g_last ? g : g_last) * (U * 32);
-            sload_x8<0>(b[0], src);
-            sload_x8<32>(b[1], src);
-            sload_x8<64>(b[2], src);
-            sload_x8<96>(b[3], src);
-        };
-        auto issue_o = [&](i32x4 &o, int g) { sload_x4(o, trow + (int64_t)(g < groups ? g : groups) * 16); };
+        uint32_t a0[U], a1[U], a2[U], a3[U]; // activation words of four groups in flight
+        // Buffer loads: address = packed activations + lane offset (VGPR) + term offset (SGPR,
+        // straight from the table), so a load costs no VALU or SALU instruction.  They are
+        // written as instructions because three groups stay in flight across loop iterations
+        // and the wait for the oldest one is a count of younger loads (buffer loads return in
+        // order): a value loaded here is undefined until a wait_a that names it, and every
+        // buffer stays named until drain_a after the loop.
+        i32x4 arsrc; // buffer resource: base, no stride, size in bytes, raw 32-bit data
+        {
+            const uint64_t base = reinterpret_cast<uint64_t>(p.apk);
+            arsrc.x = (int32_t)(uint32_t)base;
+            arsrc.y = (int32_t)(uint32_t)((base >> 32) & 0xffffu);
+            arsrc.z = (int32_t)p.apk_bytes;
+            arsrc.w = 0x00020000;
+        }
         auto load_a = [&](uint32_t (&a)[U], const i32x4 &o) {
-            // uniform base + 32-bit lane offset: one VALU add per load.  The adds are pinned
-            // here, ahead of the scalar load that refills o.
-            uint32_t off[U] = {lane_byte + ((uint32_t)o.x << 2), lane_byte + ((uint32_t)o.y << 2),
-                               lane_byte + ((uint32_t)o.z << 2), lane_byte + ((uint32_t)o.w << 2)};
-            asm volatile("" : "+v"(off[0]), "+v"(off[1]), "+v"(off[2]), "+v"(off[3]));
-#pragma unroll
-            for (int u = 0; u < U; ++u) a[u] = *reinterpret_cast<const uint32_t *>(abytes + off[u]);
+            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[0]) : "v"(lane_byte), "s"(arsrc), "s"(o.x));
+            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[1]) : "v"(lane_byte), "s"(arsrc), "s"(o.y));
+            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[2]) : "v"(lane_byte), "s"(arsrc), "s"(o.z));
+            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[3]) : "v"(lane_byte), "s"(arsrc), "s"(o.w));
+        };
+        // the group loaded three stages ago has arrived once at most 12 younger loads are pending
+        auto wait_a = [&](uint32_t (&a)[U]) {
+            asm volatile("s_waitcnt vmcnt(12)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
         };
         auto multiply = [&](const uint32_t (&a)[U], const u32x8 (&b)[U]) {
 #pragma unroll
@@ -252,28 +267,52 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
             if (since >= p.split_terms) split(); // split_terms is a multiple of U
         };
 
-        // prologue: B and A of the first group, offsets of the second
-        issue_b(b0, g_begin);
-        issue_o(o, g_begin);
+        const char *bp = wrow + (int64_t)g_begin * (U * 32); // weights of the group the next stage multiplies
+        const char *tp = trow + (int64_t)g_begin * 16;       // its activation offsets
+        // prologue: B of the first group, A of the first three, offsets of the fourth
+        sload_x8<0>(b0[0], bp);
+        sload_x8<32>(b0[1], bp);
+        sload_x8<64>(b0[2], bp);
+        sload_x8<96>(b0[3], bp);
+        sload_x4<0>(o, tp);
         wait_scalar_loads(b0, o);
         load_a(a0, o);
-        issue_o(o, g_begin + 1);
+        sload_x4<16>(o, tp);
         wait_scalar_loads(b0, o);
-        for (int g = g_begin; g < g_end; g += 2) {
-            // group g from (a0, b0); o holds the offsets of g+1
-            issue_b(b1, g + 1);
-            load_a(a1, o);
-            issue_o(o, g + 2);
-            multiply(a0, b0);
-            wait_scalar_loads(b1, o);
-            if (g + 1 >= g_end) break;
-            // group g+1 from (a1, b1); o holds the offsets of g+2
-            issue_b(b0, g + 2);
-            load_a(a0, o);
-            issue_o(o, g + 3);
-            multiply(a1, b1);
-            wait_scalar_loads(b0, o);
+        load_a(a1, o);
+        sload_x4<32>(o, tp);
+        wait_scalar_loads(b0, o);
+        load_a(a2, o);
+        sload_x4<48>(o, tp);
+        wait_scalar_loads(b0, o);
+        int left = g_end - g_begin; // groups still to multiply
+        // One stage, k-th of four, for group g+k: B of g+k+1, A of g+k+3 (o holds its offsets),
+        // offsets of g+k+4, then the multiply-accumulates of g+k.
+#define HIKONV_SREG_STAGE(k, a_cur, a_new, b_cur, b_new)          \
+        sload_x8<(k + 1) * 128 + 0>(b_new[0], bp);                 \
+        sload_x8<(k + 1) * 128 + 32>(b_new[1], bp);                \
+        sload_x8<(k + 1) * 128 + 64>(b_new[2], bp);                \
+        sload_x8<(k + 1) * 128 + 96>(b_new[3], bp);                \
+        load_a(a_new, o);                                          \
+        sload_x4<(k + 4) * 16>(o, tp);                             \
+        wait_a(a_cur);                                             \
+        pin_before_multiply(acc[0]);                               \
+        multiply(a_cur, b_cur);                                    \
+        wait_scalar_loads(b_new, o);                               \
+        if (--left == 0) break;
+        while (true) {
+            HIKONV_SREG_STAGE(0, a0, a3, b0, b1)
+            HIKONV_SREG_STAGE(1, a1, a0, b1, b0)
+            HIKONV_SREG_STAGE(2, a2, a1, b0, b1)
+            HIKONV_SREG_STAGE(3, a3, a2, b1, b0)
+            bp += 4 * U * 32;
+            tp += 4 * 16;
         }
+#undef HIKONV_SREG_STAGE
+        // nothing may reuse the buffers' registers while loads into them are in flight
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(a0[0]), "+v"(a0[1]), "+v"(a0[2]), "+v"(a0[3]), "+v"(a1[0]), "+v"(a1[1]), "+v"(a1[2]), "+v"(a1[3]),
+                       "+v"(a2[0]), "+v"(a2[1]), "+v"(a2[2]), "+v"(a2[3]), "+v"(a3[0]), "+v"(a3[1]), "+v"(a3[2]), "+v"(a3[3]));
     }
     if (since) split();
 

@@ -81,7 +81,7 @@ struct PackActArgs {
     int N, Kp, S, chunks;    // plan
     int Hp, Xs;              // padded rows (H + 2 pad), words per packed row (1 zero word + blocks)
     uint32_t *apk;           // [chunks][Nimg][C][Hp][Xs]
-    int32_t *toff;           // [toff_entries] word offset of each term's activation row (0 beyond the terms)
+    int32_t *toff;           // [toff_entries] byte offset (unsigned) of each term's activation row (0 beyond the terms)
     int toff_entries, terms, Kh;
     int64_t chunk_stride;    // words between chunk planes of apk
 };
@@ -116,13 +116,15 @@ struct Conv2dArgs {
     int pipelined;           // 1: k_conv2d_pipe, 0: k_conv2d_packed
     int ksplit;              // waves of a workgroup sharing one row group (1, 2 or 4)
     int split_terms;         // terms between splits in the pipelined kernel (multiple of 4)
-    const int32_t *toff;     // [terms_pad + kTermGroup] activation word offset of every term
+    const int32_t *toff;     // [terms_pad + 5*kTermGroup] byte offset (unsigned) of every term's activation row, 0 beyond the terms
+    uint32_t apk_bytes;      // size of the packed activations (bounds of the buffer loads)
     int Kp;                  // taps per B word
     int Co, cog0;            // output channels to write, first weight group
     int64_t chunk_stride;    // words between chunk planes of apk
     int rows_per_wave, segs; // lane mapping
     int tiles_x, tiles_y;    // row-group blocks x channel tiles; the grid is 1-D (see tile_of_workgroup)
     int per_xcd;             // ceil(tiles_x*tiles_y / 8), 0 = plain order
+    int tile_order;          // 0: channel tile fastest, 1: row-group block fastest
     int sreg;                // 1: k_conv2d_sreg (weights in scalar registers), 0: the LDS-staged kernels
     int Lr;                  // k_conv2d_sreg, segs == 0: lanes per row (blocks that hold input values)
     int64_t wave_rows;       // total rows = Nimg*Ho

@@ -272,7 +272,9 @@ def test_strided_and_3d_argument_checks():
     assert hk.hikonv_conv2d_workspace_bytes(plan2, 1, 8, 10, 10, 8, 3, 5, 2, 1, True) == 0
     assert code(lambda: hk.hikonv_conv2d(plan2, x, hk.FMT_INT8, 1, 8, 10, 10, w, 8, 3, 3, 3, 1, ws, y, stream=0)) == hk.EINVAL
     # polyphase packs `stride` phases per channel: more packed channels, narrower rows, any padding
-    assert hk.hikonv_packed_weights_bytes_ex(plan2, 8, 8, 1, 3, 3, 2) == 2 * hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 1, 3, 3, 2)
+    # (one B word per term and channel, 8 channels per group, plus one group of read-ahead slack, rounded to 256)
+    assert hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 1, 3, 3, 2) == 8 * 3 * 32 + 256
+    assert hk.hikonv_packed_weights_bytes_ex(plan2, 8, 8, 1, 3, 3, 2) == 2 * 8 * 3 * 32 + 256
     assert hk.hikonv_packed_weights_bytes_ex(plan2, 8, 8, 1, 3, 3, 1) == 0
     assert hk.hikonv_conv2d_workspace_bytes(plan2, 1, 8, 10, 10, 8, 3, 3, 2, 4, True) > 0       # pad > Kw-1 is fine here
     assert hk.hikonv_conv2d_workspace_bytes(plan3, 1, 8, 10, 10, 8, 3, 3, 2, 4, True) == 0
@@ -281,7 +283,7 @@ def test_strided_and_3d_argument_checks():
     ws2 = hk.hikonv_conv3d_workspace_bytes(plan3, 1, 8, 10, 10, 10, 8, 3, 3, 3, 1, 1, True)
     assert 0 < ws1 < ws2
     assert hk.hikonv_conv3d_workspace_bytes(plan3, 1, 8, 1, 10, 10, 8, 5, 3, 3, 1, 1, True) == 0   # depth 1 + 2 < 5
-    assert hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 3, 3, 3, 1) == 3 * hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 1, 3, 3, 1)
+    assert hk.hikonv_packed_weights_bytes_ex(plan3, 8, 8, 3, 3, 3, 1) == 3 * 8 * 3 * 32 + 256
     args3 = (1, 8, 4, 10, 10)
     assert code(lambda: hk.hikonv_conv3d(plan3, x, hk.FMT_PACKED, *args3, w, False, 8, 3, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
     assert code(lambda: hk.hikonv_conv3d(plan3, None, hk.FMT_INT8, *args3, w, False, 8, 3, 3, 3, 1, 1, ws, y, stream=0)) == hk.EINVAL
@@ -304,7 +306,7 @@ def test_workspace_and_packed_weight_sizes():
     assert hk.hikonv_conv2d_workspace_bytes(plan, 1, 64, 56, 56, 64, 3, 5, 1, 1, True) == 0   # taps differ from the plan
     bip = hk.hikonv_plan_ex(bits_a=1, bits_w=1, bipolar=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3)
     # {-1,+1} layers are ordinary signed layers (values travel as signed slices): one B word per term, no extra tables
-    assert hk.hikonv_packed_weights_bytes(bip, 256, 256, 3, 3) == 32 * 768 * 8 * 4
+    assert hk.hikonv_packed_weights_bytes(bip, 256, 256, 3, 3) == 32 * 768 * 8 * 4 + 256
     assert (bip.N, bip.K, bip.S, bip.M) == (4, 3, 10, 170) and hk.hikonv_plan_check(bip) == hk.OK
 
 
