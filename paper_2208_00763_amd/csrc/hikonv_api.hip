@@ -60,6 +60,7 @@ int conv1d_common(int bits_a, int a_signed, int w_signed, const void *x_dev, int
 struct Conv2dGeom {
     int phases;          // column phases packed separately (= stride) or 1
     int Ce, We, Kwe;     // packed channels, values per packed row, taps per packed kernel row
+    int Cq;              // channel quads: the packed channels are stored four to a 16-byte cell (zero beyond Ce)
     int padwe;           // horizontal padding that only shifts the read index (0 when materialised)
     int stride_w;        // column decimation on store (1 when the phases are packed separately)
     int pad_d, Dp, Do;   // depth padding, padded depth, output depth (0, 1, 1 for a 2-D layer)
@@ -67,8 +68,6 @@ struct Conv2dGeom {
     int Ho, Wo, Wo1, X, Xs, Hp, terms, terms_pad, n_cog;
     size_t apk_bytes, toff_bytes, wp_bytes;
 };
-
-inline int pad_terms(int terms) { return (terms + kTermGroup - 1) / kTermGroup * kTermGroup; }
 
 // taps a plan must cover for a kernel row of Kw taps at column stride `stride`, polyphase form
 inline int polyphase_taps(int Kw, int stride) { return (Kw + stride - 1) / stride; }
@@ -120,15 +119,16 @@ int conv_geom(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int 
     g->X = (g->We + g->padwe + plan->N - 1) / plan->N;
     g->Xs = g->X + 1;
     g->Hp = H + 2 * pad;
-    if ((int64_t)g->Ce * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
-    g->terms = g->Ce * g->Khe * plan->chunks;
-    g->terms_pad = pad_terms(g->terms);
+    g->Cq = (g->Ce + 3) / 4;
+    if ((int64_t)g->Cq * 4 * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
+    g->terms = g->Cq * 4 * g->Khe * plan->chunks; // four channels of a quad per (kernel row, chunk): a multiple of the term group
+    g->terms_pad = g->terms;
     g->n_cog = (Co + 7) / 8;
-    if ((int64_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
+    if ((int64_t)plan->chunks * N * g->Cq * 4 * g->Dp * g->Hp * g->Xs >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
     if ((int64_t)N * g->Do * g->Ho >= (1LL << 31) || (int64_t)g->Do * g->Ho >= (1LL << 30)) return HIKONV_EUNSUPPORTED;
-    g->apk_bytes = round256((size_t)plan->chunks * N * g->Ce * g->Dp * g->Hp * g->Xs * 4);
+    g->apk_bytes = round256((size_t)plan->chunks * N * g->Cq * g->Dp * g->Hp * g->Xs * 16);
     g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4 + kTermGroup * 32); // one group of slack: read ahead, never used
-    g->toff_bytes = round256((size_t)(g->terms_pad + 5 * kTermGroup) * 4);
+    g->toff_bytes = round256((size_t)(g->terms / kTermGroup + 8) * 4); // one offset per term group, zeros beyond
     return HIKONV_OK;
 }
 
@@ -191,11 +191,12 @@ PackActArgs pack_act_args(const hikonv_plan_t *plan, const Conv2dGeom &g, int N,
     pa.Xs = g.Xs;
     pa.apk = apk;
     pa.toff = toff;
-    pa.toff_entries = g.terms_pad + 5 * kTermGroup; // zero beyond the terms: the kernels read up to four groups ahead
-    pa.terms = g.terms;
+    pa.toff_entries = g.terms / kTermGroup + 8; // zero beyond the groups: the kernels read up to four groups ahead
+    pa.groups = g.terms / kTermGroup;
+    pa.Cq = g.Cq;
     pa.Kh = Kh;
     pa.Kd = Kd;
-    pa.chunk_stride = (int64_t)N * g.Ce * g.Dp * g.Hp * g.Xs;
+    pa.chunk_stride = (int64_t)N * g.Cq * g.Dp * g.Hp * g.Xs;
     return pa;
 }
 
@@ -242,7 +243,7 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     ca.C = g.Ce;
     ca.Ho = g.Do * g.Ho;
     ca.Ho2d = g.Ho;
-    ca.img_rows = (int64_t)g.Ce * g.Dp * g.Hp;
+    ca.img_rows = (int64_t)g.Cq * g.Dp * g.Hp;
     ca.d_rows = (int64_t)stride * g.Hp;
     ca.stride_w = g.stride_w;
     ca.Wo1 = g.Wo1;
@@ -258,7 +259,7 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     ca.M = plan->M;
     ca.terms = g.terms;
     ca.terms_pad = g.terms_pad;
-    ca.chunk_stride = (int64_t)N * g.Ce * g.Dp * g.Hp * g.Xs;
+    ca.chunk_stride = (int64_t)N * g.Cq * g.Dp * g.Hp * g.Xs;
     if (g.Xs <= 64) {
         ca.rows_per_wave = 64 / g.Xs;
         ca.segs = 0;
@@ -271,9 +272,13 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     const bool wide = plan->L_A == 32;
     const bool any_signed = plan->bipolar || plan->a_signed || plan->w_signed; // {-1,+1}: signed slices
     // the pipelined kernels split after a whole number of term groups
-    const int split_terms = (plan->M * plan->chunks) / kTermGroup * kTermGroup;
+    // A term adds at most K products to a segment, and the terms between two splits may be any
+    // mix of chunks: M*taps/K terms keep a segment within the M*taps products the plan allows.
+    const int split_terms_any = (int)((int64_t)plan->M * g.Kwe / plan->K);
+    const int split_terms = split_terms_any / kTermGroup * kTermGroup;
     ca.pipelined = split_terms >= kTermGroup ? 1 : 0;
     ca.split_terms = split_terms;
+    ca.split_terms_any = split_terms_any > 0 ? split_terms_any : 1;
     // Kernel choice.  With the weights in scalar registers the term loop has no LDS traffic
     // and rows need no lane for their zero word; it needs enough (row group, channel tile)
     // pairs to fill the chip and is slower on small layers.
@@ -324,7 +329,7 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     };
 
     ca.toff = toff;
-    ca.apk_bytes = (uint32_t)((size_t)plan->chunks * N * g.Ce * g.Dp * g.Hp * g.Xs * 4);
+    ca.apk_bytes = (uint32_t)((size_t)plan->chunks * N * g.Cq * g.Dp * g.Hp * g.Xs * 16);
     ca.Kp = plan->K;
     ca.Co = Co;
     ca.cog0 = 0;
@@ -492,10 +497,11 @@ int weights_geom(const hikonv_plan_t *plan, int Co, int C, int Kd, int Kh, int K
     g->Kwe = polyphase ? polyphase_taps(Kw, stride) : Kw;
     if (plan->chunks != (g->Kwe + plan->K - 1) / plan->K) return HIKONV_EINVAL;
     g->Ce = C * g->phases;
+    g->Cq = (g->Ce + 3) / 4;
     g->Khe = Kd * Kh;
-    if ((int64_t)g->Ce * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
-    g->terms = g->Ce * g->Khe * plan->chunks;
-    g->terms_pad = pad_terms(g->terms);
+    if ((int64_t)g->Cq * 4 * g->Khe * plan->chunks >= (1 << 24)) return HIKONV_EUNSUPPORTED;
+    g->terms = g->Cq * 4 * g->Khe * plan->chunks;
+    g->terms_pad = g->terms;
     g->n_cog = (Co + 7) / 8;
     g->wp_bytes = round256((size_t)g->n_cog * g->terms_pad * 8 * 4 + kTermGroup * 32); // one group of slack: read ahead, never used
     return HIKONV_OK;

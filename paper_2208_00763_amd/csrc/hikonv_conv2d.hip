@@ -9,9 +9,10 @@
 namespace hikonv {
 namespace {
 
-// A[chunk][n][c][dp][hp][xi] = sum_j f[(xi-1)N + j - chunk*K] 2^(S j), f = row hp-pad of depth
+// A[chunk][n][c/4][dp][hp][xi][c%4] = sum_j f[(xi-1)N + j - chunk*K] 2^(S j), f = row hp-pad of depth
 // slice dp-pad_d of the image (zero outside it; Eq. I_PRIME / Eq. pad_f0).  Word xi = 0 of
-// every row is zero.  A 2-D layer has one depth slice (Dp = 1).
+// every row is zero.  A 2-D layer has one depth slice (Dp = 1).  The words of four channels sit side
+// by side in a 16-byte cell, so that a lane fetches the words of four terms with one load.
 // Ordinary layers: the packed channel c is the source channel and f[i] is its value i; the
 // leading horizontal padding is not materialised, it only shifts the index at which an
 // output is read (Eq. off).
@@ -21,29 +22,38 @@ namespace {
 // stride-1 row convolutions with the phase kernels.
 __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
 {
-    const int64_t total = (int64_t)p.chunks * p.Nimg * p.C * p.Dp * p.Hp * p.Xs;
+    const int64_t total = (int64_t)p.chunks * p.Nimg * p.Cq * p.Dp * p.Hp * p.Xs * 4;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    // the first threads also write the table of activation offsets of the terms
-    // t = ((c*Kd + kd)*Kh + kh)*chunks + chunk  ->  byte offset 4*(chunk*chunk_stride + ((c*Dp + kd)*Hp + kh)*Xs)
+    // the first threads also write the table of activation offsets of the term groups
+    // gi = ((cq*Kd + kd)*Kh + kh)*chunks + chunk  ->  byte offset 16*(chunk*chunk_stride + ((cq*Dp + kd)*Hp + kh)*Xs)
     if (idx < p.toff_entries) {
-        const int t = (int)idx;
+        const int gi = (int)idx;
         int32_t off = 0;
-        if (t < p.terms) {
-            const int ch = t % p.chunks, kh = (t / p.chunks) % p.Kh, kd = (t / (p.chunks * p.Kh)) % p.Kd;
-            const int c = t / (p.chunks * p.Kh * p.Kd);
-            off = (int32_t)(uint32_t)(4 * (ch * p.chunk_stride + (((int64_t)c * p.Dp + kd) * p.Hp + kh) * p.Xs)); // < 2^32
+        if (gi < p.groups) {
+            const int ch = gi % p.chunks, kh = (gi / p.chunks) % p.Kh, kd = (gi / (p.chunks * p.Kh)) % p.Kd;
+            const int cq = gi / (p.chunks * p.Kh * p.Kd);
+            off = (int32_t)(uint32_t)(16 * (ch * p.chunk_stride + (((int64_t)cq * p.Dp + kd) * p.Hp + kh) * p.Xs)); // < 2^32
         }
-        p.toff[t] = off;
+        p.toff[gi] = off;
     }
     if (idx >= total) return;
-    const int xi = (int)(idx % p.Xs);
-    int64_t t = idx / p.Xs;
+    const int u = (int)(idx & 3); // channel inside the quad
+    int64_t t = idx >> 2;
+    const int xi = (int)(t % p.Xs);
+    t /= p.Xs;
     const int hp = (int)(t % p.Hp);
     t /= p.Hp;
     const int dp = (int)(t % p.Dp);
     t /= p.Dp;
-    const int64_t nc = t % ((int64_t)p.Nimg * p.C);
-    const int ch = (int)(t / ((int64_t)p.Nimg * p.C));
+    const int64_t ncq = t % ((int64_t)p.Nimg * p.Cq);
+    const int ch = (int)(t / ((int64_t)p.Nimg * p.Cq));
+    const int64_t n_img = ncq / p.Cq;
+    const int c_packed = (int)(ncq - n_img * p.Cq) * 4 + u;
+    if (c_packed >= p.C) { // channels that only fill the last quad
+        p.apk[idx] = 0;
+        return;
+    }
+    const int64_t nc = n_img * p.C + c_packed;
     const int h = hp - p.pad, d = dp - p.pad_d;
     const bool inside = xi > 0 && h >= 0 && h < p.H && d >= 0 && d < p.D;
     uint32_t a = 0;
@@ -97,13 +107,13 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     p.apk[idx] = a;
 }
 
-// B[group][term][8], term = (c*Kh + kh)*chunks + chunk (Kh counts depth x height kernel rows),
+// B[group][term][8], term = ((c/4*Kh + kh)*chunks + chunk)*4 + c%4 (Kh counts depth x height kernel rows),
 // word = sum_k g[chunk*K + k] 2^(S k) with g = the reversed kernel row (Eq. I_PRIME) of the
 // packed channel c: the source row W[co][c][kh][Kw-1:0], or, for a polyphase layer, the
 // reversed phase kernel g_phase[j] = W[co][c / s][kh][j*s + phase] (zero beyond the row).
 __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
 {
-    const int terms = p.C * p.Kh * p.chunks;
+    const int terms = p.terms_pad;
     const int64_t total = (int64_t)p.n_cog * p.terms_pad * 8;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
@@ -114,9 +124,15 @@ __global__ __launch_bounds__(256) void k_pack_weights(PackWArgs p)
         p.wp[idx] = 0;
         return;
     }
-    const int ch = term % p.chunks;
-    const int kh = (term / p.chunks) % p.Kh;
-    const int c = term / (p.chunks * p.Kh);
+    // term = (((quad*Kh + kh)*chunks + chunk)*4 + channel of the quad)
+    const int gi = term >> 2;
+    const int ch = gi % p.chunks;
+    const int kh = (gi / p.chunks) % p.Kh;
+    const int c = (gi / (p.chunks * p.Kh)) * 4 + (term & 3);
+    if (c >= p.C) { // channels that only fill the last quad
+        p.wp[idx] = 0;
+        return;
+    }
     const int csrc = c / p.phases, phase = c - csrc * p.phases;
     const int co = cog * 8 + c8;
     uint32_t bw = 0;
@@ -325,7 +341,7 @@ inline hipError_t grid_1d(int64_t total, dim3 *g)
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
 {
     dim3 g;
-    int64_t threads = (int64_t)a.chunks * a.Nimg * a.C * a.Dp * a.Hp * a.Xs;
+    int64_t threads = (int64_t)a.chunks * a.Nimg * a.Cq * a.Dp * a.Hp * a.Xs * 4;
     if (threads < a.toff_entries) threads = a.toff_entries;
     hipError_t e = grid_1d(threads, &g);
     if (e != hipSuccess) return e;

@@ -193,26 +193,28 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
     const int64_t wave = (int64_t)bx * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const LaneMap m = map_lane(p, wave, lane);
     const int co0 = by * CO_T;
-    const uint32_t *a_base = apk + m.in_row * p.Xs + m.xi;
+    const char *a_base = reinterpret_cast<const char *>(apk) + (m.in_row * p.Xs + m.xi) * 16; // this lane's 16-byte cells
     const uint32_t *w_ptr = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
 
     SplitState<N, CO_T, ANY_SIGNED, WIDE> st;
     st.init(p.S);
     int since = 0, nsplit = 0;
-    // terms in the order of the offset table: channel, kernel row (depth x height), chunk
-    for (int t = 0; t < p.terms; t += p.chunks) {
-        for (int ch = 0; ch < p.chunks; ++ch) {
-            const uint32_t a =
-                *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a_base) + (uint32_t)p.toff[t + ch]);
+    // term groups in the order of the offset table: channel quad, kernel row (depth x height), chunk;
+    // one 16-byte load brings the activation words of the group's four channels
+    for (int gi = 0; gi < p.terms / 4; ++gi) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(a_base + (uint32_t)p.toff[gi]);
+        const uint32_t a4[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-            for (int c = 0; c < CO_T; ++c) st.mad(c, a, w_ptr[c]);
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int c = 0; c < CO_T; ++c) st.mad(c, a4[u], w_ptr[c]);
             w_ptr += 8;
-        }
-        if (++since == p.M) {
-            asm volatile("" ::: "memory"); // keep the split out of the multiply block (no speculation)
-            st.split();
-            since = 0;
-            ++nsplit;
+            if (++since == p.split_terms_any) {
+                asm volatile("" ::: "memory"); // keep the split out of the multiply block (no speculation)
+                st.split();
+                since = 0;
+                ++nsplit;
+            }
         }
     }
     if (since) {
@@ -229,9 +231,10 @@ template <int N, int CO_T, bool ANY_SIGNED, bool WIDE>
 __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 {
     constexpr int U = kTermGroup;
+    static_assert(U == 4, "a term group is the four channels of a quad");
     constexpr int CE = CO_T;
     // LDS: weight words of the current term tile [tile][CO_T], the activation offsets of its
-    // terms [tile + U]; reused at the end for the slice reduction
+    // term groups [tile / U + 1]; reused at the end for the slice reduction
     extern __shared__ __attribute__((aligned(16))) uint32_t s_mem[];
 
     const uint32_t *__restrict__ apk = p.apk;
@@ -245,13 +248,13 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
     const int64_t row_group = (int64_t)bx * (4 / p.ksplit) + wave / p.ksplit;
     const LaneMap m = map_lane(p, row_group, lane);
     const int co0 = by * CO_T;
-    // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
-    const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 4);
+    // byte offset of this lane's 16-byte cell inside a term group's activation row (< 2^32, host check)
+    const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 16);
     const uint32_t *w_tile = wp + ((int64_t)(p.cog0 + co0 / 8) * p.terms_pad) * 8 + (co0 & 7);
 
     const int tile_cap = p.terms_pad < kTermTile ? p.terms_pad : kTermTile;
     uint32_t *s_w = s_mem;                                   // [tile_cap][CO_T]
-    int32_t *s_off = reinterpret_cast<int32_t *>(s_w + tile_cap * CO_T); // [tile_cap + U]
+    int32_t *s_off = reinterpret_cast<int32_t *>(s_w + tile_cap * CO_T); // [tile_cap / U + 1], one per term group
 
     SplitState<N, CE, ANY_SIGNED, WIDE> st;
     st.init(p.S);
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
                 s_w[i] = w_tile[(int64_t)(tile0 + t) * 8 + c];
             }
         }
-        for (int t = tid; t < tile_n + U; t += 256) s_off[t] = p.toff[tile0 + t];
+        for (int t = tid; t < tile_n / U + 1; t += 256) s_off[t] = p.toff[tile0 / U + t];
         __syncthreads();
 
         // this wave's slice of the tile, in groups of U terms, two register buffers for the
@@ -298,10 +301,14 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
 
         uint32_t a0[U], a1[U];
         auto request = [&](uint32_t (&a)[U], int t) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) // uniform base + 32-bit lane offset: one VALU add per load
-                a[u] = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(apk) +
-                                                            (uint32_t)(lane_byte + (uint32_t)s_off[t + u]));
+            // the words of the group's four channels sit side by side: one 16-byte load
+            // (uniform base + 32-bit lane offset: one VALU add)
+            const uint4 q = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(apk) +
+                                                             (uint32_t)(lane_byte + (uint32_t)s_off[t / U]));
+            a[0] = q.x;
+            a[1] = q.y;
+            a[2] = q.z;
+            a[3] = q.w;
         };
         auto multiply = [&](const uint32_t (&a)[U], int t) {
 #pragma unroll
@@ -395,7 +402,7 @@ inline size_t conv2d_pipe_lds(const Conv2dArgs &a, int co_tile, int n)
 {
     const int ce = co_tile;
     const size_t tile_cap = a.terms_pad < kTermTile ? a.terms_pad : kTermTile;
-    const size_t stage = (tile_cap * co_tile + tile_cap + kTermGroup) * 4;
+    const size_t stage = (tile_cap * co_tile + tile_cap / kTermGroup + 4) * 4;
     const size_t reduce = a.ksplit > 1 ? (size_t)4 * ce * n * 64 * 4 : 0;
     return stage > reduce ? stage : reduce;
 }

@@ -5,12 +5,13 @@
 // One lane owns one packed block x of one output row and eight output channels.  The B
 // words of a term (ci, kh, chunk) are the same for every lane of a wave, so they are read
 // with scalar loads (32 bytes per term) and a packed multiply-accumulate is one
-// v_mad_u64_u32 / v_mad_i64_i32 with an SGPR operand; the A word of the term is one dword
-// load per lane from the packed activation rows.  No LDS traffic in the term loop.
+// v_mad_u64_u32 / v_mad_i64_i32 with an SGPR operand; the A words of four terms (the channels of
+// a quad) are one 16-byte load per lane from the packed activation rows.  No LDS traffic in
+// the term loop.
 //
 // Software pipeline over groups of U terms:
-//   scalar loads of B for group g+1 and of the activation offsets for group g+4,
-//   buffer loads of A for group g+3 (they return in order, so three groups can be in flight;
+//   scalar loads of B for group g+1 and of the activation offset for group g+4,
+//   one 16-byte buffer load of A (the four channels of a quad) for group g+3 (they return in order, so three groups can be in flight;
 //   the address is resource + lane offset + a scalar term offset: no address arithmetic),
 //   multiply-accumulates of group g.
 // Scalar loads return out of order, so the only safe wait is "all of them"; it sits at the
@@ -113,6 +114,7 @@ __device__ __forceinline__ void finish_channel(const Conv2dArgs &p, const LaneMa
 
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Scalar loads and the packed multiply-accumulate are written as instructions: the B words
 // must stay in SGPRs, the four products of a group must chain on the accumulator (no
@@ -125,11 +127,11 @@ __device__ __forceinline__ void sload_x8(u32x8 &dst, const void *uniform_ptr)
     asm volatile("s_load_dwordx8 %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
 }
 template <int BYTE_OFFSET>
-__device__ __forceinline__ void sload_x4(i32x4 &dst, const void *uniform_ptr)
+__device__ __forceinline__ void sload_x1(int32_t &dst, const void *uniform_ptr)
 {
-    asm volatile("s_load_dwordx4 %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
+    asm volatile("s_load_dword %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
 }
-__device__ __forceinline__ void wait_scalar_loads(u32x8 (&b)[4], i32x4 &o)
+__device__ __forceinline__ void wait_scalar_loads(u32x8 (&b)[4], int32_t &o)
 {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(b[0]), "+s"(b[1]), "+s"(b[2]), "+s"(b[3]), "+s"(o));
 }
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     constexpr int CO_T = 8;
     constexpr int CE = CO_T;
     constexpr int NF = N + HI;
-    static_assert(U == 4, "offset table is read four terms at a time");
+    static_assert(U == 4, "a term group is the four channels of a quad");
     extern __shared__ __attribute__((aligned(16))) int32_t s_red[]; // [4 waves][4*NF][64]
 
     const int tid = threadIdx.x;
@@ -176,11 +178,11 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     const int64_t row_group = (int64_t)bx * (4 / p.ksplit) + wave / p.ksplit;
     const LaneMapS m = map_lane_sreg(p, row_group, lane);
     const int co0 = by * CO_T;
-    // byte offset of this lane's word inside a term's activation row (< 2^32, host check)
-    const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 4);
+    // byte offset of this lane's 16-byte cell inside a group's activation row (< 2^32, host check)
+    const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 16);
     // weight rows of this channel tile: 32 bytes per term
     const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)(p.cog0 + by) * p.terms_pad * 32;
-    const char *trow = reinterpret_cast<const char *>(p.toff); // 16 bytes per term group
+    const char *trow = reinterpret_cast<const char *>(p.toff); // 4 bytes per term group
 
     const int S = p.S;
     const uint64_t bias = ANY_SIGNED ? field_bias<NF>(S) : 0;
@@ -225,14 +227,15 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
         // stages costs two scalar pointer updates.  The loads run up to two groups past the
         // wave's range: the weight buffer and the offset table are padded for that.
         u32x8 b0[U], b1[U];
-        i32x4 o; // offsets of the next group; refilled right after the address adds that read it
-        uint32_t a0[U], a1[U], a2[U], a3[U]; // activation words of four groups in flight
-        // Buffer loads: address = packed activations + lane offset (VGPR) + term offset (SGPR,
-        // straight from the table), so a load costs no VALU or SALU instruction.  They are
-        // written as instructions because three groups stay in flight across loop iterations
-        // and the wait for the oldest one is a count of younger loads (buffer loads return in
-        // order): a value loaded here is undefined until a wait_a that names it, and every
-        // buffer stays named until drain_a after the loop.
+        int32_t o; // byte offset of the next group's activation cells; refilled right after the load that reads it
+        u32x4 a0, a1, a2, a3; // activation words of four groups in flight (one channel quad each)
+        // Buffer loads: address = packed activations + lane offset (VGPR) + group offset (SGPR,
+        // straight from the table), so the 16-byte load that brings the four words of a group
+        // costs no VALU or SALU instruction.  They are written as instructions because three
+        // groups stay in flight across loop iterations and the wait for the oldest one is a
+        // count of younger loads (buffer loads return in order): a value loaded here is
+        // undefined until a wait_a that names it, and every buffer stays named until the drain
+        // after the loop.
         i32x4 arsrc; // buffer resource: base, no stride, size in bytes, raw 32-bit data
         {
             const uint64_t base = reinterpret_cast<uint64_t>(p.apk);
@@ -241,17 +244,13 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
             arsrc.z = (int32_t)p.apk_bytes;
             arsrc.w = 0x00020000;
         }
-        auto load_a = [&](uint32_t (&a)[U], const i32x4 &o) {
-            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[0]) : "v"(lane_byte), "s"(arsrc), "s"(o.x));
-            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[1]) : "v"(lane_byte), "s"(arsrc), "s"(o.y));
-            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[2]) : "v"(lane_byte), "s"(arsrc), "s"(o.z));
-            asm volatile("buffer_load_dword %0, %1, %2, %3 offen" : "=v"(a[3]) : "v"(lane_byte), "s"(arsrc), "s"(o.w));
+        auto load_a = [&](u32x4 &a, const int32_t &o) {
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(a) : "v"(lane_byte), "s"(arsrc), "s"(o));
         };
-        // the group loaded three stages ago has arrived once at most 12 younger loads are pending
-        auto wait_a = [&](uint32_t (&a)[U]) {
-            asm volatile("s_waitcnt vmcnt(12)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
-        };
-        auto multiply = [&](const uint32_t (&a)[U], const u32x8 (&b)[U]) {
+        // the group loaded three stages ago has arrived once at most 3 younger loads are pending
+        auto wait_a = [&](u32x4 &a) { asm volatile("s_waitcnt vmcnt(3)" : "+v"(a)); };
+        auto multiply = [&](const u32x4 &a4, const u32x8 (&b)[U]) {
+            const uint32_t a[U] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 mad_sreg<ANY_SIGNED>(acc[0], a[u], b[u].s0);
@@ -268,22 +267,22 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
         };
 
         const char *bp = wrow + (int64_t)g_begin * (U * 32); // weights of the group the next stage multiplies
-        const char *tp = trow + (int64_t)g_begin * 16;       // its activation offsets
+        const char *tp = trow + (int64_t)g_begin * 4;        // its activation offset
         // prologue: B of the first group, A of the first three, offsets of the fourth
         sload_x8<0>(b0[0], bp);
         sload_x8<32>(b0[1], bp);
         sload_x8<64>(b0[2], bp);
         sload_x8<96>(b0[3], bp);
-        sload_x4<0>(o, tp);
+        sload_x1<0>(o, tp);
         wait_scalar_loads(b0, o);
         load_a(a0, o);
-        sload_x4<16>(o, tp);
+        sload_x1<4>(o, tp);
         wait_scalar_loads(b0, o);
         load_a(a1, o);
-        sload_x4<32>(o, tp);
+        sload_x1<8>(o, tp);
         wait_scalar_loads(b0, o);
         load_a(a2, o);
-        sload_x4<48>(o, tp);
+        sload_x1<12>(o, tp);
         wait_scalar_loads(b0, o);
         int left = g_end - g_begin; // groups still to multiply
         // One stage, k-th of four, for group g+k: B of g+k+1, A of g+k+3 (o holds its offsets),
@@ -294,7 +293,7 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
         sload_x8<(k + 1) * 128 + 64>(b_new[2], bp);                \
         sload_x8<(k + 1) * 128 + 96>(b_new[3], bp);                \
         load_a(a_new, o);                                          \
-        sload_x4<(k + 4) * 16>(o, tp);                             \
+        sload_x1<(k + 4) * 4>(o, tp);                              \
         wait_a(a_cur);                                             \
         pin_before_multiply(acc[0]);                               \
         multiply(a_cur, b_cur);                                    \
@@ -306,13 +305,11 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
             HIKONV_SREG_STAGE(2, a2, a1, b0, b1)
             HIKONV_SREG_STAGE(3, a3, a2, b1, b0)
             bp += 4 * U * 32;
-            tp += 4 * 16;
+            tp += 4 * 4;
         }
 #undef HIKONV_SREG_STAGE
         // nothing may reuse the buffers' registers while loads into them are in flight
-        asm volatile("s_waitcnt vmcnt(0)"
-                     : "+v"(a0[0]), "+v"(a0[1]), "+v"(a0[2]), "+v"(a0[3]), "+v"(a1[0]), "+v"(a1[1]), "+v"(a1[2]), "+v"(a1[3]),
-                       "+v"(a2[0]), "+v"(a2[1]), "+v"(a2[2]), "+v"(a2[3]), "+v"(a3[0]), "+v"(a3[1]), "+v"(a3[2]), "+v"(a3[3]));
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3));
     }
     if (since) split();
 

@@ -80,10 +80,11 @@ struct PackActArgs {
     int Nimg, C, H, W, pad;
     int N, Kp, S, chunks;    // plan
     int Hp, Xs;              // padded rows (H + 2 pad), words per packed row (1 zero word + blocks)
-    uint32_t *apk;           // [chunks][Nimg][C][Hp][Xs]
-    int32_t *toff;           // [toff_entries] byte offset (unsigned) of each term's activation row (0 beyond the terms)
-    int toff_entries, terms, Kh;
-    int64_t chunk_stride;    // words between chunk planes of apk
+    uint32_t *apk;           // [chunks][Nimg][Cq][Dp][Hp][Xs][4]: the words of four channels side by side
+    int32_t *toff;           // [toff_entries] byte offset (unsigned) of each term group's activation cells (0 beyond the groups)
+    int toff_entries, groups, Kh; // table entries, term groups (4 channels of a quad x one kernel row and chunk)
+    int Cq;                  // channel quads: ceil(C / 4)
+    int64_t chunk_stride;    // 16-byte cells between chunk planes of apk
 };
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream);
 
@@ -111,16 +112,17 @@ struct Conv2dArgs {
                              // output w sits at row-convolution index w + off
     int Hp, Xs, X;           // packed rows per image-channel, words per row, blocks per row
     int N, S, chunks, M;     // plan; M = products accumulated per split
-    int terms;               // C*Kh*chunks
-    int terms_pad;           // terms rounded up to a multiple of 4 (weights are zero beyond terms)
+    int terms;               // 4*ceil(C/4)*Kh*chunks, in the order (quad, kernel row, chunk, channel of the quad)
+    int terms_pad;           // = terms (a multiple of 4: channels come in quads, zero weights beyond the real channels)
     int pipelined;           // 1: k_conv2d_pipe, 0: k_conv2d_packed
     int ksplit;              // waves of a workgroup sharing one row group (1, 2 or 4)
-    int split_terms;         // terms between splits in the pipelined kernel (multiple of 4)
-    const int32_t *toff;     // [terms_pad + 5*kTermGroup] byte offset (unsigned) of every term's activation row, 0 beyond the terms
+    int split_terms;         // terms between splits in the pipelined kernels (multiple of 4)
+    int split_terms_any;     // terms between splits in the plain kernel
+    const int32_t *toff;     // [terms/4 + 8] byte offset (unsigned) of every term group's 16-byte activation cells, 0 beyond
     uint32_t apk_bytes;      // size of the packed activations (bounds of the buffer loads)
     int Kp;                  // taps per B word
     int Co, cog0;            // output channels to write, first weight group
-    int64_t chunk_stride;    // words between chunk planes of apk
+    int64_t chunk_stride;    // 16-byte cells between chunk planes of apk
     int rows_per_wave, segs; // lane mapping
     int tiles_x, tiles_y;    // row-group blocks x channel tiles; the grid is 1-D (see tile_of_workgroup)
     int per_xcd;             // ceil(tiles_x*tiles_y / 8), 0 = plain order
