@@ -292,12 +292,11 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
         const int real = (g.We + (plan->chunks - 1) * plan->K + plan->N - 1) / plan->N;
         const int lanes = ca.segs ? 64 : (real < g.X ? real : g.X);
         const int64_t groups_s = ca.segs ? ca.wave_rows * ca.segs : ceil_div(ca.wave_rows, 64 / lanes);
-        // measured: with at least 1024 (row group, channel tile) pairs it wins where splits are
-        // frequent (its split needs no lane exchange), where the LDS-staged weight tile would
-        // be large (>= 1024 terms), and on very large layers (the LDS-staged kernel is bound by
-        // its broadcast reads of B); on small layers it is slower
+        // measured: from about 768 (row group, channel tile) pairs on it wins (the LDS-staged
+        // kernel is bound by its broadcast reads of B and its split needs a lane exchange); on
+        // smaller layers, with few waves per SIMD to cover the scalar-load latency, it is slower
         const int64_t pairs = groups_s * ((Co + 7) / 8);
-        const bool pick = pairs >= 1024 && (split_terms <= 32 || g.terms_pad >= 1024 || pairs >= 4096);
+        const bool pick = pairs >= 768;
         ca.sreg = forced_kernel == 2 || pick ? 1 : 0;
     }
     ca.Lr = g.X;

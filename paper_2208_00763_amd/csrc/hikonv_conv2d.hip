@@ -369,6 +369,8 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_sign
     const int64_t gx = ceil_div(row_groups, a.pipelined ? 4 / a.ksplit : 4);
     const int64_t gy = ceil_div(a.Co, co_tile);
     if (gx <= 0 || gy <= 0 || gx * gy > 0x3fffffffLL) return hipErrorInvalidValue;
+    // the kernels index rows and row groups with 32-bit arithmetic (row group * rows per wave + 63 < 2^31)
+    if (a.wave_rows >= 0x3fffffffLL || row_groups >= 0x3fffffffLL) return hipErrorInvalidValue;
     // 1-D grid, tiles dealt to the XCDs in contiguous ranges (HIKONV_CONV2D_XCD=0: plain order)
     static const int xcd_order = [] {
         const char *e = getenv("HIKONV_CONV2D_XCD");

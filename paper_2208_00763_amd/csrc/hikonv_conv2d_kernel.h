@@ -50,19 +50,21 @@ struct acc_type<false> {
 // workgroups that pad the grid to a multiple of 8.
 __device__ __forceinline__ bool tile_of_workgroup(const Conv2dArgs &p, int *bx, int *by)
 {
-    int64_t v = blockIdx.x;
-    if (p.per_xcd) v = (int64_t)(blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
-    if (v >= (int64_t)p.tiles_x * p.tiles_y) return false;
+    // every quantity here is below 2^31 (the launcher checks the grid), so the divisions are 32-bit
+    uint32_t v = blockIdx.x;
+    if (p.per_xcd) v = (blockIdx.x & 7u) * (uint32_t)p.per_xcd + (blockIdx.x >> 3);
+    if (v >= (uint32_t)p.tiles_x * (uint32_t)p.tiles_y) return false;
+    uint32_t x, y;
     if (p.tile_order == 1) { // row-group block fastest: neighbours in time share the weight rows
-        *by = (int)(v / p.tiles_x);
-        *bx = (int)(v - (int64_t)*by * p.tiles_x);
+        y = v / (uint32_t)p.tiles_x;
+        x = v - y * (uint32_t)p.tiles_x;
     } else { // channel tile fastest: neighbours in time share the activation rows
-        *bx = (int)(v / p.tiles_y);
-        *by = (int)(v - (int64_t)*bx * p.tiles_y);
+        x = v / (uint32_t)p.tiles_y;
+        y = v - x * (uint32_t)p.tiles_y;
     }
     // the divisions run on the vector ALU; the results are workgroup uniform and are used as scalars
-    *bx = __builtin_amdgcn_readfirstlane(*bx);
-    *by = __builtin_amdgcn_readfirstlane(*by);
+    *bx = __builtin_amdgcn_readfirstlane((int)x);
+    *by = __builtin_amdgcn_readfirstlane((int)y);
     return true;
 }
 
@@ -73,31 +75,33 @@ struct LaneMap {
     bool active, halo;
 };
 
-__device__ __forceinline__ LaneMap map_lane(const Conv2dArgs &p, int64_t row_group, int lane)
+__device__ __forceinline__ LaneMap map_lane(const Conv2dArgs &p, int64_t row_group_in, int lane)
 {
+    // row groups and rows are below 2^31 (the launcher checks both): 32-bit divisions
+    const uint32_t row_group = (uint32_t)row_group_in;
     LaneMap m;
-    int64_t row;
+    uint32_t row;
     if (p.segs == 0) { // several whole rows per wave
-        const int rw = lane / p.Xs;
+        const int rw = (int)((uint32_t)lane / (uint32_t)p.Xs);
         m.xi = lane - rw * p.Xs;
-        row = row_group * p.rows_per_wave + rw;
-        m.active = rw < p.rows_per_wave && row < p.wave_rows;
+        row = row_group * (uint32_t)p.rows_per_wave + (uint32_t)rw;
+        m.active = rw < p.rows_per_wave && row < (uint32_t)p.wave_rows;
         m.halo = m.xi == 0;
     } else { // one 63-block segment of a long row per wave
-        row = row_group / p.segs;
-        const int seg = (int)(row_group - row * p.segs);
+        row = row_group / (uint32_t)p.segs;
+        const int seg = (int)(row_group - row * (uint32_t)p.segs);
         m.xi = seg * 63 + lane;
-        m.active = row < p.wave_rows && m.xi < p.Xs;
+        m.active = row < (uint32_t)p.wave_rows && m.xi < p.Xs;
         m.halo = lane == 0;
     }
     if (!m.active) {
         row = 0;
         m.xi = 0;
     }
-    m.n = (int)(row / p.Ho);
-    m.ho = (int)(row - (int64_t)m.n * p.Ho);
+    m.n = (int)(row / (uint32_t)p.Ho);
+    m.ho = (int)(row - (uint32_t)m.n * (uint32_t)p.Ho);
     // first packed input row of this output row: image, output depth, output row inside the depth slice
-    const int d = m.ho / p.Ho2d;
+    const int d = (int)((uint32_t)m.ho / (uint32_t)p.Ho2d);
     m.in_row = (int64_t)m.n * p.img_rows + (int64_t)d * p.d_rows + (int64_t)(m.ho - d * p.Ho2d) * p.stride;
     return m;
 }

@@ -50,24 +50,26 @@ struct LaneMapS {
     bool store_hi; // lane also writes its high segments (no lane owns the following block)
 };
 
-__device__ __forceinline__ LaneMapS map_lane_sreg(const Conv2dArgs &p, int64_t row_group, int lane)
+__device__ __forceinline__ LaneMapS map_lane_sreg(const Conv2dArgs &p, int64_t row_group_in, int lane)
 {
+    // row groups and rows are below 2^31 (the launcher checks both): 32-bit divisions
+    const uint32_t row_group = (uint32_t)row_group_in;
     LaneMapS m;
-    int64_t row;
+    uint32_t row;
     if (p.segs == 0) {
-        const int rw = lane / p.Lr;
+        const int rw = (int)((uint32_t)lane / (uint32_t)p.Lr);
         const int l = lane - rw * p.Lr;
         m.xi = l + 1;
-        row = row_group * p.rows_per_wave + rw;
-        m.active = rw < p.rows_per_wave && row < p.wave_rows;
+        row = row_group * (uint32_t)p.rows_per_wave + (uint32_t)rw;
+        m.active = rw < p.rows_per_wave && row < (uint32_t)p.wave_rows;
         m.recv = l != 0;
         m.store = m.active;
         m.store_hi = m.active && l == p.Lr - 1;
     } else {
-        row = row_group / p.segs;
-        const int seg = (int)(row_group - row * p.segs);
+        row = row_group / (uint32_t)p.segs;
+        const int seg = (int)(row_group - row * (uint32_t)p.segs);
         m.xi = seg * 63 + lane;
-        m.active = row < p.wave_rows && m.xi < p.Xs;
+        m.active = row < (uint32_t)p.wave_rows && m.xi < p.Xs;
         m.recv = lane != 0;
         m.store = m.active && lane != 0;
         m.store_hi = false;
@@ -76,10 +78,10 @@ __device__ __forceinline__ LaneMapS map_lane_sreg(const Conv2dArgs &p, int64_t r
         row = 0;
         m.xi = 0;
     }
-    m.n = (int)(row / p.Ho);
-    m.ho = (int)(row - (int64_t)m.n * p.Ho);
+    m.n = (int)(row / (uint32_t)p.Ho);
+    m.ho = (int)(row - (uint32_t)m.n * (uint32_t)p.Ho);
     // first packed input row of this output row: image, output depth, output row inside the depth slice
-    const int d = m.ho / p.Ho2d;
+    const int d = (int)((uint32_t)m.ho / (uint32_t)p.Ho2d);
     m.in_row = (int64_t)m.n * p.img_rows + (int64_t)d * p.d_rows + (int64_t)(m.ho - d * p.Ho2d) * p.stride;
     return m;
 }
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     if (g_end > groups) g_end = groups;
 
     if (g_begin < g_end) { // wave-uniform; barriers are outside this part
-        // Two pointers walk the weight rows (128 bytes per group) and the offset table (16 bytes
+        // Two pointers walk the weight rows (128 bytes per group) and the offset table (4 bytes
         // per group); the groups of a stage are reached through immediate offsets, so a pair of
         // stages costs two scalar pointer updates.  The loads run up to two groups past the
         // wave's range: the weight buffer and the offset table are padded for that.
