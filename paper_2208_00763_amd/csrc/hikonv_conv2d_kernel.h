@@ -163,24 +163,151 @@ struct SplitState {
     }
 };
 
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+// Output stores of a wave: raw buffer stores whose per-lane byte offset is either the
+// output's offset inside the wave's window of y or, for a lane or field that has no output
+// there (halo block, column outside the row, column dropped by the stride), an offset beyond
+// the buffer's size -- the hardware drops out-of-range buffer stores.  The offsets are
+// computed once per wave and serve every channel: the window of channel c starts c channel
+// planes further on.  The N own fields of a lane are consecutive output columns (unit
+// column stride), so a lane that stores all fields of a group of up to four does it with one
+// 8/12/16-byte store (dword aligned: global memory takes that); lanes at the ends of a row,
+// the high fields and strided layers use one store per field.  The window starts at the
+// output row of the wave's first lane; the launcher sets fast_store only when every lane's
+// offset from there is below 2^31 bytes.
+constexpr uint32_t kNoStore = 0x80000000u; // = size given to the buffer: never in range
+typedef int32_t i32x2 __attribute__((ext_vector_type(2)));
+typedef int32_t i32x3 __attribute__((ext_vector_type(3)));
+
+template <int N, int HI>
+struct OutputStores {
+    static constexpr int NF = N + HI;
+    static constexpr int NV = (N + 3) / 4; // groups of up to four own fields
+    uint32_t vgroup[NV]; // offset of the group's first field where the lane stores the whole group, else kNoStore
+    uint32_t vone[NF];   // offset of field j where the lane stores it by itself, else kNoStore
+    bool singles;        // the lane has such a field
+    uint64_t base;       // wave-uniform: address of (first lane's image, channel co0, first lane's row)
+    int64_t chan_bytes;  // wave-uniform: bytes between channel planes
+
+    // n, ho, x: the lane's image, output row and block; flag[j]: the lane writes field j at
+    // all; fields are consecutive stride-1 columns starting at x*N - off
+    __device__ __forceinline__ void init(const Conv2dArgs &p, int n, int ho, int x, int co0, const bool (&flag)[NF])
+    {
+        const int n0 = __builtin_amdgcn_readfirstlane(n), ho0 = __builtin_amdgcn_readfirstlane(ho);
+        chan_bytes = (int64_t)p.Ho * p.Wo * 4;
+        base = reinterpret_cast<uint64_t>(p.y) + (uint64_t)((((int64_t)n0 * p.Co + co0) * p.Ho + ho0) * p.Wo * 4);
+        // rows between the lane's output row and the window's first row (lanes are in row order)
+        const uint32_t drow = (uint32_t)(n - n0) * (uint32_t)p.Co * (uint32_t)p.Ho + (uint32_t)(ho - ho0); // wraps only on lanes that store nothing
+        const uint32_t row_byte = drow * (uint32_t)p.Wo * 4u;
+        bool ok[NF];
+        uint32_t off[NF];
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            const int w1 = x * p.N + j - p.off; // stride-1 output column
+            ok[j] = flag[j] && w1 >= 0 && w1 < p.Wo1;
+            uint32_t wo = (uint32_t)w1;
+            if (p.stride_w != 1) { // wave-uniform
+                wo = (uint32_t)w1 / (uint32_t)p.stride_w;
+                ok[j] = ok[j] && wo * (uint32_t)p.stride_w == (uint32_t)w1;
+            }
+            off[j] = row_byte + wo * 4u;
+        }
+        singles = false;
+#pragma unroll
+        for (int g = 0; g < NV; ++g) {
+            bool whole = p.stride_w == 1;
+#pragma unroll
+            for (int j = 4 * g; j < 4 * g + 4 && j < N; ++j) whole = whole && ok[j];
+            vgroup[g] = whole ? off[4 * g] : kNoStore;
+#pragma unroll
+            for (int j = 4 * g; j < 4 * g + 4 && j < N; ++j) {
+                const bool one = ok[j] && !whole;
+                vone[j] = one ? off[j] : kNoStore;
+                singles = singles || one;
+            }
+        }
+#pragma unroll
+        for (int j = N; j < NF; ++j) {
+            vone[j] = ok[j] ? off[j] : kNoStore;
+            singles = singles || ok[j];
+        }
+    }
+
+    __device__ __forceinline__ i32x4 channel(int c) const
+    {
+        const uint64_t b = base + (uint64_t)(c * chan_bytes);
+        i32x4 r;
+        r.x = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)b);
+        r.y = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)((b >> 32) & 0xffffu));
+        r.z = (int32_t)kNoStore; // size in bytes (no stride): every real offset is below it
+        r.w = 0x00020000;        // raw 32-bit data
+        return r;
+    }
+
+    // the NF values of channel c (tile-relative) of this lane
+    __device__ __forceinline__ void store_channel(int c, const int32_t (&v)[NF]) const
+    {
+        const i32x4 window = channel(c);
+#pragma unroll
+        for (int g = 0; g < NV; ++g) {
+            constexpr int kFull = 4;
+            const int width = N - 4 * g < kFull ? N - 4 * g : kFull; // compile-time after unrolling
+            if (width == 4) {
+                const i32x4 d = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+                asm volatile("buffer_store_dwordx4 %0, %1, %2, 0 offen" : : "v"(d), "v"(vgroup[g]), "s"(window) : "memory");
+            } else if (width == 3) {
+                const i32x3 d = {v[4 * g], v[4 * g + 1], v[4 * g + 2]};
+                asm volatile("buffer_store_dwordx3 %0, %1, %2, 0 offen" : : "v"(d), "v"(vgroup[g]), "s"(window) : "memory");
+            } else if (width == 2) {
+                const i32x2 d = {v[4 * g], v[4 * g + 1]};
+                asm volatile("buffer_store_dwordx2 %0, %1, %2, 0 offen" : : "v"(d), "v"(vgroup[g]), "s"(window) : "memory");
+            } else {
+                asm volatile("buffer_store_dword %0, %1, %2, 0 offen" : : "v"(v[4 * g]), "v"(vgroup[g]), "s"(window) : "memory");
+            }
+        }
+        if (singles) { // few lanes: ends of rows, high fields; all lanes of a strided layer
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                asm volatile("buffer_store_dword %0, %1, %2, 0 offen" : : "v"(v[j]), "v"(vone[j]), "s"(window) : "memory");
+        }
+    }
+};
+
+// Stores channels c_begin .. c_end-1 of the tile (out - unbias).  Every lane of the wave calls it.
 template <int N, int CO_T>
 __device__ __forceinline__ void store_outputs(const Conv2dArgs &p, const LaneMap &m, int co0, const int32_t (&out)[CO_T][N],
-                                              int32_t unbias)
+                                              int32_t unbias, int c_begin, int c_end)
 {
+    if (p.fast_store) { // wave-uniform
+        bool flag[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) flag[j] = m.active && !m.halo;
+        OutputStores<N, 0> os;
+        os.init(p, m.n, m.ho, m.xi - 1, co0, flag);
+#pragma unroll
+        for (int c = 0; c < CO_T; ++c) {
+            if (c < c_begin || c >= c_end || co0 + c >= p.Co) continue; // wave-uniform
+            int32_t v[N];
+#pragma unroll
+            for (int j = 0; j < N; ++j) v[j] = out[c][j] - unbias;
+            os.store_channel(c, v);
+        }
+        return;
+    }
+    // windows of 2^31 bytes or more: plain stores with 64-bit addresses
     if (!m.active || m.halo) return;
     const int x = m.xi - 1;
 #pragma unroll
     for (int c = 0; c < CO_T; ++c) {
-        if (co0 + c >= p.Co) break;
+        if (c < c_begin || c >= c_end || co0 + c >= p.Co) continue;
         int32_t *yrow = p.y + (((int64_t)m.n * p.Co + co0 + c) * p.Ho + m.ho) * p.Wo;
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const int w1 = x * N + j - p.off; // stride-1 output column
-            if (w1 >= 0 && w1 < p.Wo1) {
-                if (p.stride_w == 1)
-                    yrow[w1] = out[c][j] - unbias;
-                else if (w1 % p.stride_w == 0)
-                    yrow[w1 / p.stride_w] = out[c][j] - unbias;
+            if (w1 >= 0 && w1 < p.Wo1 && (p.stride_w == 1 || w1 % p.stride_w == 0)) {
+                const int wo = p.stride_w == 1 ? w1 : w1 / p.stride_w;
+                yrow[wo] = out[c][j] - unbias;
             }
         }
     }
@@ -225,7 +352,7 @@ __global__ __launch_bounds__(256) void k_conv2d_packed(Conv2dArgs p)
         st.split();
         ++nsplit;
     }
-    store_outputs<N, CO_T>(p, m, co0, st.out, ANY_SIGNED ? nsplit * (1 << (p.S - 1)) : 0);
+    store_outputs<N, CO_T>(p, m, co0, st.out, ANY_SIGNED ? nsplit * (1 << (p.S - 1)) : 0, 0, CO_T);
 }
 
 
@@ -384,21 +511,7 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
             }
         }
     }
-    if (!m.active || m.halo) return;
-    const int x = m.xi - 1;
-#pragma unroll
-    for (int c = 0; c < CO_T; ++c) {
-        if (c < c_begin || c >= c_end || co0 + c >= p.Co) continue;
-        int32_t *yrow = p.y + (((int64_t)m.n * p.Co + co0 + c) * p.Ho + m.ho) * p.Wo;
-#pragma unroll
-        for (int j = 0; j < N; ++j) {
-            const int w1 = x * N + j - p.off; // stride-1 output column
-            if (w1 >= 0 && w1 < p.Wo1 && (p.stride_w == 1 || w1 % p.stride_w == 0)) {
-                const int wo = p.stride_w == 1 ? w1 : w1 / p.stride_w;
-                yrow[wo] = st.out[c][j] - unbias;
-            }
-        }
-    }
+    store_outputs<N, CO_T>(p, m, co0, st.out, unbias, c_begin, c_end);
 }
 
 // dynamic LDS bytes of k_conv2d_pipe

@@ -114,8 +114,24 @@ __device__ __forceinline__ void finish_channel(const Conv2dArgs &p, const LaneMa
     }
 }
 
+// The same through precomputed buffer-store offsets (see OutputStores): no branch, no
+// address arithmetic per channel.  c = channel inside the tile.
+template <int N, int HI>
+__device__ __forceinline__ void finish_channel_fast(const OutputStores<N, HI> &os, bool recv, int c,
+                                                    const int32_t (&v)[N + HI])
+{
+    int32_t o[N + HI];
+#pragma unroll
+    for (int j = 0; j < N + HI; ++j) o[j] = v[j];
+#pragma unroll
+    for (int j = 0; j < HI; ++j) {
+        const int32_t r = (int32_t)lane_shr1((uint32_t)v[N + j]); // every lane takes part in the move
+        if (j < N) o[j] += recv ? r : 0;
+    }
+    os.store_channel(c, o);
+}
+
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Scalar loads and the packed multiply-accumulate are written as instructions: the B words
@@ -178,7 +194,11 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
     int bx, by;
     if (!tile_of_workgroup(p, &bx, &by)) return; // workgroup-uniform, before any barrier
     const int64_t row_group = (int64_t)bx * (4 / p.ksplit) + wave / p.ksplit;
-    const LaneMapS m = map_lane_sreg(p, row_group, lane);
+    LaneMapS m = map_lane_sreg(p, row_group, lane);
+    // the lane's flags travel through the term loop as bits of one vector register, not as lane masks in
+    // scalar registers (which the loop needs for the weight words)
+    uint32_t lane_flags = (m.recv ? 1u : 0u) | (m.store ? 2u : 0u) | (m.store_hi ? 4u : 0u);
+    asm volatile("" : "+v"(lane_flags));
     const int co0 = by * CO_T;
     // byte offset of this lane's 16-byte cell inside a group's activation row (< 2^32, host check)
     const uint32_t lane_byte = (uint32_t)((m.in_row * p.Xs + m.xi) * 16);
@@ -324,9 +344,30 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
             for (int j = 0; j < NF - 1; ++j) out[c][j] -= unbias;
     }
 
+    m.recv = (lane_flags & 1u) != 0;
+    m.store = (lane_flags & 2u) != 0;
+    m.store_hi = (lane_flags & 4u) != 0;
+    OutputStores<N, HI> os;
+    if (p.fast_store) { // wave-uniform
+        bool flag[NF];
+#pragma unroll
+        for (int j = 0; j < NF; ++j) flag[j] = j < N ? m.store : m.store_hi;
+        // the offsets are wanted here, not in registers across the term loop
+        int n_l = m.n, ho_l = m.ho, xi_l = m.xi;
+        asm volatile("" : "+v"(n_l), "+v"(ho_l), "+v"(xi_l));
+        os.init(p, n_l, ho_l, xi_l - 1, co0, flag);
+    }
+    auto finish = [&](int c, const int32_t (&v)[NF]) {
+        if (co0 + c >= p.Co) return; // wave-uniform
+        if (p.fast_store)
+            finish_channel_fast<N, HI>(os, m.recv, c, v);
+        else
+            finish_channel<N, HI>(p, m, co0 + c, v);
+    };
+
     if (p.ksplit == 1) {
 #pragma unroll
-        for (int c = 0; c < CO_T; ++c) finish_channel<N, HI>(p, m, co0 + c, out[c]);
+        for (int c = 0; c < CO_T; ++c) finish(c, out[c]);
         return;
     }
 
@@ -346,12 +387,14 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
         for (int s = ks; s < 4; s += p.ksplit) { // wave-uniform trip count
             int32_t v[NF];
 #pragma unroll
-            for (int j = 0; j < NF; ++j) {
-                int32_t t = 0;
-                for (int k2 = 0; k2 < p.ksplit; ++k2) t += s_red[((w0 + k2) * SLOTS * NF + s * NF + j) * 64 + lane];
-                v[j] = t;
+            for (int j = 0; j < NF; ++j) v[j] = 0;
+#pragma unroll 1
+            for (int k2 = 0; k2 < p.ksplit; ++k2) { // one slice's fields at a time: few registers
+                const int32_t *src = s_red + ((w0 + k2) * SLOTS * NF + s * NF) * 64 + lane;
+#pragma unroll
+                for (int j = 0; j < NF; ++j) v[j] += src[j * 64];
             }
-            finish_channel<N, HI>(p, m, co0 + pass * 4 + s, v);
+            finish(pass * 4 + s, v);
         }
     }
 }

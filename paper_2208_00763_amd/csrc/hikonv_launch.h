@@ -132,6 +132,8 @@ struct Conv2dArgs {
     int64_t wave_rows;       // total rows = Nimg*Ho
     int Wo;                  // strided output width
     int32_t *y;              // [Nimg][Co][Ho][Wo]
+    int fast_store;          // 1: every lane's output lies less than 2^31 bytes after the output row of its wave's
+                             // first lane (same channel): stores through buffer offsets (set by the launcher)
 };
 hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed, int co_tile,
                                 hipStream_t stream);

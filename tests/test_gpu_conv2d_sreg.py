@@ -126,3 +126,26 @@ def test_library_picks_the_kernel_for_a_large_layer():
     assert np.array_equal(run_conv2d(plan, x, w, 1, 1, hk.FMT_INT8, prepacked=True), ref)
     os.environ["HIKONV_CONV2D_KERNEL"] = "1"
     assert np.array_equal(run_conv2d(plan, x, w, 1, 1, hk.FMT_INT8, prepacked=True), ref)
+
+
+@pytest.mark.parametrize("kernel", ["1", "2"])
+def test_stores_with_64bit_addresses(kernel):
+    """The layer kernels store through 32-bit buffer offsets when a wave's outputs lie within
+    2^31 bytes; HIKONV_CONV2D_STORES=0 forces the path for larger windows (plain stores with
+    64-bit addresses) on shapes small enough to check in full."""
+    old = os.environ.get("HIKONV_CONV2D_STORES")
+    os.environ["HIKONV_CONV2D_STORES"] = "0"
+    os.environ["HIKONV_CONV2D_KERNEL"] = kernel
+    try:
+        for bits, a_s, w_s in ((4, True, True), (1, False, False), (8, False, True)):
+            for shape in SHAPES:
+                x, w = _case(bits, a_s, w_s, shape, "s9")
+                stride, pad, kw = shape[7], shape[8], shape[6]
+                ref = direct.conv2d(x, w, stride, pad)
+                plan = dnn_plan(bits, bits, a_s, w_s, kw, 0)
+                assert np.array_equal(run_conv2d(plan, x, w, stride, pad, hk.FMT_INT8), ref), (bits, shape, kernel)
+    finally:
+        if old is None:
+            del os.environ["HIKONV_CONV2D_STORES"]
+        else:
+            os.environ["HIKONV_CONV2D_STORES"] = old
