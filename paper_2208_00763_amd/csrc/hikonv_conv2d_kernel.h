@@ -422,15 +422,15 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
         for (int t = tid; t < tile_n / U + 1; t += 256) s_off[t] = p.toff[tile0 / U + t];
         __syncthreads();
 
-        // this wave's slice of the tile, in groups of U terms, two register buffers for the
-        // activation words: the next group's loads are in flight during the multiplies
+        // this wave's slice of the tile, in groups of U terms, four register buffers for the
+        // activation words: the next groups' loads are in flight during the multiplies
         const int slice = ((tile_n / U + p.ksplit - 1) / p.ksplit) * U;
         const int t_begin = ks * slice;
         int t_end = t_begin + slice;
         if (t_end > tile_n) t_end = tile_n;
         if (t_begin >= t_end) continue; // wave-uniform; barriers are outside this part
 
-        uint32_t a0[U], a1[U];
+        uint32_t a0[U], a1[U], a2[U], a3[U];
         auto request = [&](uint32_t (&a)[U], int t) {
             // the words of the group's four channels sit side by side: one 16-byte load
             // (uniform base + 32-bit lane offset: one VALU add)
@@ -470,13 +470,25 @@ __global__ __launch_bounds__(256) void k_conv2d_pipe(Conv2dArgs p)
             }
         };
 
+        // three groups in flight while one is multiplied: on small layers the loop is a chain
+        // of memory round trips, and this makes it a quarter as long
+        const int t_last = t_end - U;
+        auto clamp = [&](int t) { return t < t_end ? t : t_last; }; // past the end: re-read the last group
         request(a0, t_begin);
-        for (int t = t_begin; t < t_end; t += 2 * U) {
-            request(a1, t + U < t_end ? t + U : t); // past the end: re-read this group
+        request(a1, clamp(t_begin + U));
+        request(a2, clamp(t_begin + 2 * U));
+        for (int t = t_begin; t < t_end; t += 4 * U) {
+            request(a3, clamp(t + 3 * U));
             multiply(a0, t);
             if (t + U >= t_end) break;
-            request(a0, t + 2 * U < t_end ? t + 2 * U : t);
+            request(a0, clamp(t + 4 * U));
             multiply(a1, t + U);
+            if (t + 2 * U >= t_end) break;
+            request(a1, clamp(t + 5 * U));
+            multiply(a2, t + 2 * U);
+            if (t + 3 * U >= t_end) break;
+            request(a2, clamp(t + 6 * U));
+            multiply(a3, t + 3 * U);
         }
     }
     if (since) {
