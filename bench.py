@@ -132,12 +132,21 @@ def requant_extra(hk, wl, steps):
 
         event_ms(packed, 3)
         ms_p = event_ms(packed, steps)
+        # the same call with the plan's own N, K, S instead of the container-aligned slices
+        # (K = 1, N = 2, S = 16) that the library takes here by itself
+        os.environ["HIKONV_REQUANT_KERNEL"] = "1"
+        try:
+            event_ms(packed, 3)
+            ms_plan = event_ms(packed, steps)
+        finally:
+            del os.environ["HIKONV_REQUANT_KERNEL"]
         event_ms(unpacked, 3)
         ms_u = event_ms(unpacked, steps)
         algo = ROWS * (row_bytes + hk.hikonv_bitdense_row_bytes(LENGTH, bits)) + TAPS
         report["%d%s" % (bits, "s" if signed else "u")] = dict(
             ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=algo / ms_p / 1e6, unpacked_ms=ms_u,
             frac_of_unpacked_valu_peak=case["macs"] / (ms_p * 1e-3) / VALU_LANE_RATE,
+            slices="container-aligned: N=2, K=1, S=16", plan_slices_ms=ms_plan,
             plan=dict(N=plan.N, K=plan.K, S=plan.S))
         del case, q
         torch.cuda.empty_cache()

@@ -14,6 +14,7 @@ SOURCES = [
     "hikonv_conv1d.hip",
     "hikonv_conv1d_fast.hip",
     "hikonv_conv1d_requant.hip",
+    "hikonv_conv1d_requant_aligned.hip",
     "hikonv_conv2d.hip",
     "hikonv_conv2d_wide.hip",
     "hikonv_conv2d_narrow.hip",

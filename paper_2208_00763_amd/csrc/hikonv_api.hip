@@ -455,6 +455,16 @@ extern "C" int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_de
     if (rc != HIKONV_OK) return rc == 1 ? HIKONV_OK : rc;
     rc = requant_common(shift, qmax, out_bits, q_dev, &a);
     if (rc != HIKONV_OK) return rc;
+    const bool any_signed = plan->a_signed || plan->w_signed;
+    // Where input and output containers are equal and the sums fit 16-bit slices, the library
+    // computes with container-aligned slices (K = 1, N = 2, S = 16: packing becomes a mask)
+    // instead of the plan's N, K, S; HIKONV_REQUANT_KERNEL=1 (tuning / test override, read per
+    // call) keeps the plan's own slices.
+    {
+        const char *e = getenv("HIKONV_REQUANT_KERNEL");
+        if (!(e && atoi(e) == 1) && conv1d_requant_aligned_applicable(a, plan->a_signed != 0, plan->bits_w))
+            return hip_result(launch_conv1d_requant_aligned(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
+    }
     a.N = plan->N;
     a.Kp = plan->K;
     a.S = plan->S;
@@ -463,7 +473,6 @@ extern "C" int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_de
     a.rq_run_outputs = conv1d_requant_run_outputs(a.N, a.c, a.rq_c_out);
     if (a.rq_run_outputs <= 0) return HIKONV_EUNSUPPORTED;
     a.tiles_per_row = ceil_div(a.out_len, a.rq_run_outputs);
-    const bool any_signed = plan->a_signed || plan->w_signed;
     return hip_result(launch_conv1d_requant(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
 }
 

@@ -1,0 +1,270 @@
+// 1-D convolution with requantised bit-dense output, container-aligned slices.
+//
+// In a 1-D convolution every packed activation word meets one weight word only, so the cost
+// of the packed path is the packing itself (Section "Single convolver architecture": features
+// are packed at run time), not the multiplication.  This kernel uses the plan of Theorem 1
+// with K = 1 that makes packing a mask: slices of S = 16 bits, N = 2 of them in a 32-bit
+// word, and slice n of the word for residue rho holds the element rho + n*J of the window,
+// J = 16 / c elements apart (c = container bits of the bit-dense input).  Then
+//     A_tau = (window >> tau*c) & (value mask at bits 0 and 16)
+// is the packed word of elements tau and tau + J, one shift and one AND, and
+//     Y_rho = sum_k A_(rho + taps-1-k) * g[k]
+// accumulates the taps in the packed domain (the accumulation of products before a split of
+// the "DNN Convolution Extension", M = taps) and holds outputs rho and rho + J in its two
+// slices.  The guard bits are what 16 bits leave above p + q: the launcher takes this path only
+// when taps * max|a| * max|w| fits the slice (2^16 unsigned, 2^15 signed with the bias of
+// Eq. output_split in bias form folded into the accumulator's start value).
+// The slices are exactly the halves that the packed 16-bit instructions work on, so the
+// next operator's ReLU, shift and clamp run on both outputs of a word at once, and because
+// input and output containers have the same width the J words of a window, shifted by rho*c
+// and ORed, are the output dword: no per-field extraction, no staging.
+//
+// One lane produces kUnroll consecutive output dwords from kUnroll + 2 consecutive dwords of
+// the row (two loads, one 16-byte store), kSteps times, 256*kUnroll dwords apart, with the next
+// step's loads in flight.
+#include "hikonv_device.h"
+#include "hikonv_launch.h"
+
+namespace hikonv {
+namespace {
+
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
+// rows start on dword boundaries only: vectors of dwords with dword alignment (global memory takes them)
+typedef uint32_t u32x4_dw __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2_dw __attribute__((ext_vector_type(2), aligned(4)));
+
+constexpr int kUnroll = 4;
+constexpr int kSteps = 4;
+static_assert(kUnroll == 4, "a lane stores its output dwords as one 16-byte vector");
+
+__device__ __forceinline__ uint32_t checked_dword(const uint32_t *x, int64_t d, int64_t total_dwords, int64_t total_bytes)
+{
+    if (d < 0) return 0;
+    if (d < total_dwords) return x[d];
+    uint32_t v = 0;
+    const uint8_t *xb = reinterpret_cast<const uint8_t *>(x);
+    for (int t = 0; t < 4; ++t) {
+        const int64_t byte = d * 4 + t;
+        if (byte < total_bytes) v |= (uint32_t)xb[byte] << (8 * t);
+    }
+    return v;
+}
+
+// C = container bits (input and output), TAPS taps, A_SIGNED / ANY_SIGNED as in the other kernels
+template <int C, int TAPS, bool A_SIGNED, bool ANY_SIGNED>
+__global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
+{
+    constexpr int J = 16 / C;          // residues = elements between the two slices of a word
+    constexpr int PER = 32 / C;        // outputs per dword = 2*J
+    constexpr int NA = J + TAPS - 1;   // packed words per window
+    static_assert((PER + TAPS - 1) * C <= 64, "a window must fit 64 bits");
+
+    __shared__ int32_t s_g[8];
+    if (threadIdx.x < TAPS)
+        s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
+    __syncthreads();
+    int32_t gk[TAPS];
+#pragma unroll
+    for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
+
+    const int b = p.b;
+    const uint32_t vmask = ((1u << b) - 1u) * 0x00010001u;   // the value bits of both slices
+    const uint32_t sbit = (1u << (b - 1)) * 0x00010001u;     // their sign bits
+    const int64_t total_bits = p.total_bytes * 8;
+    const int64_t row_out_dwords = (p.out_len + PER - 1) / PER;
+    // q = min(qmax, max(y, 0) >> shift) on 16-bit fields: a shift that empties the field gives 0
+    const int field_bits = ANY_SIGNED ? 15 : 16;
+    const uint32_t rsh = p.rq_shift < field_bits ? (uint32_t)p.rq_shift : 0u;
+    const uint32_t qmax2 = (p.rq_shift < field_bits ? (uint32_t)p.rq_qmax : 0u) * 0x00010001u;
+    const uint32_t bias2 = ANY_SIGNED ? 0x80008000u : 0u;   // 2^15 in both slices
+
+    // the output dword of a window (elements win[t] = x[i_first + t], zero outside the row)
+    auto output_dword = [&](uint64_t win) -> uint32_t {
+        uint32_t a[NA];
+#pragma unroll
+        for (int t = 0; t < NA; ++t) {
+            uint32_t w = (uint32_t)(win >> (t * C)) & vmask;
+            if (A_SIGNED) w = (w ^ sbit) - sbit; // the signed integer sum of the two signed values (Eq. signpackslice)
+            a[t] = w;
+        }
+        uint32_t word = 0;
+#pragma unroll
+        for (int rho = 0; rho < J; ++rho) {
+            uint32_t y = bias2;
+#pragma unroll
+            for (int k = 0; k < TAPS; ++k) {
+                if (ANY_SIGNED)
+                    y = (uint32_t)(__mul24((int32_t)a[rho + TAPS - 1 - k], gk[k]) + (int32_t)y);
+                else
+                    y = __umul24(a[rho + TAPS - 1 - k], (uint32_t)gk[k]) + y;
+                asm("" : "+v"(y)); // opaque: the products chain on the accumulator (one multiply-add each)
+            }
+            uint32_t q;
+            if (ANY_SIGNED) {
+                // biased fields -> two's complement halves, ReLU, shift, clamp
+                const i16x2 s = __builtin_bit_cast(i16x2, y ^ 0x80008000u);
+                const i16x2 zero = {0, 0};
+                const u16x2 r = __builtin_bit_cast(u16x2, __builtin_elementwise_max(s, zero));
+                const u16x2 shv = {(uint16_t)rsh, (uint16_t)rsh};
+                const u16x2 m = __builtin_elementwise_min(r >> shv, __builtin_bit_cast(u16x2, qmax2));
+                q = __builtin_bit_cast(uint32_t, m);
+            } else {
+                const u16x2 r = __builtin_bit_cast(u16x2, y);
+                const u16x2 shv = {(uint16_t)rsh, (uint16_t)rsh};
+                const u16x2 m = __builtin_elementwise_min(r >> shv, __builtin_bit_cast(u16x2, qmax2));
+                q = __builtin_bit_cast(uint32_t, m);
+            }
+            word |= q << (rho * C);
+        }
+        return word;
+    };
+    auto store = [&](int64_t r, int64_t k, uint32_t word) {
+        const int64_t valid = p.out_len - k * PER; // values past the row's end are not output
+        if (valid < PER) word &= (1u << (uint32_t)(valid * C)) - 1u;
+        p.rq_out[r * p.rq_row_dwords + k] = word;
+    };
+
+    // A lane's loads for one step: kUnroll + 2 dwords hold the windows of its kUnroll
+    // consecutive output dwords (consecutive windows are 32 bits apart); ok = all of them lie
+    // inside the row and the buffer, so the step takes the two-load path
+    struct Fetch {
+        u32x4_dw lo;
+        u32x2_dw hi;
+        uint32_t sh;
+        bool ok;
+    };
+    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
+        const int64_t row_bit0 = r * p.row_stride_bits;
+        auto fetch = [&](int64_t k0) {
+            Fetch f;
+            // first element of the window of dword k: k*PER + shift_m - (TAPS-1)
+            const int64_t i_first = k0 * PER + p.shift_m - (TAPS - 1);
+            const int64_t bit = row_bit0 + i_first * C;
+            f.ok = k0 + kUnroll <= row_out_dwords && i_first >= 0 && i_first + kUnroll * PER + TAPS - 1 <= p.len &&
+                   bit + 32 * (kUnroll + 2) <= total_bits;
+            f.sh = (uint32_t)bit & 31u;
+            f.lo = u32x4_dw{0, 0, 0, 0};
+            f.hi = u32x2_dw{0, 0};
+            if (f.ok) {
+                const uint32_t *wp = p.x + (bit >> 5);
+                f.lo = *reinterpret_cast<const u32x4_dw *>(wp);
+                f.hi = *reinterpret_cast<const u32x2_dw *>(wp + 4);
+            }
+            return f;
+        };
+        auto process = [&](int64_t k0, const Fetch &f) {
+            if (k0 >= row_out_dwords) return;
+            if (f.ok) {
+                const uint32_t w[kUnroll + 2] = {f.lo.x, f.lo.y, f.lo.z, f.lo.w, f.hi.x, f.hi.y};
+                uint32_t out[kUnroll];
+#pragma unroll
+                for (int q = 0; q < kUnroll; ++q) {
+                    const uint64_t win =
+                        ((uint64_t)funnel_shr(w[q + 2], w[q + 1], f.sh) << 32) | funnel_shr(w[q + 1], w[q], f.sh);
+                    out[q] = output_dword(win);
+                }
+                uint32_t *dst = p.rq_out + r * p.rq_row_dwords + k0;
+                if (k0 + kUnroll < row_out_dwords || p.out_len % PER == 0) { // no partial dword among these
+                    const u32x4_dw v = {out[0], out[1], out[2], out[3]};
+                    *reinterpret_cast<u32x4_dw *>(dst) = v;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < kUnroll; ++q) store(r, k0 + q, out[q]);
+                }
+                return;
+            }
+            // row ends, short rows, the end of the buffer: the window element by element
+#pragma unroll 1
+            for (int q = 0; q < kUnroll; ++q) {
+                const int64_t k = k0 + q;
+                if (k >= row_out_dwords) break;
+                const int64_t i0 = k * PER + p.shift_m - (TAPS - 1);
+                uint64_t win = 0;
+#pragma unroll 1
+                for (int t = 0; t < TAPS + PER - 1; ++t) {
+                    const int64_t i = i0 + t;
+                    if (i < 0 || i >= p.len) continue; // zero extension of Eq. pad_f0
+                    const int64_t eb = row_bit0 + i * C;
+                    const uint32_t w = checked_dword(p.x, eb >> 5, p.total_dwords, p.total_bytes);
+                    win |= (uint64_t)((w >> (uint32_t)(eb & 31)) & ((1u << C) - 1u)) << (t * C);
+                }
+                store(r, k, output_dword(win));
+            }
+        };
+        // kSteps steps of 256 lanes x kUnroll dwords per workgroup; the loads of a step are in
+        // flight during the arithmetic of the step before
+        const int64_t k_first = ((int64_t)blockIdx.x * kSteps * 256 + threadIdx.x) * kUnroll;
+        Fetch cur = fetch(k_first);
+#pragma unroll
+        for (int it = 0; it < kSteps; ++it) {
+            const int64_t k0 = k_first + (int64_t)it * 256 * kUnroll;
+            Fetch nxt = cur;
+            if (it + 1 < kSteps) nxt = fetch(k0 + 256 * kUnroll);
+            process(k0, cur);
+            cur = nxt;
+        }
+    }
+}
+
+template <int C, int TAPS>
+hipError_t launch_aligned_ct(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+{
+    if constexpr ((32 / C + TAPS - 1) * C <= 64) {
+        if (a_signed)
+            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, TAPS, true, true>), g, dim3(256), 0, stream, a);
+        else if (any_signed)
+            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, TAPS, false, true>), g, dim3(256), 0, stream, a);
+        else
+            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, TAPS, false, false>), g, dim3(256), 0, stream, a);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidValue;
+    }
+}
+
+template <int C>
+hipError_t launch_aligned_c(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+{
+    switch (a.taps) {
+#define HIKONV_CASE(t) case t: return launch_aligned_ct<C, t>(a, a_signed, any_signed, g, stream);
+        HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6) HIKONV_CASE(7)
+#undef HIKONV_CASE
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace
+
+// Same containers in and out, a window of one output dword within 64 bits, and every sum of
+// taps products within a 16-bit slice (bits_w: weight value bits).
+bool conv1d_requant_aligned_applicable(const Conv1dArgs &a, bool a_signed, int bits_w)
+{
+    if (a.c != a.rq_c_out || (a.c != 1 && a.c != 2 && a.c != 4 && a.c != 8)) return false;
+    if (a.taps < 1 || a.taps > 7 || (32 / a.c + a.taps - 1) * a.c > 64) return false;
+    if (a.b < 1 || a.b > a.c || bits_w < 1 || bits_w > 8) return false;
+    const bool w_signed = a.w_signed != 0;
+    // signed products go through the 24-bit multiplier: a packed word (two values 16 bits apart) must fit 24 bits signed
+    if ((a_signed || w_signed) && a.b > 7) return false;
+    const int64_t max_a = a_signed ? (1LL << (a.b - 1)) : (1LL << a.b) - 1;
+    const int64_t max_w = w_signed ? (1LL << (bits_w - 1)) : (1LL << bits_w) - 1;
+    const int64_t bound = (int64_t)a.taps * max_a * max_w; // |sum| <= bound
+    return (a_signed || w_signed) ? bound < (1LL << 15) : bound < (1LL << 16);
+}
+
+hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
+{
+    const int per = 32 / a.c;
+    const int64_t gx = ceil_div(ceil_div(a.out_len, per), 256 * kUnroll * kSteps);
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
+    switch (a.c) {
+    case 1: return launch_aligned_c<1>(a, a_signed, any_signed, g, stream);
+    case 2: return launch_aligned_c<2>(a, a_signed, any_signed, g, stream);
+    case 4: return launch_aligned_c<4>(a, a_signed, any_signed, g, stream);
+    case 8: return launch_aligned_c<8>(a, a_signed, any_signed, g, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace hikonv

@@ -1,6 +1,8 @@
 """GPU parity: 1-D convolution with in-kernel requantisation and bit-dense output through the
 C ABI vs the oracle chain direct convolution -> ReLU/shift/clamp -> bit-dense packing,
 byte for byte (padding bits of every row included)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -16,6 +18,22 @@ if torch.cuda.is_available():
 
 SIGNS = [(False, False), (True, True), (False, True), (True, False)]
 GUARD = 0xA5
+
+
+@pytest.fixture(autouse=True, params=["library_choice", "plan_slices"])
+def requant_kernel(request):
+    """Every case runs twice: with the library's own choice (container-aligned 16-bit slices where
+    input and output containers are equal and the sums fit) and with the plan's N, K, S forced."""
+    old = os.environ.get("HIKONV_REQUANT_KERNEL")
+    if request.param == "plan_slices":
+        os.environ["HIKONV_REQUANT_KERNEL"] = "1"
+    else:
+        os.environ.pop("HIKONV_REQUANT_KERNEL", None)
+    yield request.param
+    if old is None:
+        os.environ.pop("HIKONV_REQUANT_KERNEL", None)
+    else:
+        os.environ["HIKONV_REQUANT_KERNEL"] = old
 
 
 def oracle_requant(x, g, mode, shift, qmax, out_bits):
@@ -110,9 +128,10 @@ def test_requant_extreme_values_and_partial_clamp(bits, signed):
 
 @pytest.mark.parametrize("signed", [False, True])
 def test_requant_shift_at_and_beyond_the_slice_width(signed):
-    """Shifts around S (10 for 4-bit, 3 taps) up to 31: everything ends at 0 or at the last value bit."""
+    """Shifts around S (10 for 4-bit, 3 taps; 16 for the container-aligned slices) up to 31: everything
+    ends at 0 or at the last value bit."""
     x, g = values("rq5", 4, signed, signed, 3, 4, 5000)
-    for shift in (6, 7, 8, 9, 10, 11, 31):
+    for shift in (6, 7, 8, 9, 10, 11, 14, 15, 16, 17, 31):
         ref = oracle_requant(x, g, hk.OUT_VALID, shift, 15, 4)
         for packed in (True, False):
             got = run_requant(x, g, 4, signed, signed, hk.OUT_VALID, hk.FMT_BITDENSE, shift, 15, 4, packed)

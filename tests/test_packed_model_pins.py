@@ -224,3 +224,42 @@ def test_volume_layer_is_an_outer_sum_over_kernel_depth():
         ws = np.concatenate([wt[:, :, k] for k in range(kd)], axis=1)                 # [co][(kd, ci)][kh][kw]
         got = pm.conv2d_packed(xs.tolist(), ws.tolist(), 0, 3, 3, 14, 6, True)
         assert np.array_equal(np.array(got), ref[0, :, dd])
+
+
+@pytest.mark.parametrize("c,bits,signs,taps", [(4, 4, (False, False), 3), (4, 4, (True, True), 3), (4, 3, (False, True), 5),
+                                               (1, 1, (False, False), 7), (2, 2, (True, False), 3), (8, 6, (True, True), 2)])
+def test_container_aligned_slices_with_one_tap_per_word(c, bits, signs, taps):
+    """Theorem 1 with K = 1 and the elements dealt to the slices J = 16/c apart: the word for residue
+    rho holds elements rho and rho + J of a window in two 16-bit slices, a tap multiplies it as a
+    plain integer, the taps accumulate in the packed domain, and the two slices of the sum are
+    outputs rho and rho + J.  In exact integers, against the direct definition."""
+    a_s, w_s = signs
+    j, per = 16 // c, 32 // c
+    f, g = _rand(5 * per + taps - 1, bits, a_s), _rand(taps, bits, w_s)
+    ref = direct.conv1d(np.array([f]), np.array(g), direct.VALID)[0]
+    any_signed = a_s or w_s
+    got = []
+    for k in range(5):                                   # output dword k: outputs k*per .. k*per + per - 1
+        win = f[k * per:k * per + per + taps - 1]        # window element t = f[k*per + t]
+        out = [None] * per
+        for rho in range(j):
+            y = 0
+            for kk in range(taps):
+                tau = rho + taps - 1 - kk
+                y += pm.pack([win[tau], win[tau + j]], 16) * g[kk]
+            fields = pm.split_signed_bias(y, 16, 2) if any_signed else pm.split_unsigned(y, 16, 2)
+            out[rho], out[rho + j] = fields
+        got += out
+    assert got == [int(v) for v in ref[:5 * per]]
+
+
+def test_container_aligned_slices_need_the_sum_to_fit_sixteen_bits():
+    # 8-bit unsigned, 3 taps: 3 * 255 * 255 does not fit 16 bits and the low slice spills into the high one
+    f, g = [255] * 6, [255] * 3
+    y = sum(pm.pack([f[t], f[t + 2]], 16) * g[k] for k, t in enumerate((2, 1, 0)))
+    assert pm.split_unsigned(y, 16, 2) != [3 * 255 * 255] * 2
+    # one tap fits: 255 * 255 < 2**16
+    assert pm.split_unsigned(pm.pack([255, 255], 16) * 255, 16, 2) == [255 * 255] * 2
+    # signed 7-bit, 2 taps: |sum| <= 2 * 64 * 64 = 2**13 fits the signed slice; the library's bound is |sum| < 2**15
+    y = pm.pack([-64, -64], 16) * -64 + pm.pack([-64, -64], 16) * -64
+    assert pm.split_signed_bias(y, 16, 2) == [8192, 8192]
