@@ -152,9 +152,14 @@ int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, const void *x
  * q_dev: [rows] bit-dense rows of out_len values of out_bits bits,
  * hikonv_bitdense_row_bytes(out_len, out_bits) bytes each, 16-byte aligned;
  * bits beyond out_len in a row are written as 0.  Nothing else is written.
- * Plans with N <= 12 whose N containers fit 32 bits run the streaming kernel;
- * other plans run a slow general kernel; N > 32 or more than 8 chunks give
- * HIKONV_EUNSUPPORTED.
+ * Where the input and output containers have the same width c, taps <= 7, a
+ * window of 32/c + taps - 1 containers fits 64 bits and taps*max|a|*max|w| fits
+ * a 16-bit slice (2^16 unsigned, 2^15 when an operand is signed), the library
+ * computes with container-aligned slices instead of the plan's N, K, S
+ * (Theorem 1 with K = 1, N = 2, S = 16, the elements of a word 16/c apart);
+ * the result is the same.  Otherwise plans with N <= 12 whose N containers fit
+ * 32 bits run the streaming kernel; other plans run a slow general kernel;
+ * N > 32 or more than 8 chunks give HIKONV_EUNSUPPORTED.
  */
 int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows,
                           int64_t len, const void *g_dev, int taps, int out_mode, int shift, int qmax,
