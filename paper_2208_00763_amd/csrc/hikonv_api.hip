@@ -463,7 +463,7 @@ extern "C" int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_de
     {
         const char *e = getenv("HIKONV_REQUANT_KERNEL");
         if (!(e && atoi(e) == 1) && conv1d_requant_aligned_applicable(a, plan->a_signed != 0, plan->bits_w))
-            return hip_result(launch_conv1d_requant_aligned(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
+            return hip_result(launch_conv1d_requant_aligned(a, plan->a_signed != 0, any_signed, plan->bits_w, static_cast<hipStream_t>(stream)));
     }
     a.N = plan->N;
     a.Kp = plan->K;

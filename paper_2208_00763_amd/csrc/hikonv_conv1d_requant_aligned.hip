@@ -14,6 +14,8 @@
 // slices.  The guard bits are what 16 bits leave above p + q: the launcher takes this path only
 // when taps * max|a| * max|w| fits the slice (2^16 unsigned, 2^15 signed with the bias of
 // Eq. output_split in bias form folded into the accumulator's start value).
+// (One-bit unsigned values and taps, whose sums stay below 8, use slices of 4 bits, eight to a
+// word, J = 4: see the kernel.)
 // The slices are exactly the halves that the packed 16-bit instructions work on, so the
 // next operator's ReLU, shift and clamp run on both outputs of a word at once, and because
 // input and output containers have the same width the J words of a window, shifted by rho*c
@@ -51,14 +53,16 @@ __device__ __forceinline__ uint32_t checked_dword(const uint32_t *x, int64_t d, 
     return v;
 }
 
-// C = container bits (input and output), TAPS taps, A_SIGNED / ANY_SIGNED as in the other kernels
-template <int C, int TAPS, bool A_SIGNED, bool ANY_SIGNED>
+// C = container bits (input and output), SW = slice bits (16, or 4 for one-bit values),
+// TAPS taps, A_SIGNED / ANY_SIGNED as in the other kernels
+template <int C, int SW, int TAPS, bool A_SIGNED, bool ANY_SIGNED>
 __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
 {
-    constexpr int J = 16 / C;          // residues = elements between the two slices of a word
-    constexpr int PER = 32 / C;        // outputs per dword = 2*J
+    constexpr int J = SW / C;          // residues = elements between neighbouring slices of a word
+    constexpr int PER = 32 / C;        // outputs per dword = (32 / SW) * J
     constexpr int NA = J + TAPS - 1;   // packed words per window
     static_assert((PER + TAPS - 1) * C <= 64, "a window must fit 64 bits");
+    static_assert(SW == 16 || (SW == 4 && C == 1 && !ANY_SIGNED && TAPS < 8), "nibble slices: one-bit unsigned values only");
 
     __shared__ int32_t s_g[8];
     if (threadIdx.x < TAPS)
@@ -69,8 +73,9 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
     for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
 
     const int b = p.b;
-    const uint32_t vmask = ((1u << b) - 1u) * 0x00010001u;   // the value bits of both slices
-    const uint32_t sbit = (1u << (b - 1)) * 0x00010001u;     // their sign bits
+    constexpr uint32_t kEverySlice = SW == 16 ? 0x00010001u : 0x11111111u; // bit 0 of every slice
+    const uint32_t vmask = ((1u << b) - 1u) * kEverySlice;   // the value bits of every slice
+    const uint32_t sbit = (1u << (b - 1)) * kEverySlice;     // their sign bits
     const int64_t total_bits = p.total_bytes * 8;
     const int64_t row_out_dwords = (p.out_len + PER - 1) / PER;
     // q = min(qmax, max(y, 0) >> shift) on 16-bit fields: a shift that empties the field gives 0
@@ -79,41 +84,57 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
     const uint32_t qmax2 = (p.rq_shift < field_bits ? (uint32_t)p.rq_qmax : 0u) * 0x00010001u;
     const uint32_t bias2 = ANY_SIGNED ? 0x80008000u : 0u;   // 2^15 in both slices
 
+    // Nibble slices (one-bit unsigned values, at most 7 taps: a sum stays below 8): a one-bit tap
+    // multiplies by AND with 0 or ~0; q = min(qmax, y >> shift) is 1 exactly where y >= 2^shift
+    // (nowhere if qmax = 0 or 2^shift > 7): with bit 3 of every slice set, subtracting the threshold
+    // leaves bit 3 set where the slice reaches it.
+    uint32_t gm[TAPS];
+#pragma unroll
+    for (int k = 0; k < TAPS; ++k) gm[k] = 0u - (uint32_t)(gk[k] & 1);
+    const uint32_t thr4 = (p.rq_qmax >= 1 && p.rq_shift < 3 ? (1u << p.rq_shift) : 8u) * 0x11111111u;
+
     // the output dword of a window (elements win[t] = x[i_first + t], zero outside the row)
     auto output_dword = [&](uint64_t win) -> uint32_t {
         uint32_t a[NA];
 #pragma unroll
         for (int t = 0; t < NA; ++t) {
             uint32_t w = (uint32_t)(win >> (t * C)) & vmask;
-            if (A_SIGNED) w = (w ^ sbit) - sbit; // the signed integer sum of the two signed values (Eq. signpackslice)
+            if (A_SIGNED) w = (w ^ sbit) - sbit; // the signed integer sum of the signed values (Eq. signpackslice)
             a[t] = w;
         }
         uint32_t word = 0;
 #pragma unroll
         for (int rho = 0; rho < J; ++rho) {
-            uint32_t y = bias2;
-#pragma unroll
-            for (int k = 0; k < TAPS; ++k) {
-                if (ANY_SIGNED)
-                    y = (uint32_t)(__mul24((int32_t)a[rho + TAPS - 1 - k], gk[k]) + (int32_t)y);
-                else
-                    y = __umul24(a[rho + TAPS - 1 - k], (uint32_t)gk[k]) + y;
-                asm("" : "+v"(y)); // opaque: the products chain on the accumulator (one multiply-add each)
-            }
             uint32_t q;
-            if (ANY_SIGNED) {
-                // biased fields -> two's complement halves, ReLU, shift, clamp
-                const i16x2 s = __builtin_bit_cast(i16x2, y ^ 0x80008000u);
-                const i16x2 zero = {0, 0};
-                const u16x2 r = __builtin_bit_cast(u16x2, __builtin_elementwise_max(s, zero));
-                const u16x2 shv = {(uint16_t)rsh, (uint16_t)rsh};
-                const u16x2 m = __builtin_elementwise_min(r >> shv, __builtin_bit_cast(u16x2, qmax2));
-                q = __builtin_bit_cast(uint32_t, m);
+            if constexpr (SW == 4) {
+                uint32_t y = 0;
+#pragma unroll
+                for (int k = 0; k < TAPS; ++k) y += a[rho + TAPS - 1 - k] & gm[k];
+                q = (((y | 0x88888888u) - thr4) >> 3) & 0x11111111u;
             } else {
-                const u16x2 r = __builtin_bit_cast(u16x2, y);
-                const u16x2 shv = {(uint16_t)rsh, (uint16_t)rsh};
-                const u16x2 m = __builtin_elementwise_min(r >> shv, __builtin_bit_cast(u16x2, qmax2));
-                q = __builtin_bit_cast(uint32_t, m);
+                uint32_t y = bias2;
+#pragma unroll
+                for (int k = 0; k < TAPS; ++k) {
+                    if (ANY_SIGNED)
+                        y = (uint32_t)(__mul24((int32_t)a[rho + TAPS - 1 - k], gk[k]) + (int32_t)y);
+                    else
+                        y = __umul24(a[rho + TAPS - 1 - k], (uint32_t)gk[k]) + y;
+                    asm("" : "+v"(y)); // opaque: the products chain on the accumulator (one multiply-add each)
+                }
+                if (ANY_SIGNED) {
+                    // biased fields -> two's complement halves, ReLU, shift, clamp
+                    const i16x2 s = __builtin_bit_cast(i16x2, y ^ 0x80008000u);
+                    const i16x2 zero = {0, 0};
+                    const u16x2 r = __builtin_bit_cast(u16x2, __builtin_elementwise_max(s, zero));
+                    const u16x2 shv = {(uint16_t)rsh, (uint16_t)rsh};
+                    const u16x2 m = __builtin_elementwise_min(r >> shv, __builtin_bit_cast(u16x2, qmax2));
+                    q = __builtin_bit_cast(uint32_t, m);
+                } else {
+                    const u16x2 r = __builtin_bit_cast(u16x2, y);
+                    const u16x2 shv = {(uint16_t)rsh, (uint16_t)rsh};
+                    const u16x2 m = __builtin_elementwise_min(r >> shv, __builtin_bit_cast(u16x2, qmax2));
+                    q = __builtin_bit_cast(uint32_t, m);
+                }
             }
             word |= q << (rho * C);
         }
@@ -174,20 +195,29 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
                 }
                 return;
             }
-            // row ends, short rows, the end of the buffer: the window element by element
+            // row ends, short rows, the end of the buffer: one window at a time from checked
+            // loads, with the elements outside the row cleared (zero extension of Eq. pad_f0)
 #pragma unroll 1
             for (int q = 0; q < kUnroll; ++q) {
                 const int64_t k = k0 + q;
                 if (k >= row_out_dwords) break;
                 const int64_t i0 = k * PER + p.shift_m - (TAPS - 1);
-                uint64_t win = 0;
-#pragma unroll 1
-                for (int t = 0; t < TAPS + PER - 1; ++t) {
-                    const int64_t i = i0 + t;
-                    if (i < 0 || i >= p.len) continue; // zero extension of Eq. pad_f0
-                    const int64_t eb = row_bit0 + i * C;
-                    const uint32_t w = checked_dword(p.x, eb >> 5, p.total_dwords, p.total_bytes);
-                    win |= (uint64_t)((w >> (uint32_t)(eb & 31)) & ((1u << C) - 1u)) << (t * C);
+                const int64_t wbit = row_bit0 + i0 * C; // negative only before the first row: floor shift, bits 0..31
+                const int64_t d = wbit >> 5;
+                const uint32_t wsh = (uint32_t)wbit & 31u;
+                const uint32_t w0 = checked_dword(p.x, d, p.total_dwords, p.total_bytes);
+                const uint32_t w1 = checked_dword(p.x, d + 1, p.total_dwords, p.total_bytes);
+                const uint32_t w2 = checked_dword(p.x, d + 2, p.total_dwords, p.total_bytes);
+                uint64_t win = ((uint64_t)funnel_shr(w2, w1, wsh) << 32) | funnel_shr(w1, w0, wsh);
+                const int64_t lo = i0 < 0 ? -i0 : 0;
+                int64_t hi = p.len - i0;
+                if (hi > PER + TAPS - 1) hi = PER + TAPS - 1;
+                if (hi <= lo) {
+                    win = 0;
+                } else {
+                    const uint32_t hi_bits = (uint32_t)hi * C, lo_bits = (uint32_t)lo * C; // lo_bits < hi_bits <= 64
+                    const uint64_t m_hi = hi_bits >= 64 ? ~0ull : ((1ull << hi_bits) - 1ull);
+                    win &= m_hi & ~((1ull << lo_bits) - 1ull);
                 }
                 store(r, k, output_dword(win));
             }
@@ -208,15 +238,18 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
 }
 
 template <int C, int TAPS>
-hipError_t launch_aligned_ct(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+hipError_t launch_aligned_ct(const Conv1dArgs &a, bool a_signed, bool any_signed, int bits_w, dim3 g, hipStream_t stream)
 {
     if constexpr ((32 / C + TAPS - 1) * C <= 64) {
         if (a_signed)
-            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, TAPS, true, true>), g, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, 16, TAPS, true, true>), g, dim3(256), 0, stream, a);
         else if (any_signed)
-            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, TAPS, false, true>), g, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, 16, TAPS, false, true>), g, dim3(256), 0, stream, a);
+        else if (C == 1 && a.b == 1 && bits_w == 1)
+            // one-bit unsigned values and taps: sums of at most 7 fit nibble slices, eight outputs per word
+            hipLaunchKernelGGL((k_conv1d_requant_aligned<1, 4, TAPS, false, false>), g, dim3(256), 0, stream, a);
         else
-            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, TAPS, false, false>), g, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((k_conv1d_requant_aligned<C, 16, TAPS, false, false>), g, dim3(256), 0, stream, a);
         return hipGetLastError();
     } else {
         return hipErrorInvalidValue;
@@ -224,10 +257,10 @@ hipError_t launch_aligned_ct(const Conv1dArgs &a, bool a_signed, bool any_signed
 }
 
 template <int C>
-hipError_t launch_aligned_c(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+hipError_t launch_aligned_c(const Conv1dArgs &a, bool a_signed, bool any_signed, int bits_w, dim3 g, hipStream_t stream)
 {
     switch (a.taps) {
-#define HIKONV_CASE(t) case t: return launch_aligned_ct<C, t>(a, a_signed, any_signed, g, stream);
+#define HIKONV_CASE(t) case t: return launch_aligned_ct<C, t>(a, a_signed, any_signed, bits_w, g, stream);
         HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6) HIKONV_CASE(7)
 #undef HIKONV_CASE
     default: return hipErrorInvalidValue;
@@ -252,17 +285,17 @@ bool conv1d_requant_aligned_applicable(const Conv1dArgs &a, bool a_signed, int b
     return (a_signed || w_signed) ? bound < (1LL << 15) : bound < (1LL << 16);
 }
 
-hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
+hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, bool any_signed, int bits_w, hipStream_t stream)
 {
     const int per = 32 / a.c;
     const int64_t gx = ceil_div(ceil_div(a.out_len, per), 256 * kUnroll * kSteps);
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
     switch (a.c) {
-    case 1: return launch_aligned_c<1>(a, a_signed, any_signed, g, stream);
-    case 2: return launch_aligned_c<2>(a, a_signed, any_signed, g, stream);
-    case 4: return launch_aligned_c<4>(a, a_signed, any_signed, g, stream);
-    case 8: return launch_aligned_c<8>(a, a_signed, any_signed, g, stream);
+    case 1: return launch_aligned_c<1>(a, a_signed, any_signed, bits_w, g, stream);
+    case 2: return launch_aligned_c<2>(a, a_signed, any_signed, bits_w, g, stream);
+    case 4: return launch_aligned_c<4>(a, a_signed, any_signed, bits_w, g, stream);
+    case 8: return launch_aligned_c<8>(a, a_signed, any_signed, bits_w, g, stream);
     default: return hipErrorInvalidValue;
     }
 }

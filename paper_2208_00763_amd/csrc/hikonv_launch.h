@@ -54,7 +54,7 @@ hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_si
 hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream);
 // requantised output, container-aligned 16-bit slices (K = 1, N = 2): same containers in and out, sums within a slice
 bool conv1d_requant_aligned_applicable(const Conv1dArgs &a, bool a_signed, int bits_w);
-hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
+hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, bool any_signed, int bits_w, hipStream_t stream);
 
 // ---- 2-D ---------------------------------------------------------------------------
 

@@ -185,3 +185,31 @@ def test_requant_empty_and_rejected_arguments():
         assert e.value.code == hk.EINVAL
     torch.cuda.synchronize()
     assert (q == GUARD).all()
+
+
+@pytest.mark.parametrize("p_bits,q_bits,signs", [(1, 4, (False, False)), (1, 1, (False, False)), (4, 2, (False, True)),
+                                                 (2, 6, (True, True)), (7, 3, (False, False)), (3, 8, (True, False))])
+def test_requant_mixed_widths_same_containers(p_bits, q_bits, signs):
+    """Activation and weight widths differ; output containers as wide as the input's, so the
+    container-aligned slices are taken wherever the sums fit them (and the plan's otherwise)."""
+    a_s, w_s = signs
+    out_bits = p_bits
+    for taps, rows, length in ((3, 3, 4099), (7, 2, 1000), (2, 5, 257)):
+        rng = wl.rng_for("rq7", p_bits, q_bits, a_s, w_s, taps)
+        x = wl.uniform_values(rng, (rows, length), p_bits, a_s)
+        g = wl.uniform_values(rng, (taps,), q_bits, w_s)
+        plan = conv1d_plan(p_bits, a_s, w_s, taps, bits_w=q_bits)
+        top = taps * ((1 << p_bits) - 1) * ((1 << q_bits) - 1)
+        for mode in (hk.OUT_FULL, hk.OUT_VALID):
+            for shift in (0, 1, max(0, int(top).bit_length() - out_bits - 1)):
+                qmax = (1 << out_bits) - 1
+                ref = oracle_requant(x, g, mode, shift, qmax, out_bits)
+                out_len = length + taps - 1 if mode == hk.OUT_FULL else length - taps + 1
+                row_bytes = hk.hikonv_bitdense_row_bytes(out_len, out_bits)
+                q = torch.full((rows * row_bytes + 32,), GUARD, dtype=torch.uint8, device="cuda")
+                hk.hikonv_conv1d_requant(plan, compact(x, p_bits), hk.FMT_BITDENSE, rows, length, dev(g), taps, mode,
+                                         shift, qmax, out_bits, q)
+                torch.cuda.synchronize()
+                res = q.cpu().numpy()
+                assert (res[rows * row_bytes:] == GUARD).all()
+                assert np.array_equal(res[:rows * row_bytes].reshape(rows, row_bytes), ref), (p_bits, q_bits, signs, taps, mode, shift)
