@@ -206,8 +206,9 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
 // Streaming form of the baseline: one lane produces one 16-byte aligned quad of outputs from
 // a 64-bit window of the row read straight from global memory (three dwords), and stores it
 // with one int32x4 store.  Still one v_mad_i32_i24 per low-bit product.  Needs
-// (taps + 3) containers to fit the 64-bit window; row edges take the general path above.
-template <bool A_SIGNED, int TAPS>
+// (taps + 3) containers to fit the window: 64 bits from three dwords, or (WIDE) 96 bits from
+// four; row edges take the element-by-element path.
+template <bool A_SIGNED, int TAPS, bool WIDE>
 __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
 {
     __shared__ int32_t s_g[64];
@@ -234,15 +235,19 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
         const int64_t bit = row_bit0 + i0 * c;
         int32_t out[4] = {0, 0, 0, 0};
         const bool interior = i0 >= 0 && i0 + taps + 3 <= p.len && o0 >= 0 && o0 + 4 <= p.out_len &&
-                              bit + 128 <= total_bits;
+                              bit + (WIDE ? 160 : 128) <= total_bits;
         if (interior) {
             const uint32_t *wp = p.x + (bit >> 5);
             const uint32_t sh = (uint32_t)bit & 31u;
             const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2];
+            const uint32_t w3 = WIDE ? wp[3] : 0u;
             const uint64_t win = ((uint64_t)funnel_shr(w2, w1, sh) << 32) | funnel_shr(w1, w0, sh);
+            const uint32_t win_hi = WIDE ? funnel_shr(w3, w2, sh) : 0u; // bits 64..95 of the window
 #pragma unroll
             for (int t = 0; t < TAPS + 3; ++t) {
-                const int32_t v = field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b);
+                // containers never straddle bit 64 (their width divides 64)
+                const uint32_t bits_t = WIDE && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
+                const int32_t v = field<A_SIGNED>(bits_t, 0u, (uint32_t)b);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int k = u + TAPS - 1 - t;
@@ -314,13 +319,18 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
     const int64_t gx = ceil_div(nquads + 7, kThreads); // the streaming baseline shifts its lanes by up to 7 quads
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
-    if ((a.taps + 3) * a.c <= 64 && a.taps <= 7) {
-#define HIKONV_UNP(T)                                                                        \
-    case T:                                                                                  \
-        if (a_signed)                                                                        \
-            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T>), g, b, 0, stream, a);       \
-        else                                                                                 \
-            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T>), g, b, 0, stream, a);      \
+    if ((a.taps + 3) * a.c <= 96 && a.taps <= 7) {
+        const bool wide_window = (a.taps + 3) * a.c > 64;
+#define HIKONV_UNP(T)                                                                               \
+    case T:                                                                                         \
+        if (a_signed && wide_window)                                                                \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T, true>), g, b, 0, stream, a);        \
+        else if (a_signed)                                                                          \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T, false>), g, b, 0, stream, a);       \
+        else if (wide_window)                                                                       \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T, true>), g, b, 0, stream, a);       \
+        else                                                                                        \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T, false>), g, b, 0, stream, a);      \
         break;
         switch (a.taps) {
             HIKONV_UNP(1) HIKONV_UNP(2) HIKONV_UNP(3) HIKONV_UNP(4) HIKONV_UNP(5) HIKONV_UNP(6) HIKONV_UNP(7)

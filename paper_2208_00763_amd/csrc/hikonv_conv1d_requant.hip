@@ -366,25 +366,36 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
                 emit(r, k0 + q * 256, out);
             }
         } else {
+            // row ends, short rows, the end of the buffer: the same window from checked loads,
+            // with the elements outside the row cleared
 #pragma unroll 1
             for (int q = 0; q < U; ++q) {
                 const int64_t k = k0 + q * 256;
                 if (k >= row_out_dwords) break;
                 const int64_t i0 = k * PER + p.shift_m - (TAPS - 1);
+                const int64_t wbit = row_bit0 + i0 * c; // negative only before the first row: floor shift, bits 0..31
+                const int64_t d = wbit >> 5;
+                const uint32_t wsh = (uint32_t)wbit & 31u;
+                const uint32_t v0 = load_dword_checked(p.x, d, p.total_dwords, p.total_bytes);
+                const uint32_t v1 = load_dword_checked(p.x, d + 1, p.total_dwords, p.total_bytes);
+                const uint32_t v2 = load_dword_checked(p.x, d + 2, p.total_dwords, p.total_bytes);
+                uint64_t win = ((uint64_t)funnel_shr(v2, v1, wsh) << 32) | funnel_shr(v1, v0, wsh);
+                const int64_t lo = i0 < 0 ? -i0 : 0;
+                int64_t hi = p.len - i0;
+                if (hi > TAPS + PER - 1) hi = TAPS + PER - 1;
+                if (hi <= lo) {
+                    win = 0;
+                } else {
+                    const uint32_t hi_bits = (uint32_t)hi * (uint32_t)c, lo_bits = (uint32_t)lo * (uint32_t)c;
+                    const uint64_t m_hi = hi_bits >= 64 ? ~0ull : ((1ull << hi_bits) - 1ull);
+                    win &= m_hi & ~((1ull << lo_bits) - 1ull);
+                }
                 int32_t out[PER];
 #pragma unroll
                 for (int u = 0; u < PER; ++u) out[u] = 0;
-#pragma unroll 1
-                for (int t = 0; t < TAPS + PER - 1; ++t) {
-                    const int64_t i = i0 + t;
-                    int32_t v = 0;
-                    if (i >= 0 && i < p.len) {
-                        const int64_t eb = row_bit0 + i * c;
-                        const uint32_t w = load_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
-                        v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
-                    }
-                    accumulate(out, t, v);
-                }
+#pragma unroll
+                for (int t = 0; t < TAPS + PER - 1; ++t)
+                    accumulate(out, t, field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b));
                 emit(r, k, out);
             }
         }
