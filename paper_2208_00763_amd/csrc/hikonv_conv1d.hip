@@ -208,6 +208,8 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
 // with one int32x4 store.  Still one v_mad_i32_i24 per low-bit product.  Needs
 // (taps + 3) containers to fit the window: 64 bits from three dwords, or (WIDE) 96 bits from
 // four; row edges take the element-by-element path.
+constexpr int kUnpackedQuads = 4; // output quads per lane, kThreads quads apart
+
 template <bool A_SIGNED, int TAPS, bool WIDE>
 __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
 {
@@ -227,57 +229,75 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
         // the quads of a wave start on a 128-byte line of y, as in the packed kernel: the row's
         // quad 0 sits `lead` quads into its line, so the lanes are shifted back by that much
         const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> 2) & 7);
-        const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x - lead;
-        if (q < 0 || q >= nquads) continue;
         const int64_t row_bit0 = r * p.row_stride_bits;
-        const int64_t o0 = 4 * q - a_off;                       // first output of this lane's aligned quad
-        const int64_t i0 = o0 + p.shift_m - (taps - 1);          // first element it reads
-        const int64_t bit = row_bit0 + i0 * c;
-        int32_t out[4] = {0, 0, 0, 0};
-        const bool interior = i0 >= 0 && i0 + taps + 3 <= p.len && o0 >= 0 && o0 + 4 <= p.out_len &&
-                              bit + (WIDE ? 160 : 128) <= total_bits;
-        if (interior) {
-            const uint32_t *wp = p.x + (bit >> 5);
-            const uint32_t sh = (uint32_t)bit & 31u;
-            const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2];
-            const uint32_t w3 = WIDE ? wp[3] : 0u;
-            const uint64_t win = ((uint64_t)funnel_shr(w2, w1, sh) << 32) | funnel_shr(w1, w0, sh);
-            const uint32_t win_hi = WIDE ? funnel_shr(w3, w2, sh) : 0u; // bits 64..95 of the window
+        int32_t *yrow = p.y + r * p.out_len;
+        // kUnpackedQuads quads per lane, kThreads quads apart; the window loads of all of them first
+        int64_t qv[kUnpackedQuads];
+        bool interior[kUnpackedQuads];
+        uint32_t w0[kUnpackedQuads], w1[kUnpackedQuads], w2[kUnpackedQuads], w3[kUnpackedQuads];
 #pragma unroll
-            for (int t = 0; t < TAPS + 3; ++t) {
-                // containers never straddle bit 64 (their width divides 64)
-                const uint32_t bits_t = WIDE && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
-                const int32_t v = field<A_SIGNED>(bits_t, 0u, (uint32_t)b);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int k = u + TAPS - 1 - t;
-                    if (k >= 0 && k < TAPS) out[u] = __mul24(v, gk[k]) + out[u];
-                }
-            }
-        } else {
-            for (int t = 0; t < taps + 3; ++t) {
-                const int64_t i = i0 + t;
-                int32_t v = 0;
-                if (i >= 0 && i < p.len) {
-                    const int64_t eb = row_bit0 + i * c;
-                    const uint32_t w = load_dword_safe(p.x, eb >> 5, p.total_dwords, p.total_bytes);
-                    v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int k = u + taps - 1 - t;
-                    if (k >= 0 && k < taps) out[u] = __mul24(v, s_g[k]) + out[u];
-                }
+        for (int s = 0; s < kUnpackedQuads; ++s) {
+            qv[s] = ((int64_t)blockIdx.x * kUnpackedQuads + s) * kThreads + threadIdx.x - lead;
+            const int64_t o0 = 4 * qv[s] - a_off;              // first output of this lane's aligned quad
+            const int64_t i0 = o0 + p.shift_m - (taps - 1);     // first element it reads
+            const int64_t bit = row_bit0 + i0 * c;
+            interior[s] = qv[s] >= 0 && qv[s] < nquads && i0 >= 0 && i0 + taps + 3 <= p.len && o0 >= 0 &&
+                          o0 + 4 <= p.out_len && bit + (WIDE ? 160 : 128) <= total_bits;
+            w0[s] = w1[s] = w2[s] = w3[s] = 0u;
+            if (interior[s]) {
+                const uint32_t *wp = p.x + (bit >> 5);
+                w0[s] = wp[0];
+                w1[s] = wp[1];
+                w2[s] = wp[2];
+                if (WIDE) w3[s] = wp[3];
             }
         }
-        int32_t *yrow = p.y + r * p.out_len;
-        if (o0 >= 0 && o0 + 4 <= p.out_len) {
-            typedef int32_t v4i __attribute__((ext_vector_type(4)));
-            const v4i v4 = {out[0], out[1], out[2], out[3]};
-            __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o0])); // streaming hint, whole lines per wave
-        } else {
-            for (int u = 0; u < 4; ++u)
-                if (o0 + u >= 0 && o0 + u < p.out_len) yrow[o0 + u] = out[u];
+#pragma unroll
+        for (int s = 0; s < kUnpackedQuads; ++s) {
+            const int64_t q = qv[s];
+            if (q < 0 || q >= nquads) continue;
+            const int64_t o0 = 4 * q - a_off;
+            const int64_t i0 = o0 + p.shift_m - (taps - 1);
+            int32_t out[4] = {0, 0, 0, 0};
+            if (interior[s]) {
+                const uint32_t sh = (uint32_t)(row_bit0 + i0 * c) & 31u;
+                const uint64_t win = ((uint64_t)funnel_shr(w2[s], w1[s], sh) << 32) | funnel_shr(w1[s], w0[s], sh);
+                const uint32_t win_hi = WIDE ? funnel_shr(w3[s], w2[s], sh) : 0u; // bits 64..95 of the window
+#pragma unroll
+                for (int t = 0; t < TAPS + 3; ++t) {
+                    // containers never straddle bit 64 (their width divides 64)
+                    const uint32_t bits_t = WIDE && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
+                    const int32_t v = field<A_SIGNED>(bits_t, 0u, (uint32_t)b);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int k = u + TAPS - 1 - t;
+                        if (k >= 0 && k < TAPS) out[u] = __mul24(v, gk[k]) + out[u];
+                    }
+                }
+            } else {
+                for (int t = 0; t < taps + 3; ++t) {
+                    const int64_t i = i0 + t;
+                    int32_t v = 0;
+                    if (i >= 0 && i < p.len) {
+                        const int64_t eb = row_bit0 + i * c;
+                        const uint32_t w = load_dword_safe(p.x, eb >> 5, p.total_dwords, p.total_bytes);
+                        v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int k = u + taps - 1 - t;
+                        if (k >= 0 && k < taps) out[u] = __mul24(v, s_g[k]) + out[u];
+                    }
+                }
+            }
+            if (o0 >= 0 && o0 + 4 <= p.out_len) {
+                typedef int32_t v4i __attribute__((ext_vector_type(4)));
+                const v4i v4 = {out[0], out[1], out[2], out[3]};
+                __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o0])); // streaming hint, whole lines per wave
+            } else {
+                for (int u = 0; u < 4; ++u)
+                    if (o0 + u >= 0 && o0 + u < p.out_len) yrow[o0 + u] = out[u];
+            }
         }
     }
 }
@@ -321,6 +341,7 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
     if ((a.taps + 3) * a.c <= 96 && a.taps <= 7) {
         const bool wide_window = (a.taps + 3) * a.c > 64;
+        g.x = (unsigned)ceil_div(nquads + 7, (int64_t)kThreads * kUnpackedQuads);
 #define HIKONV_UNP(T)                                                                               \
     case T:                                                                                         \
         if (a_signed && wide_window)                                                                \
