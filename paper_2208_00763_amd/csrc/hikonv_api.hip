@@ -392,7 +392,7 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
         a.CH = 0;
         conv1d_fast_tuning(&a);
         a.tiles_per_row = conv1d_fast_runs_per_row(a);
-        if (a.aligned_runs && !a.direct_store) {
+        if (a.aligned_runs) {
             a.run_outputs = conv1d_fast_run_outputs(a);
             a.y_phase = (int)((reinterpret_cast<uintptr_t>(y_dev) >> 2) & (a.align_outputs - 1));
             if (a.run_outputs >= a.align_outputs)

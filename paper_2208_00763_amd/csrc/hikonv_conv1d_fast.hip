@@ -363,8 +363,6 @@ static int env_flag(const char *name, int dflt)
 void conv1d_fast_tuning(Conv1dArgs *a)
 {
     static const int aligned = env_flag("HIKONV_CONV1D_ALIGNED", -1);
-    a->direct_store = 0;
-    a->big_runs = 1;
     a->aligned_runs = aligned >= 0 ? aligned : 1;
     a->align_outputs = kAlignOutputs;
 }

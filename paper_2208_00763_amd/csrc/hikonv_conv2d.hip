@@ -379,7 +379,6 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_sign
     a.tiles_x = (int)gx;
     a.tiles_y = (int)gy;
     a.per_xcd = xcd_order && gx * gy >= 64 ? (int)ceil_div(gx * gy, 8) : 0;
-    a.tile_order = xcd_order == 2 || (xcd_order == 3 && a.sreg) ? 1 : 0;
     dim3 g((unsigned)(a.per_xcd ? (int64_t)a.per_xcd * 8 : gx * gy));
     // Stores through 32-bit buffer offsets from the output row of a wave's first lane: the
     // lanes of a wave share one row (long rows) or cover rows_per_wave consecutive rows, which

@@ -54,14 +54,9 @@ __device__ __forceinline__ bool tile_of_workgroup(const Conv2dArgs &p, int *bx, 
     uint32_t v = blockIdx.x;
     if (p.per_xcd) v = (blockIdx.x & 7u) * (uint32_t)p.per_xcd + (blockIdx.x >> 3);
     if (v >= (uint32_t)p.tiles_x * (uint32_t)p.tiles_y) return false;
-    uint32_t x, y;
-    if (p.tile_order == 1) { // row-group block fastest: neighbours in time share the weight rows
-        y = v / (uint32_t)p.tiles_x;
-        x = v - y * (uint32_t)p.tiles_x;
-    } else { // channel tile fastest: neighbours in time share the activation rows
-        x = v / (uint32_t)p.tiles_y;
-        y = v - x * (uint32_t)p.tiles_y;
-    }
+    // channel tile fastest: neighbours in time share the activation rows
+    const uint32_t x = v / (uint32_t)p.tiles_y;
+    const uint32_t y = v - x * (uint32_t)p.tiles_y;
     // the divisions run on the vector ALU; the results are workgroup uniform and are used as scalars
     *bx = __builtin_amdgcn_readfirstlane((int)x);
     *by = __builtin_amdgcn_readfirstlane((int)y);

@@ -24,7 +24,6 @@ struct Conv1dArgs {
     int64_t n_blocks;        // packed blocks per row
     int CH;                  // wave-chunks of 63 blocks per wave
     int64_t tiles_per_row;
-    int direct_store, big_runs; // unused (kept at 0, 1)
     int aligned_runs;        // streaming kernel, staged stores: 1 = a wave owns an output interval whose
                              // ends fall on 128-byte lines of y (it recomputes a few blocks at its start)
     int64_t run_outputs;     // aligned runs: outputs per interval (a multiple of 32)
@@ -129,7 +128,6 @@ struct Conv2dArgs {
     int rows_per_wave, segs; // lane mapping
     int tiles_x, tiles_y;    // row-group blocks x channel tiles; the grid is 1-D (see tile_of_workgroup)
     int per_xcd;             // ceil(tiles_x*tiles_y / 8), 0 = plain order
-    int tile_order;          // 0: channel tile fastest, 1: row-group block fastest
     int sreg;                // 1: k_conv2d_sreg (weights in scalar registers), 0: the LDS-staged kernels
     int Lr;                  // k_conv2d_sreg, segs == 0: lanes per row (blocks that hold input values)
     int64_t wave_rows;       // total rows = Nimg*Ho
