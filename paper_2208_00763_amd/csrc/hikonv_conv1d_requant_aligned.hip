@@ -75,14 +75,22 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
     const int b = p.b;
     constexpr uint32_t kEverySlice = SW == 16 ? 0x00010001u : 0x11111111u; // bit 0 of every slice
     const uint32_t vmask = ((1u << b) - 1u) * kEverySlice;   // the value bits of every slice
-    const uint32_t sbit = (1u << (b - 1)) * kEverySlice;     // their sign bits
     const int64_t total_bits = p.total_bytes * 8;
     const int64_t row_out_dwords = (p.out_len + PER - 1) / PER;
     // q = min(qmax, max(y, 0) >> shift) on 16-bit fields: a shift that empties the field gives 0
     const int field_bits = ANY_SIGNED ? 15 : 16;
     const uint32_t rsh = p.rq_shift < field_bits ? (uint32_t)p.rq_shift : 0u;
     const uint32_t qmax2 = (p.rq_shift < field_bits ? (uint32_t)p.rq_qmax : 0u) * 0x00010001u;
-    const uint32_t bias2 = ANY_SIGNED ? 0x80008000u : 0u;   // 2^15 in both slices
+    uint32_t bias2 = ANY_SIGNED ? 0x80008000u : 0u;   // 2^15 in both slices
+    uint64_t sign_flip = 0;                            // bit b-1 of every container of a window
+    if (A_SIGNED) {
+#pragma unroll
+        for (int t = 0; t < 64 / C; ++t) sign_flip |= (uint64_t)(1u << (b - 1)) << (t * C);
+        int32_t gsum = 0;
+#pragma unroll
+        for (int k = 0; k < TAPS; ++k) gsum += gk[k];
+        bias2 -= (uint32_t)(gsum * (1 << (b - 1))) * 0x00010001u; // modular: the final sum is exact
+    }
 
     // Nibble slices (one-bit unsigned values, at most 7 taps: a sum stays below 8): a one-bit tap
     // multiplies by AND with 0 or ~0; q = min(qmax, y >> shift) is 1 exactly where y >= 2^shift
@@ -95,13 +103,13 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
 
     // the output dword of a window (elements win[t] = x[i_first + t], zero outside the row)
     auto output_dword = [&](uint64_t win) -> uint32_t {
+        // Signed activations: with the sign bit of every container flipped the value bits read as
+        // f + 2^(b-1) >= 0, so every packed word is too large by 2^(b-1) in every slice and the sum
+        // by 2^(b-1) * sum(g) in every slice: a constant of the kernel, taken off the start value.
+        if (A_SIGNED) win ^= sign_flip;
         uint32_t a[NA];
 #pragma unroll
-        for (int t = 0; t < NA; ++t) {
-            uint32_t w = (uint32_t)(win >> (t * C)) & vmask;
-            if (A_SIGNED) w = (w ^ sbit) - sbit; // the signed integer sum of the signed values (Eq. signpackslice)
-            a[t] = w;
-        }
+        for (int t = 0; t < NA; ++t) a[t] = (uint32_t)(win >> (t * C)) & vmask;
         uint32_t word = 0;
 #pragma unroll
         for (int rho = 0; rho < J; ++rho) {
