@@ -241,6 +241,33 @@ def widened_extras(hk, steps):
     rep["unpacked_ms"] = event_ms(run_u, steps)
     out["conv2d_stride2"] = rep
 
+    # the binarised layer shape at a batch that fills the chip (the configuration itself has 8 images)
+    n, c, h, w, co = 64, 256, 28, 28, 256
+    xb = (rng.integers(0, 2, (n, c, h, w), dtype=np.int8) * 2 - 1).astype(np.int8)
+    wb = (rng.integers(0, 2, (co, c, 3, 3), dtype=np.int8) * 2 - 1).astype(np.int8)
+    x_d = torch.from_numpy(xb.view("uint8")).cuda()
+    w_d = torch.from_numpy(wb.view("uint8")).cuda()
+    plan = hk.hikonv_plan_ex(L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3, bits_a=1, bits_w=1, bipolar=1)
+    ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, n, c, h, w, co, 3, 3, 1, 1, True), dtype=torch.uint8,
+                     device="cuda")
+    pw = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, 3, 3), dtype=torch.uint8, device="cuda")
+    hk.hikonv_pack_weights(plan, w_d, co, c, 3, 3, pw)
+    y = torch.empty(n * co * h * w, dtype=torch.int32, device="cuda")
+    runb = lambda: hk.hikonv_conv2d_prepacked(plan, x_d, hk.FMT_INT8, n, c, h, w, pw, co, 3, 3, 1, 1, ws, y)
+    event_ms(runb, 3)
+    ms = event_ms(runb, steps)
+    macs = n * co * h * w * c * 9
+    lane_mads = n * co * h * (-(-(w + 1) // plan.N)) * c * 3 * plan.chunks
+    out["conv2d_c4_batch64"] = dict(shape="64x256x28x28 -> 256, 3x3, stride 1, pad 1, {-1,+1}", macs=macs, ms=ms,
+                                    gops=2 * macs / ms / 1e6, plan=dict(N=plan.N, K=plan.K, S=plan.S, M=plan.M),
+                                    frac_of_unpacked_valu_peak=macs / (ms * 1e-3) / VALU_LANE_RATE,
+                                    roofline={"bound": "alu", "achieved": lane_mads / (ms * 1e-3) / 1e12,
+                                              "peak": VALU_LANE_RATE / 1e12, "unit": "T lane-instr/s",
+                                              "frac": lane_mads / (ms * 1e-3) / VALU_LANE_RATE,
+                                              "note": "packed multiply-accumulates only, whole call (input packing included)"})
+    del x_d, w_d, ws, pw, y
+    torch.cuda.empty_cache()
+
     n, c, d, h, w, co = 1, 16, 16, 56, 56, 32
     x_d = torch.from_numpy(rng.integers(-8, 8, (n, c, d, h, w), dtype=np.int8).view("uint8")).cuda()
     w_d = torch.from_numpy(rng.integers(-8, 8, (co, c, 3, 3, 3), dtype=np.int8).view("uint8")).cuda()
