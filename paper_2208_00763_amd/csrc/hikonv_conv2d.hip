@@ -38,17 +38,22 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     }
     if (idx >= total) return;
     const int u = (int)(idx & 3); // channel inside the quad
-    int64_t t = idx >> 2;
-    const int xi = (int)(t % p.Xs);
-    t /= p.Xs;
-    const int hp = (int)(t % p.Hp);
-    t /= p.Hp;
-    const int dp = (int)(t % p.Dp);
-    t /= p.Dp;
-    const int64_t ncq = t % ((int64_t)p.Nimg * p.Cq);
-    const int ch = (int)(t / ((int64_t)p.Nimg * p.Cq));
-    const int64_t n_img = ncq / p.Cq;
-    const int c_packed = (int)(ncq - n_img * p.Cq) * 4 + u;
+    // fewer than 2^30 words in all (checked by the caller): 32-bit divisions
+    uint32_t t = (uint32_t)(idx >> 2);
+    uint32_t q = t / (uint32_t)p.Xs;
+    const int xi = (int)(t - q * (uint32_t)p.Xs);
+    t = q;
+    q = t / (uint32_t)p.Hp;
+    const int hp = (int)(t - q * (uint32_t)p.Hp);
+    t = q;
+    q = t / (uint32_t)p.Dp;
+    const int dp = (int)(t - q * (uint32_t)p.Dp);
+    t = q;
+    const uint32_t ncq_all = (uint32_t)p.Nimg * (uint32_t)p.Cq;
+    const int ch = (int)(t / ncq_all);
+    const uint32_t ncq = t - (uint32_t)ch * ncq_all;
+    const int64_t n_img = ncq / (uint32_t)p.Cq;
+    const int c_packed = (int)(ncq - (uint32_t)n_img * (uint32_t)p.Cq) * 4 + u;
     if (c_packed >= p.C) { // channels that only fill the last quad
         p.apk[idx] = 0;
         return;
