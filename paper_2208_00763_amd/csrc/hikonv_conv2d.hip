@@ -20,22 +20,117 @@ namespace {
 // c / s, phase c % s) and f[i] = padded source row at s*i + phase, i.e. source value
 // s*i + phase - pad, so that a stride-s row convolution becomes the sum over the phases of
 // stride-1 row convolutions with the phase kernels.
+// One packed word: chunk ch, image n_img, packed channel c_packed, source depth d and row h
+// (both inside the image), word xi > 0.  FMT: the source format (HIKONV_FMT_INT8,
+// HIKONV_FMT_BITDENSE or kPackFromAcc), fixed at compile time in the kernels below.
+template <int FMT>
+__device__ __forceinline__ uint32_t pack_act_word(const PackActArgs &p, int ch, int64_t n_img, int c_packed, int d, int h,
+                                                  int xi)
+{
+    uint32_t a = 0;
+    const int e0 = (xi - 1) * p.N - ch * p.Kp;
+    if (FMT == kPackFromAcc) {
+        // fused epilogue of the producing layer (ReLU, shift, clamp, optional 2x2 max-pool); 2-D, one phase
+        const int32_t *src = p.acc + (n_img * p.C + c_packed) * p.acc_H * p.acc_W;
+        for (int j = 0; j < p.N; ++j) {
+            const int i = e0 + j;
+            if (i < 0 || i >= p.W) continue;
+            int32_t v;
+            if (p.pool) {
+                const int32_t *s0 = src + (int64_t)(2 * h) * p.acc_W + 2 * i;
+                v = max(max(s0[0], s0[1]), max(s0[p.acc_W], s0[p.acc_W + 1]));
+            } else {
+                v = src[(int64_t)h * p.acc_W + i];
+            }
+            v = min(max(v, 0) >> p.shift, p.qmax);
+            a += (uint32_t)v << (p.S * j);
+        }
+        return a;
+    }
+    const int csrc = c_packed / p.phases, phase = c_packed - csrc * p.phases;
+    const uint8_t *rowp =
+        static_cast<const uint8_t *>(p.x) + (((n_img * p.Csrc + csrc) * p.D + d) * p.H + h) * p.row_bytes;
+    for (int j = 0; j < p.N; ++j) {
+        const int i = e0 + j; // element of the packed row
+        if (i < 0 || i >= p.W) continue;
+        const int is = i * p.phases + phase - p.pad_w_mat; // source value
+        if (is < 0 || is >= p.Wsrc) continue;
+        int32_t v;
+        if (FMT == HIKONV_FMT_INT8) {
+            const uint8_t byte = rowp[is];
+            if (p.bipolar)
+                v = (int8_t)byte > 0 ? 1 : -1;
+            else
+                v = p.a_signed ? __builtin_amdgcn_sbfe((int)byte, 0, p.b) : (int)__builtin_amdgcn_ubfe(byte, 0, p.b);
+        } else {
+            const int bit = is * p.c;
+            const uint32_t w = reinterpret_cast<const uint32_t *>(rowp)[bit >> 5];
+            if (p.bipolar)
+                v = ((w >> (bit & 31)) & 1u) ? 1 : -1;
+            else
+                v = p.a_signed ? __builtin_amdgcn_sbfe((int)w, bit & 31, p.b) : (int)__builtin_amdgcn_ubfe(w, bit & 31, p.b);
+        }
+        a += (uint32_t)v << (p.S * j);
+    }
+    return a;
+}
+
+// the table of activation offsets of the term groups (entry gi, zero beyond the groups):
+// gi = ((cq*Kd + kd)*Kh + kh)*chunks + chunk  ->  byte offset 16*(chunk*chunk_stride + ((cq*Dp + kd)*Hp + kh)*Xs)
+__device__ __forceinline__ void write_offset_entry(const PackActArgs &p, int gi)
+{
+    int32_t off = 0;
+    if (gi < p.groups) {
+        const int ch = gi % p.chunks, kh = (gi / p.chunks) % p.Kh, kd = (gi / (p.chunks * p.Kh)) % p.Kd;
+        const int cq = gi / (p.chunks * p.Kh * p.Kd);
+        off = (int32_t)(uint32_t)(16 * (ch * p.chunk_stride + (((int64_t)cq * p.Dp + kd) * p.Hp + kh) * p.Xs)); // < 2^32
+    }
+    p.toff[gi] = off;
+}
+
+// One thread per word.  Grid: x over the 4*Xs words of a packed row (four channels of a quad
+// side by side), y = padded row hp (groups of rows_per_block rows when a row is shorter than a block), z = ((chunk*Nimg + n)*Cq + quad)*Dp + dp, so a thread finds
+// its coordinates without dividing; block (0,0,0) also writes the offset table.
+template <int FMT>
+__global__ __launch_bounds__(256) void k_pack_act_rows(PackActArgs p)
+{
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+        for (int gi = threadIdx.x; gi < p.toff_entries; gi += 256) write_offset_entry(p, gi);
+    // short rows: a block takes rows_per_block of them (one 32-bit division per thread)
+    int t = blockIdx.x * 256 + threadIdx.x, r = 0;
+    if (p.rows_per_block > 1) {
+        r = (int)((uint32_t)threadIdx.x / (uint32_t)(p.Xs * 4));
+        t = threadIdx.x - r * p.Xs * 4;
+        if (r >= p.rows_per_block) return;
+    }
+    if (t >= p.Xs * 4) return;
+    const int u = t & 3, xi = t >> 2;
+    const int hp = blockIdx.y * p.rows_per_block + r;
+    if (hp >= p.Hp) return;
+    // workgroup-uniform coordinates
+    uint32_t z = blockIdx.z;
+    uint32_t q = z / (uint32_t)p.Dp;
+    const int dp = (int)(z - q * (uint32_t)p.Dp);
+    z = q;
+    q = z / (uint32_t)p.Cq;
+    const int cq = (int)(z - q * (uint32_t)p.Cq);
+    z = q;
+    const int ch = (int)(z / (uint32_t)p.Nimg);
+    const int n_img = (int)(z - (uint32_t)ch * (uint32_t)p.Nimg);
+    const int c_packed = cq * 4 + u;
+    const int h = hp - p.pad, d = dp - p.pad_d;
+    uint32_t a = 0;
+    if (c_packed < p.C && xi > 0 && h >= 0 && h < p.H && d >= 0 && d < p.D)
+        a = pack_act_word<FMT>(p, ch, n_img, c_packed, d, h, xi);
+    p.apk[(((int64_t)blockIdx.z * p.Hp + hp) * p.Xs + xi) * 4 + u] = a;
+}
+
+// The same with a 1-D grid (any size): a thread decodes its word index.
 __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
 {
     const int64_t total = (int64_t)p.chunks * p.Nimg * p.Cq * p.Dp * p.Hp * p.Xs * 4;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    // the first threads also write the table of activation offsets of the term groups
-    // gi = ((cq*Kd + kd)*Kh + kh)*chunks + chunk  ->  byte offset 16*(chunk*chunk_stride + ((cq*Dp + kd)*Hp + kh)*Xs)
-    if (idx < p.toff_entries) {
-        const int gi = (int)idx;
-        int32_t off = 0;
-        if (gi < p.groups) {
-            const int ch = gi % p.chunks, kh = (gi / p.chunks) % p.Kh, kd = (gi / (p.chunks * p.Kh)) % p.Kd;
-            const int cq = gi / (p.chunks * p.Kh * p.Kd);
-            off = (int32_t)(uint32_t)(16 * (ch * p.chunk_stride + (((int64_t)cq * p.Dp + kd) * p.Hp + kh) * p.Xs)); // < 2^32
-        }
-        p.toff[gi] = off;
-    }
+    if (idx < p.toff_entries) write_offset_entry(p, (int)idx);
     if (idx >= total) return;
     const int u = (int)(idx & 3); // channel inside the quad
     // fewer than 2^30 words in all (checked by the caller): 32-bit divisions
@@ -52,62 +147,17 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     const uint32_t ncq_all = (uint32_t)p.Nimg * (uint32_t)p.Cq;
     const int ch = (int)(t / ncq_all);
     const uint32_t ncq = t - (uint32_t)ch * ncq_all;
-    const int64_t n_img = ncq / (uint32_t)p.Cq;
+    const int n_img = (int)(ncq / (uint32_t)p.Cq);
     const int c_packed = (int)(ncq - (uint32_t)n_img * (uint32_t)p.Cq) * 4 + u;
-    if (c_packed >= p.C) { // channels that only fill the last quad
-        p.apk[idx] = 0;
-        return;
-    }
-    const int64_t nc = n_img * p.C + c_packed;
     const int h = hp - p.pad, d = dp - p.pad_d;
-    const bool inside = xi > 0 && h >= 0 && h < p.H && d >= 0 && d < p.D;
     uint32_t a = 0;
-    if (inside && p.x_format == kPackFromAcc) {
-        // fused epilogue of the producing layer (ReLU, shift, clamp, optional 2x2 max-pool); 2-D, one phase
-        const int32_t *src = p.acc + nc * p.acc_H * p.acc_W;
-        const int e0 = (xi - 1) * p.N - ch * p.Kp;
-        for (int j = 0; j < p.N; ++j) {
-            const int i = e0 + j;
-            if (i < 0 || i >= p.W) continue;
-            int32_t v;
-            if (p.pool) {
-                const int32_t *s0 = src + (int64_t)(2 * h) * p.acc_W + 2 * i;
-                v = max(max(s0[0], s0[1]), max(s0[p.acc_W], s0[p.acc_W + 1]));
-            } else {
-                v = src[(int64_t)h * p.acc_W + i];
-            }
-            v = min(max(v, 0) >> p.shift, p.qmax);
-            a += (uint32_t)v << (p.S * j);
-        }
-    } else if (inside) {
-        const int64_t n = nc / p.C;
-        const int c = (int)(nc - n * p.C);
-        const int csrc = c / p.phases, phase = c - csrc * p.phases;
-        const uint8_t *rowp =
-            static_cast<const uint8_t *>(p.x) + (((n * p.Csrc + csrc) * p.D + d) * p.H + h) * p.row_bytes;
-        const int e0 = (xi - 1) * p.N - ch * p.Kp;
-        for (int j = 0; j < p.N; ++j) {
-            const int i = e0 + j; // element of the packed row
-            if (i < 0 || i >= p.W) continue;
-            const int is = i * p.phases + phase - p.pad_w_mat; // source value
-            if (is < 0 || is >= p.Wsrc) continue;
-            int32_t v;
-            if (p.x_format == HIKONV_FMT_INT8) {
-                const uint8_t byte = rowp[is];
-                if (p.bipolar)
-                    v = (int8_t)byte > 0 ? 1 : -1;
-                else
-                    v = p.a_signed ? __builtin_amdgcn_sbfe((int)byte, 0, p.b) : (int)__builtin_amdgcn_ubfe(byte, 0, p.b);
-            } else {
-                const int bit = is * p.c;
-                const uint32_t w = reinterpret_cast<const uint32_t *>(rowp)[bit >> 5];
-                if (p.bipolar)
-                    v = ((w >> (bit & 31)) & 1u) ? 1 : -1;
-                else
-                    v = p.a_signed ? __builtin_amdgcn_sbfe((int)w, bit & 31, p.b) : (int)__builtin_amdgcn_ubfe(w, bit & 31, p.b);
-            }
-            a += (uint32_t)v << (p.S * j);
-        }
+    if (c_packed < p.C && xi > 0 && h >= 0 && h < p.H && d >= 0 && d < p.D) {
+        if (p.x_format == kPackFromAcc)
+            a = pack_act_word<kPackFromAcc>(p, ch, n_img, c_packed, d, h, xi);
+        else if (p.x_format == HIKONV_FMT_INT8)
+            a = pack_act_word<HIKONV_FMT_INT8>(p, ch, n_img, c_packed, d, h, xi);
+        else
+            a = pack_act_word<HIKONV_FMT_BITDENSE>(p, ch, n_img, c_packed, d, h, xi);
     }
     p.apk[idx] = a;
 }
@@ -345,6 +395,19 @@ inline hipError_t grid_1d(int64_t total, dim3 *g)
 
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
 {
+    const int64_t planes = (int64_t)a.chunks * a.Nimg * a.Cq * a.Dp;
+    if (planes <= 65535 && a.Hp <= 65535) { // the grid's y and z hold the rows and the planes
+        PackActArgs b = a;
+        b.rows_per_block = a.Xs * 4 >= 256 ? 1 : 256 / (a.Xs * 4);
+        dim3 g((unsigned)ceil_div((int64_t)a.Xs * 4, 256), (unsigned)ceil_div(a.Hp, b.rows_per_block), (unsigned)planes);
+        if (a.x_format == kPackFromAcc)
+            hipLaunchKernelGGL(k_pack_act_rows<kPackFromAcc>, g, dim3(256), 0, stream, b);
+        else if (a.x_format == HIKONV_FMT_INT8)
+            hipLaunchKernelGGL(k_pack_act_rows<HIKONV_FMT_INT8>, g, dim3(256), 0, stream, b);
+        else
+            hipLaunchKernelGGL(k_pack_act_rows<HIKONV_FMT_BITDENSE>, g, dim3(256), 0, stream, b);
+        return hipGetLastError();
+    }
     dim3 g;
     int64_t threads = (int64_t)a.chunks * a.Nimg * a.Cq * a.Dp * a.Hp * a.Xs * 4;
     if (threads < a.toff_entries) threads = a.toff_entries;

@@ -87,6 +87,7 @@ struct PackActArgs {
     int toff_entries, groups, Kh; // table entries, term groups (4 channels of a quad x one kernel row and chunk)
     int Cq;                  // channel quads: ceil(C / 4)
     int64_t chunk_stride;    // 16-byte cells between chunk planes of apk
+    int rows_per_block;      // k_pack_act_rows: packed rows per workgroup (set by the launcher)
 };
 hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream);
 
