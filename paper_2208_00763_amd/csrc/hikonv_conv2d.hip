@@ -23,16 +23,20 @@ namespace {
 // One packed word: chunk ch, image n_img, packed channel c_packed, source depth d and row h
 // (both inside the image), word xi > 0.  FMT: the source format (HIKONV_FMT_INT8,
 // HIKONV_FMT_BITDENSE or kPackFromAcc), fixed at compile time in the kernels below.
-template <int FMT>
+// NV: the plan's N when it is known at compile time (the loops unroll and the loads of a word
+// are issued together), 0 = read it from the arguments.
+template <int FMT, int NV>
 __device__ __forceinline__ uint32_t pack_act_word(const PackActArgs &p, int ch, int64_t n_img, int c_packed, int d, int h,
                                                   int xi)
 {
     uint32_t a = 0;
-    const int e0 = (xi - 1) * p.N - ch * p.Kp;
+    const int pN = NV ? NV : p.N;
+    const int e0 = (xi - 1) * pN - ch * p.Kp;
     if (FMT == kPackFromAcc) {
         // fused epilogue of the producing layer (ReLU, shift, clamp, optional 2x2 max-pool); 2-D, one phase
         const int32_t *src = p.acc + (n_img * p.C + c_packed) * p.acc_H * p.acc_W;
-        for (int j = 0; j < p.N; ++j) {
+#pragma unroll
+        for (int j = 0; j < pN; ++j) {
             const int i = e0 + j;
             if (i < 0 || i >= p.W) continue;
             int32_t v;
@@ -50,7 +54,8 @@ __device__ __forceinline__ uint32_t pack_act_word(const PackActArgs &p, int ch, 
     const int csrc = c_packed / p.phases, phase = c_packed - csrc * p.phases;
     const uint8_t *rowp =
         static_cast<const uint8_t *>(p.x) + (((n_img * p.Csrc + csrc) * p.D + d) * p.H + h) * p.row_bytes;
-    for (int j = 0; j < p.N; ++j) {
+#pragma unroll
+    for (int j = 0; j < pN; ++j) {
         const int i = e0 + j; // element of the packed row
         if (i < 0 || i >= p.W) continue;
         const int is = i * p.phases + phase - p.pad_w_mat; // source value
@@ -91,7 +96,7 @@ __device__ __forceinline__ void write_offset_entry(const PackActArgs &p, int gi)
 // One thread per word.  Grid: x over the 4*Xs words of a packed row (four channels of a quad
 // side by side), y = padded row hp (groups of rows_per_block rows when a row is shorter than a block), z = ((chunk*Nimg + n)*Cq + quad)*Dp + dp, so a thread finds
 // its coordinates without dividing; block (0,0,0) also writes the offset table.
-template <int FMT>
+template <int FMT, int NV>
 __global__ __launch_bounds__(256) void k_pack_act_rows(PackActArgs p)
 {
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
@@ -121,7 +126,7 @@ __global__ __launch_bounds__(256) void k_pack_act_rows(PackActArgs p)
     const int h = hp - p.pad, d = dp - p.pad_d;
     uint32_t a = 0;
     if (c_packed < p.C && xi > 0 && h >= 0 && h < p.H && d >= 0 && d < p.D)
-        a = pack_act_word<FMT>(p, ch, n_img, c_packed, d, h, xi);
+        a = pack_act_word<FMT, NV>(p, ch, n_img, c_packed, d, h, xi);
     p.apk[(((int64_t)blockIdx.z * p.Hp + hp) * p.Xs + xi) * 4 + u] = a;
 }
 
@@ -153,11 +158,11 @@ __global__ __launch_bounds__(256) void k_pack_act(PackActArgs p)
     uint32_t a = 0;
     if (c_packed < p.C && xi > 0 && h >= 0 && h < p.H && d >= 0 && d < p.D) {
         if (p.x_format == kPackFromAcc)
-            a = pack_act_word<kPackFromAcc>(p, ch, n_img, c_packed, d, h, xi);
+            a = pack_act_word<kPackFromAcc, 0>(p, ch, n_img, c_packed, d, h, xi);
         else if (p.x_format == HIKONV_FMT_INT8)
-            a = pack_act_word<HIKONV_FMT_INT8>(p, ch, n_img, c_packed, d, h, xi);
+            a = pack_act_word<HIKONV_FMT_INT8, 0>(p, ch, n_img, c_packed, d, h, xi);
         else
-            a = pack_act_word<HIKONV_FMT_BITDENSE>(p, ch, n_img, c_packed, d, h, xi);
+            a = pack_act_word<HIKONV_FMT_BITDENSE, 0>(p, ch, n_img, c_packed, d, h, xi);
     }
     p.apk[idx] = a;
 }
@@ -400,12 +405,22 @@ hipError_t launch_pack_act(const PackActArgs &a, hipStream_t stream)
         PackActArgs b = a;
         b.rows_per_block = a.Xs * 4 >= 256 ? 1 : 256 / (a.Xs * 4);
         dim3 g((unsigned)ceil_div((int64_t)a.Xs * 4, 256), (unsigned)ceil_div(a.Hp, b.rows_per_block), (unsigned)planes);
-        if (a.x_format == kPackFromAcc)
-            hipLaunchKernelGGL(k_pack_act_rows<kPackFromAcc>, g, dim3(256), 0, stream, b);
-        else if (a.x_format == HIKONV_FMT_INT8)
-            hipLaunchKernelGGL(k_pack_act_rows<HIKONV_FMT_INT8>, g, dim3(256), 0, stream, b);
-        else
-            hipLaunchKernelGGL(k_pack_act_rows<HIKONV_FMT_BITDENSE>, g, dim3(256), 0, stream, b);
+#define HIKONV_PACK(NV)                                                                              \
+    case NV:                                                                                         \
+        if (a.x_format == kPackFromAcc)                                                              \
+            hipLaunchKernelGGL((k_pack_act_rows<kPackFromAcc, NV>), g, dim3(256), 0, stream, b);          \
+        else if (a.x_format == HIKONV_FMT_INT8)                                                      \
+            hipLaunchKernelGGL((k_pack_act_rows<HIKONV_FMT_INT8, NV>), g, dim3(256), 0, stream, b);       \
+        else                                                                                         \
+            hipLaunchKernelGGL((k_pack_act_rows<HIKONV_FMT_BITDENSE, NV>), g, dim3(256), 0, stream, b);   \
+        break;
+        switch (a.N <= 8 ? a.N : 0) {
+            HIKONV_PACK(1) HIKONV_PACK(2) HIKONV_PACK(3) HIKONV_PACK(4) HIKONV_PACK(5) HIKONV_PACK(6) HIKONV_PACK(7)
+            HIKONV_PACK(8)
+        default:
+            HIKONV_PACK(0)
+        }
+#undef HIKONV_PACK
         return hipGetLastError();
     }
     dim3 g;
