@@ -148,11 +148,11 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
         }
         return word;
     };
-    auto store = [&](int64_t r, int64_t k, uint32_t word) {
-        const int64_t valid = p.out_len - k * PER; // values past the row's end are not output
-        if (valid < PER) word &= (1u << (uint32_t)(valid * C)) - 1u;
-        p.rq_out[r * p.rq_row_dwords + k] = word;
-    };
+    // Positions inside a row fit 32 bits (the launcher checks len * C < 2^31); only the row's
+    // base is a 64-bit quantity, and it is uniform.
+    const int out_len = (int)p.out_len, len = (int)p.len;
+    const int out_dwords = (int)row_out_dwords;
+    const int lead = p.shift_m - (TAPS - 1); // first element of the window of dword k: k*PER + lead
 
     // A lane's loads for one step: kUnroll + 2 dwords hold the windows of its kUnroll
     // consecutive output dwords (consecutive windows are 32 bits apart); ok = all of them lie
@@ -165,25 +165,34 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
     };
     for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
         const int64_t row_bit0 = r * p.row_stride_bits;
-        auto fetch = [&](int64_t k0) {
+        const uint32_t *row_dwords = p.x + (row_bit0 >> 5);     // the dword that holds the row's first bit
+        const uint32_t row_sh = (uint32_t)row_bit0 & 31u;       // and that bit's position in it
+        uint32_t *row_out = p.rq_out + r * p.rq_row_dwords;
+        // last bit offset (from row_dwords) at which the kUnroll + 2 dwords of a step still lie in the buffer
+        int64_t room = total_bits - (row_bit0 - row_sh) - 32 * (kUnroll + 2);
+        const int bit_limit = room < 0 ? -1 : (room > 0x7fffffff ? 0x7fffffff : (int)room);
+        auto store = [&](int k, uint32_t word) {
+            const int valid = out_len - k * PER; // values past the row's end are not output
+            if (valid < PER) word &= (1u << (uint32_t)(valid * C)) - 1u;
+            row_out[k] = word;
+        };
+        auto fetch = [&](int k0) {
             Fetch f;
-            // first element of the window of dword k: k*PER + shift_m - (TAPS-1)
-            const int64_t i_first = k0 * PER + p.shift_m - (TAPS - 1);
-            const int64_t bit = row_bit0 + i_first * C;
-            f.ok = k0 + kUnroll <= row_out_dwords && i_first >= 0 && i_first + kUnroll * PER + TAPS - 1 <= p.len &&
-                   bit + 32 * (kUnroll + 2) <= total_bits;
+            const int i_first = k0 * PER + lead;
+            const int bit = (int)row_sh + i_first * C; // offset from row_dwords (meaningful when i_first >= 0)
+            f.ok = k0 + kUnroll <= out_dwords && i_first >= 0 && i_first + kUnroll * PER + TAPS - 1 <= len && bit <= bit_limit;
             f.sh = (uint32_t)bit & 31u;
             f.lo = u32x4_dw{0, 0, 0, 0};
             f.hi = u32x2_dw{0, 0};
             if (f.ok) {
-                const uint32_t *wp = p.x + (bit >> 5);
+                const uint32_t *wp = row_dwords + (bit >> 5);
                 f.lo = *reinterpret_cast<const u32x4_dw *>(wp);
                 f.hi = *reinterpret_cast<const u32x2_dw *>(wp + 4);
             }
             return f;
         };
-        auto process = [&](int64_t k0, const Fetch &f) {
-            if (k0 >= row_out_dwords) return;
+        auto process = [&](int k0, const Fetch &f) {
+            if (k0 >= out_dwords) return;
             if (f.ok) {
                 const uint32_t w[kUnroll + 2] = {f.lo.x, f.lo.y, f.lo.z, f.lo.w, f.hi.x, f.hi.y};
                 uint32_t out[kUnroll];
@@ -193,13 +202,12 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
                         ((uint64_t)funnel_shr(w[q + 2], w[q + 1], f.sh) << 32) | funnel_shr(w[q + 1], w[q], f.sh);
                     out[q] = output_dword(win);
                 }
-                uint32_t *dst = p.rq_out + r * p.rq_row_dwords + k0;
-                if (k0 + kUnroll < row_out_dwords || p.out_len % PER == 0) { // no partial dword among these
+                if (k0 + kUnroll < out_dwords || out_len % PER == 0) { // no partial dword among these
                     const u32x4_dw v = {out[0], out[1], out[2], out[3]};
-                    *reinterpret_cast<u32x4_dw *>(dst) = v;
+                    *reinterpret_cast<u32x4_dw *>(row_out + k0) = v;
                 } else {
 #pragma unroll
-                    for (int q = 0; q < kUnroll; ++q) store(r, k0 + q, out[q]);
+                    for (int q = 0; q < kUnroll; ++q) store(k0 + q, out[q]);
                 }
                 return;
             }
@@ -207,18 +215,18 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
             // loads, with the elements outside the row cleared (zero extension of Eq. pad_f0)
 #pragma unroll 1
             for (int q = 0; q < kUnroll; ++q) {
-                const int64_t k = k0 + q;
-                if (k >= row_out_dwords) break;
-                const int64_t i0 = k * PER + p.shift_m - (TAPS - 1);
-                const int64_t wbit = row_bit0 + i0 * C; // negative only before the first row: floor shift, bits 0..31
+                const int k = k0 + q;
+                if (k >= out_dwords) break;
+                const int i0 = k * PER + lead;
+                const int64_t wbit = row_bit0 + (int64_t)i0 * C; // negative only before the first row: floor shift, bits 0..31
                 const int64_t d = wbit >> 5;
                 const uint32_t wsh = (uint32_t)wbit & 31u;
                 const uint32_t w0 = checked_dword(p.x, d, p.total_dwords, p.total_bytes);
                 const uint32_t w1 = checked_dword(p.x, d + 1, p.total_dwords, p.total_bytes);
                 const uint32_t w2 = checked_dword(p.x, d + 2, p.total_dwords, p.total_bytes);
                 uint64_t win = ((uint64_t)funnel_shr(w2, w1, wsh) << 32) | funnel_shr(w1, w0, wsh);
-                const int64_t lo = i0 < 0 ? -i0 : 0;
-                int64_t hi = p.len - i0;
+                const int lo = i0 < 0 ? -i0 : 0;
+                int hi = len - i0;
                 if (hi > PER + TAPS - 1) hi = PER + TAPS - 1;
                 if (hi <= lo) {
                     win = 0;
@@ -227,16 +235,16 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_aligned(Conv1dArgs p)
                     const uint64_t m_hi = hi_bits >= 64 ? ~0ull : ((1ull << hi_bits) - 1ull);
                     win &= m_hi & ~((1ull << lo_bits) - 1ull);
                 }
-                store(r, k, output_dword(win));
+                store(k, output_dword(win));
             }
         };
         // kSteps steps of 256 lanes x kUnroll dwords per workgroup; the loads of a step are in
-        // flight during the arithmetic of the step before
-        const int64_t k_first = ((int64_t)blockIdx.x * kSteps * 256 + threadIdx.x) * kUnroll;
+        // flight during the arithmetic of the step before (the launcher keeps the grid within 2^31 dwords)
+        const int k_first = (int)((blockIdx.x * (unsigned)(kSteps * 256) + threadIdx.x) * (unsigned)kUnroll);
         Fetch cur = fetch(k_first);
 #pragma unroll
         for (int it = 0; it < kSteps; ++it) {
-            const int64_t k0 = k_first + (int64_t)it * 256 * kUnroll;
+            const int k0 = k_first + it * 256 * kUnroll;
             Fetch nxt = cur;
             if (it + 1 < kSteps) nxt = fetch(k0 + 256 * kUnroll);
             process(k0, cur);
@@ -284,6 +292,7 @@ bool conv1d_requant_aligned_applicable(const Conv1dArgs &a, bool a_signed, int b
     if (a.c != a.rq_c_out || (a.c != 1 && a.c != 2 && a.c != 4 && a.c != 8)) return false;
     if (a.taps < 1 || a.taps > 7 || (32 / a.c + a.taps - 1) * a.c > 64) return false;
     if (a.b < 1 || a.b > a.c || bits_w < 1 || bits_w > 8) return false;
+    if ((a.len + (1 << 18)) * a.c >= (1LL << 31)) return false; // positions inside a row (and a grid's overhang) are 32-bit in the kernel
     const bool w_signed = a.w_signed != 0;
     // signed products go through the 24-bit multiplier: a packed word (two values 16 bits apart) must fit 24 bits signed
     if ((a_signed || w_signed) && a.b > 7) return false;
