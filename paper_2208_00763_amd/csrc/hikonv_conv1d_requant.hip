@@ -323,8 +323,10 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             const int32_t y = min(max(out[u], 0) >> rsh, qmax);
-            if (k * PER + u < p.out_len) word |= (uint32_t)y << (u * (32 / PER));
+            word |= (uint32_t)y << (u * (32 / PER));
         }
+        const int64_t valid = p.out_len - k * PER; // values past the row's end are not output
+        if (valid < PER) word &= (1u << (uint32_t)(valid * (32 / PER))) - 1u;
         p.rq_out[r * p.rq_row_dwords + k] = word;
     };
     auto accumulate = [&](int32_t (&out)[PER], int t, int32_t v) {
