@@ -217,10 +217,14 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
     if (threadIdx.x < p.taps)
         s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
     __syncthreads();
-    const int64_t nquads = (p.out_len + 3 + 3) / 4;
+    // positions inside a row are 32-bit quantities (the launcher checks (len + 2^18) * c < 2^31);
+    // only the row's base is 64-bit, and it is uniform
+    const int out_len = (int)p.out_len, len = (int)p.len;
+    const int nquads = (out_len + 3 + 3) / 4;
     const int64_t total_bits = p.total_bytes * 8;
     const int c = p.c, b = p.b;
     constexpr int taps = TAPS;
+    const int lead_in = p.shift_m - (taps - 1); // first element read for output o: o + lead_in
     int32_t gk[TAPS];
 #pragma unroll
     for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
@@ -230,22 +234,27 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
         // quad 0 sits `lead` quads into its line, so the lanes are shifted back by that much
         const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> 2) & 7);
         const int64_t row_bit0 = r * p.row_stride_bits;
+        const uint32_t *row_dwords = p.x + (row_bit0 >> 5); // the dword that holds the row's first bit
+        const int row_sh = (int)(row_bit0 & 31);            // and that bit's position in it
+        int64_t room = total_bits - (row_bit0 - row_sh) - (WIDE ? 160 : 128);
+        const int bit_limit = room < 0 ? -1 : (room > 0x7fffffff ? 0x7fffffff : (int)room);
         int32_t *yrow = p.y + r * p.out_len;
         // kUnpackedQuads quads per lane, kThreads quads apart; the window loads of all of them first
-        int64_t qv[kUnpackedQuads];
+        int qv[kUnpackedQuads];
         bool interior[kUnpackedQuads];
-        uint32_t w0[kUnpackedQuads], w1[kUnpackedQuads], w2[kUnpackedQuads], w3[kUnpackedQuads];
+        uint32_t w0[kUnpackedQuads], w1[kUnpackedQuads], w2[kUnpackedQuads], w3[kUnpackedQuads], shv[kUnpackedQuads];
 #pragma unroll
         for (int s = 0; s < kUnpackedQuads; ++s) {
-            qv[s] = ((int64_t)blockIdx.x * kUnpackedQuads + s) * kThreads + threadIdx.x - lead;
-            const int64_t o0 = 4 * qv[s] - a_off;              // first output of this lane's aligned quad
-            const int64_t i0 = o0 + p.shift_m - (taps - 1);     // first element it reads
-            const int64_t bit = row_bit0 + i0 * c;
-            interior[s] = qv[s] >= 0 && qv[s] < nquads && i0 >= 0 && i0 + taps + 3 <= p.len && o0 >= 0 &&
-                          o0 + 4 <= p.out_len && bit + (WIDE ? 160 : 128) <= total_bits;
+            qv[s] = (int)((blockIdx.x * (unsigned)kUnpackedQuads + s) * (unsigned)kThreads + threadIdx.x) - lead;
+            const int o0 = 4 * qv[s] - a_off;   // first output of this lane's aligned quad
+            const int i0 = o0 + lead_in;        // first element it reads
+            const int bit = row_sh + i0 * c;    // offset from row_dwords (meaningful when i0 >= 0)
+            interior[s] = qv[s] >= 0 && qv[s] < nquads && i0 >= 0 && i0 + taps + 3 <= len && o0 >= 0 && o0 + 4 <= out_len &&
+                          bit <= bit_limit;
             w0[s] = w1[s] = w2[s] = w3[s] = 0u;
+            shv[s] = (uint32_t)bit & 31u;
             if (interior[s]) {
-                const uint32_t *wp = p.x + (bit >> 5);
+                const uint32_t *wp = row_dwords + (bit >> 5);
                 w0[s] = wp[0];
                 w1[s] = wp[1];
                 w2[s] = wp[2];
@@ -254,13 +263,13 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
         }
 #pragma unroll
         for (int s = 0; s < kUnpackedQuads; ++s) {
-            const int64_t q = qv[s];
+            const int q = qv[s];
             if (q < 0 || q >= nquads) continue;
-            const int64_t o0 = 4 * q - a_off;
-            const int64_t i0 = o0 + p.shift_m - (taps - 1);
+            const int o0 = 4 * q - a_off;
+            const int i0 = o0 + lead_in;
             int32_t out[4] = {0, 0, 0, 0};
             if (interior[s]) {
-                const uint32_t sh = (uint32_t)(row_bit0 + i0 * c) & 31u;
+                const uint32_t sh = shv[s];
                 const uint64_t win = ((uint64_t)funnel_shr(w2[s], w1[s], sh) << 32) | funnel_shr(w1[s], w0[s], sh);
                 const uint32_t win_hi = WIDE ? funnel_shr(w3[s], w2[s], sh) : 0u; // bits 64..95 of the window
 #pragma unroll
@@ -276,10 +285,10 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
                 }
             } else {
                 for (int t = 0; t < taps + 3; ++t) {
-                    const int64_t i = i0 + t;
+                    const int i = i0 + t;
                     int32_t v = 0;
-                    if (i >= 0 && i < p.len) {
-                        const int64_t eb = row_bit0 + i * c;
+                    if (i >= 0 && i < len) {
+                        const int64_t eb = row_bit0 + (int64_t)i * c;
                         const uint32_t w = load_dword_safe(p.x, eb >> 5, p.total_dwords, p.total_bytes);
                         v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
                     }
@@ -290,13 +299,13 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
                     }
                 }
             }
-            if (o0 >= 0 && o0 + 4 <= p.out_len) {
+            if (o0 >= 0 && o0 + 4 <= out_len) {
                 typedef int32_t v4i __attribute__((ext_vector_type(4)));
                 const v4i v4 = {out[0], out[1], out[2], out[3]};
                 __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o0])); // streaming hint, whole lines per wave
             } else {
                 for (int u = 0; u < 4; ++u)
-                    if (o0 + u >= 0 && o0 + u < p.out_len) yrow[o0 + u] = out[u];
+                    if (o0 + u >= 0 && o0 + u < out_len) yrow[o0 + u] = out[u];
             }
         }
     }
@@ -339,7 +348,7 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
     const int64_t gx = ceil_div(nquads + 7, kThreads); // the streaming baseline shifts its lanes by up to 7 quads
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
-    if ((a.taps + 3) * a.c <= 96 && a.taps <= 7) {
+    if ((a.taps + 3) * a.c <= 96 && a.taps <= 7 && (a.len + (1 << 18)) * a.c < (1LL << 31)) {
         const bool wide_window = (a.taps + 3) * a.c > 64;
         g.x = (unsigned)ceil_div(nquads + 7, (int64_t)kThreads * kUnpackedQuads);
 #define HIKONV_UNP(T)                                                                               \
