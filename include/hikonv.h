@@ -35,6 +35,7 @@ extern "C" {
 #define HIKONV_EHIP (-4)         /* a HIP call failed; see hikonv_last_hip_error()                 */
 #define HIKONV_EWORKSPACE (-5)   /* workspace missing or too small                                 */
 #define HIKONV_EUNSUPPORTED (-6) /* valid request that this build has no kernel for                */
+#define HIKONV_ESCRATCH (-7)     /* hikonv_conv2d_noalloc: the layer needs more than HIKONV_NOALLOC_SCRATCH_BYTES */
 
 /* Use of the multiplier; selects the guard-bit rule (Section "Maximizing Processing Throughput"). */
 #define HIKONV_MODE_SINGLE 0 /* one multiply, F_{N,K}:           G_b = ceil(log2 min(K,N))  */
@@ -213,6 +214,27 @@ int hikonv_conv2d_prepacked(const hikonv_plan_t *plan, const void *x_dev, int x_
                             int H, int W, const void *w_packed_dev, int Co, int Kh, int Kw, int stride,
                             int pad, void *workspace_dev, size_t workspace_bytes, int32_t *y_dev,
                             void *stream);
+
+/*
+ * hikonv_conv2d_noalloc -- hikonv_conv2d for callers that cannot allocate device
+ * memory and have no workspace to hand over: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * error codes as hikonv_conv2d (raw weights w_dev, packed on every call) without
+ * the workspace: packed activations, term offsets and packed weights go to a fixed
+ * array of HIKONV_NOALLOC_SCRATCH_BYTES bytes that is part of the library's device
+ * code (each GPU the library runs on holds one copy until the process ends).  The
+ * call allocates and frees nothing and does not synchronise.
+ *   - x_format: HIKONV_FMT_INT8 or HIKONV_FMT_BITDENSE (HIKONV_FMT_PACKED: HIKONV_EINVAL).
+ *   - A layer whose hikonv_conv2d_workspace_bytes(..., prepacked = 0) exceeds
+ *     HIKONV_NOALLOC_SCRATCH_BYTES returns HIKONV_ESCRATCH; nothing is launched.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one GPU
+ *     (different streams, several host threads) race; calls on one stream are ordered.
+ *     The array keeps the last call's contents; every call writes all it reads.
+ */
+#define HIKONV_NOALLOC_SCRATCH_BYTES (8u << 20)
+int hikonv_conv2d_noalloc(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H,
+                          int W, const void *w_dev, int Co, int Kh, int Kw, int stride, int pad,
+                          int32_t *y_dev, void *stream);
 
 /*
  * Weight pre-packing for any layer form: Kd kernel depth slices (1 for a 2-D

@@ -10,7 +10,8 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("HIKONV_LIB", os.path.join(HERE, "libhikonv.so"))   # HIKONV_LIB: a tuning variant
 
-OK, EINVAL, EOVERFLOW, ENOPLAN, EHIP, EWORKSPACE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, EOVERFLOW, ENOPLAN, EHIP, EWORKSPACE, EUNSUPPORTED, ESCRATCH = 0, -1, -2, -3, -4, -5, -6, -7
+NOALLOC_SCRATCH_BYTES = 8 << 20
 MODE_SINGLE, MODE_CONV1D, MODE_DNN = 0, 1, 2
 A_SIGNED, W_SIGNED, BIPOLAR = 1, 2, 4
 FMT_INT8, FMT_BITDENSE, FMT_PACKED = 0, 1, 2
@@ -75,6 +76,7 @@ SIGNATURES = {
     "hikonv_conv2d_workspace_bytes": (_sz, [_pp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i]),
     "hikonv_conv2d": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
     "hikonv_conv2d_prepacked": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp, _vp]),
+    "hikonv_conv2d_noalloc": (_i, [_pp, _vp, _i, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
     "hikonv_conv2d_unpacked": (_i, [_i, _i, _i, _vp, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
     "hikonv_epilogue": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _i, _i, _vp, _vp]),
     "hikonv_epilogue_pack": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i, _pp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
@@ -216,6 +218,11 @@ def hikonv_conv2d(plan, x, x_format, n, c, h, w, weights, co, kh, kw, stride, pa
     _check(lib.hikonv_conv2d(C.byref(plan), _ptr(x), x_format, n, c, h, w, _ptr(weights), co, kh, kw, stride, pad,
                              _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(y),
                              _stream(stream)), "hikonv_conv2d")
+
+
+def hikonv_conv2d_noalloc(plan, x, x_format, n, c, h, w, weights, co, kh, kw, stride, pad, y, stream=None):
+    _check(lib.hikonv_conv2d_noalloc(C.byref(plan), _ptr(x), x_format, n, c, h, w, _ptr(weights), co, kh, kw, stride,
+                                     pad, _ptr(y), _stream(stream)), "hikonv_conv2d_noalloc")
 
 
 def hikonv_conv2d_prepacked(plan, x, x_format, n, c, h, w, packed, co, kh, kw, stride, pad, workspace, y,

@@ -1,5 +1,6 @@
 // extern "C" entry points of libhikonv.so: argument checks, workspace layout, launches.
 // No entry point allocates device memory or synchronises.
+#include <atomic>
 #include <cstdlib>
 
 #include "hikonv_launch.h"
@@ -570,6 +571,62 @@ extern "C" int hikonv_conv2d_prepacked(const hikonv_plan_t *plan, const void *x_
 {
     return layer_impl(plan, x_dev, x_format, N, C, 1, H, W, w_packed_dev, 1, Co, 1, Kh, Kw, stride, pad, 0,
                       workspace_dev, workspace_bytes, y_dev, stream);
+}
+
+// ---- layer call for callers that cannot allocate ------------------------------------
+//
+// The workspace of hikonv_conv2d (packed activation words, term-offset table, packed weight
+// words) lives in a fixed array in device memory instead of a caller buffer.  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the device
+// address is looked up once per device, with that device current, and only that address is
+// ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[HIKONV_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices]; // device address of `scratch` on each device (nullptr: not looked up yet)
+
+// device address of this device's copy of `scratch`; nullptr (and the HIP error recorded) on failure
+void *scratch_of_current_device()
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidDevice);
+        return nullptr;
+    }
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr) return ptr;
+    // two threads may both get here: the lookup has no side effect and both read the same address
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+        g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+
+} // namespace
+
+extern "C" int hikonv_conv2d_noalloc(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H,
+                                     int W, const void *w_dev, int Co, int Kh, int Kw, int stride, int pad,
+                                     int32_t *y_dev, void *stream)
+{
+    if (x_format == HIKONV_FMT_PACKED) return HIKONV_EINVAL; // nobody else can have filled the library's own array
+    Conv2dGeom g;
+    int rc = conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, stride, pad, &g);
+    if (rc != HIKONV_OK) return rc;
+    if (g.apk_bytes + g.toff_bytes + g.wp_bytes > (size_t)HIKONV_NOALLOC_SCRATCH_BYTES) return HIKONV_ESCRATCH;
+    void *ptr = scratch_of_current_device();
+    if (!ptr) return HIKONV_EHIP;
+    // Every word of the array that the layer kernels read is written by this call's own packing
+    // kernels first (zero words, padding rows and the tail of the offset table included), so
+    // nothing has to be cleared between calls; all of it is ordered on `stream`.
+    return layer_impl(plan, x_dev, x_format, N, C, 1, H, W, w_dev, 0, Co, 1, Kh, Kw, stride, pad, 0, ptr,
+                      (size_t)HIKONV_NOALLOC_SCRATCH_BYTES, y_dev, stream);
 }
 
 extern "C" size_t hikonv_conv3d_workspace_bytes(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int Co,

@@ -338,6 +338,7 @@ extern "C" const char *hikonv_strerror(int code)
     case HIKONV_EHIP: return "HIP runtime error";
     case HIKONV_EWORKSPACE: return "workspace missing, misaligned or too small";
     case HIKONV_EUNSUPPORTED: return "request not supported by this build";
+    case HIKONV_ESCRATCH: return "layer needs more than the library's fixed scratch array (hikonv_conv2d_noalloc)";
     default: return "unknown error";
     }
 }
