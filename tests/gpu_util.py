@@ -14,6 +14,33 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(a).cuda()
 
 
+GUARD_BYTES = 256         # untouched-guard region on each side of a buffer the library writes
+GUARD_I32 = -77777
+
+
+class Guarded:
+    """An output buffer of `count` elements with untouched-guard regions before and after it.
+
+    `view` is what the library gets (it starts 256 bytes + `offset` elements into the
+    allocation, so its alignment is 256 bytes plus `offset` elements); `result()` checks
+    that neither guard region was written and returns the payload as numpy."""
+
+    def __init__(self, count, dtype=torch.int32, fill=GUARD_I32, offset=0):
+        guard = GUARD_BYTES // torch.empty(0, dtype=dtype).element_size()
+        self.count, self.fill, self.front = int(count), fill, guard + offset
+        self.buf = torch.full((self.front + self.count + guard,), fill, dtype=dtype, device="cuda")
+        self.view = self.buf[self.front:self.front + self.count]
+
+    def check(self):
+        assert bool((self.buf[:self.front] == self.fill).all()), "wrote before the start of the output"
+        assert bool((self.buf[self.front + self.count:] == self.fill).all()), "wrote past the end of the output"
+
+    def result(self):
+        torch.cuda.synchronize()
+        self.check()
+        return self.view.cpu().numpy()
+
+
 def conv1d_plan(bits, a_signed, w_signed, taps, tight=0, bits_w=None):
     return hk.hikonv_plan_ex(bits_a=bits, bits_w=bits_w or bits, a_signed=int(a_signed), w_signed=int(w_signed),
                              L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=taps, tight=tight)
@@ -23,16 +50,21 @@ def compact(x_np: np.ndarray, bits: int, bipolar=False) -> torch.Tensor:
     """[rows][len] bytes -> bit-dense rows on the device, through hikonv_compact."""
     rows, length = x_np.shape
     row_bytes = hk.hikonv_bitdense_row_bytes(length, bits)
-    out = torch.zeros(rows * row_bytes + 16, dtype=torch.uint8, device="cuda")
-    hk.hikonv_compact(dev(x_np), rows, length, bits, bipolar, out)
-    return out
+    out = Guarded(rows * row_bytes, torch.uint8, 0xA5)       # sized exactly: nothing behind the last row
+    hk.hikonv_compact(dev(x_np), rows, length, bits, bipolar, out.view)
+    torch.cuda.synchronize()
+    out.check()
+    return out.view
 
 
-def run_conv1d(x_np, g_np, bits, a_signed, w_signed, mode, fmt, packed=True, plan=None):
+def run_conv1d(x_np, g_np, bits, a_signed, w_signed, mode, fmt, packed=True, plan=None, y_offset=0):
+    """y_offset: int32 elements by which the output pointer is moved off its 256-byte alignment
+    (a multiple of 4: the entry points ask for 16-byte alignment)."""
     rows, length = x_np.shape
     taps = g_np.shape[0]
     out_len = length + taps - 1 if mode == hk.OUT_FULL else max(length - taps + 1, 0)
-    y = torch.full((rows * out_len + 8,), -77777, dtype=torch.int32, device="cuda")
+    out = Guarded(rows * out_len, offset=y_offset)
+    y = out.view
     x_d = compact(x_np, bits) if fmt == hk.FMT_BITDENSE else dev(x_np)
     g_d = dev(g_np)
     if packed:
@@ -41,10 +73,7 @@ def run_conv1d(x_np, g_np, bits, a_signed, w_signed, mode, fmt, packed=True, pla
     else:
         hk.hikonv_conv1d_unpacked(bits, bits, hk.signedness(a_signed, w_signed), x_d, fmt, rows, length, g_d, taps,
                                   mode, y)
-    torch.cuda.synchronize()
-    res = y.cpu().numpy()
-    assert (res[rows * out_len:] == -77777).all(), "wrote past the end of the output"
-    return res[:rows * out_len].reshape(rows, out_len)
+    return out.result().reshape(rows, out_len)
 
 
 def oracle_conv1d(x_np, g_np, mode):
@@ -62,7 +91,8 @@ def run_conv2d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
     n, c, h, w = x_np.shape
     co, _, kh, kw = w_np.shape
     ho, wo = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad - kw) // stride + 1
-    y = torch.full((n * co * ho * wo + 8,), -77777, dtype=torch.int32, device="cuda")
+    out = Guarded(n * co * ho * wo)
+    y = out.view
     if fmt == hk.FMT_BITDENSE:
         x_d = compact(x_np.reshape(n * c * h, w), plan.bits_a, bool(plan.bipolar))
     else:
@@ -70,18 +100,20 @@ def run_conv2d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
     w_d = dev(w_np)
     ws_bytes = hk.hikonv_conv2d_workspace_bytes(plan, n, c, h, w, co, kh, kw, stride, pad, prepacked)
     assert ws_bytes > 0
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    wsg = Guarded(ws_bytes, torch.uint8, 0x5A)
+    ws = wsg.view
     if prepacked:
-        pw = torch.empty(hk.hikonv_packed_weights_bytes_ex(plan, co, c, 1, kh, kw, stride), dtype=torch.uint8,
-                         device="cuda")
+        pwg = Guarded(hk.hikonv_packed_weights_bytes_ex(plan, co, c, 1, kh, kw, stride), torch.uint8, 0x5A)
+        pw = pwg.view
         hk.hikonv_pack_weights_ex(plan, w_d, co, c, 1, kh, kw, stride, pw)
         hk.hikonv_conv2d_prepacked(plan, x_d, fmt, n, c, h, w, pw, co, kh, kw, stride, pad, ws, y)
+        torch.cuda.synchronize()
+        pwg.check()
     else:
         hk.hikonv_conv2d(plan, x_d, fmt, n, c, h, w, w_d, co, kh, kw, stride, pad, ws, y)
-    torch.cuda.synchronize()
-    res = y.cpu().numpy()
-    assert (res[n * co * ho * wo:] == -77777).all(), "wrote past the end of the output"
-    return res[:n * co * ho * wo].reshape(n, co, ho, wo)
+    res = out.result()
+    wsg.check()
+    return res.reshape(n, co, ho, wo)
 
 
 def run_conv3d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
@@ -90,20 +122,23 @@ def run_conv3d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
     do, ho, wo = ((d + 2 * pad - kd) // stride + 1, (h + 2 * pad - kh) // stride + 1,
                   (w + 2 * pad - kw) // stride + 1)
     count = n * co * do * ho * wo
-    y = torch.full((count + 8,), -77777, dtype=torch.int32, device="cuda")
+    out = Guarded(count)
+    y = out.view
     x_d = compact(x_np.reshape(n * c * d * h, w), plan.bits_a, bool(plan.bipolar)) if fmt == hk.FMT_BITDENSE else dev(x_np)
     w_d = dev(w_np)
     ws_bytes = hk.hikonv_conv3d_workspace_bytes(plan, n, c, d, h, w, co, kd, kh, kw, stride, pad, prepacked)
     assert ws_bytes > 0
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    wsg = Guarded(ws_bytes, torch.uint8, 0x5A)
+    ws = wsg.view
     if prepacked:
-        pw = torch.empty(hk.hikonv_packed_weights_bytes_ex(plan, co, c, kd, kh, kw, stride), dtype=torch.uint8,
-                         device="cuda")
+        pwg = Guarded(hk.hikonv_packed_weights_bytes_ex(plan, co, c, kd, kh, kw, stride), torch.uint8, 0x5A)
+        pw = pwg.view
         hk.hikonv_pack_weights_ex(plan, w_d, co, c, kd, kh, kw, stride, pw)
         hk.hikonv_conv3d(plan, x_d, fmt, n, c, d, h, w, pw, True, co, kd, kh, kw, stride, pad, ws, y)
+        torch.cuda.synchronize()
+        pwg.check()
     else:
         hk.hikonv_conv3d(plan, x_d, fmt, n, c, d, h, w, w_d, False, co, kd, kh, kw, stride, pad, ws, y)
-    torch.cuda.synchronize()
-    res = y.cpu().numpy()
-    assert (res[count:] == -77777).all(), "wrote past the end of the output"
-    return res[:count].reshape(n, co, do, ho, wo)
+    res = out.result()
+    wsg.check()
+    return res.reshape(n, co, do, ho, wo)

@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2208_00763_amd as hk
-    from gpu_util import run_conv1d, oracle_conv1d, conv1d_plan, dev
+    from gpu_util import run_conv1d, oracle_conv1d, conv1d_plan, dev, compact, Guarded, GUARD_I32
 
 SIGNS = [(False, False), (True, True), (False, True), (True, False)]
 
@@ -112,40 +112,70 @@ def test_conv1d_empty_and_error_paths():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("bits", [1, 4, 8])
-def test_conv1d_full_size_all_rows(bits):
-    """4096 x 65536, K = 3, unsigned: every output compared (the bench launch configuration)."""
-    x, g = wl.conv1d_case(bits, False, 3, 4096, 65536)
-    plan = conv1d_plan(bits, False, False, 3)
-    x_d = torch.zeros(4096 * hk.hikonv_bitdense_row_bytes(65536, bits), dtype=torch.uint8, device="cuda")
-    hk.hikonv_compact(dev(x), 4096, 65536, bits, False, x_d)
-    y = torch.empty(4096 * 65534, dtype=torch.int32, device="cuda")
-    hk.hikonv_conv1d(plan, x_d, hk.FMT_BITDENSE, 4096, 65536, dev(g), 3, hk.OUT_VALID, y)
-    torch.cuda.synchronize()
-    ref = oracle_conv1d(x, g, hk.OUT_VALID)
-    assert np.array_equal(y.cpu().numpy().reshape(4096, 65534), ref)
+def _first_mismatch(got_d, ref_d, out_len):
+    bad = torch.nonzero(got_d != ref_d)[0].item()
+    return "row %d, output %d: got %d, oracle %d" % (bad // out_len, bad % out_len, got_d[bad].item(), ref_d[bad].item())
 
 
-def test_conv1d_full_size_sweep_sampled_rows():
-    """All 48 cases of the sweep at 4096 x 65536; 24 sampled rows of each compared in full."""
-    rng = np.random.default_rng(7)
-    for bits in range(1, 9):
-        for signed in (False, True):
-            x = wl.uniform_values(wl.rng_for("c2x", bits, signed), (4096, 65536), bits, signed)
-            x_d = torch.zeros(4096 * hk.hikonv_bitdense_row_bytes(65536, bits), dtype=torch.uint8, device="cuda")
-            hk.hikonv_compact(dev(x), 4096, 65536, bits, False, x_d)
-            rows = np.unique(np.concatenate([[0, 1, 4095], rng.integers(0, 4096, size=21)]))
-            for taps in (3, 5, 7):
-                g = wl.uniform_values(wl.rng_for("c2g", bits, signed, taps), (taps,), bits, signed)
-                plan = conv1d_plan(bits, signed, signed, taps)
-                out_len = 65536 - taps + 1
-                y = torch.empty(4096 * out_len, dtype=torch.int32, device="cuda")
-                hk.hikonv_conv1d(plan, x_d, hk.FMT_BITDENSE, 4096, 65536, dev(g), taps, hk.OUT_VALID, y)
-                torch.cuda.synchronize()
-                got = y.view(4096, out_len)[torch.from_numpy(rows).cuda()].cpu().numpy()
-                ref = oracle_conv1d(x[rows], g, hk.OUT_VALID)
-                assert np.array_equal(got, ref), (bits, signed, taps)
-                del y
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("bits", range(1, 9))
+def test_conv1d_full_size_sweep_all_rows(bits, signed):
+    """All 48 cases of the sweep at 4096 x 65536 in the launch configuration the benchmark times
+    (bit-dense input, valid outputs, 256-byte aligned y): every one of the 4096 x out_len
+    outputs of the packed kernel, and of the unpacked baseline, is compared with the oracle's
+    (on the device, so that no second copy of the outputs crosses to the host)."""
+    rows, length = 4096, 65536
+    x = wl.uniform_values(wl.rng_for("c2x", bits, signed), (rows, length), bits, signed)
+    x_d = compact(x, bits)
+    for taps in (3, 5, 7):
+        g = wl.uniform_values(wl.rng_for("c2g", bits, signed, taps), (taps,), bits, signed)
+        plan = conv1d_plan(bits, signed, signed, taps)
+        out_len = length - taps + 1
+        ref_d = torch.from_numpy(oracle_conv1d(x, g, hk.OUT_VALID)).cuda().view(-1)
+        out = Guarded(rows * out_len)
+        hk.hikonv_conv1d(plan, x_d, hk.FMT_BITDENSE, rows, length, dev(g), taps, hk.OUT_VALID, out.view)
+        torch.cuda.synchronize()
+        out.check()
+        assert torch.equal(out.view, ref_d), (bits, signed, taps, _first_mismatch(out.view, ref_d, out_len))
+        out.view.fill_(GUARD_I32)
+        hk.hikonv_conv1d_unpacked(bits, bits, hk.signedness(signed, signed), x_d, hk.FMT_BITDENSE, rows, length,
+                                  dev(g), taps, hk.OUT_VALID, out.view)
+        torch.cuda.synchronize()
+        out.check()
+        assert torch.equal(out.view, ref_d), ("unpacked", bits, signed, taps, _first_mismatch(out.view, ref_d, out_len))
+        del out, ref_d
+
+
+def _phase_plans():
+    """One plan of every form of the streaming kernel: single B word (N = 11, 6, 3), taps cut into
+    chunks of N taps whose delayed words come from the preceding lanes (2, 3 and 4 chunks), and
+    chunks cut out of one 64-bit window."""
+    return [(1, False, 3), (2, False, 3), (4, False, 3), (4, True, 3),     # one B word: N = 11, 6, 3
+            (8, False, 3), (8, True, 7), (6, True, 7),                      # K = N chunks shared through the lanes
+            (3, False, 5), (2, True, 7), (5, False, 7)]                     # other chunked plans
+
+
+@pytest.mark.parametrize("bits,signed,taps", _phase_plans() if torch.cuda.is_available() else [])
+def test_conv1d_every_store_phase(bits, signed, taps):
+    """The streaming kernel cuts a row's outputs into runs whose ends fall on 128-byte lines of y;
+    where they fall depends on (address of y / 4 + row * out_len) mod 32.  Walk every reachable
+    value: y moved off its alignment by 0, 4, ..., 28 outputs, out_len mod 32 over 0..31, five
+    rows of several runs each; guard regions on both sides of y."""
+    plan = conv1d_plan(bits, signed, signed, taps)
+    seen = set()
+    for extra in range(32):
+        length = 3 * 1536 + 7 + extra                                # three to four runs per row
+        x = wl.uniform_values(wl.rng_for("ph", bits, signed, taps, extra), (5, length), bits, signed)
+        g = wl.uniform_values(wl.rng_for("phg", bits, signed, taps), (taps,), bits, signed)
+        for mode in (hk.OUT_VALID, hk.OUT_FULL):
+            ref = oracle_conv1d(x, g, mode)
+            for y_offset in range(0, 32, 4):
+                got = run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_BITDENSE, plan=plan, y_offset=y_offset)
+                assert np.array_equal(got, ref), (bits, signed, taps, length, mode, y_offset)
+                seen.update((y_offset + r * ref.shape[1]) % 32 for r in range(5))
+            got = run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_BITDENSE, packed=False, y_offset=4 * (extra % 8))
+            assert np.array_equal(got, ref), ("unpacked", bits, signed, taps, length, mode)
+    assert seen == set(range(32))
 
 
 def test_conv1d_many_short_rows_and_one_long_row():
