@@ -4,10 +4,13 @@
 A step is one pass of the packed 1-D convolution path (load of bit-dense inputs, packing,
 one wide multiply per block, lane exchange, split, int32 store) over one batch of the
 bitwidth sweep: 4096 independent rows of 65536 values, K = 3 taps, 4-bit unsigned, valid
-outputs.  Inputs are resident in HBM before the timed region.  The JSON line also carries
-the 1-bit and 8-bit cases, the unpacked one-product-per-multiply GPU kernel on the same
-inputs, the two DNN-layer configurations (ALU-bound), the roofline of the dominant kernel
-and the CPU oracle timed on a bounded sample.
+outputs.  Inputs are resident in HBM before the timed region.  The JSON line also carries,
+at its top level, the 1-bit and 8-bit cases with the unpacked one-product-per-multiply GPU
+kernel timed on the same inputs in the same way (every kernel warmed, equal repetition
+counts, interleaved rounds), the roofline of the dominant kernel, the VALU-integer roofline
+of the binarised layer, and the CPU oracle timed on a bounded sample; `extras` holds the
+requantising path, both DNN-layer configurations, the widened layers and the complete CNN
+(packed and unpacked chains).
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras]
 """
@@ -36,6 +39,30 @@ def event_ms(fn, reps):
     end.record()
     torch.cuda.synchronize()
     return start.elapsed_time(end) / reps
+
+
+def timed_pair(fn_a, fn_b, reps, rounds=3):
+    """Milliseconds per call of two kernels measured the same way: both warmed with three
+    launches, then `rounds` interleaved rounds of `reps` launches each; the mean over rounds."""
+    event_ms(fn_a, 3)
+    event_ms(fn_b, 3)
+    ta, tb = [], []
+    for _ in range(rounds):
+        ta.append(event_ms(fn_a, reps))
+        tb.append(event_ms(fn_b, reps))
+    return sum(ta) / rounds, sum(tb) / rounds
+
+
+def read_profile_json(name):
+    """A figure that needs a profiler run (HBM byte counters, SQ counters) comes from the summary
+    committed under profiles/, with its source named; None when the file is not there."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        data = json.load(fh)
+    data["source"] = "profiles/" + name
+    return data
 
 
 def conv1d_case(hk, wl, bits, signed, taps=TAPS):
@@ -117,37 +144,36 @@ def requant_extra(hk, wl, steps):
     for bits, signed in ((4, False), (1, False), (2, False), (4, True)):
         case = conv1d_case(hk, wl, bits, signed)
         x_bd, g_d = case["keep"]
-        plan, out_len = case["plan"], case["out_len"]
+        out_len = case["out_len"]
         row_bytes = hk.hikonv_bitdense_row_bytes(out_len, bits)
         q = torch.empty(ROWS * row_bytes, dtype=torch.uint8, device="cuda")
         shift, qmax = max(0, 2 * bits - 3), (1 << bits) - 1 if bits < 8 else 127
 
-        def packed():
-            hk.hikonv_conv1d_requant(plan, x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d, TAPS, hk.OUT_VALID, shift, qmax,
-                                     bits, q)
+        # the plan of the measured-cost objective (container-aligned slices here) against
+        # Algorithm 1's plan (most operations per multiply), both through the same entry point
+        kw = dict(bits_a=bits, bits_w=bits, a_signed=int(signed), w_signed=int(signed), L_A=32, L_B=32, L_acc=64,
+                  mode=hk.MODE_CONV1D, taps=TAPS, out_bits=bits)
+        plan_cost = hk.hikonv_plan_ex(objective=hk.OBJ_MEASURED_COST, **kw)
+        plan_paper = hk.hikonv_plan_ex(objective=hk.OBJ_PAPER_OPS, **kw)
+
+        def run_with(p):
+            return lambda: hk.hikonv_conv1d_requant(p, x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d, TAPS, hk.OUT_VALID,
+                                                    shift, qmax, bits, q)
 
         def unpacked():
             hk.hikonv_conv1d_requant_unpacked(bits, bits, hk.signedness(signed, signed), x_bd, hk.FMT_BITDENSE, ROWS,
                                               LENGTH, g_d, TAPS, hk.OUT_VALID, shift, qmax, bits, q)
 
-        event_ms(packed, 3)
-        ms_p = event_ms(packed, steps)
-        # the same call with the plan's own N, K, S instead of the container-aligned slices
-        # (K = 1, N = 2, S = 16) that the library takes here by itself
-        os.environ["HIKONV_REQUANT_KERNEL"] = "1"
-        try:
-            event_ms(packed, 3)
-            ms_plan = event_ms(packed, steps)
-        finally:
-            del os.environ["HIKONV_REQUANT_KERNEL"]
-        event_ms(unpacked, 3)
-        ms_u = event_ms(unpacked, steps)
+        ms_p, ms_u = timed_pair(run_with(plan_cost), unpacked, steps)
+        ms_plan, _ = timed_pair(run_with(plan_paper), unpacked, steps, rounds=1)
+        plan = plan_cost
         algo = ROWS * (row_bytes + hk.hikonv_bitdense_row_bytes(LENGTH, bits)) + TAPS
         report["%d%s" % (bits, "s" if signed else "u")] = dict(
             ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=algo / ms_p / 1e6, unpacked_ms=ms_u,
-            frac_of_unpacked_valu_peak=case["macs"] / (ms_p * 1e-3) / VALU_LANE_RATE,
-            slices="container-aligned: N=2, K=1, S=16", plan_slices_ms=ms_plan,
-            plan=dict(N=plan.N, K=plan.K, S=plan.S))
+            vs_unpacked=ms_u / ms_p, frac_of_unpacked_valu_peak=case["macs"] / (ms_p * 1e-3) / VALU_LANE_RATE,
+            plan=dict(N=plan.N, K=plan.K, S=plan.S, stride_elems=plan.stride_elems, cost_milli=plan.cost_milli),
+            paper_plan=dict(N=plan_paper.N, K=plan_paper.K, S=plan_paper.S, cost_milli=plan_paper.cost_milli,
+                            ms=ms_plan))
         del case, q
         torch.cuda.empty_cache()
     return report
@@ -174,9 +200,7 @@ def conv2d_extra(hk, wl, name, steps):
     for label, width, acc, tight in (("wide32", 32, 64, 0), ("wide32_tight", 32, 64, 1), ("narrow24", 24, 32, 0)):
         try:
             plan = hk.hikonv_plan_ex(L_A=width, L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=0, taps=kw, tight=tight,
-                                     **plan_kw)
-            if plan.N > 8:
-                raise hk.HikonvError(hk.EUNSUPPORTED, "plan")
+                                     max_N=hk.LAYER_MAX_N, **plan_kw)
         except hk.HikonvError:
             continue
         ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, n, c, h, wd, co, kh, kw, 1, 1, True), dtype=torch.uint8,
@@ -217,7 +241,8 @@ def widened_extras(hk, steps):
     import torch
     rng = np.random.default_rng(2208)
     out = {}
-    kw_plan = dict(bits_a=4, bits_w=4, a_signed=1, w_signed=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0)
+    kw_plan = dict(bits_a=4, bits_w=4, a_signed=1, w_signed=1, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0,
+                   max_N=hk.LAYER_MAX_N)
 
     n, c, h, w, co = 8, 64, 56, 56, 128
     x_d = torch.from_numpy(rng.integers(-8, 8, (n, c, h, w), dtype=np.int8).view("uint8")).cuda()
@@ -247,7 +272,8 @@ def widened_extras(hk, steps):
     wb = (rng.integers(0, 2, (co, c, 3, 3), dtype=np.int8) * 2 - 1).astype(np.int8)
     x_d = torch.from_numpy(xb.view("uint8")).cuda()
     w_d = torch.from_numpy(wb.view("uint8")).cuda()
-    plan = hk.hikonv_plan_ex(L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3, bits_a=1, bits_w=1, bipolar=1)
+    plan = hk.hikonv_plan_ex(L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3, bits_a=1, bits_w=1, bipolar=1,
+                             max_N=hk.LAYER_MAX_N)
     ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, n, c, h, w, co, 3, 3, 1, 1, True), dtype=torch.uint8,
                      device="cuda")
     pw = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, 3, 3), dtype=torch.uint8, device="cuda")
@@ -290,7 +316,7 @@ def small_extras(hk, wl, steps):
     """Latency-scale configurations: the 4096-value 1-D case and the nine-layer 4-bit CNN forward
     (eager launches and the same launches replayed from a captured HIP graph)."""
     import torch
-    from paper_2208_00763_amd.cnn import PackedCnn
+    from paper_2208_00763_amd.cnn import PackedCnn, UnpackedCnn
     out = {}
     x, g = wl.config1()
     plan = hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3)
@@ -327,6 +353,16 @@ def small_extras(hk, wl, steps):
     fwd_plain = lambda: plain.forward(x5, 1, 160, 320, shifts)
     g5p = graph_replay_ms(fwd_plain, 1, steps)
     out["cnn_c5_unfused_graph_us"] = g5p * 1e3 if g5p else None
+    # the same network on the baseline kernels (one multiply per product; activations one value per byte)
+    base = UnpackedCnn([torch.from_numpy(w.view("uint8")).cuda() for w in weights], specs)
+    x5b = torch.from_numpy(xi).cuda()
+    fwd_base = lambda: base.forward(x5b, 1, 160, 320, shifts)
+    event_ms(fwd_base, 3)
+    out["cnn_c5_unpacked_eager_us"] = event_ms(fwd_base, steps) * 1e3
+    g5u = graph_replay_ms(fwd_base, 1, steps)
+    out["cnn_c5_unpacked_graph_us"] = g5u * 1e3 if g5u else None
+    if g5 and g5u:
+        out["cnn_c5_packed_vs_unpacked_graph"] = g5u / g5
     return out
 
 
@@ -340,10 +376,7 @@ def sweep(hk, wl, steps):
         for signed in (False, True):
             for taps in (3, 5, 7):
                 case = conv1d_case(hk, wl, bits, signed, taps)
-                event_ms(case["packed"], 2)
-                ms_p = min(event_ms(case["packed"], steps) for _ in range(2))
-                event_ms(case["unpacked"], 2)
-                ms_u = min(event_ms(case["unpacked"], steps) for _ in range(2))
+                ms_p, ms_u = timed_pair(case["packed"], case["unpacked"], steps, rounds=2)
                 plan = case["plan"]
                 rows.append(dict(bits=bits, signed=signed, taps=taps, N=plan.N, K=plan.K, S=plan.S, chunks=plan.chunks,
                                  packed_ms=ms_p, unpacked_ms=ms_u, gops=2 * case["macs"] / ms_p / 1e6,
@@ -428,7 +461,7 @@ def main():
         del cal
 
     head = conv1d_case(hk, wl, 4, False)
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 0)):
         head["packed"]()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -437,50 +470,76 @@ def main():
     gops = 2 * head["macs"] / (ms_kernel * 1e-3) / 1e9
     achieved_gbs = head["bytes"] / (ms_kernel * 1e-3) / 1e9
 
-    traffic = None
-    traffic_file = os.path.join(ROOT, "profiles", "conv1d_packed_c2_b4u_k3_traffic.json")
-    if os.path.exists(traffic_file):
-        with open(traffic_file) as fh:
-            traffic = json.load(fh).get("hbm_bytes_per_launch")
+    traffic = read_profile_json("conv1d_packed_c2_b4u_k3_traffic.json")
+    reps = max(3, args.steps // 5)
 
+    def case_report(case, ms_p, ms_u):
+        plan = case["plan"]
+        return dict(ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=case["bytes"] / ms_p / 1e6,
+                    hbm_frac=case["bytes"] / ms_p / 1e6 / HBM_PEAK_GBS, unpacked_ms=ms_u,
+                    unpacked_gops=2 * case["macs"] / ms_u / 1e6, vs_unpacked=ms_u / ms_p,
+                    plan=dict(N=plan.N, K=plan.K, S=plan.S, chunks=plan.chunks))
+
+    # the metric's three widths, packed and unpacked timed the same way on the same inputs
+    ms_p, ms_u = timed_pair(head["packed"], head["unpacked"], reps)
+    by_bits = {"4u": case_report(head, ms_p, ms_u)}
+    x_keep, g_keep = head["x"], head["g"]
+    for key in ("packed", "unpacked", "y", "keep"):
+        head.pop(key)
+    torch.cuda.empty_cache()
+    cases = [(1, False), (8, False)] + ([] if args.no_extras else [(2, False), (4, True), (1, True), (8, True)])
+    for bits, signed in cases:
+        case = conv1d_case(hk, wl, bits, signed)
+        ms_p, ms_u = timed_pair(case["packed"], case["unpacked"], reps)
+        by_bits["%d%s" % (bits, "s" if signed else "u")] = case_report(case, ms_p, ms_u)
+        del case
+        torch.cuda.empty_cache()
+
+    low = [k for k in by_bits if int(k[0]) <= 4]
+    misses = {k: round(by_bits[k]["vs_unpacked"], 3) for k in low if by_bits[k]["vs_unpacked"] < 1.0}
     line = {
-        "metric": "effective low-bit MACs/s (GOPS) at 4-bit, packed 1-D convolution",
+        "metric": "effective low-bit MACs/s (GOPS) at 1/4/8-bit; % of VALU-int roofline",
         "value": gops, "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_kernel, "wall_ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "1-D sweep case: 4096 rows x 65536, K=3, 4-bit unsigned, valid, bit-dense input",
+        "config": {"workload": "1-D sweep case: 4096 rows x 65536, K=3, 4-bit unsigned, valid, bit-dense input; "
+                               "value = the 4-bit case; by_bits holds 1/4/8-bit",
                    "plan": {k: getattr(head["plan"], k) for k in ("N", "K", "S", "G_b", "chunks")}},
         "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved_gbs / HBM_PEAK_GBS,
+                     "traffic": traffic.get("hbm_bytes_per_launch") if traffic else None,
+                     "traffic_source": ("%s (rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this kernel, not measured in this "
+                                        "run)" % traffic["source"]) if traffic else None,
                      "kernel": "k_conv1d_fast<N=3>", "algorithmic_bytes_per_launch": head["bytes"]},
+        "by_bits": by_bits,
+        "gops_1bit": by_bits["1u"]["gops"], "gops_4bit": by_bits["4u"]["gops"], "gops_8bit": by_bits["8u"]["gops"],
+        "vs_unpacked_4bit": by_bits["4u"]["vs_unpacked"],
+        "target": {"statement": "packed above the unpacked GPU baseline at 1-4 bit (int32 outputs, 3 taps)",
+                   "met": not misses, "below_unpacked": misses},
     }
+
+    # VALU-integer roofline of the ALU-bound configuration (the binarised layer at its stated batch)
+    c4 = conv2d_extra(hk, wl, "c4", max(5, args.steps // 2))
+    if "wide32" in c4:
+        util = read_profile_json("conv2d_c4_valu_utilisation.json")
+        alu = dict(c4["wide32"]["roofline"])
+        alu.update(workload="binarised layer 8x256x28x28 -> 256, 3x3, stride 1, pad 1 (input packing included)",
+                   ms=c4["wide32"]["ms"], gops=c4["wide32"]["gops"], unpacked_ms=c4["unpacked"]["ms"],
+                   vs_unpacked=c4["unpacked"]["ms"] / c4["wide32"]["ms"],
+                   effective_macs_vs_one_mac_per_lane_peak=c4["wide32"]["frac_of_unpacked_valu_peak"],
+                   valu_utilisation=util.get("valu_utilisation") if util else None,
+                   valu_utilisation_source=("%s (SQ_ACTIVE_INST_VALU x 4 / (1024 SIMDs x kernel cycles), rocprofv3 "
+                                            "run of this layer; not measured in this run)" % util["source"]) if util else None)
+        line["roofline_alu"] = alu
 
     extras = {}
     if not args.no_extras:
-        ms_unp = event_ms(head["unpacked"], max(3, args.steps // 5))
-        extras["unpacked_4bit"] = dict(ms=ms_unp, gops=2 * head["macs"] / ms_unp / 1e6)
-        by_bits = {"4u": dict(ms=ms_kernel, gops=gops, gbs=achieved_gbs)}
-        x_keep, g_keep = head["x"], head["g"]
-        for key in ("packed", "unpacked", "y", "keep"):
-            head.pop(key)
-        torch.cuda.empty_cache()
-        for bits, signed in ((1, False), (8, False), (4, True), (1, True), (8, True)):
-            case = conv1d_case(hk, wl, bits, signed)
-            event_ms(case["packed"], 3)
-            ms_p = event_ms(case["packed"], max(3, args.steps // 5))
-            ms_u = event_ms(case["unpacked"], max(3, args.steps // 5))
-            by_bits["%d%s" % (bits, "s" if signed else "u")] = dict(
-                ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=case["bytes"] / ms_p / 1e6, unpacked_ms=ms_u,
-                plan=dict(N=case["plan"].N, K=case["plan"].K, S=case["plan"].S, chunks=case["plan"].chunks))
-            del case
-            torch.cuda.empty_cache()
-        extras["conv1d_by_bits"] = by_bits
-        extras["conv1d_requant_bitdense_out"] = requant_extra(hk, wl, max(3, args.steps // 5))
-        for name in ("c3", "c4"):
-            extras["conv2d_" + name] = conv2d_extra(hk, wl, name, max(5, args.steps // 2))
+        extras["conv1d_requant_bitdense_out"] = requant_extra(hk, wl, reps)
+        extras["conv2d_c3"] = conv2d_extra(hk, wl, "c3", max(5, args.steps // 2))
+        extras["conv2d_c4"] = c4
         extras["widened_layers"] = widened_extras(hk, max(5, args.steps // 2))
         extras["latency"] = small_extras(hk, wl, max(5, args.steps // 2))
-        head["x"], head["g"] = x_keep, g_keep
+    head["x"], head["g"] = x_keep, g_keep
     line["extras"] = extras
 
     if not args.no_cpu:

@@ -61,9 +61,30 @@ extern "C" {
 #define HIKONV_OUT_FULL 0  /* len + taps - 1 outputs per row (Eq. pad_f) */
 #define HIKONV_OUT_VALID 1 /* y[taps-1 .. len-1]: len - taps + 1 outputs */
 
+/* What the planner optimises (hikonv_plan_t.objective). */
+#define HIKONV_OBJ_PAPER_OPS 0     /* Algorithm 1: most low-bit operations per multiply, Eq. (tot_ops); with a  */
+                                   /* fixed tap count: most multiply-accumulates per multiply                    */
+#define HIKONV_OBJ_MEASURED_COST 1 /* fewest modelled VALU issue slots per output on gfx950: every candidate   */
+                                   /* (N, K, S) is priced with per-instruction counts for packing, multiplying, */
+                                   /* exchanging, splitting and storing calibrated on MI355X counters, bounded  */
+                                   /* below by the slots that fit under the HBM time of its bytes               */
+
+/* Layer kernel form (hikonv_plan_t.kernel); AUTO lets the library choose by layer size. */
+#define HIKONV_KERNEL_AUTO 0
+#define HIKONV_KERNEL_LDS 1  /* weight words staged in LDS (small layers)              */
+#define HIKONV_KERNEL_SREG 2 /* weight words in scalar registers wherever the plan allows it */
+
+/* hikonv_plan_t.flags */
+#define HIKONV_F_STORES64 1 /* layer kernels: address every output store with 64 bits (the library does this by */
+                            /* itself for outputs of 2^31 bytes or more)                                        */
+
+/* The layer kernels (hikonv_conv2d, hikonv_conv3d) hold at most this many slices per lane. */
+#define HIKONV_LAYER_MAX_N 8
+
 /*
  * A packing plan.  Request fields are read by hikonv_plan_ex; result fields are
- * written by the planner and read by the convolution entry points.
+ * written by the planner and read by the convolution entry points, which run
+ * exactly the plan they are handed.
  *   Section "Multiplier for Convolution": p, q, L_A, L_B, slice S, guard bits G_b.
  */
 typedef struct hikonv_plan_t {
@@ -82,6 +103,14 @@ typedef struct hikonv_plan_t {
                                 /* needs it); 1: the smallest S for which every segment sum of the   */
                                 /* declared value ranges provably fits (G_b then reports S minus the */
                                 /* product width and may be smaller than the paper's)                */
+    int32_t objective;          /* HIKONV_OBJ_*                                                      */
+    int32_t out_bits;           /* CONV1D mode, measured-cost objective: what the split produces.    */
+                                /* 0: int32 outputs (hikonv_conv1d); 1..8: outputs requantised to    */
+                                /* this many bits and stored bit-dense (hikonv_conv1d_requant)       */
+    int32_t max_N;              /* 0: no limit; else only plans with N <= max_N are considered       */
+                                /* (HIKONV_LAYER_MAX_N for plans meant for hikonv_conv2d/conv3d)     */
+    int32_t kernel;             /* layer calls: HIKONV_KERNEL_*; copied through by the planner       */
+    int32_t flags;              /* HIKONV_F_*; copied through by the planner                         */
     /* result */
     int32_t N, K, S, G_b;       /* elements per A word, taps per B word, slice bits, guard bits      */
     int32_t chunks;             /* ceil(taps / K): B words per kernel row (1 if taps == 0)           */
@@ -89,6 +118,16 @@ typedef struct hikonv_plan_t {
     int32_t paper_exact;        /* 1: (N,K,S,G_b) are exactly what Eq. (slice1)-(slice3) and         */
                                 /* Algorithm 1 give; 0: adjusted so that every value of the declared */
                                 /* ranges is computed exactly (signed corner cases, accumulator fit) */
+                                /* or chosen by another objective                                    */
+    int32_t stride_elems;       /* elements between the values of neighbouring slices of an A word:  */
+                                /* 1 = consecutive elements (Eq. inpack); J > 1 = container-aligned  */
+                                /* slices (K = 1, S a multiple of the container width c, J = S / c): */
+                                /* slice n of the word for residue r holds element r + n*J, so that  */
+                                /* packing is a shift and a mask of the bit-dense input (Theorem 1   */
+                                /* has no cross terms when K = 1, so any assignment of elements to   */
+                                /* slices is a valid packing)                                        */
+    int32_t cost_milli;         /* modelled VALU issue slots per output element x 1000 (CONV1D mode  */
+                                /* with fixed taps; 0 where the model does not apply)                */
 } hikonv_plan_t;
 
 /*
@@ -107,6 +146,20 @@ int hikonv_plan(int bits_a, int bits_w, int signedness, int mult_width, hikonv_p
  * fields ignored.  `out` (host) may alias request.
  */
 int hikonv_plan_ex(const hikonv_plan_t *request, hikonv_plan_t *out);
+
+/*
+ * With objective = HIKONV_OBJ_MEASURED_COST, mode CONV1D and fixed taps the search
+ * of hikonv_plan_ex minimises the modelled cost instead (Algorithm 1's loop with
+ * another objective; Section "Maximizing Processing Throughput" states the
+ * optimisation for a multiplier whose every use costs the same, which does not hold
+ * for a GPU lane that also has to pack and split).  Besides the (N, K, S) of
+ * Eq. (slice1)-(slice3) it considers container-aligned slices (stride_elems > 1)
+ * when out_bits names an output container as wide as the input's.
+ * hikonv_plan_cost -- the model's price of a fully specified plan (request and
+ * result fields set; out_bits selects the output form): VALU issue slots per
+ * output element x 1000, or a negative HIKONV_E* code.  Host only.
+ */
+int hikonv_plan_cost(const hikonv_plan_t *plan);
 
 /*
  * hikonv_plan_check -- exact interval check of a fully specified plan: every
@@ -133,7 +186,8 @@ int hikonv_compact(const void *x_dev, int64_t rows, int64_t len, int bits, int b
  * plan: mode CONV1D, L_A = L_B = 32, taps == `taps`, from hikonv_plan_ex.
  * x_dev: [rows][len] in x_format.  g_dev: `taps` bytes on the device, shared by
  * all rows.  y_dev: [rows][out_len] int32, out_len = len+taps-1 (FULL) or
- * len-taps+1 (VALID, 0 if len < taps).
+ * len-taps+1 (VALID, 0 if len < taps).  x_dev must be 4-byte aligned, y_dev
+ * 16-byte aligned (HIKONV_EINVAL otherwise); stride_elems must be 1.
  */
 int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows,
                   int64_t len, const void *g_dev, int taps, int out_mode, int32_t *y_dev,
@@ -153,13 +207,16 @@ int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, const void *x
  * q_dev: [rows] bit-dense rows of out_len values of out_bits bits,
  * hikonv_bitdense_row_bytes(out_len, out_bits) bytes each, 16-byte aligned;
  * bits beyond out_len in a row are written as 0.  Nothing else is written.
- * Where the input and output containers have the same width c, taps <= 7, a
- * window of 32/c + taps - 1 containers fits 64 bits and taps*max|a|*max|w| fits
- * a 16-bit slice (2^16 unsigned, 2^15 when an operand is signed), the library
- * computes with container-aligned slices instead of the plan's N, K, S
- * (Theorem 1 with K = 1, N = 2, S = 16, the elements of a word 16/c apart);
- * the result is the same.  Otherwise plans with N <= 12 whose N containers fit
- * 32 bits run the streaming kernel; other plans run a slow general kernel;
+ * The call runs the plan it is handed.  Plans with stride_elems = 1 and N <= 12
+ * whose N containers fit 32 bits run the streaming kernel; other such plans run a
+ * slow general kernel.
+ * Plans with container-aligned slices (stride_elems = S / c > 1, K = 1,
+ * chunks = taps; N = 2, S = 16, or for one-bit unsigned values and taps N = 8,
+ * S = 4), as hikonv_plan_ex returns them under HIKONV_OBJ_MEASURED_COST with
+ * out_bits set, need: input and output containers of the same width c, taps <= 7,
+ * a window of 32/c + taps - 1 containers within 64 bits, and
+ * taps*max|a|*max|w| within the slice (hikonv_plan_check tells); otherwise
+ * HIKONV_EINVAL.
  * N > 32 or more than 8 chunks give HIKONV_EUNSUPPORTED.
  */
 int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows,
@@ -298,35 +355,6 @@ int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H, int W, int
                          const hikonv_plan_t *next_plan, int next_Co, int next_Kh, int next_Kw,
                          int next_stride, int next_pad, void *next_workspace_dev,
                          size_t next_workspace_bytes, void *stream);
-
-/*
- * Roofline micro-benchmarks.  kind: HIKONV_UB_*.  Launches one kernel on
- * `stream`; the caller times it.  For VALU kinds every lane of `blocks` x 256
- * threads issues iters x 64 dependent-chain-free instructions of the kind;
- * buf_dev (>= 4*blocks*256 bytes) receives a checksum so nothing is optimised
- * away.  For HBM kinds buf_dev holds `bytes` bytes (copy: first half -> second).
- */
-#define HIKONV_UB_MAD_U32_U24 0
-#define HIKONV_UB_MAD_U64_U32 1
-#define HIKONV_UB_MUL_LO_U32 2
-#define HIKONV_UB_BFE_U32 3
-#define HIKONV_UB_LSHR_B64 4
-#define HIKONV_UB_DPP_MOV 5
-#define HIKONV_UB_ADD_U32 6
-#define HIKONV_UB_MAD_I32_I24 7
-#define HIKONV_UB_MAD_I64_I32 8
-#define HIKONV_UB_ADD_U64 9
-#define HIKONV_UB_ALIGNBIT 10
-#define HIKONV_UB_AND_B32 11
-#define HIKONV_UB_HBM_WRITE 16
-#define HIKONV_UB_HBM_COPY 17
-#define HIKONV_UB_HBM_READ 18
-#define HIKONV_UB_HBM_WRITE_NT 19 /* write with the non-temporal hint */
-#define HIKONV_UB_HBM_WRITE_RUNS 20 /* non-temporal, one contiguous 6016-byte run per wave (the 1-D kernel's store pattern) */
-int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream);
-
-/* Lane-exchange self check: out_dev[i] (64 ints) = value lane i receives from lane i-1 (lane 0: 0). */
-int hikonv_selftest_lane_shift(int32_t *out_dev, void *stream);
 
 const char *hikonv_strerror(int code);
 int hikonv_last_hip_error(void); /* hipError_t of the most recent failing HIP call in this thread */

@@ -20,8 +20,13 @@ UB_MAD_U32_U24, UB_MAD_U64_U32, UB_MUL_LO_U32, UB_BFE_U32, UB_LSHR_B64, UB_DPP_M
 UB_MAD_I32_I24, UB_MAD_I64_I32, UB_ADD_U64, UB_ALIGNBIT, UB_AND_B32 = range(7, 12)
 UB_HBM_WRITE, UB_HBM_COPY, UB_HBM_READ, UB_HBM_WRITE_NT, UB_HBM_WRITE_RUNS = 16, 17, 18, 19, 20
 
-PLAN_FIELDS = ("bits_a bits_w a_signed w_signed bipolar L_A L_B L_acc mode M taps tight "
-               "N K S G_b chunks ops_per_mul paper_exact").split()
+OBJ_PAPER_OPS, OBJ_MEASURED_COST = 0, 1
+KERNEL_AUTO, KERNEL_LDS, KERNEL_SREG = 0, 1, 2
+F_STORES64 = 1
+LAYER_MAX_N = 8
+
+PLAN_FIELDS = ("bits_a bits_w a_signed w_signed bipolar L_A L_B L_acc mode M taps tight objective out_bits max_N "
+               "kernel flags N K S G_b chunks ops_per_mul paper_exact stride_elems cost_milli").split()
 
 
 class Plan(C.Structure):
@@ -61,6 +66,7 @@ SIGNATURES = {
     "hikonv_plan": (_i, [_i, _i, _i, _i, _pp]),
     "hikonv_plan_ex": (_i, [_pp, _pp]),
     "hikonv_plan_check": (_i, [_pp]),
+    "hikonv_plan_cost": (_i, [_pp]),
     "hikonv_bitdense_row_bytes": (_i64, [_i64, _i]),
     "hikonv_compact": (_i, [_vp, _i64, _i64, _i, _i, _vp, _vp]),
     "hikonv_conv1d": (_i, [_pp, _vp, _i, _i64, _i64, _vp, _i, _i, _vp, _vp]),
@@ -142,6 +148,19 @@ def hikonv_plan_ex(**request):
 
 def hikonv_plan_check(plan):
     return lib.hikonv_plan_check(C.byref(plan))
+
+
+def hikonv_plan_cost(plan):
+    """Modelled VALU issue slots per output x 1000 of a fully specified 1-D plan (negative: error code)."""
+    return lib.hikonv_plan_cost(C.byref(plan))
+
+
+def with_fields(plan, **fields):
+    """A copy of `plan` with some fields replaced (e.g. kernel=KERNEL_SREG, flags=F_STORES64)."""
+    out = Plan(**plan.as_dict())
+    for name, value in fields.items():
+        setattr(out, name, value)
+    return out
 
 
 def hikonv_bitdense_row_bytes(length, bits):

@@ -20,7 +20,8 @@ class PackedCnn:
         for w_dev, spec in zip(weights, specs):
             co, c, kh, kw = w_dev.shape
             plan = hk.hikonv_plan_ex(bits_a=act_bits, bits_w=w_bits, a_signed=0, w_signed=int(w_signed), L_A=width,
-                                     L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=m, taps=kw, tight=tight)
+                                     L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=m, taps=kw, tight=tight,
+                                     max_N=hk.LAYER_MAX_N)
             packed = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8,
                                  device=w_dev.device)
             hk.hikonv_pack_weights(plan, w_dev, co, c, kh, kw, packed)
@@ -71,4 +72,45 @@ class PackedCnn:
                 hk.hikonv_epilogue(buf["acc"], n, layer["co"], buf["ho"], buf["wo"], shifts[i], qmax, layer["pool"],
                                    self.act_bits, hk.FMT_BITDENSE, buf["nxt"])
                 cur = buf["nxt"]
+        return accs[-1], accs
+
+
+class UnpackedCnn:
+    """The same chain on the baseline kernels: every layer is the direct convolution with one
+    v_mad_i32_i24 per low-bit product (hikonv_conv2d_unpacked), followed by the same epilogue
+    writing one value per byte.  The counterpart of the paper's unpacked complete model."""
+
+    def __init__(self, weights, specs, act_bits=4, w_bits=4, w_signed=True):
+        self.layers = [dict(w=w_dev, co=w_dev.shape[0], c=w_dev.shape[1], kh=w_dev.shape[2], kw=w_dev.shape[3],
+                            pad=spec["pad"], pool=spec["pool"]) for w_dev, spec in zip(weights, specs)]
+        self.act_bits, self.w_bits = act_bits, w_bits
+        self.sign = hk.signedness(False, w_signed)
+        self.buffers = None
+
+    def _allocate(self, n, h, w):
+        bufs = []
+        for layer in self.layers:
+            ho = h + 2 * layer["pad"] - layer["kh"] + 1
+            wo = w + 2 * layer["pad"] - layer["kw"] + 1
+            acc = torch.empty(n * layer["co"] * ho * wo, dtype=torch.int32, device="cuda")
+            h2, w2 = (ho // 2, wo // 2) if layer["pool"] else (ho, wo)
+            nxt = torch.empty(n * layer["co"] * h2 * w2, dtype=torch.uint8, device="cuda")
+            bufs.append(dict(acc=acc, nxt=nxt, h=h, w=w, ho=ho, wo=wo))
+            h, w = h2, w2
+        self.buffers = (n, bufs)
+
+    def forward(self, x_bytes, n, h, w, shifts, qmax=15):
+        """x_bytes: [n][c0][h][w], one value per byte.  Returns (last accumulators, all accumulators)."""
+        if self.buffers is None or self.buffers[0] != n or self.buffers[1][0]["h"] != h or self.buffers[1][0]["w"] != w:
+            self._allocate(n, h, w)
+        cur, accs, bufs = x_bytes, [], self.buffers[1]
+        for i, (layer, buf) in enumerate(zip(self.layers, bufs)):
+            hk.hikonv_conv2d_unpacked(self.act_bits, self.w_bits, self.sign, cur, n, layer["c"], buf["h"], buf["w"],
+                                      layer["w"], layer["co"], layer["kh"], layer["kw"], 1, layer["pad"], buf["acc"])
+            accs.append(buf["acc"])
+            if i + 1 == len(self.layers):
+                break
+            hk.hikonv_epilogue(buf["acc"], n, layer["co"], buf["ho"], buf["wo"], shifts[i], qmax, layer["pool"],
+                               self.act_bits, hk.FMT_INT8, buf["nxt"])
+            cur = buf["nxt"]
         return accs[-1], accs

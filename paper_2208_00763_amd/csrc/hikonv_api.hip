@@ -3,6 +3,7 @@
 #include <atomic>
 #include <cstdlib>
 
+#include "../../include/hikonv_bench.h"
 #include "hikonv_launch.h"
 
 using namespace hikonv;
@@ -88,7 +89,7 @@ int conv_geom(const hikonv_plan_t *plan, int N, int C, int D, int H, int W, int 
     const bool wide = plan->L_A == 32 && plan->L_B == 32 && (plan->L_acc == 64 || plan->L_acc == 0);
     const bool narrow = plan->L_A == 24 && plan->L_B == 24 && plan->L_acc == 32;
     if (!wide && !narrow) return HIKONV_EUNSUPPORTED;
-    if (plan->N > 8 || plan->chunks > 8 || Kd > 64 || Kh > 64 || Kw > 64) return HIKONV_EUNSUPPORTED;
+    if (plan->N > HIKONV_LAYER_MAX_N || plan->stride_elems > 1 || plan->chunks > 8 || Kd > 64 || Kh > 64 || Kw > 64) return HIKONV_EUNSUPPORTED;
     if (!polyphase && pad > Kw - 1) return HIKONV_EUNSUPPORTED; // the leading padding must fit inside the kernel width
     if (H + 2 * pad < Kh || W + 2 * pad < Kw || (is3d && D + 2 * pad < Kd)) return HIKONV_EINVAL;
     if (!is3d && (D != 1 || Kd != 1)) return HIKONV_EINVAL;
@@ -283,10 +284,9 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     // Kernel choice.  With the weights in scalar registers the term loop has no LDS traffic
     // and rows need no lane for their zero word; it needs enough (row group, channel tile)
     // pairs to fill the chip and is slower on small layers.
-    // HIKONV_CONV2D_KERNEL (tuning / test override, read per call): 1 = LDS-staged kernels
-    // only, 2 = scalar-register kernel wherever the plan allows it.
-    const char *kernel_env = getenv("HIKONV_CONV2D_KERNEL");
-    const int forced_kernel = kernel_env ? atoi(kernel_env) : 0;
+    // plan->kernel: HIKONV_KERNEL_LDS = LDS-staged kernels only, HIKONV_KERNEL_SREG =
+    // scalar-register kernel wherever the plan allows it, HIKONV_KERNEL_AUTO = by layer size.
+    const int forced_kernel = plan->kernel;
     ca.sreg = 0;
     if (forced_kernel != 1 && Co >= 8 &&
         conv2d_sreg_applicable(plan->N, plan->K, split_terms, wide)) {
@@ -313,13 +313,7 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     // workgroup when the layer has few (row group, channel tile) pairs
     auto choose_split = [&](int64_t base_waves, Conv2dArgs *args) {
         int ks = 1;
-        static const int forced = [] {
-            const char *e = getenv("HIKONV_CONV2D_KSPLIT"); // tuning override: 1, 2 or 4
-            return e ? atoi(e) : 0;
-        }();
-        if (args->pipelined && (forced == 1 || forced == 2 || forced == 4)) {
-            ks = g.terms_pad >= kTermGroup * forced ? forced : 1;
-        } else if (args->pipelined) {
+        if (args->pipelined) {
             if (base_waves < 2048 && g.terms_pad >= 64)
                 ks = 4;
             else if (base_waves < 4096 && g.terms_pad >= 32)
@@ -334,17 +328,11 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     ca.Co = Co;
     ca.cog0 = 0;
     ca.y = y_dev;
+    ca.stores64 = (plan->flags & HIKONV_F_STORES64) ? 1 : 0;
     // Eight output channels per wave reuse every activation word eight times; layers with few
     // (row group, channel tile) pairs run faster with two channels per wave and four times the waves.
     int co_tile = Co >= 8 ? 8 : 2;
     if (!ca.sreg && ca.pipelined && row_groups * ((Co + 7) / 8) < 768) co_tile = 2;
-    {
-        static const int forced_tile = [] {
-            const char *e = getenv("HIKONV_CONV2D_COTILE"); // tuning override: 2 or 8
-            return e ? atoi(e) : 0;
-        }();
-        if (!ca.sreg && (forced_tile == 2 || forced_tile == 8)) co_tile = forced_tile;
-    }
     choose_split(row_groups * ((Co + co_tile - 1) / co_tile), &ca);
     rc = hip_result(launch_conv2d_packed(ca, wide, any_signed, co_tile, stream));
     if (rc != HIKONV_OK) return rc;
@@ -373,6 +361,7 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
     if (!plan) return HIKONV_EINVAL;
     if (plan->mode != HIKONV_MODE_CONV1D || plan->taps != taps) return HIKONV_EINVAL;
     if (plan->bipolar) return HIKONV_EUNSUPPORTED;
+    if (plan->stride_elems > 1) return HIKONV_EUNSUPPORTED; // container-aligned slices: requantised outputs only
     if (plan->L_A != 32 || plan->L_B != 32 || (plan->L_acc != 64 && plan->L_acc != 0)) return HIKONV_EUNSUPPORTED;
     if (plan->N < 1 || plan->N > 32 || plan->K < 1 || plan->S < 1 || plan->chunks < 1 || plan->chunks > 8)
         return HIKONV_EUNSUPPORTED;
@@ -391,7 +380,8 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
     const bool any_signed = plan->a_signed || plan->w_signed;
     if (conv1d_fast_applicable(a)) {
         a.CH = 0;
-        conv1d_fast_tuning(&a);
+        a.aligned_runs = 1;     // a wave's output interval ends on 128-byte lines of y
+        a.align_outputs = 32;
         a.tiles_per_row = conv1d_fast_runs_per_row(a);
         if (a.aligned_runs) {
             a.run_outputs = conv1d_fast_run_outputs(a);
@@ -457,14 +447,15 @@ extern "C" int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_de
     rc = requant_common(shift, qmax, out_bits, q_dev, &a);
     if (rc != HIKONV_OK) return rc;
     const bool any_signed = plan->a_signed || plan->w_signed;
-    // Where input and output containers are equal and the sums fit 16-bit slices, the library
-    // computes with container-aligned slices (K = 1, N = 2, S = 16: packing becomes a mask)
-    // instead of the plan's N, K, S; HIKONV_REQUANT_KERNEL=1 (tuning / test override, read per
-    // call) keeps the plan's own slices.
-    {
-        const char *e = getenv("HIKONV_REQUANT_KERNEL");
-        if (!(e && atoi(e) == 1) && conv1d_requant_aligned_applicable(a, plan->a_signed != 0, plan->bits_w))
-            return hip_result(launch_conv1d_requant_aligned(a, plan->a_signed != 0, any_signed, plan->bits_w, static_cast<hipStream_t>(stream)));
+    // Container-aligned slices (K = 1, the elements of a word S/c apart: packing becomes a mask):
+    // the planner returns them under the measured-cost objective; the kernel takes its slice
+    // width from the operands exactly as the planner does, so the two must agree.
+    if (plan->stride_elems > 1) {
+        if (!conv1d_requant_aligned_applicable(a, plan->a_signed != 0, plan->bits_w)) return HIKONV_EINVAL;
+        const int sw = conv1d_requant_aligned_slice(a, any_signed, plan->bits_w);
+        if (plan->S != sw || plan->N != 32 / sw || plan->K != 1 || plan->stride_elems != sw / a.c) return HIKONV_EINVAL;
+        return hip_result(launch_conv1d_requant_aligned(a, plan->a_signed != 0, any_signed, plan->bits_w,
+                                                        static_cast<hipStream_t>(stream)));
     }
     a.N = plan->N;
     a.Kp = plan->K;

@@ -353,20 +353,6 @@ hipError_t launch_n(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g,
 
 } // namespace
 
-// HIKONV_CONV1D_ALIGNED=0 (tuning override) switches the line-aligned output intervals off.
-static int env_flag(const char *name, int dflt)
-{
-    const char *e = getenv(name);
-    return e ? atoi(e) : dflt;
-}
-
-void conv1d_fast_tuning(Conv1dArgs *a)
-{
-    static const int aligned = env_flag("HIKONV_CONV1D_ALIGNED", -1);
-    a->aligned_runs = aligned >= 0 ? aligned : 1;
-    a->align_outputs = kAlignOutputs;
-}
-
 bool conv1d_fast_applicable(const Conv1dArgs &a)
 {
     return a.N >= 1 && a.N <= 12 && a.N * a.c <= 32 && a.chunks <= 8 && a.taps <= 64;

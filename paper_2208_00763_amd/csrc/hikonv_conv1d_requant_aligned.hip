@@ -261,7 +261,7 @@ hipError_t launch_aligned_ct(const Conv1dArgs &a, bool a_signed, bool any_signed
             hipLaunchKernelGGL((k_conv1d_requant_aligned<C, 16, TAPS, true, true>), g, dim3(256), 0, stream, a);
         else if (any_signed)
             hipLaunchKernelGGL((k_conv1d_requant_aligned<C, 16, TAPS, false, true>), g, dim3(256), 0, stream, a);
-        else if (C == 1 && a.b == 1 && bits_w == 1)
+        else if (conv1d_requant_aligned_slice(a, any_signed, bits_w) == 4)
             // one-bit unsigned values and taps: sums of at most 7 fit nibble slices, eight outputs per word
             hipLaunchKernelGGL((k_conv1d_requant_aligned<1, 4, TAPS, false, false>), g, dim3(256), 0, stream, a);
         else
@@ -300,6 +300,11 @@ bool conv1d_requant_aligned_applicable(const Conv1dArgs &a, bool a_signed, int b
     const int64_t max_w = w_signed ? (1LL << (bits_w - 1)) : (1LL << bits_w) - 1;
     const int64_t bound = (int64_t)a.taps * max_a * max_w; // |sum| <= bound
     return (a_signed || w_signed) ? bound < (1LL << 15) : bound < (1LL << 16);
+}
+
+int conv1d_requant_aligned_slice(const Conv1dArgs &a, bool any_signed, int bits_w)
+{
+    return !any_signed && a.c == 1 && a.b == 1 && bits_w == 1 ? 4 : 16;
 }
 
 hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, bool any_signed, int bits_w, hipStream_t stream)

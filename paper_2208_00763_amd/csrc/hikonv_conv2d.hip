@@ -454,27 +454,22 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_sign
     if (gx <= 0 || gy <= 0 || gx * gy > 0x3fffffffLL) return hipErrorInvalidValue;
     // the kernels index rows and row groups with 32-bit arithmetic (row group * rows per wave + 63 < 2^31)
     if (a.wave_rows >= 0x3fffffffLL || row_groups >= 0x3fffffffLL) return hipErrorInvalidValue;
-    // 1-D grid, tiles dealt to the XCDs in contiguous ranges (HIKONV_CONV2D_XCD=0: plain order)
-    static const int xcd_order = [] {
-        const char *e = getenv("HIKONV_CONV2D_XCD");
-        return e ? atoi(e) : 1;
-    }();
+    // 1-D grid, tiles dealt to the XCDs in contiguous ranges
     a.tiles_x = (int)gx;
     a.tiles_y = (int)gy;
-    a.per_xcd = xcd_order && gx * gy >= 64 ? (int)ceil_div(gx * gy, 8) : 0;
+    a.per_xcd = gx * gy >= 64 ? (int)ceil_div(gx * gy, 8) : 0;
     dim3 g((unsigned)(a.per_xcd ? (int64_t)a.per_xcd * 8 : gx * gy));
     // Stores through 32-bit buffer offsets from the output row of a wave's first lane: the
     // lanes of a wave share one row (long rows) or cover rows_per_wave consecutive rows, which
-    // may run into the following images.  HIKONV_CONV2D_STORES=0 (test override, read per
-    // call) forces the stores with 64-bit addresses.
+    // may run into the following images.  Larger windows, or the caller's HIKONV_F_STORES64,
+    // take the stores with 64-bit addresses.
     {
         int64_t window_rows = 1;
         if (a.segs == 0) {
             const int64_t more_images = (a.rows_per_wave - 1 + a.Ho - 1) / a.Ho;
             window_rows = more_images * a.Co * a.Ho + a.rows_per_wave + 1;
         }
-        const char *e = getenv("HIKONV_CONV2D_STORES");
-        a.fast_store = window_rows * a.Wo * 4 < 0x7fffffffLL && !(e && atoi(e) == 0) ? 1 : 0;
+        a.fast_store = window_rows * a.Wo * 4 < 0x7fffffffLL && !a.stores64 ? 1 : 0;
     }
     if (a.sreg) {
         if (!wide || co_tile != 8) return hipErrorInvalidValue;

@@ -42,7 +42,6 @@ hipError_t launch_conv1d_packed(const Conv1dArgs &a, bool a_signed, bool any_sig
 hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream);
 // streaming variant (no workgroup barrier) for N <= 12 and N*c <= 32
 bool conv1d_fast_applicable(const Conv1dArgs &a);
-void conv1d_fast_tuning(Conv1dArgs *a);
 int64_t conv1d_fast_runs_per_row(const Conv1dArgs &a);
 int64_t conv1d_fast_run_outputs(const Conv1dArgs &a); // outputs per line-aligned interval
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
@@ -53,6 +52,7 @@ hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_si
 hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream);
 // requantised output, container-aligned 16-bit slices (K = 1, N = 2): same containers in and out, sums within a slice
 bool conv1d_requant_aligned_applicable(const Conv1dArgs &a, bool a_signed, int bits_w);
+int conv1d_requant_aligned_slice(const Conv1dArgs &a, bool any_signed, int bits_w); // slice width the kernel uses: 16, or 4 (one-bit unsigned operands)
 hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, bool any_signed, int bits_w, hipStream_t stream);
 
 // ---- 2-D ---------------------------------------------------------------------------
@@ -134,6 +134,7 @@ struct Conv2dArgs {
     int64_t wave_rows;       // total rows = Nimg*Ho
     int Wo;                  // strided output width
     int32_t *y;              // [Nimg][Co][Ho][Wo]
+    int stores64;            // 1: the caller asks for stores with 64-bit addresses
     int fast_store;          // 1: every lane's output lies less than 2^31 bytes after the output row of its wave's
                              // first lane (same channel): stores through buffer offsets (set by the launcher)
 };

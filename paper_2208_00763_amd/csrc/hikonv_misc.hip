@@ -2,6 +2,7 @@
 // the un-accelerated layer epilogue of the complete-model experiment, roofline
 // micro-benchmarks, and a lane-exchange self check.
 #include "hikonv_device.h"
+#include "../../include/hikonv_bench.h"
 #include "hikonv_launch.h"
 
 namespace hikonv {

@@ -67,6 +67,7 @@ struct Req {
     bool a_signed, w_signed, any_signed, bipolar;
     int L_A, L_B, L_acc, mode, M, taps;
     bool tight;
+    int objective, out_bits, max_N;
     Range fa, gw, prod;
 };
 
@@ -91,6 +92,9 @@ Req make_req(const hikonv_plan_t &in)
     r.M = in.mode == HIKONV_MODE_DNN ? (in.M > 0 ? in.M : 1) : 1;
     r.taps = in.taps;
     r.tight = in.tight != 0;
+    r.objective = in.objective;
+    r.out_bits = in.out_bits;
+    r.max_N = in.max_N;
     r.fa = r.bipolar ? Range{-1, 1} : value_range(r.p, r.a_signed);
     r.gw = r.bipolar ? Range{-1, 1} : value_range(r.q, r.w_signed);
     r.prod = mul_range(r.fa, r.gw);
@@ -165,23 +169,137 @@ bool exact_ok(const Req &r, int n, int k, int s)
 
 struct Cand {
     int n = 0, k = 0, s = 0, gb = 0, chunks = 1;
+    int stride = 1;    // elements between the values of neighbouring slices (1: Eq. inpack)
+    double cost = 0.0; // modelled VALU issue slots per output (measured-cost objective)
     bool found = false;
 };
 
+// ---- issue-cost model of the 1-D kernels (HIKONV_OBJ_MEASURED_COST) -----------------------
+//
+// Algorithm 1 prices every candidate by the low-bit operations one multiply replaces, as if
+// the multiply were all a convolution costs.  On a gfx950 lane the multiply is one issue slot
+// among many: building A from bit-dense containers, exchanging the high part with the
+// neighbour lane, cutting the word into fields and storing them cost a slot per instruction
+// too.  The model below counts VALU issue slots per output element for each kernel form.  The
+// coefficients are fitted to SQ_INSTS_VALU (wave instructions x 64 / outputs) of the kernels
+// on MI355X at 4096 rows x 65536, 3 taps; a DPP move counts 1.75 slots (it issues at 57 % of
+// the full rate), every other integer instruction the kernels use issues at 93-99 %.
+//
+//   streaming kernel, int32 outputs (stride_elems = 1), per block of N outputs:
+//       kI32Block + kI32Elem*N  [+ N + 1 signed]  + per extra B word: kShareChunk when the
+//       delayed words come from the preceding lanes (K = N), else a second packing
+//   streaming kernel, requantised bit-dense outputs:
+//       kRqBlock + kRqElem*N  [+ N + 1 signed] + the same per extra B word
+//   container-aligned slices (K = 1, S = SW, J = SW/c residues), per output dword of 32/c values:
+//       2 per packed word of the window (shift, mask), J + taps - 1 of them
+//       taps per residue word (multiply-add; AND + add for one-bit taps), J residue words
+//       kAlignedRequant (2 unsigned, 4 signed, 3 nibble) per residue word for ReLU/shift/clamp
+//       1.5 per residue word to place it in the output dword, kAlignedDword per dword for
+//       window assembly, addresses and the store
+//
+// A kernel cannot run faster than its bytes move: the price of a plan is bounded below by the
+// slots that pass during the HBM time of its algorithmic bytes per output at the published
+// peaks (8 TB/s, 256 CUs x 64 lanes x 2.4 GHz: 4.9 slots per byte).  Plans under that floor tie
+// and the one with fewer slots wins.
+constexpr double kI32Block = 15.0, kI32Elem = 11.7;
+constexpr double kRqBlock = 21.0, kRqElem = 13.9;
+constexpr double kShareChunk = 4.2;
+constexpr double kAlignedDword = 25.0;
+constexpr double kSlotsPerByte = 256.0 * 64.0 * 2.4e9 / 8.0e12;
+
+inline int container_of(int bits) { return hikonv::container_bits(bits); }
+
+double hbm_floor_slots(const Req &r)
+{
+    const double in_bytes = container_of(r.p) / 8.0;
+    const double out_bytes = r.out_bits > 0 ? container_of(r.out_bits) / 8.0 : 4.0;
+    return (in_bytes + out_bytes) * kSlotsPerByte;
+}
+
+// slots per output of the kernel that runs (n, k, s, stride) in CONV1D mode; < 0: no kernel
+double conv1d_slots(const Req &r, int n, int k, int chunks, int s, int stride)
+{
+    if (stride > 1) {
+        const int c = container_of(r.p);
+        const int j = stride, per = 32 / c;
+        const bool nibble = s == 4;
+        const double words = j + r.taps - 1;
+        const double requant = nibble ? 3.0 : (r.any_signed ? 4.0 : 2.0);
+        const double mac = nibble ? 2.0 : 1.0;
+        return (2.0 * words + j * (mac * r.taps + requant + 1.5) + kAlignedDword) / per;
+    }
+    const bool share = chunks >= 2 && chunks <= 4 && k == n && n >= 2 && n <= 5;
+    double block = r.out_bits > 0 ? kRqBlock + kRqElem * n : kI32Block + kI32Elem * n;
+    if (r.any_signed) block += n + 1;
+    if (chunks > 1) block += (chunks - 1) * (share ? kShareChunk : 2.0 * n + 3.0);
+    return block / n;
+}
+
+// Container-aligned slices of SW bits (16, or 4 for one-bit unsigned operands): K = 1, N = 32/SW,
+// the values of a word SW/c elements apart, every tap's product accumulated in the same word
+// (chunks = taps).  Exact when the sum of taps products fits the slice (the symmetric signed
+// bound of the carried-sign split, as in exact_ok) and the packed word fits the 24-bit
+// multiplier input that the kernel uses; the kernel also needs equal input and output
+// containers, at most 7 taps and a window of one output dword within 64 bits.
+bool aligned_ok(const Req &r, int sw, Cand *out)
+{
+    if (r.mode != HIKONV_MODE_CONV1D || r.taps < 1 || r.taps > 7 || r.bipolar) return false;
+    const int c = container_of(r.p);
+    if (r.out_bits < 1 || r.out_bits > 8 || container_of(r.out_bits) != c) return false;
+    if (sw % c != 0 || (32 / c + r.taps - 1) * c > 64) return false;
+    if (r.L_A < 24 || r.L_B < 8 || r.L_acc < 32) return false;
+    if (sw == 4 && (r.p != 1 || r.q != 1 || r.any_signed)) return false;
+    if (sw == 16 && r.any_signed && r.p > 7) return false; // two values 16 bits apart must fit 24 bits signed
+    const Range seg{r.prod.lo * r.taps, r.prod.hi * r.taps};
+    if (sw == 4) {
+        if (seg.hi > 7) return false; // the threshold compare keeps bit 3 of every slice free
+    } else if (r.any_signed) {
+        const i128 lim = ((i128)1 << (sw - 1)) - 1;
+        if (seg.lo < -lim || seg.hi > lim) return false;
+    } else if (seg.hi > ((i128)1 << sw) - 1) {
+        return false;
+    }
+    out->n = 32 / sw;
+    out->k = 1;
+    out->s = sw;
+    out->chunks = r.taps;
+    out->stride = sw / c;
+    const int prod_bits = r.p == 1 ? r.q : (r.q == 1 ? r.p : r.p + r.q);
+    out->gb = sw - prod_bits;
+    return true;
+}
+
+inline double priced(const Req &r, double slots)
+{
+    const double floor = hbm_floor_slots(r);
+    return slots < floor ? floor : slots;
+}
+
 // score comparison: free mode -> Eq. tot_ops; fixed taps -> MACs per multiply n*taps/chunks
+inline bool by_cost(const Req &r) { return r.objective == HIKONV_OBJ_MEASURED_COST && r.mode == HIKONV_MODE_CONV1D && r.taps > 0; }
+
 inline bool better(const Req &r, const Cand &c, const Cand &best)
 {
     if (!best.found) return true;
+    if (by_cost(r)) {
+        const double pc = priced(r, c.cost), pb = priced(r, best.cost);
+        if (pc != pb) return pc < pb;
+        return c.cost < best.cost; // both under the memory floor: fewer slots
+    }
     if (r.taps == 0)
         return (long long)c.n * c.k + (long long)(c.n - 1) * (c.k - 1) >
                (long long)best.n * best.k + (long long)(best.n - 1) * (best.k - 1);
     return (long long)c.n * best.chunks > (long long)best.n * c.chunks;
 }
 
-Cand search(const Req &r, bool paper_only)
+// paper_only: Eq. slice1-slice3 as printed and Algorithm 1's own objective, whatever the request's
+Cand search(const Req &r_in, bool paper_only)
 {
+    Req r = r_in;
+    if (paper_only) r.objective = HIKONV_OBJ_PAPER_OPS;
     Cand best;
     auto try_one = [&](int n, int k) {
+        if (!paper_only && r.max_N > 0 && n > r.max_N) return; // Algorithm 1 itself has no such bound
         Cand c;
         c.n = n;
         c.k = k;
@@ -204,9 +322,21 @@ Cand search(const Req &r, bool paper_only)
             if (!c.s) return;
             if (c.s < s0) c.gb -= s0 - c.s;
         }
+        if (r.mode == HIKONV_MODE_CONV1D && r.taps > 0) c.cost = conv1d_slots(r, c.n, c.k, c.chunks, c.s, 1);
         c.found = true;
         if (better(r, c, best)) best = c;
     };
+    // container-aligned slices (outside Eq. slice1's S = p + q + G_b): only under the cost objective
+    if (!paper_only && by_cost(r) && r.out_bits > 0) {
+        for (int sw : {16, 4}) {
+            Cand c;
+            if (!aligned_ok(r, sw, &c)) continue;
+            if (r.max_N > 0 && c.n > r.max_N) continue;
+            c.cost = conv1d_slots(r, c.n, c.k, c.chunks, c.s, c.stride);
+            c.found = true;
+            if (better(r, c, best)) best = c;
+        }
+    }
     if (r.taps == 0) {
         for (int k = 1; k <= r.L_B; ++k)
             for (int n = 1; n <= r.L_A; ++n) try_one(n, k);
@@ -226,6 +356,10 @@ bool valid_request(const hikonv_plan_t &in)
     if (in.M < 0 || in.M > (1 << 20) || in.taps < 0 || in.taps > 64) return false;
     if (in.bipolar && (in.bits_a != 1 || in.bits_w != 1)) return false;
     if (in.tight != 0 && in.tight != 1) return false;
+    if (in.objective != HIKONV_OBJ_PAPER_OPS && in.objective != HIKONV_OBJ_MEASURED_COST) return false;
+    if (in.out_bits < 0 || in.out_bits > 8 || in.max_N < 0 || in.max_N > 64) return false;
+    if (in.kernel < HIKONV_KERNEL_AUTO || in.kernel > HIKONV_KERNEL_SREG) return false;
+    if (in.flags & ~HIKONV_F_STORES64) return false;
     return true;
 }
 
@@ -240,6 +374,8 @@ void fill_result(hikonv_plan_t *out, const Req &r, const Cand &c, bool paper_exa
     out->chunks = c.chunks;
     out->ops_per_mul = c.n * c.k + (c.n - 1) * (c.k - 1);
     out->paper_exact = paper_exact ? 1 : 0;
+    out->stride_elems = c.stride;
+    out->cost_milli = (int32_t)(c.cost * 1000.0 + 0.5);
 }
 
 // Issue-slot model used only to choose M when the caller leaves it open.  Measured on
@@ -279,7 +415,7 @@ extern "C" int hikonv_plan_ex(const hikonv_plan_t *request, hikonv_plan_t *out)
             if (sc > best_score * 1.0000001) {
                 best_score = sc;
                 Cand pc = search(r, true);
-                fill_result(&trial, r, c, pc.found && pc.n == c.n && pc.k == c.k && pc.s == c.s);
+                fill_result(&trial, r, c, pc.found && pc.n == c.n && pc.k == c.k && pc.s == c.s && c.stride == 1);
                 best_plan = trial;
                 any = true;
             }
@@ -293,7 +429,7 @@ extern "C" int hikonv_plan_ex(const hikonv_plan_t *request, hikonv_plan_t *out)
     if (!c.found) return HIKONV_ENOPLAN;
     Cand pc = search(r, true);
     *out = in;
-    fill_result(out, r, c, pc.found && pc.n == c.n && pc.k == c.k && pc.s == c.s);
+    fill_result(out, r, c, pc.found && pc.n == c.n && pc.k == c.k && pc.s == c.s && c.stride == 1);
     return HIKONV_OK;
 }
 
@@ -317,8 +453,29 @@ extern "C" int hikonv_plan_check(const hikonv_plan_t *plan)
     if (!plan || !valid_request(*plan)) return HIKONV_EINVAL;
     if (plan->N < 1 || plan->K < 1 || plan->S < 1 || plan->N > 64 || plan->K > 64) return HIKONV_EINVAL;
     if (plan->taps && plan->chunks != (plan->taps + plan->K - 1) / plan->K) return HIKONV_EINVAL;
+    if (plan->stride_elems < 0 || plan->stride_elems > 32) return HIKONV_EINVAL;
+    if (plan->max_N > 0 && plan->N > plan->max_N) return HIKONV_EINVAL;
     Req r = make_req(*plan);
+    if (plan->stride_elems > 1) {
+        // container-aligned slices: the one form per slice width that aligned_ok describes
+        if (r.out_bits == 0) r.out_bits = r.p; // the check needs a container: the input's own
+        Cand c;
+        if (!aligned_ok(r, plan->S, &c)) return plan->S == 16 || plan->S == 4 ? HIKONV_EOVERFLOW : HIKONV_EINVAL;
+        if (c.n != plan->N || c.k != plan->K || c.stride != plan->stride_elems || c.chunks != plan->chunks)
+            return HIKONV_EINVAL;
+        return HIKONV_OK;
+    }
     return exact_ok(r, plan->N, plan->K, plan->S) ? HIKONV_OK : HIKONV_EOVERFLOW;
+}
+
+extern "C" int hikonv_plan_cost(const hikonv_plan_t *plan)
+{
+    int rc = hikonv_plan_check(plan);
+    if (rc != HIKONV_OK) return rc;
+    if (plan->mode != HIKONV_MODE_CONV1D || plan->taps < 1) return HIKONV_EUNSUPPORTED;
+    Req r = make_req(*plan);
+    const double slots = conv1d_slots(r, plan->N, plan->K, plan->chunks, plan->S, plan->stride_elems > 1 ? plan->stride_elems : 1);
+    return (int)(slots * 1000.0 + 0.5);
 }
 
 extern "C" int64_t hikonv_bitdense_row_bytes(int64_t len, int bits)

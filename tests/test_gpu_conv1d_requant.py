@@ -1,8 +1,6 @@
 """GPU parity: 1-D convolution with in-kernel requantisation and bit-dense output through the
 C ABI vs the oracle chain direct convolution -> ReLU/shift/clamp -> bit-dense packing,
 byte for byte (padding bits of every row included)."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -14,26 +12,34 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2208_00763_amd as hk
-    from gpu_util import compact, conv1d_plan, dev
+    from gpu_util import compact, dev, Guarded
 
 SIGNS = [(False, False), (True, True), (False, True), (True, False)]
 GUARD = 0xA5
 
 
-@pytest.fixture(autouse=True, params=["library_choice", "plan_slices"])
-def requant_kernel(request):
-    """Every case runs twice: with the library's own choice (container-aligned 16-bit slices where
-    input and output containers are equal and the sums fit) and with the plan's N, K, S forced."""
-    old = os.environ.get("HIKONV_REQUANT_KERNEL")
-    if request.param == "plan_slices":
-        os.environ["HIKONV_REQUANT_KERNEL"] = "1"
-    else:
-        os.environ.pop("HIKONV_REQUANT_KERNEL", None)
+OBJECTIVE = {"value": 0}
+
+
+@pytest.fixture(autouse=True, params=["measured_cost", "paper_ops"])
+def objective(request):
+    """Every case runs twice: with the plan of the measured-cost objective (container-aligned
+    slices where input and output containers are equal and the sums fit) and with Algorithm 1's."""
+    OBJECTIVE["value"] = hk.OBJ_MEASURED_COST if request.param == "measured_cost" else hk.OBJ_PAPER_OPS
     yield request.param
-    if old is None:
-        os.environ.pop("HIKONV_REQUANT_KERNEL", None)
-    else:
-        os.environ["HIKONV_REQUANT_KERNEL"] = old
+    OBJECTIVE["value"] = 0
+
+
+def requant_plan(bits, a_s, w_s, taps, out_bits, bits_w=None, fmt=None):
+    """The plan of the objective under test.  The planner prices bit-dense inputs; for inputs
+    stored one value per byte the containers differ from what it assumed, so a container-aligned
+    plan does not describe that call (the entry point refuses it) and Algorithm 1's plan is taken."""
+    kw = dict(bits_a=bits, bits_w=bits_w or bits, a_signed=int(a_s), w_signed=int(w_s), L_A=32, L_B=32, L_acc=64,
+              mode=hk.MODE_CONV1D, taps=taps, out_bits=out_bits)
+    plan = hk.hikonv_plan_ex(objective=OBJECTIVE["value"], **kw)
+    if fmt == hk.FMT_INT8 and plan.stride_elems > 1 and bits < 5:
+        plan = hk.hikonv_plan_ex(objective=hk.OBJ_PAPER_OPS, **kw)
+    return plan
 
 
 def oracle_requant(x, g, mode, shift, qmax, out_bits):
@@ -48,19 +54,17 @@ def run_requant(x, g, bits, a_s, w_s, mode, fmt, shift, qmax, out_bits, packed=T
     taps = g.shape[0]
     out_len = length + taps - 1 if mode == hk.OUT_FULL else max(length - taps + 1, 0)
     row_bytes = hk.hikonv_bitdense_row_bytes(out_len, out_bits) if out_len else 0
-    q = torch.full((rows * row_bytes + 32,), GUARD, dtype=torch.uint8, device="cuda")
+    out = Guarded(rows * row_bytes, torch.uint8, GUARD)
+    q = out.view
     x_d = compact(x, bits) if fmt == hk.FMT_BITDENSE else dev(x)
     g_d = dev(g)
     if packed:
-        plan = conv1d_plan(bits, a_s, w_s, taps)
+        plan = requant_plan(bits, a_s, w_s, taps, out_bits, fmt=fmt)
         hk.hikonv_conv1d_requant(plan, x_d, fmt, rows, length, g_d, taps, mode, shift, qmax, out_bits, q)
     else:
         hk.hikonv_conv1d_requant_unpacked(bits, bits, hk.signedness(a_s, w_s), x_d, fmt, rows, length, g_d, taps,
                                           mode, shift, qmax, out_bits, q)
-    torch.cuda.synchronize()
-    res = q.cpu().numpy()
-    assert (res[rows * row_bytes:] == GUARD).all(), "wrote past the end of the output"
-    return res[:rows * row_bytes].reshape(rows, row_bytes)
+    return out.result().reshape(rows, row_bytes)
 
 
 def values(tag, bits, a_s, w_s, taps, rows, length):
@@ -138,9 +142,41 @@ def test_requant_shift_at_and_beyond_the_slice_width(signed):
             assert np.array_equal(got, ref), (signed, shift, packed)
 
 
-def test_requant_full_size_rows_sampled():
-    """The benchmark's shape: 4096 x 65536, 3 taps, 4-bit unsigned in, 4-bit out; the oracle checks
-    a sample of whole rows."""
+@pytest.mark.parametrize("bits,signed", [(4, False), (1, False), (2, False), (4, True)])
+def test_requant_full_size_all_rows(bits, signed):
+    """The benchmark's four cases in its launch configuration: 4096 x 65536, 3 taps, valid,
+    bit-dense in and out at the same width, shift and clamp as in bench.py.  Every byte of every
+    output row (padding bits included) is compared with the oracle chain, on the device, for the
+    packed kernel of the objective under test and for the unpacked baseline."""
+    taps, rows, length = 3, 4096, 65536
+    x, g = wl.conv1d_case(bits, signed, taps, rows, length)
+    shift, qmax, out_bits = max(0, 2 * bits - 3), (1 << bits) - 1, bits
+    x_d, g_d = compact(x, bits), dev(g)
+    out_len = length - taps + 1
+    row_bytes = hk.hikonv_bitdense_row_bytes(out_len, out_bits)
+    ref_d = torch.from_numpy(oracle_requant(x, g, hk.OUT_VALID, shift, qmax, out_bits)).cuda().view(-1)
+    plan = requant_plan(bits, signed, signed, taps, out_bits)
+    assert (plan.stride_elems > 1) == (OBJECTIVE["value"] == hk.OBJ_MEASURED_COST)
+    for packed in (True, False):
+        out = Guarded(rows * row_bytes, torch.uint8, GUARD)
+        if packed:
+            hk.hikonv_conv1d_requant(plan, x_d, hk.FMT_BITDENSE, rows, length, g_d, taps, hk.OUT_VALID, shift, qmax,
+                                     out_bits, out.view)
+        else:
+            hk.hikonv_conv1d_requant_unpacked(bits, bits, hk.signedness(signed, signed), x_d, hk.FMT_BITDENSE, rows,
+                                              length, g_d, taps, hk.OUT_VALID, shift, qmax, out_bits, out.view)
+        torch.cuda.synchronize()
+        out.check()
+        if not torch.equal(out.view, ref_d):
+            bad = torch.nonzero(out.view != ref_d)[0].item()
+            raise AssertionError((bits, signed, packed, "row %d byte %d" % (bad // row_bytes, bad % row_bytes)))
+        # a sizeable share of the outputs is neither 0 nor clamped, so the comparison means something
+    vals = ref_d[:row_bytes * 8].cpu().numpy()
+    assert 0 < np.count_nonzero(vals) < vals.size
+
+
+def test_requant_full_size_full_mode_sampled_rows():
+    """FULL outputs at the benchmark's size (the row ends differ from VALID): sampled whole rows."""
     bits, taps, rows, length = 4, 3, 4096, 65536
     x, g = wl.conv1d_case(bits, False, taps, rows, length)
     shift, qmax, out_bits = 5, 15, 4
@@ -149,24 +185,19 @@ def test_requant_full_size_rows_sampled():
     row_bytes = hk.hikonv_bitdense_row_bytes(out_len, out_bits)
     sample = [0, 1, 2047, 4094, 4095] + list(wl.rng_for("rq_rows").integers(0, rows, 24))
     ref = oracle_requant(x[sample], g, hk.OUT_FULL, shift, qmax, out_bits)
-    plan = conv1d_plan(bits, False, False, taps)
-    for packed in (True, False):
-        q = torch.full((rows * row_bytes + 32,), GUARD, dtype=torch.uint8, device="cuda")
-        if packed:
-            hk.hikonv_conv1d_requant(plan, x_d, hk.FMT_BITDENSE, rows, length, g_d, taps, hk.OUT_FULL, shift, qmax,
-                                     out_bits, q)
-        else:
-            hk.hikonv_conv1d_requant_unpacked(bits, bits, 0, x_d, hk.FMT_BITDENSE, rows, length, g_d, taps,
-                                              hk.OUT_FULL, shift, qmax, out_bits, q)
-        torch.cuda.synchronize()
-        assert (q[rows * row_bytes:] == GUARD).all()
-        got = q[:rows * row_bytes].view(rows, row_bytes)[sample].cpu().numpy()
-        assert np.array_equal(got, ref), packed
+    plan = requant_plan(bits, False, False, taps, out_bits)
+    out = Guarded(rows * row_bytes, torch.uint8, GUARD)
+    hk.hikonv_conv1d_requant(plan, x_d, hk.FMT_BITDENSE, rows, length, g_d, taps, hk.OUT_FULL, shift, qmax, out_bits,
+                             out.view)
+    torch.cuda.synchronize()
+    out.check()
+    got = out.view.view(rows, row_bytes)[sample].cpu().numpy()
+    assert np.array_equal(got, ref)
 
 
 def test_requant_empty_and_rejected_arguments():
     x, g = values("rq4", 4, False, False, 3, 2, 64)
-    plan = conv1d_plan(4, False, False, 3)
+    plan = requant_plan(4, False, False, 3, 4, fmt=hk.FMT_INT8)
     q = torch.full((256,), GUARD, dtype=torch.uint8, device="cuda")
     x_d, g_d = dev(x), dev(g)
     # nothing to do: no rows, no elements, VALID shorter than the kernel
@@ -198,7 +229,7 @@ def test_requant_mixed_widths_same_containers(p_bits, q_bits, signs):
         rng = wl.rng_for("rq7", p_bits, q_bits, a_s, w_s, taps)
         x = wl.uniform_values(rng, (rows, length), p_bits, a_s)
         g = wl.uniform_values(rng, (taps,), q_bits, w_s)
-        plan = conv1d_plan(p_bits, a_s, w_s, taps, bits_w=q_bits)
+        plan = requant_plan(p_bits, a_s, w_s, taps, out_bits, bits_w=q_bits)
         top = taps * ((1 << p_bits) - 1) * ((1 << q_bits) - 1)
         for mode in (hk.OUT_FULL, hk.OUT_VALID):
             for shift in (0, 1, max(0, int(top).bit_length() - out_bits - 1)):
@@ -206,10 +237,28 @@ def test_requant_mixed_widths_same_containers(p_bits, q_bits, signs):
                 ref = oracle_requant(x, g, mode, shift, qmax, out_bits)
                 out_len = length + taps - 1 if mode == hk.OUT_FULL else length - taps + 1
                 row_bytes = hk.hikonv_bitdense_row_bytes(out_len, out_bits)
-                q = torch.full((rows * row_bytes + 32,), GUARD, dtype=torch.uint8, device="cuda")
+                out = Guarded(rows * row_bytes, torch.uint8, GUARD)
                 hk.hikonv_conv1d_requant(plan, compact(x, p_bits), hk.FMT_BITDENSE, rows, length, dev(g), taps, mode,
-                                         shift, qmax, out_bits, q)
-                torch.cuda.synchronize()
-                res = q.cpu().numpy()
-                assert (res[rows * row_bytes:] == GUARD).all()
-                assert np.array_equal(res[:rows * row_bytes].reshape(rows, row_bytes), ref), (p_bits, q_bits, signs, taps, mode, shift)
+                                         shift, qmax, out_bits, out.view)
+                assert np.array_equal(out.result().reshape(rows, row_bytes), ref), (p_bits, q_bits, signs, taps, mode, shift)
+
+
+def test_requant_refuses_aligned_plans_that_do_not_fit_the_call():
+    """A container-aligned plan describes one kernel form; a call with another output container,
+    or a plan whose slice width is not the one the operands take, is refused, nothing is written."""
+    x, g = values("rq8", 4, False, False, 3, 2, 256)
+    plan = hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3,
+                             objective=hk.OBJ_MEASURED_COST, out_bits=4)
+    assert plan.stride_elems == 4
+    out = Guarded(2 * 256, torch.uint8, GUARD)
+    x_d, g_d = compact(x, 4), dev(g)
+    with pytest.raises(hk.HikonvError) as e:    # 8-bit output containers with a plan made for 4-bit ones
+        hk.hikonv_conv1d_requant(plan, x_d, hk.FMT_BITDENSE, 2, 256, g_d, 3, hk.OUT_VALID, 0, 15, 8, out.view)
+    assert e.value.code == hk.EINVAL
+    with pytest.raises(hk.HikonvError) as e:    # one value per byte in, 4-bit containers out
+        hk.hikonv_conv1d_requant(plan, dev(x), hk.FMT_INT8, 2, 256, g_d, 3, hk.OUT_VALID, 0, 15, 4, out.view)
+    assert e.value.code == hk.EINVAL
+    with pytest.raises(hk.HikonvError) as e:    # int32 outputs take stride_elems = 1 plans only
+        hk.hikonv_conv1d(plan, x_d, hk.FMT_BITDENSE, 2, 256, g_d, 3, hk.OUT_VALID, out.view)
+    assert e.value.code == hk.EUNSUPPORTED
+    out.result()

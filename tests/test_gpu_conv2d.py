@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2208_00763_amd as hk
-    from paper_2208_00763_amd.cnn import PackedCnn
+    from paper_2208_00763_amd.cnn import PackedCnn, UnpackedCnn
     from gpu_util import run_conv2d, dnn_plan, dev, compact
 
 SHAPES = [  # n, c, h, w, co, kh, kw, stride, pad
@@ -47,8 +47,6 @@ def test_conv2d_packed_small_shapes(bits, signs):
                 except hk.HikonvError as e:
                     assert e.code == hk.ENOPLAN
                     continue
-                if plan.N > 8:
-                    continue
                 for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
                     got = run_conv2d(plan, x, w, stride, pad, fmt, prepacked=(m == 4))
                     assert np.array_equal(got, ref), (bits, signs, shape, wide, m, fmt, plan)
@@ -65,8 +63,6 @@ def test_conv2d_long_rows_are_segmented(wide):
         try:
             plan = dnn_plan(bits, bits, a_s, w_s, 3, 3, wide)
         except hk.HikonvError:
-            continue
-        if plan.N > 8:
             continue
         assert (width + 1 + plan.N - 1) // plan.N > 63
         assert np.array_equal(run_conv2d(plan, x, w, 1, 1), direct.conv2d(x, w, 1, 1))
@@ -103,8 +99,6 @@ def test_conv2d_bipolar_small(shape):
     for wide in (True, False):
         for m in (3, 0):
             plan = dnn_plan(1, 1, False, False, kw, m, wide, bipolar=True)
-            if plan.N > 8:
-                continue
             for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
                 got = run_conv2d(plan, x, wt, stride, pad, fmt, prepacked=(m == 3))
                 assert np.array_equal(got, ref), (shape, wide, m, fmt, plan)
@@ -116,8 +110,7 @@ def test_conv2d_config4_full():
     ref = direct.conv2d(x, w, 1, 1)
     for wide in (True, False):
         plan = dnn_plan(1, 1, False, False, 3, 0, wide, bipolar=True)
-        if plan.N > 8:
-            plan = dnn_plan(1, 1, False, False, 3, 10, wide, bipolar=True)
+        assert plan.N <= hk.LAYER_MAX_N
         assert np.array_equal(run_conv2d(plan, x, w, 1, 1, hk.FMT_BITDENSE, prepacked=True), ref)
 
 
@@ -252,6 +245,13 @@ def test_cnn_forward_config5(size, fused):
     torch.cuda.synchronize()
     for i, (got, ref) in enumerate(zip(accs, ref_accs)):
         assert np.array_equal(got.cpu().numpy().reshape(ref.shape), ref), "layer %d" % i
+    if fused:
+        # the baseline chain (one multiply per product) that the benchmark times beside it
+        base = UnpackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs)
+        _, accs_u = base.forward(dev(x), 1, h, w, shifts)
+        torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(accs_u, ref_accs)):
+            assert np.array_equal(got.cpu().numpy().reshape(ref.shape), ref), "unpacked layer %d" % i
     # deep layers of a random-weight network go mostly to zero after ReLU, so every layer is
     # also checked in isolation on fresh uniform inputs of its own shape
     hh, ww = h, w
@@ -281,8 +281,6 @@ def test_conv2d_degenerate_and_strided_shapes():
             ref = direct.conv2d(x, w, stride, pad)
             for m in (2, 0):
                 plan = dnn_plan(bits, bits, a_s, w_s, kw, m, True)
-                if plan.N > 8:
-                    continue
                 assert np.array_equal(run_conv2d(plan, x, w, stride, pad, hk.FMT_BITDENSE), ref), (shape, bits, m, plan)
         n, c, h, wd, co, kh, kw2 = shape[:7]
         xb, wb = wl.bipolar_case(n, c, h, wd, co, kh, kw2, tag="d5")

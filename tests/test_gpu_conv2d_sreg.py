@@ -1,9 +1,8 @@
 """GPU parity of the layer kernel that keeps the weight words in scalar registers.  The
-library picks it by itself only for large layers; here HIKONV_CONV2D_KERNEL=2 forces it
-wherever the plan allows it, so that small and ragged shapes reach it too.  Through the
+library picks it by itself only for large layers; here the plans ask for it
+(kernel = HIKONV_KERNEL_SREG) wherever the plan allows it, so that small and ragged shapes
+reach it too.  Through the
 C ABI vs the int64 oracle, bit-exact."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -15,18 +14,16 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2208_00763_amd as hk
+    import gpu_util
     from gpu_util import run_conv2d, dnn_plan
 
 
 @pytest.fixture(autouse=True)
 def force_scalar_register_kernel():
-    old = os.environ.get("HIKONV_CONV2D_KERNEL")
-    os.environ["HIKONV_CONV2D_KERNEL"] = "2"
+    old = dict(gpu_util.LAYER_DEFAULTS)
+    gpu_util.LAYER_DEFAULTS.update(kernel=hk.KERNEL_SREG, flags=0)
     yield
-    if old is None:
-        del os.environ["HIKONV_CONV2D_KERNEL"]
-    else:
-        os.environ["HIKONV_CONV2D_KERNEL"] = old
+    gpu_util.LAYER_DEFAULTS.update(old)
 
 
 SHAPES = [  # n, c, h, w, co, kh, kw, stride, pad
@@ -64,8 +61,6 @@ def test_scalar_register_kernel_small_shapes(bits, signs):
                 except hk.HikonvError as e:
                     assert e.code == hk.ENOPLAN
                     continue
-                if plan.N > 8:
-                    continue
                 got = run_conv2d(plan, x, w, stride, pad, hk.FMT_BITDENSE, prepacked=(m == 4))
                 assert np.array_equal(got, ref), (bits, signs, shape, m, tight, plan)
                 ran += 1
@@ -94,8 +89,6 @@ def test_scalar_register_kernel_bipolar(shape):
     for m in (3, 0):
         for tight in (0, 1):
             plan = dnn_plan(1, 1, False, False, kw, m, True, bipolar=True, tight=tight)
-            if plan.N > 8:
-                continue
             for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
                 got = run_conv2d(plan, x, wt, stride, pad, fmt, prepacked=(m == 3))
                 assert np.array_equal(got, ref), (shape, m, tight, fmt, plan)
@@ -117,35 +110,27 @@ def test_scalar_register_kernel_full_layers():
 def test_library_picks_the_kernel_for_a_large_layer():
     # without the override: 256 input channels (768 terms) and more than a thousand
     # (row group, channel tile) pairs select the scalar-register kernel; same result either way
-    del os.environ["HIKONV_CONV2D_KERNEL"]
     rng = wl.rng_for("s5")
     x = wl.uniform_values(rng, (8, 256, 28, 28), 4, True)
     w = wl.uniform_values(rng, (256, 256, 3, 3), 4, True)
     ref = direct.conv2d(x, w, 1, 1)
-    plan = dnn_plan(4, 4, True, True, 3, 0, True)
+    plan = hk.with_fields(dnn_plan(4, 4, True, True, 3, 0, True), kernel=hk.KERNEL_AUTO)
     assert np.array_equal(run_conv2d(plan, x, w, 1, 1, hk.FMT_INT8, prepacked=True), ref)
-    os.environ["HIKONV_CONV2D_KERNEL"] = "1"
+    plan = hk.with_fields(plan, kernel=hk.KERNEL_LDS)
     assert np.array_equal(run_conv2d(plan, x, w, 1, 1, hk.FMT_INT8, prepacked=True), ref)
 
 
-@pytest.mark.parametrize("kernel", ["1", "2"])
+@pytest.mark.parametrize("kernel", ["lds", "sreg"])
 def test_stores_with_64bit_addresses(kernel):
     """The layer kernels store through 32-bit buffer offsets when a wave's outputs lie within
-    2^31 bytes; HIKONV_CONV2D_STORES=0 forces the path for larger windows (plain stores with
-    64-bit addresses) on shapes small enough to check in full."""
-    old = os.environ.get("HIKONV_CONV2D_STORES")
-    os.environ["HIKONV_CONV2D_STORES"] = "0"
-    os.environ["HIKONV_CONV2D_KERNEL"] = kernel
-    try:
-        for bits, a_s, w_s in ((4, True, True), (1, False, False), (8, False, True)):
-            for shape in SHAPES:
-                x, w = _case(bits, a_s, w_s, shape, "s9")
-                stride, pad, kw = shape[7], shape[8], shape[6]
-                ref = direct.conv2d(x, w, stride, pad)
-                plan = dnn_plan(bits, bits, a_s, w_s, kw, 0)
-                assert np.array_equal(run_conv2d(plan, x, w, stride, pad, hk.FMT_INT8), ref), (bits, shape, kernel)
-    finally:
-        if old is None:
-            del os.environ["HIKONV_CONV2D_STORES"]
-        else:
-            os.environ["HIKONV_CONV2D_STORES"] = old
+    2^31 bytes; the plan flag HIKONV_F_STORES64 forces the path for larger windows (plain stores
+    with 64-bit addresses) on shapes small enough to check in full."""
+    gpu_util.LAYER_DEFAULTS.update(kernel=hk.KERNEL_LDS if kernel == "lds" else hk.KERNEL_SREG, flags=hk.F_STORES64)
+    for bits, a_s, w_s in ((4, True, True), (1, False, False), (8, False, True)):
+        for shape in SHAPES:
+            x, w = _case(bits, a_s, w_s, shape, "s9")
+            stride, pad, kw = shape[7], shape[8], shape[6]
+            ref = direct.conv2d(x, w, stride, pad)
+            plan = dnn_plan(bits, bits, a_s, w_s, kw, 0)
+            assert plan.flags == hk.F_STORES64
+            assert np.array_equal(run_conv2d(plan, x, w, stride, pad, hk.FMT_INT8), ref), (bits, shape, kernel)

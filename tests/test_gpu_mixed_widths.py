@@ -49,11 +49,10 @@ def test_conv2d_mixed_widths(widths, wide):
     for (a_s, w_s), tight in itertools.product(SIGNS, (0, 1)):
         try:
             plan = hk.hikonv_plan_ex(bits_a=p, bits_w=q, a_signed=int(a_s), w_signed=int(w_s), L_A=width, L_B=width,
-                                     L_acc=64 if wide else 32, mode=hk.MODE_DNN, M=0, taps=3, tight=tight)
+                                     L_acc=64 if wide else 32, mode=hk.MODE_DNN, M=0, taps=3, tight=tight,
+                                     max_N=hk.LAYER_MAX_N)
         except hk.HikonvError as e:
             assert e.code == hk.ENOPLAN
-            continue
-        if plan.N > 8:
             continue
         rng = wl.rng_for("mixed2", p, q, a_s, w_s, wide, tight)
         c = min(max(plan.M // 3 + 2, 6), 120)

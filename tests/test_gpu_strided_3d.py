@@ -1,8 +1,6 @@
 """GPU parity of the two widened layer forms: column stride as a sum over packed column
 phases (polyphase) and the three-dimensional layer, through the C ABI vs the int64 oracle,
 bit-exact.  Every case also runs with the scalar-register kernel forced."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -14,19 +12,17 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2208_00763_amd as hk
+    import gpu_util
     from gpu_util import run_conv2d, run_conv3d, dnn_plan
 
 
 @pytest.fixture(params=["default", "scalar_register_kernel"])
 def kernel_choice(request):
-    old = os.environ.get("HIKONV_CONV2D_KERNEL")
+    old = dict(gpu_util.LAYER_DEFAULTS)
     if request.param == "scalar_register_kernel":
-        os.environ["HIKONV_CONV2D_KERNEL"] = "2"
+        gpu_util.LAYER_DEFAULTS.update(kernel=hk.KERNEL_SREG)
     yield request.param
-    if old is None:
-        os.environ.pop("HIKONV_CONV2D_KERNEL", None)
-    else:
-        os.environ["HIKONV_CONV2D_KERNEL"] = old
+    gpu_util.LAYER_DEFAULTS.update(old)
 
 
 def _values(tag, bits, a_s, w_s, xshape, wshape):
@@ -47,8 +43,8 @@ def _plans(bits, a_s, w_s, kw, stride, wide=True):
             except hk.HikonvError as e:
                 assert e.code == hk.ENOPLAN
                 continue
-            if plan.N <= 8:
-                out.append((label, plan))
+            assert plan.N <= hk.LAYER_MAX_N
+            out.append((label, plan))
     return out
 
 

@@ -66,8 +66,6 @@ def test_conv2d_tight_plans_random_and_extreme(wide):
             plan = dnn_plan(bits, bits, a_s, w_s, 3, 0, wide, tight=1)
         except hk.HikonvError:
             continue
-        if plan.N > 8:
-            continue
         c = min(max(plan.M // 3 + 2, 8), 160)      # at least one full split group of (channel, row) terms
         x, w = wl.conv2d_case(bits, a_s, w_s, 1, c, 9, 21, 10, 3, 3, tag="tight2")
         assert np.array_equal(run_conv2d(plan, x, w, 1, 1), direct.conv2d(x, w, 1, 1)), (bits, a_s, w_s, plan)
