@@ -29,39 +29,125 @@ __global__ __launch_bounds__(256) void k_compact(const uint8_t *x, int64_t rows,
     out[idx] = word;
 }
 
-// ReLU + requantise (+ 2x2 max-pool), one thread per output byte (INT8) or dword (bit-dense)
+// Runtime feature compression, streaming form (Section "Single convolver architecture": the
+// unused bits of quantised features are dropped in storage).  Rows whose bytes start on dword
+// boundaries (x and len multiples of 4).  A thread turns 16 consecutive values (one 16-byte
+// load; 32 values for one-bit containers) into 16*C bits with a few shift-or steps per input
+// dword and stores them as one 16/8/4-byte vector; grid.y walks the rows, so nothing is divided.
+typedef uint32_t u32x4_dw4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2_dw4 __attribute__((ext_vector_type(2), aligned(4)));
+
+// the C-bit containers of the four byte values of w, gathered into the low 4*C bits
+template <int C>
+__device__ __forceinline__ uint32_t gather_bytes(uint32_t w, uint32_t vmask4, int bipolar)
+{
+    if (bipolar) {
+        // bit 1 for values > 0 (as int8): some low bit set and the sign bit clear
+        const uint32_t nz = ((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) & 0x80808080u;
+        w = (nz & ~w) >> 7;
+    } else {
+        w &= vmask4;
+    }
+    if (C == 8) return w;
+    if (C == 4) {
+        w = (w | (w >> 4)) & 0x00ff00ffu;
+        return (w | (w >> 8)) & 0xffffu;
+    }
+    if (C == 2) {
+        w = (w | (w >> 6)) & 0x000f000fu;
+        return (w | (w >> 12)) & 0xffu;
+    }
+    // C == 1: bit 0 of byte i goes to bit 28 + i of the product (all partial products fall on distinct bits)
+    return ((w & 0x01010101u) * 0x10204080u) >> 28;
+}
+
+template <int C>
+__global__ __launch_bounds__(256) void k_compact_rows(const uint8_t *x, int64_t rows, int len, int b, int bipolar,
+                                                      uint32_t *out, int row_dwords)
+{
+    constexpr int IN_DW = C == 1 ? 8 : 4;           // input dwords per thread
+    constexpr int OUT_DW = IN_DW * C / 8;           // output dwords per thread: 1, 1, 2, 4
+    const uint32_t vmask4 = ((1u << b) - 1u) * 0x01010101u;
+    const int q = blockIdx.x * 256 + threadIdx.x;   // this thread's group of IN_DW*4 values in the row
+    const int i0 = q * IN_DW * 4;
+    if (i0 >= len) return;
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        const uint8_t *row = x + r * len;
+        uint32_t in[IN_DW];
+        if (i0 + IN_DW * 4 <= len) {
+#pragma unroll
+            for (int v = 0; v < IN_DW / 4; ++v) {
+                const u32x4_dw4 t = *reinterpret_cast<const u32x4_dw4 *>(row + i0 + 16 * v);
+                in[4 * v] = t.x, in[4 * v + 1] = t.y, in[4 * v + 2] = t.z, in[4 * v + 3] = t.w;
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < IN_DW; ++d) {
+                uint32_t w = 0;
+                for (int t = 0; t < 4; ++t)
+                    if (i0 + 4 * d + t < len) w |= (uint32_t)row[i0 + 4 * d + t] << (8 * t);
+                in[d] = w;
+            }
+        }
+        uint32_t o[OUT_DW];
+#pragma unroll
+        for (int k = 0; k < OUT_DW; ++k) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int d = 0; d < IN_DW / OUT_DW; ++d)
+                word |= gather_bytes<C>(in[k * (IN_DW / OUT_DW) + d], vmask4, bipolar) << (4 * C * d);
+            o[k] = word;
+        }
+        uint32_t *dst = out + r * (int64_t)row_dwords + (int64_t)q * OUT_DW;
+        const int left = row_dwords - q * OUT_DW;   // dwords of the row from here on (>= 1)
+        if (OUT_DW == 4 && left >= 4) {
+            *reinterpret_cast<u32x4_dw4 *>(dst) = u32x4_dw4{o[0], o[1], o[2], o[3]};
+        } else if (OUT_DW == 2 && left >= 2) {
+            *reinterpret_cast<u32x2_dw4 *>(dst) = u32x2_dw4{o[0], o[1]};
+        } else {
+#pragma unroll
+            for (int k = 0; k < OUT_DW; ++k)
+                if (k < left) dst[k] = o[k];
+        }
+    }
+}
+
+// ReLU + requantise (+ 2x2 max-pool).  grid.y walks the output rows (image, channel, row), a
+// thread makes one output dword (bit-dense) or four output bytes (one value per byte); one
+// 32-bit division per thread finds the row's plane.
+template <bool POOL, bool BITDENSE>
 __global__ __launch_bounds__(256) void k_epilogue(EpilogueArgs p)
 {
-    const int per = p.out_format == HIKONV_FMT_BITDENSE ? 32 / p.c : 1;
-    const int64_t units_per_row = p.out_format == HIKONV_FMT_BITDENSE ? p.out_row_bytes / 4 : p.Wo;
-    const int64_t rows = (int64_t)p.Nimg * p.C * p.Ho;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= rows * units_per_row) return;
-    const int64_t row = idx / units_per_row, j = idx % units_per_row;
-    const int64_t nc = row / p.Ho;
-    const int h = (int)(row % p.Ho);
-    const int32_t *src = p.acc + nc * p.H * p.W;
-    uint32_t word = 0;
-    for (int t = 0; t < per; ++t) {
-        int64_t w = j * per + t;
-        if (w >= p.Wo) break;
-        int32_t v;
-        if (p.pool) {
-            const int32_t *s0 = src + (int64_t)(2 * h) * p.W + 2 * w;
-            int32_t a = s0[0], b = s0[1], cc = s0[p.W], d = s0[p.W + 1];
-            v = max(max(a, b), max(cc, d));
-        } else {
-            v = src[(int64_t)h * p.W + w];
+    const int per = BITDENSE ? 32 / p.c : 4;         // values per thread
+    const int j = blockIdx.x * 256 + threadIdx.x;    // this thread's unit in the row
+    const int w0 = j * per;
+    if (w0 >= p.Wo) return;
+    const uint32_t total_rows = (uint32_t)p.Nimg * p.C * p.Ho;
+    for (uint32_t row = blockIdx.y; row < total_rows; row += gridDim.y) {
+        const uint32_t nc = row / (uint32_t)p.Ho;
+        const int h = (int)(row - nc * (uint32_t)p.Ho);
+        const int32_t *src = p.acc + (int64_t)nc * p.H * p.W + (POOL ? (int64_t)(2 * h) * p.W : (int64_t)h * p.W);
+        uint32_t word = 0;
+        for (int t = 0; t < per; ++t) {
+            const int w = w0 + t;
+            if (w >= p.Wo) break;
+            int32_t v;
+            if (POOL) {
+                const int32_t *s0 = src + 2 * w;
+                v = max(max(s0[0], s0[1]), max(s0[p.W], s0[p.W + 1]));
+            } else {
+                v = src[w];
+            }
+            v = min(max(v, 0) >> p.shift, p.qmax);
+            word |= (uint32_t)v << (t * (BITDENSE ? p.c : 8));
         }
-        v = v < 0 ? 0 : v;
-        v >>= p.shift;
-        v = v > p.qmax ? p.qmax : v;
-        word |= (uint32_t)v << (t * p.c);
+        if (BITDENSE) {
+            reinterpret_cast<uint32_t *>(p.out + (int64_t)row * p.out_row_bytes)[j] = word;
+        } else {
+            uint8_t *dst = p.out + (int64_t)row * p.Wo + w0;
+            for (int t = 0; t < 4 && w0 + t < p.Wo; ++t) dst[t] = (uint8_t)(word >> (8 * t));
+        }
     }
-    if (p.out_format == HIKONV_FMT_BITDENSE)
-        reinterpret_cast<uint32_t *>(p.out + row * p.out_row_bytes)[j] = word;
-    else
-        p.out[row * p.Wo + j] = (uint8_t)word;
 }
 
 // ---- micro-benchmarks --------------------------------------------------------------
@@ -81,21 +167,30 @@ __global__ __launch_bounds__(256) void k_ubench_valu(int iters, uint32_t *buf, u
         for (int u = 0; u < 8; ++u) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                // every chain feeds on its neighbour so that nothing folds into a closed form
+                // One named instruction per slot, written as the instruction itself so that the rate
+                // printed next to a mnemonic is that instruction's; every chain feeds on its neighbour.
                 const int nb = (i + 1) & 7;
-                if (KIND == HIKONV_UB_MAD_U32_U24) a[i] = __umul24(a[i], a[nb]) + s2;
-                if (KIND == HIKONV_UB_MAD_I32_I24) a[i] = (uint32_t)(__mul24((int)a[i], (int)a[nb]) + (int)s2);
-                if (KIND == HIKONV_UB_MAD_U64_U32) w[i] = (uint64_t)(uint32_t)w[nb] * (uint64_t)s1 + w[i];
-                if (KIND == HIKONV_UB_MAD_I64_I32)
-                    w[i] = (uint64_t)((int64_t)(int32_t)w[nb] * (int64_t)(int32_t)s1 + (int64_t)w[i]);
-                if (KIND == HIKONV_UB_MUL_LO_U32) a[i] = a[i] * a[nb];
-                if (KIND == HIKONV_UB_BFE_U32) a[i] = __builtin_amdgcn_ubfe(a[nb], s2, s1 + 20u) + 0u;
-                if (KIND == HIKONV_UB_LSHR_B64) w[i] = w[nb] >> s2;
-                if (KIND == HIKONV_UB_DPP_MOV) a[i] = lane_shr1(a[nb]);
-                if (KIND == HIKONV_UB_ADD_U32) a[i] = a[i] + a[nb];
-                if (KIND == HIKONV_UB_ADD_U64) w[i] = w[i] + w[nb];
-                if (KIND == HIKONV_UB_ALIGNBIT) a[i] = funnel_shr(a[i], a[nb], s2);
-                if (KIND == HIKONV_UB_AND_B32) a[i] = a[i] & a[nb];
+                if (KIND == HIKONV_UB_MAD_U32_U24)
+                    asm volatile("v_mad_u32_u24 %0, %0, %1, %2" : "+v"(a[i]) : "v"(a[nb]), "v"(s2));
+                if (KIND == HIKONV_UB_MAD_I32_I24)
+                    asm volatile("v_mad_i32_i24 %0, %0, %1, %2" : "+v"(a[i]) : "v"(a[nb]), "v"(s2));
+                if (KIND == HIKONV_UB_MAD_U64_U32) {
+                    uint64_t carry;
+                    asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(w[i]), "=s"(carry) : "v"((uint32_t)w[nb]), "v"(s1));
+                }
+                if (KIND == HIKONV_UB_MAD_I64_I32) {
+                    uint64_t carry;
+                    asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(w[i]), "=s"(carry) : "v"((uint32_t)w[nb]), "v"(s1));
+                }
+                if (KIND == HIKONV_UB_MUL_LO_U32) asm volatile("v_mul_lo_u32 %0, %0, %1" : "+v"(a[i]) : "v"(a[nb]));
+                if (KIND == HIKONV_UB_BFE_U32) asm volatile("v_bfe_u32 %0, %1, %2, %3" : "=v"(a[i]) : "v"(a[nb]), "v"(s2), "v"(s1 + 20u));
+                if (KIND == HIKONV_UB_LSHR_B64) asm volatile("v_lshrrev_b64 %0, %1, %2" : "=v"(w[i]) : "v"(s2), "v"(w[nb]));
+                if (KIND == HIKONV_UB_DPP_MOV)
+                    asm volatile("v_mov_b32_dpp %0, %1 wave_shr:1 row_mask:0xf bank_mask:0xf" : "+v"(a[i]) : "v"(a[nb]));
+                if (KIND == HIKONV_UB_ADD_U32) asm volatile("v_add_u32 %0, %0, %1" : "+v"(a[i]) : "v"(a[nb]));
+                if (KIND == HIKONV_UB_ADD_U64) asm volatile("v_lshl_add_u64 %0, %0, 0, %1" : "+v"(w[i]) : "v"(w[nb]));
+                if (KIND == HIKONV_UB_ALIGNBIT) asm volatile("v_alignbit_b32 %0, %0, %1, %2" : "+v"(a[i]) : "v"(a[nb]), "v"(s2));
+                if (KIND == HIKONV_UB_AND_B32) asm volatile("v_and_b32 %0, %0, %1" : "+v"(a[i]) : "v"(a[nb]));
             }
         }
     }
@@ -166,21 +261,42 @@ hipError_t launch_compact(const uint8_t *x, int64_t rows, int64_t len, int bits,
 {
     const int64_t total = rows * row_dwords;
     if (total <= 0) return hipSuccess;
+    const int c = container_bits(bits);
+    // streaming form: every row starts on a dword boundary and positions inside a row fit 32 bits
+    if ((reinterpret_cast<uintptr_t>(x) & 3) == 0 && (len & 3) == 0 && len < (1LL << 30)) {
+        const int per_thread = c == 1 ? 32 : 16;
+        dim3 g((unsigned)ceil_div(len, (int64_t)256 * per_thread), (unsigned)(rows < 65535 ? rows : 65535));
+        switch (c) {
+        case 1: hipLaunchKernelGGL(k_compact_rows<1>, g, dim3(256), 0, stream, x, rows, (int)len, bits, bipolar, out, (int)row_dwords); break;
+        case 2: hipLaunchKernelGGL(k_compact_rows<2>, g, dim3(256), 0, stream, x, rows, (int)len, bits, bipolar, out, (int)row_dwords); break;
+        case 4: hipLaunchKernelGGL(k_compact_rows<4>, g, dim3(256), 0, stream, x, rows, (int)len, bits, bipolar, out, (int)row_dwords); break;
+        default: hipLaunchKernelGGL(k_compact_rows<8>, g, dim3(256), 0, stream, x, rows, (int)len, bits, bipolar, out, (int)row_dwords); break;
+        }
+        return hipGetLastError();
+    }
     const int64_t grid = ceil_div(total, 256);
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_compact, dim3((unsigned)grid), dim3(256), 0, stream, x, rows, len, bits,
-                       container_bits(bits), bipolar, out, row_dwords);
+    hipLaunchKernelGGL(k_compact, dim3((unsigned)grid), dim3(256), 0, stream, x, rows, len, bits, c, bipolar, out,
+                       row_dwords);
     return hipGetLastError();
 }
 
 hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t stream)
 {
-    const int64_t units = a.out_format == HIKONV_FMT_BITDENSE ? a.out_row_bytes / 4 : a.Wo;
-    const int64_t total = (int64_t)a.Nimg * a.C * a.Ho * units;
-    if (total <= 0) return hipSuccess;
-    const int64_t grid = ceil_div(total, 256);
-    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_epilogue, dim3((unsigned)grid), dim3(256), 0, stream, a);
+    const bool bitdense = a.out_format == HIKONV_FMT_BITDENSE;
+    const int64_t units = bitdense ? a.out_row_bytes / 4 : ceil_div(a.Wo, 4);
+    const int64_t rows = (int64_t)a.Nimg * a.C * a.Ho;
+    if (rows <= 0 || units <= 0) return hipSuccess;
+    if (rows >= (1LL << 31) || a.Wo >= (1 << 30)) return hipErrorInvalidValue;
+    dim3 g((unsigned)ceil_div(units, 256), (unsigned)(rows < 65535 ? rows : 65535));
+    if (a.pool && bitdense)
+        hipLaunchKernelGGL((k_epilogue<true, true>), g, dim3(256), 0, stream, a);
+    else if (a.pool)
+        hipLaunchKernelGGL((k_epilogue<true, false>), g, dim3(256), 0, stream, a);
+    else if (bitdense)
+        hipLaunchKernelGGL((k_epilogue<false, true>), g, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((k_epilogue<false, false>), g, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -14,6 +14,8 @@
 //  * outside single-multiplier mode K <= N+1 is required (one-neighbour overlap-add);
 //  * on request ("tight") the slice is the smallest one the exact check accepts, not
 //    p+q+G_b: e.g. 3 signed 4-bit products sum to at most 192 in magnitude, which fits 9 bits.
+#include <initializer_list>
+
 #include "hikonv_internal.h"
 
 namespace {

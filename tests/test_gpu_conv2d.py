@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 if torch.cuda.is_available():
     import paper_2208_00763_amd as hk
     from paper_2208_00763_amd.cnn import PackedCnn, UnpackedCnn
-    from gpu_util import run_conv2d, dnn_plan, dev, compact
+    from gpu_util import run_conv2d, dnn_plan, dev, compact, Guarded
 
 SHAPES = [  # n, c, h, w, co, kh, kw, stride, pad
     (1, 3, 5, 7, 2, 3, 3, 1, 1),
@@ -135,31 +135,44 @@ def test_conv2d_unpacked_baseline():
 
 
 def test_compact_matches_oracle_layout():
+    # row lengths that are and are not multiples of 4 (the streaming kernel takes the first kind),
+    # of 16 and of 32; rows ending inside a thread's group of values; one row longer than a workgroup's reach
     for bits in range(1, 9):
         for signed in (False, True):
-            x = wl.uniform_values(wl.rng_for("cp", bits, signed), (5, 1003), bits, signed)
-            got = compact(x, bits).cpu().numpy()
-            ref = direct.bitdense_pack(x, bits)
-            assert np.array_equal(got[:ref.size].reshape(ref.shape), ref)
+            for rows, length in ((5, 1003), (3, 4), (7, 16), (4, 20), (3, 36), (5, 1000), (2, 1028), (3, 8192 + 44),
+                                 (70000, 12)):
+                x = wl.uniform_values(wl.rng_for("cp", bits, signed, length), (rows, length), bits, signed)
+                got = compact(x, bits).cpu().numpy()        # guard regions on both sides are checked inside
+                ref = direct.bitdense_pack(x, bits)
+                assert got.size == ref.size
+                assert np.array_equal(got.reshape(ref.shape), ref), (bits, signed, rows, length)
+    # {-1,+1} rows: bit 1 where the value is positive; any int8 value is a legal input byte
+    for rows, length in ((3, 64), (5, 100), (2, 1003)):
+        x = wl.bipolar_values(wl.rng_for("cpb", length), (rows, length))
+        ref = direct.bitdense_pack(((x > 0).astype(np.int8)), 1)
+        assert np.array_equal(compact(x, 1, bipolar=True).cpu().numpy().reshape(ref.shape), ref)
+        odd = wl.rng_for("cpo", length).integers(-128, 128, (rows, length)).astype(np.int8)
+        ref = direct.bitdense_pack(((odd > 0).astype(np.int8)), 1)
+        assert np.array_equal(compact(odd, 1, bipolar=True).cpu().numpy().reshape(ref.shape), ref)
 
 
 def test_epilogue_matches_oracle():
     rng = np.random.default_rng(3)
     for (n, c, h, w, shift, pool) in ((1, 3, 6, 10, 3, True), (2, 5, 7, 9, 0, False), (1, 4, 9, 17, 5, True),
-                                      (1, 2, 4, 64, 2, False)):
+                                      (1, 2, 4, 64, 2, False), (1, 1, 2, 2100, 1, True), (1, 2, 3, 1031, 4, False),
+                                      (2, 40000, 2, 2, 0, True), (1, 3, 5, 1, 0, False)):
         acc = rng.integers(-3000, 3000, size=(n, c, h, w), dtype=np.int32)
         q = direct.relu_requant(acc, shift, 15)
         if pool:
             q = direct.maxpool2x2(q)
         ho, wo = q.shape[2], q.shape[3]
         ref_bd = direct.bitdense_pack(q.reshape(n * c * ho, wo), 4)
-        out_bd = torch.zeros(ref_bd.size, dtype=torch.uint8, device="cuda")
-        hk.hikonv_epilogue(dev(acc), n, c, h, w, shift, 15, pool, 4, hk.FMT_BITDENSE, out_bd)
-        out_i8 = torch.zeros(n * c * ho * wo + 4, dtype=torch.uint8, device="cuda")
-        hk.hikonv_epilogue(dev(acc), n, c, h, w, shift, 15, pool, 4, hk.FMT_INT8, out_i8)
-        torch.cuda.synchronize()
-        assert np.array_equal(out_bd.cpu().numpy().reshape(ref_bd.shape), ref_bd)
-        assert np.array_equal(out_i8.cpu().numpy()[:q.size].reshape(q.shape), q.view(np.uint8))
+        out_bd = Guarded(ref_bd.size, torch.uint8, 0xA5)
+        hk.hikonv_epilogue(dev(acc), n, c, h, w, shift, 15, pool, 4, hk.FMT_BITDENSE, out_bd.view)
+        out_i8 = Guarded(n * c * ho * wo, torch.uint8, 0xA5)
+        hk.hikonv_epilogue(dev(acc), n, c, h, w, shift, 15, pool, 4, hk.FMT_INT8, out_i8.view)
+        assert np.array_equal(out_bd.result().reshape(ref_bd.shape), ref_bd), (n, c, h, w, pool)
+        assert np.array_equal(out_i8.result().reshape(q.shape), q.view(np.uint8)), (n, c, h, w, pool)
 
 
 def oracle_cnn(x, weights, specs):

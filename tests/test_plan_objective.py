@@ -168,6 +168,15 @@ def test_max_n_bounds_layer_plans():
                                 max_N=hk.LAYER_MAX_N)
     assert bounded.N == hk.LAYER_MAX_N and bounded.paper_exact == 0
     assert hk.hikonv_plan_check(bounded) == hk.OK
+    # the layer entry points refuse the unbounded plan on the host, before anything is launched
+    # (no device pointer is touched: the arguments here are null), and size a workspace for the bounded one
+    import ctypes as C
+    assert hk.hikonv_conv2d_workspace_bytes(free, 1, 4, 8, 8, 8, 3, 3, 1, 1, False) == 0
+    assert hk.hikonv_conv2d_workspace_bytes(bounded, 1, 4, 8, 8, 8, 3, 3, 1, 1, False) > 0
+    rc = hk.lib.hikonv_conv2d(C.byref(free), None, hk.FMT_INT8, 1, 4, 8, 8, None, 8, 3, 3, 1, 1, None, 0, None, None)
+    assert rc == hk.EUNSUPPORTED
+    rc = hk.lib.hikonv_conv2d_noalloc(C.byref(free), None, hk.FMT_INT8, 1, 4, 8, 8, None, 8, 3, 3, 1, 1, None, None)
+    assert rc == hk.EUNSUPPORTED
     for b, m in itertools.product(range(1, 9), (1, 4, 16, 0)):
         p = hk.hikonv_plan_ex(bits_a=b, bits_w=b, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=m, taps=3, max_N=5)
         assert 1 <= p.N <= 5
