@@ -65,6 +65,9 @@ def read_profile_json(name):
     return data
 
 
+CONV1D_KERNEL = {"form": 0}   # --kernel: kernel form asked for in the 1-D plans (0 = the library's choice)
+
+
 def conv1d_case(hk, wl, bits, signed, taps=TAPS):
     """Device buffers and launch closures for one case of the sweep."""
     import torch
@@ -79,7 +82,7 @@ def conv1d_case(hk, wl, bits, signed, taps=TAPS):
     out_len = LENGTH - TAPS + 1
     y = torch.empty(ROWS * out_len, dtype=torch.int32, device="cuda")
     plan = hk.hikonv_plan_ex(bits_a=bits, bits_w=bits, a_signed=int(signed), w_signed=int(signed), L_A=32, L_B=32,
-                             L_acc=64, mode=hk.MODE_CONV1D, taps=TAPS)
+                             L_acc=64, mode=hk.MODE_CONV1D, taps=TAPS, kernel=CONV1D_KERNEL["form"])
 
     def packed():
         hk.hikonv_conv1d(plan, x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d, TAPS, hk.OUT_VALID, y)
@@ -423,6 +426,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="time all 48 cases of the 1-D bitwidth sweep (packed and unpacked), print them as JSON "
                          "and as a table, then exit")
+    ap.add_argument("--kernel", choices=["auto", "lanes", "window"], default="auto",
+                    help="kernel form asked for in the 1-D plans: the library's choice, one lane per packed block "
+                         "with lane exchange, or one lane per output quad")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain copy kernel of known size (512 MiB read + 512 MiB written, 3 launches) "
                          "so that HBM byte counters collected by a profiler can be scaled")
@@ -439,13 +445,16 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
 
+    CONV1D_KERNEL["form"] = {"auto": hk.KERNEL_AUTO, "lanes": hk.KERNEL_LANES, "window": hk.KERNEL_WINDOW}[args.kernel]
+
     if args.ubench:
         print(json.dumps(microbench(hk)))
         return 0
 
     if args.sweep:
         rows = sweep(hk, wl, max(3, args.steps // 5))
-        print(json.dumps({"metric": "1-D bitwidth sweep, 4096 rows x 65536, valid, bit-dense input", "cases": rows}))
+        print(json.dumps({"metric": "1-D bitwidth sweep, 4096 rows x 65536, valid, bit-dense input",
+                          "kernel": args.kernel, "cases": rows}))
         print("bits signed taps  N  K  S chunks  packed_ms unpacked_ms  speedup   GOPS  GB/s  frac_of_8TB/s", file=sys.stderr)
         for r in rows:
             print("%4d %6s %4d %2d %2d %2d %6d %10.4f %11.4f %8.2f %6.0f %5.0f %8.3f" % (

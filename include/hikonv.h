@@ -69,10 +69,15 @@ extern "C" {
                                    /* exchanging, splitting and storing calibrated on MI355X counters, bounded  */
                                    /* below by the slots that fit under the HBM time of its bytes               */
 
-/* Layer kernel form (hikonv_plan_t.kernel); AUTO lets the library choose by layer size. */
+/* Kernel form (hikonv_plan_t.kernel); AUTO lets the library choose (layers: by size). */
 #define HIKONV_KERNEL_AUTO 0
-#define HIKONV_KERNEL_LDS 1  /* weight words staged in LDS (small layers)              */
-#define HIKONV_KERNEL_SREG 2 /* weight words in scalar registers wherever the plan allows it */
+#define HIKONV_KERNEL_LDS 1    /* layers: weight words staged in LDS (small layers)                      */
+#define HIKONV_KERNEL_SREG 2   /* layers: weight words in scalar registers wherever the plan allows it   */
+#define HIKONV_KERNEL_LANES 3  /* hikonv_conv1d: one lane = one packed block, high parts exchanged between */
+                               /* neighbouring lanes, outputs staged per wave                             */
+#define HIKONV_KERNEL_WINDOW 4 /* hikonv_conv1d: one lane = one aligned quad of outputs, the blocks that  */
+                               /* cover it multiplied one after the other (AUTO takes it where it applies: */
+                               /* at most 7 taps, K = min(taps, N), N in {2,3,4,5,6,8,11})                 */
 
 /* hikonv_plan_t.flags */
 #define HIKONV_F_STORES64 1 /* layer kernels: address every output store with 64 bits (the library does this by */
@@ -109,7 +114,7 @@ typedef struct hikonv_plan_t {
                                 /* this many bits and stored bit-dense (hikonv_conv1d_requant)       */
     int32_t max_N;              /* 0: no limit; else only plans with N <= max_N are considered       */
                                 /* (HIKONV_LAYER_MAX_N for plans meant for hikonv_conv2d/conv3d)     */
-    int32_t kernel;             /* layer calls: HIKONV_KERNEL_*; copied through by the planner       */
+    int32_t kernel;             /* HIKONV_KERNEL_*; copied through by the planner                    */
     int32_t flags;              /* HIKONV_F_*; copied through by the planner                         */
     /* result */
     int32_t N, K, S, G_b;       /* elements per A word, taps per B word, slice bits, guard bits      */

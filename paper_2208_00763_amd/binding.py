@@ -21,7 +21,7 @@ UB_MAD_I32_I24, UB_MAD_I64_I32, UB_ADD_U64, UB_ALIGNBIT, UB_AND_B32 = range(7, 1
 UB_HBM_WRITE, UB_HBM_COPY, UB_HBM_READ, UB_HBM_WRITE_NT, UB_HBM_WRITE_RUNS = 16, 17, 18, 19, 20
 
 OBJ_PAPER_OPS, OBJ_MEASURED_COST = 0, 1
-KERNEL_AUTO, KERNEL_LDS, KERNEL_SREG = 0, 1, 2
+KERNEL_AUTO, KERNEL_LDS, KERNEL_SREG, KERNEL_LANES, KERNEL_WINDOW = 0, 1, 2, 3, 4
 F_STORES64 = 1
 LAYER_MAX_N = 8
 

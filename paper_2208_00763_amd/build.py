@@ -13,6 +13,14 @@ SOURCES = [
     "hikonv_api.hip",
     "hikonv_conv1d.hip",
     "hikonv_conv1d_fast.hip",
+    "hikonv_conv1d_window.hip",
+    "hikonv_conv1d_window_t1.hip",
+    "hikonv_conv1d_window_t2.hip",
+    "hikonv_conv1d_window_t3.hip",
+    "hikonv_conv1d_window_t4.hip",
+    "hikonv_conv1d_window_t5.hip",
+    "hikonv_conv1d_window_t6.hip",
+    "hikonv_conv1d_window_t7.hip",
     "hikonv_conv1d_requant.hip",
     "hikonv_conv1d_requant_aligned.hip",
     "hikonv_conv2d.hip",

@@ -287,6 +287,7 @@ int layer_impl(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N
     // plan->kernel: HIKONV_KERNEL_LDS = LDS-staged kernels only, HIKONV_KERNEL_SREG =
     // scalar-register kernel wherever the plan allows it, HIKONV_KERNEL_AUTO = by layer size.
     const int forced_kernel = plan->kernel;
+    if (forced_kernel > HIKONV_KERNEL_SREG) return HIKONV_EINVAL;
     ca.sreg = 0;
     if (forced_kernel != 1 && Co >= 8 &&
         conv2d_sreg_applicable(plan->N, plan->K, split_terms, wide)) {
@@ -378,6 +379,16 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
     const int64_t m_end = out_mode == HIKONV_OUT_VALID ? len : len + taps - 1;
     a.n_blocks = ceil_div(m_end, a.N);
     const bool any_signed = plan->a_signed || plan->w_signed;
+    if (plan->kernel != HIKONV_KERNEL_AUTO && plan->kernel != HIKONV_KERNEL_LANES && plan->kernel != HIKONV_KERNEL_WINDOW)
+        return HIKONV_EINVAL;
+    // Kernel form: a lane per aligned output quad where the plan allows it (its stores follow
+    // the order of y across the whole workgroup, which the memory system takes faster than
+    // per-wave runs); else a lane per block with the high parts exchanged between lanes.
+    if (plan->kernel != HIKONV_KERNEL_LANES && conv1d_window_applicable(a)) {
+        a.y_phase = (int)((reinterpret_cast<uintptr_t>(y_dev) >> 2) & 31);
+        return hip_result(launch_conv1d_window(a, plan->a_signed != 0, any_signed, static_cast<hipStream_t>(stream)));
+    }
+    if (plan->kernel == HIKONV_KERNEL_WINDOW) return HIKONV_EUNSUPPORTED;
     if (conv1d_fast_applicable(a)) {
         a.CH = 0;
         a.aligned_runs = 1;     // a wave's output interval ends on 128-byte lines of y

@@ -1,0 +1,48 @@
+// Launcher of the quad-per-lane packed 1-D kernel (hikonv_conv1d_window.h); the kernels are
+// instantiated per tap count in hikonv_conv1d_window_t*.hip.
+#include "hikonv_conv1d_window.h"
+
+namespace hikonv {
+
+hipError_t launch_window_t1(const Conv1dArgs &, bool, bool, dim3, hipStream_t);
+hipError_t launch_window_t2(const Conv1dArgs &, bool, bool, dim3, hipStream_t);
+hipError_t launch_window_t3(const Conv1dArgs &, bool, bool, dim3, hipStream_t);
+hipError_t launch_window_t4(const Conv1dArgs &, bool, bool, dim3, hipStream_t);
+hipError_t launch_window_t5(const Conv1dArgs &, bool, bool, dim3, hipStream_t);
+hipError_t launch_window_t6(const Conv1dArgs &, bool, bool, dim3, hipStream_t);
+hipError_t launch_window_t7(const Conv1dArgs &, bool, bool, dim3, hipStream_t);
+
+// Plans this form covers: up to 7 taps, K = min(taps, N) taps per B word (so that a kernel wider
+// than one B word meets whole blocks), N one of the slice counts the planner produces for 32-bit
+// words, a window of taps + 3 containers within 96 bits, positions inside a row within 32 bits.
+bool conv1d_window_applicable(const Conv1dArgs &a)
+{
+    if (a.taps < 1 || a.taps > 7) return false;
+    if (a.N != 2 && a.N != 3 && a.N != 4 && a.N != 5 && a.N != 6 && a.N != 8 && a.N != 11) return false;
+    if (a.Kp != (a.taps < a.N ? a.taps : a.N) || a.chunks != (a.taps + a.Kp - 1) / a.Kp) return false;
+    if (a.N * a.c > 32) return false;                        // a block's containers come out of one dword
+    if ((a.taps + 3) * a.c > 96) return false;
+    if ((a.taps + 3) * a.c > 64 && (a.c != 8 || a.N > 3)) return false;
+    if (a.total_bytes < 16) return false;                    // every lane may read the buffer's first four dwords
+    return (a.len + (1 << 18)) * a.c < (1LL << 31);
+}
+
+hipError_t launch_conv1d_window(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
+{
+    if (!conv1d_window_applicable(a)) return hipErrorInvalidValue;
+    const int64_t nquads = (a.out_len + 6) / 4;
+    const int64_t gx = ceil_div(nquads + 7, (int64_t)kWindowThreads * kWindowQuads); // lanes are shifted by up to 7 quads
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
+    switch (a.taps) {
+    case 1: return launch_window_t1(a, a_signed, any_signed, g, stream);
+    case 2: return launch_window_t2(a, a_signed, any_signed, g, stream);
+    case 3: return launch_window_t3(a, a_signed, any_signed, g, stream);
+    case 4: return launch_window_t4(a, a_signed, any_signed, g, stream);
+    case 5: return launch_window_t5(a, a_signed, any_signed, g, stream);
+    case 6: return launch_window_t6(a, a_signed, any_signed, g, stream);
+    default: return launch_window_t7(a, a_signed, any_signed, g, stream);
+    }
+}
+
+} // namespace hikonv

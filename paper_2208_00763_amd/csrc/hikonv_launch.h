@@ -45,6 +45,9 @@ bool conv1d_fast_applicable(const Conv1dArgs &a);
 int64_t conv1d_fast_runs_per_row(const Conv1dArgs &a);
 int64_t conv1d_fast_run_outputs(const Conv1dArgs &a); // outputs per line-aligned interval
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
+// one lane = one aligned output quad, blocks walked inside the lane (no LDS, no lane exchange)
+bool conv1d_window_applicable(const Conv1dArgs &a);
+hipError_t launch_conv1d_window(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
 // requantised bit-dense output: packed (streaming kernel for N <= 12 and N*c <= 32, a slow
 // general kernel for the other plans up to N = 32) and baseline
 int64_t conv1d_requant_run_outputs(int N, int c, int c_out);

@@ -184,10 +184,13 @@ struct Cand {
 // neighbour lane, cutting the word into fields and storing them cost a slot per instruction
 // too.  The model below counts VALU issue slots per output element for each kernel form.  The
 // coefficients are fitted to SQ_INSTS_VALU (wave instructions x 64 / outputs) of the kernels
-// on MI355X at 4096 rows x 65536, 3 taps; a DPP move counts 1.75 slots (it issues at 57 % of
-// the full rate), every other integer instruction the kernels use issues at 93-99 %.
+// on MI355X at 4096 rows x 65536, 3, 5 and 7 taps (every integer instruction the kernels use
+// issues at 87-99 % of the full rate, so an instruction is priced as one slot).
 //
-//   streaming kernel, int32 outputs (stride_elems = 1), per block of N outputs:
+//   quad-per-lane kernel, int32 outputs (taps <= 7, K = min(taps, N), N in {2,3,4,5,6,8,11}),
+//   per output: kWinBase + kWinTap*taps + kWinBlock*ceil((taps+3)/N)  [+ kWinSigned signed]
+//       (most of it index arithmetic and bounds tests per quad, not packed arithmetic)
+//   lane-per-block kernel, int32 outputs (the other stride_elems = 1 plans), per block of N outputs:
 //       kI32Block + kI32Elem*N  [+ N + 1 signed]  + per extra B word: kShareChunk when the
 //       delayed words come from the preceding lanes (K = N), else a second packing
 //   streaming kernel, requantised bit-dense outputs:
@@ -202,10 +205,18 @@ struct Cand {
 // A kernel cannot run faster than its bytes move: the price of a plan is bounded below by the
 // slots that pass during the HBM time of its algorithmic bytes per output at the published
 // peaks (8 TB/s, 256 CUs x 64 lanes x 2.4 GHz: 4.9 slots per byte).  Plans under that floor tie
-// and the one with fewer slots wins.
+// and Algorithm 1's own order decides among them.
 constexpr double kI32Block = 15.0, kI32Elem = 11.7;
 constexpr double kRqBlock = 21.0, kRqElem = 13.9;
 constexpr double kShareChunk = 4.2;
+constexpr double kWinBase = 10.2, kWinTap = 0.9, kWinBlock = 0.45, kWinSigned = 1.5;
+
+// plans the quad-per-lane int32 kernel takes (the launcher's rule, without the geometry)
+inline bool window_form(int taps, int n, int k)
+{
+    if (taps < 1 || taps > 7 || k != (taps < n ? taps : n)) return false;
+    return n == 2 || n == 3 || n == 4 || n == 5 || n == 6 || n == 8 || n == 11;
+}
 constexpr double kAlignedDword = 25.0;
 constexpr double kSlotsPerByte = 256.0 * 64.0 * 2.4e9 / 8.0e12;
 
@@ -230,6 +241,8 @@ double conv1d_slots(const Req &r, int n, int k, int chunks, int s, int stride)
         const double mac = nibble ? 2.0 : 1.0;
         return (2.0 * words + j * (mac * r.taps + requant + 1.5) + kAlignedDword) / per;
     }
+    if (r.out_bits == 0 && window_form(r.taps, n, k) && n * container_of(r.p) <= 32)
+        return kWinBase + kWinTap * r.taps + kWinBlock * ((r.taps + 3 + n - 1) / n) + (r.any_signed ? kWinSigned : 0.0);
     const bool share = chunks >= 2 && chunks <= 4 && k == n && n >= 2 && n <= 5;
     double block = r.out_bits > 0 ? kRqBlock + kRqElem * n : kI32Block + kI32Elem * n;
     if (r.any_signed) block += n + 1;
@@ -286,7 +299,11 @@ inline bool better(const Req &r, const Cand &c, const Cand &best)
     if (by_cost(r)) {
         const double pc = priced(r, c.cost), pb = priced(r, best.cost);
         if (pc != pb) return pc < pb;
-        return c.cost < best.cost; // both under the memory floor: fewer slots
+        // both under the memory floor: the kernel waits for HBM either way, and Algorithm 1's own
+        // order (most multiply-accumulates per multiply) decides; then fewer slots
+        if ((long long)c.n * best.chunks != (long long)best.n * c.chunks)
+            return (long long)c.n * best.chunks > (long long)best.n * c.chunks;
+        return c.cost < best.cost;
     }
     if (r.taps == 0)
         return (long long)c.n * c.k + (long long)(c.n - 1) * (c.k - 1) >
@@ -360,7 +377,7 @@ bool valid_request(const hikonv_plan_t &in)
     if (in.tight != 0 && in.tight != 1) return false;
     if (in.objective != HIKONV_OBJ_PAPER_OPS && in.objective != HIKONV_OBJ_MEASURED_COST) return false;
     if (in.out_bits < 0 || in.out_bits > 8 || in.max_N < 0 || in.max_N > 64) return false;
-    if (in.kernel < HIKONV_KERNEL_AUTO || in.kernel > HIKONV_KERNEL_SREG) return false;
+    if (in.kernel < HIKONV_KERNEL_AUTO || in.kernel > HIKONV_KERNEL_WINDOW) return false;
     if (in.flags & ~HIKONV_F_STORES64) return false;
     return true;
 }

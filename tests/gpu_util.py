@@ -41,9 +41,15 @@ class Guarded:
         return self.view.cpu().numpy()
 
 
+# kernel form that conv1d_plan puts into its plans (a fixture of the 1-D tests switches it, so that
+# every case runs on the lane-exchange kernel and on the library's own choice)
+CONV1D_DEFAULTS = {"kernel": 0}
+
+
 def conv1d_plan(bits, a_signed, w_signed, taps, tight=0, bits_w=None):
     return hk.hikonv_plan_ex(bits_a=bits, bits_w=bits_w or bits, a_signed=int(a_signed), w_signed=int(w_signed),
-                             L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=taps, tight=tight)
+                             L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=taps, tight=tight,
+                             kernel=CONV1D_DEFAULTS["kernel"])
 
 
 def compact(x_np: np.ndarray, bits: int, bipolar=False) -> torch.Tensor:

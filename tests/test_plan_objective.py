@@ -146,8 +146,8 @@ def test_cost_ranking_reproduces_the_measured_ranking():
 def test_int32_output_plans_sit_under_the_memory_floor():
     """With int32 outputs every candidate of the sweep needs fewer issue slots than pass during
     the HBM time of its 4 + c/8 bytes per output (4.9 slots per byte at the published peaks), so
-    the cost objective ties them at the floor and keeps the plan with the fewest slots; for the
-    3-tap sweep cases that is Algorithm 1's own plan."""
+    the cost objective ties them at the floor, where Algorithm 1's own order decides: the sweep's
+    int32 plans are the same under both objectives."""
     for b, signed in itertools.product(range(1, 9), (False, True)):
         cost = conv1d_request(b, signed, 3, hk.OBJ_MEASURED_COST)
         paper = conv1d_request(b, signed, 3, hk.OBJ_PAPER_OPS)
@@ -188,7 +188,7 @@ def test_request_fields_are_validated_and_copied_through():
     p = hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3,
                           kernel=hk.KERNEL_SREG, flags=hk.F_STORES64, max_N=8)
     assert (p.kernel, p.flags, p.max_N) == (hk.KERNEL_SREG, hk.F_STORES64, 8)
-    for bad in (dict(objective=2), dict(objective=-1), dict(out_bits=9), dict(out_bits=-1), dict(kernel=3),
+    for bad in (dict(objective=2), dict(objective=-1), dict(out_bits=9), dict(out_bits=-1), dict(kernel=5), dict(kernel=-1),
                 dict(flags=2), dict(max_N=-1)):
         with pytest.raises(hk.HikonvError) as e:
             hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3, **bad)
