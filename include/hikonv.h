@@ -361,6 +361,33 @@ int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H, int W, int
                          int next_stride, int next_pad, void *next_workspace_dev,
                          size_t next_workspace_bytes, void *stream);
 
+/*
+ * hikonv_conv2d_fused -- one kernel per layer of a chain (Section "Complete model
+ * evaluation": a layer is the convolution followed by activation and pooling).  The
+ * packed stride-1 layer of hikonv_conv2d_prepacked whose store stage also applies the
+ * epilogue of hikonv_epilogue_pack (q = min(qmax, max(acc, 0) >> shift), optional
+ * 2x2/stride-2 max-pool) and writes the result directly as the NEXT layer's packed
+ * activation words into next_workspace_dev, which that layer then takes with
+ * x_format = HIKONV_FMT_PACKED (same next_plan and geometry: input [N][Co][H'][W'],
+ * H' = Ho/2, W' = Wo/2 when pool, else Ho, Wo).  Neither the int32 accumulators nor
+ * a packing pass touch memory between the two layers.
+ *   y_dev: NCHW int32 accumulators of this layer, or NULL to skip storing them.
+ *   next_plan NULL: no following layer (y_dev required); shift, qmax, pool and the
+ *   next_* arguments are ignored.
+ *   x_format INT8 / BITDENSE: the input is packed into workspace_dev by a first
+ *   kernel, as in hikonv_conv2d; PACKED: workspace_dev already holds it.
+ * Covers plans with (L_A, L_B, L_acc) = (32, 32, 64) and N <= 4, layers with at most
+ * 16 waves per workgroup (2 rows with pooling x ceil(Co/8) channel tiles x 63-block
+ * row segments) and an int32 tile of rows x Co x Wo within 64 KiB, next plans with
+ * unsigned activations; anything else returns HIKONV_EUNSUPPORTED and the caller
+ * chains hikonv_conv2d_prepacked and hikonv_epilogue_pack instead.
+ */
+int hikonv_conv2d_fused(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H,
+                        int W, const void *w_packed_dev, int Co, int Kh, int Kw, int pad,
+                        void *workspace_dev, size_t workspace_bytes, int32_t *y_dev, int shift, int qmax,
+                        int pool, const hikonv_plan_t *next_plan, int next_Co, int next_Kh, int next_Kw,
+                        int next_pad, void *next_workspace_dev, size_t next_workspace_bytes, void *stream);
+
 const char *hikonv_strerror(int code);
 int hikonv_last_hip_error(void); /* hipError_t of the most recent failing HIP call in this thread */
 

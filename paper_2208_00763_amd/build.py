@@ -24,6 +24,7 @@ SOURCES = [
     "hikonv_conv1d_requant.hip",
     "hikonv_conv1d_requant_aligned.hip",
     "hikonv_conv2d.hip",
+    "hikonv_conv2d_fused.hip",
     "hikonv_conv2d_wide.hip",
     "hikonv_conv2d_narrow.hip",
     "hikonv_conv2d_sreg_unsigned.hip",

@@ -12,9 +12,14 @@ from . import binding as hk
 class PackedCnn:
     """Pre-packs the weights of a list of conv layers once; forward() runs the chain."""
 
-    def __init__(self, weights, specs, act_bits=4, w_bits=4, w_signed=True, wide=True, m=0, tight=0, fused=True):
-        """fused: every epilogue writes the next layer's packed activation words directly
-        (hikonv_epilogue_pack); otherwise it writes bit-dense rows that the next layer packs."""
+    def __init__(self, weights, specs, act_bits=4, w_bits=4, w_signed=True, wide=True, m=0, tight=0, fused=True,
+                 keep_accs=True):
+        """fused: "layer" = one kernel per layer (hikonv_conv2d_fused: the convolution's store stage
+        writes the next layer's packed activation words; layers it does not cover fall back to the
+        next form); True = a convolution kernel and an epilogue kernel that writes the next
+        layer's packed words (hikonv_epilogue_pack); False = the epilogue writes bit-dense rows
+        that the next layer packs.  keep_accs (fused == "layer" only): also store every layer's
+        int32 accumulators (the last layer's are always stored)."""
         self.layers = []
         width, acc = (32, 64) if wide else (24, 32)
         for w_dev, spec in zip(weights, specs):
@@ -29,6 +34,8 @@ class PackedCnn:
                                     pool=spec["pool"]))
         self.act_bits = act_bits
         self.fused = fused
+        self.keep_accs = keep_accs
+        self.layer_kernel = [fused == "layer"] * len(self.layers)   # cleared where the fused kernel does not apply
         self.buffers = None
 
     def _allocate(self, n, h, w):
@@ -56,6 +63,23 @@ class PackedCnn:
         accs = []
         bufs = self.buffers[1]
         for i, (layer, buf) in enumerate(zip(self.layers, bufs)):
+            last = i + 1 == len(self.layers)
+            if self.layer_kernel[i]:
+                nxt = None if last else self.layers[i + 1]
+                try:
+                    hk.hikonv_conv2d_fused(
+                        layer["plan"], cur, fmt, n, layer["c"], buf["h"], buf["w"], layer["packed"], layer["co"],
+                        layer["kh"], layer["kw"], layer["pad"], buf["ws"], buf["acc"] if (self.keep_accs or last) else None,
+                        0 if last else shifts[i], qmax, layer["pool"], None if last else nxt["plan"],
+                        0 if last else nxt["co"], 0 if last else nxt["kh"], 0 if last else nxt["kw"],
+                        0 if last else nxt["pad"], None if last else bufs[i + 1]["ws"])
+                    accs.append(buf["acc"])
+                    cur, fmt = None, hk.FMT_PACKED
+                    continue
+                except hk.HikonvError as err:
+                    if err.code != hk.EUNSUPPORTED:
+                        raise
+                    self.layer_kernel[i] = False        # refused on the host, nothing was launched
             hk.hikonv_conv2d_prepacked(layer["plan"], cur, fmt, n, layer["c"], buf["h"], buf["w"],
                                        layer["packed"], layer["co"], layer["kh"], layer["kw"], 1, layer["pad"],
                                        buf["ws"], buf["acc"])

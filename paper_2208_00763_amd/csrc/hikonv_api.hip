@@ -731,6 +731,102 @@ extern "C" int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H,
     return hip_result(launch_pack_act(pa, static_cast<hipStream_t>(stream)));
 }
 
+extern "C" int hikonv_conv2d_fused(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H,
+                                   int W, const void *w_packed_dev, int Co, int Kh, int Kw, int pad,
+                                   void *workspace_dev, size_t workspace_bytes, int32_t *y_dev, int shift, int qmax,
+                                   int pool, const hikonv_plan_t *next_plan, int next_Co, int next_Kh, int next_Kw,
+                                   int next_pad, void *next_workspace_dev, size_t next_workspace_bytes, void *stream_v)
+{
+    Conv2dGeom g;
+    int rc = conv2d_geom(plan, N, C, H, W, Co, Kh, Kw, 1, pad, &g);
+    if (rc != HIKONV_OK) return rc;
+    if (!w_packed_dev || !aligned(w_packed_dev, 256) || (y_dev && !aligned(y_dev, 4))) return HIKONV_EINVAL;
+    if (!next_plan && !y_dev) return HIKONV_EINVAL; // nothing would be produced
+    if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE && x_format != HIKONV_FMT_PACKED)
+        return HIKONV_EINVAL;
+    if (x_format != HIKONV_FMT_PACKED && (!x_dev || !aligned(x_dev, 4))) return HIKONV_EINVAL;
+    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < g.apk_bytes + g.toff_bytes)
+        return HIKONV_EWORKSPACE;
+    if (!(plan->L_A == 32 && plan->L_B == 32 && (plan->L_acc == 64 || plan->L_acc == 0)) || plan->N > 4)
+        return HIKONV_EUNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
+    uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
+    int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+
+    FusedLayerArgs f = {};
+    f.pool = pool ? 1 : 0;
+    f.R = f.pool ? 2 : 1;
+    f.n_tiles = (Co + 7) / 8;
+    f.segs = g.Xs <= 64 ? 1 : (g.X + 62) / 63;
+    f.shift = shift;
+    f.qmax = qmax;
+    f.has_next = next_plan ? 1 : 0;
+    if (f.R * f.segs > 16) return HIKONV_EUNSUPPORTED; // a workgroup holds at most 16 waves
+    // the term range of a (row, segment) divided over as many waves as the workgroup still holds,
+    // two term groups per wave at least
+    f.ksplit = 1;
+    while (f.ksplit < 8 && f.R * f.segs * f.ksplit * 2 <= 16 && g.terms / 4 >= f.ksplit * 4) f.ksplit *= 2;
+    if (next_plan) {
+        if (shift < 0 || shift > 31) return HIKONV_EINVAL;
+        if (next_plan->bipolar || next_plan->a_signed) return HIKONV_EUNSUPPORTED; // the outputs are unsigned values
+        if (qmax < 0 || qmax > (1 << next_plan->bits_a) - 1) return HIKONV_EINVAL;
+        const int Hn = pool ? g.Ho / 2 : g.Ho, Wn = pool ? g.Wo / 2 : g.Wo;
+        if (Hn < 1 || Wn < 1) return HIKONV_EINVAL;
+        Conv2dGeom gn;
+        rc = conv2d_geom(next_plan, N, Co, Hn, Wn, next_Co, next_Kh, next_Kw, 1, next_pad, &gn);
+        if (rc != HIKONV_OK) return rc;
+        if (!next_workspace_dev || !aligned(next_workspace_dev, 256) || next_workspace_bytes < gn.apk_bytes + gn.toff_bytes)
+            return HIKONV_EWORKSPACE;
+        uint8_t *nws = static_cast<uint8_t *>(next_workspace_dev);
+        f.nx = pack_act_args(next_plan, gn, N, Co, 1, Hn, Wn, 1, next_Kh, next_pad, reinterpret_cast<uint32_t *>(nws),
+                             reinterpret_cast<int32_t *>(nws + gn.apk_bytes));
+    }
+    if (x_format != HIKONV_FMT_PACKED) {
+        PackActArgs pa = pack_act_args(plan, g, N, C, 1, H, W, 1, Kh, pad, apk, toff);
+        pa.x = x_dev;
+        pa.x_format = x_format;
+        pa.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
+        pa.row_bytes = x_format == HIKONV_FMT_INT8 ? W : hikonv_bitdense_row_bytes(W, plan->bits_a);
+        rc = hip_result(launch_pack_act(pa, stream));
+        if (rc != HIKONV_OK) return rc;
+    }
+    Conv2dArgs &ca = f.c;
+    ca.apk = apk;
+    ca.wp = static_cast<const uint32_t *>(w_packed_dev);
+    ca.toff = toff;
+    ca.Nimg = N;
+    ca.C = g.Ce;
+    ca.Ho = g.Ho;
+    ca.Ho2d = g.Ho;
+    ca.Wo = g.Wo;
+    ca.Wo1 = g.Wo1;
+    ca.img_rows = (int64_t)g.Cq * g.Hp;
+    ca.stride = 1;
+    ca.stride_w = 1;
+    ca.off = g.Kwe - 1 - g.padwe;
+    ca.Hp = g.Hp;
+    ca.Xs = g.Xs;
+    ca.X = g.X;
+    ca.N = plan->N;
+    ca.S = plan->S;
+    ca.Kp = plan->K;
+    ca.chunks = plan->chunks;
+    ca.M = plan->M;
+    ca.terms = g.terms;
+    ca.terms_pad = g.terms_pad;
+    const int split_any = (int)((int64_t)plan->M * g.Kwe / plan->K);
+    ca.split_terms_any = split_any > 0 ? split_any : 1;
+    f.split_terms = split_any / kTermGroup * kTermGroup;
+    ca.Co = Co;
+    ca.Kh = Kh;
+    ca.chunk_stride = (int64_t)N * g.Cq * g.Dp * g.Hp * g.Xs;
+    ca.y = y_dev;
+    if (conv2d_fused_lds(f) > 64 * 1024) return HIKONV_EUNSUPPORTED; // the tile's B words and int32 sums live in LDS
+    const bool any_signed = plan->bipolar || plan->a_signed || plan->w_signed;
+    return hip_result(launch_conv2d_fused(f, any_signed, stream));
+}
+
 extern "C" int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream)
 {
     if (!buf_dev || iters < 0 || blocks < 1 || blocks > (1 << 20) || !aligned(buf_dev, 16)) return HIKONV_EINVAL;

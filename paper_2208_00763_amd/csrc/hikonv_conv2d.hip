@@ -80,19 +80,6 @@ __device__ __forceinline__ uint32_t pack_act_word(const PackActArgs &p, int ch, 
     return a;
 }
 
-// the table of activation offsets of the term groups (entry gi, zero beyond the groups):
-// gi = ((cq*Kd + kd)*Kh + kh)*chunks + chunk  ->  byte offset 16*(chunk*chunk_stride + ((cq*Dp + kd)*Hp + kh)*Xs)
-__device__ __forceinline__ void write_offset_entry(const PackActArgs &p, int gi)
-{
-    int32_t off = 0;
-    if (gi < p.groups) {
-        const int ch = gi % p.chunks, kh = (gi / p.chunks) % p.Kh, kd = (gi / (p.chunks * p.Kh)) % p.Kd;
-        const int cq = gi / (p.chunks * p.Kh * p.Kd);
-        off = (int32_t)(uint32_t)(16 * (ch * p.chunk_stride + (((int64_t)cq * p.Dp + kd) * p.Hp + kh) * p.Xs)); // < 2^32
-    }
-    p.toff[gi] = off;
-}
-
 // One thread per word.  Grid: x over the 4*Xs words of a packed row (four channels of a quad
 // side by side), y = padded row hp (groups of rows_per_block rows when a row is shorter than a block), z = ((chunk*Nimg + n)*Cq + quad)*Dp + dp, so a thread finds
 // its coordinates without dividing; block (0,0,0) also writes the offset table.

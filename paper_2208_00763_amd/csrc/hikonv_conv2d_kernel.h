@@ -4,9 +4,11 @@
 // (ci, kh) pairs before one split (Section "DNN Convolution Extension").
 //
 // Mapping: one lane owns one packed block x of one output row (n, ho) and CO_T output
-// channels.  Activation words A[chunk][n][ci][row][x] come pre-packed from k_pack_act (one
-// coalesced dword load per term); weight words B[co][term] are wave uniform and are fetched
-// with scalar loads, so a multiply-accumulate is one VALU instruction with an SGPR operand:
+// channels.  Activation words A[chunk][n][ci/4][row][x][ci%4] come pre-packed from k_pack_act
+// (one 16-byte load brings the words of four terms); weight words B[co][term] are wave
+// uniform: k_conv2d_pipe stages the channel tile's words in LDS once per workgroup and reads
+// them back as broadcast 128-bit reads, k_conv2d_packed fetches them with scalar loads.  The
+// multiply-accumulate is
 //   WIDE   v_mad_u64_u32 / v_mad_i64_i32   (32x32+64 -> 64)
 //   narrow v_mad_u32_u24 / v_mad_i32_i24   (24x24+32 -> 32)
 // Split (every M pairs): Comb = Acc + (Acc of lane-1 >> S N) via DPP wave_shr:1, then N
@@ -32,6 +34,19 @@
 #include "hikonv_launch.h"
 
 namespace hikonv {
+
+// the table of activation offsets of the term groups (entry gi, zero beyond the groups):
+// gi = ((cq*Kd + kd)*Kh + kh)*chunks + chunk  ->  byte offset 16*(chunk*chunk_stride + ((cq*Dp + kd)*Hp + kh)*Xs)
+__device__ __forceinline__ void write_offset_entry(const PackActArgs &p, int gi)
+{
+    int32_t off = 0;
+    if (gi < p.groups) {
+        const int ch = gi % p.chunks, kh = (gi / p.chunks) % p.Kh, kd = (gi / (p.chunks * p.Kh)) % p.Kd;
+        const int cq = gi / (p.chunks * p.Kh * p.Kd);
+        off = (int32_t)(uint32_t)(16 * (ch * p.chunk_stride + (((int64_t)cq * p.Dp + kd) * p.Hp + kh) * p.Xs)); // < 2^32
+    }
+    p.toff[gi] = off;
+}
 
 template <bool WIDE>
 struct acc_type {

@@ -144,6 +144,21 @@ struct Conv2dArgs {
 hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed, int co_tile,
                                 hipStream_t stream);
 
+// One kernel per layer of a chain: the packed layer whose store stage writes the next layer's
+// packed activation words (ReLU, requantisation, optional 2x2 max-pool on the way).
+struct FusedLayerArgs {
+    Conv2dArgs c;        // this layer; y may be null (the accumulators are then not stored)
+    int R;               // output rows per workgroup (2 with pooling)
+    int n_tiles, segs;   // channel tiles of eight; 63-block segments per row (1: the row fits a wave)
+    int ksplit;          // waves that divide the term range of one (row, segment)
+    int split_terms;     // terms between splits rounded down to whole term groups (0: fewer than 4 allowed)
+    int shift, qmax, pool;
+    int has_next;        // 0: plain layer (y only)
+    PackActArgs nx;      // geometry and buffers of the next layer's packed activations
+};
+size_t conv2d_fused_lds(const FusedLayerArgs &f); // dynamic LDS bytes (at most 64 KiB)
+hipError_t launch_conv2d_fused(const FusedLayerArgs &f, bool any_signed, hipStream_t stream);
+
 // plans this kernel covers: 32x32+64 multiply, at most three taps per B word and no more
 // high segments than own segments, a whole number of term groups between splits
 inline bool conv2d_sreg_applicable(int N, int Kp, int split_terms, bool wide)

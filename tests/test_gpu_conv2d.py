@@ -245,20 +245,28 @@ def test_epilogue_pack_feeds_the_next_layer(pool, wide):
         assert e.value.code == code
 
 
-@pytest.mark.parametrize("fused", [True, False])
-@pytest.mark.parametrize("size", [(32, 64), (160, 320)])
+@pytest.mark.parametrize("fused", ["layer", True, False])
+@pytest.mark.parametrize("size", [(32, 64), (160, 320), (38, 70)])
 def test_cnn_forward_config5(size, fused):
     h, w = size
     x, weights, specs = wl.config5(h, w)
     ref_accs, shifts = oracle_cnn(x, weights, specs)
     net = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs, fused=fused,
-                    tight=int(fused))
+                    tight=int(fused is True))
     x_bd = compact(x.reshape(3 * h, w), 4)
     _, accs = net.forward(x_bd, 1, h, w, shifts)
     torch.cuda.synchronize()
     for i, (got, ref) in enumerate(zip(accs, ref_accs)):
         assert np.array_equal(got.cpu().numpy().reshape(ref.shape), ref), "layer %d" % i
-    if fused:
+    if fused == "layer":
+        assert all(net.layer_kernel), "every layer of this network fits the one-kernel-per-layer form"
+        # the chain as the benchmark runs it: intermediate accumulators never stored
+        lean = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs, fused="layer",
+                         keep_accs=False)
+        last, _ = lean.forward(x_bd, 1, h, w, shifts)
+        torch.cuda.synchronize()
+        assert np.array_equal(last.cpu().numpy().reshape(ref_accs[-1].shape), ref_accs[-1])
+    if fused is True:
         # the baseline chain (one multiply per product) that the benchmark times beside it
         base = UnpackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs)
         _, accs_u = base.forward(dev(x), 1, h, w, shifts)
