@@ -374,13 +374,20 @@ int hikonv_epilogue_pack(const int32_t *acc_dev, int N, int C, int H, int W, int
  *   y_dev: NCHW int32 accumulators of this layer, or NULL to skip storing them.
  *   next_plan NULL: no following layer (y_dev required); shift, qmax, pool and the
  *   next_* arguments are ignored.
- *   x_format INT8 / BITDENSE: the input is packed into workspace_dev by a first
- *   kernel, as in hikonv_conv2d; PACKED: workspace_dev already holds it.
- * Covers plans with (L_A, L_B, L_acc) = (32, 32, 64) and N <= 4, layers with at most
- * 16 waves per workgroup (2 rows with pooling x ceil(Co/8) channel tiles x 63-block
- * row segments) and an int32 tile of rows x Co x Wo within 64 KiB, next plans with
- * unsigned activations; anything else returns HIKONV_EUNSUPPORTED and the caller
- * chains hikonv_conv2d_prepacked and hikonv_epilogue_pack instead.
+ *   x_format INT8 / BITDENSE: where a workgroup's share of the input is small (at
+ *   most 2048 packed words: few input channels), or where plan->kernel ==
+ *   HIKONV_KERNEL_LDS asks for it and the rows fit its LDS, every workgroup packs
+ *   the input rows it needs into LDS itself (one kernel for the whole layer;
+ *   workspace_dev is not used and may be NULL); otherwise the input is packed into
+ *   workspace_dev by a first kernel, as in hikonv_conv2d (HIKONV_EWORKSPACE if it
+ *   is missing).
+ *   PACKED: workspace_dev already holds the packed input.
+ * Covers plans with (L_A, L_B, L_acc) = (32, 32, 64) and N <= 4, rows of at most
+ * 16 (8 with pooling) 63-block segments, and layers whose per-workgroup LDS (the
+ * B words of eight output channels, an int32 tile of rows x 8 x Wo) stays within
+ * 64 KiB; next plans with unsigned activations; anything else returns
+ * HIKONV_EUNSUPPORTED and the caller chains hikonv_conv2d_prepacked and
+ * hikonv_epilogue_pack instead.
  */
 int hikonv_conv2d_fused(const hikonv_plan_t *plan, const void *x_dev, int x_format, int N, int C, int H,
                         int W, const void *w_packed_dev, int Co, int Kh, int Kw, int pad,

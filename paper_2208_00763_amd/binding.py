@@ -274,10 +274,12 @@ def hikonv_epilogue_pack(acc, n, c, h, w, shift, qmax, pool, next_plan, next_co,
 
 def hikonv_conv2d_fused(plan, x, x_format, n, c, h, w, packed, co, kh, kw, pad, workspace, y, shift=0, qmax=0, pool=False,
                         next_plan=None, next_co=0, next_kh=0, next_kw=0, next_pad=0, next_workspace=None, stream=None):
-    """y may be None (accumulators not stored); next_plan None: plain layer."""
+    """y may be None (accumulators not stored); next_plan None: plain layer; workspace may be None
+    where the layer packs its own input (see include/hikonv.h)."""
     nws_bytes = next_workspace.numel() * next_workspace.element_size() if next_workspace is not None else 0
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.hikonv_conv2d_fused(C.byref(plan), _ptr(x), x_format, n, c, h, w, _ptr(packed), co, kh, kw, pad,
-                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(y), shift, qmax,
+                                   _ptr(workspace), ws_bytes, _ptr(y), shift, qmax,
                                    int(pool), C.byref(next_plan) if next_plan is not None else None, next_co, next_kh,
                                    next_kw, next_pad, _ptr(next_workspace), nws_bytes, _stream(stream)),
            "hikonv_conv2d_fused")

@@ -745,28 +745,35 @@ extern "C" int hikonv_conv2d_fused(const hikonv_plan_t *plan, const void *x_dev,
     if (x_format != HIKONV_FMT_INT8 && x_format != HIKONV_FMT_BITDENSE && x_format != HIKONV_FMT_PACKED)
         return HIKONV_EINVAL;
     if (x_format != HIKONV_FMT_PACKED && (!x_dev || !aligned(x_dev, 4))) return HIKONV_EINVAL;
-    if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < g.apk_bytes + g.toff_bytes)
-        return HIKONV_EWORKSPACE;
     if (!(plan->L_A == 32 && plan->L_B == 32 && (plan->L_acc == 64 || plan->L_acc == 0)) || plan->N > 4)
         return HIKONV_EUNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
-    uint32_t *apk = reinterpret_cast<uint32_t *>(ws);
-    int32_t *toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
 
     FusedLayerArgs f = {};
     f.pool = pool ? 1 : 0;
-    f.R = f.pool ? 2 : 1;
     f.n_tiles = (Co + 7) / 8;
     f.segs = g.Xs <= 64 ? 1 : (g.X + 62) / 63;
+    // rows per wave: as many whole rows as fit 64 lanes, fewer while that leaves the chip with
+    // under 128 workgroups; with pooling a workgroup holds an even number of rows
+    f.rpw = f.segs > 1 ? 1 : 64 / g.Xs;
+    if (f.rpw > g.Ho) f.rpw = g.Ho;
+    f.wr = 1;
+    const int rpw_min = f.pool ? 2 : 1;
+    if (f.pool) {
+        if (f.rpw >= 2)
+            f.rpw &= ~1;
+        else
+            f.wr = 2;
+    }
+    while (f.rpw > rpw_min && (int64_t)N * ((g.Ho + f.rpw * f.wr - 1) / (f.rpw * f.wr)) * f.n_tiles < 128) f.rpw = f.rpw / 2 < rpw_min ? rpw_min : (f.pool ? (f.rpw / 2 + 1) & ~1 : f.rpw / 2);
     f.shift = shift;
     f.qmax = qmax;
     f.has_next = next_plan ? 1 : 0;
-    if (f.R * f.segs > 16) return HIKONV_EUNSUPPORTED; // a workgroup holds at most 16 waves
-    // the term range of a (row, segment) divided over as many waves as the workgroup still holds,
+    if (f.wr * f.segs > 16) return HIKONV_EUNSUPPORTED; // a workgroup holds at most 16 waves
+    // the term range of a (rows, segment) divided over as many waves as the workgroup still holds,
     // two term groups per wave at least
     f.ksplit = 1;
-    while (f.ksplit < 8 && f.R * f.segs * f.ksplit * 2 <= 16 && g.terms / 4 >= f.ksplit * 4) f.ksplit *= 2;
+    while (f.ksplit < 8 && f.wr * f.segs * f.ksplit * 2 <= 16 && g.terms / 4 >= f.ksplit * 4) f.ksplit *= 2;
     if (next_plan) {
         if (shift < 0 || shift > 31) return HIKONV_EINVAL;
         if (next_plan->bipolar || next_plan->a_signed) return HIKONV_EUNSUPPORTED; // the outputs are unsigned values
@@ -782,19 +789,8 @@ extern "C" int hikonv_conv2d_fused(const hikonv_plan_t *plan, const void *x_dev,
         f.nx = pack_act_args(next_plan, gn, N, Co, 1, Hn, Wn, 1, next_Kh, next_pad, reinterpret_cast<uint32_t *>(nws),
                              reinterpret_cast<int32_t *>(nws + gn.apk_bytes));
     }
-    if (x_format != HIKONV_FMT_PACKED) {
-        PackActArgs pa = pack_act_args(plan, g, N, C, 1, H, W, 1, Kh, pad, apk, toff);
-        pa.x = x_dev;
-        pa.x_format = x_format;
-        pa.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
-        pa.row_bytes = x_format == HIKONV_FMT_INT8 ? W : hikonv_bitdense_row_bytes(W, plan->bits_a);
-        rc = hip_result(launch_pack_act(pa, stream));
-        if (rc != HIKONV_OK) return rc;
-    }
     Conv2dArgs &ca = f.c;
-    ca.apk = apk;
     ca.wp = static_cast<const uint32_t *>(w_packed_dev);
-    ca.toff = toff;
     ca.Nimg = N;
     ca.C = g.Ce;
     ca.Ho = g.Ho;
@@ -822,7 +818,46 @@ extern "C" int hikonv_conv2d_fused(const hikonv_plan_t *plan, const void *x_dev,
     ca.Kh = Kh;
     ca.chunk_stride = (int64_t)N * g.Cq * g.Dp * g.Hp * g.Xs;
     ca.y = y_dev;
-    if (conv2d_fused_lds(f) > 64 * 1024) return HIKONV_EUNSUPPORTED; // the tile's B words and int32 sums live in LDS
+
+    // Input not packed yet: the workgroups pack the rows they need into LDS themselves when
+    // that fits (no packing kernel, no workspace); else a packing kernel fills the workspace first.
+    if (x_format != HIKONV_FMT_PACKED) {
+        f.in = pack_act_args(plan, g, N, C, 1, H, W, 1, Kh, pad, nullptr, nullptr);
+        f.in.x = x_dev;
+        f.in.x_format = x_format;
+        f.in.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
+        f.in.row_bytes = x_format == HIKONV_FMT_INT8 ? W : hikonv_bitdense_row_bytes(W, plan->bits_a);
+        // in-kernel packing reads a word's N containers as one 32-bit window of a tensor that is a
+        // whole number of dwords
+        // whole number of dwords below 2^31, with bit offsets inside an image below 2^30
+        const int64_t in_bytes = (int64_t)N * C * H * f.in.row_bytes;
+        f.pack_input = plan->N * f.in.c <= 32 && (in_bytes & 3) == 0 && in_bytes < (1LL << 32) &&
+                               (int64_t)H * f.in.row_bytes * 32 < (1LL << 30)
+                           ? 1
+                           : 0;
+        if (f.pack_input && conv2d_fused_lds(f) > 64 * 1024) f.pack_input = 0;
+        // Every channel tile of a row group packs the same rows again, so this pays only while a
+        // workgroup's share is small (measured: a 3-channel 320-wide layer gains a kernel launch;
+        // on the 64-channel 56x56 layer the one-kernel form takes 17 us against 10.4 us for the
+        // packing kernel plus the layer kernel).  HIKONV_KERNEL_LDS in the plan asks for it anyway.
+        const int64_t words = (int64_t)plan->chunks * g.Cq * (f.rpw * f.wr + Kh - 1) * g.Xs * 4;
+        if (f.pack_input && words > 2048 && plan->kernel != HIKONV_KERNEL_LDS) f.pack_input = 0;
+    }
+    if (!f.pack_input) {
+        if (!workspace_dev || !aligned(workspace_dev, 256) || workspace_bytes < g.apk_bytes + g.toff_bytes)
+            return HIKONV_EWORKSPACE;
+        uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
+        ca.apk = reinterpret_cast<uint32_t *>(ws);
+        ca.toff = reinterpret_cast<int32_t *>(ws + g.apk_bytes);
+        if (conv2d_fused_lds(f) > 64 * 1024) return HIKONV_EUNSUPPORTED; // the tile's B words and int32 sums live in LDS
+        if (x_format != HIKONV_FMT_PACKED) {
+            PackActArgs pa = f.in;
+            pa.apk = const_cast<uint32_t *>(ca.apk);
+            pa.toff = const_cast<int32_t *>(ca.toff);
+            rc = hip_result(launch_pack_act(pa, stream));
+            if (rc != HIKONV_OK) return rc;
+        }
+    }
     const bool any_signed = plan->bipolar || plan->a_signed || plan->w_signed;
     return hip_result(launch_conv2d_fused(f, any_signed, stream));
 }

@@ -9,77 +9,6 @@
 namespace hikonv {
 namespace {
 
-// A[chunk][n][c/4][dp][hp][xi][c%4] = sum_j f[(xi-1)N + j - chunk*K] 2^(S j), f = row hp-pad of depth
-// slice dp-pad_d of the image (zero outside it; Eq. I_PRIME / Eq. pad_f0).  Word xi = 0 of
-// every row is zero.  A 2-D layer has one depth slice (Dp = 1).  The words of four channels sit side
-// by side in a 16-byte cell, so that a lane fetches the words of four terms with one load.
-// Ordinary layers: the packed channel c is the source channel and f[i] is its value i; the
-// leading horizontal padding is not materialised, it only shifts the index at which an
-// output is read (Eq. off).
-// Polyphase layers (column stride s packed as s phases): packed channel c = (source channel
-// c / s, phase c % s) and f[i] = padded source row at s*i + phase, i.e. source value
-// s*i + phase - pad, so that a stride-s row convolution becomes the sum over the phases of
-// stride-1 row convolutions with the phase kernels.
-// One packed word: chunk ch, image n_img, packed channel c_packed, source depth d and row h
-// (both inside the image), word xi > 0.  FMT: the source format (HIKONV_FMT_INT8,
-// HIKONV_FMT_BITDENSE or kPackFromAcc), fixed at compile time in the kernels below.
-// NV: the plan's N when it is known at compile time (the loops unroll and the loads of a word
-// are issued together), 0 = read it from the arguments.
-template <int FMT, int NV>
-__device__ __forceinline__ uint32_t pack_act_word(const PackActArgs &p, int ch, int64_t n_img, int c_packed, int d, int h,
-                                                  int xi)
-{
-    uint32_t a = 0;
-    const int pN = NV ? NV : p.N;
-    const int e0 = (xi - 1) * pN - ch * p.Kp;
-    if (FMT == kPackFromAcc) {
-        // fused epilogue of the producing layer (ReLU, shift, clamp, optional 2x2 max-pool); 2-D, one phase
-        const int32_t *src = p.acc + (n_img * p.C + c_packed) * p.acc_H * p.acc_W;
-#pragma unroll
-        for (int j = 0; j < pN; ++j) {
-            const int i = e0 + j;
-            if (i < 0 || i >= p.W) continue;
-            int32_t v;
-            if (p.pool) {
-                const int32_t *s0 = src + (int64_t)(2 * h) * p.acc_W + 2 * i;
-                v = max(max(s0[0], s0[1]), max(s0[p.acc_W], s0[p.acc_W + 1]));
-            } else {
-                v = src[(int64_t)h * p.acc_W + i];
-            }
-            v = min(max(v, 0) >> p.shift, p.qmax);
-            a += (uint32_t)v << (p.S * j);
-        }
-        return a;
-    }
-    const int csrc = c_packed / p.phases, phase = c_packed - csrc * p.phases;
-    const uint8_t *rowp =
-        static_cast<const uint8_t *>(p.x) + (((n_img * p.Csrc + csrc) * p.D + d) * p.H + h) * p.row_bytes;
-#pragma unroll
-    for (int j = 0; j < pN; ++j) {
-        const int i = e0 + j; // element of the packed row
-        if (i < 0 || i >= p.W) continue;
-        const int is = i * p.phases + phase - p.pad_w_mat; // source value
-        if (is < 0 || is >= p.Wsrc) continue;
-        int32_t v;
-        if (FMT == HIKONV_FMT_INT8) {
-            const uint8_t byte = rowp[is];
-            if (p.bipolar)
-                v = (int8_t)byte > 0 ? 1 : -1;
-            else
-                v = p.a_signed ? __builtin_amdgcn_sbfe((int)byte, 0, p.b) : (int)__builtin_amdgcn_ubfe(byte, 0, p.b);
-        } else {
-            const int bit = is * p.c;
-            const uint32_t w = reinterpret_cast<const uint32_t *>(rowp)[bit >> 5];
-            if (p.bipolar)
-                v = ((w >> (bit & 31)) & 1u) ? 1 : -1;
-            else
-                v = p.a_signed ? __builtin_amdgcn_sbfe((int)w, bit & 31, p.b) : (int)__builtin_amdgcn_ubfe(w, bit & 31, p.b);
-        }
-        a += (uint32_t)v << (p.S * j);
-    }
-    return a;
-}
-
 // One thread per word.  Grid: x over the 4*Xs words of a packed row (four channels of a quad
 // side by side), y = padded row hp (groups of rows_per_block rows when a row is shorter than a block), z = ((chunk*Nimg + n)*Cq + quad)*Dp + dp, so a thread finds
 // its coordinates without dividing; block (0,0,0) also writes the offset table.

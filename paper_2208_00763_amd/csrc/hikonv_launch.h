@@ -148,13 +148,16 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a, bool wide, bool any_signed,
 // packed activation words (ReLU, requantisation, optional 2x2 max-pool on the way).
 struct FusedLayerArgs {
     Conv2dArgs c;        // this layer; y may be null (the accumulators are then not stored)
-    int R;               // output rows per workgroup (2 with pooling)
+    int rpw, wr;         // whole rows per wave (1 when a row is cut into segments), waves in the row direction;
+                         // the workgroup owns rpw*wr output rows (an even number with pooling)
     int n_tiles, segs;   // channel tiles of eight; 63-block segments per row (1: the row fits a wave)
-    int ksplit;          // waves that divide the term range of one (row, segment)
+    int ksplit;          // waves that divide the term range of one (rows, segment)
     int split_terms;     // terms between splits rounded down to whole term groups (0: fewer than 4 allowed)
     int shift, qmax, pool;
     int has_next;        // 0: plain layer (y only)
-    PackActArgs nx;      // geometry and buffers of the next layer's packed activations
+    int pack_input;      // 1: the activation words are packed in the kernel, into LDS, from `in`
+    PackActArgs in;      // pack_input: this layer's raw input (INT8 or bit-dense) and packing geometry
+    PackActArgs nx;      // has_next: geometry and buffers of the next layer's packed activations
 };
 size_t conv2d_fused_lds(const FusedLayerArgs &f); // dynamic LDS bytes (at most 64 KiB)
 hipError_t launch_conv2d_fused(const FusedLayerArgs &f, bool any_signed, hipStream_t stream);

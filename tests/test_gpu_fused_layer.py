@@ -25,6 +25,10 @@ CASES = [  # n, c, h, w, co, k, pad, pool, shift | next: co2, k2, pad2
     (3, 64, 10, 20, 64, 3, 1, 0, 7, 36, 1, 0),      # eight channel tiles, three images, term range over eight waves
     (1, 64, 4, 9, 36, 1, 0, 0, 3, 6, 3, 1),         # 36 channels: the last tile is half empty; 1x1 kernel
     (2, 12, 7, 30, 13, 3, 1, 1, 3, 7, 3, 1),        # 13 channels: a quad of the next layer padded with zero words
+    (2, 8, 23, 5, 8, 3, 1, 1, 2, 8, 3, 1),          # short rows: many rows per wave, odd row count with pooling
+    (1, 8, 40, 14, 16, 3, 1, 0, 3, 8, 3, 1),        # four rows per wave, no pooling
+    (4, 4, 3, 9, 8, 3, 1, 1, 2, 4, 3, 1),           # three rows in all: one pooled row, the third row dropped
+    (1, 256, 6, 12, 8, 3, 1, 0, 8, 8, 1, 0),        # 768 terms: the packed input of a workgroup exceeds its LDS
     (1, 7, 2, 9, 3, 1, 0, 1, 0, 2, 3, 1),           # one workgroup per image writes both padding rows
     (1, 6, 1, 9, 8, 3, 1, 0, 1, 8, 3, 1),           # a single output row
 ]
@@ -58,8 +62,20 @@ def test_fused_layer_matches_oracle_chain(case, tight):
         y2 = Guarded(ref2.size)
         ws2.view.fill_(0x5A)
         x_bd = compact(x.reshape(n * c * h, w), 4)
-        hk.hikonv_conv2d_fused(plan1, x_bd, hk.FMT_BITDENSE, n, c, h, w, pw1, co, k, k, pad, ws1.view,
-                               y1.view if keep_y else None, shift, 15, bool(pool), plan2, co2, k2, k2, pad2, ws2.view)
+        # bit-dense input with a workspace, one value per byte without one (the workgroups pack
+        # their own input rows whenever those fit their LDS, which holds for every case here but the widest)
+        if keep_y:
+            hk.hikonv_conv2d_fused(plan1, x_bd, hk.FMT_BITDENSE, n, c, h, w, pw1, co, k, k, pad, ws1.view, y1.view, shift,
+                                   15, bool(pool), plan2, co2, k2, k2, pad2, ws2.view)
+        else:
+            own = hk.with_fields(plan1, kernel=hk.KERNEL_LDS)   # the workgroups pack their own input rows
+            try:
+                hk.hikonv_conv2d_fused(own, dev(x), hk.FMT_INT8, n, c, h, w, pw1, co, k, k, pad, None, None, shift, 15,
+                                       bool(pool), plan2, co2, k2, k2, pad2, ws2.view)
+            except hk.HikonvError as err:
+                assert err.code == hk.EWORKSPACE          # too large for in-kernel packing: the workspace is needed
+                hk.hikonv_conv2d_fused(own, dev(x), hk.FMT_INT8, n, c, h, w, pw1, co, k, k, pad, ws1.view, None, shift,
+                                       15, bool(pool), plan2, co2, k2, k2, pad2, ws2.view)
         # the follower reads the packed words the first kernel wrote; as a plain layer through the same entry point
         hk.hikonv_conv2d_fused(plan2, None, hk.FMT_PACKED, n, co, hn, wn, pw2, co2, k2, k2, pad2, ws2.view, y2.view)
         got2 = y2.result().reshape(ref2.shape)
