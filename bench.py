@@ -41,16 +41,19 @@ def event_ms(fn, reps):
     return start.elapsed_time(end) / reps
 
 
-def timed_pair(fn_a, fn_b, reps, rounds=3):
+def timed_pair(fn_a, fn_b, reps, rounds=5):
     """Milliseconds per call of two kernels measured the same way: both warmed with three
-    launches, then `rounds` interleaved rounds of `reps` launches each; the mean over rounds."""
+    launches, then `rounds` interleaved rounds of `reps` launches each; the median over rounds
+    (clock and cache state drift during a run; interleaving gives both kernels the same share)."""
     event_ms(fn_a, 3)
     event_ms(fn_b, 3)
     ta, tb = [], []
     for _ in range(rounds):
         ta.append(event_ms(fn_a, reps))
         tb.append(event_ms(fn_b, reps))
-    return sum(ta) / rounds, sum(tb) / rounds
+    ta.sort()
+    tb.sort()
+    return ta[rounds // 2], tb[rounds // 2]
 
 
 def read_profile_json(name):
@@ -391,7 +394,7 @@ def sweep(hk, wl, steps):
         for signed in (False, True):
             for taps in (3, 5, 7):
                 case = conv1d_case(hk, wl, bits, signed, taps)
-                ms_p, ms_u = timed_pair(case["packed"], case["unpacked"], steps, rounds=2)
+                ms_p, ms_u = timed_pair(case["packed"], case["unpacked"], steps, rounds=3)
                 plan = case["plan"]
                 rows.append(dict(bits=bits, signed=signed, taps=taps, N=plan.N, K=plan.K, S=plan.S, chunks=plan.chunks,
                                  packed_ms=ms_p, unpacked_ms=ms_u, gops=2 * case["macs"] / ms_p / 1e6,

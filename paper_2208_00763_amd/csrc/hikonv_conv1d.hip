@@ -14,8 +14,7 @@
 //          sign never arises)
 //   store  through an LDS staging tile, 16-byte aligned coalesced int32x4 stores
 // k_conv1d_unpacked: the baseline, one v_mad_i32_i24 per low-bit product.
-#include "hikonv_device.h"
-#include "hikonv_launch.h"
+#include "hikonv_quad_stream.h"
 
 namespace hikonv {
 
@@ -203,112 +202,35 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
     }
 }
 
-// Streaming form of the baseline: one lane produces one 16-byte aligned quad of outputs from
-// a 64-bit window of the row read straight from global memory (three dwords), and stores it
-// with one int32x4 store.  Still one v_mad_i32_i24 per low-bit product.  Needs
-// (taps + 3) containers to fit the window: 64 bits from three dwords, or (WIDE) 96 bits from
-// four; row edges take the element-by-element path.
-constexpr int kUnpackedQuads = 4; // output quads per lane, kThreads quads apart
-
+// Streaming form of the baseline: one lane produces aligned quads of outputs, each from a
+// window of TAPS + 3 elements, on the same skeleton as the packed quad-per-lane kernel (same
+// loads, same stores, same row handling); the arithmetic is one v_mad_i32_i24 per low-bit
+// product.  Needs the window within 64 bits (three dwords) or, WIDE, 96 bits (four).
 template <bool A_SIGNED, int TAPS, bool WIDE>
-__global__ __launch_bounds__(kThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
+__global__ __launch_bounds__(kStreamThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
 {
-    __shared__ int32_t s_g[64];
-    if (threadIdx.x < p.taps)
+    __shared__ int32_t s_g[8];
+    if (threadIdx.x < TAPS)
         s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
     __syncthreads();
-    // positions inside a row are 32-bit quantities (the launcher checks (len + 2^18) * c < 2^31);
-    // only the row's base is 64-bit, and it is uniform
-    const int out_len = (int)p.out_len, len = (int)p.len;
-    const int nquads = (out_len + 3 + 3) / 4;
-    const int64_t total_bits = p.total_bytes * 8;
-    const int c = p.c, b = p.b;
-    constexpr int taps = TAPS;
-    const int lead_in = p.shift_m - (taps - 1); // first element read for output o: o + lead_in
     int32_t gk[TAPS];
 #pragma unroll
     for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
-    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
-        const int a_off = (int)((r * p.out_len) & 3);
-        // the quads of a wave start on a 128-byte line of y, as in the packed kernel: the row's
-        // quad 0 sits `lead` quads into its line, so the lanes are shifted back by that much
-        const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> 2) & 7);
-        const int64_t row_bit0 = r * p.row_stride_bits;
-        const uint32_t *row_dwords = p.x + (row_bit0 >> 5); // the dword that holds the row's first bit
-        const int row_sh = (int)(row_bit0 & 31);            // and that bit's position in it
-        int64_t room = total_bits - (row_bit0 - row_sh) - (WIDE ? 160 : 128);
-        const int bit_limit = room < 0 ? -1 : (room > 0x7fffffff ? 0x7fffffff : (int)room);
-        int32_t *yrow = p.y + r * p.out_len;
-        // kUnpackedQuads quads per lane, kThreads quads apart; the window loads of all of them first
-        int qv[kUnpackedQuads];
-        bool interior[kUnpackedQuads];
-        uint32_t w0[kUnpackedQuads], w1[kUnpackedQuads], w2[kUnpackedQuads], w3[kUnpackedQuads], shv[kUnpackedQuads];
+    const int c = WIDE ? 8 : p.c, b = p.b;
+    auto direct = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[4]) {
 #pragma unroll
-        for (int s = 0; s < kUnpackedQuads; ++s) {
-            qv[s] = (int)((blockIdx.x * (unsigned)kUnpackedQuads + s) * (unsigned)kThreads + threadIdx.x) - lead;
-            const int o0 = 4 * qv[s] - a_off;   // first output of this lane's aligned quad
-            const int i0 = o0 + lead_in;        // first element it reads
-            const int bit = row_sh + i0 * c;    // offset from row_dwords (meaningful when i0 >= 0)
-            interior[s] = qv[s] >= 0 && qv[s] < nquads && i0 >= 0 && i0 + taps + 3 <= len && o0 >= 0 && o0 + 4 <= out_len &&
-                          bit <= bit_limit;
-            w0[s] = w1[s] = w2[s] = w3[s] = 0u;
-            shv[s] = (uint32_t)bit & 31u;
-            if (interior[s]) {
-                const uint32_t *wp = row_dwords + (bit >> 5);
-                w0[s] = wp[0];
-                w1[s] = wp[1];
-                w2[s] = wp[2];
-                if (WIDE) w3[s] = wp[3];
+        for (int t = 0; t < TAPS + 3; ++t) {
+            // containers never straddle bit 64 (their width divides 64)
+            const uint32_t bits_t = WIDE && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
+            const int32_t v = field<A_SIGNED>(bits_t, 0u, (uint32_t)b);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = u + TAPS - 1 - t;
+                if (k >= 0 && k < TAPS) out[u] = __mul24(v, gk[k]) + out[u];
             }
         }
-#pragma unroll
-        for (int s = 0; s < kUnpackedQuads; ++s) {
-            const int q = qv[s];
-            if (q < 0 || q >= nquads) continue;
-            const int o0 = 4 * q - a_off;
-            const int i0 = o0 + lead_in;
-            int32_t out[4] = {0, 0, 0, 0};
-            if (interior[s]) {
-                const uint32_t sh = shv[s];
-                const uint64_t win = ((uint64_t)funnel_shr(w2[s], w1[s], sh) << 32) | funnel_shr(w1[s], w0[s], sh);
-                const uint32_t win_hi = WIDE ? funnel_shr(w3[s], w2[s], sh) : 0u; // bits 64..95 of the window
-#pragma unroll
-                for (int t = 0; t < TAPS + 3; ++t) {
-                    // containers never straddle bit 64 (their width divides 64)
-                    const uint32_t bits_t = WIDE && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
-                    const int32_t v = field<A_SIGNED>(bits_t, 0u, (uint32_t)b);
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int k = u + TAPS - 1 - t;
-                        if (k >= 0 && k < TAPS) out[u] = __mul24(v, gk[k]) + out[u];
-                    }
-                }
-            } else {
-                for (int t = 0; t < taps + 3; ++t) {
-                    const int i = i0 + t;
-                    int32_t v = 0;
-                    if (i >= 0 && i < len) {
-                        const int64_t eb = row_bit0 + (int64_t)i * c;
-                        const uint32_t w = load_dword_safe(p.x, eb >> 5, p.total_dwords, p.total_bytes);
-                        v = field<A_SIGNED>(w, (uint32_t)(eb & 31), (uint32_t)b);
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int k = u + taps - 1 - t;
-                        if (k >= 0 && k < taps) out[u] = __mul24(v, s_g[k]) + out[u];
-                    }
-                }
-            }
-            if (o0 >= 0 && o0 + 4 <= out_len) {
-                typedef int32_t v4i __attribute__((ext_vector_type(4)));
-                const v4i v4 = {out[0], out[1], out[2], out[3]};
-                __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o0])); // streaming hint, whole lines per wave
-            } else {
-                for (int u = 0; u < 4; ++u)
-                    if (o0 + u >= 0 && o0 + u < out_len) yrow[o0 + u] = out[u];
-            }
-        }
-    }
+    };
+    for_each_output_quad<TAPS + 3, WIDE>(p, p.shift_m - (TAPS - 1), direct);
 }
 
 } // namespace
@@ -345,12 +267,12 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
 {
     if (a.taps > 64) return hipErrorInvalidValue;
     const int64_t nquads = (a.out_len + 6) / 4;
-    const int64_t gx = ceil_div(nquads + 7, kThreads); // the streaming baseline shifts its lanes by up to 7 quads
+    const int64_t gx = ceil_div(nquads + 7, kThreads); // the lanes are shifted by up to 7 quads
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
-    if ((a.taps + 3) * a.c <= 96 && a.taps <= 7 && (a.len + (1 << 18)) * a.c < (1LL << 31)) {
+    if (a.taps <= 7 && quad_stream_applicable(a, a.taps + 3) && ((a.taps + 3) * a.c <= 64 || a.c == 8)) {
         const bool wide_window = (a.taps + 3) * a.c > 64;
-        g.x = (unsigned)ceil_div(nquads + 7, (int64_t)kThreads * kUnpackedQuads);
+        g = quad_stream_grid(a);
 #define HIKONV_UNP(T)                                                                               \
     case T:                                                                                         \
         if (a_signed && wide_window)                                                                \

@@ -27,31 +27,13 @@
 #ifndef HIKONV_CONV1D_WINDOW_H
 #define HIKONV_CONV1D_WINDOW_H
 
-#include "hikonv_device.h"
-#include "hikonv_launch.h"
+#include "hikonv_quad_stream.h"
 
 namespace hikonv {
 
-constexpr int kWindowThreads = 256;
-constexpr int kWindowQuads = 4; // output quads per lane, kWindowThreads quads apart
-
-__device__ __forceinline__ uint32_t window_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
-                                                         int64_t total_bytes)
-{
-    if (d < 0) return 0;
-    if (d < total_dwords) return x[d];
-    uint32_t v = 0;
-    const uint8_t *xb = reinterpret_cast<const uint8_t *>(x);
-    for (int t = 0; t < 4; ++t) {
-        const int64_t byte = d * 4 + t;
-        if (byte < total_bytes) v |= (uint32_t)xb[byte] << (8 * t);
-    }
-    return v;
-}
-
 // WIDE: the window needs more than 64 bits, which happens only with 8-bit containers
 template <int N, int TAPS, bool A_SIGNED, bool ANY_SIGNED, bool WIDE>
-__global__ __launch_bounds__(kWindowThreads) void k_conv1d_window(Conv1dArgs p)
+__global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
 {
     constexpr int T = TAPS + 3;                    // elements of a quad's window
     constexpr int NB = (T + N - 1) / N;            // blocks that cover them
@@ -84,13 +66,6 @@ __global__ __launch_bounds__(kWindowThreads) void k_conv1d_window(Conv1dArgs p)
         for (int m = 0; m < N; ++m) bias_low += 1ull << (S * m + S - 1);
         bias_f = 1 << (S - 1);
     }
-
-    // positions inside a row are 32-bit quantities (the launcher checks (len + 2^18) * c < 2^31);
-    // only the row's base is 64-bit, and it is uniform
-    const int out_len = (int)p.out_len, len = (int)p.len;
-    const int nquads = (out_len + 3 + 3) / 4;
-    const int64_t total_bits = p.total_bytes * 8;
-    const int lead_in = p.shift_m - (TAPS - 1); // first element read for output o: o + lead_in
 
     // the four outputs of a quad from its window (elements at bits t*c of win_hi:win)
     auto quad = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[4]) {
@@ -131,84 +106,7 @@ __global__ __launch_bounds__(kWindowThreads) void k_conv1d_window(Conv1dArgs p)
         }
     };
 
-    for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
-        const int a_off = (int)((r * p.out_len) & 3);
-        // the quads of a wave start on a 128-byte line of y: the row's quad 0 sits `lead` quads
-        // into its line, so the lanes are shifted back by that much
-        const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> 2) & 7);
-        const int64_t row_bit0 = r * p.row_stride_bits;
-        const uint32_t *row_dwords = p.x + (row_bit0 >> 5); // the dword that holds the row's first bit
-        const int row_sh = (int)(row_bit0 & 31);            // and that bit's position in it
-        const int64_t room = total_bits - (row_bit0 - row_sh) - (WIDE ? 160 : 128);
-        const int bit_limit = room < 0 ? -1 : (room > 0x7fffffff ? 0x7fffffff : (int)room);
-        int32_t *yrow = p.y + r * p.out_len;
-        // The window loads of all of a lane's quads are issued before the first is used.  They
-        // are unconditional (a quad that is not interior reads the buffer's first dwords, which
-        // the launcher guarantees to exist, and ignores them), so that no branch separates them.
-        bool interior[kWindowQuads];
-        int o0v[kWindowQuads];
-        uint32_t w0[kWindowQuads], w1[kWindowQuads], w2[kWindowQuads], w3[kWindowQuads], shv[kWindowQuads];
-        bool any_edge = false;
-#pragma unroll
-        for (int s = 0; s < kWindowQuads; ++s) {
-            const int q = (int)((blockIdx.x * (unsigned)kWindowQuads + s) * (unsigned)kWindowThreads + threadIdx.x) - lead;
-            const int o0 = 4 * q - a_off;       // first output of this lane's aligned quad
-            const int i0 = o0 + lead_in;        // first element it reads
-            const int bit = row_sh + i0 * c;    // offset from row_dwords (meaningful when i0 >= 0)
-            const bool valid = q >= 0 && q < nquads;
-            interior[s] = valid && i0 >= 0 && i0 + T <= len && o0 >= 0 && o0 + 4 <= out_len && bit <= bit_limit;
-            any_edge |= valid && !interior[s];
-            o0v[s] = o0;
-            shv[s] = (uint32_t)bit & 31u;
-            const uint32_t *wp = interior[s] ? row_dwords + (bit >> 5) : p.x;
-            w0[s] = wp[0];
-            w1[s] = wp[1];
-            w2[s] = wp[2];
-            w3[s] = WIDE ? wp[3] : 0u;
-        }
-#pragma unroll
-        for (int s = 0; s < kWindowQuads; ++s) {
-            if (!interior[s]) continue;
-            int32_t out[4] = {0, 0, 0, 0};
-            const uint32_t sh = shv[s];
-            const uint64_t win = ((uint64_t)funnel_shr(w2[s], w1[s], sh) << 32) | funnel_shr(w1[s], w0[s], sh);
-            quad(win, WIDE ? funnel_shr(w3[s], w2[s], sh) : 0u, out);
-            typedef int32_t v4i __attribute__((ext_vector_type(4)));
-            const v4i v4 = {out[0], out[1], out[2], out[3]};
-            __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(&yrow[o0v[s]]));
-        }
-        // Quads at the row's ends (and where a load would leave the buffer): the same window from
-        // checked loads, element by element, zero outside the row; the same arithmetic.
-        if (__builtin_amdgcn_ballot_w64(any_edge) != 0) {
-#pragma unroll 1
-            for (int s = 0; s < kWindowQuads; ++s) {
-                const int q = (int)((blockIdx.x * (unsigned)kWindowQuads + s) * (unsigned)kWindowThreads + threadIdx.x) - lead;
-                const int o0 = 4 * q - a_off;
-                const int i0 = o0 + lead_in;
-                const int bit = row_sh + i0 * c;
-                const bool valid = q >= 0 && q < nquads;
-                const bool inside = valid && i0 >= 0 && i0 + T <= len && o0 >= 0 && o0 + 4 <= out_len && bit <= bit_limit;
-                if (!valid || inside) continue;
-                uint64_t win = 0;
-                uint32_t win_hi = 0;
-                for (int t = 0; t < T; ++t) {
-                    const int i = i0 + t;
-                    if (i < 0 || i >= len) continue;
-                    const int64_t eb = row_bit0 + (int64_t)i * c;
-                    const uint32_t w = window_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
-                    const uint64_t v = (w >> (uint32_t)(eb & 31)) & ((1u << c) - 1u);
-                    if (t * c < 64)
-                        win |= v << (t * c);
-                    else
-                        win_hi |= (uint32_t)v << (t * c - 64);
-                }
-                int32_t out[4] = {0, 0, 0, 0};
-                quad(win, win_hi, out);
-                for (int u = 0; u < 4; ++u)
-                    if (o0 + u >= 0 && o0 + u < out_len) yrow[o0 + u] = out[u];
-            }
-        }
-    }
+    for_each_output_quad<T, WIDE>(p, p.shift_m - (TAPS - 1), quad);
 }
 
 // instantiations live in one translation unit per tap count
@@ -219,7 +117,7 @@ template <int N, int TAPS>
 hipError_t launch_window_nt(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
 {
     const bool wide = (TAPS + 3) * a.c > 64;
-    dim3 b(kWindowThreads);
+    dim3 b(kStreamThreads);
 #define HIKONV_WIN(AS, ANY)                                                                              \
     do {                                                                                                 \
         if constexpr ((TAPS + 3) * 8 > 64 && N <= 3) {                                                   \

@@ -21,19 +21,14 @@ bool conv1d_window_applicable(const Conv1dArgs &a)
     if (a.N != 2 && a.N != 3 && a.N != 4 && a.N != 5 && a.N != 6 && a.N != 8 && a.N != 11) return false;
     if (a.Kp != (a.taps < a.N ? a.taps : a.N) || a.chunks != (a.taps + a.Kp - 1) / a.Kp) return false;
     if (a.N * a.c > 32) return false;                        // a block's containers come out of one dword
-    if ((a.taps + 3) * a.c > 96) return false;
     if ((a.taps + 3) * a.c > 64 && (a.c != 8 || a.N > 3)) return false;
-    if (a.total_bytes < 16) return false;                    // every lane may read the buffer's first four dwords
-    return (a.len + (1 << 18)) * a.c < (1LL << 31);
+    return quad_stream_applicable(a, a.taps + 3);
 }
 
 hipError_t launch_conv1d_window(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
     if (!conv1d_window_applicable(a)) return hipErrorInvalidValue;
-    const int64_t nquads = (a.out_len + 6) / 4;
-    const int64_t gx = ceil_div(nquads + 7, (int64_t)kWindowThreads * kWindowQuads); // lanes are shifted by up to 7 quads
-    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
-    dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
+    const dim3 g = quad_stream_grid(a);
     switch (a.taps) {
     case 1: return launch_window_t1(a, a_signed, any_signed, g, stream);
     case 2: return launch_window_t2(a, a_signed, any_signed, g, stream);

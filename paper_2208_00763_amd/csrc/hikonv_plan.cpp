@@ -209,7 +209,7 @@ struct Cand {
 constexpr double kI32Block = 15.0, kI32Elem = 11.7;
 constexpr double kRqBlock = 21.0, kRqElem = 13.9;
 constexpr double kShareChunk = 4.2;
-constexpr double kWinBase = 10.2, kWinTap = 0.9, kWinBlock = 0.45, kWinSigned = 1.5;
+constexpr double kWinBase = 8.6, kWinTap = 0.6, kWinBlock = 0.6, kWinSigned = 1.5;
 
 // plans the quad-per-lane int32 kernel takes (the launcher's rule, without the geometry)
 inline bool window_form(int taps, int n, int k)
