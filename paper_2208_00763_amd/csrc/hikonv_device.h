@@ -8,10 +8,11 @@
 namespace hikonv {
 
 // Value held by the previous lane of the wavefront (lane i receives lane i-1); lane 0
-// receives 0.  One DPP move (wave_shr:1), no LDS traffic.
+// receives 0.  One DPP move (wave_shr:1 with bound_ctrl: a lane without a source reads 0, so
+// the destination needs no preset), no LDS traffic.
 __device__ __forceinline__ uint32_t lane_shr1(uint32_t v)
 {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, true);
 }
 
 __device__ __forceinline__ uint64_t lane_shr1(uint64_t v)
