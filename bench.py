@@ -198,11 +198,13 @@ def conv2d_extra(hk, wl, name, steps):
         sg, bits = hk.BIPOLAR, 1
     n, c, h, wd = x.shape
     co, _, kh, kw = w.shape
-    x_d = torch.from_numpy(x.view("uint8")).cuda()
+    x_d = torch.from_numpy(x.view("uint8")).cuda()                # one value per byte: the baseline's input
+    x_bd = torch.zeros(n * c * h * hk.hikonv_bitdense_row_bytes(wd, bits), dtype=torch.uint8, device="cuda")
+    hk.hikonv_compact(x_d, n * c * h, wd, bits, name == "c4", x_bd)  # bit-dense: the packed kernels' input
     w_d = torch.from_numpy(w.view("uint8")).cuda()
     y = torch.empty(n * co * h * wd, dtype=torch.int32, device="cuda")
     macs = n * co * h * wd * c * kh * kw
-    report = {"macs": macs}
+    report = {"macs": macs, "input": "bit-dense %d-bit containers (packed kernels), one value per byte (baseline)" % bits}
     for label, width, acc, tight in (("wide32", 32, 64, 0), ("wide32_tight", 32, 64, 1), ("narrow24", 24, 32, 0)):
         try:
             plan = hk.hikonv_plan_ex(L_A=width, L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=0, taps=kw, tight=tight,
@@ -215,7 +217,7 @@ def conv2d_extra(hk, wl, name, steps):
         hk.hikonv_pack_weights(plan, w_d, co, c, kh, kw, pw)
 
         def run():
-            hk.hikonv_conv2d_prepacked(plan, x_d, hk.FMT_INT8, n, c, h, wd, pw, co, kh, kw, 1, 1, ws, y)
+            hk.hikonv_conv2d_prepacked(plan, x_bd, hk.FMT_BITDENSE, n, c, h, wd, pw, co, kh, kw, 1, 1, ws, y)
 
         event_ms(run, 3)
         ms = event_ms(run, steps)
@@ -230,6 +232,20 @@ def conv2d_extra(hk, wl, name, steps):
                                        "peak": VALU_LANE_RATE / 1e12, "unit": "T lane-instr/s",
                                        "frac": lane_mads / (ms * 1e-3) / VALU_LANE_RATE,
                                        "note": "packed multiply-accumulates only, whole call (input packing included)"})
+        if label == "wide32":
+            # the layer kernel alone, on input that is already packed (what a preceding layer's fused store stage leaves)
+            run_pk = lambda: hk.hikonv_conv2d_prepacked(plan, None, hk.FMT_PACKED, n, c, h, wd, pw, co, kh, kw, 1, 1, ws, y)
+            event_ms(run_pk, 3)
+            report[label]["packed_input_ms"] = event_ms(run_pk, steps)
+            if plan.N <= 4:
+                # one kernel for the whole call: every workgroup packs the input rows it needs into LDS itself
+                own = hk.with_fields(plan, kernel=hk.KERNEL_LDS)
+                try:
+                    run_1k = lambda: hk.hikonv_conv2d_fused(own, x_bd, hk.FMT_BITDENSE, n, c, h, wd, pw, co, kh, kw, 1, None, y)
+                    event_ms(run_1k, 3)
+                    report[label]["single_kernel_ms"] = event_ms(run_1k, steps)
+                except hk.HikonvError:
+                    report[label]["single_kernel_ms"] = None
 
     def run_unpacked():
         hk.hikonv_conv2d_unpacked(bits, bits, sg, x_d, n, c, h, wd, w_d, co, kh, kw, 1, 1, y)
@@ -441,6 +457,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="time all 48 cases of the 1-D bitwidth sweep (packed and unpacked), print them as JSON "
                          "and as a table, then exit")
+    ap.add_argument("--only", choices=["c3", "c4", "cnn", "requant"], default=None,
+                    help="run one of the extra workloads alone (for profiler runs) and print its report")
     ap.add_argument("--kernel", choices=["auto", "lanes", "window"], default="auto",
                     help="kernel form asked for in the 1-D plans: the library's choice, one lane per packed block "
                          "with lane exchange, or one lane per output quad")
@@ -461,6 +479,12 @@ def main():
         return 2
 
     CONV1D_KERNEL["form"] = {"auto": hk.KERNEL_AUTO, "lanes": hk.KERNEL_LANES, "window": hk.KERNEL_WINDOW}[args.kernel]
+
+    if args.only:
+        rep = {"c3": lambda: conv2d_extra(hk, wl, "c3", args.steps), "c4": lambda: conv2d_extra(hk, wl, "c4", args.steps),
+               "cnn": lambda: small_extras(hk, wl, args.steps), "requant": lambda: requant_extra(hk, wl, args.steps)}[args.only]()
+        print(json.dumps({"only": args.only, "report": rep}))
+        return 0
 
     if args.ubench:
         print(json.dumps(microbench(hk)))

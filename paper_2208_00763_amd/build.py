@@ -38,6 +38,29 @@ HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
              "-Wall", "-Wno-unused-command-line-argument", "-Wno-option-ignored"]
 
 
+# Kernels whose hand-written load/wait pipeline keeps loaded values in registers across
+# separate inline-assembly statements: a register spill between a load and its wait would make
+# them read stale data, so the build fails if the compiler reports any for them.
+NO_SPILL_SOURCES = ("hikonv_conv2d_sreg_unsigned.hip", "hikonv_conv2d_sreg_signed.hip")
+
+
+def check_no_spills(src: str, remarks: str) -> None:
+    """Parse -Rpass-analysis=kernel-resource-usage remarks; raise if a k_conv2d_sreg kernel spills."""
+    kernel, seen = None, 0
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            kernel = line.split("Function Name:")[1].strip()
+        for key in ("SGPRs Spill:", "VGPRs Spill:", "ScratchSize [bytes/lane]:"):
+            if key in line and kernel and "k_conv2d_sreg" in kernel:
+                seen += 1
+                value = int(line.split(key)[1].split()[0])
+                if value != 0:
+                    raise RuntimeError("%s: %s spills registers (%s %d); its load/wait pipeline needs all values "
+                                       "in registers" % (src, kernel, key, value))
+    if seen == 0:
+        raise RuntimeError("%s: no resource-usage remarks for k_conv2d_sreg found; the spill check did not run" % src)
+
+
 def _hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if cand and (os.path.sep not in cand or os.path.exists(cand)):
@@ -67,9 +90,13 @@ def build(force: bool = True, jobs: int = 8, extra_flags=(), out: str = LIB, obj
     def compile_one(src: str) -> str:
         obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc] + HIP_FLAGS + list(extra_flags) + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if src in NO_SPILL_SOURCES:
+            cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s" % (src, res.stderr[-4000:]))
+        if src in NO_SPILL_SOURCES:
+            check_no_spills(src, res.stderr)
         return obj
 
     with ThreadPoolExecutor(max_workers=jobs) as pool:

@@ -16,7 +16,9 @@ inline int hip_result(hipError_t e)
 {
     if (e == hipSuccess) return HIKONV_OK;
     g_last_hip_error = (int)e;
-    return e == hipErrorInvalidValue ? HIKONV_EUNSUPPORTED : HIKONV_EHIP;
+    // the launchers of this library answer hipErrorNotSupported when no kernel covers a request;
+    // everything else comes from the HIP runtime
+    return e == hipErrorNotSupported ? HIKONV_EUNSUPPORTED : HIKONV_EHIP;
 }
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }

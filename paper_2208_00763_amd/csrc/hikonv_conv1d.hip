@@ -247,12 +247,12 @@ int conv1d_tile_chunks(int N, int64_t n_blocks)
 hipError_t launch_conv1d_packed(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
     const int bpt = kWaves * a.CH * kBlocksPerWaveChunk;
-    if ((int64_t)bpt * a.N > kStageMax) return hipErrorInvalidValue;
+    if ((int64_t)bpt * a.N > kStageMax) return hipErrorNotSupported;
     // staged input dwords: ((bpt+1)*N + (chunks-1)*Kp) elements of c bits, plus alignment slack
     const int64_t in_bits = ((int64_t)(bpt + 1) * a.N + (int64_t)(a.chunks - 1) * a.Kp) * a.c;
-    if (in_bits / 32 + 4 > kInMax) return hipErrorInvalidValue;
+    if (in_bits / 32 + 4 > kInMax) return hipErrorNotSupported;
     const int64_t grid = a.tiles_per_row * a.rows;
-    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)grid), b(kThreads);
     if (a_signed)
         hipLaunchKernelGGL((k_conv1d_packed<true, true>), g, b, 0, stream, a);
@@ -265,10 +265,10 @@ hipError_t launch_conv1d_packed(const Conv1dArgs &a, bool a_signed, bool any_sig
 
 hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream)
 {
-    if (a.taps > 64) return hipErrorInvalidValue;
+    if (a.taps > 64) return hipErrorNotSupported;
     const int64_t nquads = (a.out_len + 6) / 4;
     const int64_t gx = ceil_div(nquads + 7, kThreads); // the lanes are shifted by up to 7 quads
-    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
     if (a.taps <= 7 && quad_stream_applicable(a, a.taps + 3) && ((a.taps + 3) * a.c <= 64 || a.c == 8)) {
         const bool wide_window = (a.taps + 3) * a.c > 64;

@@ -388,17 +388,17 @@ int64_t conv1d_fast_run_outputs(const Conv1dArgs &a)
 // a.tiles_per_row must hold conv1d_fast_runs_per_row(a), or the number of line-aligned intervals
 hipError_t launch_conv1d_fast(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
-    if (!conv1d_fast_applicable(a)) return hipErrorInvalidValue;
+    if (!conv1d_fast_applicable(a)) return hipErrorNotSupported;
     const int64_t runs = a.tiles_per_row * a.rows;
     const int64_t grid = ceil_div(runs, kWavesPerGroup);
-    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)grid);
     switch (a.N) {
 #define HIKONV_CASE(n) case n: return launch_n<n>(a, a_signed, any_signed, g, stream);
         HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
         HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
 #undef HIKONV_CASE
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
 }
 

@@ -467,7 +467,7 @@ hipError_t launch_rq_unpacked_t(const Conv1dArgs &a, bool a_signed, dim3 g, hipS
         break;
     switch (32 / a.rq_c_out) {
         HIKONV_LAUNCH(4) HIKONV_LAUNCH(8) HIKONV_LAUNCH(16) HIKONV_LAUNCH(32)
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
 #undef HIKONV_LAUNCH
     return hipGetLastError();
@@ -496,11 +496,11 @@ int64_t conv1d_requant_run_outputs(int N, int c, int c_out)
 
 hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
-    if (a.N < 1 || a.N > kAnyMaxN || a.chunks < 1 || a.chunks > 8) return hipErrorInvalidValue;
+    if (a.N < 1 || a.N > kAnyMaxN || a.chunks < 1 || a.chunks > 8) return hipErrorNotSupported;
     if (a.rq_run_outputs <= 0 || a.rq_run_outputs != conv1d_requant_run_outputs(a.N, a.c, a.rq_c_out))
-        return hipErrorInvalidValue;
+        return hipErrorNotSupported;
     const int64_t grid = ceil_div(a.tiles_per_row * a.rows, kWavesPerGroup);
-    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)grid);
     if (!conv1d_requant_streaming(a.N, a.c)) {
         if (any_signed)
@@ -514,7 +514,7 @@ hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_si
         HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6)
         HIKONV_CASE(7) HIKONV_CASE(8) HIKONV_CASE(9) HIKONV_CASE(10) HIKONV_CASE(11) HIKONV_CASE(12)
 #undef HIKONV_CASE
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
 }
 
@@ -523,7 +523,7 @@ hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hi
     const int per = 32 / a.rq_c_out;
     const bool windowed = a.taps <= 7 && (a.taps + per - 1) * a.c <= 64;
     const int64_t gx = ceil_div(ceil_div(a.out_len, per), windowed ? 256 * unpacked_unroll(per) : 256);
-    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
     if (!windowed) {
         if (a_signed)
@@ -536,7 +536,7 @@ hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hi
 #define HIKONV_CASE(t) case t: return launch_rq_unpacked_t<t>(a, a_signed, g, stream);
         HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6) HIKONV_CASE(7)
 #undef HIKONV_CASE
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
 }
 

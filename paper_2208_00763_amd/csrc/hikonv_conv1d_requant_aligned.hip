@@ -268,7 +268,7 @@ hipError_t launch_aligned_ct(const Conv1dArgs &a, bool a_signed, bool any_signed
             hipLaunchKernelGGL((k_conv1d_requant_aligned<C, 16, TAPS, false, false>), g, dim3(256), 0, stream, a);
         return hipGetLastError();
     } else {
-        return hipErrorInvalidValue;
+        return hipErrorNotSupported;
     }
 }
 
@@ -279,7 +279,7 @@ hipError_t launch_aligned_c(const Conv1dArgs &a, bool a_signed, bool any_signed,
 #define HIKONV_CASE(t) case t: return launch_aligned_ct<C, t>(a, a_signed, any_signed, bits_w, g, stream);
         HIKONV_CASE(1) HIKONV_CASE(2) HIKONV_CASE(3) HIKONV_CASE(4) HIKONV_CASE(5) HIKONV_CASE(6) HIKONV_CASE(7)
 #undef HIKONV_CASE
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
 }
 
@@ -311,14 +311,14 @@ hipError_t launch_conv1d_requant_aligned(const Conv1dArgs &a, bool a_signed, boo
 {
     const int per = 32 / a.c;
     const int64_t gx = ceil_div(ceil_div(a.out_len, per), 256 * kUnroll * kSteps);
-    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
     switch (a.c) {
     case 1: return launch_aligned_c<1>(a, a_signed, any_signed, bits_w, g, stream);
     case 2: return launch_aligned_c<2>(a, a_signed, any_signed, bits_w, g, stream);
     case 4: return launch_aligned_c<4>(a, a_signed, any_signed, bits_w, g, stream);
     case 8: return launch_aligned_c<8>(a, a_signed, any_signed, bits_w, g, stream);
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
 }
 

@@ -126,7 +126,7 @@ hipError_t launch_window_nt(const Conv1dArgs &a, bool a_signed, bool any_signed,
                 return hipGetLastError();                                                                \
             }                                                                                            \
         }                                                                                                \
-        if (wide) return hipErrorInvalidValue;                                                           \
+        if (wide) return hipErrorNotSupported;                                                           \
         hipLaunchKernelGGL((k_conv1d_window<N, TAPS, AS, ANY, false>), g, b, 0, stream, a);              \
         return hipGetLastError();                                                                        \
     } while (0)
@@ -147,7 +147,7 @@ hipError_t launch_conv1d_window_taps(const Conv1dArgs &a, bool a_signed, bool an
     case 6: return launch_window_nt<6, TAPS>(a, a_signed, any_signed, g, stream);
     case 8: return launch_window_nt<8, TAPS>(a, a_signed, any_signed, g, stream);
     case 11: return launch_window_nt<11, TAPS>(a, a_signed, any_signed, g, stream);
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
 }
 

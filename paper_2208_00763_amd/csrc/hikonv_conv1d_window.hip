@@ -27,7 +27,7 @@ bool conv1d_window_applicable(const Conv1dArgs &a)
 
 hipError_t launch_conv1d_window(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
-    if (!conv1d_window_applicable(a)) return hipErrorInvalidValue;
+    if (!conv1d_window_applicable(a)) return hipErrorNotSupported;
     const dim3 g = quad_stream_grid(a);
     switch (a.taps) {
     case 1: return launch_window_t1(a, a_signed, any_signed, g, stream);

@@ -307,7 +307,7 @@ __global__ __launch_bounds__(256) void k_conv2d_unpacked_3x3(Conv2dDirectArgs p,
 inline hipError_t grid_1d(int64_t total, dim3 *g)
 {
     const int64_t blocks = ceil_div(total, 256);
-    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorNotSupported;
     *g = dim3((unsigned)blocks);
     return hipSuccess;
 }
@@ -367,9 +367,9 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_sign
         row_groups = a.wave_rows * a.segs;
     const int64_t gx = ceil_div(row_groups, a.pipelined ? 4 / a.ksplit : 4);
     const int64_t gy = ceil_div(a.Co, co_tile);
-    if (gx <= 0 || gy <= 0 || gx * gy > 0x3fffffffLL) return hipErrorInvalidValue;
+    if (gx <= 0 || gy <= 0 || gx * gy > 0x3fffffffLL) return hipErrorNotSupported;
     // the kernels index rows and row groups with 32-bit arithmetic (row group * rows per wave + 63 < 2^31)
-    if (a.wave_rows >= 0x3fffffffLL || row_groups >= 0x3fffffffLL) return hipErrorInvalidValue;
+    if (a.wave_rows >= 0x3fffffffLL || row_groups >= 0x3fffffffLL) return hipErrorNotSupported;
     // 1-D grid, tiles dealt to the XCDs in contiguous ranges
     a.tiles_x = (int)gx;
     a.tiles_y = (int)gy;
@@ -388,7 +388,7 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_sign
         a.fast_store = window_rows * a.Wo * 4 < 0x7fffffffLL && !a.stores64 ? 1 : 0;
     }
     if (a.sreg) {
-        if (!wide || co_tile != 8) return hipErrorInvalidValue;
+        if (!wide || co_tile != 8) return hipErrorNotSupported;
         const int hi = a.Kp - 1;
         return any_signed ? launch_conv2d_sreg_signed(a, hi, g, stream) : launch_conv2d_sreg_unsigned(a, hi, g, stream);
     }
@@ -398,14 +398,14 @@ hipError_t launch_conv2d_packed(const Conv2dArgs &a_in, bool wide, bool any_sign
 
 hipError_t launch_conv2d_unpacked(const Conv2dDirectArgs &a, hipStream_t stream)
 {
-    if (a.Kh * a.Kw > kMaxTaps2d) return hipErrorInvalidValue;
+    if (a.Kh * a.Kw > kMaxTaps2d) return hipErrorNotSupported;
     const int64_t gy = ceil_div(a.Co, 8);
-    if (gy <= 0 || gy > 65535) return hipErrorInvalidValue;
+    if (gy <= 0 || gy > 65535) return hipErrorNotSupported;
     if (a.Kh == 3 && a.Kw == 3) {
         const int64_t groups = ceil_div((int64_t)a.Nimg * a.Ho * a.Wo, 64);
         const int ksplit = groups * gy < 2048 && a.C >= 16 ? 4 : (groups * gy < 4096 && a.C >= 8 ? 2 : 1);
         const int64_t gx3 = ceil_div(groups, 4 / ksplit);
-        if (gx3 <= 0 || gx3 > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (gx3 <= 0 || gx3 > 0x7fffffffLL) return hipErrorNotSupported;
         dim3 g3((unsigned)gx3, (unsigned)gy);
         if (a.a_signed)
             hipLaunchKernelGGL((k_conv2d_unpacked_3x3<true>), g3, dim3(256), 0, stream, a, ksplit);
@@ -414,7 +414,7 @@ hipError_t launch_conv2d_unpacked(const Conv2dDirectArgs &a, hipStream_t stream)
         return hipGetLastError();
     }
     const int64_t gx = ceil_div((int64_t)a.Nimg * a.Ho * a.Wo, 256);
-    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)gx, (unsigned)gy);
     if (a.a_signed)
         hipLaunchKernelGGL((k_conv2d_unpacked<true>), g, dim3(256), 0, stream, a);

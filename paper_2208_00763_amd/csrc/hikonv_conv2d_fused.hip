@@ -360,12 +360,12 @@ hipError_t launch_conv2d_fused(const FusedLayerArgs &f, bool any_signed, hipStre
     const int waves = f.wr * f.segs * f.ksplit;
     const int R = f.rpw * f.wr;
     if (waves < 1 || waves > 16 || f.rpw < 1 || (f.segs > 1 && f.rpw != 1) || f.rpw * f.c.Xs > 64 * (f.segs > 1 ? f.segs : 1))
-        return hipErrorInvalidValue;
-    if (f.pool && (R & 1)) return hipErrorInvalidValue;
+        return hipErrorNotSupported;
+    if (f.pool && (R & 1)) return hipErrorNotSupported;
     const size_t lds = conv2d_fused_lds(f);
-    if (lds > 64 * 1024) return hipErrorInvalidValue;
+    if (lds > 64 * 1024) return hipErrorNotSupported;
     const int64_t groups = (int64_t)f.c.Nimg * ((f.c.Ho + R - 1) / R) * f.n_tiles;
-    if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)groups), b((unsigned)(waves * 64));
     const bool gs = f.split_terms >= 4, pk = f.pack_input != 0;
     switch (f.c.N) {
@@ -381,7 +381,7 @@ hipError_t launch_conv2d_fused(const FusedLayerArgs &f, bool any_signed, hipStre
         HIKONV_FUSED(1) HIKONV_FUSED(2) HIKONV_FUSED(3) HIKONV_FUSED(4)
 #undef HIKONV_FUSED
 #undef HIKONV_FUSED4
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
     return hipGetLastError();
 }

@@ -646,7 +646,7 @@ inline hipError_t launch_conv2d_sw(const Conv2dArgs &a, int co_tile, dim3 g, hip
     case 6: launch_conv2d_n<6, ANY_SIGNED, WIDE>(a, co_tile, g, stream); break;
     case 7: launch_conv2d_n<7, ANY_SIGNED, WIDE>(a, co_tile, g, stream); break;
     case 8: launch_conv2d_n<8, ANY_SIGNED, WIDE>(a, co_tile, g, stream); break;
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
     return hipGetLastError();
 }

@@ -432,7 +432,7 @@ inline hipError_t launch_conv2d_sreg_sw(const Conv2dArgs &a, int hi, dim3 g, hip
     case 6: launch_conv2d_sreg_n<6, ANY_SIGNED>(a, hi, g, stream); break;
     case 7: launch_conv2d_sreg_n<7, ANY_SIGNED>(a, hi, g, stream); break;
     case 8: launch_conv2d_sreg_n<8, ANY_SIGNED>(a, hi, g, stream); break;
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
     return hipGetLastError();
 }

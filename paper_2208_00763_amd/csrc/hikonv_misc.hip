@@ -275,7 +275,7 @@ hipError_t launch_compact(const uint8_t *x, int64_t rows, int64_t len, int bits,
         return hipGetLastError();
     }
     const int64_t grid = ceil_div(total, 256);
-    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (grid > 0x7fffffffLL) return hipErrorNotSupported;
     hipLaunchKernelGGL(k_compact, dim3((unsigned)grid), dim3(256), 0, stream, x, rows, len, bits, c, bipolar, out,
                        row_dwords);
     return hipGetLastError();
@@ -287,7 +287,7 @@ hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t stream)
     const int64_t units = bitdense ? a.out_row_bytes / 4 : ceil_div(a.Wo, 4);
     const int64_t rows = (int64_t)a.Nimg * a.C * a.Ho;
     if (rows <= 0 || units <= 0) return hipSuccess;
-    if (rows >= (1LL << 31) || a.Wo >= (1 << 30)) return hipErrorInvalidValue;
+    if (rows >= (1LL << 31) || a.Wo >= (1 << 30)) return hipErrorNotSupported;
     dim3 g((unsigned)ceil_div(units, 256), (unsigned)(rows < 65535 ? rows : 65535));
     if (a.pool && bitdense)
         hipLaunchKernelGGL((k_epilogue<true, true>), g, dim3(256), 0, stream, a);
@@ -307,7 +307,7 @@ hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t byte
     switch (kind) {
 #define HIKONV_UB_CASE(K)                                                                      \
     case K:                                                                                    \
-        if (bytes < (size_t)blocks * 256 * 4) return hipErrorInvalidValue;                     \
+        if (bytes < (size_t)blocks * 256 * 4) return hipErrorNotSupported;                     \
         hipLaunchKernelGGL((k_ubench_valu<K>), g, b, 0, stream, iters, u, 3u, 1u);             \
         break;
         HIKONV_UB_CASE(HIKONV_UB_MAD_U32_U24)
@@ -339,11 +339,11 @@ hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t byte
         break;
     }
     case HIKONV_UB_HBM_READ:
-        if (bytes < 32) return hipErrorInvalidValue;
+        if (bytes < 32) return hipErrorNotSupported;
         hipLaunchKernelGGL(k_ubench_read, g, b, 0, stream, static_cast<const int4 *>(buf) + 1,
                            (int64_t)(bytes / 16) - 1, static_cast<int *>(buf));
         break;
-    default: return hipErrorInvalidValue;
+    default: return hipErrorNotSupported;
     }
     return hipGetLastError();
 }
