@@ -558,7 +558,7 @@ def main():
                      "traffic": traffic.get("hbm_bytes_per_launch") if traffic else None,
                      "traffic_source": ("%s (rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this kernel, not measured in this "
                                         "run)" % traffic["source"]) if traffic else None,
-                     "kernel": "k_conv1d_fast<N=3>", "algorithmic_bytes_per_launch": head["bytes"]},
+                     "kernel": "k_conv1d_window<N=3, taps=3, unsigned>", "algorithmic_bytes_per_launch": head["bytes"]},
         "by_bits": by_bits,
         "gops_1bit": by_bits["1u"]["gops"], "gops_4bit": by_bits["4u"]["gops"], "gops_8bit": by_bits["8u"]["gops"],
         "vs_unpacked_4bit": by_bits["4u"]["vs_unpacked"],
