@@ -186,6 +186,17 @@ int hikonv_compact(const void *x_dev, int64_t rows, int64_t len, int bits, int b
                    void *out_dev, void *stream);
 
 /*
+ * hikonv_check_range -- debugging aid for the convention above that values
+ * outside the declared bit range give undefined results: adds to
+ * *violations_dev (a device uint32 the caller has set, normally to 0) the
+ * number of the `count` one-value-per-byte entries at x_dev that are not a
+ * `bits`-bit value of the given signedness ({-1,+1} entries when bipolar).  Bit-dense data
+ * cannot be out of range and needs no check.  Asynchronous like every call.
+ */
+int hikonv_check_range(const void *x_dev, int64_t count, int bits, int is_signed, int bipolar,
+                       uint32_t *violations_dev, void *stream);
+
+/*
  * hikonv_conv1d -- packed 1-D convolution (Eq. pad_f, Theorem 2):
  *   y[r][m] = sum_k h_r[m-k] g[k],  h_r = zero extension of row r of x.
  * plan: mode CONV1D, L_A = L_B = 32, taps == `taps`, from hikonv_plan_ex.

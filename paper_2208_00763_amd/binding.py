@@ -69,6 +69,7 @@ SIGNATURES = {
     "hikonv_plan_cost": (_i, [_pp]),
     "hikonv_bitdense_row_bytes": (_i64, [_i64, _i]),
     "hikonv_compact": (_i, [_vp, _i64, _i64, _i, _i, _vp, _vp]),
+    "hikonv_check_range": (_i, [_vp, _i64, _i, _i, _i, _vp, _vp]),
     "hikonv_conv1d": (_i, [_pp, _vp, _i, _i64, _i64, _vp, _i, _i, _vp, _vp]),
     "hikonv_conv1d_unpacked": (_i, [_i, _i, _i, _vp, _i, _i64, _i64, _vp, _i, _i, _vp, _vp]),
     "hikonv_conv1d_requant": (_i, [_pp, _vp, _i, _i64, _i64, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
@@ -174,6 +175,11 @@ def hikonv_strerror(code):
 
 
 # ---- device entry points ---------------------------------------------------------------
+def hikonv_check_range(x, count, bits, is_signed, bipolar, violations, stream=None):
+    _check(lib.hikonv_check_range(_ptr(x), count, bits, int(is_signed), int(bipolar), _ptr(violations), _stream(stream)),
+           "hikonv_check_range")
+
+
 def hikonv_compact(x, rows, length, bits, bipolar, out, stream=None):
     _check(lib.hikonv_compact(_ptr(x), rows, length, bits, int(bipolar), _ptr(out), _stream(stream)), "hikonv_compact")
 

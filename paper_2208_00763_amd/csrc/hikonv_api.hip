@@ -358,6 +358,19 @@ extern "C" int hikonv_compact(const void *x_dev, int64_t rows, int64_t len, int 
                                      static_cast<uint32_t *>(out_dev), row_dwords, static_cast<hipStream_t>(stream)));
 }
 
+extern "C" int hikonv_check_range(const void *x_dev, int64_t count, int bits, int is_signed, int bipolar,
+                                  uint32_t *violations_dev, void *stream)
+{
+    if (container_bits(bits) == 0 || count < 0 || (bipolar && bits != 1)) return HIKONV_EINVAL;
+    if (count == 0) return HIKONV_OK;
+    if (!x_dev || !violations_dev || !aligned(violations_dev, 4)) return HIKONV_EINVAL;
+    const bool sgn = is_signed || bipolar;
+    const int lo = sgn ? -(1 << (bits - 1)) : 0;
+    const int hi = sgn ? (1 << (bits - 1)) - 1 : (1 << bits) - 1;
+    return hip_result(launch_check_range(static_cast<const uint8_t *>(x_dev), count, lo, hi, sgn, bipolar != 0,
+                                         violations_dev, static_cast<hipStream_t>(stream)));
+}
+
 extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x_format, int64_t rows, int64_t len,
                              const void *g_dev, int taps, int out_mode, int32_t *y_dev, void *stream)
 {

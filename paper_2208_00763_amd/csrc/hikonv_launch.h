@@ -191,6 +191,8 @@ hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t stream);
 // ---- misc --------------------------------------------------------------------------
 hipError_t launch_compact(const uint8_t *x, int64_t rows, int64_t len, int bits, int bipolar,
                           uint32_t *out, int64_t row_dwords, hipStream_t stream);
+hipError_t launch_check_range(const uint8_t *x, int64_t count, int lo, int hi, int is_signed, int bipolar,
+                              uint32_t *violations, hipStream_t stream);
 hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t bytes, hipStream_t stream);
 hipError_t launch_selftest_lane_shift(int32_t *out, hipStream_t stream);
 

@@ -249,6 +249,21 @@ __global__ __launch_bounds__(256) void k_ubench_read(const int4 *src, int64_t n1
     if (acc == 0x7fffffff) sink[0] = acc; // practically never: keeps the loads alive
 }
 
+// Counts the bytes of a one-value-per-byte buffer that lie outside the declared value range:
+// [lo, hi] as signed bytes, or, for {-1,+1} data, anything but -1 and +1.  One atomic per wave.
+__global__ void __launch_bounds__(256) k_check_range(const uint8_t *x, int64_t count, int lo, int hi, int is_signed,
+                                                      int bipolar, uint32_t *violations)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    uint32_t bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const int v = is_signed ? (int)(int8_t)x[i] : (int)x[i];
+        bad += bipolar ? (v != 1 && v != -1) : (v < lo || v > hi);
+    }
+    for (int off = 32; off > 0; off >>= 1) bad += __shfl_down(bad, off, 64);
+    if ((threadIdx.x & 63) == 0 && bad) atomicAdd(violations, bad);
+}
+
 __global__ void k_selftest_lane_shift(int32_t *out)
 {
     out[threadIdx.x] = (int32_t)lane_shr1((uint32_t)(threadIdx.x + 100));
@@ -278,6 +293,16 @@ hipError_t launch_compact(const uint8_t *x, int64_t rows, int64_t len, int bits,
     if (grid > 0x7fffffffLL) return hipErrorNotSupported;
     hipLaunchKernelGGL(k_compact, dim3((unsigned)grid), dim3(256), 0, stream, x, rows, len, bits, c, bipolar, out,
                        row_dwords);
+    return hipGetLastError();
+}
+
+hipError_t launch_check_range(const uint8_t *x, int64_t count, int lo, int hi, int is_signed, int bipolar,
+                              uint32_t *violations, hipStream_t stream)
+{
+    if (count <= 0) return hipSuccess;
+    const int64_t want = ceil_div(count, 256 * 16);
+    const unsigned grid = (unsigned)(want < 1 ? 1 : want > 8192 ? 8192 : want);
+    hipLaunchKernelGGL(k_check_range, dim3(grid), dim3(256), 0, stream, x, count, lo, hi, is_signed, bipolar, violations);
     return hipGetLastError();
 }
 

@@ -329,6 +329,9 @@ def test_conv1d_and_misc_argument_checks():
     assert code(lambda: hk.hikonv_conv1d(narrow, x, hk.FMT_INT8, 2, 100, g, 3, hk.OUT_FULL, y, stream=0)) == hk.EUNSUPPORTED
     assert code(lambda: hk.hikonv_compact(x, 2, 100, 9, False, y, stream=0)) == hk.EINVAL
     assert code(lambda: hk.hikonv_compact(x, 2, 100, 4, True, y, stream=0)) == hk.EINVAL                          # bipolar needs 1 bit
+    assert code(lambda: hk.hikonv_check_range(x, 100, 0, False, False, y, stream=0)) == hk.EINVAL
+    assert code(lambda: hk.hikonv_check_range(x, 100, 4, False, True, y, stream=0)) == hk.EINVAL                  # bipolar needs 1 bit
+    assert code(lambda: hk.hikonv_check_range(x, 100, 4, False, False, _Fake(0x3002), stream=0)) == hk.EINVAL     # counter alignment
     assert code(lambda: hk.hikonv_epilogue(x, 1, 4, 8, 8, 40, 15, True, 4, hk.FMT_BITDENSE, y, stream=0)) == hk.EINVAL   # shift
     assert code(lambda: hk.hikonv_epilogue(x, 1, 4, 8, 8, 3, 16, True, 4, hk.FMT_BITDENSE, y, stream=0)) == hk.EINVAL    # qmax > 2^bits-1
     assert code(lambda: hk.hikonv_epilogue(x, 1, 4, 1, 8, 3, 15, True, 4, hk.FMT_BITDENSE, y, stream=0)) == hk.EINVAL    # nothing left after pooling

@@ -156,6 +156,34 @@ def test_compact_matches_oracle_layout():
         assert np.array_equal(compact(odd, 1, bipolar=True).cpu().numpy().reshape(ref.shape), ref)
 
 
+def test_check_range_counts_out_of_range_values():
+    # counts are compared with a count in numpy over the same bytes; sizes below, at and above one grid stride
+    rng = np.random.default_rng(11)
+    for count in (1, 63, 64, 4097, 1 << 20, (8192 * 256) * 2 + 77):
+        raw = rng.integers(-128, 128, count).astype(np.int8)
+        x_d = dev(raw.view(np.uint8))
+        for bits in range(1, 9):
+            for signed in (False, True):
+                v = raw.astype(np.int32) if signed else raw.view(np.uint8).astype(np.int32)
+                lo, hi = (-(1 << (bits - 1)), (1 << (bits - 1)) - 1) if signed else (0, (1 << bits) - 1)
+                n_bad = torch.full((1,), 5, dtype=torch.int32, device="cuda")      # the call adds to the counter
+                hk.hikonv_check_range(x_d, count, bits, signed, False, n_bad)
+                assert int(n_bad.item()) == 5 + int(((v < lo) | (v > hi)).sum()), (count, bits, signed)
+        n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+        hk.hikonv_check_range(x_d, count, 1, False, True, n_bad)
+        assert int(n_bad.item()) == int(((raw != 1) & (raw != -1)).sum())
+    # in-range data of every kind the generators make: nothing counted
+    for bits, signed in ((1, False), (4, True), (8, False), (8, True)):
+        x = wl.uniform_values(wl.rng_for("rg", bits, signed), (7, 1001), bits, signed)
+        n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+        hk.hikonv_check_range(dev(x), x.size, bits, signed, False, n_bad)
+        assert int(n_bad.item()) == 0
+    x = wl.bipolar_values(wl.rng_for("rgb"), (3, 999))
+    n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hk.hikonv_check_range(dev(x), x.size, 1, False, True, n_bad)
+    assert int(n_bad.item()) == 0
+
+
 def test_epilogue_matches_oracle():
     rng = np.random.default_rng(3)
     for (n, c, h, w, shift, pool) in ((1, 3, 6, 10, 3, True), (2, 5, 7, 9, 0, False), (1, 4, 9, 17, 5, True),
