@@ -843,8 +843,7 @@ extern "C" int hikonv_conv2d_fused(const hikonv_plan_t *plan, const void *x_dev,
         f.in.c = x_format == HIKONV_FMT_INT8 ? 8 : container_bits(plan->bits_a);
         f.in.row_bytes = x_format == HIKONV_FMT_INT8 ? W : hikonv_bitdense_row_bytes(W, plan->bits_a);
         // in-kernel packing reads a word's N containers as one 32-bit window of a tensor that is a
-        // whole number of dwords
-        // whole number of dwords below 2^31, with bit offsets inside an image below 2^30
+        // whole number of dwords below 2^32 bytes, with bit offsets inside an image below 2^30
         const int64_t in_bytes = (int64_t)N * C * H * f.in.row_bytes;
         f.pack_input = plan->N * f.in.c <= 32 && (in_bytes & 3) == 0 && in_bytes < (1LL << 32) &&
                                (int64_t)H * f.in.row_bytes * 32 < (1LL << 30)

@@ -289,11 +289,14 @@ def test_cnn_forward_config5(size, fused):
     if fused == "layer":
         assert all(net.layer_kernel), "every layer of this network fits the one-kernel-per-layer form"
         # the chain as the benchmark runs it: intermediate accumulators never stored
-        lean = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs, fused="layer",
-                         keep_accs=False)
-        last, _ = lean.forward(x_bd, 1, h, w, shifts)
-        torch.cuda.synchronize()
-        assert np.array_equal(last.cpu().numpy().reshape(ref_accs[-1].shape), ref_accs[-1])
+        # (exact-interval plans, as there, and the paper's slices)
+        for tight in (1, 0):
+            lean = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs, fused="layer",
+                             keep_accs=False, tight=tight)
+            last, _ = lean.forward(x_bd, 1, h, w, shifts)
+            torch.cuda.synchronize()
+            assert all(lean.layer_kernel)
+            assert np.array_equal(last.cpu().numpy().reshape(ref_accs[-1].shape), ref_accs[-1]), tight
     if fused is True:
         # the baseline chain (one multiply per product) that the benchmark times beside it
         base = UnpackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs)
