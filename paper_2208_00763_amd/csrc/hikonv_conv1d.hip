@@ -202,11 +202,12 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
     }
 }
 
-// Streaming form of the baseline: one lane produces aligned quads of outputs, each from a
-// window of TAPS + 3 elements, on the same skeleton as the packed quad-per-lane kernel (same
-// loads, same stores, same row handling); the arithmetic is one v_mad_i32_i24 per low-bit
-// product.  Needs the window within 64 bits (three dwords) or, WIDE, 96 bits (four).
-template <bool A_SIGNED, int TAPS, bool WIDE>
+// Streaming form of the baseline: one lane produces aligned groups of G outputs, each from a
+// window of TAPS + G - 1 elements, on the same skeleton as the packed window kernel (same
+// loads, same stores, same row handling, the same group size for the same containers); the
+// arithmetic is one v_mad_i32_i24 per low-bit product.  Needs the window within 64 bits (three
+// dwords) or, WIDE, 96 bits (four).
+template <bool A_SIGNED, int TAPS, bool WIDE, int G>
 __global__ __launch_bounds__(kStreamThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
 {
     __shared__ int32_t s_g[8];
@@ -217,20 +218,20 @@ __global__ __launch_bounds__(kStreamThreads) void k_conv1d_unpacked_fast(Conv1dA
 #pragma unroll
     for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
     const int c = WIDE ? 8 : p.c, b = p.b;
-    auto direct = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[4]) {
+    auto direct = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[G]) {
 #pragma unroll
-        for (int t = 0; t < TAPS + 3; ++t) {
+        for (int t = 0; t < TAPS + G - 1; ++t) {
             // containers never straddle bit 64 (their width divides 64)
             const uint32_t bits_t = WIDE && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
             const int32_t v = field<A_SIGNED>(bits_t, 0u, (uint32_t)b);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < G; ++u) {
                 const int k = u + TAPS - 1 - t;
                 if (k >= 0 && k < TAPS) out[u] = __mul24(v, gk[k]) + out[u];
             }
         }
     };
-    for_each_output_quad<TAPS + 3, WIDE>(p, p.shift_m - (TAPS - 1), direct);
+    for_each_output_group<G, TAPS + G - 1, WIDE>(p, p.shift_m - (TAPS - 1), direct);
 }
 
 } // namespace
@@ -270,19 +271,24 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
     const int64_t gx = ceil_div(nquads + 7, kThreads); // the lanes are shifted by up to 7 quads
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535)), b(kThreads);
-    if (a.taps <= 7 && quad_stream_applicable(a, a.taps + 3) && ((a.taps + 3) * a.c <= 64 || a.c == 8)) {
-        const bool wide_window = (a.taps + 3) * a.c > 64;
-        g = quad_stream_grid(a);
+    const bool octets = stream_group(a.c) == 8; // eight outputs per window, by the packed window kernel's rule
+    if (a.taps <= 7 && quad_stream_applicable(a, a.taps + (octets ? 7 : 3)) && ((a.taps + 3) * a.c <= 64 || a.c == 8)) {
+        const bool wide_window = !octets && (a.taps + 3) * a.c > 64;
+        g = quad_stream_grid(a, octets ? 8 : 4);
 #define HIKONV_UNP(T)                                                                               \
     case T:                                                                                         \
-        if (a_signed && wide_window)                                                                \
-            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T, true>), g, b, 0, stream, a);        \
+        if (octets && a_signed)                                                                     \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T, false, 8>), g, b, 0, stream, a);    \
+        else if (octets)                                                                            \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T, false, 8>), g, b, 0, stream, a);   \
+        else if (a_signed && wide_window)                                                           \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T, true, 4>), g, b, 0, stream, a);     \
         else if (a_signed)                                                                          \
-            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T, false>), g, b, 0, stream, a);       \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<true, T, false, 4>), g, b, 0, stream, a);    \
         else if (wide_window)                                                                       \
-            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T, true>), g, b, 0, stream, a);       \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T, true, 4>), g, b, 0, stream, a);    \
         else                                                                                        \
-            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T, false>), g, b, 0, stream, a);      \
+            hipLaunchKernelGGL((k_conv1d_unpacked_fast<false, T, false, 4>), g, b, 0, stream, a);   \
         break;
         switch (a.taps) {
             HIKONV_UNP(1) HIKONV_UNP(2) HIKONV_UNP(3) HIKONV_UNP(4) HIKONV_UNP(5) HIKONV_UNP(6) HIKONV_UNP(7)

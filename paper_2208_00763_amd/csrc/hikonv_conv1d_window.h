@@ -1,28 +1,29 @@
-// Packed 1-D convolution, one lane = one aligned quad of outputs (the form the int32-output
-// path takes wherever it applies).
+// Packed 1-D convolution, one lane = one aligned group of G outputs (the form the
+// int32-output path takes wherever it applies).  G = 8 with containers of 1, 2 or 4 bits,
+// G = 4 with 8-bit containers.
 //
 // Theorem 2 cuts a long convolution into F_{N,K} blocks whose products overlap by K - 1
-// segments.  Here a lane walks the few blocks that cover its own four outputs one after the
+// segments.  Here a lane walks the few blocks that cover its own G outputs one after the
 // other and carries the high part of a product into the next block in a register, as the
 // paper's processor loop does with its `prev` and `this` words (Section "General purpose
 // processors"), instead of handing it to the neighbour lane:
-//   window  the TAPS + 3 consecutive elements the quad needs, read straight from global memory
-//           as three (four) dwords and funnel-shifted to bit 0;
-//   pack    A_j = sum_n e[jN + n] 2^(S n), j = 0 .. ceil((TAPS+3)/N) - 1        (Eq. inpack)
+//   window  the T = TAPS + G - 1 consecutive elements the group needs, read straight from
+//           global memory as three (four) dwords and funnel-shifted to bit 0;
+//   pack    A_j = sum_n e[jN + n] 2^(S n), j = 0 .. ceil(T/N) - 1                (Eq. inpack)
 //   mul     Acc_j = bias + Hi(Acc_(j-1)) + sum_c A_(j-c) B_c    (v_mad_u64_u32 / v_mad_i64_i32;
 //           B_c holds taps cK .. cK+K-1, K = min(TAPS, N); a kernel wider than one B word
 //           multiplies the packed word of the block c places back, which is the input
 //           delayed by cK = cN elements)
 //   align   Hi(Acc) = Acc >> S N, added through the multiply-add's addend (Eq. 1dnx in the
 //           packed domain)
-//   split   y[.] = field_i(Acc_j) - 2^(S-1) for the four segments jN + i = TAPS-1 .. TAPS+2
+//   split   y[.] = field_i(Acc_j) - 2^(S-1) for the G segments jN + i = TAPS-1 .. TAPS+G-2
 //           (Eq. output_split in bias form)
-//   store   one aligned int32x4 store per quad with the streaming hint; the quads of a wave
-//           cover whole 128-byte lines of y.
-// No LDS, no lane exchange, no barrier; each lane packs TAPS + 3 elements for 4 outputs (the
-// lane-exchange kernel packs every element once), which is the cheaper side of the trade on
-// this chip because the path is bound by the bytes it writes.
-// Quads at a row's ends, or whose loads would leave the buffer, assemble the same window from
+//   store   aligned int32x4 stores with the streaming hint; every store instruction of a wave
+//           covers whole 128-byte lines of y (see hikonv_quad_stream.h).
+// No lane exchange, no barrier; each lane packs T elements for G outputs (the lane-exchange
+// kernel packs every element once), which is the cheaper side of the trade on this chip
+// because the path is bound by the bytes it writes.
+// Groups at a row's ends, or whose loads would leave the buffer, assemble the same window from
 // checked element loads (zero outside the row, Eq. pad_f0) and run the same arithmetic.
 #ifndef HIKONV_CONV1D_WINDOW_H
 #define HIKONV_CONV1D_WINDOW_H
@@ -31,11 +32,12 @@
 
 namespace hikonv {
 
+// G: outputs per window (8 with containers of up to 4 bits, else 4).
 // WIDE: the window needs more than 64 bits, which happens only with 8-bit containers
-template <int N, int TAPS, bool A_SIGNED, bool ANY_SIGNED, bool WIDE>
+template <int N, int TAPS, bool A_SIGNED, bool ANY_SIGNED, bool WIDE, int G>
 __global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
 {
-    constexpr int T = TAPS + 3;                    // elements of a quad's window
+    constexpr int T = TAPS + G - 1;                // elements of a group's window
     constexpr int NB = (T + N - 1) / N;            // blocks that cover them
     constexpr int K = TAPS < N ? TAPS : N;         // taps per B word
     constexpr int CH = (TAPS + K - 1) / K;         // B words (CH > 1 only with K == N)
@@ -67,8 +69,8 @@ __global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
         bias_f = 1 << (S - 1);
     }
 
-    // the four outputs of a quad from its window (elements at bits t*c of win_hi:win)
-    auto quad = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[4]) {
+    // the G outputs of a group from its window (elements at bits t*c of win_hi:win)
+    auto group = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[G]) {
         uint32_t a[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
@@ -100,35 +102,49 @@ __global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
             for (int i = 0; i < N; ++i) {
                 constexpr int first = TAPS - 1;
                 const int m = j * N + i;
-                if (m >= first && m < first + 4)
+                if (m >= first && m < first + G)
                     out[m - first] = (int32_t)((uint32_t)(acc >> (S * i)) & fmask) - bias_f;
             }
         }
     };
 
-    for_each_output_quad<T, WIDE>(p, p.shift_m - (TAPS - 1), quad);
+    for_each_output_group<G, T, WIDE>(p, p.shift_m - (TAPS - 1), group);
 }
 
 // instantiations live in one translation unit per tap count
 template <int TAPS>
-hipError_t launch_conv1d_window_taps(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream);
+hipError_t launch_conv1d_window_taps(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream);
 
+// outputs per window for this call
+inline int conv1d_window_group(const Conv1dArgs &a) { return stream_group(a.c); }
+
+// containers of 1, 2 or 4 bits: eight outputs per window (taps + 7 containers within 64 bits);
+// 8-bit containers: four, from a window of up to 96 bits
 template <int N, int TAPS>
-hipError_t launch_window_nt(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+hipError_t launch_window_nt(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
-    const bool wide = (TAPS + 3) * a.c > 64;
-    dim3 b(kStreamThreads);
+    const bool octets = conv1d_window_group(a) == 8;
+    const bool wide = !octets && (TAPS + 3) * a.c > 64;
+    const dim3 g = quad_stream_grid(a, octets ? 8 : 4), b(kStreamThreads);
 #define HIKONV_WIN(AS, ANY)                                                                              \
     do {                                                                                                 \
+        if (octets) {                                                                                    \
+            hipLaunchKernelGGL((k_conv1d_window<N, TAPS, AS, ANY, false, 8>), g, b, 0, stream, a);       \
+            return hipGetLastError();                                                                    \
+        }                                                                                                \
         if constexpr ((TAPS + 3) * 8 > 64 && N <= 3) {                                                   \
             if (wide) {                                                                                  \
-                hipLaunchKernelGGL((k_conv1d_window<N, TAPS, AS, ANY, true>), g, b, 0, stream, a);       \
+                hipLaunchKernelGGL((k_conv1d_window<N, TAPS, AS, ANY, true, 4>), g, b, 0, stream, a);    \
                 return hipGetLastError();                                                                \
             }                                                                                            \
         }                                                                                                \
-        if (wide) return hipErrorNotSupported;                                                           \
-        hipLaunchKernelGGL((k_conv1d_window<N, TAPS, AS, ANY, false>), g, b, 0, stream, a);              \
-        return hipGetLastError();                                                                        \
+        if constexpr (N <= 4) { /* quads: 8-bit containers, so N <= 4 */                                 \
+            if (!wide) {                                                                                 \
+                hipLaunchKernelGGL((k_conv1d_window<N, TAPS, AS, ANY, false, 4>), g, b, 0, stream, a);   \
+                return hipGetLastError();                                                                \
+            }                                                                                            \
+        }                                                                                                \
+        return hipErrorNotSupported;                                                                     \
     } while (0)
     if (a_signed) HIKONV_WIN(true, true);
     if (any_signed) HIKONV_WIN(false, true);
@@ -137,16 +153,16 @@ hipError_t launch_window_nt(const Conv1dArgs &a, bool a_signed, bool any_signed,
 }
 
 template <int TAPS>
-hipError_t launch_conv1d_window_taps(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+hipError_t launch_conv1d_window_taps(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
     switch (a.N) {
-    case 2: return launch_window_nt<2, TAPS>(a, a_signed, any_signed, g, stream);
-    case 3: return launch_window_nt<3, TAPS>(a, a_signed, any_signed, g, stream);
-    case 4: return launch_window_nt<4, TAPS>(a, a_signed, any_signed, g, stream);
-    case 5: return launch_window_nt<5, TAPS>(a, a_signed, any_signed, g, stream);
-    case 6: return launch_window_nt<6, TAPS>(a, a_signed, any_signed, g, stream);
-    case 8: return launch_window_nt<8, TAPS>(a, a_signed, any_signed, g, stream);
-    case 11: return launch_window_nt<11, TAPS>(a, a_signed, any_signed, g, stream);
+    case 2: return launch_window_nt<2, TAPS>(a, a_signed, any_signed, stream);
+    case 3: return launch_window_nt<3, TAPS>(a, a_signed, any_signed, stream);
+    case 4: return launch_window_nt<4, TAPS>(a, a_signed, any_signed, stream);
+    case 5: return launch_window_nt<5, TAPS>(a, a_signed, any_signed, stream);
+    case 6: return launch_window_nt<6, TAPS>(a, a_signed, any_signed, stream);
+    case 8: return launch_window_nt<8, TAPS>(a, a_signed, any_signed, stream);
+    case 11: return launch_window_nt<11, TAPS>(a, a_signed, any_signed, stream);
     default: return hipErrorNotSupported;
     }
 }

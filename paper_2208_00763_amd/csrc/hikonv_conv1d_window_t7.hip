@@ -2,8 +2,8 @@
 #include "hikonv_conv1d_window.h"
 
 namespace hikonv {
-hipError_t launch_window_t7(const Conv1dArgs &a, bool a_signed, bool any_signed, dim3 g, hipStream_t stream)
+hipError_t launch_window_t7(const Conv1dArgs &a, bool a_signed, bool any_signed, hipStream_t stream)
 {
-    return launch_conv1d_window_taps<7>(a, a_signed, any_signed, g, stream);
+    return launch_conv1d_window_taps<7>(a, a_signed, any_signed, stream);
 }
 } // namespace hikonv

@@ -3,14 +3,17 @@
 // window loads, stores and row ends are the same code, so that the two kernels differ only in
 // the arithmetic that turns a window of T elements into four outputs.
 //
-// A lane owns kStreamQuads aligned quads of outputs per row (kStreamThreads quads apart).  The
-// window of a quad, its T consecutive elements starting at output index + lead_in, is read
-// straight from global memory as three (WIDE: four) dwords and funnel-shifted to bit 0; the
-// quad leaves as one int32x4 store with the streaming hint, and the quads of a wave cover
-// whole 128-byte lines of y.  Everything that depends only on the row (the range of quads whose
+// A lane owns aligned groups of G outputs (G = 8 where the window of taps + 7 containers fits
+// 64 bits, i.e. containers of 1, 2 or 4 bits; else aligned quads, G = 4): 16 outputs per row
+// pass, its groups kStreamThreads groups apart.  The window of a group, its T = taps + G - 1
+// consecutive elements starting at output index + lead_in, is read straight from global memory
+// as three (WIDE: four) dwords and funnel-shifted to bit 0; the group leaves as int32x4 stores
+// and the groups of a wave cover whole 128-byte lines of y.  Eight outputs per window halve
+// the index arithmetic per output and let neighbouring outputs share the window's elements
+// (the packed kernel packs (taps + 7)/8 elements per output instead of (taps + 3)/4).  Everything that depends only on the row (the range of quads whose
 // window lies inside the row and the buffer, bit and byte offsets) is worked out once per row
-// with scalar arithmetic; a quad then costs two compares, four integer instructions for its
-// addresses and one select.  Quads at a row's ends assemble the same window from checked
+// with scalar arithmetic; a group then costs two compares, four integer instructions for its
+// addresses and one select.  Groups at a row's ends assemble the same window from checked
 // element loads (zero outside the row, Eq. pad_f0).
 #ifndef HIKONV_QUAD_STREAM_H
 #define HIKONV_QUAD_STREAM_H
@@ -21,7 +24,10 @@
 namespace hikonv {
 
 constexpr int kStreamThreads = 256;
-constexpr int kStreamQuads = 4;
+// outputs per window: 8 where taps + 7 containers fit 64 bits (containers of 1, 2 or 4 bits), else 4
+inline int stream_group(int container_bits) { return container_bits <= 4 ? 8 : 4; }
+// groups a lane makes per row pass: 16 outputs either way (measured: four groups of 8 are slower than two)
+constexpr int stream_steps(int group) { return 16 / group; }
 
 __device__ __forceinline__ uint32_t stream_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
                                                          int64_t total_bytes)
@@ -37,10 +43,6 @@ __device__ __forceinline__ uint32_t stream_dword_checked(const uint32_t *x, int6
     return v;
 }
 
-// floor(a / 4) and ceil(a / 4) for any sign
-__device__ __forceinline__ int floor_quarter(int a) { return a >> 2; }
-__device__ __forceinline__ int ceil_quarter(int a) { return (a + 3) >> 2; }
-
 // the launcher's conditions for this skeleton: positions inside a row and byte offsets inside
 // the input buffer fit 32 bits, the buffer holds at least four dwords, containers are 1, 2, 4 or 8 bits
 inline bool quad_stream_applicable(const Conv1dArgs &a, int window_elems)
@@ -51,19 +53,28 @@ inline bool quad_stream_applicable(const Conv1dArgs &a, int window_elems)
     return (a.len + (1 << 18)) * a.c < (1LL << 31);
 }
 
-inline dim3 quad_stream_grid(const Conv1dArgs &a)
+inline dim3 quad_stream_grid(const Conv1dArgs &a, int group = 4)
 {
-    const int64_t nquads = (a.out_len + 6) / 4;
-    const int64_t gx = ceil_div(nquads + 7, (int64_t)kStreamThreads * kStreamQuads); // lanes are shifted by up to 7 quads
+    const int64_t ngroups = (a.out_len + 2 * (group - 1)) / group;
+    const int steps = stream_steps(group);
+    // lanes are shifted back by up to a 128-byte line of groups
+    const int64_t gx = ceil_div(ngroups + 32 / group - 1, (int64_t)kStreamThreads * steps);
     return dim3((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));
 }
 
-// compute(win, win_hi, out): the T elements of the window sit at bits t*c of win_hi:win
-template <int T, bool WIDE, typename F>
-__device__ __forceinline__ void for_each_output_quad(const Conv1dArgs &p, int lead_in, F &&compute)
+// compute(win, win_hi, out): the T = taps + G - 1 elements of the window sit at bits t*c of
+// win_hi:win; out receives the group's G outputs.  G = 4: one streaming int32x4 store per group.
+// G = 8 (windows within 64 bits): two int32x4 stores per group.
+template <int G, int T, bool WIDE, typename F>
+__device__ __forceinline__ void for_each_output_group(const Conv1dArgs &p, int lead_in, F &&compute)
 {
+    static_assert(G == 4 || G == 8, "groups of 4 or 8 outputs");
+    static_assert(G == 4 || !WIDE, "a window wider than 64 bits feeds a quad only");
+    constexpr int LG = G == 4 ? 2 : 3;
+    constexpr int STEPS = stream_steps(G);
+    constexpr int LINE = 32 / G;                                    // groups per 128-byte line of y
     const int out_len = (int)p.out_len, len = (int)p.len;
-    const int nquads = (out_len + 3 + 3) / 4;
+    const int ngroups = (out_len + 2 * (G - 1)) / G;
     const int c = WIDE ? 8 : p.c;
     const int lc = WIDE ? 3 : (p.c == 1 ? 0 : p.c == 2 ? 1 : p.c == 4 ? 2 : 3); // log2 of the container width
     const int64_t total_bits = p.total_bytes * 8;
@@ -71,53 +82,58 @@ __device__ __forceinline__ void for_each_output_quad(const Conv1dArgs &p, int le
     typedef uint32_t u32x3_dw __attribute__((ext_vector_type(3), aligned(4)));
     typedef uint32_t u32x4_dw __attribute__((ext_vector_type(4), aligned(4)));
     typedef int32_t v4i __attribute__((ext_vector_type(4)));
+    __shared__ v4i s_turn[G == 8 ? kStreamThreads * 2 : 1];        // G = 8: 2 KB per wave, see the stores below
+    auto floor_g = [](int a) { return a >> LG; };                   // floor(a / G) and ceil(a / G) for any sign
+    auto ceil_g = [](int a) { return (a + G - 1) >> LG; };
 
     for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
         // ---- per row, wave-uniform ----
-        const int a_off = (int)((r * p.out_len) & 3);
-        // the quads of a wave start on a 128-byte line of y: the row's quad 0 sits `lead` quads
+        // groups are aligned in memory (y_dev itself is 16-byte aligned): the row's first group
+        // starts a_off outputs before the row
+        const int a_off = (int)((p.y_phase + r * p.out_len) & (G - 1));
+        // the groups of a wave start on a 128-byte line of y: the row's group 0 sits `lead` groups
         // into its line, so the lanes are shifted back by that much
-        const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> 2) & 7);
+        const int lead = (int)(((p.y_phase + r * p.out_len - a_off) >> LG) & (LINE - 1));
         const int64_t row_bit0 = r * p.row_stride_bits;
         const int row_sh = (int)(row_bit0 & 31);                    // bit of the row's first element in its dword
         const uint32_t row_byte = (uint32_t)((row_bit0 >> 5) << 2); // byte offset of that dword in the buffer
         const int64_t room = total_bits - (row_bit0 - row_sh) - (WIDE ? 160 : 128);
         const int bit_limit = room < 0 ? -1 : (room > 0x7fffffff ? 0x7fffffff : (int)room);
-        // quad q: first output o0 = 4q - a_off, first element i0 = o0 + lead_in, window at bit
+        // group q: first output o0 = G q - a_off, first element i0 = o0 + lead_in, window at bit
         // row_sh + i0*c of the row's first dword.  It is interior (window inside the row and the
-        // buffer, all four outputs exist) for q_lo <= q <= q_hi:
-        const int k_in = lead_in - a_off;                           // i0 = 4q + k_in
-        int q_lo = ceil_quarter(-k_in);
-        if (q_lo < ceil_quarter(a_off)) q_lo = ceil_quarter(a_off);
+        // buffer, all G outputs exist) for q_lo <= q <= q_hi:
+        const int k_in = lead_in - a_off;                           // i0 = G q + k_in
+        int q_lo = ceil_g(-k_in);
+        if (q_lo < ceil_g(a_off)) q_lo = ceil_g(a_off);
         if (q_lo < 0) q_lo = 0;
-        int q_hi = nquads - 1;
-        if (q_hi > floor_quarter(len - T - k_in)) q_hi = floor_quarter(len - T - k_in);
-        if (q_hi > floor_quarter(out_len - 4 + a_off)) q_hi = floor_quarter(out_len - 4 + a_off);
+        int q_hi = ngroups - 1;
+        if (q_hi > floor_g(len - T - k_in)) q_hi = floor_g(len - T - k_in);
+        if (q_hi > floor_g(out_len - G + a_off)) q_hi = floor_g(out_len - G + a_off);
         if (bit_limit < row_sh) {
             q_hi = q_lo - 1;
         } else {
             const int i_max = (bit_limit - row_sh) >> lc;           // largest i0 whose loads stay inside the buffer
-            if (q_hi > floor_quarter(i_max - k_in)) q_hi = floor_quarter(i_max - k_in);
+            if (q_hi > floor_g(i_max - k_in)) q_hi = floor_g(i_max - k_in);
         }
         const uint32_t q_span = q_hi >= q_lo ? (uint32_t)(q_hi - q_lo) : 0u;
         const bool none = q_hi < q_lo;
-        const int kb = row_sh + k_in * c;                           // window bit = (q << (2 + lc)) + kb
+        const int kb = row_sh + k_in * c;                           // window bit = (q << (LG + lc)) + kb
         int32_t *yrow = p.y + r * p.out_len;
-        char *ybytes = reinterpret_cast<char *>(yrow) - 4 * a_off;  // quad q is stored at ybytes + 16 q
+        char *ybytes = reinterpret_cast<char *>(yrow) - 4 * a_off;  // group q is stored at ybytes + 4 G q
 
-        // ---- per quad ----
-        const int q_first = (int)(blockIdx.x * (unsigned)(kStreamQuads * kStreamThreads) + threadIdx.x) - lead;
-        bool interior[kStreamQuads];
-        uint32_t w0[kStreamQuads], w1[kStreamQuads], w2[kStreamQuads], w3[kStreamQuads], shv[kStreamQuads];
+        // ---- per group ----
+        const int q_first = (int)(blockIdx.x * (unsigned)(STEPS * kStreamThreads) + threadIdx.x) - lead;
+        bool interior[STEPS];
+        uint32_t w0[STEPS], w1[STEPS], w2[STEPS], w3[STEPS], shv[STEPS];
         bool any_edge = false;
-        // all window loads of a lane's quads are issued before the first is used; they are
-        // unconditional (a quad that is not interior reads the buffer's first dwords and ignores them)
+        // all window loads of a lane's groups are issued before the first is used; they are
+        // unconditional (a group that is not interior reads the buffer's first dwords and ignores them)
 #pragma unroll
-        for (int s = 0; s < kStreamQuads; ++s) {
+        for (int s = 0; s < STEPS; ++s) {
             const int q = q_first + s * kStreamThreads;
             interior[s] = !none && (uint32_t)(q - q_lo) <= q_span;
-            any_edge |= !interior[s] && (uint32_t)q < (uint32_t)nquads;
-            const int bit = (int)((uint32_t)q << (2 + lc)) + kb;
+            any_edge |= !interior[s] && (uint32_t)q < (uint32_t)ngroups;
+            const int bit = (int)((uint32_t)q << (LG + lc)) + kb;
             shv[s] = (uint32_t)bit & 31u;
             const uint32_t off = interior[s] ? row_byte + (((uint32_t)bit >> 5) << 2) : 0u;
             if (WIDE) {
@@ -128,26 +144,64 @@ __device__ __forceinline__ void for_each_output_quad(const Conv1dArgs &p, int le
                 w0[s] = v.x, w1[s] = v.y, w2[s] = v.z, w3[s] = 0u;
             }
         }
+        // the loaded dwords are named here, after the last load has been issued and ahead of every
+        // branch: the compiler otherwise moves a load into the branch that uses it, where its
+        // round trip is waited for alone
 #pragma unroll
-        for (int s = 0; s < kStreamQuads; ++s) {
-            if (!interior[s]) continue;
-            int32_t out[4] = {0, 0, 0, 0};
-            const uint32_t sh = shv[s];
-            const uint64_t win = ((uint64_t)funnel_shr(w2[s], w1[s], sh) << 32) | funnel_shr(w1[s], w0[s], sh);
-            compute(win, WIDE ? funnel_shr(w3[s], w2[s], sh) : 0u, out);
-            const v4i v4 = {out[0], out[1], out[2], out[3]};
-            const uint32_t yoff = (uint32_t)(q_first + s * kStreamThreads) << 4; // interior: q >= 0, and 16 q < 2^32 (launcher)
-            __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(ybytes + yoff));
+        for (int s = 0; s < STEPS; ++s) {
+            asm volatile("" : "+v"(w0[s]), "+v"(w1[s]), "+v"(w2[s]));
+            if (WIDE) asm volatile("" : "+v"(w3[s]));
         }
-        // quads at the row's ends (and where a load would leave the buffer): the same window from
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            int32_t out[G];
+#pragma unroll
+            for (int u = 0; u < G; ++u) out[u] = 0;
+            if (interior[s]) {
+                const uint32_t sh = shv[s];
+                const uint64_t win = ((uint64_t)funnel_shr(w2[s], w1[s], sh) << 32) | funnel_shr(w1[s], w0[s], sh);
+                compute(win, WIDE ? funnel_shr(w3[s], w2[s], sh) : 0u, out);
+            }
+            // interior: q >= 0, and 4 G q < 2^32 (launcher)
+            const uint32_t yoff = (uint32_t)(q_first + s * kStreamThreads) << (LG + 2);
+            if (G == 4) {
+                if (!interior[s]) continue;
+                const v4i v4 = {out[0], out[1], out[2], out[3]};
+                __builtin_nontemporal_store(v4, reinterpret_cast<v4i *>(ybytes + yoff));
+            } else {
+                // A lane's eight outputs are 32 contiguous bytes, but a store instruction moves 16
+                // per lane, and the memory pipeline wants the 64 pieces of one instruction side by
+                // side.  So the wave's 2 KB pass through its own LDS region: lane l writes quads 2l
+                // and 2l+1, reads quads l and 64+l, and each of the two stores covers 1 KB of y.
+                // (A wave's LDS instructions execute in order; nothing else touches the region.)
+                const v4i lo = {out[0], out[1], out[2], out[3]}, hi = {out[G - 4], out[G - 3], out[G - 2], out[G - 1]};
+                if (__builtin_amdgcn_ballot_w64(interior[s]) == ~0ull) { // wave-uniform
+                    v4i *mine = s_turn + (threadIdx.x & ~63) * 2;
+                    const int lane = threadIdx.x & 63;
+                    __builtin_amdgcn_wave_barrier();
+                    mine[2 * lane] = lo;
+                    mine[2 * lane + 1] = hi;
+                    __builtin_amdgcn_wave_barrier();
+                    const v4i t0 = mine[lane], t1 = mine[64 + lane];
+                    __builtin_amdgcn_wave_barrier();
+                    char *wave_y = ybytes + (yoff - 32u * (uint32_t)lane); // lane 0's group
+                    __builtin_nontemporal_store(t0, reinterpret_cast<v4i *>(wave_y + 16 * lane));
+                    __builtin_nontemporal_store(t1, reinterpret_cast<v4i *>(wave_y + 1024 + 16 * lane));
+                } else if (interior[s]) {
+                    *reinterpret_cast<v4i *>(ybytes + yoff) = lo;
+                    *reinterpret_cast<v4i *>(ybytes + yoff + 16) = hi;
+                }
+            }
+        }
+        // groups at the row's ends (and where a load would leave the buffer): the same window from
         // checked loads, element by element, zero outside the row; the same arithmetic
         if (__builtin_amdgcn_ballot_w64(any_edge) != 0) {
 #pragma unroll 1
-            for (int s = 0; s < kStreamQuads; ++s) {
+            for (int s = 0; s < STEPS; ++s) {
                 const int q = q_first + s * kStreamThreads;
                 const bool inside = !none && (uint32_t)(q - q_lo) <= q_span;
-                if (inside || (uint32_t)q >= (uint32_t)nquads) continue;
-                const int o0 = 4 * q - a_off;
+                if (inside || (uint32_t)q >= (uint32_t)ngroups) continue;
+                const int o0 = G * q - a_off;
                 const int i0 = o0 + lead_in;
                 uint64_t win = 0;
                 uint32_t win_hi = 0;
@@ -162,9 +216,12 @@ __device__ __forceinline__ void for_each_output_quad(const Conv1dArgs &p, int le
                     else
                         win_hi |= (uint32_t)v << (t * c - 64);
                 }
-                int32_t out[4] = {0, 0, 0, 0};
+                int32_t out[G];
+#pragma unroll
+                for (int u = 0; u < G; ++u) out[u] = 0;
                 compute(win, win_hi, out);
-                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int u = 0; u < G; ++u)
                     if (o0 + u >= 0 && o0 + u < out_len) yrow[o0 + u] = out[u];
             }
         }
