@@ -75,7 +75,7 @@ extern "C" {
 #define HIKONV_KERNEL_SREG 2   /* layers: weight words in scalar registers wherever the plan allows it   */
 #define HIKONV_KERNEL_LANES 3  /* hikonv_conv1d: one lane = one packed block, high parts exchanged between */
                                /* neighbouring lanes, outputs staged per wave                             */
-#define HIKONV_KERNEL_WINDOW 4 /* hikonv_conv1d: one lane = one aligned quad of outputs, the blocks that  */
+#define HIKONV_KERNEL_WINDOW 4 /* hikonv_conv1d: one lane = an aligned group of 4 or 8 outputs, the blocks that */
                                /* cover it multiplied one after the other (AUTO takes it where it applies: */
                                /* at most 7 taps, K = min(taps, N), N in {2,3,4,5,6,8,11})                 */
 

@@ -1,4 +1,4 @@
-// Launcher of the quad-per-lane packed 1-D kernel (hikonv_conv1d_window.h); the kernels are
+// Launcher of the packed 1-D window kernel (hikonv_conv1d_window.h); the kernels are
 // instantiated per tap count in hikonv_conv1d_window_t*.hip.
 #include "hikonv_conv1d_window.h"
 

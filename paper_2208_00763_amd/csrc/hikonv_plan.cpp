@@ -187,9 +187,10 @@ struct Cand {
 // on MI355X at 4096 rows x 65536, 3, 5 and 7 taps (every integer instruction the kernels use
 // issues at 87-99 % of the full rate, so an instruction is priced as one slot).
 //
-//   quad-per-lane kernel, int32 outputs (taps <= 7, K = min(taps, N), N in {2,3,4,5,6,8,11}),
-//   per output: kWinBase + kWinTap*taps + kWinBlock*ceil((taps+3)/N)  [+ kWinSigned signed]
-//       (most of it index arithmetic and bounds tests per quad, not packed arithmetic)
+//   window kernel, int32 outputs (taps <= 7, K = min(taps, N), N in {2,3,4,5,6,8,11}); a lane
+//   makes G = 8 outputs from one window with containers of up to 4 bits, G = 4 with 8-bit ones;
+//   per output: base + tap*taps + block*ceil((taps+G-1)/N)  [+ signed], kWin8* / kWin4*
+//       (most of it index arithmetic, bounds tests and stores per group, not packed arithmetic)
 //   lane-per-block kernel, int32 outputs (the other stride_elems = 1 plans), per block of N outputs:
 //       kI32Block + kI32Elem*N  [+ N + 1 signed]  + per extra B word: kShareChunk when the
 //       delayed words come from the preceding lanes (K = N), else a second packing
@@ -209,9 +210,10 @@ struct Cand {
 constexpr double kI32Block = 15.0, kI32Elem = 11.7;
 constexpr double kRqBlock = 21.0, kRqElem = 13.9;
 constexpr double kShareChunk = 4.2;
-constexpr double kWinBase = 8.6, kWinTap = 0.6, kWinBlock = 0.6, kWinSigned = 1.5;
+constexpr double kWin8Base = 8.7, kWin8Tap = 0.58, kWin8Block = 0.31, kWin8Signed = 1.3;
+constexpr double kWin4Base = 8.3, kWin4Tap = 0.86, kWin4Block = 0.52, kWin4Signed = 1.5;
 
-// plans the quad-per-lane int32 kernel takes (the launcher's rule, without the geometry)
+// plans the window kernel (int32 outputs) takes (the launcher's rule, without the geometry)
 inline bool window_form(int taps, int n, int k)
 {
     if (taps < 1 || taps > 7 || k != (taps < n ? taps : n)) return false;
@@ -241,8 +243,11 @@ double conv1d_slots(const Req &r, int n, int k, int chunks, int s, int stride)
         const double mac = nibble ? 2.0 : 1.0;
         return (2.0 * words + j * (mac * r.taps + requant + 1.5) + kAlignedDword) / per;
     }
-    if (r.out_bits == 0 && window_form(r.taps, n, k) && n * container_of(r.p) <= 32)
-        return kWinBase + kWinTap * r.taps + kWinBlock * ((r.taps + 3 + n - 1) / n) + (r.any_signed ? kWinSigned : 0.0);
+    if (r.out_bits == 0 && window_form(r.taps, n, k) && n * container_of(r.p) <= 32) {
+        if (container_of(r.p) <= 4)
+            return kWin8Base + kWin8Tap * r.taps + kWin8Block * ((r.taps + 7 + n - 1) / n) + (r.any_signed ? kWin8Signed : 0.0);
+        return kWin4Base + kWin4Tap * r.taps + kWin4Block * ((r.taps + 3 + n - 1) / n) + (r.any_signed ? kWin4Signed : 0.0);
+    }
     const bool share = chunks >= 2 && chunks <= 4 && k == n && n >= 2 && n <= 5;
     double block = r.out_bits > 0 ? kRqBlock + kRqElem * n : kI32Block + kI32Elem * n;
     if (r.any_signed) block += n + 1;
