@@ -80,6 +80,30 @@ __device__ __forceinline__ uint32_t pack_act_word(const PackActArgs &p, int ch, 
     const int csrc = c_packed / p.phases, phase = c_packed - csrc * p.phases;
     const uint8_t *rowp =
         static_cast<const uint8_t *>(p.x) + (((n_img * p.Csrc + csrc) * p.D + d) * p.H + h) * p.row_bytes;
+    if (FMT == HIKONV_FMT_BITDENSE && NV > 0 && p.phases == 1 && NV * p.c <= 32) {
+        // The word's N containers are consecutive bits of the row: one 32-bit window cut out of
+        // two dwords that are loaded unconditionally (a load inside a branch is waited for
+        // alone).  Dword indices are clamped into the row (bit-dense rows are whole dwords); a
+        // clamped dword only supplies containers of elements outside the row, which are skipped.
+        const int lo = e0 < 0 ? -e0 : 0;                     // elements lo .. hi-1 of the word exist
+        const int hi = p.W - e0 < NV ? p.W - e0 : NV;
+        const int bit0 = e0 * p.c;                           // may be negative: floor division below
+        const int last = (int)(p.row_bytes >> 2) - 1;
+        const int dw = bit0 >> 5;
+        const int d0 = dw < 0 ? 0 : (dw > last ? last : dw), d1 = dw + 1 < 0 ? 0 : (dw + 1 > last ? last : dw + 1);
+        const uint32_t *rw = reinterpret_cast<const uint32_t *>(rowp);
+        const uint32_t raw = funnel_shr(rw[d1], rw[d0], (uint32_t)bit0 & 31u);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            int32_t v;
+            if (p.bipolar)
+                v = ((raw >> (j * p.c)) & 1u) ? 1 : -1;
+            else
+                v = p.a_signed ? __builtin_amdgcn_sbfe((int)raw, j * p.c, p.b) : (int)__builtin_amdgcn_ubfe(raw, j * p.c, p.b);
+            if (j >= lo && j < hi) a += (uint32_t)v << (p.S * j);
+        }
+        return a;
+    }
 #pragma unroll
     for (int j = 0; j < pN; ++j) {
         const int i = e0 + j; // element of the packed row
