@@ -62,7 +62,8 @@ def test_conv2d_long_rows_are_segmented(wide):
         x, w = _case(bits, a_s, w_s, shape, "d2")
         try:
             plan = dnn_plan(bits, bits, a_s, w_s, 3, 3, wide)
-        except hk.HikonvError:
+        except hk.HikonvError as e:
+            assert e.code == hk.ENOPLAN    # no plan exists for this request; nothing is skipped silently
             continue
         assert (width + 1 + plan.N - 1) // plan.N > 63
         assert np.array_equal(run_conv2d(plan, x, w, 1, 1), direct.conv2d(x, w, 1, 1))
@@ -246,7 +247,8 @@ def test_epilogue_pack_feeds_the_next_layer(pool, wide):
         ref = direct.conv2d(q.view(np.uint8), wt, 1, pad)
         try:
             plan = dnn_plan(4, 4, False, True, kw, 0, wide, tight=tight)
-        except hk.HikonvError:
+        except hk.HikonvError as e:
+            assert e.code == hk.ENOPLAN    # no plan exists for this request; nothing is skipped silently
             continue
         ws = torch.empty(hk.hikonv_conv2d_workspace_bytes(plan, n, c, hn, wn, co, kh, kw, 1, pad, True),
                          dtype=torch.uint8, device="cuda")

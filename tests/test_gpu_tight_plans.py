@@ -64,7 +64,8 @@ def test_conv2d_tight_plans_random_and_extreme(wide):
                            (8, True, True)):
         try:
             plan = dnn_plan(bits, bits, a_s, w_s, 3, 0, wide, tight=1)
-        except hk.HikonvError:
+        except hk.HikonvError as e:
+            assert e.code == hk.ENOPLAN    # no plan exists for this request; nothing is skipped silently
             continue
         c = min(max(plan.M // 3 + 2, 8), 160)      # at least one full split group of (channel, row) terms
         x, w = wl.conv2d_case(bits, a_s, w_s, 1, c, 9, 21, 10, 3, 3, tag="tight2")
