@@ -205,9 +205,12 @@ def conv2d_extra(hk, wl, name, steps):
     y = torch.empty(n * co * h * wd, dtype=torch.int32, device="cuda")
     macs = n * co * h * wd * c * kh * kw
     report = {"macs": macs, "input": "bit-dense %d-bit containers (packed kernels), one value per byte (baseline)" % bits}
-    for label, width, acc, tight in (("wide32", 32, 64, 0), ("wide32_tight", 32, 64, 1), ("narrow24", 24, 32, 0)):
+    # wide32: Algorithm 1's plan; wide32_tight: the planner's cost objective (exact-interval slices, more
+    # products per split); narrow24: the 24-bit multiplier
+    for label, width, acc, objective in (("wide32", 32, 64, hk.OBJ_PAPER_OPS), ("wide32_tight", 32, 64, hk.OBJ_MEASURED_COST),
+                                         ("narrow24", 24, 32, hk.OBJ_PAPER_OPS)):
         try:
-            plan = hk.hikonv_plan_ex(L_A=width, L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=0, taps=kw, tight=tight,
+            plan = hk.hikonv_plan_ex(L_A=width, L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=0, taps=kw, objective=objective,
                                      max_N=hk.LAYER_MAX_N, **plan_kw)
         except hk.HikonvError:
             continue
@@ -360,7 +363,7 @@ def small_extras(hk, wl, steps):
     # one kernel per layer: the convolution's store stage requantises, pools and packs for the next layer
     # (10 kernels: input packing + 9 layers; intermediate accumulators never reach memory)
     lean = PackedCnn([torch.from_numpy(w.view("uint8")).cuda() for w in weights], specs, fused="layer", keep_accs=False,
-                     tight=1)
+                     objective=hk.OBJ_MEASURED_COST)
     fwd_lean = lambda: lean.forward(x5, 1, 160, 320, shifts)
     event_ms(fwd_lean, 3)
     out["cnn_c5_layer_kernels_eager_us"] = event_ms(fwd_lean, steps) * 1e3

@@ -64,7 +64,8 @@ extern "C" {
 /* What the planner optimises (hikonv_plan_t.objective). */
 #define HIKONV_OBJ_PAPER_OPS 0     /* Algorithm 1: most low-bit operations per multiply, Eq. (tot_ops); with a  */
                                    /* fixed tap count: most multiply-accumulates per multiply                    */
-#define HIKONV_OBJ_MEASURED_COST 1 /* fewest modelled VALU issue slots per output on gfx950: every candidate   */
+#define HIKONV_OBJ_MEASURED_COST 1 /* fewest modelled VALU issue slots per output (layers: per multiply-       */
+                                   /* accumulate) on gfx950: every candidate                                    */
                                    /* (N, K, S) is priced with per-instruction counts for packing, multiplying, */
                                    /* exchanging, splitting and storing calibrated on MI355X counters, bounded  */
                                    /* below by the slots that fit under the HBM time of its bytes               */
@@ -160,9 +161,15 @@ int hikonv_plan_ex(const hikonv_plan_t *request, hikonv_plan_t *out);
  * for a GPU lane that also has to pack and split).  Besides the (N, K, S) of
  * Eq. (slice1)-(slice3) it considers container-aligned slices (stride_elems > 1)
  * when out_bits names an output container as wide as the input's.
+ * In mode DNN with fixed taps the same objective prices a layer plan by the
+ * multiply-accumulates it does per issue slot, splits and extra B words included
+ * (Section "DNN Convolution Extension": M products accumulate before a split), and
+ * searches the exact-interval slices as `tight` does: a narrower slice lets more
+ * products accumulate, and on this chip the splits are what a layer pays for.
  * hikonv_plan_cost -- the model's price of a fully specified plan (request and
- * result fields set; out_bits selects the output form): VALU issue slots per
- * output element x 1000, or a negative HIKONV_E* code.  Host only.
+ * result fields set; out_bits selects the output form): VALU issue slots x 1000
+ * per output element (CONV1D) or per low-bit multiply-accumulate (DNN), or a
+ * negative HIKONV_E* code.  Host only.
  */
 int hikonv_plan_cost(const hikonv_plan_t *plan);
 

@@ -13,20 +13,21 @@ class PackedCnn:
     """Pre-packs the weights of a list of conv layers once; forward() runs the chain."""
 
     def __init__(self, weights, specs, act_bits=4, w_bits=4, w_signed=True, wide=True, m=0, tight=0, fused=True,
-                 keep_accs=True):
+                 keep_accs=True, objective=hk.OBJ_PAPER_OPS):
         """fused: "layer" = one kernel per layer (hikonv_conv2d_fused: the convolution's store stage
         writes the next layer's packed activation words; layers it does not cover fall back to the
         next form); True = a convolution kernel and an epilogue kernel that writes the next
         layer's packed words (hikonv_epilogue_pack); False = the epilogue writes bit-dense rows
         that the next layer packs.  keep_accs (fused == "layer" only): also store every layer's
-        int32 accumulators (the last layer's are always stored)."""
+        int32 accumulators (the last layer's are always stored).  objective: what the planner
+        optimises for every layer (Algorithm 1's operations per multiply, or the modelled cost)."""
         self.layers = []
         width, acc = (32, 64) if wide else (24, 32)
         for w_dev, spec in zip(weights, specs):
             co, c, kh, kw = w_dev.shape
             plan = hk.hikonv_plan_ex(bits_a=act_bits, bits_w=w_bits, a_signed=0, w_signed=int(w_signed), L_A=width,
                                      L_B=width, L_acc=acc, mode=hk.MODE_DNN, M=m, taps=kw, tight=tight,
-                                     max_N=hk.LAYER_MAX_N)
+                                     objective=objective, max_N=hk.LAYER_MAX_N)
             packed = torch.empty(hk.hikonv_packed_weights_bytes(plan, co, c, kh, kw), dtype=torch.uint8,
                                  device=w_dev.device)
             hk.hikonv_pack_weights(plan, w_dev, co, c, kh, kw, packed)

@@ -93,8 +93,11 @@ Req make_req(const hikonv_plan_t &in)
     r.mode = in.mode;
     r.M = in.mode == HIKONV_MODE_DNN ? (in.M > 0 ? in.M : 1) : 1;
     r.taps = in.taps;
-    r.tight = in.tight != 0;
     r.objective = in.objective;
+    // the cost objective of a layer plan searches the exact-interval slices as well: a narrower slice
+    // lets more products accumulate before a split, which is what a layer pays for on this chip
+    r.tight = in.tight != 0 ||
+              (in.objective == HIKONV_OBJ_MEASURED_COST && in.mode == HIKONV_MODE_DNN && in.taps > 0);
     r.out_bits = in.out_bits;
     r.max_N = in.max_N;
     r.fa = r.bipolar ? Range{-1, 1} : value_range(r.p, r.a_signed);
@@ -295,6 +298,23 @@ inline double priced(const Req &r, double slots)
     return slots < floor ? floor : slots;
 }
 
+// Issue-slot model of the layer kernels (DNN mode).  Measured on gfx950: v_mad_u64_u32 and
+// v_mad_u32_u24 both issue at (nearly) the full VALU rate, the layer kernel spends about 1.4 issue
+// slots per multiply-accumulate (address and LDS traffic included), and a split costs an
+// exchange (64-bit shift, DPP moves, 64-bit add) plus three instructions per field; the narrow
+// path needs half the exchange.  Used to choose M when the caller leaves it open and, under the
+// measured-cost objective, to choose among the candidates of a layer plan.
+double modelled_macs_per_slot(const Req &r, const Cand &c)
+{
+    const bool wide = r.L_acc > 32;
+    const double c_mul = 1.4;
+    const double c_split = (wide ? 8.0 : 5.0) + 3.0 * c.n;
+    const double macs = (double)r.M * c.n * r.taps;
+    return macs / (r.M * c.chunks * c_mul + c_split);
+}
+
+inline bool by_cost_dnn(const Req &r) { return r.objective == HIKONV_OBJ_MEASURED_COST && r.mode == HIKONV_MODE_DNN && r.taps > 0; }
+
 // score comparison: free mode -> Eq. tot_ops; fixed taps -> MACs per multiply n*taps/chunks
 inline bool by_cost(const Req &r) { return r.objective == HIKONV_OBJ_MEASURED_COST && r.mode == HIKONV_MODE_CONV1D && r.taps > 0; }
 
@@ -309,6 +329,11 @@ inline bool better(const Req &r, const Cand &c, const Cand &best)
         if ((long long)c.n * best.chunks != (long long)best.n * c.chunks)
             return (long long)c.n * best.chunks > (long long)best.n * c.chunks;
         return c.cost < best.cost;
+    }
+    if (by_cost_dnn(r)) {
+        // layers: most multiply-accumulates per modelled issue slot (splits and extra B words priced in)
+        const double sc = modelled_macs_per_slot(r, c), sb = modelled_macs_per_slot(r, best);
+        if (sc != sb) return sc > sb;
     }
     if (r.taps == 0)
         return (long long)c.n * c.k + (long long)(c.n - 1) * (c.k - 1) >
@@ -347,6 +372,7 @@ Cand search(const Req &r_in, bool paper_only)
             if (c.s < s0) c.gb -= s0 - c.s;
         }
         if (r.mode == HIKONV_MODE_CONV1D && r.taps > 0) c.cost = conv1d_slots(r, c.n, c.k, c.chunks, c.s, 1);
+        if (r.mode == HIKONV_MODE_DNN && r.taps > 0) c.cost = 1.0 / modelled_macs_per_slot(r, c); // slots per multiply-accumulate
         c.found = true;
         if (better(r, c, best)) best = c;
     };
@@ -400,20 +426,6 @@ void fill_result(hikonv_plan_t *out, const Req &r, const Cand &c, bool paper_exa
     out->paper_exact = paper_exact ? 1 : 0;
     out->stride_elems = c.stride;
     out->cost_milli = (int32_t)(c.cost * 1000.0 + 0.5);
-}
-
-// Issue-slot model used only to choose M when the caller leaves it open.  Measured on
-// gfx950: v_mad_u64_u32 and v_mad_u32_u24 both issue at the full VALU rate, the layer
-// kernel spends about 1.4 issue slots per multiply-accumulate (address and LDS traffic
-// included), and a split costs an exchange (64-bit shift, two half-rate DPP moves, 64-bit
-// add) plus three instructions per field; the narrow path needs half the exchange.
-double modelled_macs_per_slot(const Req &r, const Cand &c)
-{
-    const bool wide = r.L_acc > 32;
-    const double c_mul = 1.4;
-    const double c_split = (wide ? 8.0 : 5.0) + 3.0 * c.n;
-    const double macs = (double)r.M * c.n * r.taps;
-    return macs / (r.M * c.chunks * c_mul + c_split);
 }
 
 } // namespace
@@ -496,8 +508,15 @@ extern "C" int hikonv_plan_cost(const hikonv_plan_t *plan)
 {
     int rc = hikonv_plan_check(plan);
     if (rc != HIKONV_OK) return rc;
-    if (plan->mode != HIKONV_MODE_CONV1D || plan->taps < 1) return HIKONV_EUNSUPPORTED;
+    if (plan->taps < 1 || plan->mode == HIKONV_MODE_SINGLE) return HIKONV_EUNSUPPORTED;
     Req r = make_req(*plan);
+    if (plan->mode == HIKONV_MODE_DNN) {
+        Cand c;
+        c.n = plan->N;
+        c.k = plan->K;
+        c.chunks = plan->chunks;
+        return (int)(1000.0 / modelled_macs_per_slot(r, c) + 0.5);
+    }
     const double slots = conv1d_slots(r, plan->N, plan->K, plan->chunks, plan->S, plan->stride_elems > 1 ? plan->stride_elems : 1);
     return (int)(slots * 1000.0 + 0.5);
 }

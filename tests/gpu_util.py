@@ -91,12 +91,13 @@ def oracle_conv1d(x_np, g_np, mode):
 LAYER_DEFAULTS = {"kernel": 0, "flags": 0}
 
 
-def dnn_plan(bits_a, bits_w, a_signed, w_signed, taps, m, wide=True, bipolar=False, tight=0, max_n=None):
+def dnn_plan(bits_a, bits_w, a_signed, w_signed, taps, m, wide=True, bipolar=False, tight=0, max_n=None,
+             objective=hk.OBJ_PAPER_OPS):
     """A layer plan the layer kernels can run (N <= LAYER_MAX_N unless max_n says otherwise)."""
     width = 32 if wide else 24
     return hk.hikonv_plan_ex(bits_a=bits_a, bits_w=bits_w, a_signed=int(a_signed), w_signed=int(w_signed),
                              bipolar=int(bipolar), L_A=width, L_B=width, L_acc=64 if wide else 32,
-                             mode=hk.MODE_DNN, M=m, taps=taps, tight=tight,
+                             mode=hk.MODE_DNN, M=m, taps=taps, tight=tight, objective=objective,
                              max_N=hk.LAYER_MAX_N if max_n is None else max_n,
                              kernel=LAYER_DEFAULTS["kernel"], flags=LAYER_DEFAULTS["flags"])
 

@@ -291,14 +291,14 @@ def test_cnn_forward_config5(size, fused):
     if fused == "layer":
         assert all(net.layer_kernel), "every layer of this network fits the one-kernel-per-layer form"
         # the chain as the benchmark runs it: intermediate accumulators never stored
-        # (exact-interval plans, as there, and the paper's slices)
-        for tight in (1, 0):
+        # (the planner's cost objective, as there, and Algorithm 1's plans)
+        for objective in (hk.OBJ_MEASURED_COST, hk.OBJ_PAPER_OPS):
             lean = PackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs, fused="layer",
-                             keep_accs=False, tight=tight)
+                             keep_accs=False, objective=objective)
             last, _ = lean.forward(x_bd, 1, h, w, shifts)
             torch.cuda.synchronize()
             assert all(lean.layer_kernel)
-            assert np.array_equal(last.cpu().numpy().reshape(ref_accs[-1].shape), ref_accs[-1]), tight
+            assert np.array_equal(last.cpu().numpy().reshape(ref_accs[-1].shape), ref_accs[-1]), objective
     if fused is True:
         # the baseline chain (one multiply per product) that the benchmark times beside it
         base = UnpackedCnn([dev(wt).view(torch.uint8).reshape(wt.shape) for wt in weights], specs)

@@ -58,12 +58,15 @@ def test_conv1d_tight_signed_4bit_plan_and_full_size_rows():
     assert np.array_equal(got, direct.conv1d(x[sample], g, direct.VALID))
 
 
+@pytest.mark.parametrize("how", ["tight", "cost_objective"])
 @pytest.mark.parametrize("wide", [True, False])
-def test_conv2d_tight_plans_random_and_extreme(wide):
+def test_conv2d_tight_plans_random_and_extreme(wide, how):
+    # the exact-interval slices, asked for directly and as the planner's cost objective finds them
+    request = dict(tight=1) if how == "tight" else dict(objective=hk.OBJ_MEASURED_COST)
     for bits, a_s, w_s in ((4, True, True), (4, False, True), (4, False, False), (2, True, True), (3, False, True),
                            (8, True, True)):
         try:
-            plan = dnn_plan(bits, bits, a_s, w_s, 3, 0, wide, tight=1)
+            plan = dnn_plan(bits, bits, a_s, w_s, 3, 0, wide, **request)
         except hk.HikonvError as e:
             assert e.code == hk.ENOPLAN    # no plan exists for this request; nothing is skipped silently
             continue

@@ -194,3 +194,43 @@ def test_request_fields_are_validated_and_copied_through():
             hk.hikonv_plan_ex(bits_a=4, bits_w=4, L_A=32, L_B=32, L_acc=64, mode=hk.MODE_CONV1D, taps=3, **bad)
         assert e.value.code == hk.EINVAL
     assert hk.hikonv_plan_cost(hk.hikonv_plan(4, 4, 0, 32)) == hk.EUNSUPPORTED      # single-multiplier plan: no kernel to price
+
+
+# Layer plans (mode DNN).  Measured on one MI355X, layer 8x256x28x28 -> 256, 3x3, int4 signed, packed
+# input: Algorithm 1's plan (N=3, K=3, S=13, M=10) 54 us, the exact-interval plan (M=21) 40 us.
+MEASURED_INT4_LAYER_US = (40.0, 54.0)
+
+
+def layer_request(objective, tight=0, **kw):
+    base = dict(L_A=32, L_B=32, L_acc=64, mode=hk.MODE_DNN, M=0, taps=3, objective=objective, tight=tight,
+                max_N=hk.LAYER_MAX_N)
+    base.update(kw)
+    return hk.hikonv_plan_ex(**base)
+
+
+def test_layer_cost_objective_finds_the_exact_interval_plans():
+    """In DNN mode the cost objective prices splits and extra B words; what it returns is the plan
+    that `tight` asks for by hand (more products per split, or more slices per word), never a costlier
+    one than Algorithm 1's."""
+    cases = (dict(bits_a=4, bits_w=4, a_signed=1, w_signed=1), dict(bits_a=4, bits_w=4, w_signed=1),
+             dict(bits_a=8, bits_w=8, a_signed=1, w_signed=1), dict(bits_a=2, bits_w=2), dict(bits_a=1, bits_w=1),
+             dict(bits_a=1, bits_w=1, bipolar=1), dict(bits_a=3, bits_w=5, w_signed=1))
+    for kw in cases:
+        paper = layer_request(hk.OBJ_PAPER_OPS, **kw)
+        tight = layer_request(hk.OBJ_PAPER_OPS, tight=1, **kw)
+        cost = layer_request(hk.OBJ_MEASURED_COST, **kw)
+        assert (cost.N, cost.K, cost.S, cost.M, cost.chunks) == (tight.N, tight.K, tight.S, tight.M, tight.chunks), kw
+        assert hk.hikonv_plan_check(cost) == hk.OK
+        assert cost.cost_milli == hk.hikonv_plan_cost(cost) <= hk.hikonv_plan_cost(paper), kw
+        if (cost.N, cost.S, cost.M) != (paper.N, paper.S, paper.M):
+            assert cost.paper_exact == 0
+
+
+def test_layer_cost_ranking_reproduces_the_measured_ranking():
+    kw = dict(bits_a=4, bits_w=4, a_signed=1, w_signed=1)
+    paper, cost = layer_request(hk.OBJ_PAPER_OPS, **kw), layer_request(hk.OBJ_MEASURED_COST, **kw)
+    assert (paper.M, cost.M) == (10, 21)
+    model = hk.hikonv_plan_cost(paper) / hk.hikonv_plan_cost(cost)
+    clock = MEASURED_INT4_LAYER_US[1] / MEASURED_INT4_LAYER_US[0]
+    assert model > 1.0 and clock > 1.0
+    assert 1 / 1.3 < model / clock < 1.3
