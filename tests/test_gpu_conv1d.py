@@ -189,6 +189,24 @@ def test_conv1d_every_store_phase(bits, signed, taps):
     assert seen == set(range(32))
 
 
+@pytest.mark.parametrize("bits,signed", [(1, False), (2, True), (4, False), (4, True), (8, False)])
+def test_conv1d_every_length_around_group_boundaries(bits, signed):
+    """Rows so short that a lane's group of eight (four) outputs is never complete, rows that end
+    anywhere inside a group or a 128-byte line, several rows so that the groups start at every
+    offset: packed and unpacked kernels, both output modes."""
+    lengths = list(range(1, 41)) + [47, 48, 49, 63, 64, 65, 71, 72, 73, 127, 128, 129, 255, 256, 257, 511, 513]
+    for taps in (1, 3, 7):
+        g = wl.uniform_values(wl.rng_for("lb-g", bits, signed, taps), (taps,), bits, signed)
+        for length in lengths:
+            x = wl.uniform_values(wl.rng_for("lb", bits, signed, taps, length), (4, length), bits, signed)
+            for mode in (hk.OUT_FULL, hk.OUT_VALID):
+                ref = oracle_conv1d(x, g, mode)
+                got = run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_BITDENSE, y_offset=4 * (length % 8))
+                assert np.array_equal(got, ref), (bits, signed, taps, length, mode)
+                got = run_conv1d(x, g, bits, signed, signed, mode, hk.FMT_BITDENSE, packed=False)
+                assert np.array_equal(got, ref), ("unpacked", bits, signed, taps, length, mode)
+
+
 def test_conv1d_many_short_rows_and_one_long_row():
     # more rows than a grid dimension holds; rows shorter than one packed run; one very long row
     for bits, signed, taps in ((4, False, 3), (1, True, 7), (8, True, 3)):
