@@ -174,7 +174,22 @@ def requant_extra(hk, wl, steps):
         ms_plan, _ = timed_pair(run_with(plan_paper), unpacked, steps, rounds=1)
         plan = plan_cost
         algo = ROWS * (row_bytes + hk.hikonv_bitdense_row_bytes(LENGTH, bits)) + TAPS
-        report["%d%s" % (bits, "s" if signed else "u")] = dict(
+        key = "%d%s" % (bits, "s" if signed else "u")
+        # this path is bound by integer VALU issue: instructions of the launch (the profiled count per
+        # output x the outputs) over the time measured here, against the chip's lane-instruction peak
+        prof = (read_profile_json("conv1d_requant_valu.json") or {}).get("cases", {}).get(key)
+        roof = None
+        if prof:
+            lane_instr = prof["valu_lane_instructions_per_output"] * ROWS * out_len
+            achieved = lane_instr / (ms_p * 1e-3) / 1e12
+            roof = {"bound": "alu", "achieved": achieved, "peak": VALU_LANE_RATE / 1e12, "unit": "T lane-instr/s",
+                    "frac": achieved / (VALU_LANE_RATE / 1e12), "kernel": prof["kernel"],
+                    "valu_lane_instructions_per_output": prof["valu_lane_instructions_per_output"],
+                    "valu_utilisation_profiled": prof["valu_utilisation"],
+                    "source": "profiles/conv1d_requant_valu.json (SQ_INSTS_VALU of a rocprofv3 run of this kernel; the time is "
+                              "this run's)"}
+        report[key] = dict(
+            roofline=roof,
             ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=algo / ms_p / 1e6, unpacked_ms=ms_u,
             vs_unpacked=ms_u / ms_p, frac_of_unpacked_valu_peak=case["macs"] / (ms_p * 1e-3) / VALU_LANE_RATE,
             plan=dict(N=plan.N, K=plan.K, S=plan.S, stride_elems=plan.stride_elems, cost_milli=plan.cost_milli),
@@ -588,6 +603,14 @@ def main():
     extras = {}
     if not args.no_extras:
         extras["conv1d_requant_bitdense_out"] = requant_extra(hk, wl, reps)
+        rq4 = extras["conv1d_requant_bitdense_out"].get("4u", {})
+        if rq4.get("roofline"):
+            # the VALU-bound half of the 1-D path at the top level of the line
+            line["roofline_alu_requant"] = dict(rq4["roofline"], workload="the headline case with requantised 4-bit bit-dense "
+                                                "output (cost-objective plan N=%d, K=%d, S=%d)" % (
+                                                    rq4["plan"]["N"], rq4["plan"]["K"], rq4["plan"]["S"]),
+                                                ms=rq4["ms"], gops=rq4["gops"], unpacked_ms=rq4["unpacked_ms"],
+                                                vs_unpacked=rq4["vs_unpacked"])
         extras["conv2d_c3"] = conv2d_extra(hk, wl, "c3", max(5, args.steps // 2))
         extras["conv2d_c4"] = c4
         extras["widened_layers"] = widened_extras(hk, max(5, args.steps // 2))
