@@ -151,46 +151,55 @@ __global__ __launch_bounds__(1024) void k_conv2d_fused(FusedLayerArgs f)
                 d_quad = row_ok ? cq * 4 : in.C;           // first channel of the quad; in.C: no channel of it exists
             }
             const int rows_w = (rows_a - first + nwaves - 1) / nwaves < 64 ? (rows_a - first + nwaves - 1) / nwaves : 64;
-            for (int e = lane; e < ((4 * p.Xs + 63) & ~63); e += 64) { // every lane takes part; e >= 4*Xs stores nothing
-                const int u = e & 3, xw = e >> 2;
-                const bool word_ok = e < 4 * p.Xs && xw > 0;
-                const int lane_bits = u * plane_bits + (xw - 1) * N * cbits;
-                for (int b0 = 0; b0 < rows_w; b0 += kPackBatch) {
-                    uint32_t w0[kPackBatch], w1[kPackBatch], shb[kPackBatch];
-                    int lo[kPackBatch], hi[kPackBatch];
+            // Work items of the wave: (row b of its rows_w rows, pass ei over the row's 4*Xs words, 64 words a
+            // pass), rows fastest; kPackBatch items are loaded together whether they are rows of one pass or
+            // passes over one row (a layer with few channels has a single row per wave and many passes).
+            const int passes = (4 * p.Xs + 63) >> 6;
+            const int items = rows_w * passes;
+            for (int i0 = 0; i0 < items; i0 += kPackBatch) {
+                uint32_t w0[kPackBatch], w1[kPackBatch], shb[kPackBatch];
+                int lo[kPackBatch], hi[kPackBatch];
 #pragma unroll
-                    for (int b = 0; b < kPackBatch; ++b) {
-                        const int bb = b0 + b < rows_w ? b0 + b : b0; // past the end: the batch's first row again, not stored
-                        const int r_dw = __builtin_amdgcn_readlane(d_dw, bb), r_sh = __builtin_amdgcn_readlane(d_sh, bb);
-                        const int r_delay = __builtin_amdgcn_readlane(d_delay, bb), r_quad = __builtin_amdgcn_readlane(d_quad, bb);
-                        const int e0 = (xw - 1) * N - r_delay;             // first element of the word
-                        const bool ok = word_ok && r_quad + u < in.C;
-                        lo[b] = e0 < 0 ? -e0 : 0;
-                        hi[b] = ok ? (in.W - e0 < N ? in.W - e0 : N) : 0;
-                        const int bit = r_sh + (ok ? lane_bits - r_delay * cbits : 0); // from the row's first dword; may be negative
-                        const int d = r_dw + (bit >> 5);                   // floor shift
-                        const int d0 = d < 0 ? 0 : (d > last ? last : d), d1 = d + 1 < 0 ? 0 : (d + 1 > last ? last : d + 1);
-                        w0[b] = xd[d0];
-                        w1[b] = xd[d1];
-                        shb[b] = (uint32_t)bit & 31u;
+                for (int b = 0; b < kPackBatch; ++b) {
+                    const int item = i0 + b < items ? i0 + b : i0; // past the end: the batch's first item again, not stored
+                    const int ei = (int)((uint32_t)item / (uint32_t)rows_w), bb = item - ei * rows_w; // wave-uniform
+                    const int e = lane + 64 * ei;                       // every lane takes part; e >= 4*Xs stores nothing
+                    const int u = e & 3, xw = e >> 2;
+                    const bool word_ok = e < 4 * p.Xs && xw > 0;
+                    const int lane_bits = u * plane_bits + (xw - 1) * N * cbits;
+                    const int r_dw = __builtin_amdgcn_readlane(d_dw, bb), r_sh = __builtin_amdgcn_readlane(d_sh, bb);
+                    const int r_delay = __builtin_amdgcn_readlane(d_delay, bb), r_quad = __builtin_amdgcn_readlane(d_quad, bb);
+                    const int e0 = (xw - 1) * N - r_delay;             // first element of the word
+                    const bool ok = word_ok && r_quad + u < in.C;
+                    lo[b] = e0 < 0 ? -e0 : 0;
+                    hi[b] = ok ? (in.W - e0 < N ? in.W - e0 : N) : 0;
+                    const int bit = r_sh + (ok ? lane_bits - r_delay * cbits : 0); // from the row's first dword; may be negative
+                    const int d = r_dw + (bit >> 5);                   // floor shift
+                    const int d0 = d < 0 ? 0 : (d > last ? last : d), d1 = d + 1 < 0 ? 0 : (d + 1 > last ? last : d + 1);
+                    w0[b] = xd[d0];
+                    w1[b] = xd[d1];
+                    shb[b] = (uint32_t)bit & 31u;
+                }
+#pragma unroll
+                for (int b = 0; b < kPackBatch; ++b) {
+                    if (i0 + b >= items) break; // wave-uniform
+                    const int item = i0 + b;
+                    const int ei = (int)((uint32_t)item / (uint32_t)rows_w), bb = item - ei * rows_w;
+                    const int e = lane + 64 * ei;
+                    const int u = e & 3, xw = e >> 2;
+                    const uint32_t raw = funnel_shr(w1[b], w0[b], shb[b]);
+                    uint32_t a = 0;
+#pragma unroll
+                    for (int j = 0; j < N; ++j) {
+                        int32_t val;
+                        if (in.bipolar)
+                            val = cbits == 8 ? ((int8_t)(raw >> (8 * j)) > 0 ? 1 : -1) : (((raw >> (j * cbits)) & 1u) ? 1 : -1);
+                        else
+                            val = in.a_signed ? __builtin_amdgcn_sbfe((int)raw, j * cbits, vb)
+                                              : (int32_t)__builtin_amdgcn_ubfe(raw, j * cbits, vb);
+                        if (j >= lo[b] && j < hi[b]) a += (uint32_t)val << (p.S * j);
                     }
-#pragma unroll
-                    for (int b = 0; b < kPackBatch; ++b) {
-                        if (b0 + b >= rows_w) break; // wave-uniform
-                        const uint32_t raw = funnel_shr(w1[b], w0[b], shb[b]);
-                        uint32_t a = 0;
-#pragma unroll
-                        for (int j = 0; j < N; ++j) {
-                            int32_t val;
-                            if (in.bipolar)
-                                val = cbits == 8 ? ((int8_t)(raw >> (8 * j)) > 0 ? 1 : -1) : (((raw >> (j * cbits)) & 1u) ? 1 : -1);
-                            else
-                                val = in.a_signed ? __builtin_amdgcn_sbfe((int)raw, j * cbits, vb)
-                                                  : (int32_t)__builtin_amdgcn_ubfe(raw, j * cbits, vb);
-                            if (j >= lo[b] && j < hi[b]) a += (uint32_t)val << (p.S * j);
-                        }
-                        if (e < 4 * p.Xs) s_a[((size_t)(first + (b0 + b) * nwaves) * p.Xs + xw) * 4 + u] = a;
-                    }
+                    if (e < 4 * p.Xs) s_a[((size_t)(first + bb * nwaves) * p.Xs + xw) * 4 + u] = a;
                 }
             }
         }
