@@ -157,3 +157,29 @@ def run_conv3d(plan, x_np, w_np, stride, pad, fmt=hk.FMT_INT8, prepacked=False):
     res = out.result()
     wsg.check()
     return res.reshape(n, co, do, ho, wo)
+
+
+def oracle_cnn(x, weights, specs, shifts=None):
+    """Layer-by-layer oracle forward; the per-layer requantisation shift is chosen here so that
+    the 99th percentile of the positive accumulators maps to at most 15 (or taken from `shifts`)."""
+    given = shifts
+    accs, shifts = [], []
+    cur = x
+    for i, (w, spec) in enumerate(zip(weights, specs)):
+        acc = direct.conv2d(cur, w, 1, spec["pad"])
+        accs.append(acc)
+        if i + 1 == len(weights):
+            break
+        pos = acc[acc > 0]
+        p99 = int(np.percentile(pos, 99)) if pos.size else 0
+        shift = 0
+        while (p99 >> shift) > 15:
+            shift += 1
+        if given is not None:
+            shift = given[i]
+        shifts.append(shift)
+        q = direct.relu_requant(acc, shift, 15)
+        if spec["pool"]:
+            q = direct.maxpool2x2(q)
+        cur = q.view(np.uint8)
+    return accs, shifts

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 if torch.cuda.is_available():
     import paper_2208_00763_amd as hk
     from paper_2208_00763_amd.cnn import PackedCnn, UnpackedCnn
-    from gpu_util import run_conv2d, dnn_plan, dev, compact, Guarded
+    from gpu_util import run_conv2d, dnn_plan, dev, compact, Guarded, oracle_cnn
 
 SHAPES = [  # n, c, h, w, co, kh, kw, stride, pad
     (1, 3, 5, 7, 2, 3, 3, 1, 1),
@@ -202,29 +202,6 @@ def test_epilogue_matches_oracle():
         hk.hikonv_epilogue(dev(acc), n, c, h, w, shift, 15, pool, 4, hk.FMT_INT8, out_i8.view)
         assert np.array_equal(out_bd.result().reshape(ref_bd.shape), ref_bd), (n, c, h, w, pool)
         assert np.array_equal(out_i8.result().reshape(q.shape), q.view(np.uint8)), (n, c, h, w, pool)
-
-
-def oracle_cnn(x, weights, specs):
-    """Layer-by-layer oracle forward; the per-layer requantisation shift is chosen here so that
-    the 99th percentile of the positive accumulators maps to at most 15."""
-    accs, shifts = [], []
-    cur = x
-    for i, (w, spec) in enumerate(zip(weights, specs)):
-        acc = direct.conv2d(cur, w, 1, spec["pad"])
-        accs.append(acc)
-        if i + 1 == len(weights):
-            break
-        pos = acc[acc > 0]
-        p99 = int(np.percentile(pos, 99)) if pos.size else 0
-        shift = 0
-        while (p99 >> shift) > 15:
-            shift += 1
-        shifts.append(shift)
-        q = direct.relu_requant(acc, shift, 15)
-        if spec["pool"]:
-            q = direct.maxpool2x2(q)
-        cur = q.view(np.uint8)
-    return accs, shifts
 
 
 @pytest.mark.parametrize("pool", [0, 1])
