@@ -396,7 +396,7 @@ extern "C" int hikonv_conv1d(const hikonv_plan_t *plan, const void *x_dev, int x
     const bool any_signed = plan->a_signed || plan->w_signed;
     if (plan->kernel != HIKONV_KERNEL_AUTO && plan->kernel != HIKONV_KERNEL_LANES && plan->kernel != HIKONV_KERNEL_WINDOW)
         return HIKONV_EINVAL;
-    // Kernel form: a lane per aligned output quad where the plan allows it (its stores follow
+    // Kernel form: a lane per aligned group of 8 or 4 outputs where the plan allows it (its stores follow
     // the order of y across the whole workgroup, which the memory system takes faster than
     // per-wave runs); else a lane per block with the high parts exchanged between lanes.
     if (plan->kernel != HIKONV_KERNEL_LANES && conv1d_window_applicable(a)) {

@@ -138,7 +138,7 @@ hipError_t launch_window_nt(const Conv1dArgs &a, bool a_signed, bool any_signed,
                 return hipGetLastError();                                                                \
             }                                                                                            \
         }                                                                                                \
-        if constexpr (N <= 4) { /* quads: 8-bit containers, so N <= 4 */                                 \
+        if constexpr (N <= 4) { /* groups of 4: 8-bit containers, so N <= 4 */                           \
             if (!wide) {                                                                                 \
                 hipLaunchKernelGGL((k_conv1d_window<N, TAPS, AS, ANY, false, 4>), g, b, 0, stream, a);   \
                 return hipGetLastError();                                                                \

@@ -17,8 +17,8 @@ SIGNS = [(False, False), (True, True), (False, True), (True, False)]
 
 @pytest.fixture(autouse=True, params=["library_choice", "lane_exchange"])
 def kernel_form(request):
-    """Every case runs on the kernel the library picks (a lane per output quad where the plan
-    allows it) and with the lane-per-block kernel asked for through the plan."""
+    """Every case runs on the kernel the library picks (a lane per aligned group of outputs where
+    the plan allows it) and with the lane-per-block kernel asked for through the plan."""
     import gpu_util
     old = dict(gpu_util.CONV1D_DEFAULTS)
     gpu_util.CONV1D_DEFAULTS["kernel"] = hk.KERNEL_AUTO if request.param == "library_choice" else hk.KERNEL_LANES
