@@ -16,7 +16,7 @@
 //             cooperatively, once per workgroup instead of once per lane and term);
 //   stage     the tile's B words go to LDS once per workgroup, the int32 tile [R][8][Wo] is cleared;
 //   multiply  as in k_conv2d_pipe: one 16-byte read brings the A words of four terms (from
-//             LDS, or from the packed activations in global memory with up to eight loads in
+//             LDS, or from the packed activations in global memory with three loads in
 //             flight), B words come as broadcast LDS reads, Acc += A * B over M terms before
 //             a split (Theorem 3, "DNN Convolution Extension");
 //   split     high part to the next lane (DPP), N fields per channel (Eq. output_split, bias form);
@@ -33,7 +33,8 @@
 namespace hikonv {
 namespace {
 
-constexpr int kFusedBatch = 8; // activation cells (term groups) a lane requests before it multiplies
+constexpr int kFusedBatch = 3; // activation cells (term groups) a lane requests before it multiplies (measured on the
+                               // nine-layer chain: 2, 3, 4, 6, 8 -> 77.5, 76.8, 78.5, 78.1, 80.8 us)
 
 // GROUP_SPLITS: the plan allows at least four terms between splits, which then fall on the
 // boundaries of term groups (f.split_terms, a multiple of 4); else a split may follow any term.
