@@ -149,6 +149,15 @@ __device__ __forceinline__ void sload_x1(int32_t &dst, const void *uniform_ptr)
 {
     asm volatile("s_load_dword %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
 }
+template <int BYTE_OFFSET>
+__device__ __forceinline__ void sload_x4(i32x4 &dst, const void *uniform_ptr)
+{
+    asm volatile("s_load_dwordx4 %0, %1, %2" : "=&s"(dst) : "s"(uniform_ptr), "n"(BYTE_OFFSET));
+}
+__device__ __forceinline__ void wait_scalar_loads(u32x8 (&b)[4], i32x4 &o4)
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(b[0]), "+s"(b[1]), "+s"(b[2]), "+s"(b[3]), "+s"(o4));
+}
 __device__ __forceinline__ void wait_scalar_loads(u32x8 (&b)[4], int32_t &o)
 {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(b[0]), "+s"(b[1]), "+s"(b[2]), "+s"(b[3]), "+s"(o));
@@ -290,22 +299,19 @@ __global__ __launch_bounds__(256) void k_conv2d_sreg(Conv2dArgs p)
 
         const char *bp = wrow + (int64_t)g_begin * (U * 32); // weights of the group the next stage multiplies
         const char *tp = trow + (int64_t)g_begin * 4;        // its activation offset
-        // prologue: B of the first group, A of the first three, offsets of the fourth
+        // prologue: B of the first group and the offsets of the first four with one wait, then A of
+        // the first three (the table is padded past the wave's range, like the weights)
+        i32x4 o4;
         sload_x8<0>(b0[0], bp);
         sload_x8<32>(b0[1], bp);
         sload_x8<64>(b0[2], bp);
         sload_x8<96>(b0[3], bp);
-        sload_x1<0>(o, tp);
-        wait_scalar_loads(b0, o);
-        load_a(a0, o);
-        sload_x1<4>(o, tp);
-        wait_scalar_loads(b0, o);
-        load_a(a1, o);
-        sload_x1<8>(o, tp);
-        wait_scalar_loads(b0, o);
-        load_a(a2, o);
-        sload_x1<12>(o, tp);
-        wait_scalar_loads(b0, o);
+        sload_x4<0>(o4, tp);
+        wait_scalar_loads(b0, o4);
+        load_a(a0, o4.x);
+        load_a(a1, o4.y);
+        load_a(a2, o4.z);
+        o = o4.w;
         int left = g_end - g_begin; // groups still to multiply
         // One stage, k-th of four, for group g+k: B of g+k+1, A of g+k+3 (o holds its offsets),
         // offsets of g+k+4, then the multiply-accumulates of g+k.
