@@ -14,6 +14,8 @@
 //          sign never arises)
 //   store  through an LDS staging tile, 16-byte aligned coalesced int32x4 stores
 // k_conv1d_unpacked: the baseline, one v_mad_i32_i24 per low-bit product.
+#include <type_traits>
+
 #include "hikonv_quad_stream.h"
 
 namespace hikonv {
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
 // arithmetic is one v_mad_i32_i24 per low-bit product.  Needs the window within 64 bits (three
 // dwords) or, WIDE, 96 bits (four).
 template <bool A_SIGNED, int TAPS, bool WIDE, int G>
-__global__ __launch_bounds__(kStreamThreads) void k_conv1d_unpacked_fast(Conv1dArgs p)
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_conv1d_unpacked_fast(Conv1dArgs p)
 {
     __shared__ int32_t s_g[8];
     if (threadIdx.x < TAPS)
@@ -217,21 +219,42 @@ __global__ __launch_bounds__(kStreamThreads) void k_conv1d_unpacked_fast(Conv1dA
     int32_t gk[TAPS];
 #pragma unroll
     for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
-    const int c = WIDE ? 8 : p.c, b = p.b;
-    auto direct = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[G]) {
+    const int b = p.b;
+    // the container width is a compile-time constant inside, so an element is one bit-field
+    // extract from the dword that holds it (containers never straddle a dword)
+    auto direct_c = [&](auto cc, uint64_t win, uint32_t win_hi, int32_t (&out)[G]) {
+        constexpr int C = decltype(cc)::value;
+        const uint32_t dw[3] = {(uint32_t)win, (uint32_t)(win >> 32), win_hi};
+        bool started[G];
+#pragma unroll
+        for (int u = 0; u < G; ++u) started[u] = false, out[u] = 0;
 #pragma unroll
         for (int t = 0; t < TAPS + G - 1; ++t) {
-            // containers never straddle bit 64 (their width divides 64)
-            const uint32_t bits_t = WIDE && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
-            const int32_t v = field<A_SIGNED>(bits_t, 0u, (uint32_t)b);
+            const int32_t v = field<A_SIGNED>(dw[(t * C) >> 5], (uint32_t)((t * C) & 31), (uint32_t)b);
 #pragma unroll
             for (int u = 0; u < G; ++u) {
                 const int k = u + TAPS - 1 - t;
-                if (k >= 0 && k < TAPS) out[u] = __mul24(v, gk[k]) + out[u];
+                if (k < 0 || k >= TAPS) continue;
+                // the first product of an output is a multiply, every further one a multiply-add
+                out[u] = started[u] ? mad24(v, gk[k], out[u]) : __mul24(v, gk[k]);
+                started[u] = true;
             }
         }
     };
-    for_each_output_group<G, TAPS + G - 1, WIDE>(p, p.shift_m - (TAPS - 1), direct);
+    // wave-uniform choice of the container width, outside the loops
+    __shared__ stream_v4i s_turn[stream_turn_quads(G)];
+    auto run = [&](auto cc) {
+        for_each_output_group<G, TAPS + G - 1, WIDE>(p, p.shift_m - (TAPS - 1), s_turn,
+                                                     [&](uint64_t win, uint32_t win_hi, int32_t (&out)[G]) { direct_c(cc, win, win_hi, out); });
+    };
+    if (G == 4)
+        run(std::integral_constant<int, 8>{});
+    else if (p.c == 4)
+        run(std::integral_constant<int, 4>{});
+    else if (p.c == 2)
+        run(std::integral_constant<int, 2>{});
+    else
+        run(std::integral_constant<int, 1>{});
 }
 
 } // namespace

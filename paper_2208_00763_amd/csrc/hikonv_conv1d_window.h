@@ -28,6 +28,8 @@
 #ifndef HIKONV_CONV1D_WINDOW_H
 #define HIKONV_CONV1D_WINDOW_H
 
+#include <type_traits>
+
 #include "hikonv_quad_stream.h"
 
 namespace hikonv {
@@ -35,7 +37,7 @@ namespace hikonv {
 // G: outputs per window (8 with containers of up to 4 bits, else 4).
 // WIDE: the window needs more than 64 bits, which happens only with 8-bit containers
 template <int N, int TAPS, bool A_SIGNED, bool ANY_SIGNED, bool WIDE, int G>
-__global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_conv1d_window(Conv1dArgs p)
 {
     constexpr int T = TAPS + G - 1;                // elements of a group's window
     constexpr int NB = (T + N - 1) / N;            // blocks that cover them
@@ -48,7 +50,6 @@ __global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
         s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
     __syncthreads();
     const int S = p.S, b = p.b;
-    const int c = WIDE ? 8 : p.c;
     // B words (Eq. inpack), wave-uniform
     uint32_t bw[CH];
 #pragma unroll
@@ -69,25 +70,22 @@ __global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
         bias_f = 1 << (S - 1);
     }
 
-    // the G outputs of a group from its window (elements at bits t*c of win_hi:win)
-    auto group = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[G]) {
+    // the G outputs of a group from its window (elements at bits t*C of win_hi:win).  The container
+    // width is a compile-time constant inside, so an element's dword and bit are known and a
+    // container is one bit-field extract (containers never straddle a dword).
+    auto group_c = [&](auto cc, uint64_t win, uint32_t win_hi, int32_t (&out)[G]) {
+        constexpr int C = decltype(cc)::value;
+        const uint32_t dw[3] = {(uint32_t)win, (uint32_t)(win >> 32), win_hi};
         uint32_t a[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            const int pos = j * N * c;             // bit of the block's first element in the window
-            uint32_t raw;
-            if (!WIDE)
-                raw = (uint32_t)(win >> pos);
-            else if (pos >= 64)
-                raw = win_hi >> (pos - 64);
-            else if (pos > 32)
-                raw = (uint32_t)(win >> pos) | (win_hi << (64 - pos));
-            else
-                raw = (uint32_t)(win >> pos);
+            // Eq. inpack from the top element down: one shift-and-add per element
             uint32_t w = 0;
 #pragma unroll
-            for (int n = 0; n < N; ++n)
-                if (j * N + n < T) w += (uint32_t)field<A_SIGNED>(raw, (uint32_t)(n * c), (uint32_t)b) << (S * n);
+            for (int n = N - 1; n >= 0; --n) {
+                const int e = j * N + n;
+                if (e < T) w = (w << S) + (uint32_t)field<A_SIGNED>(dw[(e * C) >> 5], (uint32_t)((e * C) & 31), (uint32_t)b);
+            }
             a[j] = w;
         }
         uint64_t hi = 0;
@@ -102,13 +100,30 @@ __global__ __launch_bounds__(kStreamThreads) void k_conv1d_window(Conv1dArgs p)
             for (int i = 0; i < N; ++i) {
                 constexpr int first = TAPS - 1;
                 const int m = j * N + i;
-                if (m >= first && m < first + G)
-                    out[m - first] = (int32_t)((uint32_t)(acc >> (S * i)) & fmask) - bias_f;
+                if (m >= first && m < first + G) {
+                    // a packed word fits 32 bits, so S (N - 1) < 32: every segment but the last lies
+                    // inside the low dword (one bit-field extract); the last may straddle the dwords
+                    const uint32_t f = i < N - 1 ? __builtin_amdgcn_ubfe((uint32_t)acc, (uint32_t)(S * i), (uint32_t)S)
+                                                 : (uint32_t)(acc >> (S * i)) & fmask;
+                    out[m - first] = (int32_t)f - bias_f;
+                }
             }
         }
     };
-
-    for_each_output_group<G, T, WIDE>(p, p.shift_m - (TAPS - 1), group);
+    // wave-uniform choice of the container width, outside the loops
+    __shared__ stream_v4i s_turn[stream_turn_quads(G)];
+    auto run = [&](auto cc) {
+        for_each_output_group<G, T, WIDE>(p, p.shift_m - (TAPS - 1), s_turn,
+                                          [&](uint64_t win, uint32_t win_hi, int32_t (&out)[G]) { group_c(cc, win, win_hi, out); });
+    };
+    if (G == 4)
+        run(std::integral_constant<int, 8>{});
+    else if (p.c == 4)
+        run(std::integral_constant<int, 4>{});
+    else if (p.c == 2)
+        run(std::integral_constant<int, 2>{});
+    else
+        run(std::integral_constant<int, 1>{});
 }
 
 // instantiations live in one translation unit per tap count

@@ -53,6 +53,16 @@ __device__ __forceinline__ uint32_t mad_narrow(uint32_t a, uint32_t b, uint32_t 
     return __umul24(a, b) + acc;
 }
 
+// a*b + c on 24-bit signed operands, written as the instruction: left to itself the compiler
+// turns a chain of these into separate multiplies and three-operand adds (4 instructions for 3
+// products instead of 3).
+__device__ __forceinline__ int32_t mad24(int32_t a, int32_t b, int32_t c)
+{
+    int32_t d;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
 // Segments N.. of an accumulated word (shift by S*N).  A shift that reaches the register
 // width happens only for one-tap kernels, which have no high segments: the result is 0.
 template <bool SIGNED>

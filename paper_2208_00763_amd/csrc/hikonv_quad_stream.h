@@ -69,8 +69,13 @@ inline dim3 quad_stream_grid(const Conv1dArgs &a, int group = 4)
 // compute(win, win_hi, out): the T = taps + G - 1 elements of the window sit at bits t*c of
 // win_hi:win; out receives the group's G outputs.  G = 4: one streaming int32x4 store per group.
 // G = 8 (windows within 64 bits): two int32x4 stores per group.
+typedef int32_t stream_v4i __attribute__((ext_vector_type(4)));
+// LDS the skeleton needs per workgroup, in 16-byte units (the caller declares it once per kernel,
+// so that a kernel which instantiates the skeleton several times holds one copy)
+constexpr int stream_turn_quads(int group) { return group == 8 ? kStreamThreads * 2 : 1; }
+
 template <int G, int T, bool WIDE, typename F>
-__device__ __forceinline__ void for_each_output_group(const Conv1dArgs &p, int lead_in, F &&compute)
+__device__ __forceinline__ void for_each_output_group(const Conv1dArgs &p, int lead_in, stream_v4i *s_turn, F &&compute)
 {
     static_assert(G == 4 || G == 8, "groups of 4 or 8 outputs");
     static_assert(G == 4 || !WIDE, "a window wider than 64 bits feeds a quad only");
@@ -85,8 +90,7 @@ __device__ __forceinline__ void for_each_output_group(const Conv1dArgs &p, int l
     const char *xbytes = reinterpret_cast<const char *>(p.x);
     typedef uint32_t u32x3_dw __attribute__((ext_vector_type(3), aligned(4)));
     typedef uint32_t u32x4_dw __attribute__((ext_vector_type(4), aligned(4)));
-    typedef int32_t v4i __attribute__((ext_vector_type(4)));
-    __shared__ v4i s_turn[G == 8 ? kStreamThreads * 2 : 1];        // G = 8: 2 KB per wave, see the stores below
+    typedef stream_v4i v4i;                                         // s_turn, G = 8: 2 KB per wave, see the stores below
     auto floor_g = [](int a) { return a >> LG; };                   // floor(a / G) and ceil(a / G) for any sign
     auto ceil_g = [](int a) { return (a + G - 1) >> LG; };
 
@@ -158,10 +162,11 @@ __device__ __forceinline__ void for_each_output_group(const Conv1dArgs &p, int l
         }
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
+            // every lane runs the arithmetic (a group that is not interior works on the dwords it
+            // loaded from the buffer's start and stores nothing): no preset of the outputs and no
+            // change of the execution mask around the arithmetic
             int32_t out[G];
-#pragma unroll
-            for (int u = 0; u < G; ++u) out[u] = 0;
-            if (interior[s]) {
+            {
                 const uint32_t sh = shv[s];
                 const uint64_t win = ((uint64_t)funnel_shr(w2[s], w1[s], sh) << 32) | funnel_shr(w1[s], w0[s], sh);
                 compute(win, WIDE ? funnel_shr(w3[s], w2[s], sh) : 0u, out);
