@@ -459,7 +459,36 @@ def microbench(hk):
                        ("copy_read_plus_write", hk.UB_HBM_COPY), ("read", hk.UB_HBM_READ)):
         best = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, nb, big), 5) for nb in (4096, 16384, 32768, 65536, 89240))
         out["hbm_TB_per_s"][name] = big.numel() * 4 / (best * 1e-3) / 1e12
+    # the same plain write with values of 2, 10, 18 and 32 varied bits per int32 (the value range of the
+    # outputs of a 1-, 4- and 8-bit 3-tap convolution, and full words)
+    for bits in (2, 10, 18, 32):
+        best = min(event_ms(lambda: hk.hikonv_ubench(hk.UB_HBM_WRITE_VARIED, bits, nb, big), 5)
+                   for nb in (4096, 16384, 32768, 65536, 89240))
+        out["hbm_TB_per_s"]["write_varied_values_%d_bits" % bits] = big.numel() * 4 / (best * 1e-3) / 1e12
+    del big
+    torch.cuda.empty_cache()
     return out
+
+
+def output_value_dependence(hk, wl):
+    """The headline launch (4-bit, 3 taps, 4096 x 65536) timed on the same buffers with the taps as
+    generated, with all taps 0 (every output 0) and with taps (1, 0, 0) on an input of all ones
+    (every output 1): same kernel, same instruction stream, same bytes; only the values differ."""
+    import numpy as np
+    import torch
+    case = conv1d_case(hk, wl, 4, False)
+    x_bd, g_d = case["keep"]
+    res = {}
+    for name, taps, fill in (("taps_as_generated", None, None), ("all_outputs_0", (0, 0, 0), None),
+                             ("all_outputs_1", (1, 0, 0), 0x11), ("taps_as_generated_again", None, None)):
+        g_use = g_d if taps is None else torch.tensor(taps, dtype=torch.uint8, device="cuda")
+        x_use = x_bd if fill is None else torch.full_like(x_bd, fill)
+
+        def fn():
+            hk.hikonv_conv1d(case["plan"], x_use, hk.FMT_BITDENSE, ROWS, LENGTH, g_use, TAPS, hk.OUT_VALID, case["y"])
+        event_ms(fn, 3)
+        res[name] = {"ms": round(min(event_ms(fn, 20) for _ in range(3)), 4), "max_output": int(case["y"].max())}
+    return res
 
 
 def main():
@@ -505,7 +534,9 @@ def main():
         return 0
 
     if args.ubench:
-        print(json.dumps(microbench(hk)))
+        out = microbench(hk)
+        out["conv1d_headline_ms_by_output_values"] = output_value_dependence(hk, wl)
+        print(json.dumps(out))
         return 0
 
     if args.sweep:

@@ -38,6 +38,7 @@ extern "C" {
 #define HIKONV_UB_HBM_READ 18
 #define HIKONV_UB_HBM_WRITE_NT 19 /* write with the non-temporal hint */
 #define HIKONV_UB_HBM_WRITE_RUNS 20 /* non-temporal, one contiguous 6016-byte run per wave (the 1-D kernel's store pattern) */
+#define HIKONV_UB_HBM_WRITE_VARIED 21 /* plain writes of int32 values that vary from word to word, `iters` (1..32) low bits of a hash of the position */
 int hikonv_ubench(int kind, int iters, int blocks, void *buf_dev, size_t bytes, void *stream);
 
 /* Lane-exchange self check: out_dev[i] (64 ints) = value lane i receives from lane i-1 (lane 0: 0). */

@@ -337,6 +337,27 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
         }
     };
 
+    // the PER outputs of a window.  With the same container width in and out (the usual case) the
+    // position of an element is a compile-time constant: one bit-field extract from the dword that
+    // holds it (a container never straddles a dword).  Taken for containers of 4 and 8 bits, where
+    // it is faster (measured at 4096 x 65536, 3 taps: 0.100 against 0.112 ms at 4 bit; at 2 and 1
+    // bit the shifted form below is the faster one, 0.094 against 0.131 and 0.234 against 0.264 ms)
+    auto window_outputs = [&](uint64_t win, int32_t (&out)[PER]) {
+#pragma unroll
+        for (int u = 0; u < PER; ++u) out[u] = 0;
+        if (PER <= 8 && c == 32 / PER) { // wave-uniform
+            constexpr int CC = 32 / PER;
+            const uint32_t lo = (uint32_t)win, hi = (uint32_t)(win >> 32);
+#pragma unroll
+            for (int t = 0; t < TAPS + PER - 1; ++t)
+                accumulate(out, t, field<A_SIGNED>(t * CC < 32 ? lo : hi, (uint32_t)((t * CC) & 31), (uint32_t)b));
+        } else {
+#pragma unroll
+            for (int t = 0; t < TAPS + PER - 1; ++t)
+                accumulate(out, t, field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b));
+        }
+    };
+
     for (int64_t r = blockIdx.y; r < p.rows; r += gridDim.y) {
         const int64_t row_bit0 = r * p.row_stride_bits;
         const int64_t k0 = (int64_t)blockIdx.x * (256 * U) + threadIdx.x;
@@ -360,11 +381,7 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
             for (int q = 0; q < U; ++q) {
                 const uint64_t win = ((uint64_t)funnel_shr(w2[q], w1[q], sh[q]) << 32) | funnel_shr(w1[q], w0[q], sh[q]);
                 int32_t out[PER];
-#pragma unroll
-                for (int u = 0; u < PER; ++u) out[u] = 0;
-#pragma unroll
-                for (int t = 0; t < TAPS + PER - 1; ++t)
-                    accumulate(out, t, field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b));
+                window_outputs(win, out);
                 emit(r, k0 + q * 256, out);
             }
         } else {
@@ -393,11 +410,7 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
                     win &= m_hi & ~((1ull << lo_bits) - 1ull);
                 }
                 int32_t out[PER];
-#pragma unroll
-                for (int u = 0; u < PER; ++u) out[u] = 0;
-#pragma unroll
-                for (int t = 0; t < TAPS + PER - 1; ++t)
-                    accumulate(out, t, field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b));
+                window_outputs(win, out);
                 emit(r, k, out);
             }
         }

@@ -113,17 +113,19 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     // wave-uniform choice of the container width, outside the loops
     __shared__ stream_v4i s_turn[stream_turn_quads(G)];
     auto run = [&](auto cc) {
-        for_each_output_group<G, T, WIDE>(p, p.shift_m - (TAPS - 1), s_turn,
+        for_each_output_group<G, T, WIDE, decltype(cc)::value>(p, p.shift_m - (TAPS - 1), s_turn,
                                           [&](uint64_t win, uint32_t win_hi, int32_t (&out)[G]) { group_c(cc, win, win_hi, out); });
     };
-    if (G == 4)
+    if constexpr (G == 4) {
         run(std::integral_constant<int, 8>{});
-    else if (p.c == 4)
-        run(std::integral_constant<int, 4>{});
-    else if (p.c == 2)
-        run(std::integral_constant<int, 2>{});
-    else
-        run(std::integral_constant<int, 1>{});
+    } else {
+        if (p.c == 4)
+            run(std::integral_constant<int, 4>{});
+        else if (p.c == 2)
+            run(std::integral_constant<int, 2>{});
+        else
+            run(std::integral_constant<int, 1>{});
+    }
 }
 
 // instantiations live in one translation unit per tap count

@@ -216,6 +216,21 @@ __global__ __launch_bounds__(256) void k_ubench_write_nt(int4 *dst, int64_t n16)
         __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(dst) + i);
 }
 
+// Plain writes of values that differ from store to store: every int32 is a hash of its position,
+// cut to `value_bits` low bits (the time to write a buffer depends on what is written: int32
+// words that are mostly zero bits, such as the outputs of a 1-bit convolution, move slower than
+// varied ones).
+__global__ __launch_bounds__(256) void k_ubench_write_varied(int4 *dst, int64_t n16, int value_bits)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const uint32_t mask = value_bits >= 32 ? 0xffffffffu : (1u << value_bits) - 1u;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+        const uint32_t h = (uint32_t)i * 2654435761u;
+        dst[i] = make_int4((int)(h & mask), (int)((h >> 7 ^ h * 3u) & mask), (int)((h >> 13 ^ h * 5u) & mask),
+                           (int)((h >> 19 ^ h * 7u) & mask));
+    }
+}
+
 // The store pattern of the streaming 1-D kernel without its arithmetic: every wave owns one
 // contiguous run of 47 lines of 128 bytes and writes it with six line-aligned 1 KB stores.
 __global__ __launch_bounds__(256) void k_ubench_write_runs(int4 *dst, int64_t n16)
@@ -353,6 +368,10 @@ hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t byte
         break;
     case HIKONV_UB_HBM_WRITE_NT:
         hipLaunchKernelGGL(k_ubench_write_nt, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));
+        break;
+    case HIKONV_UB_HBM_WRITE_VARIED:
+        if (iters < 1 || iters > 32) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(k_ubench_write_varied, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16), iters);
         break;
     case HIKONV_UB_HBM_WRITE_RUNS:
         hipLaunchKernelGGL(k_ubench_write_runs, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));

@@ -33,20 +33,6 @@ inline int stream_group(int container_bits) { return container_bits <= 4 ? 8 : 4
 // groups a lane makes per row pass: 16 outputs either way (measured: four groups of 8 are slower than two)
 constexpr int stream_steps(int group) { return 16 / group; }
 
-__device__ __forceinline__ uint32_t stream_dword_checked(const uint32_t *x, int64_t d, int64_t total_dwords,
-                                                         int64_t total_bytes)
-{
-    if (d < 0) return 0;
-    if (d < total_dwords) return x[d];
-    uint32_t v = 0;
-    const uint8_t *xb = reinterpret_cast<const uint8_t *>(x);
-    for (int t = 0; t < 4; ++t) {
-        const int64_t byte = d * 4 + t;
-        if (byte < total_bytes) v |= (uint32_t)xb[byte] << (8 * t);
-    }
-    return v;
-}
-
 // the launcher's conditions for this skeleton: positions inside a row and byte offsets inside
 // the input buffer fit 32 bits, the buffer holds at least four dwords, containers are 1, 2, 4 or 8 bits
 inline bool quad_stream_applicable(const Conv1dArgs &a, int window_elems)
@@ -74,18 +60,20 @@ typedef int32_t stream_v4i __attribute__((ext_vector_type(4)));
 // so that a kernel which instantiates the skeleton several times holds one copy)
 constexpr int stream_turn_quads(int group) { return group == 8 ? kStreamThreads * 2 : 1; }
 
-template <int G, int T, bool WIDE, typename F>
+template <int G, int T, bool WIDE, int C, typename F>
 __device__ __forceinline__ void for_each_output_group(const Conv1dArgs &p, int lead_in, stream_v4i *s_turn, F &&compute)
 {
     static_assert(G == 4 || G == 8, "groups of 4 or 8 outputs");
     static_assert(G == 4 || !WIDE, "a window wider than 64 bits feeds a quad only");
+    static_assert(C == 1 || C == 2 || C == 4 || C == 8, "container width");
+    static_assert(!WIDE || C == 8, "a window wider than 64 bits has 8-bit containers");
     constexpr int LG = G == 4 ? 2 : 3;
     constexpr int STEPS = stream_steps(G);
     constexpr int LINE = 32 / G;                                    // groups per 128-byte line of y
     const int out_len = (int)p.out_len, len = (int)p.len;
     const int ngroups = (out_len + 2 * (G - 1)) / G;
-    const int c = WIDE ? 8 : p.c;
-    const int lc = WIDE ? 3 : (p.c == 1 ? 0 : p.c == 2 ? 1 : p.c == 4 ? 2 : 3); // log2 of the container width
+    constexpr int c = C;                                            // the container width (p.c, chosen by the caller)
+    constexpr int lc = C == 1 ? 0 : C == 2 ? 1 : C == 4 ? 2 : 3;    // its log2
     const int64_t total_bits = p.total_bytes * 8;
     const char *xbytes = reinterpret_cast<const char *>(p.x);
     typedef uint32_t u32x3_dw __attribute__((ext_vector_type(3), aligned(4)));
@@ -203,35 +191,45 @@ __device__ __forceinline__ void for_each_output_group(const Conv1dArgs &p, int l
             }
         }
         // groups at the row's ends (and where a load would leave the buffer): the same window from
-        // checked loads, element by element, zero outside the row; the same arithmetic
+        // one byte load per element (a container never straddles a byte; an element of the row is
+        // inside the buffer), zero outside the row; the same arithmetic; checked element stores.
+        // The loads of a window are unconditional (clamped) and independent, so they overlap.
         if (__builtin_amdgcn_ballot_w64(any_edge) != 0) {
+            const uint8_t *xb = reinterpret_cast<const uint8_t *>(p.x);
 #pragma unroll 1
             for (int s = 0; s < STEPS; ++s) {
                 const int q = q_first + s * kStreamThreads;
                 const bool inside = !none && (uint32_t)(q - q_lo) <= q_span;
-                if (inside || (uint32_t)q >= (uint32_t)ngroups) continue;
+                const bool edge = !inside && (uint32_t)q < (uint32_t)ngroups;
+                if (__builtin_amdgcn_ballot_w64(edge) == 0) continue;   // wave-uniform
                 const int o0 = G * q - a_off;
                 const int i0 = o0 + lead_in;
-                uint64_t win = 0;
-                uint32_t win_hi = 0;
+                uint32_t e[T];
+#pragma unroll
                 for (int t = 0; t < T; ++t) {
                     const int i = i0 + t;
-                    if (i < 0 || i >= len) continue;
-                    const int64_t eb = row_bit0 + (int64_t)i * c;
-                    const uint32_t w = stream_dword_checked(p.x, eb >> 5, p.total_dwords, p.total_bytes);
-                    const uint64_t v = (w >> (uint32_t)(eb & 31)) & ((1u << c) - 1u);
+                    const bool ok = edge && (uint32_t)i < (uint32_t)len;
+                    // bits from the row's first dword fit 32 bits, byte offsets in the buffer too (launcher)
+                    const uint32_t rel = (uint32_t)row_sh + (uint32_t)i * (uint32_t)c;
+                    const uint32_t v = xb[ok ? row_byte + (rel >> 3) : 0u];
+                    e[t] = ok ? (v >> (rel & 7u)) & ((1u << c) - 1u) : 0u;
+                }
+                uint64_t win = 0;
+                uint32_t win_hi = 0;
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
                     if (t * c < 64)
-                        win |= v << (t * c);
+                        win |= (uint64_t)e[t] << (t * c);
                     else
-                        win_hi |= (uint32_t)v << (t * c - 64);
+                        win_hi |= e[t] << (t * c - 64);
                 }
                 int32_t out[G];
-#pragma unroll
-                for (int u = 0; u < G; ++u) out[u] = 0;
                 compute(win, win_hi, out);
+                if (edge) {
 #pragma unroll
-                for (int u = 0; u < G; ++u)
-                    if (o0 + u >= 0 && o0 + u < out_len) yrow[o0 + u] = out[u];
+                    for (int u = 0; u < G; ++u)
+                        if (o0 + u >= 0 && o0 + u < out_len) yrow[o0 + u] = out[u];
+                }
             }
         }
     }
