@@ -122,8 +122,8 @@ def test_aligned_plans_are_exact_in_the_big_integer_model_on_corner_inputs():
 # Measured on one MI355X, 4096 rows x 65536, 3 taps, valid, requantised bit-dense output at the
 # input's width (milliseconds per launch; bench.py, conv1d_requant_bitdense_out):
 # (bits, signed) -> (container-aligned slices, the paper's plan)
-MEASURED_REQUANT_MS = {(4, False): (0.051, 0.174), (2, False): (0.043, 0.141), (1, False): (0.023, 0.135),
-                       (4, True): (0.061, 0.176)}
+MEASURED_REQUANT_MS = {(4, False): (0.050, 0.163), (2, False): (0.040, 0.136), (1, False): (0.022, 0.132),
+                       (4, True): (0.057, 0.169)}
 
 
 def test_cost_ranking_reproduces_the_measured_ranking():
