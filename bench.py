@@ -445,7 +445,8 @@ def microbench(hk):
     kinds = {"v_mad_u32_u24": hk.UB_MAD_U32_U24, "v_mad_i32_i24": hk.UB_MAD_I32_I24,
              "v_mad_u64_u32": hk.UB_MAD_U64_U32, "v_mad_i64_i32": hk.UB_MAD_I64_I32,
              "v_mul_lo_u32": hk.UB_MUL_LO_U32, "v_bfe_u32": hk.UB_BFE_U32, "v_lshrrev_b64": hk.UB_LSHR_B64,
-             "v_lshl_add_u64": hk.UB_ADD_U64, "v_alignbit_b32": hk.UB_ALIGNBIT, "v_mov_b32_dpp wave_shr:1": hk.UB_DPP_MOV}
+             "v_lshl_add_u64": hk.UB_ADD_U64, "v_alignbit_b32": hk.UB_ALIGNBIT, "v_mov_b32_dpp wave_shr:1": hk.UB_DPP_MOV,
+             "v_ashrrev_i64": hk.UB_ASHR_I64, "v_bfe_i32": hk.UB_BFE_I32}
     blocks, iters = 256 * 32, 2000                       # 32 waves per CU, 64 instructions per iteration
     buf = torch.zeros(blocks * 256, dtype=torch.int32, device="cuda")
     out = {"valu_T_lane_instr_per_s": {}, "hbm_TB_per_s": {}, "nominal_valu_T": VALU_LANE_RATE / 1e12}
@@ -453,6 +454,12 @@ def microbench(hk):
         full = min(event_ms(lambda: hk.hikonv_ubench(kind, iters, blocks, buf), 3) for _ in range(3))
         empty = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, blocks, buf), 3) for _ in range(3))
         out["valu_T_lane_instr_per_s"][name] = blocks * 256 * iters * 64 / ((full - empty) * 1e-3) / 1e12
+    # dependent-issue latency: one wave per SIMD (256 workgroups of four waves), one chain per lane
+    out["dependent_issue_cycles"] = {}
+    for name, kind in (("v_mad_i64_i32", hk.UB_CHAIN_MAD_I64_I32), ("v_mad_i32_i24", hk.UB_CHAIN_MAD_I32_I24)):
+        full = min(event_ms(lambda: hk.hikonv_ubench(kind, iters, 256, buf), 3) for _ in range(3))
+        empty = min(event_ms(lambda: hk.hikonv_ubench(kind, 0, 256, buf), 3) for _ in range(3))
+        out["dependent_issue_cycles"][name] = (full - empty) * 1e-3 * 2.4e9 / (iters * 64)
     big = torch.zeros(2 * 1024 ** 3 // 4, dtype=torch.int32, device="cuda")
     for name, kind in (("write", hk.UB_HBM_WRITE), ("write_nontemporal", hk.UB_HBM_WRITE_NT),
                        ("write_nontemporal_runs_per_wave", hk.UB_HBM_WRITE_RUNS),

@@ -33,6 +33,10 @@ extern "C" {
 #define HIKONV_UB_ADD_U64 9
 #define HIKONV_UB_ALIGNBIT 10
 #define HIKONV_UB_AND_B32 11
+#define HIKONV_UB_ASHR_I64 12
+#define HIKONV_UB_BFE_I32 13
+#define HIKONV_UB_CHAIN_MAD_I64_I32 14 /* one dependent chain per lane: with one wave per SIMD the time per slot is the latency */
+#define HIKONV_UB_CHAIN_MAD_I32_I24 15
 #define HIKONV_UB_HBM_WRITE 16
 #define HIKONV_UB_HBM_COPY 17
 #define HIKONV_UB_HBM_READ 18

@@ -18,6 +18,7 @@ FMT_INT8, FMT_BITDENSE, FMT_PACKED = 0, 1, 2
 OUT_FULL, OUT_VALID = 0, 1
 UB_MAD_U32_U24, UB_MAD_U64_U32, UB_MUL_LO_U32, UB_BFE_U32, UB_LSHR_B64, UB_DPP_MOV, UB_ADD_U32 = range(7)
 UB_MAD_I32_I24, UB_MAD_I64_I32, UB_ADD_U64, UB_ALIGNBIT, UB_AND_B32 = range(7, 12)
+UB_ASHR_I64, UB_BFE_I32, UB_CHAIN_MAD_I64_I32, UB_CHAIN_MAD_I32_I24 = 12, 13, 14, 15
 UB_HBM_WRITE, UB_HBM_COPY, UB_HBM_READ, UB_HBM_WRITE_NT, UB_HBM_WRITE_RUNS, UB_HBM_WRITE_VARIED = 16, 17, 18, 19, 20, 21
 
 OBJ_PAPER_OPS, OBJ_MEASURED_COST = 0, 1

@@ -191,6 +191,15 @@ __global__ __launch_bounds__(256) void k_ubench_valu(int iters, uint32_t *buf, u
                 if (KIND == HIKONV_UB_ADD_U64) asm volatile("v_lshl_add_u64 %0, %0, 0, %1" : "+v"(w[i]) : "v"(w[nb]));
                 if (KIND == HIKONV_UB_ALIGNBIT) asm volatile("v_alignbit_b32 %0, %0, %1, %2" : "+v"(a[i]) : "v"(a[nb]), "v"(s2));
                 if (KIND == HIKONV_UB_AND_B32) asm volatile("v_and_b32 %0, %0, %1" : "+v"(a[i]) : "v"(a[nb]));
+                if (KIND == HIKONV_UB_ASHR_I64) asm volatile("v_ashrrev_i64 %0, %1, %2" : "=v"(w[i]) : "v"(s2), "v"(w[nb]));
+                if (KIND == HIKONV_UB_BFE_I32) asm volatile("v_bfe_i32 %0, %1, %2, %3" : "=v"(a[i]) : "v"(a[nb]), "v"(s2), "v"(s1 + 20u));
+                // dependent chains: every slot works on the same accumulator (run with one wave per SIMD,
+                // the time per slot is the instruction's dependent-issue latency)
+                if (KIND == HIKONV_UB_CHAIN_MAD_I64_I32) {
+                    uint64_t carry;
+                    asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(w[0]), "=s"(carry) : "v"(a[1]), "v"(s1));
+                }
+                if (KIND == HIKONV_UB_CHAIN_MAD_I32_I24) asm volatile("v_mad_i32_i24 %0, %0, %1, %2" : "+v"(a[0]) : "v"(a[1]), "v"(s2));
             }
         }
     }
@@ -362,6 +371,10 @@ hipError_t launch_ubench(int kind, int iters, int blocks, void *buf, size_t byte
         HIKONV_UB_CASE(HIKONV_UB_ADD_U64)
         HIKONV_UB_CASE(HIKONV_UB_ALIGNBIT)
         HIKONV_UB_CASE(HIKONV_UB_AND_B32)
+        HIKONV_UB_CASE(HIKONV_UB_ASHR_I64)
+        HIKONV_UB_CASE(HIKONV_UB_BFE_I32)
+        HIKONV_UB_CASE(HIKONV_UB_CHAIN_MAD_I64_I32)
+        HIKONV_UB_CASE(HIKONV_UB_CHAIN_MAD_I32_I24)
 #undef HIKONV_UB_CASE
     case HIKONV_UB_HBM_WRITE:
         hipLaunchKernelGGL(k_ubench_write, g, b, 0, stream, static_cast<int4 *>(buf), (int64_t)(bytes / 16));
