@@ -212,13 +212,8 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_unpacked(Conv1dArgs p)
 template <bool A_SIGNED, int TAPS, bool WIDE, int G>
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_conv1d_unpacked_fast(Conv1dArgs p)
 {
-    __shared__ int32_t s_g[8];
-    if (threadIdx.x < TAPS)
-        s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
-    __syncthreads();
     int32_t gk[TAPS];
-#pragma unroll
-    for (int k = 0; k < TAPS; ++k) gk[k] = s_g[k];
+    load_taps_scalar<TAPS>(p.g, p.w_signed != 0, gk);
     const int b = p.b;
     // the container width is a compile-time constant inside, so an element is one bit-field
     // extract from the dword that holds it (containers never straddle a dword)
@@ -300,6 +295,7 @@ hipError_t launch_conv1d_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_
     if (a.taps <= 7 && quad_stream_applicable(a, a.taps + (octets ? 7 : 3)) && ((a.taps + 3) * a.c <= 64 || a.c == 8)) {
         const bool wide_window = !octets && (a.taps + 3) * a.c > 64;
         g = quad_stream_grid(a, octets ? 8 : 4);
+        b = dim3(kStreamThreads);
 #define HIKONV_UNP(T)                                                                               \
     case T:                                                                                         \
         if (octets && a_signed)                                                                     \

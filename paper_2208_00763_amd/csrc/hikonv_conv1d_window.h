@@ -45,10 +45,8 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
     constexpr int CH = (TAPS + K - 1) / K;         // B words (CH > 1 only with K == N)
     static_assert(CH == 1 || K == N, "a delayed block is the packed word of an earlier block only when K == N");
 
-    __shared__ int32_t s_g[8];
-    if (threadIdx.x < TAPS)
-        s_g[threadIdx.x] = p.w_signed ? (int32_t)(int8_t)p.g[threadIdx.x] : (int32_t)p.g[threadIdx.x];
-    __syncthreads();
+    int32_t s_g[TAPS];
+    load_taps_scalar<TAPS>(p.g, p.w_signed != 0, s_g);
     const int S = p.S, b = p.b;
     // B words (Eq. inpack), wave-uniform
     uint32_t bw[CH];

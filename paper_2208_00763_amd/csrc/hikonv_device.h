@@ -63,6 +63,42 @@ __device__ __forceinline__ int32_t mad24(int32_t a, int32_t b, int32_t c)
     return d;
 }
 
+// The TAPS (<= 8) filter taps at g, one byte each, sign- or zero-extended, fetched by scalar
+// loads of the aligned dwords that hold them (an aligned dword that contains a valid byte lies
+// in that byte's page, so nothing outside the buffer's pages is touched).  The taps arrive in
+// scalar registers: no LDS staging and no workgroup barrier ahead of the kernel's first loads.
+template <int TAPS>
+__device__ __forceinline__ void load_taps_scalar(const uint8_t *g, bool is_signed, int32_t (&taps)[TAPS])
+{
+    static_assert(TAPS >= 1 && TAPS <= 8, "at most eight taps");
+    const uintptr_t a = reinterpret_cast<uintptr_t>(g);
+    const uint32_t *gp = reinterpret_cast<const uint32_t *>(a & ~static_cast<uintptr_t>(3));
+    const uint32_t first = (uint32_t)(a & 3u);
+    const uint32_t last = (first + TAPS - 1) >> 2; // index of the last dword with a tap: 0..2
+    uint32_t d[4] = {0u, 0u, 0u, 0u};
+    if (last == 0) {
+        asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(d[0]) : "s"(gp) : "memory");
+    } else if (last == 1) {
+        asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %2, 0x4\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(d[0]), "=&s"(d[1])
+                     : "s"(gp)
+                     : "memory");
+    } else {
+        asm volatile("s_load_dword %0, %3, 0x0\n\ts_load_dword %1, %3, 0x4\n\ts_load_dword %2, %3, 0x8\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(d[0]), "=&s"(d[1]), "=&s"(d[2])
+                     : "s"(gp)
+                     : "memory");
+    }
+#pragma unroll
+    for (int k = 0; k < TAPS; ++k) {
+        const uint32_t pos = first * 8u + 8u * k;
+        // bytes never straddle a dword
+        const uint32_t w = pos < 32u ? d[0] : pos < 64u ? d[1] : d[2];
+        const uint32_t b = (w >> (pos & 31u)) & 0xffu;
+        taps[k] = is_signed ? (int32_t)(int8_t)b : (int32_t)b;
+    }
+}
+
 // Segments N.. of an accumulated word (shift by S*N).  A shift that reaches the register
 // width happens only for one-tap kernels, which have no high segments: the result is 0.
 template <bool SIGNED>
