@@ -213,8 +213,8 @@ struct Cand {
 constexpr double kI32Block = 15.0, kI32Elem = 11.7;
 constexpr double kRqBlock = 21.0, kRqElem = 13.9;
 constexpr double kShareChunk = 4.2;
-constexpr double kWin8Base = 6.3, kWin8Tap = 0.51, kWin8Block = 0.45, kWin8Signed = 1.3;
-constexpr double kWin4Base = 4.7, kWin4Tap = 0.66, kWin4Block = 1.41, kWin4Signed = 1.4;
+constexpr double kWin8Base = 6.1, kWin8Tap = 0.39, kWin8Block = 0.46, kWin8Signed = 1.3;
+constexpr double kWin4Base = 4.7, kWin4Tap = 0.56, kWin4Block = 1.36, kWin4Signed = 1.4;
 
 // plans the window kernel (int32 outputs) takes (the launcher's rule, without the geometry)
 inline bool window_form(int taps, int n, int k)
