@@ -20,7 +20,8 @@
 //           (Eq. output_split in bias form)
 //   store   aligned int32x4 stores with the streaming hint; every store instruction of a wave
 //           covers whole 128-byte lines of y (see hikonv_quad_stream.h).
-// No lane exchange, no barrier; each lane packs T elements for G outputs (the lane-exchange
+// No lane exchange, and no barrier that the arithmetic needs (the skeleton has the workgroup's waves
+// meet once, for the timing of their stores); each lane packs T elements for G outputs (the lane-exchange
 // kernel packs every element once), which is the cheaper side of the trade on this chip
 // because the path is bound by the bytes it writes.
 // Groups at a row's ends, or whose loads would leave the buffer, assemble the same window from
