@@ -145,59 +145,80 @@ def graph_replay_ms(fn, calls, reps):
 def requant_extra(hk, wl, steps):
     """The same 1-D cases with the outputs requantised in the kernel and written bit-dense at the
     input's width: no int32 stream, so the integer VALUs bound it instead of HBM writes."""
-    import torch
     report = {}
     for bits, signed in ((4, False), (1, False), (2, False), (4, True)):
-        case = conv1d_case(hk, wl, bits, signed)
-        x_bd, g_d = case["keep"]
-        out_len = case["out_len"]
-        row_bytes = hk.hikonv_bitdense_row_bytes(out_len, bits)
-        q = torch.empty(ROWS * row_bytes, dtype=torch.uint8, device="cuda")
-        shift, qmax = max(0, 2 * bits - 3), (1 << bits) - 1 if bits < 8 else 127
-
-        # the plan of the measured-cost objective (container-aligned slices here) against
-        # Algorithm 1's plan (most operations per multiply), both through the same entry point
-        kw = dict(bits_a=bits, bits_w=bits, a_signed=int(signed), w_signed=int(signed), L_A=32, L_B=32, L_acc=64,
-                  mode=hk.MODE_CONV1D, taps=TAPS, out_bits=bits)
-        plan_cost = hk.hikonv_plan_ex(objective=hk.OBJ_MEASURED_COST, **kw)
-        plan_paper = hk.hikonv_plan_ex(objective=hk.OBJ_PAPER_OPS, **kw)
-
-        def run_with(p):
-            return lambda: hk.hikonv_conv1d_requant(p, x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d, TAPS, hk.OUT_VALID,
-                                                    shift, qmax, bits, q)
-
-        def unpacked():
-            hk.hikonv_conv1d_requant_unpacked(bits, bits, hk.signedness(signed, signed), x_bd, hk.FMT_BITDENSE, ROWS,
-                                              LENGTH, g_d, TAPS, hk.OUT_VALID, shift, qmax, bits, q)
-
-        ms_p, ms_u = timed_pair(run_with(plan_cost), unpacked, steps)
-        ms_plan, _ = timed_pair(run_with(plan_paper), unpacked, steps, rounds=1)
-        plan = plan_cost
-        algo = ROWS * (row_bytes + hk.hikonv_bitdense_row_bytes(LENGTH, bits)) + TAPS
-        key = "%d%s" % (bits, "s" if signed else "u")
-        # this path is bound by integer VALU issue: instructions of the launch (the profiled count per
-        # output x the outputs) over the time measured here, against the chip's lane-instruction peak
-        prof = (read_profile_json("conv1d_requant_valu.json") or {}).get("cases", {}).get(key)
-        roof = None
-        if prof:
-            lane_instr = prof["valu_lane_instructions_per_output"] * ROWS * out_len
-            achieved = lane_instr / (ms_p * 1e-3) / 1e12
-            roof = {"bound": "alu", "achieved": achieved, "peak": VALU_LANE_RATE / 1e12, "unit": "T lane-instr/s",
-                    "frac": achieved / (VALU_LANE_RATE / 1e12), "kernel": prof["kernel"],
-                    "valu_lane_instructions_per_output": prof["valu_lane_instructions_per_output"],
-                    "valu_utilisation_profiled": prof["valu_utilisation"],
-                    "source": "profiles/conv1d_requant_valu.json (SQ_INSTS_VALU of a rocprofv3 run of this kernel; the time is "
-                              "this run's)"}
-        report[key] = dict(
-            roofline=roof,
-            ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=algo / ms_p / 1e6, unpacked_ms=ms_u,
-            vs_unpacked=ms_u / ms_p, frac_of_unpacked_valu_peak=case["macs"] / (ms_p * 1e-3) / VALU_LANE_RATE,
-            plan=dict(N=plan.N, K=plan.K, S=plan.S, stride_elems=plan.stride_elems, cost_milli=plan.cost_milli),
-            paper_plan=dict(N=plan_paper.N, K=plan_paper.K, S=plan_paper.S, cost_milli=plan_paper.cost_milli,
-                            ms=ms_plan))
-        del case, q
-        torch.cuda.empty_cache()
+        report["%d%s" % (bits, "s" if signed else "u")] = requant_case(hk, wl, bits, signed, TAPS, steps)
     return report
+
+
+def sweep_requant(hk, wl, steps):
+    """The 48 cases of the 1-D sweep with requantised bit-dense outputs at the input's width: the
+    cost objective's plan, Algorithm 1's plan and the unpacked kernel."""
+    rows = []
+    for bits in range(1, 9):
+        for signed in (False, True):
+            for taps in (3, 5, 7):
+                r = requant_case(hk, wl, bits, signed, taps, steps, profile=False)
+                rows.append(dict(bits=bits, signed=signed, taps=taps, ms=r["ms"], unpacked_ms=r["unpacked_ms"],
+                                 paper_ms=r["paper_plan"]["ms"], plan=r["plan"], paper_plan=r["paper_plan"],
+                                 gops=r["gops"], vs_unpacked=r["vs_unpacked"]))
+    return rows
+
+
+def requant_case(hk, wl, bits, signed, TAPS, steps, profile=True):
+    """One requantising case: milliseconds of the cost objective's plan, of Algorithm 1's plan and of the
+    unpacked kernel, all through the same buffers."""
+    import torch
+    case = conv1d_case(hk, wl, bits, signed, TAPS)
+    x_bd, g_d = case["keep"]
+    out_len = case["out_len"]
+    row_bytes = hk.hikonv_bitdense_row_bytes(out_len, bits)
+    q = torch.empty(ROWS * row_bytes, dtype=torch.uint8, device="cuda")
+    shift, qmax = max(0, 2 * bits - 3), (1 << bits) - 1 if bits < 8 else 127
+
+    # the plan of the measured-cost objective (container-aligned slices here) against
+    # Algorithm 1's plan (most operations per multiply), both through the same entry point
+    kw = dict(bits_a=bits, bits_w=bits, a_signed=int(signed), w_signed=int(signed), L_A=32, L_B=32, L_acc=64,
+              mode=hk.MODE_CONV1D, taps=TAPS, out_bits=bits)
+    plan_cost = hk.hikonv_plan_ex(objective=hk.OBJ_MEASURED_COST, **kw)
+    plan_paper = hk.hikonv_plan_ex(objective=hk.OBJ_PAPER_OPS, **kw)
+
+    def run_with(p):
+        return lambda: hk.hikonv_conv1d_requant(p, x_bd, hk.FMT_BITDENSE, ROWS, LENGTH, g_d, TAPS, hk.OUT_VALID,
+                                                shift, qmax, bits, q)
+
+    def unpacked():
+        hk.hikonv_conv1d_requant_unpacked(bits, bits, hk.signedness(signed, signed), x_bd, hk.FMT_BITDENSE, ROWS,
+                                          LENGTH, g_d, TAPS, hk.OUT_VALID, shift, qmax, bits, q)
+
+    ms_p, ms_u = timed_pair(run_with(plan_cost), unpacked, steps)
+    ms_plan, _ = timed_pair(run_with(plan_paper), unpacked, steps, rounds=1)
+    plan = plan_cost
+    algo = ROWS * (row_bytes + hk.hikonv_bitdense_row_bytes(LENGTH, bits)) + TAPS
+    key = "%d%s" % (bits, "s" if signed else "u")
+    # this path is bound by integer VALU issue: instructions of the launch (the profiled count per
+    # output x the outputs) over the time measured here, against the chip's lane-instruction peak
+    prof = (read_profile_json("conv1d_requant_valu.json") or {}).get("cases", {}).get(key) if profile else None
+    roof = None
+    if prof:
+        lane_instr = prof["valu_lane_instructions_per_output"] * ROWS * out_len
+        achieved = lane_instr / (ms_p * 1e-3) / 1e12
+        roof = {"bound": "alu", "achieved": achieved, "peak": VALU_LANE_RATE / 1e12, "unit": "T lane-instr/s",
+                "frac": achieved / (VALU_LANE_RATE / 1e12), "kernel": prof["kernel"],
+                "valu_lane_instructions_per_output": prof["valu_lane_instructions_per_output"],
+                "valu_utilisation_profiled": prof["valu_utilisation"],
+                "source": "profiles/conv1d_requant_valu.json (SQ_INSTS_VALU of a rocprofv3 run of this kernel; the time is "
+                          "this run's)"}
+    result = dict(
+        roofline=roof,
+        ms=ms_p, gops=2 * case["macs"] / ms_p / 1e6, gbs=algo / ms_p / 1e6, unpacked_ms=ms_u,
+        vs_unpacked=ms_u / ms_p, frac_of_unpacked_valu_peak=case["macs"] / (ms_p * 1e-3) / VALU_LANE_RATE,
+        plan=dict(N=plan.N, K=plan.K, S=plan.S, stride_elems=plan.stride_elems, cost_milli=plan.cost_milli),
+        paper_plan=dict(N=plan_paper.N, K=plan_paper.K, S=plan_paper.S, cost_milli=plan_paper.cost_milli,
+                        ms=ms_plan))
+    del case, q
+    torch.cuda.empty_cache()
+    return result
 
 
 def conv2d_extra(hk, wl, name, steps):
@@ -511,6 +532,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="time all 48 cases of the 1-D bitwidth sweep (packed and unpacked), print them as JSON "
                          "and as a table, then exit")
+    ap.add_argument("--sweep-requant", action="store_true",
+                    help="time all 48 cases of the 1-D sweep with requantised bit-dense outputs (cost-objective plan, "
+                         "Algorithm 1's plan, unpacked kernel), print them as JSON and as a table, then exit")
     ap.add_argument("--only", choices=["c3", "c4", "cnn", "requant"], default=None,
                     help="run one of the extra workloads alone (for profiler runs) and print its report")
     ap.add_argument("--kernel", choices=["auto", "lanes", "window"], default="auto",
@@ -555,6 +579,19 @@ def main():
             print("%4d %6s %4d %2d %2d %2d %6d %10.4f %11.4f %8.2f %6.0f %5.0f %8.3f" % (
                 r["bits"], "s" if r["signed"] else "u", r["taps"], r["N"], r["K"], r["S"], r["chunks"], r["packed_ms"],
                 r["unpacked_ms"], r["speedup_vs_unpacked"], r["gops"], r["gbs"], r["hbm_frac"]), file=sys.stderr)
+        return 0
+
+    if args.sweep_requant:
+        rows = sweep_requant(hk, wl, max(3, args.steps // 5))
+        print(json.dumps({"metric": "1-D bitwidth sweep with requantised bit-dense outputs, 4096 rows x 65536, valid",
+                          "cases": rows}))
+        print("bits signed taps | cost-objective plan: N  K  S stride   ms | Algorithm 1's plan: N  K  S   ms | unpacked_ms | "
+              "cost plan vs unpacked | GOPS", file=sys.stderr)
+        for r in rows:
+            print("%4d %6s %4d | %22d %2d %2d %6d %7.4f | %21d %2d %2d %7.4f | %11.4f | %21.2f | %6.0f" % (
+                r["bits"], "s" if r["signed"] else "u", r["taps"], r["plan"]["N"], r["plan"]["K"], r["plan"]["S"],
+                r["plan"]["stride_elems"], r["ms"], r["paper_plan"]["N"], r["paper_plan"]["K"], r["paper_plan"]["S"],
+                r["paper_ms"], r["unpacked_ms"], r["vs_unpacked"], r["gops"]), file=sys.stderr)
         return 0
 
     if args.calibrate:
