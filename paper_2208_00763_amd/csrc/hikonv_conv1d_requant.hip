@@ -299,10 +299,11 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_any(Conv1dArgs p, int a_
 }
 
 // Baseline with the same output format: a lane produces unpacked_unroll(PER) output dwords (PER
-// values each), 256 dwords apart, from 64-bit windows of the row whose loads are all issued first.
+// values each), 256 dwords apart, from 64-bit windows of the row whose loads are all issued first
+// (W96: windows of up to 96 bits from four dwords, for 8-bit containers with 6 or 7 taps).
 __host__ __device__ constexpr int unpacked_unroll(int per) { return per <= 8 ? 4 : 1; }
 
-template <bool A_SIGNED, int TAPS, int PER>
+template <bool A_SIGNED, int TAPS, int PER, bool W96 = false>
 __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
 {
     constexpr int U = unpacked_unroll(PER);
@@ -342,19 +343,22 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
     // holds it (a container never straddles a dword).  Taken for containers of 4 and 8 bits, where
     // it is faster (measured at 4096 x 65536, 3 taps: 0.100 against 0.112 ms at 4 bit; at 2 and 1
     // bit the shifted form below is the faster one, 0.094 against 0.131 and 0.234 against 0.264 ms)
-    auto window_outputs = [&](uint64_t win, int32_t (&out)[PER]) {
+    auto window_outputs = [&](uint64_t win, uint32_t win_hi, int32_t (&out)[PER]) {
 #pragma unroll
         for (int u = 0; u < PER; ++u) out[u] = 0;
         if (PER <= 8 && c == 32 / PER) { // wave-uniform
             constexpr int CC = 32 / PER;
-            const uint32_t lo = (uint32_t)win, hi = (uint32_t)(win >> 32);
+            const uint32_t dw[3] = {(uint32_t)win, (uint32_t)(win >> 32), win_hi};
 #pragma unroll
             for (int t = 0; t < TAPS + PER - 1; ++t)
-                accumulate(out, t, field<A_SIGNED>(t * CC < 32 ? lo : hi, (uint32_t)((t * CC) & 31), (uint32_t)b));
+                accumulate(out, t, field<A_SIGNED>(dw[(t * CC) >> 5], (uint32_t)((t * CC) & 31), (uint32_t)b));
         } else {
 #pragma unroll
-            for (int t = 0; t < TAPS + PER - 1; ++t)
-                accumulate(out, t, field<A_SIGNED>((uint32_t)(win >> (t * c)), 0u, (uint32_t)b));
+            for (int t = 0; t < TAPS + PER - 1; ++t) {
+                // a container never straddles bit 64 (its width divides 64)
+                const uint32_t bits_t = W96 && t * c >= 64 ? win_hi >> (t * c - 64) : (uint32_t)(win >> (t * c));
+                accumulate(out, t, field<A_SIGNED>(bits_t, 0u, (uint32_t)b));
+            }
         }
     };
 
@@ -367,7 +371,7 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
         const bool fast = k0 + (U - 1) * 256 < row_out_dwords && i_first >= 0 && i_last + TAPS + PER - 1 <= p.len &&
                           row_bit0 + i_last * c + 128 <= total_bits;
         if (fast) {
-            uint32_t w0[U], w1[U], w2[U], sh[U];
+            uint32_t w0[U], w1[U], w2[U], w3[U], sh[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) {
                 const int64_t bit = row_bit0 + (i_first + (int64_t)q * 256 * PER) * c;
@@ -375,13 +379,14 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
                 w0[q] = wp[0];
                 w1[q] = wp[1];
                 w2[q] = wp[2];
+                w3[q] = W96 ? wp[3] : 0u; // inside the buffer: the fast path keeps 128 bits from the window's dword
                 sh[q] = (uint32_t)bit & 31u;
             }
 #pragma unroll
             for (int q = 0; q < U; ++q) {
                 const uint64_t win = ((uint64_t)funnel_shr(w2[q], w1[q], sh[q]) << 32) | funnel_shr(w1[q], w0[q], sh[q]);
                 int32_t out[PER];
-                window_outputs(win, out);
+                window_outputs(win, W96 ? funnel_shr(w3[q], w2[q], sh[q]) : 0u, out);
                 emit(r, k0 + q * 256, out);
             }
         } else {
@@ -399,18 +404,25 @@ __global__ __launch_bounds__(256) void k_conv1d_requant_unpacked(Conv1dArgs p)
                 const uint32_t v1 = load_dword_checked(p.x, d + 1, p.total_dwords, p.total_bytes);
                 const uint32_t v2 = load_dword_checked(p.x, d + 2, p.total_dwords, p.total_bytes);
                 uint64_t win = ((uint64_t)funnel_shr(v2, v1, wsh) << 32) | funnel_shr(v1, v0, wsh);
+                uint32_t win_hi = W96 ? funnel_shr(load_dword_checked(p.x, d + 3, p.total_dwords, p.total_bytes), v2, wsh) : 0u;
                 const int64_t lo = i0 < 0 ? -i0 : 0;
                 int64_t hi = p.len - i0;
                 if (hi > TAPS + PER - 1) hi = TAPS + PER - 1;
                 if (hi <= lo) {
                     win = 0;
+                    win_hi = 0;
                 } else {
+                    // lo < TAPS elements: lo_bits < 64; hi_bits up to 96 with four dwords
                     const uint32_t hi_bits = (uint32_t)hi * (uint32_t)c, lo_bits = (uint32_t)lo * (uint32_t)c;
                     const uint64_t m_hi = hi_bits >= 64 ? ~0ull : ((1ull << hi_bits) - 1ull);
                     win &= m_hi & ~((1ull << lo_bits) - 1ull);
+                    if (hi_bits <= 64)
+                        win_hi = 0;
+                    else if (hi_bits < 96)
+                        win_hi &= (1u << (hi_bits - 64)) - 1u;
                 }
                 int32_t out[PER];
-                window_outputs(win, out);
+                window_outputs(win, win_hi, out);
                 emit(r, k, out);
             }
         }
@@ -478,6 +490,17 @@ hipError_t launch_rq_unpacked_t(const Conv1dArgs &a, bool a_signed, dim3 g, hipS
         else                                                                                                     \
             hipLaunchKernelGGL((k_conv1d_requant_unpacked<false, TAPS, PER>), g, dim3(256), 0, stream, a);       \
         break;
+    // windows of 65..96 bits: 8-bit containers in and out, 6 or 7 taps
+    if constexpr (TAPS >= 6) {
+        if ((TAPS + 32 / a.rq_c_out - 1) * a.c > 64) {
+            if (a.rq_c_out != 8 || (TAPS + 3) * a.c > 96) return hipErrorNotSupported;
+            if (a_signed)
+                hipLaunchKernelGGL((k_conv1d_requant_unpacked<true, TAPS, 4, true>), g, dim3(256), 0, stream, a);
+            else
+                hipLaunchKernelGGL((k_conv1d_requant_unpacked<false, TAPS, 4, true>), g, dim3(256), 0, stream, a);
+            return hipGetLastError();
+        }
+    }
     switch (32 / a.rq_c_out) {
         HIKONV_LAUNCH(4) HIKONV_LAUNCH(8) HIKONV_LAUNCH(16) HIKONV_LAUNCH(32)
     default: return hipErrorNotSupported;
@@ -534,7 +557,8 @@ hipError_t launch_conv1d_requant(const Conv1dArgs &a, bool a_signed, bool any_si
 hipError_t launch_conv1d_requant_unpacked(const Conv1dArgs &a, bool a_signed, hipStream_t stream)
 {
     const int per = 32 / a.rq_c_out;
-    const bool windowed = a.taps <= 7 && (a.taps + per - 1) * a.c <= 64;
+    const bool windowed = a.taps <= 7 && ((a.taps + per - 1) * a.c <= 64 ||
+                                          (a.taps >= 6 && a.rq_c_out == 8 && (a.taps + 3) * a.c <= 96)); // 96: four dwords
     const int64_t gx = ceil_div(ceil_div(a.out_len, per), windowed ? 256 * unpacked_unroll(per) : 256);
     if (gx <= 0 || gx > 0x7fffffffLL) return hipErrorNotSupported;
     dim3 g((unsigned)gx, (unsigned)(a.rows < 65535 ? a.rows : 65535));

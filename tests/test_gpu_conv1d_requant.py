@@ -262,3 +262,20 @@ def test_requant_refuses_aligned_plans_that_do_not_fit_the_call():
         hk.hikonv_conv1d(plan, x_d, hk.FMT_BITDENSE, 2, 256, g_d, 3, hk.OUT_VALID, out.view)
     assert e.value.code == hk.EUNSUPPORTED
     out.result()
+
+
+@pytest.mark.parametrize("bits,signed", [(5, False), (7, True), (8, False), (8, True)])
+def test_requant_unpacked_windows_of_up_to_96_bits(bits, signed):
+    """The baseline with 8-bit containers in and out and 6 or 7 taps reads its windows from four
+    dwords: rows that end anywhere inside a window, short rows, both formats, both output modes."""
+    for taps in (6, 7):
+        for rows, length in ((3, 5), (4, 9), (2, 10), (5, 11), (3, 37), (2, 4099), (1, 20011), (6, 1023)):
+            x, g = values("rq96", bits, signed, signed, taps, rows, length)
+            for out_bits in (5, 8):
+                qmax = (1 << out_bits) - 1 if out_bits < 8 else 255
+                for mode in (hk.OUT_FULL, hk.OUT_VALID):
+                    for shift in (0, pick_shift(bits, taps, out_bits)):
+                        ref = oracle_requant(x, g, mode, shift, qmax, out_bits)
+                        for fmt in (hk.FMT_INT8, hk.FMT_BITDENSE):
+                            got = run_requant(x, g, bits, signed, signed, mode, fmt, shift, qmax, out_bits, packed=False)
+                            assert np.array_equal(got, ref), (bits, signed, taps, rows, length, out_bits, mode, shift, fmt)
