@@ -160,7 +160,10 @@ int hikonv_plan_ex(const hikonv_plan_t *request, hikonv_plan_t *out);
  * optimisation for a multiplier whose every use costs the same, which does not hold
  * for a GPU lane that also has to pack and split).  Besides the (N, K, S) of
  * Eq. (slice1)-(slice3) it considers container-aligned slices (stride_elems > 1)
- * when out_bits names an output container as wide as the input's.
+ * when out_bits names an output container as wide as the input's, and with out_bits
+ * set it prices the degenerate plan N = K = 1 (one value and one tap per multiply,
+ * Theorem 1's smallest case) as the one-product-per-multiply kernel that runs it:
+ * where no packed plan is cheaper (8-bit operands, for one) that plan is the answer.
  * In mode DNN with fixed taps the same objective prices a layer plan by the
  * multiply-accumulates it does per issue slot, splits and extra B words included
  * (Section "DNN Convolution Extension": M products accumulate before a split), and
@@ -232,7 +235,8 @@ int hikonv_conv1d_unpacked(int bits_a, int bits_w, int signedness, const void *x
  * bits beyond out_len in a row are written as 0.  Nothing else is written.
  * The call runs the plan it is handed.  Plans with stride_elems = 1 and N <= 12
  * whose N containers fit 32 bits run the streaming kernel; other such plans run a
- * slow general kernel.
+ * slow general kernel.  A plan with N = K = 1 packs nothing and runs the kernel of
+ * hikonv_conv1d_requant_unpacked.
  * Plans with container-aligned slices (stride_elems = S / c > 1, K = 1,
  * chunks = taps; N = 2, S = 16, or for one-bit unsigned values and taps N = 8,
  * S = 4), as hikonv_plan_ex returns them under HIKONV_OBJ_MEASURED_COST with

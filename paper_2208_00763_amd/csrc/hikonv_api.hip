@@ -483,6 +483,11 @@ extern "C" int hikonv_conv1d_requant(const hikonv_plan_t *plan, const void *x_de
         return hip_result(launch_conv1d_requant_aligned(a, plan->a_signed != 0, any_signed, plan->bits_w,
                                                         static_cast<hipStream_t>(stream)));
     }
+    // One value and one tap per multiply (Theorem 1 with N = K = 1): nothing is packed, and the
+    // one-product-per-multiply kernel is that plan's kernel.  The measured-cost objective returns
+    // it where no packed plan is cheaper (8-bit operands, for one).
+    if (plan->N == 1 && plan->K == 1)
+        return hip_result(launch_conv1d_requant_unpacked(a, plan->a_signed != 0, static_cast<hipStream_t>(stream)));
     a.N = plan->N;
     a.Kp = plan->K;
     a.S = plan->S;

@@ -199,6 +199,8 @@ struct Cand {
 //       delayed words come from the preceding lanes (K = N), else a second packing
 //   streaming kernel, requantised bit-dense outputs:
 //       kRqBlock + kRqElem*N  [+ N + 1 signed] + the same per extra B word
+//   one value and one tap per multiply (N = K = 1), requantised outputs: the one-product kernel,
+//       13.7 .. 21 per output at 3 taps by output container, 1.9 per further tap
 //   container-aligned slices (K = 1, S = SW, J = SW/c residues), per output dword of 32/c values:
 //       2 per packed word of the window (shift, mask), J + taps - 1 of them
 //       taps per residue word (multiply-add; AND + add for one-bit taps), J residue words
@@ -237,6 +239,15 @@ double hbm_floor_slots(const Req &r)
 // slots per output of the kernel that runs (n, k, s, stride) in CONV1D mode; < 0: no kernel
 double conv1d_slots(const Req &r, int n, int k, int chunks, int s, int stride)
 {
+    // One value and one tap per multiply (the degenerate F_{1,1}) with requantised output: the entry
+    // point runs the one-product-per-multiply kernel for it.  Measured slots per output at 3 taps by
+    // output container (1, 2, 4, 8 bits: 19.4, 14.8, 13.7, 21), about 1.9 more per further tap.
+    if (stride <= 1 && r.out_bits > 0 && n == 1 && k == 1) {
+        const int co = container_of(r.out_bits);
+        const double base = co == 1 ? 19.4 : co == 2 ? 14.8 : co == 4 ? 13.7 : 21.0;
+        const double slots = base + 1.9 * (r.taps - 3);
+        return slots < 8.0 ? 8.0 : slots;
+    }
     if (stride > 1) {
         const int c = container_of(r.p);
         const int j = stride, per = 32 / c;
@@ -255,6 +266,9 @@ double conv1d_slots(const Req &r, int n, int k, int chunks, int s, int stride)
     double block = r.out_bits > 0 ? kRqBlock + kRqElem * n : kI32Block + kI32Elem * n;
     if (r.any_signed) block += n + 1;
     if (chunks > 1) block += (chunks - 1) * (share ? kShareChunk : 2.0 * n + 3.0);
+    // with 8-bit containers the streaming requantising kernel measures about 1.5 times these figures
+    // (41 slots per output for N = 2, two B words at 3 taps; the fit above is to containers of up to 4 bits)
+    if (r.out_bits > 0 && container_of(r.p) == 8) block *= 1.5;
     return block / n;
 }
 

@@ -47,11 +47,20 @@ def test_cost_objective_returns_container_aligned_slices_for_requantised_output(
 
 
 def test_cost_objective_keeps_the_plan_slices_where_aligned_slices_are_not_exact():
-    # 3 taps of 8-bit unsigned products reach 195075 > 2^16 - 1; other containers in and out
-    for kw in (dict(bits=8, signed=False, out_bits=8), dict(bits=4, signed=False, out_bits=8),
-               dict(bits=4, signed=False, out_bits=0), dict(bits=8, signed=True, out_bits=8)):
+    # int32 outputs: no container-aligned slices, Algorithm 1's plan (the path is memory-bound)
+    plan = conv1d_request(4, False, 3, hk.OBJ_MEASURED_COST, out_bits=0)
+    assert plan.stride_elems == 1 and plan.K > 1
+    # 3 taps of 8-bit unsigned products reach 195075 > 2^16 - 1; other containers in and out: no aligned
+    # slices either, and with requantised outputs no packed plan is then cheaper than one product per
+    # multiply (measured, 4096 x 65536, 3 taps, 8 bit: Algorithm 1's plan 0.31 ms, the one-product kernel
+    # 0.16 ms): the objective answers with Theorem 1's smallest case, N = K = 1
+    assert conv1d_request(4, False, 3, hk.OBJ_MEASURED_COST, out_bits=8).stride_elems == 1
+    for kw in (dict(bits=8, signed=False, out_bits=8), dict(bits=8, signed=True, out_bits=8)):
         plan = conv1d_request(kw["bits"], kw["signed"], 3, hk.OBJ_MEASURED_COST, out_bits=kw["out_bits"])
-        assert plan.stride_elems == 1 and plan.K > 1
+        assert (plan.N, plan.K, plan.stride_elems, plan.chunks) == (1, 1, 1, 3)
+        assert hk.hikonv_plan_check(plan) == hk.OK
+        paper = conv1d_request(kw["bits"], kw["signed"], 3, hk.OBJ_PAPER_OPS, out_bits=kw["out_bits"])
+        assert paper.K > 1 and hk.hikonv_plan_cost(paper) > plan.cost_milli
     # 7-bit signed, 5 taps: 5 * 64 * 64 = 20480 < 2^15 fits and the window of 4 + 4 bytes is 64 bits;
     # 6 taps: the window would be 72 bits
     assert conv1d_request(7, True, 5, hk.OBJ_MEASURED_COST, out_bits=7).stride_elems == 2
